@@ -1,0 +1,19 @@
+"""CPU oracle (test infrastructure only).
+
+Importable from tests, the smoke check and the benchmark's cpu_baseline leg.
+The product package never imports this.
+"""
+from .segquant_oracle import (  # noqa: F401
+    OracleResult,
+    build,
+    cast_bf16,
+    dequant,
+    error_bound,
+    fp_reference,
+    int_gemm,
+    num_threads,
+    quantize_act,
+    quantize_weight,
+    seglinear,
+    widen_bf16,
+)

@@ -1,0 +1,312 @@
+/*
+ * CPU ORACLE for the SegLinear + DualScale quantized linear layer (arXiv 2507.14811).
+ *
+ * TEST INFRASTRUCTURE ONLY.  Plain, slow, obviously-correct C.  Nothing in the
+ * product path may call into this file; only tests, the smoke check and the
+ * cpu_baseline leg of the benchmark do.  It shares no code, header, table or
+ * helper with the HIP library.
+ *
+ * The method is an encoding + approximation, so the oracle takes the paper's
+ * steps in the paper's order:
+ *
+ *   Quant(W)       uniform symmetric quantizer of Sec. 3 (z = 0), applied
+ *                  separately to every segment of the weight (Sec. 4.2.2):
+ *                  here per output channel and per K-segment.
+ *   Q_dual(X)      Sec. 4.3.2: x < 0 uses the step s_-, x >= 0 uses s_+; the
+ *                  matrix is split X = X_+ + X_- (element-wise max / min with 0)
+ *                  and each part is quantized with its own step.
+ *   integer GEMM   X^_+ W^ and X^_- W^ per K-segment (input-segmented sum of
+ *                  Sec. 4.2.2 item 2; output segments of item 1 are column
+ *                  blocks of the same product).
+ *   DeQuant        Sec. 4.3.2 last display:  s_+ s_w (X^_+ W^) + s_- s_w (X^_- W^),
+ *                  summed over K-segments, App. A "symmetric" recovery for a
+ *                  single-scale segment.
+ *
+ * Readings where the paper is silent (listed in the design notes of the repo):
+ *   round()            = round-half-to-even (nearbyintf under FE_TONEAREST)
+ *   [q_min, q_max]     = [-127, 127]
+ *   s_-                = |min x| / 127  (positive step; codes of x < 0 are <= 0)
+ *   x / s              = a true IEEE fp32 division
+ *   weight layout      = W[n][k] (row = output channel), i.e. the transpose of
+ *                        the paper's k x n matrix
+ *   arithmetic         = fp32, every operation individually rounded (build with
+ *                        -ffp-contract=off -fno-fast-math); an fp64 evaluation of
+ *                        the same dequant sum is returned beside it.
+ *
+ * All functions return 0 on success, non-zero on a violated precondition.
+ */
+#include <fenv.h>
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define SQO_QMAX 127.0f
+
+int sqo_num_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
+
+/* bf16 -> fp32: append 16 zero bits (exact). */
+static float widen_bf16(uint16_t b) {
+  uint32_t u = ((uint32_t)b) << 16;
+  float f;
+  memcpy(&f, &u, 4);
+  return f;
+}
+
+void sqo_widen_bf16(const uint16_t* in, int64_t n, float* out) {
+  for (int64_t i = 0; i < n; ++i) out[i] = widen_bf16(in[i]);
+}
+
+/* fp32 -> bf16 with round-half-to-even on the dropped 16 bits (finite inputs). */
+void sqo_cast_bf16(const float* in, int64_t n, uint16_t* out) {
+  for (int64_t i = 0; i < n; ++i) {
+    uint32_t u;
+    memcpy(&u, &in[i], 4);
+    uint32_t lower = u & 0xFFFFu;
+    uint32_t upper = u >> 16;
+    if (lower > 0x8000u || (lower == 0x8000u && (upper & 1u))) upper += 1u;
+    out[i] = (uint16_t)upper;
+  }
+}
+
+/* Sec. 3 quantizer with z = 0: clip(round(v / s), -127, 127). */
+static int8_t quant_sym(float v, float s) {
+  float q = nearbyintf(v / s);
+  if (q > SQO_QMAX) q = SQO_QMAX;
+  if (q < -SQO_QMAX) q = -SQO_QMAX;
+  return (int8_t)q;
+}
+
+static int check_offsets(int n, int S, const int32_t* off) {
+  if (S < 1 || off[0] != 0 || off[S] != n) return 1;
+  for (int i = 0; i < S; ++i)
+    if (off[i + 1] <= off[i]) return 1;
+  return 0;
+}
+
+/*
+ * Weight quantization, Sec. 3 quantizer applied per segment (Sec. 4.2.2):
+ * for each output channel n and K-segment ks, a = max |W[n][k]| over the segment,
+ * step = a / 127 (1.0 if the segment row is all zero), codes = clip(round(W / step)).
+ *   w      fp32 [N][K]      wq  int8 [N][K]      wscale fp32 [S][N]
+ */
+int sqo_quantize_weight(const float* w, int N, int K, int S, const int32_t* kseg_off,
+                        int8_t* wq, float* wscale) {
+  if (fegetround() != FE_TONEAREST) return 2;
+  if (check_offsets(K, S, kseg_off)) return 1;
+#pragma omp parallel for schedule(static)
+  for (int n = 0; n < N; ++n) {
+    for (int ks = 0; ks < S; ++ks) {
+      float a = 0.0f;
+      for (int k = kseg_off[ks]; k < kseg_off[ks + 1]; ++k) {
+        float v = fabsf(w[(int64_t)n * K + k]);
+        if (v > a) a = v;
+      }
+      float sw = (a == 0.0f) ? 1.0f : a / SQO_QMAX;
+      wscale[(int64_t)ks * N + n] = sw;
+      for (int k = kseg_off[ks]; k < kseg_off[ks + 1]; ++k)
+        wq[(int64_t)n * K + k] = quant_sym(w[(int64_t)n * K + k], sw);
+    }
+  }
+  return 0;
+}
+
+/*
+ * Activation quantization.  Dual segment (Sec. 4.3.2): X_+ = max(X, 0), X_- = min(X, 0);
+ * x < 0 -> code round(x / s_-) in xq_neg (clipped at -127), x >= 0 -> code
+ * round(x / s_+) in xq_pos (clipped at 127); the other polarity's code is 0.
+ * Single-scale segment (Sec. 3, z = 0): xq_pos = clip(round(x / s_+)), xq_neg = 0.
+ *   x fp32 [M][K]     xq_pos, xq_neg int8 [M][K]
+ */
+int sqo_quantize_act(const float* x, int M, int K, int S, const int32_t* kseg_off,
+                     const uint8_t* dual, const float* s_pos, const float* s_neg,
+                     int8_t* xq_pos, int8_t* xq_neg) {
+  if (fegetround() != FE_TONEAREST) return 2;
+  if (check_offsets(K, S, kseg_off)) return 1;
+  for (int ks = 0; ks < S; ++ks) {
+    if (!(s_pos[ks] > 0.0f) || !isfinite(s_pos[ks])) return 3;
+    if (dual[ks] && (!(s_neg[ks] > 0.0f) || !isfinite(s_neg[ks]))) return 3;
+  }
+#pragma omp parallel for schedule(static)
+  for (int m = 0; m < M; ++m) {
+    for (int ks = 0; ks < S; ++ks) {
+      for (int k = kseg_off[ks]; k < kseg_off[ks + 1]; ++k) {
+        int64_t i = (int64_t)m * K + k;
+        float v = x[i];
+        if (dual[ks]) {
+          float xp = (v > 0.0f) ? v : 0.0f; /* max(x, 0); +-0 land here */
+          float xn = (v < 0.0f) ? v : 0.0f; /* min(x, 0) */
+          if (v < 0.0f) {
+            xq_neg[i] = quant_sym(xn, s_neg[ks]);
+            xq_pos[i] = 0;
+          } else {
+            xq_pos[i] = quant_sym(xp, s_pos[ks]);
+            xq_neg[i] = 0;
+          }
+        } else {
+          xq_pos[i] = quant_sym(v, s_pos[ks]);
+          xq_neg[i] = 0;
+        }
+      }
+    }
+  }
+  return 0;
+}
+
+/*
+ * Integer GEMM per K-segment on a subset of token rows.
+ *   acc_pos[ks][r][n] = sum_{k in ks} xq_pos[rows[r]][k] * wq[n][k]     (exact)
+ *   acc_neg[ks][r][n] = same with xq_neg for a dual segment, 0 otherwise.
+ * Sums are formed in int64 (int32 partial sums over at most 1024 terms, which
+ * cannot overflow: 1024 * 127 * 127 < 2^31) and must fit int32, else return 4.
+ *   rows == NULL  means rows 0..nrows-1.
+ *   acc_* int32 [S][nrows][N]
+ */
+int sqo_int_gemm(const int8_t* xq_pos, const int8_t* xq_neg, const int8_t* wq, int M, int K, int N,
+                 int S, const int32_t* kseg_off, const uint8_t* dual, int nrows, const int32_t* rows,
+                 int32_t* acc_pos, int32_t* acc_neg) {
+  if (check_offsets(K, S, kseg_off)) return 1;
+  for (int r = 0; r < nrows; ++r) {
+    int m = rows ? rows[r] : r;
+    if (m < 0 || m >= M) return 1;
+  }
+  int overflow = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic, 64) reduction(| : overflow)
+  for (int r = 0; r < nrows; ++r) {
+    for (int n = 0; n < N; ++n) {
+      int m = rows ? rows[r] : r;
+      const int8_t* xp = xq_pos + (int64_t)m * K;
+      const int8_t* xn = xq_neg + (int64_t)m * K;
+      const int8_t* wr = wq + (int64_t)n * K;
+      for (int ks = 0; ks < S; ++ks) {
+        int64_t sp = 0, sn = 0;
+        int k0 = kseg_off[ks], k1 = kseg_off[ks + 1];
+        for (int kb = k0; kb < k1; kb += 1024) {
+          int ke = kb + 1024 < k1 ? kb + 1024 : k1;
+          int32_t pp = 0, pn = 0;
+          for (int k = kb; k < ke; ++k) pp += (int32_t)xp[k] * (int32_t)wr[k];
+          if (dual[ks])
+            for (int k = kb; k < ke; ++k) pn += (int32_t)xn[k] * (int32_t)wr[k];
+          sp += pp;
+          sn += pn;
+        }
+        if (sp > INT32_MAX || sp < INT32_MIN || sn > INT32_MAX || sn < INT32_MIN) overflow |= 1;
+        int64_t o = ((int64_t)ks * nrows + r) * N + n;
+        acc_pos[o] = (int32_t)sp;
+        acc_neg[o] = (int32_t)sn;
+      }
+    }
+  }
+  return overflow ? 4 : 0;
+}
+
+/*
+ * Dequantization and recombination (Sec. 4.3.2 last display, summed over the
+ * K-segments of Sec. 4.2.2 item 2, column n scaled with the step of its own
+ * weight segment, item 1).  fp32, in this order:
+ *   y = 0
+ *   for ks:  c = seg_scale[ks][ns(n)] * wscale[ks][n]
+ *            t = s_pos[ks] * (float)acc_pos ;  if dual: t += s_neg[ks] * (float)acc_neg
+ *            y += c * t
+ *   y += bias[n]
+ * y64 (optional) is the same sum evaluated in double.
+ *   acc_* int32 [S][nrows][N]; wscale fp32 [S][N]; seg_scale fp32 [S][T] or NULL (= 1);
+ *   bias fp32 [N] or NULL;  y32 fp32 [nrows][N]; y64 double [nrows][N] or NULL
+ */
+int sqo_dequant(const int32_t* acc_pos, const int32_t* acc_neg, int nrows, int N, int S, int T,
+                const int32_t* nseg_off, const uint8_t* dual, const float* s_pos, const float* s_neg,
+                const float* wscale, const float* seg_scale, const float* bias, float* y32,
+                double* y64) {
+  if (check_offsets(N, T, nseg_off)) return 1;
+  int* nsof = (int*)malloc(sizeof(int) * (size_t)N);
+  if (!nsof) return 5;
+  for (int t = 0; t < T; ++t)
+    for (int n = nseg_off[t]; n < nseg_off[t + 1]; ++n) nsof[n] = t;
+#pragma omp parallel for schedule(static)
+  for (int r = 0; r < nrows; ++r) {
+    for (int n = 0; n < N; ++n) {
+      float y = 0.0f;
+      double yd = 0.0;
+      for (int ks = 0; ks < S; ++ks) {
+        float g = seg_scale ? seg_scale[ks * T + nsof[n]] : 1.0f;
+        float sw = wscale[(int64_t)ks * N + n];
+        int64_t o = ((int64_t)ks * nrows + r) * N + n;
+        float c = g * sw;
+        float t = s_pos[ks] * (float)acc_pos[o];
+        double td = (double)s_pos[ks] * (double)acc_pos[o];
+        if (dual[ks]) {
+          t += s_neg[ks] * (float)acc_neg[o];
+          td += (double)s_neg[ks] * (double)acc_neg[o];
+        }
+        y += c * t;
+        yd += (double)g * (double)sw * td;
+      }
+      if (bias) {
+        y += bias[n];
+        yd += (double)bias[n];
+      }
+      y32[(int64_t)r * N + n] = y;
+      if (y64) y64[(int64_t)r * N + n] = yd;
+    }
+  }
+  free(nsof);
+  return 0;
+}
+
+/* Full-precision layer the quantized one approximates: Y = X W^T (+ bias) in double, selected rows. */
+int sqo_fp_reference(const float* x, const float* w, int M, int K, int N, int nrows,
+                     const int32_t* rows, const float* bias, double* yfp) {
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int r = 0; r < nrows; ++r) {
+    for (int n = 0; n < N; ++n) {
+      int m = rows ? rows[r] : r;
+      double s = 0.0;
+      for (int k = 0; k < K; ++k) s += (double)x[(int64_t)m * K + k] * (double)w[(int64_t)n * K + k];
+      if (bias) s += (double)bias[n];
+      yfp[(int64_t)r * N + n] = s;
+    }
+  }
+  (void)M;
+  return 0;
+}
+
+/*
+ * Analytic bound on |y_quantized - y_full_precision| when no value is clipped
+ * (steps = absmax / 127) and seg_scale == 1.  Rounding to nearest (Sec. 3) gives
+ * |x - s_x x^| <= s_x / 2 and |w - s_w w^| <= s_w / 2, hence per product
+ *   |x w - (s_x x^)(s_w w^)| <= |x| s_w / 2 + |w| s_x / 2 + s_x s_w / 4
+ * with s_x the step of x's segment and polarity.  Summed over k, in double.
+ */
+int sqo_error_bound(const float* x, const float* w, int M, int K, int N, int S,
+                    const int32_t* kseg_off, const uint8_t* dual, const float* s_pos,
+                    const float* s_neg, const float* wscale, int nrows, const int32_t* rows,
+                    double* bound) {
+  if (check_offsets(K, S, kseg_off)) return 1;
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int r = 0; r < nrows; ++r) {
+    for (int n = 0; n < N; ++n) {
+      int m = rows ? rows[r] : r;
+      double b = 0.0;
+      for (int ks = 0; ks < S; ++ks) {
+        double sw = wscale[(int64_t)ks * N + n];
+        for (int k = kseg_off[ks]; k < kseg_off[ks + 1]; ++k) {
+          double xv = x[(int64_t)m * K + k], wv = w[(int64_t)n * K + k];
+          double sx = (dual[ks] && xv < 0.0) ? s_neg[ks] : s_pos[ks];
+          b += fabs(xv) * sw * 0.5 + fabs(wv) * sx * 0.5 + sx * sw * 0.25;
+        }
+      }
+      bound[(int64_t)r * N + n] = b;
+    }
+  }
+  (void)M;
+  return 0;
+}

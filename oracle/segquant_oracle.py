@@ -1,0 +1,191 @@
+"""numpy front-end of the plain-C CPU oracle (test infrastructure only).
+
+Argument marshalling only: every arithmetic step is in ``segquant_oracle.c``
+next to this file.  ``build()`` compiles it with gcc; the shared object is
+loaded lazily and rebuilt when the source is newer.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "segquant_oracle.c")
+_SO = os.path.join(_HERE, "libsegquant_oracle.so")
+_lib = None
+
+_CFLAGS = ["-O3", "-std=c99", "-fopenmp", "-fno-fast-math", "-ffp-contract=off", "-frounding-math",
+           "-fPIC", "-shared", "-Wall"]
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle (gcc).  Returns the path of the shared object."""
+    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
+        tmp = _SO + f".tmp{os.getpid()}"
+        subprocess.check_call(["gcc", *_CFLAGS, _SRC, "-o", tmp, "-lm"])
+        os.replace(tmp, _SO)
+    return _SO
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = C.CDLL(_SO)
+        _lib.sqo_num_threads.restype = C.c_int
+    return _lib
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _u8(a):
+    return np.ascontiguousarray(a, dtype=np.uint8)
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise RuntimeError(f"oracle {what} failed with code {rc}")
+
+
+def num_threads() -> int:
+    return int(_load().sqo_num_threads())
+
+
+def widen_bf16(bits: np.ndarray) -> np.ndarray:
+    bits = np.ascontiguousarray(bits, dtype=np.uint16)
+    out = np.empty(bits.shape, dtype=np.float32)
+    _load().sqo_widen_bf16(_p(bits), C.c_int64(bits.size), _p(out))
+    return out
+
+
+def cast_bf16(y: np.ndarray) -> np.ndarray:
+    y = _f32(y)
+    out = np.empty(y.shape, dtype=np.uint16)
+    _load().sqo_cast_bf16(_p(y), C.c_int64(y.size), _p(out))
+    return out
+
+
+def quantize_weight(w: np.ndarray, kseg_off):
+    """-> (wq int8 [N][K], wscale fp32 [S][N])"""
+    w = _f32(w)
+    N, K = w.shape
+    off = _i32(kseg_off)
+    S = len(off) - 1
+    wq = np.empty((N, K), dtype=np.int8)
+    ws = np.empty((S, N), dtype=np.float32)
+    _check(_load().sqo_quantize_weight(_p(w), N, K, S, _p(off), _p(wq), _p(ws)), "quantize_weight")
+    return wq, ws
+
+
+def quantize_act(x: np.ndarray, kseg_off, dual, s_pos, s_neg):
+    """x fp32 [M][K] (bf16 inputs are widened first) -> (xq_pos, xq_neg) int8 [M][K]"""
+    x = _f32(x)
+    M, K = x.shape
+    off, dual, s_pos, s_neg = _i32(kseg_off), _u8(dual), _f32(s_pos), _f32(s_neg)
+    S = len(off) - 1
+    xp = np.empty((M, K), dtype=np.int8)
+    xn = np.empty((M, K), dtype=np.int8)
+    _check(_load().sqo_quantize_act(_p(x), M, K, S, _p(off), _p(dual), _p(s_pos), _p(s_neg), _p(xp), _p(xn)),
+           "quantize_act")
+    return xp, xn
+
+
+def int_gemm(xq_pos, xq_neg, wq, kseg_off, dual, rows=None):
+    """-> (acc_pos, acc_neg) int32 [S][nrows][N]; rows = subset of token rows or None (all)."""
+    xq_pos = np.ascontiguousarray(xq_pos, dtype=np.int8)
+    xq_neg = np.ascontiguousarray(xq_neg, dtype=np.int8)
+    wq = np.ascontiguousarray(wq, dtype=np.int8)
+    M, K = xq_pos.shape
+    N = wq.shape[0]
+    off, dual = _i32(kseg_off), _u8(dual)
+    S = len(off) - 1
+    r = None if rows is None else _i32(rows)
+    nrows = M if r is None else len(r)
+    ap = np.empty((S, nrows, N), dtype=np.int32)
+    an = np.empty((S, nrows, N), dtype=np.int32)
+    _check(_load().sqo_int_gemm(_p(xq_pos), _p(xq_neg), _p(wq), M, K, N, S, _p(off), _p(dual), nrows, _p(r),
+                                _p(ap), _p(an)), "int_gemm")
+    return ap, an
+
+
+def dequant(acc_pos, acc_neg, nseg_off, dual, s_pos, s_neg, wscale, seg_scale=None, bias=None, want64=True):
+    """-> (y32 fp32 [nrows][N], y64 double [nrows][N] or None)"""
+    acc_pos = np.ascontiguousarray(acc_pos, dtype=np.int32)
+    acc_neg = np.ascontiguousarray(acc_neg, dtype=np.int32)
+    S, nrows, N = acc_pos.shape
+    noff, dual, s_pos, s_neg, wscale = _i32(nseg_off), _u8(dual), _f32(s_pos), _f32(s_neg), _f32(wscale)
+    T = len(noff) - 1
+    g = None if seg_scale is None else _f32(seg_scale)
+    b = None if bias is None else _f32(bias)
+    y32 = np.empty((nrows, N), dtype=np.float32)
+    y64 = np.empty((nrows, N), dtype=np.float64) if want64 else None
+    _check(_load().sqo_dequant(_p(acc_pos), _p(acc_neg), nrows, N, S, T, _p(noff), _p(dual), _p(s_pos), _p(s_neg),
+                               _p(wscale), _p(g), _p(b), _p(y32), _p(y64)), "dequant")
+    return y32, y64
+
+
+def fp_reference(x, w, rows=None, bias=None):
+    x, w = _f32(x), _f32(w)
+    M, K = x.shape
+    N = w.shape[0]
+    r = None if rows is None else _i32(rows)
+    nrows = M if r is None else len(r)
+    b = None if bias is None else _f32(bias)
+    y = np.empty((nrows, N), dtype=np.float64)
+    _check(_load().sqo_fp_reference(_p(x), _p(w), M, K, N, nrows, _p(r), _p(b), _p(y)), "fp_reference")
+    return y
+
+
+def error_bound(x, w, kseg_off, dual, s_pos, s_neg, wscale, rows=None):
+    x, w = _f32(x), _f32(w)
+    M, K = x.shape
+    N = w.shape[0]
+    off, dual, s_pos, s_neg, wscale = _i32(kseg_off), _u8(dual), _f32(s_pos), _f32(s_neg), _f32(wscale)
+    S = len(off) - 1
+    r = None if rows is None else _i32(rows)
+    nrows = M if r is None else len(r)
+    out = np.empty((nrows, N), dtype=np.float64)
+    _check(_load().sqo_error_bound(_p(x), _p(w), M, K, N, S, _p(off), _p(dual), _p(s_pos), _p(s_neg), _p(wscale),
+                                   nrows, _p(r), _p(out)), "error_bound")
+    return out
+
+
+@dataclass
+class OracleResult:
+    wq: np.ndarray
+    wscale: np.ndarray
+    xq_pos: np.ndarray
+    xq_neg: np.ndarray
+    rows: Optional[np.ndarray]
+    acc_pos: np.ndarray
+    acc_neg: np.ndarray
+    y32: np.ndarray
+    y64: Optional[np.ndarray]
+
+    @property
+    def y_bf16_bits(self) -> np.ndarray:
+        return cast_bf16(self.y32)
+
+
+def seglinear(x, w, kseg_off, nseg_off, dual, s_pos, s_neg, seg_scale=None, bias=None, rows=None) -> OracleResult:
+    """The whole layer, step by step: Quant(W), Q_dual(X), integer GEMM, DeQuant."""
+    wq, ws = quantize_weight(w, kseg_off)
+    xp, xn = quantize_act(x, kseg_off, dual, s_pos, s_neg)
+    ap, an = int_gemm(xp, xn, wq, kseg_off, dual, rows)
+    y32, y64 = dequant(ap, an, nseg_off, dual, s_pos, s_neg, ws, seg_scale, bias)
+    return OracleResult(wq, ws, xp, xn, None if rows is None else np.asarray(rows), ap, an, y32, y64)

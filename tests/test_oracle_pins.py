@@ -1,0 +1,339 @@
+"""Pins for the CPU oracle: everything here runs without a GPU.
+
+The oracle is checked against things that are not the oracle: hand-worked
+numbers (tests/golden), brute force in Python integers / exact rationals,
+closed forms, invariants the paper states, reduction to textbook W8A8, and the
+analytic quantization-error bound.
+"""
+import json
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from paper_2507_14811_amd import workloads as wl
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ----------------------------------------------------------------------------
+# hand-worked example (tests/golden/handworked_2x4x2.json)
+# ----------------------------------------------------------------------------
+@pytest.fixture(scope="module")
+def gold():
+    with open(os.path.join(GOLD, "handworked_2x4x2.json")) as f:
+        return json.load(f)
+
+
+def test_handworked_codes_and_accumulators(oracle, gold):
+    g, e = gold, gold["expect"]
+    x = np.array(g["x"], np.float32)
+    w = np.array(g["w"], np.float32)
+    wq, ws = oracle.quantize_weight(w, g["kseg_off"])
+    xp, xn = oracle.quantize_act(x, g["kseg_off"], g["dual"], g["s_pos"], g["s_neg"])
+    ap, an = oracle.int_gemm(xp, xn, wq, g["kseg_off"], g["dual"])
+    assert wq.tolist() == e["wq"]
+    assert ws.tolist() == e["wscale"]
+    assert xp.tolist() == e["xq_pos"]
+    assert xn.tolist() == e["xq_neg"]
+    assert ap.tolist() == e["acc_pos"]
+    assert an.tolist() == e["acc_neg"]
+
+
+@pytest.mark.parametrize("case", ["case_plain", "case_segscale_bias"])
+def test_handworked_output(oracle, gold, case):
+    g, c = gold, gold[case]
+    r = oracle.seglinear(np.array(g["x"], np.float32), np.array(g["w"], np.float32), g["kseg_off"], c["nseg_off"],
+                         g["dual"], g["s_pos"], g["s_neg"],
+                         None if c["seg_scale"] is None else np.array(c["seg_scale"], np.float32),
+                         None if c["bias"] is None else np.array(c["bias"], np.float32))
+    assert r.y32.tolist() == c["y"]          # exact: every operand is a dyadic rational
+    assert r.y64.tolist() == c["y"]
+
+
+def test_bf16_cast_ties(oracle, gold):
+    b = gold["bf16_cast"]
+    f = np.array([int(h, 16) for h in b["f32_hex"]], np.uint32).view(np.float32)
+    got = oracle.cast_bf16(f)
+    assert [f"{v:04X}" for v in got.tolist()] == b["bf16_hex"]
+    # widening is the exact inverse on bf16 values
+    assert np.array_equal(oracle.cast_bf16(oracle.widen_bf16(got)), got)
+    # and agrees with the (independent) data-preparation helper on random values
+    r = np.random.default_rng(1).standard_normal(10000).astype(np.float32) * 37
+    assert np.array_equal(oracle.cast_bf16(r), wl.f32_to_bf16_bits(r))
+
+
+# ----------------------------------------------------------------------------
+# brute force on tiny inputs: Python ints and exact rationals
+# ----------------------------------------------------------------------------
+def _rne_fraction(q: Fraction) -> int:
+    fl = math.floor(q)
+    d = q - fl
+    if d > Fraction(1, 2):
+        return fl + 1
+    if d < Fraction(1, 2):
+        return fl
+    return fl if fl % 2 == 0 else fl + 1
+
+
+def _clip(v, lo=-127, hi=127):
+    return max(lo, min(hi, v))
+
+
+def _brute(x, w, kseg, nseg, dual, s_pos, s_neg, seg_scale, bias):
+    """Independent evaluation with exact rationals.  Scales must be powers of two times small
+    integers so that fp32 x / s is exact and the rational rounding equals the fp32 one."""
+    M, K = x.shape
+    N = w.shape[0]
+    S, T = len(kseg) - 1, len(nseg) - 1
+    F = lambda v: Fraction(float(v))
+    wq = [[0] * K for _ in range(N)]
+    wsc = [[Fraction(1)] * N for _ in range(S)]
+    for n in range(N):
+        for ks in range(S):
+            a = max(abs(F(w[n, k])) for k in range(kseg[ks], kseg[ks + 1]))
+            sw = a / 127 if a != 0 else Fraction(1)
+            wsc[ks][n] = sw
+            for k in range(kseg[ks], kseg[ks + 1]):
+                wq[n][k] = _clip(_rne_fraction(F(w[n, k]) / sw))
+    xp = [[0] * K for _ in range(M)]
+    xn = [[0] * K for _ in range(M)]
+    for m in range(M):
+        for ks in range(S):
+            for k in range(kseg[ks], kseg[ks + 1]):
+                v = F(x[m, k])
+                if dual[ks]:
+                    if v < 0:
+                        xn[m][k] = _clip(_rne_fraction(v / F(s_neg[ks])))
+                    else:
+                        xp[m][k] = _clip(_rne_fraction(v / F(s_pos[ks])))
+                else:
+                    xp[m][k] = _clip(_rne_fraction(v / F(s_pos[ks])))
+    y = [[Fraction(0)] * N for _ in range(M)]
+    accp = [[[0] * N for _ in range(M)] for _ in range(S)]
+    accn = [[[0] * N for _ in range(M)] for _ in range(S)]
+    for m in range(M):
+        for n in range(N):
+            t = next(j for j in range(T) if nseg[j] <= n < nseg[j + 1])
+            for ks in range(S):
+                ap = sum(xp[m][k] * wq[n][k] for k in range(kseg[ks], kseg[ks + 1]))
+                an = sum(xn[m][k] * wq[n][k] for k in range(kseg[ks], kseg[ks + 1])) if dual[ks] else 0
+                accp[ks][m][n], accn[ks][m][n] = ap, an
+                g = F(seg_scale[ks][t]) if seg_scale is not None else Fraction(1)
+                y[m][n] += g * wsc[ks][n] * (F(s_pos[ks]) * ap + (F(s_neg[ks]) * an if dual[ks] else 0))
+            if bias is not None:
+                y[m][n] += F(bias[n])
+    return wq, wsc, xp, xn, accp, accn, y
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_brute_force_tiny(oracle, seed):
+    rng = np.random.default_rng(100 + seed)
+    M, K, N = int(rng.integers(1, 7)), int(rng.integers(2, 9)), int(rng.integers(1, 8))
+    S = 2 if K >= 2 and seed % 2 else 1
+    T = 2 if N >= 2 and seed % 3 else 1
+    kseg = [0, K] if S == 1 else [0, int(rng.integers(1, K)), K]
+    nseg = [0, N] if T == 1 else [0, int(rng.integers(1, N)), N]
+    dual = [int(rng.integers(0, 2)) for _ in range(S)]
+    if seed == 0:
+        dual = [1] * S
+    # dyadic data: x multiples of 1/64, scales powers of two => fp32 x/s exact, ties occur often.
+    # weights: integers i/2^j with the per-(row, segment) absmax forced to 127/2^j => step exactly 2^-j.
+    x = (rng.integers(-300, 301, size=(M, K)) / 64.0).astype(np.float32)
+    s_pos = np.array([2.0 ** int(rng.integers(-6, 1)) for _ in range(S)], np.float32)
+    s_neg = np.array([2.0 ** int(rng.integers(-8, -2)) for _ in range(S)], np.float32)
+    w = np.zeros((N, K), np.float32)
+    for n in range(N):
+        for ks in range(S):
+            j = int(rng.integers(3, 9))
+            seg = rng.integers(-2 * 127, 2 * 127 + 1, size=kseg[ks + 1] - kseg[ks]) / 2.0   # half-integers: ties
+            seg[int(rng.integers(0, len(seg)))] = 127.0 * (1 if rng.integers(0, 2) else -1)
+            w[n, kseg[ks]:kseg[ks + 1]] = seg / 2.0 ** j
+    seg_scale = rng.choice([0.5, 1.0, 2.0, 4.0], size=(S, T)).astype(np.float32) if seed % 2 else None
+    bias = (rng.integers(-8, 9, size=N) / 4.0).astype(np.float32) if seed % 3 == 0 else None
+
+    r = oracle.seglinear(x, w, kseg, nseg, dual, s_pos, s_neg, seg_scale, bias)
+    wq, wsc, xp, xn, accp, accn, y = _brute(x, w, kseg, nseg, dual, s_pos, s_neg, seg_scale, bias)
+    assert r.wq.tolist() == wq
+    assert [[Fraction(float(v)) for v in row] for row in r.wscale] == wsc
+    assert r.xq_pos.tolist() == xp and r.xq_neg.tolist() == xn
+    assert r.acc_pos.tolist() == accp and r.acc_neg.tolist() == accn
+    yb = np.array([[float(v) for v in row] for row in y])
+    assert np.allclose(r.y64, yb, rtol=1e-13, atol=1e-13)
+    scale = max(1.0, float(np.abs(yb).max()))
+    assert np.abs(r.y32 - yb).max() <= 1e-6 * scale
+
+
+def test_general_scales_nearest_code_property(oracle):
+    """For arbitrary (non-dyadic) steps the code is the nearest integer to x/s, clipped (Sec. 3)."""
+    rng = np.random.default_rng(7)
+    x = (rng.standard_normal((5, 64)) * 3).astype(np.float32)
+    s_pos, s_neg = np.array([0.0123], np.float32), np.array([0.00457], np.float32)
+    xp, xn = oracle.quantize_act(x, [0, 64], [1], s_pos, s_neg)
+    for v, p, n in zip(x.ravel().tolist(), xp.ravel().tolist(), xn.ravel().tolist()):
+        q = Fraction(v) / Fraction(float(s_neg[0] if v < 0 else s_pos[0]))
+        want = _clip(_rne_fraction(q))
+        got = n if v < 0 else p
+        assert abs(got - want) <= (1 if abs(abs(q - math.floor(q)) - Fraction(1, 2)) < Fraction(1, 10 ** 5) else 0)
+        assert (p == 0) if v < 0 else (n == 0)
+    assert np.any(xp == 127) and np.any(xn == -127)      # clipping exercised
+
+
+# ----------------------------------------------------------------------------
+# invariants stated by the paper
+# ----------------------------------------------------------------------------
+def test_polarity_split_is_exact(oracle):
+    """X = X_+ + X_- (Sec. 4.3.2) and the two code tensors have disjoint support and fixed signs."""
+    w_ = wl.cfg1_tiny()
+    xpos, xneg = np.maximum(w_.x, 0), np.minimum(w_.x, 0)
+    assert np.array_equal((xpos + xneg).view(np.uint32), w_.x.view(np.uint32))
+    xp, xn = oracle.quantize_act(w_.x, w_.kseg_off, w_.dual, w_.s_pos, w_.s_neg)
+    assert (xp >= 0).all() and (xn <= 0).all()
+    assert not np.any((xp != 0) & (xn != 0))
+    assert xp.max() == 127 and xn.min() == -127            # steps = extreme / 127 reach the range ends
+    # quantizing the two halves separately gives the same codes as Q_dual on X
+    zp, _ = oracle.quantize_act(xpos, w_.kseg_off, w_.dual, w_.s_pos, w_.s_neg)
+    _, zn = oracle.quantize_act(xneg, w_.kseg_off, w_.dual, w_.s_pos, w_.s_neg)
+    assert np.array_equal(zp, xp) and np.array_equal(zn, xn)
+
+
+def test_reduces_to_textbook_w8a8(oracle):
+    """x >= 0, one segment, per-tensor weight step: DualScale == plain symmetric W8A8 (App. A)."""
+    rng = np.random.default_rng(11)
+    M, K, N = 9, 40, 7
+    x = np.maximum(rng.standard_normal((M, K)), 0).astype(np.float32)
+    w = (rng.standard_normal((N, K)) * 0.05).astype(np.float32)
+    w[:, 0] = np.abs(w).max() * np.sign(w[:, 0] + 1e-9)        # every row reaches the same absmax
+    s_x = np.float32(x.max()) / np.float32(127)
+    r = oracle.seglinear(x, w, [0, K], [0, N], [1], [s_x], [np.float32(1.0)])
+    assert not r.acc_neg.any()
+    s_w = np.float32(np.abs(w).max()) / np.float32(127)
+    assert np.all(r.wscale == s_w)
+    # textbook routine: numpy rint (half-even) + int64 matmul + one product of scales
+    xq = np.clip(np.rint(x / s_x), -127, 127).astype(np.int64)
+    wq = np.clip(np.rint(w / s_w), -127, 127).astype(np.int64)
+    yhat = xq @ wq.T
+    assert np.array_equal(r.acc_pos[0], yhat)
+    y = np.float64(s_x) * np.float64(s_w) * yhat
+    assert np.abs(r.y64 - y).max() <= 1e-12 * np.abs(y).max()
+    assert np.abs(r.y32 - y).max() <= 2e-7 * np.abs(y).max()
+
+
+def test_grid_values_round_trip(oracle):
+    """Values on the quantization grid come back as their own codes; small-K product is exact."""
+    rng = np.random.default_rng(5)
+    M, K, N = 6, 16, 5
+    s_p, s_n, s_w = np.float32(2.0 ** -4), np.float32(2.0 ** -7), 2.0 ** -6
+    j = rng.integers(-127, 128, size=(M, K))
+    j[0, 0], j[0, 1] = 127, -127
+    x = np.where(j >= 0, j * float(s_p), j * float(s_n)).astype(np.float32)
+    i = rng.integers(-127, 128, size=(N, K))
+    i[:, 3] = 127
+    w = (i * s_w).astype(np.float32)
+    r = oracle.seglinear(x, w, [0, K], [0, N], [1], [s_p], [s_n])
+    assert np.array_equal(r.xq_pos, np.where(j >= 0, j, 0))
+    assert np.array_equal(r.xq_neg, np.where(j < 0, j, 0))
+    assert np.array_equal(r.wq, i)
+    assert np.all(r.wscale == np.float32(s_w))
+    exact = x.astype(np.float64) @ w.astype(np.float64).T
+    assert np.array_equal(r.y64, exact)
+    assert np.array_equal(r.y32.astype(np.float64), exact)   # all partial sums fit 24 bits here
+
+
+def test_equal_scales_collapse_to_single_path(oracle):
+    """s_+ = s_- makes Q_dual the plain symmetric quantizer: codes and accumulators add up exactly."""
+    w_ = wl.random_layer(13, 96, 21, [0, 32, 96], [0, 21], [1, 1], seed=3, x_dtype="f32", act="normal")
+    s = np.maximum(w_.s_pos, w_.s_neg)
+    wq, _ = oracle.quantize_weight(w_.w, w_.kseg_off)
+    xp, xn = oracle.quantize_act(w_.x, w_.kseg_off, [1, 1], s, s)
+    x1, z1 = oracle.quantize_act(w_.x, w_.kseg_off, [0, 0], s, s)
+    assert np.array_equal(xp.astype(np.int32) + xn, x1) and not z1.any()
+    ap, an = oracle.int_gemm(xp, xn, wq, w_.kseg_off, [1, 1])
+    a1, _ = oracle.int_gemm(x1, z1, wq, w_.kseg_off, [0, 0])
+    assert np.array_equal(ap + an, a1)
+
+
+def test_segmentation_bookkeeping(oracle):
+    """SegLinear invariances (Sec. 4.2.2): splitting a K-segment with equal steps keeps the integer sum;
+    permuting whole N-segments permutes output columns; N-segment boundaries do not matter when seg_scale = 1."""
+    w_ = wl.random_layer(7, 64, 24, [0, 64], [0, 8, 24], [1], seed=9, x_dtype="f32", act="gelu")
+    wq, ws = oracle.quantize_weight(w_.w, [0, 64])
+    xp, xn = oracle.quantize_act(w_.x, [0, 64], [1], w_.s_pos, w_.s_neg)
+    a1p, a1n = oracle.int_gemm(xp, xn, wq, [0, 64], [1])
+    a2p, a2n = oracle.int_gemm(xp, xn, wq, [0, 24, 64], [1, 1])
+    assert np.array_equal(a2p.sum(0), a1p[0]) and np.array_equal(a2n.sum(0), a1n[0])
+    # K-segment slices really are the column ranges kseg_off names
+    a_first, _ = oracle.int_gemm(xp[:, :24].copy(), xn[:, :24].copy(), wq[:, :24].copy(), [0, 24], [1])
+    assert np.array_equal(a2p[0], a_first[0])
+    y_a, _ = oracle.dequant(a1p, a1n, [0, 8, 24], [1], w_.s_pos, w_.s_neg, ws)
+    y_b, _ = oracle.dequant(a1p, a1n, [0, 24], [1], w_.s_pos, w_.s_neg, ws)
+    assert np.array_equal(y_a, y_b)
+    perm = np.r_[8:24, 0:8]
+    r_p = oracle.seglinear(w_.x, w_.w[perm], [0, 64], [0, 16, 24], [1], w_.s_pos, w_.s_neg)
+    assert np.array_equal(r_p.y32, y_a[:, perm])
+    # seg_scale multiplies exactly its own (K-segment, N-segment) block
+    g = np.array([[2.0, 0.5]], np.float32)
+    y_g, _ = oracle.dequant(a1p, a1n, [0, 8, 24], [1], w_.s_pos, w_.s_neg, ws, g)
+    assert np.array_equal(y_g[:, :8], 2 * y_a[:, :8]) and np.array_equal(y_g[:, 8:], 0.5 * y_a[:, 8:])
+
+
+def test_int32_guard(oracle):
+    """127 * 127 * K_ks must fit int32: the oracle refuses a segment whose worst case does not."""
+    K = 133200                                   # 127^2 * K > 2^31 - 1
+    xp = np.full((1, K), 127, np.int8)
+    wq = np.full((1, K), 127, np.int8)
+    with pytest.raises(RuntimeError):
+        oracle.int_gemm(xp, np.zeros_like(xp), wq, [0, K], [0])
+    ap, _ = oracle.int_gemm(xp[:, :133143].copy(), xp[:, :133143].copy() * 0, wq[:, :133143].copy(), [0, 133143], [0])
+    assert int(ap[0, 0, 0]) == 127 * 127 * 133143
+
+
+# ----------------------------------------------------------------------------
+# accuracy: analytic bound and the paper's qualitative claims
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("name", ["cfg1", "rand"])
+def test_analytic_error_bound(oracle, name):
+    w_ = wl.cfg1_tiny() if name == "cfg1" else wl.random_layer(11, 192, 37, [0, 64, 192], [0, 37], [0, 1], seed=21,
+                                                               x_dtype="bf16", act="gelu")
+    r = oracle.seglinear(w_.x, w_.w, w_.kseg_off, w_.nseg_off, w_.dual, w_.s_pos, w_.s_neg)
+    yfp = oracle.fp_reference(w_.x, w_.w)
+    bound = oracle.error_bound(w_.x, w_.w, w_.kseg_off, w_.dual, w_.s_pos, w_.s_neg, r.wscale)
+    err = np.abs(r.y64 - yfp)
+    assert (err <= bound * (1 + 1e-6) + 1e-9).all()
+    assert err.max() > 1e-3 * bound.max()          # the bound is not vacuous: real error is within 3 decades of it
+    assert np.abs(r.y32 - r.y64).max() <= 1e-6 * np.abs(r.y64).max()
+
+
+def test_silu_gelu_negative_range_anchors():
+    """Closed forms behind the narrow negative range (Sec. 4.3.1): min SiLU = -0.27846, min GELU = -0.16997."""
+    z = np.linspace(-6, 0, 600001)
+    assert abs(wl._silu(z).min() + 0.278464542761) < 1e-9
+    assert abs(wl._gelu(z).min() + 0.169971) < 1e-6
+    w_ = wl.cfg1_tiny()
+    assert (w_.s_neg <= np.float32(0.2785 / 127)).all() and (w_.s_pos > 5 * w_.s_neg).all()
+
+
+def test_dual_scale_beats_single_scale_on_silu(oracle):
+    """Direction of the sensitivity table in App. B: lower relative F-norm error with DualScale."""
+    w_ = wl.random_layer(64, 256, 96, [0, 256], [0, 96], [1], seed=2, x_dtype="f32", act="silu")
+    yfp = oracle.fp_reference(w_.x, w_.w)
+    rd = oracle.seglinear(w_.x, w_.w, w_.kseg_off, w_.nseg_off, [1], w_.s_pos, w_.s_neg)
+    s1 = np.float32(np.abs(w_.x).max()) / np.float32(127)
+    rs = oracle.seglinear(w_.x, w_.w, w_.kseg_off, w_.nseg_off, [0], [s1], [s1])
+    fd = np.linalg.norm(rd.y64 - yfp) / np.linalg.norm(yfp)
+    fs = np.linalg.norm(rs.y64 - yfp) / np.linalg.norm(yfp)
+    assert fd < fs
+
+
+def test_workload_recipes():
+    """Shapes, segment tables and op counts of the named configurations."""
+    c1 = wl.cfg1_tiny()
+    assert (c1.M, c1.K, c1.N, c1.S, c1.T) == (64, 256, 384, 2, 3) and c1.int8_ops == 2 * 64 * 384 * 512
+    c3 = wl.cfg3_adaln()
+    assert (c3.M, c3.K, c3.N, c3.T) == (16, 1152, 6912, 6) and sorted(c3.extra["sigma"]) == [0.01, 0.02, 0.05, 0.1, 0.2, 0.5]
+    assert c3.x_dtype == "bf16" and np.array_equal(wl.bf16_bits_to_f32(c3.x_bf16_bits()), c3.x)
+    stds = [c3.w[j * 1152:(j + 1) * 1152].std() for j in range(6)]
+    assert np.allclose(stds, c3.extra["sigma"], rtol=0.02)
+    assert c3.seglinear_bytes() == 16 * 2304 + 6912 * 1152 + 4 * 6912 + 16 * 6912 * 2
