@@ -1,0 +1,135 @@
+/*
+ * segquant.h - C ABI of the MI355X (gfx950) SegLinear + DualScale quantized linear layer
+ * (SegQuant, arXiv 2507.14811).
+ *
+ * The quantized forward pass is the three-step composition of App. A,
+ *     Y ~= DeQuant( Quant(X) . Quant(W) ),
+ * with
+ *   - SegLinear (Sec. 4.2.2): the weight is cut along its output dimension into N-segments
+ *     (item 1, layers followed by chunk/split) and along its input dimension into K-segments
+ *     (item 2, layers fed by concat/reshape); every segment has quantization steps of its own
+ *     and the K-segment products are summed;
+ *   - DualScale (Sec. 4.3.2): an activation that follows SiLU/GELU is split by polarity,
+ *     X = X_+ + X_-, each part is quantized with its own step (s_+, s_-), both int8 products
+ *     run against the same int8 weight and are recombined as
+ *         s_+ s_w (X^_+ W^) + s_- s_w (X^_- W^).
+ *
+ * Conventions shared by all calls
+ *   Memory     "dev" pointers are device (HBM) memory owned by the caller, dense row-major, base
+ *              16-byte aligned.  Pointers inside sq_layer are HOST memory, read during the call
+ *              only.  The library allocates nothing and keeps no per-call state.
+ *   Layout     activations X[M][K] (K contiguous); weights W[N][K] (row = output channel, K
+ *              contiguous: the transpose of the paper's k x n matrix); outputs Y[M][N].
+ *   Streams    `stream` is a hipStream_t passed as void* (NULL = the default stream).  Kernels are
+ *              enqueued; no call synchronises with the host.
+ *   Numbers    round() is round-half-to-even, the code range is [-127, 127], x / s is an IEEE
+ *              fp32 division; all steps ("scales") are fp32.
+ *   Errors     every call returns an sq_status and never throws or aborts.  Host-side checks:
+ *              NULL pointers, non-monotone offsets, off[S] != K, off[T] != N, steps that are not
+ *              finite and > 0, unknown dtype  -> SQ_ERR_INVALID_ARG;  legal but outside the limits
+ *              below -> SQ_ERR_UNSUPPORTED;  a failed launch -> SQ_ERR_LAUNCH.  Device data are
+ *              not validated (finite inputs are a precondition).
+ *   Limits     1 <= S, T <= SQ_MAX_SEGMENTS; seg_scale needs S*T <= SQ_MAX_SEG_SCALE; every
+ *              K-segment is at most SQ_MAX_KSEG_LEN long so that 127*127*K_ks fits int32;
+ *              M*K, N*K and M*N below 2^31.
+ */
+#ifndef SEGQUANT_H
+#define SEGQUANT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SQ_MAX_SEGMENTS 64
+#define SQ_MAX_SEG_SCALE 512
+#define SQ_MAX_KSEG_LEN 133143
+
+typedef enum { SQ_OK = 0, SQ_ERR_INVALID_ARG = 1, SQ_ERR_UNSUPPORTED = 2, SQ_ERR_LAUNCH = 3 } sq_status;
+typedef enum { SQ_F32 = 0, SQ_BF16 = 1 } sq_dtype;
+
+/*
+ * One quantized linear layer: shapes, the segment tables produced by the graph analysis of
+ * Sec. 4.2.2 (App. B, pattern detection), and the static activation steps of Sec. 4.3.2.
+ * All pointers are HOST memory.
+ */
+typedef struct sq_layer {
+  int32_t M, K, N;         /* tokens, in-features, out-features; all >= 1, M may be ragged        */
+  int32_t S;               /* number of K-segments (input-segmented, Sec. 4.2.2 item 2)           */
+  const int32_t* kseg_off; /* S+1 entries, 0 = off[0] < ... < off[S] = K                          */
+  int32_t T;               /* number of N-segments (output-segmented, Sec. 4.2.2 item 1)          */
+  const int32_t* nseg_off; /* T+1 entries, 0 = off[0] < ... < off[T] = N                          */
+  const uint8_t* dual;     /* S entries: 1 = DualScale on this K-segment, 0 = one symmetric step  */
+  const float* s_pos;      /* S entries: s_+ (or the single step of a non-dual segment)           */
+  const float* s_neg;      /* S entries: s_- > 0 (|min x| / 127); ignored where dual[ks] == 0     */
+  const float* seg_scale;  /* S*T entries [ks][ns], extra multiplier of block (ks, ns); or NULL   */
+} sq_layer;
+
+/*
+ * Quant(W), Sec. 3 quantizer with z = 0 applied per segment (Sec. 4.2.2): for every output channel
+ * n and K-segment ks:  a = max_k |W[n][k]|,  wscale[ks][n] = a / 127 (1.0 if a == 0),
+ * wq[n][k] = clip(round(W[n][k] / wscale[ks][n]), -127, 127).
+ *   w      dev, [N][K] of w_dt (SQ_F32 or SQ_BF16)        in
+ *   wq     dev, int8 [N][K]                               out
+ *   wscale dev, fp32 [S][N]                               out
+ * Offline step (once per layer).  M of the layer is ignored.
+ */
+sq_status sq_quantize_weight(const sq_layer* layer, const void* w, sq_dtype w_dt, int8_t* wq,
+                             float* wscale, void* stream);
+
+/*
+ * Q_dual(X) with the polarity split fused in (Sec. 4.3.2).  For a dual K-segment:
+ *   x <  0 : xq_neg = max(round(x / s_neg[ks]), -127), xq_pos = 0
+ *   x >= 0 : xq_pos = min(round(x / s_pos[ks]),  127), xq_neg = 0
+ * For a non-dual K-segment (Sec. 3, z = 0): xq_pos = clip(round(x / s_pos[ks]), -127, 127) and the
+ * xq_neg columns of that segment are neither written here nor read by sq_seglinear.
+ *   x       dev, [M][K] of x_dt                           in
+ *   xq_pos  dev, int8 [M][K]                              out
+ *   xq_neg  dev, int8 [M][K]                              out (may be NULL if no segment is dual)
+ */
+sq_status sq_quantize_act(const sq_layer* layer, const void* x, sq_dtype x_dt, int8_t* xq_pos,
+                          int8_t* xq_neg, void* stream);
+
+/*
+ * Dual-path integer GEMM with per-K-segment accumulators and the fused dequant epilogue
+ * (Sec. 4.2.2 items 1-2 combined with the last display of Sec. 4.3.2):
+ *   acc_+[ks][m][n] = sum_{k in ks} xq_pos[m][k] wq[n][k]            (int32, exact)
+ *   acc_-[ks][m][n] = sum_{k in ks} xq_neg[m][k] wq[n][k]            (dual segments only)
+ *   y[m][n] = sum_ks seg_scale[ks][ns(n)] wscale[ks][n] ( s_pos[ks] acc_+ + s_neg[ks] acc_- ) + bias[n]
+ * evaluated in fp32 and stored as fp32 or bf16 (round-half-to-even).  The weight tile is read once
+ * and feeds both accumulator sets.  M <= 64 selects the weight-streaming (bandwidth-bound) kernel.
+ *   xq_pos, xq_neg dev int8 [M][K];  wq dev int8 [N][K];  wscale dev fp32 [S][N];
+ *   bias dev fp32 [N] or NULL;  y dev [M][N] of y_dt.
+ */
+sq_status sq_seglinear(const sq_layer* layer, const int8_t* xq_pos, const int8_t* xq_neg,
+                       const int8_t* wq, const float* wscale, const float* bias, void* y,
+                       sq_dtype y_dt, void* stream);
+
+/*
+ * Parity instrument: runs the same main loop as sq_seglinear (same kernel selection) and stores the
+ * raw int32 accumulators instead of the dequantized output.
+ *   acc_pos, acc_neg  dev int32 [S][M][N];  acc_neg[ks] of a non-dual segment is written as 0.
+ */
+sq_status sq_seglinear_debug_acc(const sq_layer* layer, const int8_t* xq_pos, const int8_t* xq_neg,
+                                 const int8_t* wq, int32_t* acc_pos, int32_t* acc_neg, void* stream);
+
+/* Human-readable name of a status code (static storage). */
+const char* sq_status_string(sq_status s);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int sq_version(void);
+
+/*
+ * Diagnostics hook for benchmarks and tests: process-wide override of kernel selection.
+ *   key "gemm_variant": -1 = automatic (default), otherwise the index of a tile configuration
+ *   key "force_path":   -1 = automatic, 0 = generic kernel, 1 = MFMA tile kernel, 2 = skinny kernel
+ * Returns SQ_ERR_INVALID_ARG for an unknown key or value.  Not thread-safe against running calls.
+ */
+sq_status sq_tuning_set(const char* key, int value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SEGQUANT_H */

@@ -1,0 +1,17 @@
+"""MI355X-native SegLinear + DualScale quantized linear layer (SegQuant, arXiv 2507.14811).
+
+`binding` mirrors the C ABI of libsegquant.so (include/segquant.h); `workloads` holds the seeded
+synthetic layer generators; `build` compiles the HIP sources for gfx950.
+"""
+from .binding import (  # noqa: F401
+    Layer,
+    SqError,
+    load_library,
+    sq_quantize_act,
+    sq_quantize_weight,
+    sq_seglinear,
+    sq_seglinear_debug_acc,
+    sq_tuning_set,
+    sq_version,
+    status_string,
+)

@@ -1,0 +1,168 @@
+"""Thin ctypes binding of libsegquant.so: same names as the C ABI, argument marshalling only.
+
+Every step of the path runs in the HIP kernels.  Device buffers are torch tensors (memory and
+streams only); there is no CPU fallback: a missing library raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libsegquant.so")
+
+SQ_OK, SQ_ERR_INVALID_ARG, SQ_ERR_UNSUPPORTED, SQ_ERR_LAUNCH = 0, 1, 2, 3
+SQ_F32, SQ_BF16 = 0, 1
+SQ_MAX_SEGMENTS = 64
+SQ_MAX_SEG_SCALE = 512
+SQ_MAX_KSEG_LEN = 133143
+
+EXPORTS = ("sq_quantize_weight", "sq_quantize_act", "sq_seglinear", "sq_seglinear_debug_acc",
+           "sq_status_string", "sq_version", "sq_tuning_set")
+
+
+class SqError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: {status_string(status)}")
+
+
+class sq_layer(C.Structure):
+    _fields_ = [
+        ("M", C.c_int32), ("K", C.c_int32), ("N", C.c_int32),
+        ("S", C.c_int32), ("kseg_off", C.POINTER(C.c_int32)),
+        ("T", C.c_int32), ("nseg_off", C.POINTER(C.c_int32)),
+        ("dual", C.POINTER(C.c_uint8)),
+        ("s_pos", C.POINTER(C.c_float)), ("s_neg", C.POINTER(C.c_float)),
+        ("seg_scale", C.POINTER(C.c_float)),
+    ]
+
+
+_lib = None
+
+
+def load_library() -> C.CDLL:
+    """Load libsegquant.so (built in-tree by paper_2507_14811_amd.build).  Raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2507_14811_amd.build` "
+                           "(there is no CPU fallback)")
+    import torch  # noqa: F401  loads the HIP runtime the library binds to
+
+    lib = C.CDLL(LIB_PATH)
+    vp, i32 = C.c_void_p, C.c_int
+    lp = C.POINTER(sq_layer)
+    lib.sq_quantize_weight.argtypes = [lp, vp, i32, vp, vp, vp]
+    lib.sq_quantize_act.argtypes = [lp, vp, i32, vp, vp, vp]
+    lib.sq_seglinear.argtypes = [lp, vp, vp, vp, vp, vp, vp, i32, vp]
+    lib.sq_seglinear_debug_acc.argtypes = [lp, vp, vp, vp, vp, vp, vp]
+    for f in (lib.sq_quantize_weight, lib.sq_quantize_act, lib.sq_seglinear, lib.sq_seglinear_debug_acc):
+        f.restype = i32
+    lib.sq_status_string.argtypes = [i32]
+    lib.sq_status_string.restype = C.c_char_p
+    lib.sq_version.restype = i32
+    lib.sq_tuning_set.argtypes = [C.c_char_p, i32]
+    lib.sq_tuning_set.restype = i32
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load_library().sq_status_string(int(status)).decode()
+
+
+def sq_version() -> int:
+    return int(load_library().sq_version())
+
+
+def sq_tuning_set(key: str, value: int) -> None:
+    st = load_library().sq_tuning_set(key.encode(), int(value))
+    if st != SQ_OK:
+        raise SqError(st, f"sq_tuning_set({key!r}, {value})")
+
+
+class Layer:
+    """Host-side descriptor (the C struct plus the numpy arrays that keep its pointers alive)."""
+
+    def __init__(self, M: int, K: int, N: int, kseg_off: Sequence[int], nseg_off: Sequence[int],
+                 dual: Sequence[int], s_pos=None, s_neg=None, seg_scale=None):
+        self.kseg_off = np.ascontiguousarray(kseg_off, dtype=np.int32)
+        self.nseg_off = np.ascontiguousarray(nseg_off, dtype=np.int32)
+        self.dual = np.ascontiguousarray(dual, dtype=np.uint8)
+        self.s_pos = None if s_pos is None else np.ascontiguousarray(s_pos, dtype=np.float32)
+        self.s_neg = None if s_neg is None else np.ascontiguousarray(s_neg, dtype=np.float32)
+        self.seg_scale = None if seg_scale is None else np.ascontiguousarray(seg_scale, dtype=np.float32)
+        self.M, self.K, self.N = int(M), int(K), int(N)
+        self.S, self.T = len(self.kseg_off) - 1, len(self.nseg_off) - 1
+
+        def ptr(a, ty):
+            return None if a is None else a.ctypes.data_as(C.POINTER(ty))
+
+        self.c = sq_layer(self.M, self.K, self.N, self.S, ptr(self.kseg_off, C.c_int32), self.T,
+                          ptr(self.nseg_off, C.c_int32), ptr(self.dual, C.c_uint8), ptr(self.s_pos, C.c_float),
+                          ptr(self.s_neg, C.c_float), ptr(self.seg_scale, C.c_float))
+
+    @classmethod
+    def from_workload(cls, w) -> "Layer":
+        return cls(w.M, w.K, w.N, w.kseg_off, w.nseg_off, w.dual, w.s_pos, w.s_neg, w.seg_scale)
+
+    @property
+    def any_dual(self) -> bool:
+        return bool(self.dual.any())
+
+
+def _dptr(t) -> Optional[int]:
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> C.c_void_p:
+    if stream is None:
+        import torch
+
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(getattr(stream, "cuda_stream", stream))
+
+
+def _dt(t) -> int:
+    import torch
+
+    if t.dtype == torch.float32:
+        return SQ_F32
+    if t.dtype == torch.bfloat16:
+        return SQ_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _check(st: int, what: str):
+    if st != SQ_OK:
+        raise SqError(st, what)
+
+
+def sq_quantize_weight(layer: Layer, w, wq, wscale, stream=None) -> None:
+    """w [N][K] fp32/bf16 -> wq int8 [N][K], wscale fp32 [S][N]  (device tensors, written in place)."""
+    _check(load_library().sq_quantize_weight(C.byref(layer.c), _dptr(w), _dt(w), _dptr(wq), _dptr(wscale),
+                                             _stream(stream)), "sq_quantize_weight")
+
+
+def sq_quantize_act(layer: Layer, x, xq_pos, xq_neg, stream=None) -> None:
+    """x [M][K] fp32/bf16 -> xq_pos, xq_neg int8 [M][K]."""
+    _check(load_library().sq_quantize_act(C.byref(layer.c), _dptr(x), _dt(x), _dptr(xq_pos), _dptr(xq_neg),
+                                          _stream(stream)), "sq_quantize_act")
+
+
+def sq_seglinear(layer: Layer, xq_pos, xq_neg, wq, wscale, bias, y, stream=None) -> None:
+    """int8 x int8 -> int32 per K-segment, dequantized into y [M][N] fp32/bf16."""
+    _check(load_library().sq_seglinear(C.byref(layer.c), _dptr(xq_pos), _dptr(xq_neg), _dptr(wq), _dptr(wscale),
+                                       _dptr(bias), _dptr(y), _dt(y), _stream(stream)), "sq_seglinear")
+
+
+def sq_seglinear_debug_acc(layer: Layer, xq_pos, xq_neg, wq, acc_pos, acc_neg, stream=None) -> None:
+    """Same main loop, raw int32 accumulators: acc_pos, acc_neg int32 [S][M][N]."""
+    _check(load_library().sq_seglinear_debug_acc(C.byref(layer.c), _dptr(xq_pos), _dptr(xq_neg), _dptr(wq),
+                                                 _dptr(acc_pos), _dptr(acc_neg), _stream(stream)),
+           "sq_seglinear_debug_acc")

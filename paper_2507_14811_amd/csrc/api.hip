@@ -1,0 +1,205 @@
+// C ABI of the library: host-side validation, table marshalling and kernel selection.  No device
+// memory is allocated and no state is kept between calls (apart from the diagnostics overrides).
+#include <cmath>
+#include <cstring>
+
+#include "sq_kernels.hpp"
+
+namespace {
+
+int g_gemm_variant = -1;   // sq_tuning_set("gemm_variant", v)
+int g_force_path = -1;     // sq_tuning_set("force_path", p): 0 generic, 1 MFMA tiles, 2 skinny
+
+bool offsets_ok(int n, int cnt, const int32_t* off) {
+  if (cnt < 1 || cnt > SQ_MAX_SEGMENTS || off == nullptr) return false;
+  if (off[0] != 0 || off[cnt] != n) return false;
+  for (int i = 0; i < cnt; ++i)
+    if (off[i + 1] <= off[i]) return false;
+  return true;
+}
+
+bool step_ok(float s) { return std::isfinite(s) && s > 0.0f; }
+
+// Shape / table checks shared by every entry point.  need_scales: s_pos / s_neg are used by the call.
+sq_status check_layer(const sq_layer* L, bool need_m, bool need_scales) {
+  if (L == nullptr) return SQ_ERR_INVALID_ARG;
+  if (L->K < 1 || L->N < 1 || (need_m && L->M < 1)) return SQ_ERR_INVALID_ARG;
+  if (L->S < 1 || L->T < 1) return SQ_ERR_INVALID_ARG;
+  if (L->S > SQ_MAX_SEGMENTS || L->T > SQ_MAX_SEGMENTS) return SQ_ERR_UNSUPPORTED;
+  if (!offsets_ok(L->K, L->S, L->kseg_off) || !offsets_ok(L->N, L->T, L->nseg_off)) return SQ_ERR_INVALID_ARG;
+  if (L->dual == nullptr) return SQ_ERR_INVALID_ARG;
+  if (need_scales) {
+    if (L->s_pos == nullptr) return SQ_ERR_INVALID_ARG;
+    for (int s = 0; s < L->S; ++s) {
+      if (!step_ok(L->s_pos[s])) return SQ_ERR_INVALID_ARG;
+      if (L->dual[s]) {
+        if (L->s_neg == nullptr || !step_ok(L->s_neg[s])) return SQ_ERR_INVALID_ARG;
+      }
+    }
+    if (L->seg_scale) {
+      if ((long)L->S * L->T > SQ_MAX_SEG_SCALE) return SQ_ERR_UNSUPPORTED;
+      for (int i = 0; i < L->S * L->T; ++i)
+        if (!std::isfinite(L->seg_scale[i])) return SQ_ERR_INVALID_ARG;
+    }
+  }
+  for (int s = 0; s < L->S; ++s)
+    if (L->kseg_off[s + 1] - L->kseg_off[s] > SQ_MAX_KSEG_LEN) return SQ_ERR_UNSUPPORTED;
+  const long long lim = 0x7FFFFFFFll;
+  if ((long long)L->N * L->K > lim) return SQ_ERR_UNSUPPORTED;
+  if (need_m && ((long long)L->M * L->K > lim || (long long)L->M * L->N > lim)) return SQ_ERR_UNSUPPORTED;
+  return SQ_OK;
+}
+
+void fill_gemm_table(const sq_layer* L, sq::GemmTable& tb) {
+  std::memset(&tb, 0, sizeof(tb));
+  tb.S = L->S;
+  tb.T = L->T;
+  for (int s = 0; s <= L->S; ++s) tb.kseg_off[s] = L->kseg_off[s];
+  for (int t = 0; t <= L->T; ++t) tb.nseg_off[t] = L->nseg_off[t];
+  for (int s = 0; s < L->S; ++s) {
+    tb.dual[s] = L->dual[s] ? 1 : 0;
+    tb.s_pos[s] = L->s_pos ? L->s_pos[s] : 1.0f;
+    tb.s_neg[s] = (L->dual[s] && L->s_neg) ? L->s_neg[s] : 0.0f;
+  }
+  tb.has_seg_scale = L->seg_scale != nullptr;
+  if (L->seg_scale) std::memcpy(tb.seg_scale, L->seg_scale, sizeof(float) * L->S * L->T);
+}
+
+// Reciprocal used by the fast path of round(x / s); NaN tells the kernel to always divide.
+float safe_inv(float s) {
+  if (!(s >= 1e-30f && s <= 1e30f)) return std::nanf("");
+  return 1.0f / s;
+}
+
+sq_status run_gemm(const sq_layer* L, const int8_t* xq_pos, const int8_t* xq_neg, const int8_t* wq,
+                   const float* wscale, const float* bias, void* y, int32_t* acc_pos, int32_t* acc_neg,
+                   sq::OutMode mode, void* stream) {
+  sq::GemmTable tb;
+  fill_gemm_table(L, tb);
+  bool any_dual = false;
+  for (int s = 0; s < L->S; ++s) any_dual = any_dual || L->dual[s];
+  if (any_dual && xq_neg == nullptr) return SQ_ERR_INVALID_ARG;
+  sq::GemmArgs a{};
+  a.xp = xq_pos;
+  a.xn = any_dual ? xq_neg : xq_pos;   // never dereferenced for a non-dual layer; kept non-null
+  a.wq = wq;
+  a.wscale = wscale;
+  a.bias = bias;
+  a.y = y;
+  a.acc_pos = acc_pos;
+  a.acc_neg = acc_neg;
+  a.M = L->M;
+  a.K = L->K;
+  a.N = L->N;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  int path = g_force_path;
+  if (path == 2 && !sq::skinny_supported(a, tb)) return SQ_ERR_UNSUPPORTED;
+  if (path == 1 && !sq::mfma_supported(a, tb)) return SQ_ERR_UNSUPPORTED;
+  if (path < 0) {
+    if (sq::skinny_supported(a, tb)) path = 2;
+    else if (sq::mfma_supported(a, tb)) path = 1;
+    else path = 0;
+  }
+  hipError_t e;
+  if (path == 2) {
+    e = sq::launch_seglinear_skinny(a, tb, mode, st);
+  } else if (path == 1) {
+    int v = g_gemm_variant >= 0 ? g_gemm_variant : sq::mfma_pick_variant(a, tb, mode);
+    e = sq::launch_seglinear_mfma(a, tb, mode, v, st);
+    if (e == hipErrorInvalidConfiguration) return SQ_ERR_UNSUPPORTED;
+  } else {
+    e = sq::launch_seglinear_generic(a, tb, mode, st);
+  }
+  return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+sq_status sq_quantize_weight(const sq_layer* layer, const void* w, sq_dtype w_dt, int8_t* wq, float* wscale,
+                             void* stream) {
+  sq_status st = check_layer(layer, false, false);
+  if (st != SQ_OK) return st;
+  if (w == nullptr || wq == nullptr || wscale == nullptr) return SQ_ERR_INVALID_ARG;
+  if (w_dt != SQ_F32 && w_dt != SQ_BF16) return SQ_ERR_INVALID_ARG;
+  sq::KsegTable tb;
+  tb.S = layer->S;
+  for (int s = 0; s <= layer->S; ++s) tb.off[s] = layer->kseg_off[s];
+  hipError_t e = sq::launch_quantize_weight(w, w_dt == SQ_BF16, wq, wscale, layer->N, layer->K, tb,
+                                            reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
+sq_status sq_quantize_act(const sq_layer* layer, const void* x, sq_dtype x_dt, int8_t* xq_pos, int8_t* xq_neg,
+                          void* stream) {
+  sq_status st = check_layer(layer, true, true);
+  if (st != SQ_OK) return st;
+  if (x == nullptr || xq_pos == nullptr) return SQ_ERR_INVALID_ARG;
+  if (x_dt != SQ_F32 && x_dt != SQ_BF16) return SQ_ERR_INVALID_ARG;
+  sq::ActTable tb;
+  std::memset(&tb, 0, sizeof(tb));
+  tb.S = layer->S;
+  bool any_dual = false;
+  for (int s = 0; s <= layer->S; ++s) tb.kseg_off[s] = layer->kseg_off[s];
+  for (int s = 0; s < layer->S; ++s) {
+    tb.dual[s] = layer->dual[s] ? 1 : 0;
+    any_dual = any_dual || layer->dual[s];
+    tb.s_pos[s] = layer->s_pos[s];
+    tb.inv_pos[s] = safe_inv(layer->s_pos[s]);
+    tb.s_neg[s] = layer->dual[s] ? layer->s_neg[s] : 1.0f;
+    tb.inv_neg[s] = layer->dual[s] ? safe_inv(layer->s_neg[s]) : 1.0f;
+  }
+  if (any_dual && xq_neg == nullptr) return SQ_ERR_INVALID_ARG;
+  hipError_t e = sq::launch_quantize_act(x, x_dt == SQ_BF16, xq_pos, xq_neg, layer->M, layer->K, tb,
+                                         reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
+sq_status sq_seglinear(const sq_layer* layer, const int8_t* xq_pos, const int8_t* xq_neg, const int8_t* wq,
+                       const float* wscale, const float* bias, void* y, sq_dtype y_dt, void* stream) {
+  sq_status st = check_layer(layer, true, true);
+  if (st != SQ_OK) return st;
+  if (xq_pos == nullptr || wq == nullptr || wscale == nullptr || y == nullptr) return SQ_ERR_INVALID_ARG;
+  if (y_dt != SQ_F32 && y_dt != SQ_BF16) return SQ_ERR_INVALID_ARG;
+  return run_gemm(layer, xq_pos, xq_neg, wq, wscale, bias, y, nullptr, nullptr,
+                  y_dt == SQ_BF16 ? sq::OUT_BF16 : sq::OUT_F32, stream);
+}
+
+sq_status sq_seglinear_debug_acc(const sq_layer* layer, const int8_t* xq_pos, const int8_t* xq_neg,
+                                 const int8_t* wq, int32_t* acc_pos, int32_t* acc_neg, void* stream) {
+  sq_status st = check_layer(layer, true, false);
+  if (st != SQ_OK) return st;
+  if (xq_pos == nullptr || wq == nullptr || acc_pos == nullptr || acc_neg == nullptr) return SQ_ERR_INVALID_ARG;
+  if ((long long)layer->S * layer->M * layer->N > 0x7FFFFFFFll) return SQ_ERR_UNSUPPORTED;
+  return run_gemm(layer, xq_pos, xq_neg, wq, nullptr, nullptr, nullptr, acc_pos, acc_neg, sq::OUT_DEBUG_ACC, stream);
+}
+
+const char* sq_status_string(sq_status s) {
+  switch (s) {
+    case SQ_OK: return "SQ_OK";
+    case SQ_ERR_INVALID_ARG: return "SQ_ERR_INVALID_ARG";
+    case SQ_ERR_UNSUPPORTED: return "SQ_ERR_UNSUPPORTED";
+    case SQ_ERR_LAUNCH: return "SQ_ERR_LAUNCH";
+    default: return "SQ_ERR_UNKNOWN";
+  }
+}
+
+int sq_version(void) { return 100; }
+
+sq_status sq_tuning_set(const char* key, int value) {
+  if (key == nullptr) return SQ_ERR_INVALID_ARG;
+  if (std::strcmp(key, "gemm_variant") == 0) {
+    if (value < -1 || value >= sq::mfma_num_variants()) return SQ_ERR_INVALID_ARG;
+    g_gemm_variant = value;
+    return SQ_OK;
+  }
+  if (std::strcmp(key, "force_path") == 0) {
+    if (value < -1 || value > 2) return SQ_ERR_INVALID_ARG;
+    g_force_path = value;
+    return SQ_OK;
+  }
+  return SQ_ERR_INVALID_ARG;
+}
+
+}  // extern "C"

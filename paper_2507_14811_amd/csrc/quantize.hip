@@ -1,0 +1,195 @@
+// Quant(.) kernels: the fused polarity-split / DualScale activation quantizer (Sec. 4.3.2) and the
+// per-segment symmetric weight quantizer (Sec. 3 quantizer applied per segment, Sec. 4.2.2).
+// Both are single-pass, HBM-bandwidth-bound streams.
+#include "sq_kernels.hpp"
+
+namespace sq {
+
+// ------------------------------------------------------------------------------------------------
+// Activation quantize, fast path: K and every K-segment boundary are multiples of 8, so a thread owns
+// 8 consecutive elements of one row and one segment: 16 B (bf16) or 32 B (fp32) in, 8 B out per
+// polarity.  A block streams 4 x 256 such chunks; all loads are issued before any arithmetic.
+// ------------------------------------------------------------------------------------------------
+constexpr int kActUnroll = 4;
+
+__device__ __forceinline__ uint32_t pack4(int c0, int c1, int c2, int c3) {
+  return (uint32_t)(c0 & 0xFF) | ((uint32_t)(c1 & 0xFF) << 8) | ((uint32_t)(c2 & 0xFF) << 16) | ((uint32_t)c3 << 24);
+}
+
+template <bool BF16, bool ONESEG>
+__global__ __launch_bounds__(256) void quantize_act_fast_kernel(const void* __restrict__ x, int8_t* __restrict__ xq_pos,
+                                                                int8_t* __restrict__ xq_neg, uint32_t nchunks,
+                                                                uint32_t kchunks, uint32_t kmagic, const ActTable tb) {
+  const uint32_t base = blockIdx.x * (256u * kActUnroll) + threadIdx.x;
+  v4i raw[kActUnroll][BF16 ? 1 : 2];
+#pragma unroll
+  for (int j = 0; j < kActUnroll; ++j) {
+    const uint32_t c = base + j * 256u;
+    if (c < nchunks) {
+      if (BF16) {
+        raw[j][0] = reinterpret_cast<const v4i*>(x)[c];
+      } else {
+        raw[j][0] = reinterpret_cast<const v4i*>(x)[2 * (size_t)c];
+        raw[j][BF16 ? 0 : 1] = reinterpret_cast<const v4i*>(x)[2 * (size_t)c + 1];
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < kActUnroll; ++j) {
+    const uint32_t c = base + j * 256u;
+    if (c >= nchunks) continue;
+    float sp = tb.s_pos[0], sn = tb.s_neg[0], ip = tb.inv_pos[0], in = tb.inv_neg[0];
+    bool dual = tb.dual[0] != 0;
+    if (!ONESEG) {
+      // column of this chunk: c mod kchunks via a reciprocal multiply (q is exact or one too small)
+      uint32_t q = __umulhi(c, kmagic);
+      uint32_t r = c - q * kchunks;
+      if (r >= kchunks) r -= kchunks;
+      const int col = (int)(r * 8u);
+      for (int s = 1; s < tb.S; ++s) {
+        if (col >= tb.kseg_off[s]) {
+          sp = tb.s_pos[s]; sn = tb.s_neg[s]; ip = tb.inv_pos[s]; in = tb.inv_neg[s]; dual = tb.dual[s] != 0;
+        }
+      }
+    }
+    float v[8];
+    if (BF16) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint32_t u = (uint32_t)raw[j][0][i];
+        v[2 * i] = __uint_as_float(u << 16);
+        v[2 * i + 1] = __uint_as_float(u & 0xFFFF0000u);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] = __int_as_float(raw[j][BF16 ? 0 : i / 4][i % 4]);
+    }
+    int cp[8], cn[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const bool ng = dual && (v[i] < 0.0f);          // X_- = min(X, 0) takes the s_- branch of Q_dual
+      const float r = round_quotient(v[i], ng ? sn : sp, ng ? in : ip);
+      const int code = clip_code(r);
+      cp[i] = ng ? 0 : code;
+      cn[i] = ng ? code : 0;
+    }
+    v2i op, on;
+    op[0] = (int)pack4(cp[0], cp[1], cp[2], cp[3]);
+    op[1] = (int)pack4(cp[4], cp[5], cp[6], cp[7]);
+    reinterpret_cast<v2i*>(xq_pos)[c] = op;
+    if (dual) {
+      on[0] = (int)pack4(cn[0], cn[1], cn[2], cn[3]);
+      on[1] = (int)pack4(cn[4], cn[5], cn[6], cn[7]);
+      reinterpret_cast<v2i*>(xq_neg)[c] = on;
+    }
+  }
+}
+
+// Any K / segment alignment: one element per thread.
+template <bool BF16>
+__global__ __launch_bounds__(256) void quantize_act_generic_kernel(const void* __restrict__ x, int8_t* __restrict__ xq_pos,
+                                                                   int8_t* __restrict__ xq_neg, int M, int K,
+                                                                   const ActTable tb) {
+  const size_t total = (size_t)M * K;
+  for (size_t i = blockIdx.x * (size_t)256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+    const int col = (int)(i % (size_t)K);
+    float sp = tb.s_pos[0], sn = tb.s_neg[0], ip = tb.inv_pos[0], in = tb.inv_neg[0];
+    bool dual = tb.dual[0] != 0;
+    for (int s = 1; s < tb.S; ++s) {
+      if (col >= tb.kseg_off[s]) {
+        sp = tb.s_pos[s]; sn = tb.s_neg[s]; ip = tb.inv_pos[s]; in = tb.inv_neg[s]; dual = tb.dual[s] != 0;
+      }
+    }
+    const float v = BF16 ? bf16_to_f32(reinterpret_cast<const uint16_t*>(x)[i]) : reinterpret_cast<const float*>(x)[i];
+    const bool ng = dual && (v < 0.0f);
+    const int code = clip_code(round_quotient(v, ng ? sn : sp, ng ? in : ip));
+    xq_pos[i] = (int8_t)(ng ? 0 : code);
+    if (dual) xq_neg[i] = (int8_t)(ng ? code : 0);
+  }
+}
+
+hipError_t launch_quantize_act(const void* x, bool x_is_bf16, int8_t* xq_pos, int8_t* xq_neg, int M, int K,
+                               const ActTable& tb, hipStream_t st) {
+  bool aligned = (K % 8 == 0) && (reinterpret_cast<uintptr_t>(x) % 16 == 0) &&
+                 (reinterpret_cast<uintptr_t>(xq_pos) % 8 == 0) && (reinterpret_cast<uintptr_t>(xq_neg) % 8 == 0);
+  for (int s = 0; s <= tb.S; ++s) aligned = aligned && (tb.kseg_off[s] % 8 == 0);
+  if (aligned) {
+    const uint32_t kchunks = (uint32_t)(K / 8);
+    const uint32_t nchunks = (uint32_t)(((size_t)M * K) / 8);
+    const uint32_t kmagic = (uint32_t)(0x100000000ull / kchunks > 0xFFFFFFFFull ? 0xFFFFFFFFull : 0x100000000ull / kchunks);
+    const unsigned blocks = (nchunks + 256u * kActUnroll - 1) / (256u * kActUnroll);
+    const bool one = (tb.S == 1);
+#define SQ_LAUNCH_ACT(B, O) \
+  hipLaunchKernelGGL((quantize_act_fast_kernel<B, O>), dim3(blocks), dim3(256), 0, st, x, xq_pos, xq_neg, nchunks, kchunks, kmagic, tb)
+    if (x_is_bf16) { if (one) SQ_LAUNCH_ACT(true, true); else SQ_LAUNCH_ACT(true, false); }
+    else           { if (one) SQ_LAUNCH_ACT(false, true); else SQ_LAUNCH_ACT(false, false); }
+#undef SQ_LAUNCH_ACT
+  } else {
+    const size_t total = (size_t)M * K;
+    const unsigned blocks = (unsigned)((total + 255) / 256 > 65536 ? 65536 : (total + 255) / 256);
+    if (x_is_bf16) hipLaunchKernelGGL((quantize_act_generic_kernel<true>), dim3(blocks), dim3(256), 0, st, x, xq_pos, xq_neg, M, K, tb);
+    else           hipLaunchKernelGGL((quantize_act_generic_kernel<false>), dim3(blocks), dim3(256), 0, st, x, xq_pos, xq_neg, M, K, tb);
+  }
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// Weight quantize: one wavefront per (output channel n, K-segment ks).  Pass 1 reduces max |w| over the
+// row segment, pass 2 re-reads it (L2-resident: a row segment is at most 0.5 MB) and writes the codes.
+// ------------------------------------------------------------------------------------------------
+template <bool BF16>
+__device__ __forceinline__ float load_w(const void* w, size_t i) {
+  return BF16 ? bf16_to_f32(reinterpret_cast<const uint16_t*>(w)[i]) : reinterpret_cast<const float*>(w)[i];
+}
+
+template <bool BF16, bool VEC4>
+__global__ __launch_bounds__(256) void quantize_weight_kernel(const void* __restrict__ w, int8_t* __restrict__ wq,
+                                                              float* __restrict__ wscale, int N, int K,
+                                                              const KsegTable tb) {
+  const int lane = threadIdx.x & 63;
+  const long item = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (item >= (long)N * tb.S) return;            // whole wave leaves together
+  const int n = (int)(item / tb.S), ks = (int)(item % tb.S);
+  int k0 = 0, k1 = 0;
+  for (int s = 0; s < tb.S; ++s)
+    if (s == ks) { k0 = tb.off[s]; k1 = tb.off[s + 1]; }
+  const size_t row = (size_t)n * K;
+  float a = 0.0f;
+  if (VEC4) {
+    for (int k = k0 + 4 * lane; k < k1; k += 256) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) a = __builtin_fmaxf(a, __builtin_fabsf(load_w<BF16>(w, row + k + i)));
+    }
+  } else {
+    for (int k = k0 + lane; k < k1; k += 64) a = __builtin_fmaxf(a, __builtin_fabsf(load_w<BF16>(w, row + k)));
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) a = __builtin_fmaxf(a, __shfl_xor(a, off, 64));
+  const float sw = (a == 0.0f) ? 1.0f : a / kQmax;
+  if (lane == 0) wscale[(size_t)ks * N + n] = sw;
+  if (VEC4) {
+    for (int k = k0 + 4 * lane; k < k1; k += 256) {
+      int c[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) c[i] = clip_code(__builtin_rintf(load_w<BF16>(w, row + k + i) / sw));
+      *reinterpret_cast<uint32_t*>(wq + row + k) = pack4(c[0], c[1], c[2], c[3]);
+    }
+  } else {
+    for (int k = k0 + lane; k < k1; k += 64) wq[row + k] = (int8_t)clip_code(__builtin_rintf(load_w<BF16>(w, row + k) / sw));
+  }
+}
+
+hipError_t launch_quantize_weight(const void* w, bool w_is_bf16, int8_t* wq, float* wscale, int N, int K,
+                                  const KsegTable& tb, hipStream_t st) {
+  bool vec = (K % 4 == 0) && (reinterpret_cast<uintptr_t>(w) % 16 == 0) && (reinterpret_cast<uintptr_t>(wq) % 4 == 0);
+  for (int s = 0; s <= tb.S; ++s) vec = vec && (tb.off[s] % 4 == 0);
+  const long items = (long)N * tb.S;
+  const unsigned blocks = (unsigned)((items + 3) / 4);
+#define SQ_LAUNCH_W(B, V) hipLaunchKernelGGL((quantize_weight_kernel<B, V>), dim3(blocks), dim3(256), 0, st, w, wq, wscale, N, K, tb)
+  if (w_is_bf16) { if (vec) SQ_LAUNCH_W(true, true); else SQ_LAUNCH_W(true, false); }
+  else           { if (vec) SQ_LAUNCH_W(false, true); else SQ_LAUNCH_W(false, false); }
+#undef SQ_LAUNCH_W
+  return hipGetLastError();
+}
+
+}  // namespace sq

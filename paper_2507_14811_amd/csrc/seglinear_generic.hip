@@ -1,0 +1,53 @@
+// SegLinear + DualScale GEMM for arbitrary shapes and alignments: one thread per output element.
+// Used only when the tile kernels' alignment requirements do not hold (K not a multiple of 16 or a
+// K-segment boundary not a multiple of 64).  Same arithmetic: exact int32 per-K-segment accumulators
+// (Sec. 4.2.2 item 2), flushed to fp32 with the per-segment steps (Sec. 4.3.2, last display).
+#include "sq_kernels.hpp"
+
+namespace sq {
+
+template <int MODE>
+__global__ __launch_bounds__(256) void seglinear_generic_kernel(const GemmArgs a, const GemmTable tb) {
+  const int n = blockIdx.y * 64 + (threadIdx.x & 63);
+  const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (n >= a.N || m >= a.M) return;
+  const int8_t* xp = a.xp + (size_t)m * a.K;
+  const int8_t* xn = a.xn + (size_t)m * a.K;
+  const int8_t* wr = a.wq + (size_t)n * a.K;
+  float y = 0.0f;
+  for (int ks = 0; ks < tb.S; ++ks) {
+    const bool dual = tb.dual[ks] != 0;
+    int ap = 0, an = 0;
+    for (int k = tb.kseg_off[ks]; k < tb.kseg_off[ks + 1]; ++k) {
+      const int wv = wr[k];
+      ap += (int)xp[k] * wv;
+      if (dual) an += (int)xn[k] * wv;
+    }
+    if (MODE == OUT_DEBUG_ACC) {
+      const size_t o = ((size_t)ks * a.M + m) * a.N + n;
+      a.acc_pos[o] = ap;
+      a.acc_neg[o] = an;
+    } else {
+      const float c = seg_scale_of(tb, ks, n) * a.wscale[(size_t)ks * a.N + n];
+      float t = tb.s_pos[ks] * (float)ap;
+      if (dual) t += tb.s_neg[ks] * (float)an;
+      y += c * t;
+    }
+  }
+  if (MODE != OUT_DEBUG_ACC) {
+    if (a.bias) y += a.bias[n];
+    const size_t o = (size_t)m * a.N + n;
+    if (MODE == OUT_F32) reinterpret_cast<float*>(a.y)[o] = y;
+    else reinterpret_cast<uint16_t*>(a.y)[o] = f32_to_bf16(y);
+  }
+}
+
+hipError_t launch_seglinear_generic(const GemmArgs& a, const GemmTable& tb, OutMode mode, hipStream_t st) {
+  dim3 grid((a.M + 3) / 4, (a.N + 63) / 64);
+  if (mode == OUT_F32) hipLaunchKernelGGL((seglinear_generic_kernel<OUT_F32>), grid, dim3(256), 0, st, a, tb);
+  else if (mode == OUT_BF16) hipLaunchKernelGGL((seglinear_generic_kernel<OUT_BF16>), grid, dim3(256), 0, st, a, tb);
+  else hipLaunchKernelGGL((seglinear_generic_kernel<OUT_DEBUG_ACC>), grid, dim3(256), 0, st, a, tb);
+  return hipGetLastError();
+}
+
+}  // namespace sq

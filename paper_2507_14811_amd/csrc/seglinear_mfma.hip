@@ -1,0 +1,90 @@
+// Variant table and selection heuristic of the large-M MFMA kernel; the kernels themselves are
+// instantiated one variant per translation unit (seglinear_mfma_inst.hip).
+#include "seglinear_mfma_variants.hpp"
+
+namespace sq {
+
+#define SQ_DECL(V) extern template hipError_t launch_mfma_variant<V>(const GemmArgs&, const GemmTable&, int, bool, bool, hipStream_t);
+SQ_DECL(0) SQ_DECL(1) SQ_DECL(2) SQ_DECL(3) SQ_DECL(4) SQ_DECL(5)
+#undef SQ_DECL
+
+template <int V> static MfmaVariantInfo info_of() {
+  using P = MfmaVariant<V>;
+  return {P::BM, P::BN, P::DUAL_OK, P::MULTI_DUAL_OK};
+}
+static MfmaVariantInfo variant_info(int v) {
+  switch (v) {
+    case 0: return info_of<0>();
+    case 1: return info_of<1>();
+    case 2: return info_of<2>();
+    case 3: return info_of<3>();
+    case 4: return info_of<4>();
+    default: return info_of<5>();
+  }
+}
+// Relative main-loop efficiency of a tile shape (larger wave tiles re-use LDS fragments more).
+static const float kTileEff[kNumMfmaVariants] = {1.00f, 0.85f, 0.85f, 0.70f, 1.00f, 0.90f};
+
+int mfma_num_variants() { return kNumMfmaVariants; }
+
+static void layer_flags(const GemmTable& tb, bool& dual, bool& multi) {
+  dual = false;
+  for (int s = 0; s < tb.S; ++s) dual = dual || (tb.dual[s] != 0);
+  multi = tb.S > 1;
+}
+
+static bool variant_ok(int v, bool dual, bool multi) {
+  if (v < 0 || v >= kNumMfmaVariants) return false;
+  const MfmaVariantInfo i = variant_info(v);
+  if (dual && !i.dual_ok) return false;
+  if (dual && multi && !i.multi_dual_ok) return false;
+  return true;
+}
+
+bool mfma_supported(const GemmArgs& a, const GemmTable& tb) {
+  if (a.K % 64 != 0) return false;
+  for (int s = 0; s <= tb.S; ++s)
+    if (tb.kseg_off[s] % 64 != 0) return false;
+  if ((reinterpret_cast<uintptr_t>(a.xp) | reinterpret_cast<uintptr_t>(a.wq)) % 16 != 0) return false;
+  if (a.xn && reinterpret_cast<uintptr_t>(a.xn) % 16 != 0) return false;
+  return true;
+}
+
+int mfma_pick_variant(const GemmArgs& a, const GemmTable& tb, OutMode) {
+  bool dual, multi;
+  layer_flags(tb, dual, multi);
+  int dev = 0, cus = 256;
+  if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+  int best = -1;
+  float best_score = -1.0f;
+  for (int v = 0; v < kNumMfmaVariants; ++v) {
+    if (!variant_ok(v, dual, multi)) continue;
+    const MfmaVariantInfo i = variant_info(v);
+    const long tiles = (long)((a.M + i.BM - 1) / i.BM) * ((a.N + i.BN - 1) / i.BN);
+    const long rounds = (tiles + cus - 1) / cus;
+    const float fill = (float)((double)a.M * a.N / ((double)rounds * cus * i.BM * i.BN));
+    const float score = fill * kTileEff[v];
+    if (score > best_score) { best_score = score; best = v; }
+  }
+  return best;
+}
+
+hipError_t launch_seglinear_mfma(GemmArgs a, const GemmTable& tb, OutMode mode, int variant, hipStream_t st) {
+  bool dual, multi;
+  layer_flags(tb, dual, multi);
+  if (!variant_ok(variant, dual, multi)) return hipErrorInvalidConfiguration;
+  const MfmaVariantInfo i = variant_info(variant);
+  a.tiles_m = (a.M + i.BM - 1) / i.BM;
+  a.tiles_n = (a.N + i.BN - 1) / i.BN;
+  a.group_m = a.tiles_m < 8 ? a.tiles_m : 8;
+  switch (variant) {
+    case 0: return launch_mfma_variant<0>(a, tb, mode, dual, multi, st);
+    case 1: return launch_mfma_variant<1>(a, tb, mode, dual, multi, st);
+    case 2: return launch_mfma_variant<2>(a, tb, mode, dual, multi, st);
+    case 3: return launch_mfma_variant<3>(a, tb, mode, dual, multi, st);
+    case 4: return launch_mfma_variant<4>(a, tb, mode, dual, multi, st);
+    default: return launch_mfma_variant<5>(a, tb, mode, dual, multi, st);
+  }
+}
+
+}  // namespace sq

@@ -1,0 +1,86 @@
+// Shared device-side declarations of the SegLinear + DualScale HIP library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "segquant.h"
+
+namespace sq {
+
+typedef int v2i __attribute__((ext_vector_type(2)));
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+constexpr float kQmax = 127.0f;
+
+// Segment tables travel by value in the kernel-argument block: no device allocation, stream-ordered,
+// safe under graph capture.  Indexing them with wave-uniform indices keeps them in scalar registers.
+struct ActTable {                      // for the activation quantize pass
+  int S;
+  int kseg_off[SQ_MAX_SEGMENTS + 1];
+  float s_pos[SQ_MAX_SEGMENTS];
+  float s_neg[SQ_MAX_SEGMENTS];
+  float inv_pos[SQ_MAX_SEGMENTS];      // 1 / s (NaN = reciprocal not usable, always divide)
+  float inv_neg[SQ_MAX_SEGMENTS];
+  unsigned char dual[SQ_MAX_SEGMENTS];
+};
+
+struct GemmTable {                     // for the SegLinear GEMM kernels
+  int S, T;
+  int has_seg_scale;
+  int kseg_off[SQ_MAX_SEGMENTS + 1];
+  int nseg_off[SQ_MAX_SEGMENTS + 1];
+  float s_pos[SQ_MAX_SEGMENTS];
+  float s_neg[SQ_MAX_SEGMENTS];
+  unsigned char dual[SQ_MAX_SEGMENTS];
+  float seg_scale[SQ_MAX_SEG_SCALE];   // [ks][ns], valid when has_seg_scale
+};
+
+struct GemmArgs {
+  const int8_t* xp;        // [M][K]
+  const int8_t* xn;        // [M][K] (unused columns of non-dual segments are never read)
+  const int8_t* wq;        // [N][K]
+  const float* wscale;     // [S][N]
+  const float* bias;       // [N] or nullptr
+  void* y;                 // [M][N] fp32 or bf16
+  int32_t* acc_pos;        // debug: [S][M][N]
+  int32_t* acc_neg;
+  int M, K, N;
+  int tiles_m, tiles_n, group_m;
+};
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// fp32 -> bf16, round-half-to-even on the dropped bits (finite inputs).
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+// round(v / s) of the Sec. 3 quantizer, bit-identical to an IEEE division followed by
+// round-half-to-even.  v * (1/s) is within 2^-14.4 of the correctly rounded quotient whenever the
+// quotient matters (|q| <= 256, beyond that both clip), so the cheap product decides unless it lands
+// within 2^-13 of a tie; only then (or when inv is NaN/Inf) the true division is evaluated.
+__device__ __forceinline__ float round_quotient(float v, float s, float inv) {
+  float q0 = v * inv;
+  float r = __builtin_rintf(q0);
+  float t = q0 - r;
+  if (!(__builtin_fabsf(t) < 0.4998779296875f)) r = __builtin_rintf(v / s);
+  return r;
+}
+
+__device__ __forceinline__ int clip_code(float r) {
+  return (int)__builtin_fminf(__builtin_fmaxf(r, -kQmax), kQmax);
+}
+
+// Column-dependent multiplier seg_scale[ks][ns(n)] without per-lane indexing of the by-value table.
+__device__ __forceinline__ float seg_scale_of(const GemmTable& tb, int ks, int n) {
+  if (!tb.has_seg_scale) return 1.0f;
+  float g = tb.seg_scale[ks * tb.T];
+  for (int t = 1; t < tb.T; ++t) g = (n >= tb.nseg_off[t]) ? tb.seg_scale[ks * tb.T + t] : g;
+  return g;
+}
+
+}  // namespace sq

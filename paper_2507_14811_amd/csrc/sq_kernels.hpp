@@ -1,0 +1,33 @@
+// Host-side launchers of the HIP kernels (one per source file).  Shapes are validated by the caller.
+#pragma once
+#include "sq_common.hpp"
+
+namespace sq {
+
+struct KsegTable {
+  int S;
+  int off[SQ_MAX_SEGMENTS + 1];
+};
+
+enum OutMode { OUT_F32 = 0, OUT_BF16 = 1, OUT_DEBUG_ACC = 2 };
+
+// quantize.hip
+hipError_t launch_quantize_act(const void* x, bool x_is_bf16, int8_t* xq_pos, int8_t* xq_neg, int M, int K,
+                               const ActTable& tb, hipStream_t st);
+hipError_t launch_quantize_weight(const void* w, bool w_is_bf16, int8_t* wq, float* wscale, int N, int K,
+                                  const KsegTable& tb, hipStream_t st);
+
+// seglinear_generic.hip : any shape / alignment, one thread per output element
+hipError_t launch_seglinear_generic(const GemmArgs& a, const GemmTable& tb, OutMode mode, hipStream_t st);
+
+// seglinear_mfma.hip : large-M int8 MFMA tile kernel.  Needs K % 16 == 0 and every K-segment boundary % 64 == 0.
+int mfma_num_variants();
+bool mfma_supported(const GemmArgs& a, const GemmTable& tb);
+int mfma_pick_variant(const GemmArgs& a, const GemmTable& tb, OutMode mode);
+hipError_t launch_seglinear_mfma(GemmArgs a, const GemmTable& tb, OutMode mode, int variant, hipStream_t st);
+
+// seglinear_skinny.hip : M <= 64, weight-streaming kernel.  Same alignment needs as the MFMA kernel.
+bool skinny_supported(const GemmArgs& a, const GemmTable& tb);
+hipError_t launch_seglinear_skinny(const GemmArgs& a, const GemmTable& tb, OutMode mode, hipStream_t st);
+
+}  // namespace sq
