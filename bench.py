@@ -1,0 +1,246 @@
+#!/usr/bin/env python3
+"""Benchmark of the SegLinear + DualScale hot path on one MI355X.
+
+A "step" is one pass of the whole online path over one batch of synthetic input that is already
+resident in HBM:  sq_quantize_act (bf16 -> int8 x+/x-)  followed by  sq_seglinear (dual-path int8 GEMM
+with per-K-segment accumulators and the fused dequant epilogue, bf16 out).  Weights are quantized once
+before the timed region (the offline step) and reported separately.
+
+Prints ONE JSON line.  `value` = executed int8 ops of the step (both polarity paths counted, skipped
+x- work of single-scale segments not counted) / step time.  `roofline` is the GEMM kernel alone, timed
+with HIP events on the launch stream inside the timed region.  `cpu_baseline` is the CPU oracle on a
+bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+INT8_MFMA_PEAK_TOPS = 5033.2   # 256 CU x 2.4 GHz x 8192 int8 ops/clk/CU (dense)
+HBM_PEAK_GBS = 8000.0
+
+# HBM traffic per GEMM launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/), bytes.
+# None until a counter run for that workload has been committed.
+MEASURED_TRAFFIC = {}
+
+
+def _setup(name):
+    import torch
+
+    from paper_2507_14811_amd import workloads as wl
+    import paper_2507_14811_amd as sq
+
+    w = wl.make(name)
+    dev = "cuda:0"
+    layer = sq.Layer.from_workload(w)
+    if w.x_dtype == "bf16":
+        x = torch.from_numpy(wl.f32_to_bf16_bits(w.x).view(np.int16)).view(torch.bfloat16).to(dev)
+    else:
+        x = torch.from_numpy(w.x).to(dev)
+    wt = torch.from_numpy(w.w).to(dev)
+    wq = torch.empty((w.N, w.K), dtype=torch.int8, device=dev)
+    wscale = torch.empty((w.S, w.N), dtype=torch.float32, device=dev)
+    xp = torch.empty((w.M, w.K), dtype=torch.int8, device=dev)
+    xn = torch.empty((w.M, w.K), dtype=torch.int8, device=dev)
+    y = torch.empty((w.M, w.N), dtype=torch.bfloat16, device=dev)
+    return dict(w=w, layer=layer, x=x, wt=wt, wq=wq, wscale=wscale, xp=xp, xn=xn, y=y)
+
+
+def _time_events(fn, iters):
+    import torch
+
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+    for a, b in evs:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    return [a.elapsed_time(b) for a, b in evs]
+
+
+def measure(name, steps, warmup, rotate_quant=True):
+    """Times one workload.  Returns a dict of per-kernel and per-step figures."""
+    import torch
+
+    import paper_2507_14811_amd as sq
+
+    s = _setup(name)
+    w, layer = s["w"], s["layer"]
+
+    # offline step: weight quantization (timed on its own)
+    sq.sq_quantize_weight(layer, s["wt"], s["wq"], s["wscale"])
+    torch.cuda.synchronize()
+    t_wq = float(np.median(_time_events(lambda: sq.sq_quantize_weight(layer, s["wt"], s["wq"], s["wscale"]), 5)))
+
+    def quant():
+        sq.sq_quantize_act(layer, s["x"], s["xp"], s["xn"])
+
+    def gemm():
+        sq.sq_seglinear(layer, s["xp"], s["xn"], s["wq"], s["wscale"], None, s["y"])
+
+    for _ in range(warmup):
+        quant()
+        gemm()
+    torch.cuda.synchronize()
+
+    # ---- the timed region: exactly `steps` steps, HIP events around every GEMM launch ----------------
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for a, b in ev:
+        quant()
+        a.record()
+        gemm()
+        b.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_step = (t1 - t0) * 1e3 / steps
+    ms_gemm = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+
+    # quantize pass alone (outside the step timing).  Small inputs would sit in the 256 MB Infinity
+    # Cache between calls, so rotate over distinct buffers totalling > 512 MB to measure HBM.
+    qbytes = w.quantize_act_bytes()
+    nrot = 1
+    if rotate_quant and qbytes < 300e6:
+        nrot = int(min(64, max(2, np.ceil(600e6 / qbytes))))
+    xs = [s["x"]] + [s["x"].clone() for _ in range(nrot - 1)]
+    xps = [s["xp"]] + [torch.empty_like(s["xp"]) for _ in range(nrot - 1)]
+    xns = [s["xn"]] + [torch.empty_like(s["xn"]) for _ in range(nrot - 1)]
+    reps = max(2, int(np.ceil(40 / nrot)))
+
+    def quant_rot():
+        for i in range(nrot):
+            sq.sq_quantize_act(layer, xs[i], xps[i], xns[i])
+
+    quant_rot()
+    torch.cuda.synchronize()
+    ms_quant = float(np.median(_time_events(quant_rot, reps))) / nrot
+    # restore the canonical buffers for the GEMM
+    quant()
+    torch.cuda.synchronize()
+
+    gbytes = w.seglinear_bytes("bf16")
+    return dict(
+        name=w.name, M=w.M, K=w.K, N=w.N, S=w.S, T=w.T, dual=[int(d) for d in w.dual],
+        int8_ops=w.int8_ops, ms_step=ms_step, ms_gemm=ms_gemm, ms_quant=ms_quant, ms_quantize_weight=t_wq,
+        gemm_tops=w.int8_ops / (ms_gemm * 1e-3) / 1e12, step_tops=w.int8_ops / (ms_step * 1e-3) / 1e12,
+        gemm_bytes=gbytes, gemm_gbs=gbytes / (ms_gemm * 1e-3) / 1e9,
+        quant_bytes=qbytes, quant_gbs=qbytes / (ms_quant * 1e-3) / 1e9, quant_rotation=nrot,
+    )
+
+
+def cpu_baseline(name, budget_s=15.0):
+    """The CPU oracle, as it stands, on a bounded sample of the workload's token rows."""
+    import oracle
+    from paper_2507_14811_amd import workloads as wl
+
+    oracle.build()
+    w = wl.make(name)
+    wq, ws = oracle.quantize_weight(w.w, w.kseg_off)
+    probe = min(w.M, 8)
+    xp, xn = oracle.quantize_act(w.x[:probe], w.kseg_off, w.dual, w.s_pos, w.s_neg)
+    t0 = time.perf_counter()
+    oracle.int_gemm(xp, xn, wq, w.kseg_off, w.dual)
+    per_row = max((time.perf_counter() - t0) / probe, 1e-6)
+    rows = int(max(probe, min(w.M, budget_s / per_row)))
+    xs = np.ascontiguousarray(w.x[:rows])
+    t0 = time.perf_counter()
+    xp, xn = oracle.quantize_act(xs, w.kseg_off, w.dual, w.s_pos, w.s_neg)
+    ap, an = oracle.int_gemm(xp, xn, wq, w.kseg_off, w.dual)
+    y32, _ = oracle.dequant(ap, an, w.nseg_off, w.dual, w.s_pos, w.s_neg, ws, w.seg_scale, w.bias, want64=False)
+    oracle.cast_bf16(y32)
+    dt = time.perf_counter() - t0
+    ops = 2.0 * rows * w.N * w.keff
+    return {"value": ops / dt / 1e12, "unit": "int8 TOPS", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"first {rows} of {w.M} token rows of {w.name}: quantize_act + integer GEMM + dequant + bf16 cast, "
+                      f"{dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="cfg5", help="headline workload (cfg2 | cfg4 | cfg4d | cfg5)")
+    ap.add_argument("--others", default="cfg2,cfg3,cfg4,cfg4d", help="extra workloads summarised in the same line")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--variant", type=int, default=-1, help="force an MFMA tile variant (diagnostics)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(the path shards along M without any exchange; see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2507_14811_amd as sq
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    sq.load_library()
+    if args.variant >= 0:
+        sq.sq_tuning_set("gemm_variant", args.variant)
+
+    head = measure(args.config, args.steps, args.warmup)
+    others = {}
+    for name in [n for n in args.others.split(",") if n and n != args.config]:
+        sq.sq_tuning_set("gemm_variant", -1)
+        r = measure(name, max(10, args.steps // 2), max(3, args.warmup // 2))
+        skinny = r["M"] <= 64
+        others[name] = {
+            "M": r["M"], "K": r["K"], "N": r["N"], "ms_gemm": round(r["ms_gemm"], 5), "ms_quant": round(r["ms_quant"], 5),
+            "gemm_tops": round(r["gemm_tops"], 2), "gemm_frac_mfma_peak": round(r["gemm_tops"] / INT8_MFMA_PEAK_TOPS, 4),
+            "gemm_gbs": round(r["gemm_gbs"], 1), "gemm_frac_hbm_peak": round(r["gemm_gbs"] / HBM_PEAK_GBS, 4),
+            "gemm_bound": "hbm" if skinny else "mfma",
+            "quant_gbs": round(r["quant_gbs"], 1), "quant_frac_hbm_peak": round(r["quant_gbs"] / HBM_PEAK_GBS, 4),
+            "ms_quantize_weight": round(r["ms_quantize_weight"], 5),
+        }
+
+    line = {
+        "metric": "int8 TOPS (both dual paths) of SegLinear+DualScale GEMM; % int8 MFMA peak",
+        "value": round(head["step_tops"], 3),
+        "unit": "int8 TOPS",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(head["ms_step"], 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int8",
+        "data": "synthetic",
+        "config": {"workload": head["name"], "M": head["M"], "K": head["K"], "N": head["N"],
+                   "k_segments": head["S"], "n_segments": head["T"], "dual": head["dual"],
+                   "step": "sq_quantize_act + sq_seglinear (bf16 in, bf16 out); weights pre-quantized"},
+        "roofline": {
+            "kernel": "seglinear_mfma_kernel",
+            "bound": "mfma",
+            "achieved": round(head["gemm_tops"], 2),
+            "peak": INT8_MFMA_PEAK_TOPS,
+            "unit": "TOP/s",
+            "frac": round(head["gemm_tops"] / INT8_MFMA_PEAK_TOPS, 4),
+            "ms_per_launch": round(head["ms_gemm"], 5),
+            "traffic": MEASURED_TRAFFIC.get(head["name"]),
+        },
+        "quantize_act": {"bound": "hbm", "achieved": round(head["quant_gbs"], 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": round(head["quant_gbs"] / HBM_PEAK_GBS, 4), "ms_per_launch": round(head["ms_quant"], 5),
+                         "bytes": head["quant_bytes"]},
+        "quantize_weight_ms": round(head["ms_quantize_weight"], 5),
+        "other_workloads": others,
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(args.config)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

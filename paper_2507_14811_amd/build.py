@@ -44,7 +44,7 @@ def _jobs():
 
 def _compile(job):
     src, obj, extra = job
-    cmd = [HIPCC, *FLAGS, *extra, "-c", src, "-o", obj]
+    cmd = [HIPCC, *FLAGS, *extra, *os.environ.get("SQ_EXTRA_HIPCC_FLAGS", "").split(), "-c", src, "-o", obj]
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     out = "\n".join(l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l and l.strip())
     if r.returncode != 0:

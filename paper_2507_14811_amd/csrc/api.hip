@@ -58,6 +58,7 @@ void fill_gemm_table(const sq_layer* L, sq::GemmTable& tb) {
   for (int t = 0; t <= L->T; ++t) tb.nseg_off[t] = L->nseg_off[t];
   for (int s = 0; s < L->S; ++s) {
     tb.dual[s] = L->dual[s] ? 1 : 0;
+    tb.seg_order[s] = s;
     tb.s_pos[s] = L->s_pos ? L->s_pos[s] : 1.0f;
     tb.s_neg[s] = (L->dual[s] && L->s_neg) ? L->s_neg[s] : 0.0f;
   }

@@ -4,13 +4,13 @@
 
 namespace sq {
 
-#define SQ_DECL(V) extern template hipError_t launch_mfma_variant<V>(const GemmArgs&, const GemmTable&, int, bool, bool, hipStream_t);
-SQ_DECL(0) SQ_DECL(1) SQ_DECL(2) SQ_DECL(3) SQ_DECL(4) SQ_DECL(5)
+#define SQ_DECL(V) extern template hipError_t launch_mfma_variant<V>(const GemmArgs&, const GemmTable&, int, bool, bool, bool, hipStream_t);
+SQ_DECL(0) SQ_DECL(1) SQ_DECL(2) SQ_DECL(3) SQ_DECL(4) SQ_DECL(5) SQ_DECL(6)
 #undef SQ_DECL
 
 template <int V> static MfmaVariantInfo info_of() {
   using P = MfmaVariant<V>;
-  return {P::BM, P::BN, P::DUAL_OK, P::MULTI_DUAL_OK};
+  return {P::BM, P::BN, P::SK, P::DUAL_OK, P::MULTI_OK, P::MULTI_DUAL_OK, P::SHARE_OK};
 }
 static MfmaVariantInfo variant_info(int v) {
   switch (v) {
@@ -19,25 +19,41 @@ static MfmaVariantInfo variant_info(int v) {
     case 2: return info_of<2>();
     case 3: return info_of<3>();
     case 4: return info_of<4>();
-    default: return info_of<5>();
+    case 5: return info_of<5>();
+    default: return info_of<6>();
   }
 }
 // Relative main-loop efficiency of a tile shape (larger wave tiles re-use LDS fragments more).
-static const float kTileEff[kNumMfmaVariants] = {1.00f, 0.85f, 0.85f, 0.70f, 1.00f, 0.90f};
+static const float kTileEff[kNumMfmaVariants] = {1.00f, 0.85f, 0.85f, 0.70f, 1.00f, 0.90f, 0.60f};
 
 int mfma_num_variants() { return kNumMfmaVariants; }
 
-static void layer_flags(const GemmTable& tb, bool& dual, bool& multi) {
-  dual = false;
-  for (int s = 0; s < tb.S; ++s) dual = dual || (tb.dual[s] != 0);
+// dual: some K-segment runs both polarity paths; multi: more than one K-segment; share: exactly one dual
+// segment among several, so it can be visited first and its X^_- accumulator registers re-used as the fp32
+// running sum afterwards.
+static void layer_flags(const GemmTable& tb, bool& dual, bool& multi, bool& share) {
+  int ndual = 0;
+  for (int s = 0; s < tb.S; ++s) ndual += (tb.dual[s] != 0);
+  dual = ndual > 0;
   multi = tb.S > 1;
+  share = multi && ndual == 1;
 }
 
-static bool variant_ok(int v, bool dual, bool multi) {
+// Largest stage depth (128 or 64 bytes of K) that K and every K-segment boundary are a multiple of.
+static int k_alignment(const GemmArgs& a, const GemmTable& tb) {
+  int al = (a.K % 128 == 0) ? 128 : 64;
+  for (int s = 0; s <= tb.S; ++s)
+    if (tb.kseg_off[s] % 128 != 0) al = 64;
+  return al;
+}
+
+static bool variant_ok(int v, bool dual, bool multi, bool share, int kalign) {
   if (v < 0 || v >= kNumMfmaVariants) return false;
   const MfmaVariantInfo i = variant_info(v);
+  if (i.SK > kalign) return false;
   if (dual && !i.dual_ok) return false;
-  if (dual && multi && !i.multi_dual_ok) return false;
+  if (dual && multi && !(i.multi_dual_ok || (share && i.share_ok))) return false;
+  if (!dual && multi && !i.multi_ok) return false;
   return true;
 }
 
@@ -51,14 +67,14 @@ bool mfma_supported(const GemmArgs& a, const GemmTable& tb) {
 }
 
 int mfma_pick_variant(const GemmArgs& a, const GemmTable& tb, OutMode) {
-  bool dual, multi;
-  layer_flags(tb, dual, multi);
+  bool dual, multi, share;
+  layer_flags(tb, dual, multi, share);
   int dev = 0, cus = 256;
   if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
   int best = -1;
   float best_score = -1.0f;
   for (int v = 0; v < kNumMfmaVariants; ++v) {
-    if (!variant_ok(v, dual, multi)) continue;
+    if (!variant_ok(v, dual, multi, share, k_alignment(a, tb))) continue;
     const MfmaVariantInfo i = variant_info(v);
     const long tiles = (long)((a.M + i.BM - 1) / i.BM) * ((a.N + i.BN - 1) / i.BN);
     const long rounds = (tiles + cus - 1) / cus;
@@ -69,21 +85,31 @@ int mfma_pick_variant(const GemmArgs& a, const GemmTable& tb, OutMode) {
   return best;
 }
 
-hipError_t launch_seglinear_mfma(GemmArgs a, const GemmTable& tb, OutMode mode, int variant, hipStream_t st) {
-  bool dual, multi;
-  layer_flags(tb, dual, multi);
-  if (!variant_ok(variant, dual, multi)) return hipErrorInvalidConfiguration;
+hipError_t launch_seglinear_mfma(GemmArgs a, const GemmTable& tb_in, OutMode mode, int variant, hipStream_t st) {
+  bool dual, multi, share;
+  layer_flags(tb_in, dual, multi, share);
+  if (!variant_ok(variant, dual, multi, share, k_alignment(a, tb_in))) return hipErrorInvalidConfiguration;
   const MfmaVariantInfo i = variant_info(variant);
+  GemmTable tb = tb_in;
+  share = share && i.share_ok;        // prefer the register-sharing mode wherever the tile supports it
+  if (share) {                        // visit the dual K-segment first, the others in ascending order
+    int pos = 0;
+    for (int s = 0; s < tb.S; ++s)
+      if (tb.dual[s]) tb.seg_order[pos++] = s;
+    for (int s = 0; s < tb.S; ++s)
+      if (!tb.dual[s]) tb.seg_order[pos++] = s;
+  }
   a.tiles_m = (a.M + i.BM - 1) / i.BM;
   a.tiles_n = (a.N + i.BN - 1) / i.BN;
   a.group_m = a.tiles_m < 8 ? a.tiles_m : 8;
   switch (variant) {
-    case 0: return launch_mfma_variant<0>(a, tb, mode, dual, multi, st);
-    case 1: return launch_mfma_variant<1>(a, tb, mode, dual, multi, st);
-    case 2: return launch_mfma_variant<2>(a, tb, mode, dual, multi, st);
-    case 3: return launch_mfma_variant<3>(a, tb, mode, dual, multi, st);
-    case 4: return launch_mfma_variant<4>(a, tb, mode, dual, multi, st);
-    default: return launch_mfma_variant<5>(a, tb, mode, dual, multi, st);
+    case 0: return launch_mfma_variant<0>(a, tb, mode, dual, multi, share, st);
+    case 1: return launch_mfma_variant<1>(a, tb, mode, dual, multi, share, st);
+    case 2: return launch_mfma_variant<2>(a, tb, mode, dual, multi, share, st);
+    case 3: return launch_mfma_variant<3>(a, tb, mode, dual, multi, share, st);
+    case 4: return launch_mfma_variant<4>(a, tb, mode, dual, multi, share, st);
+    case 5: return launch_mfma_variant<5>(a, tb, mode, dual, multi, share, st);
+    default: return launch_mfma_variant<6>(a, tb, mode, dual, multi, share, st);
   }
 }
 

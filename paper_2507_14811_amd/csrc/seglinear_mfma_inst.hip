@@ -9,33 +9,41 @@
 
 namespace sq {
 
-template <int V, bool DUAL, bool MULTI>
+template <int V, bool DUAL, bool MULTI, bool SHARE>
 static hipError_t launch_one(const GemmArgs& a, const GemmTable& tb, int mode, hipStream_t st) {
   using P = MfmaVariant<V>;
-  auto kern = seglinear_mfma_kernel<P::BM, P::BN, P::WM, P::WN, P::NS, DUAL, MULTI>;
+  auto kern = seglinear_mfma_kernel<P::BM, P::BN, P::WM, P::WN, P::NS, P::SK, DUAL, MULTI, SHARE>;
   const int blocks = a.tiles_m * a.tiles_n;
   hipLaunchKernelGGL(kern, dim3(blocks), dim3(P::WM * P::WN * 64), 0, st, a, tb, mode);
   return hipGetLastError();
 }
 
 template <int V>
-hipError_t launch_mfma_variant(const GemmArgs& a, const GemmTable& tb, int mode, bool dual, bool multi, hipStream_t st) {
+hipError_t launch_mfma_variant(const GemmArgs& a, const GemmTable& tb, int mode, bool dual, bool multi, bool share,
+                               hipStream_t st) {
   using P = MfmaVariant<V>;
   if (dual) {
     if constexpr (P::DUAL_OK) {
-      if (multi) {
-        if constexpr (P::MULTI_DUAL_OK) return launch_one<V, true, true>(a, tb, mode, st);
+      if (multi && share) {
+        if constexpr (P::SHARE_OK) return launch_one<V, true, true, true>(a, tb, mode, st);
         else return hipErrorInvalidConfiguration;
       }
-      return launch_one<V, true, false>(a, tb, mode, st);
+      if (multi) {
+        if constexpr (P::MULTI_DUAL_OK) return launch_one<V, true, true, false>(a, tb, mode, st);
+        else return hipErrorInvalidConfiguration;
+      }
+      return launch_one<V, true, false, false>(a, tb, mode, st);
     } else {
       return hipErrorInvalidConfiguration;
     }
   }
-  if (multi) return launch_one<V, false, true>(a, tb, mode, st);
-  return launch_one<V, false, false>(a, tb, mode, st);
+  if (multi) {
+    if constexpr (P::MULTI_OK) return launch_one<V, false, true, false>(a, tb, mode, st);
+    else return hipErrorInvalidConfiguration;
+  }
+  return launch_one<V, false, false, false>(a, tb, mode, st);
 }
 
-template hipError_t launch_mfma_variant<SQ_VARIANT>(const GemmArgs&, const GemmTable&, int, bool, bool, hipStream_t);
+template hipError_t launch_mfma_variant<SQ_VARIANT>(const GemmArgs&, const GemmTable&, int, bool, bool, bool, hipStream_t);
 
 }  // namespace sq

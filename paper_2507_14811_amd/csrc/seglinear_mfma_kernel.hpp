@@ -10,17 +10,22 @@
 //     "B" operand (C column = lane & 31), so every lane needs the dequant constants of only TN/32
 //     output columns.
 //   * Operand tiles are fetched with direct global->LDS loads (global_load_lds_dwordx4): no staging
-//     registers and a ring of NSTAGE 64-byte-deep K stages, i.e. NSTAGE-1 stages of prefetch in flight.
-//   * One LDS stage holds [X^_+ rows][X^_- rows][W^ rows], 64 B per row; the W^ fragments read from it
-//     feed both accumulator sets, so W^ is fetched and read once for the two polarity paths.
-//   * Inside a row the four 16-byte chunks are XOR-swizzled with bits 1-2 of the row index.  A direct
-//     load writes lane l to byte 16*l of a 1 KiB block (= row l/4, slot l%4), so the swizzle is applied
-//     to the *global* column each lane fetches; ds_read_b128 fragment reads (lane -> row l%32) then hit
-//     all LDS banks evenly.  The k-order inside a fragment is irrelevant as long as both operands use
-//     the same one, which they do.
+//     registers, and a ring of NSTAGE stages of SK bytes of K each.  SK = 128 makes every row of a
+//     stage one full 128-byte cache line (the default); SK = 64 serves layers whose K-segment
+//     boundaries are only 64-aligned.
+//   * One LDS stage holds [X^_+ rows][X^_- rows][W^ rows], SK bytes per row; the W^ fragments read from
+//     it feed both accumulator sets, so W^ is fetched and read once for the two polarity paths.
+//   * Inside a row the 16-byte chunks are XOR-swizzled with row bits chosen so that the 16 lanes the
+//     LDS serves per cycle (256 B/clk) fall on distinct bank groups for the MFMA fragment read pattern
+//     (lane -> row lane%32): chunk ^= (row >> 1) & 7 for 128-byte rows, (row >> 2) & 3 for 64-byte rows.
+//     A direct load writes lane l to byte 16*l of a 1 KiB block, so the swizzle is applied to the
+//     *global* column each lane fetches.  The k-order inside a fragment is irrelevant as long as both
+//     operands use the same one, which they do.
 //   * int32 accumulators are exact; at a K-segment boundary they are scaled into an fp32 running sum
 //     (only instantiated when the layer has more than one K-segment) and cleared.  A non-dual segment
 //     neither loads X^_- nor issues its MFMAs.
+//   * The epilogue stages each 32-row block of the wave's result through (now idle) LDS so that global
+//     stores are 16 bytes per lane along N (full cache lines) instead of 2-byte scatters.
 //   * Workgroup ids are remapped so that each XCD (ids are dealt round-robin to the 8 XCDs) works on a
 //     contiguous run of tiles, ordered in panels of group_m row-tiles so concurrently resident
 //     workgroups of an XCD share X^ and W^ tiles in that XCD's L2.
@@ -47,6 +52,7 @@ __device__ __forceinline__ void wait_vmcnt(int n) {
 #define SQ_WAIT(i) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(i) : "memory")
   if (n == FAST0) { SQ_WAIT(FAST0); }
   else if (n == FAST1) { SQ_WAIT(FAST1); }
+  else if (n >= 32) { SQ_WAIT(32); }
   else if (n >= 24) { SQ_WAIT(24); }
   else if (n >= 16) { SQ_WAIT(16); }
   else if (n >= 12) { SQ_WAIT(12); }
@@ -62,27 +68,46 @@ __device__ __forceinline__ void wait_vmcnt(int n) {
 
 #define SQ_LDS(p) ((__attribute__((address_space(3))) char*)(p))
 
-template <int BM, int BN, int WM, int WN, int NSTAGE, bool DUAL, bool MULTI>
+template <int BM, int BN, int WM, int WN, int NSTAGE, int SK, bool DUAL, bool MULTI, bool SHARE>
 struct MfmaCfg {
   static constexpr int NW = WM * WN;
   static constexpr int THREADS = NW * 64;
   static constexpr int TM = BM / WM, TN = BN / WN;
   static constexpr int IM = TM / 32, JN = TN / 32;
   static constexpr int AROWS = BM * (DUAL ? 2 : 1);
-  static constexpr int STAGE = (AROWS + BN) * 64;
-  static constexpr int GA = BM / 16 / NW;   // 16-row load groups per wave, per polarity
-  static constexpr int GB = BN / 16 / NW;
+  static constexpr int STAGE = (AROWS + BN) * SK;
+  static constexpr int RPL = 1024 / SK;            // rows covered by one direct-load instruction
+  static constexpr int GA = BM / RPL / NW;         // load instructions per wave and stage, per polarity
+  static constexpr int GB = BN / RPL / NW;
+  static constexpr int SUB = SK / 32;              // 32-byte MFMA k-steps per stage
+  static constexpr int CPR = SK / 16;              // 16-byte chunks per row
+  static constexpr int EPI_ROW = TN * 4 + 16;      // staging row of the epilogue (fp32 worst case, padded)
+  static constexpr int EPI = 32 * EPI_ROW;         // per wave
+  static constexpr int LDS_BYTES = NSTAGE * STAGE;
+  static constexpr int LT = 2 * GA + GB;           // direct-load slots of one stage: X^_+ groups, X^_- groups, W^ groups
+  static constexpr int NSLOT = SUB * IM;           // points inside a stage's MFMA stream where loads are interleaved
+  static_assert(SK == 64 || SK == 128, "stage depth");
+  static_assert(!SHARE || (DUAL && MULTI), "register sharing is a mode of dual multi-segment layers");
   static_assert(TM % 32 == 0 && TN % 32 == 0, "wave tile must be a multiple of the 32x32 MFMA");
-  static_assert(BM % (16 * NW) == 0 && BN % (16 * NW) == 0, "load groups must divide evenly over the waves");
-  static_assert(NSTAGE * STAGE <= 160 * 1024, "LDS ring exceeds 160 KB");
+  static_assert(BM % (RPL * NW) == 0 && BN % (RPL * NW) == 0, "load groups must divide evenly over the waves");
+  static_assert(LDS_BYTES <= 160 * 1024, "LDS ring exceeds 160 KB");
+  static_assert(NW * EPI <= NSTAGE * STAGE, "epilogue staging must fit in the ring");
+  static_assert((NSTAGE - 1) * (2 * GA + GB) < 64, "vmcnt is a 6-bit counter");
 };
 
-template <int BM, int BN, int WM, int WN, int NSTAGE, bool DUAL, bool MULTI>
+template <int SK> __device__ __forceinline__ int row_swizzle(int row) {
+  return SK == 128 ? ((row >> 1) & 7) : ((row >> 2) & 3);
+}
+
+template <int BM, int BN, int WM, int WN, int NSTAGE, int SK, bool DUAL, bool MULTI, bool SHARE>
 __global__ __launch_bounds__(WM * WN * 64, 1) void seglinear_mfma_kernel(const GemmArgs a, const GemmTable tb,
                                                                          const int mode) {
-  using C = MfmaCfg<BM, BN, WM, WN, NSTAGE, DUAL, MULTI>;
-  constexpr int IM = C::IM, JN = C::JN, GA = C::GA, GB = C::GB, STAGE = C::STAGE;
-  __shared__ __attribute__((aligned(1024))) char smem[NSTAGE * STAGE];
+  using C = MfmaCfg<BM, BN, WM, WN, NSTAGE, SK, DUAL, MULTI, SHARE>;
+  constexpr bool FSUM = MULTI && !SHARE;      // a separate fp32 running-sum register set
+  constexpr int IM = C::IM, JN = C::JN, GA = C::GA, GB = C::GB, STAGE = C::STAGE, RPL = C::RPL, SUB = C::SUB;
+  constexpr int KSH = SK == 128 ? 7 : 6;
+  constexpr int LT = C::LT, NSLOT = C::NSLOT;
+  __shared__ __attribute__((aligned(1024))) char smem[C::LDS_BYTES];
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -104,112 +129,190 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void seglinear_mfma_kernel(const G
   const int m0 = tm * BM, n0 = tn * BN;
 
   // ---- per-lane source offsets of the direct loads (constant over the K loop) ----------------------
-  const int lrow = lane >> 2;                               // row inside a 16-row group
-  const int lchunk = (lane & 3) ^ ((lrow >> 1) & 3);        // logical 16 B chunk that belongs in slot lane&3
+  // lane -> (row lane / CPR of the instruction's RPL rows, 16 B slot lane % CPR holding chunk slot ^ swizzle(row))
+  const int lrow = lane / C::CPR, lslot = lane % C::CPR;
   uint32_t voffA[GA], voffB[GB];
 #pragma unroll
   for (int g = 0; g < GA; ++g) {
-    int r = m0 + (wave * GA + g) * 16 + lrow;
+    const int rt = (wave * GA + g) * RPL + lrow;            // row inside the tile
+    int r = m0 + rt;
     r = r < a.M ? r : a.M - 1;                              // ragged tail: re-read the last row, masked at the store
-    voffA[g] = (uint32_t)r * (uint32_t)a.K + (uint32_t)lchunk * 16u;
+    voffA[g] = (uint32_t)r * (uint32_t)a.K + (uint32_t)((lslot ^ row_swizzle<SK>(rt)) << 4);
   }
 #pragma unroll
   for (int g = 0; g < GB; ++g) {
-    int r = n0 + (wave * GB + g) * 16 + lrow;
+    const int rt = (wave * GB + g) * RPL + lrow;
+    int r = n0 + rt;
     r = r < a.N ? r : a.N - 1;
-    voffB[g] = (uint32_t)r * (uint32_t)a.K + (uint32_t)lchunk * 16u;
+    voffB[g] = (uint32_t)r * (uint32_t)a.K + (uint32_t)((lslot ^ row_swizzle<SK>(rt)) << 4);
   }
   const uint32_t lds0 = (uint32_t)(uintptr_t)SQ_LDS(smem);
   const uint32_t ldsA = lds0 + (uint32_t)(wave * GA) * 1024u;
-  const uint32_t ldsN = ldsA + (uint32_t)BM * 64u;
-  const uint32_t ldsB = lds0 + (uint32_t)C::AROWS * 64u + (uint32_t)(wave * GB) * 1024u;
+  const uint32_t ldsN = ldsA + (uint32_t)BM * SK;
+  const uint32_t ldsB = lds0 + (uint32_t)C::AROWS * SK + (uint32_t)(wave * GB) * 1024u;
 
   // ---- per-lane fragment read offsets: row = lane%32, chunk = 2h + lane/32, swizzled ---------------
-  const int frow = lane & 31, fsw = (frow >> 1) & 3, fhi = lane >> 5;
-  const int foff0 = frow * 64 + (((0 + fhi) ^ fsw) << 4);
-  const int foff1 = frow * 64 + (((2 + fhi) ^ fsw) << 4);
-  const char* fragA = smem + (wm * C::TM) * 64;
-  const char* fragN = fragA + BM * 64;
-  const char* fragB = smem + C::AROWS * 64 + (wn * C::TN) * 64;
+  const int frow = lane & 31, fsw = row_swizzle<SK>(frow), fhi = lane >> 5;
+  int foff[SUB];
+#pragma unroll
+  for (int h = 0; h < SUB; ++h) foff[h] = frow * SK + (((2 * h + fhi) ^ fsw) << 4);
+  const char* fragA = smem + (wm * C::TM) * SK;
+  const char* fragN = fragA + BM * SK;
+  const char* fragB = smem + C::AROWS * SK + (wn * C::TN) * SK;
 
   v16i accp[IM][JN];
   v16i accn[DUAL ? IM : 1][DUAL ? JN : 1];
-  float fsum[MULTI ? IM : 1][MULTI ? JN : 1][16];
+  float fsum[FSUM ? IM : 1][FSUM ? JN : 1][16];
 #pragma unroll
   for (int i = 0; i < IM; ++i)
 #pragma unroll
     for (int j = 0; j < JN; ++j) {
       accp[i][j] = (v16i)(0);
       if (DUAL) accn[i][j] = (v16i)(0);
-      if (MULTI)
+      if (FSUM)
 #pragma unroll
         for (int v = 0; v < 16; ++v) fsum[i][j][v] = 0.0f;
     }
 
-  const int nkt = a.K >> 6;
-  // issue cursor
-  int iks = 0, issued = 0, ikt = 0;
-  auto issue = [&]() {
-    const int k0 = ikt << 6;
-    while (k0 >= tb.kseg_off[iks + 1]) ++iks;
-    const bool dl = DUAL && (tb.dual[iks] != 0);
-    const uint32_t so = (uint32_t)(ikt % NSTAGE) * (uint32_t)STAGE;
-#pragma unroll
-    for (int g = 0; g < GA; ++g) glds16(a.xp + k0, voffA[g], ldsA + so + g * 1024u);
-    if (dl) {
-#pragma unroll
-      for (int g = 0; g < GA; ++g) glds16(a.xn + k0, voffA[g], ldsN + so + g * 1024u);
+  const int nkt = a.K >> KSH;
+  // ---- direct loads of one stage, issued slot by slot ------------------------------------------------
+  // A stage's loads are a list of LT slots (X^_+ groups, X^_- groups, W^ groups).  The pipeline fill issues
+  // whole stages; in steady state the slots of the next stage are spread over the current stage's MFMA
+  // stream, so that a wave never sits in a burst of load issues while its MFMA pipe is idle.
+  // K-segments are visited in the order tb.seg_order (identity unless SHARE); stages are numbered in visit order.
+  int issued = 0, ikt = 0;
+  int ipos = 0, iks = tb.seg_order[0];
+  int ik = tb.kseg_off[iks] >> KSH, ik_end = tb.kseg_off[iks + 1] >> KSH;
+  const int8_t* ipA = a.xp;    // operand base pointers of the stage being issued
+  const int8_t* ipN = a.xn;
+  const int8_t* ipB = a.wq;
+  bool idl = false;
+  uint32_t iso = 0;
+  auto issue_begin = [&]() {
+    const int k0 = ik << KSH;
+    idl = DUAL && (tb.dual[iks] != 0);
+    iso = (uint32_t)(ikt % NSTAGE) * (uint32_t)STAGE;
+    ipA = a.xp + k0;
+    ipN = a.xn + k0;
+    ipB = a.wq + k0;
+  };
+  auto issue_slot = [&](const int e) {          // e is a compile-time constant after unrolling
+    if (e < GA) {
+      glds16(ipA, voffA[e < GA ? e : 0], ldsA + iso + (uint32_t)e * 1024u);
+      ++issued;
+    } else if (e < 2 * GA) {
+      if (idl) {
+        glds16(ipN, voffA[(e - GA) < GA ? (e >= GA ? e - GA : 0) : 0], ldsN + iso + (uint32_t)(e - GA) * 1024u);
+        ++issued;
+      }
+    } else {
+      glds16(ipB, voffB[(e - 2 * GA) < GB ? (e >= 2 * GA ? e - 2 * GA : 0) : 0], ldsB + iso + (uint32_t)(e - 2 * GA) * 1024u);
+      ++issued;
     }
-#pragma unroll
-    for (int g = 0; g < GB; ++g) glds16(a.wq + k0, voffB[g], ldsB + so + g * 1024u);
-    issued += GA * (dl ? 2 : 1) + GB;
+  };
+  auto issue_end = [&]() {
     ++ikt;
+    if (++ik == ik_end && ipos + 1 < tb.S) {
+      iks = tb.seg_order[++ipos];
+      ik = tb.kseg_off[iks] >> KSH;
+      ik_end = tb.kseg_off[iks + 1] >> KSH;
+    }
   };
 #pragma unroll 1
-  for (int s = 0; s < NSTAGE - 1 && s < nkt; ++s) issue();
+  for (int s = 0; s < NSTAGE - 1 && s < nkt; ++s) {
+    issue_begin();
+#pragma unroll
+    for (int e = 0; e < LT; ++e) issue_slot(e);
+    issue_end();
+  }
 
   // ---- main loop over one K-segment: DL = this segment runs both polarity paths ----------------------
   int kt = 0, retired = 0;
-  auto run_segment = [&](auto dl_tag, const int kt_end) {
+  // One stage of MFMAs; MORE = the next stage's direct loads are interleaved (one share per MFMA row).
+  auto compute_stage = [&](auto dl_tag, auto more_tag) {
     constexpr bool DL = decltype(dl_tag)::value;
-#pragma unroll 1
-    for (; kt < kt_end; ++kt) {
-      retired += GA * (DL ? 2 : 1) + GB;         // loads of stage kt are the oldest outstanding ones
-      wait_vmcnt<(NSTAGE - 2) * (2 * GA + GB), (NSTAGE - 2) * (GA + GB)>(issued - retired);
-      __syncthreads();                           // stage kt visible to all waves; stage kt-1 free for reuse
-      if (ikt < nkt) issue();
-
-      const int so = (kt % NSTAGE) * STAGE;
+    constexpr bool MORE = decltype(more_tag)::value;
+    const int so = (kt % NSTAGE) * STAGE;
 #pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const int fo = so + (h ? foff1 : foff0);
-        v4i bf[JN], af[IM], nf[DL ? IM : 1];
+    for (int h = 0; h < SUB; ++h) {
+      const int fo = so + foff[h];
+      v4i bf[JN], af[IM], nf[DL ? IM : 1];
 #pragma unroll
-        for (int j = 0; j < JN; ++j) bf[j] = *reinterpret_cast<const v4i*>(fragB + j * 2048 + fo);
+      for (int j = 0; j < JN; ++j) bf[j] = *reinterpret_cast<const v4i*>(fragB + j * (32 * SK) + fo);
 #pragma unroll
-        for (int i = 0; i < IM; ++i) af[i] = *reinterpret_cast<const v4i*>(fragA + i * 2048 + fo);
-        if (DL) {
+      for (int i = 0; i < IM; ++i) af[i] = *reinterpret_cast<const v4i*>(fragA + i * (32 * SK) + fo);
+      if (DL) {
 #pragma unroll
-          for (int i = 0; i < IM; ++i) nf[i] = *reinterpret_cast<const v4i*>(fragN + i * 2048 + fo);
+        for (int i = 0; i < IM; ++i) nf[i] = *reinterpret_cast<const v4i*>(fragN + i * (32 * SK) + fo);
+      }
+#pragma unroll
+      for (int i = 0; i < IM; ++i) {
+#pragma unroll
+        for (int j = 0; j < JN; ++j) {
+          accp[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], accp[i][j], 0, 0, 0);
+          if (DL)
+            accn[DUAL ? i : 0][DUAL ? j : 0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
+                nf[DL ? i : 0], bf[j], accn[DUAL ? i : 0][DUAL ? j : 0], 0, 0, 0);
         }
+        if (MORE) {
 #pragma unroll
-        for (int i = 0; i < IM; ++i)
-#pragma unroll
-          for (int j = 0; j < JN; ++j) {
-            accp[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], accp[i][j], 0, 0, 0);
-            if (DL)
-              accn[DUAL ? i : 0][DUAL ? j : 0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
-                  nf[DL ? i : 0], bf[j], accn[DUAL ? i : 0][DUAL ? j : 0], 0, 0, 0);
-          }
+          for (int e = 0; e < LT; ++e)
+            if (e * NSLOT / LT == h * IM + i) issue_slot(e);
+        }
       }
     }
   };
 
-  auto flush = [&](const int ks, const bool dl, const bool last) {
-    // ---- K-segment boundary (or end of K): flush the exact int32 sums --------------------------------
+  // ---- main loop over one K-segment: DL = this segment runs both polarity paths ----------------------
+  // Two plain loops (first the stages that still prefetch, then the last NSTAGE-1 stages of K that do not)
+  // rather than one loop with a branch: the accumulators then flow through a single MFMA block per loop and
+  // stay in accumulation registers.
+  auto run_segment = [&](auto dl_tag, const int nstages) {
+    constexpr bool DL = decltype(dl_tag)::value;
+    // stages of this segment that still prefetch (n_pf) and those at the very end of K that do not
+    const int pf_left = nkt - (NSTAGE - 1) - kt;
+    const int n_pf = pf_left < 0 ? 0 : (pf_left < nstages ? pf_left : nstages);
+    const int kt_pf_end = kt + n_pf;
+    const int kt_end = kt + nstages;
+#pragma unroll 1
+    for (; kt < kt_pf_end; ++kt) {
+      retired += GA * (DL ? 2 : 1) + GB;         // loads of stage kt are the oldest outstanding ones
+      wait_vmcnt<(NSTAGE - 2) * (2 * GA + GB), (NSTAGE - 2) * (GA + GB)>(issued - retired);
+      __syncthreads();                           // stage kt visible to all waves; stage kt-1 free for reuse
+      issue_begin();                             // stage kt + NSTAGE - 1 goes into the buffer just freed
+      compute_stage(dl_tag, std::true_type{});
+      issue_end();
+    }
+#pragma unroll 1
+    for (; kt < kt_end; ++kt) {
+      retired += GA * (DL ? 2 : 1) + GB;
+      wait_vmcnt<(NSTAGE - 2) * (2 * GA + GB), (NSTAGE - 2) * (GA + GB)>(issued - retired);
+      __syncthreads();
+      compute_stage(dl_tag, std::false_type{});
+    }
+  };
+
+  // Keep the accumulators in accumulation registers at the end of the K loop.  Without this the register
+  // allocator starts moving them to ordinary VGPRs inside the last stage (the epilogue's VALU code cannot
+  // read AGPRs), which exhausts the VGPR file inside the loop and spills the loop's own address registers.
+  auto pin_accumulators = [&]() {
+#pragma unroll
+    for (int i = 0; i < IM; ++i)
+#pragma unroll
+      for (int j = 0; j < JN; ++j) {
+        asm volatile("" : "+a"(accp[i][j]));
+        if (DUAL) asm volatile("" : "+a"(accn[DUAL ? i : 0][DUAL ? j : 0]));
+      }
+  };
+
+  // ---- K-segment boundary: scale the exact int32 sums into the fp32 running sum, clear them ----------
+  // SHARE: the layer has exactly one dual K-segment and it is visited first.  Two int32 sets are live only
+  // during that segment; at its end the X^_- set's registers are re-used for the fp32 running sum (its bits
+  // are kept in accn), and every later segment accumulates in accp alone.  `first` = first visited segment.
+  auto flush_mid = [&](const int ks, const bool dl, const bool first) {
     int ncol = n0 + wn * C::TN + (lane & 31);
     int mrow = m0 + wm * C::TM + 4 * (lane >> 5);
-    asm volatile("" : "+v"(ncol), "+v"(mrow));   // keep the store addressing out of the K loop's live ranges
+    asm volatile("" : "+v"(ncol), "+v"(mrow));   // keep this addressing out of the K loop's live ranges
     if (mode == OUT_DEBUG_ACC) {
       const int o0 = (ks * a.M + mrow) * a.N + ncol;   // S*M*N < 2^31 is checked by the host
 #pragma unroll
@@ -222,65 +325,164 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void seglinear_mfma_kernel(const G
             if (mrow + dm < a.M && ncol + j * 32 < a.N) {
               const int o = o0 + dm * a.N + j * 32;
               a.acc_pos[o] = accp[i][j][v];
-              a.acc_neg[o] = (DUAL && dl) ? accn[DUAL ? i : 0][DUAL ? j : 0][v] : 0;
+              a.acc_neg[o] = (DUAL && dl && (!SHARE || first)) ? accn[DUAL ? i : 0][DUAL ? j : 0][v] : 0;
             }
           }
         }
-    } else {
+    } else if (SHARE) {
       const float sp = tb.s_pos[ks], sn = tb.s_neg[ks];
-      const int o0 = mrow * a.N + ncol;
 #pragma unroll
       for (int j = 0; j < JN; ++j) {
         const int n = ncol + j * 32;
-        const bool nok = n < a.N;
-        const float cw = nok ? seg_scale_of(tb, ks, n) * a.wscale[(size_t)ks * a.N + n] : 0.0f;
-        const float cpos = cw * sp, cneg = dl ? cw * sn : 0.0f;
-        const float bs = (last && nok && a.bias) ? a.bias[n] : 0.0f;
+        const float cw = (n < a.N) ? seg_scale_of(tb, ks, n) * a.wscale[(size_t)ks * a.N + n] : 0.0f;
+        const float cpos = cw * sp, cneg = cw * sn;
 #pragma unroll
-        for (int i = 0; i < IM; ++i) {
+        for (int i = 0; i < IM; ++i)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int old = accn[DUAL ? i : 0][DUAL ? j : 0][v];
+            const float prev = first ? cneg * (float)old : __int_as_float(old);
+            accn[DUAL ? i : 0][DUAL ? j : 0][v] = __float_as_int(prev + cpos * (float)accp[i][j][v]);
+          }
+      }
+    } else if (FSUM) {
+      const float sp = tb.s_pos[ks], sn = tb.s_neg[ks];
+#pragma unroll
+      for (int j = 0; j < JN; ++j) {
+        const int n = ncol + j * 32;
+        const float cw = (n < a.N) ? seg_scale_of(tb, ks, n) * a.wscale[(size_t)ks * a.N + n] : 0.0f;
+        const float cpos = cw * sp, cneg = dl ? cw * sn : 0.0f;
+#pragma unroll
+        for (int i = 0; i < IM; ++i)
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
             float t = cpos * (float)accp[i][j][v];
             if (DUAL) t += cneg * (float)accn[DUAL ? i : 0][DUAL ? j : 0][v];
-            if (MULTI) t += fsum[MULTI ? i : 0][MULTI ? j : 0][v];
-            if (!last) {
-              if (MULTI) fsum[MULTI ? i : 0][MULTI ? j : 0][v] = t;
-            } else {
-              t += bs;
-              const int dm = i * 32 + 8 * (v >> 2) + (v & 3);
-              if (mrow + dm < a.M && nok) {
-                const int o = o0 + dm * a.N + j * 32;
-                if (mode == OUT_F32) reinterpret_cast<float*>(a.y)[o] = t;
-                else reinterpret_cast<uint16_t*>(a.y)[o] = f32_to_bf16(t);
-              }
-            }
+            fsum[FSUM ? i : 0][FSUM ? j : 0][v] += t;
           }
-        }
       }
     }
-    if (!last) {
 #pragma unroll
-      for (int i = 0; i < IM; ++i)
+    for (int i = 0; i < IM; ++i)
+#pragma unroll
+      for (int j = 0; j < JN; ++j) {
+        accp[i][j] = (v16i)(0);
+        if (DUAL && (!SHARE || mode == OUT_DEBUG_ACC)) accn[i][j] = (v16i)(0);
+      }
+  };
+
+  // ---- last K-segment: dequantize, add bias, store ----------------------------------------------------
+  auto flush_last = [&](const int ks, const bool dl, const bool first) {
+    if (mode == OUT_DEBUG_ACC) { flush_mid(ks, dl, first); return; }
+    int ncol = n0 + wn * C::TN + (lane & 31);
+    int mrow = m0 + wm * C::TM + 4 * (lane >> 5);
+    asm volatile("" : "+v"(ncol), "+v"(mrow));
+    const float sp = tb.s_pos[ks], sn = tb.s_neg[ks];
+    float cpos[JN], cneg[JN], bs[JN];
+#pragma unroll
+    for (int j = 0; j < JN; ++j) {
+      const int n = ncol + j * 32;
+      const bool nok = n < a.N;
+      const float cw = nok ? seg_scale_of(tb, ks, n) * a.wscale[(size_t)ks * a.N + n] : 0.0f;
+      cpos[j] = cw * sp;
+      cneg[j] = dl ? cw * sn : 0.0f;
+      bs[j] = (nok && a.bias) ? a.bias[n] : 0.0f;
+    }
+    // 1) dequantize in place: the accumulator registers now hold the fp32 result bits
+#pragma unroll
+    for (int j = 0; j < JN; ++j) {
+#pragma unroll
+      for (int i = 0; i < IM; ++i) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          float t = cpos[j] * (float)accp[i][j][v];
+          if (SHARE) t += __int_as_float(accn[DUAL ? i : 0][DUAL ? j : 0][v]);   // running sum (never the first segment)
+          else if (DUAL) t += cneg[j] * (float)accn[DUAL ? i : 0][DUAL ? j : 0][v];
+          if (FSUM) t += fsum[FSUM ? i : 0][FSUM ? j : 0][v];
+          t += bs[j];
+          accp[i][j][v] = __float_as_int(t);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    // 2) store
+    const int esz = (mode == OUT_F32) ? 4 : 2;
+    const bool vec = (a.N % (16 / esz)) == 0 && (reinterpret_cast<uintptr_t>(a.y) % 16 == 0);
+    if (vec) {
+      // Stage 32 rows x TN columns at a time through this wave's slice of the (idle) ring, then store
+      // 16 bytes per lane along N.
+      __syncthreads();                                   // every wave is done reading operand stages
+      char* stg = smem + wave * C::EPI;
+      const int rowb = C::TN * esz + 16;                 // padded staging row
+      const int cpl = 16 / esz;                          // columns per 16-byte store
+      const int lpr = C::TN / cpl;                       // lanes that cover one staged row
+      const int rows_per_it = 64 / lpr;
+      char* wbase = stg + (4 * (lane >> 5)) * rowb + (lane & 31) * esz;
+      const char* rbase = stg + (lane / lpr) * rowb + (lane % lpr) * 16;
+      const int mbase = m0 + wm * C::TM + lane / lpr;
+      const int nst = n0 + wn * C::TN + (lane % lpr) * cpl;
+#pragma unroll
+      for (int i = 0; i < IM; ++i) {
 #pragma unroll
         for (int j = 0; j < JN; ++j) {
-          accp[i][j] = (v16i)(0);
-          if (DUAL) accn[i][j] = (v16i)(0);
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            char* p = wbase + (8 * (v >> 2) + (v & 3)) * rowb + (j * 32) * esz;
+            const float t = __int_as_float(accp[i][j][v]);
+            if (mode == OUT_F32) *reinterpret_cast<float*>(p) = t;
+            else *reinterpret_cast<uint16_t*>(p) = f32_to_bf16(t);
+          }
+          __builtin_amdgcn_sched_barrier(0);
         }
+        // read back row-contiguous and store
+#pragma unroll 2
+        for (int r0 = 0; r0 < 32; r0 += rows_per_it) {
+          const v4i val = *reinterpret_cast<const v4i*>(rbase + r0 * rowb);
+          const int m = mbase + i * 32 + r0;
+          if (m < a.M && nst < a.N)
+            *reinterpret_cast<v4i*>(reinterpret_cast<char*>(a.y) + ((size_t)m * a.N + nst) * esz) = val;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    } else {
+      const int o0 = mrow * a.N + ncol;
+#pragma unroll
+      for (int j = 0; j < JN; ++j) {
+        const bool nok = ncol + j * 32 < a.N;
+#pragma unroll
+        for (int i = 0; i < IM; ++i) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const float t = __int_as_float(accp[i][j][v]);
+            const int dm = i * 32 + 8 * (v >> 2) + (v & 3);
+            if (mrow + dm < a.M && nok) {
+              const int o = o0 + dm * a.N + j * 32;
+              if (mode == OUT_F32) reinterpret_cast<float*>(a.y)[o] = t;
+              else reinterpret_cast<uint16_t*>(a.y)[o] = f32_to_bf16(t);
+            }
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
     }
   };
 
   if constexpr (!MULTI) {
     // one K-segment: the host selects the DUAL instantiation exactly when that segment is dual
     run_segment(std::integral_constant<bool, DUAL>{}, nkt);
-    flush(0, DUAL, true);
+    pin_accumulators();
+    flush_last(0, DUAL, true);
   } else {
 #pragma unroll 1
-    for (int ks = 0; ks < tb.S; ++ks) {
+    for (int pos = 0; pos < tb.S; ++pos) {
+      const int ks = tb.seg_order[pos];
       const bool dl = DUAL && (tb.dual[ks] != 0);
-      const int kt_end = tb.kseg_off[ks + 1] >> 6;
-      if (dl) run_segment(std::integral_constant<bool, DUAL>{}, kt_end);
-      else run_segment(std::integral_constant<bool, false>{}, kt_end);
-      flush(ks, dl, ks == tb.S - 1);
+      const int nst = (tb.kseg_off[ks + 1] - tb.kseg_off[ks]) >> KSH;
+      if (dl) run_segment(std::integral_constant<bool, DUAL>{}, nst);
+      else run_segment(std::integral_constant<bool, false>{}, nst);
+      pin_accumulators();
+      if (pos == tb.S - 1) flush_last(ks, dl, pos == 0);
+      else flush_mid(ks, dl, pos == 0);
     }
   }
 }

@@ -16,6 +16,10 @@ constexpr float kQmax = 127.0f;
 
 // Segment tables travel by value in the kernel-argument block: no device allocation, stream-ordered,
 // safe under graph capture.  Indexing them with wave-uniform indices keeps them in scalar registers.
+// Every table is made of 4-byte elements: with byte-sized tables next to int tables the compiler
+// shares the byte-granular base "kernarg + index" between both and then issues scalar dword loads
+// from a base that is not 4-byte aligned, which the scalar memory unit aligns down: the load returns
+// the entry of a neighbouring index.
 struct ActTable {                      // for the activation quantize pass
   int S;
   int kseg_off[SQ_MAX_SEGMENTS + 1];
@@ -23,7 +27,7 @@ struct ActTable {                      // for the activation quantize pass
   float s_neg[SQ_MAX_SEGMENTS];
   float inv_pos[SQ_MAX_SEGMENTS];      // 1 / s (NaN = reciprocal not usable, always divide)
   float inv_neg[SQ_MAX_SEGMENTS];
-  unsigned char dual[SQ_MAX_SEGMENTS];
+  int dual[SQ_MAX_SEGMENTS];           // 32-bit on purpose, see the note below
 };
 
 struct GemmTable {                     // for the SegLinear GEMM kernels
@@ -33,7 +37,8 @@ struct GemmTable {                     // for the SegLinear GEMM kernels
   int nseg_off[SQ_MAX_SEGMENTS + 1];
   float s_pos[SQ_MAX_SEGMENTS];
   float s_neg[SQ_MAX_SEGMENTS];
-  unsigned char dual[SQ_MAX_SEGMENTS];
+  int dual[SQ_MAX_SEGMENTS];
+  int seg_order[SQ_MAX_SEGMENTS];      // order in which the MFMA kernel visits the K-segments
   float seg_scale[SQ_MAX_SEG_SCALE];   // [ks][ns], valid when has_seg_scale
 };
 

@@ -142,25 +142,46 @@ def _check_layer(oracle, g, w, path, variant=-1, rows=None, y_dtypes=("f32", "bf
 
 SMALL = [
     dict(M=64, K=256, N=384, kseg=[0, 128, 256], nseg=[0, 128, 256, 384], dual=[1, 1]),
-    dict(M=130, K=192, N=70, kseg=[0, 192], nseg=[0, 70], dual=[1]),
-    dict(M=257, K=320, N=300, kseg=[0, 64, 320], nseg=[0, 100, 300], dual=[0, 1]),
-    dict(M=1, K=64, N=1, kseg=[0, 64], nseg=[0, 1], dual=[0]),
-    dict(M=200, K=512, N=513, kseg=[0, 128, 256, 512], nseg=[0, 513], dual=[1, 0, 1]),
+    dict(M=130, K=384, N=70, kseg=[0, 384], nseg=[0, 70], dual=[1]),
+    dict(M=257, K=640, N=300, kseg=[0, 128, 640], nseg=[0, 100, 300], dual=[0, 1]),
+    dict(M=1, K=128, N=1, kseg=[0, 128], nseg=[0, 1], dual=[0]),
+    dict(M=200, K=512, N=520, kseg=[0, 128, 256, 512], nseg=[0, 520], dual=[1, 0, 1]),
     dict(M=300, K=128, N=40, kseg=[0, 128], nseg=[0, 40], dual=[0]),
+    dict(M=257, K=320, N=300, kseg=[0, 64, 320], nseg=[0, 100, 300], dual=[0, 1]),     # 64-aligned: 64-byte stages
+    dict(M=97, K=192, N=264, kseg=[0, 192], nseg=[0, 264], dual=[1]),                  # 64-aligned
+    dict(M=140, K=768, N=272, kseg=[0, 256, 384, 768], nseg=[0, 272], dual=[0, 1, 0]),   # one dual segment, in the middle
+    dict(M=70, K=512, N=136, kseg=[0, 128, 512], nseg=[0, 136], dual=[1, 0]),           # one dual segment, first
 ]
+
+# what each tile variant can hold: (K bytes per stage, two accumulator sets, fp32 running sum, both,
+# both when exactly one K-segment is dual: its X^_- registers then double as the running sum)
+VARIANT_CAPS = {0: (128, True, True, False, True), 1: (128, True, True, True, True), 2: (128, True, True, True, True),
+                3: (128, True, True, True, True), 4: (128, False, False, False, False), 5: (128, True, True, True, True),
+                6: (64, True, True, True, True)}
 
 
 @pytest.mark.parametrize("case", SMALL)
-@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5])
+@pytest.mark.parametrize("variant", sorted(VARIANT_CAPS))
 def test_seglinear_mfma_small(oracle, case, variant):
     g = _gpu()
     any_dual, multi = any(case["dual"]), len(case["dual"]) > 1
-    if variant == 4 and any_dual:
-        pytest.skip("tile 256x256 holds a single accumulator set")
-    if variant == 0 and any_dual and multi:
-        pytest.skip("tile 128x256 has no room for the fp32 running sum beside two accumulator sets")
+    sk, dual_ok, multi_ok, multi_dual_ok, share_ok = VARIANT_CAPS[variant]
+    kalign = 128 if all(k % 128 == 0 for k in case["kseg"]) else 64
+    share = multi and sum(case["dual"]) == 1
+    supported = sk <= kalign and (dual_ok or not any_dual) and (multi_ok or not multi or any_dual) and \
+        (multi_dual_ok or (share and share_ok) or not (multi and any_dual))
     w = wl.random_layer(case["M"], case["K"], case["N"], case["kseg"], case["nseg"], case["dual"],
                         seed=case["M"] * 7 + variant, x_dtype="bf16", act="gelu", with_seg_scale=True, with_bias=True)
+    if not supported:
+        gl = g.GpuLayer(w)
+        gl.quantize_weight()
+        gl.quantize_act()
+        sq.sq_tuning_set("force_path", 1)
+        sq.sq_tuning_set("gemm_variant", variant)
+        with pytest.raises(sq.SqError) as e:
+            gl.seglinear("f32")
+        assert e.value.status == 2          # SQ_ERR_UNSUPPORTED, nothing launched
+        return
     _check_layer(oracle, g, w, path=1, variant=variant)
 
 
@@ -203,8 +224,12 @@ def test_many_segments(oracle):
     kseg = [64 * i for i in range(25)]
     w = wl.random_layer(150, 1536, 192, kseg, [32 * i for i in range(7)], [i % 2 for i in range(24)], seed=77,
                         x_dtype="bf16", act="silu", with_seg_scale=True)
-    _check_layer(oracle, g, w, path=1, variant=1)
-    _check_layer(oracle, g, w, path=1, variant=5)
+    _check_layer(oracle, g, w, path=1, variant=6)
+    _check_layer(oracle, g, w, path=-1)
+    w2 = wl.random_layer(150, 3072, 192, [128 * i for i in range(25)], [32 * i for i in range(7)],
+                         [i % 2 for i in range(24)], seed=78, x_dtype="bf16", act="silu", with_seg_scale=True)
+    _check_layer(oracle, g, w2, path=1, variant=1)
+    _check_layer(oracle, g, w2, path=1, variant=5)
 
 
 def test_saturated_accumulators(oracle):
