@@ -190,6 +190,13 @@ def main():
     if args.variant >= 0:
         sq.sq_tuning_set("gemm_variant", args.variant)
 
+    # One plain device copy of known size (256 MiB read + 256 MiB written): under rocprofv3 --pmc it gives
+    # the reading of FETCH_SIZE / WRITE_SIZE for a known traffic, which scales the kernels' readings.
+    cal = torch.zeros(64 << 20, dtype=torch.int32, device="cuda:0")
+    cal.add_(1)            # an elementwise kernel: 256 MiB fetched, 256 MiB written
+    torch.cuda.synchronize()
+    del cal
+
     head = measure(args.config, args.steps, args.warmup)
     others = {}
     for name in [n for n in args.others.split(",") if n and n != args.config]:

@@ -23,9 +23,6 @@ static MfmaVariantInfo variant_info(int v) {
     default: return info_of<6>();
   }
 }
-// Relative main-loop efficiency of a tile shape (larger wave tiles re-use LDS fragments more).
-static const float kTileEff[kNumMfmaVariants] = {1.00f, 0.85f, 0.85f, 0.70f, 1.00f, 0.90f, 0.60f};
-
 int mfma_num_variants() { return kNumMfmaVariants; }
 
 // dual: some K-segment runs both polarity paths; multi: more than one K-segment; share: exactly one dual
@@ -66,11 +63,18 @@ bool mfma_supported(const GemmArgs& a, const GemmTable& tb) {
   return true;
 }
 
+// Automatic choice: occupancy of the last round of tiles (fill) times a relative efficiency of the tile
+// shape, measured on MI355X per layer class (single-path / dual / dual with several K-segments).
+static const float kEffSingle[kNumMfmaVariants] = {1.00f, 0.88f, 0.88f, 0.73f, 0.98f, 1.30f, 1.17f};
+static const float kEffDual[kNumMfmaVariants] = {1.00f, 0.90f, 0.93f, 0.82f, 0.00f, 0.82f, 0.83f};
+static const float kEffDualMulti[kNumMfmaVariants] = {0.87f, 1.00f, 1.00f, 0.79f, 0.00f, 0.87f, 0.87f};
+
 int mfma_pick_variant(const GemmArgs& a, const GemmTable& tb, OutMode) {
   bool dual, multi, share;
   layer_flags(tb, dual, multi, share);
   int dev = 0, cus = 256;
   if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+  const float* eff = dual ? (multi ? kEffDualMulti : kEffDual) : kEffSingle;
   int best = -1;
   float best_score = -1.0f;
   for (int v = 0; v < kNumMfmaVariants; ++v) {
@@ -79,7 +83,7 @@ int mfma_pick_variant(const GemmArgs& a, const GemmTable& tb, OutMode) {
     const long tiles = (long)((a.M + i.BM - 1) / i.BM) * ((a.N + i.BN - 1) / i.BN);
     const long rounds = (tiles + cus - 1) / cus;
     const float fill = (float)((double)a.M * a.N / ((double)rounds * cus * i.BM * i.BN));
-    const float score = fill * kTileEff[v];
+    const float score = fill * eff[v];
     if (score > best_score) { best_score = score; best = v; }
   }
   return best;

@@ -1,0 +1,114 @@
+"""Host-side checks that need no GPU: the C-ABI library loads, exports every declared symbol, and its
+argument validation returns the documented status codes before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def sq():
+    import paper_2507_14811_amd as m
+    from paper_2507_14811_amd import binding, build
+
+    if not os.path.exists(binding.LIB_PATH):          # tests load what is built; build only if nothing is
+        build.build_library(verbose=False)
+    m.load_library()
+    return m
+
+
+def test_every_declared_symbol_is_exported(sq):
+    with open(os.path.join(ROOT, "include", "segquant.h")) as f:
+        header = f.read()
+    declared = set(re.findall(r"\b(sq_[a-z_]+)\s*\(", header))
+    assert {"sq_quantize_weight", "sq_quantize_act", "sq_seglinear", "sq_seglinear_debug_acc", "sq_status_string",
+            "sq_version", "sq_tuning_set"} <= declared
+    lib = sq.load_library()
+    for name in declared:
+        assert hasattr(lib, name), f"{name} is declared in segquant.h but not exported"
+    from paper_2507_14811_amd import binding
+
+    assert set(binding.EXPORTS) == declared
+
+
+def test_status_strings_and_version(sq):
+    assert sq.sq_version() >= 100
+    assert [sq.status_string(i) for i in range(4)] == ["SQ_OK", "SQ_ERR_INVALID_ARG", "SQ_ERR_UNSUPPORTED", "SQ_ERR_LAUNCH"]
+
+
+def test_tuning_hook_validation(sq):
+    sq.sq_tuning_set("gemm_variant", -1)
+    sq.sq_tuning_set("force_path", -1)
+    for key, val in (("gemm_variant", 99), ("force_path", 7), ("no_such_key", 0)):
+        with pytest.raises(sq.SqError) as e:
+            sq.sq_tuning_set(key, val)
+        assert e.value.status == 1
+
+
+def _layer(sq, **kw):
+    d = dict(M=8, K=128, N=16, kseg_off=[0, 128], nseg_off=[0, 16], dual=[1], s_pos=[0.5], s_neg=[0.25], seg_scale=None)
+    d.update(kw)
+    return sq.Layer(d["M"], d["K"], d["N"], d["kseg_off"], d["nseg_off"], d["dual"], d["s_pos"], d["s_neg"], d["seg_scale"])
+
+
+FAKE = C.c_void_p(0x1000)      # never dereferenced: every case below is rejected on the host
+
+
+def _act(sq, layer, x=FAKE, dt=1, xp=FAKE, xn=FAKE):
+    return sq.load_library().sq_quantize_act(C.byref(layer.c), x, dt, xp, xn, None)
+
+
+def _gemm(sq, layer, xp=FAKE, xn=FAKE, wq=FAKE, ws=FAKE, y=FAKE, dt=0):
+    return sq.load_library().sq_seglinear(C.byref(layer.c), xp, xn, wq, ws, None, y, dt, None)
+
+
+def test_invalid_arguments_are_rejected_on_the_host(sq):
+    INVALID, UNSUPPORTED = 1, 2
+    lib = sq.load_library()
+    ok = _layer(sq)
+    assert _act(sq, ok, x=None) == INVALID
+    assert _act(sq, ok, xp=None) == INVALID
+    assert _act(sq, ok, xn=None) == INVALID                       # dual segment needs xq_neg
+    assert _act(sq, ok, dt=5) == INVALID
+    assert lib.sq_quantize_act(None, FAKE, 1, FAKE, FAKE, None) == INVALID
+    assert _act(sq, _layer(sq, kseg_off=[0, 64])) == INVALID      # off[S] != K
+    assert _act(sq, _layer(sq, kseg_off=[0, 64, 64, 128], dual=[1, 1, 1], s_pos=[1, 1, 1], s_neg=[1, 1, 1])) == INVALID
+    assert _act(sq, _layer(sq, nseg_off=[0, 8, 4, 16])) == INVALID
+    assert _act(sq, _layer(sq, kseg_off=[1, 128])) == INVALID
+    for bad in (0.0, -1.0, float("nan"), float("inf")):
+        assert _act(sq, _layer(sq, s_pos=[bad])) == INVALID
+        assert _act(sq, _layer(sq, s_neg=[bad])) == INVALID
+    assert _act(sq, _layer(sq, M=0)) == INVALID
+    assert _gemm(sq, ok, wq=None) == INVALID
+    assert _gemm(sq, ok, y=None) == INVALID
+    assert _gemm(sq, ok, dt=9) == INVALID
+    assert _gemm(sq, _layer(sq, seg_scale=[[float("nan")]])) == INVALID
+    # legal but outside the documented limits
+    n = 65
+    many = _layer(sq, K=64 * n, kseg_off=[64 * i for i in range(n + 1)], dual=[0] * n, s_pos=[1.0] * n, s_neg=[1.0] * n)
+    assert _act(sq, many) == UNSUPPORTED
+    long_seg = _layer(sq, K=133144, kseg_off=[0, 133144])
+    assert _gemm(sq, long_seg) == UNSUPPORTED                     # 127*127*K_ks would not fit int32
+    big = _layer(sq, M=70000, K=40000, N=16, kseg_off=[0, 40000])
+    assert _act(sq, big) == UNSUPPORTED                           # M*K >= 2^31
+    s, t = 32, 32
+    blocks = _layer(sq, K=64 * s, N=t, kseg_off=[64 * i for i in range(s + 1)], nseg_off=list(range(t + 1)), dual=[0] * s,
+                    s_pos=[1.0] * s, s_neg=[1.0] * s, seg_scale=np.ones((s, t), np.float32))
+    assert _gemm(sq, blocks) == UNSUPPORTED                       # S*T > SQ_MAX_SEG_SCALE
+    w = _layer(sq)
+    assert lib.sq_quantize_weight(C.byref(w.c), None, 0, FAKE, FAKE, None) == INVALID
+    assert lib.sq_quantize_weight(C.byref(w.c), FAKE, 3, FAKE, FAKE, None) == INVALID
+    assert lib.sq_seglinear_debug_acc(C.byref(w.c), FAKE, FAKE, FAKE, None, FAKE, None) == INVALID
+
+
+def test_missing_library_fails_loudly(monkeypatch, sq):
+    from paper_2507_14811_amd import binding
+
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/libsegquant.so")
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        binding.load_library()
