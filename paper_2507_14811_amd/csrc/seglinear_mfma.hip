@@ -5,12 +5,12 @@
 namespace sq {
 
 #define SQ_DECL(V) extern template hipError_t launch_mfma_variant<V>(const GemmArgs&, const GemmTable&, int, bool, bool, bool, hipStream_t);
-SQ_DECL(0) SQ_DECL(1) SQ_DECL(2) SQ_DECL(3) SQ_DECL(4) SQ_DECL(5) SQ_DECL(6)
+SQ_DECL(0) SQ_DECL(1) SQ_DECL(2) SQ_DECL(3) SQ_DECL(4) SQ_DECL(5) SQ_DECL(6) SQ_DECL(7)
 #undef SQ_DECL
 
 template <int V> static MfmaVariantInfo info_of() {
   using P = MfmaVariant<V>;
-  return {P::BM, P::BN, P::SK, P::DUAL_OK, P::MULTI_OK, P::MULTI_DUAL_OK, P::SHARE_OK};
+  return {P::BM, P::BN, P::SK, P::MINB, P::DUAL_OK, P::MULTI_OK, P::MULTI_DUAL_OK, P::SHARE_OK};
 }
 static MfmaVariantInfo variant_info(int v) {
   switch (v) {
@@ -20,7 +20,8 @@ static MfmaVariantInfo variant_info(int v) {
     case 3: return info_of<3>();
     case 4: return info_of<4>();
     case 5: return info_of<5>();
-    default: return info_of<6>();
+    case 6: return info_of<6>();
+    default: return info_of<7>();
   }
 }
 int mfma_num_variants() { return kNumMfmaVariants; }
@@ -65,9 +66,9 @@ bool mfma_supported(const GemmArgs& a, const GemmTable& tb) {
 
 // Automatic choice: occupancy of the last round of tiles (fill) times a relative efficiency of the tile
 // shape, measured on MI355X per layer class (single-path / dual / dual with several K-segments).
-static const float kEffSingle[kNumMfmaVariants] = {1.00f, 0.88f, 0.88f, 0.73f, 0.98f, 1.30f, 1.17f};
-static const float kEffDual[kNumMfmaVariants] = {1.00f, 0.90f, 0.93f, 0.82f, 0.00f, 0.82f, 0.83f};
-static const float kEffDualMulti[kNumMfmaVariants] = {0.87f, 1.00f, 1.00f, 0.79f, 0.00f, 0.87f, 0.87f};
+static const float kEffSingle[kNumMfmaVariants] = {1.00f, 0.88f, 0.88f, 0.73f, 0.98f, 1.30f, 1.17f, 0.0f};
+static const float kEffDual[kNumMfmaVariants] = {1.00f, 0.90f, 0.93f, 0.82f, 0.00f, 0.82f, 0.83f, 0.0f};
+static const float kEffDualMulti[kNumMfmaVariants] = {0.87f, 1.00f, 1.00f, 0.79f, 0.00f, 0.87f, 0.87f, 0.0f};
 
 int mfma_pick_variant(const GemmArgs& a, const GemmTable& tb, OutMode) {
   bool dual, multi, share;
@@ -81,8 +82,9 @@ int mfma_pick_variant(const GemmArgs& a, const GemmTable& tb, OutMode) {
     if (!variant_ok(v, dual, multi, share, k_alignment(a, tb))) continue;
     const MfmaVariantInfo i = variant_info(v);
     const long tiles = (long)((a.M + i.BM - 1) / i.BM) * ((a.N + i.BN - 1) / i.BN);
-    const long rounds = (tiles + cus - 1) / cus;
-    const float fill = (float)((double)a.M * a.N / ((double)rounds * cus * i.BM * i.BN));
+    const long slots = (long)cus * i.MINB;
+    const long rounds = (tiles + slots - 1) / slots;
+    const float fill = (float)((double)a.M * a.N / ((double)rounds * slots * i.BM * i.BN));
     const float score = fill * eff[v];
     if (score > best_score) { best_score = score; best = v; }
   }
@@ -113,7 +115,8 @@ hipError_t launch_seglinear_mfma(GemmArgs a, const GemmTable& tb_in, OutMode mod
     case 3: return launch_mfma_variant<3>(a, tb, mode, dual, multi, share, st);
     case 4: return launch_mfma_variant<4>(a, tb, mode, dual, multi, share, st);
     case 5: return launch_mfma_variant<5>(a, tb, mode, dual, multi, share, st);
-    default: return launch_mfma_variant<6>(a, tb, mode, dual, multi, share, st);
+    case 6: return launch_mfma_variant<6>(a, tb, mode, dual, multi, share, st);
+    default: return launch_mfma_variant<7>(a, tb, mode, dual, multi, share, st);
   }
 }
 

@@ -99,8 +99,8 @@ template <int SK> __device__ __forceinline__ int row_swizzle(int row) {
   return SK == 128 ? ((row >> 1) & 7) : ((row >> 2) & 3);
 }
 
-template <int BM, int BN, int WM, int WN, int NSTAGE, int SK, bool DUAL, bool MULTI, bool SHARE>
-__global__ __launch_bounds__(WM * WN * 64, 1) void seglinear_mfma_kernel(const GemmArgs a, const GemmTable tb,
+template <int BM, int BN, int WM, int WN, int NSTAGE, int SK, int MINB, bool DUAL, bool MULTI, bool SHARE>
+__global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(const GemmArgs a, const GemmTable tb,
                                                                          const int mode) {
   using C = MfmaCfg<BM, BN, WM, WN, NSTAGE, SK, DUAL, MULTI, SHARE>;
   constexpr bool FSUM = MULTI && !SHARE;      // a separate fp32 running-sum register set
@@ -274,6 +274,15 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void seglinear_mfma_kernel(const G
     const int n_pf = pf_left < 0 ? 0 : (pf_left < nstages ? pf_left : nstages);
     const int kt_pf_end = kt + n_pf;
     const int kt_end = kt + nstages;
+    // Start fresh live ranges for the per-lane addresses here: if the register allocator has to spill them
+    // around the (register-hungry) flush code, the reload then happens once in front of the loop.  A reload
+    // inside the loop would come with compiler-inserted vmcnt waits that drain the direct-load pipeline.
+#pragma unroll
+    for (int g = 0; g < GA; ++g) asm volatile("" : "+v"(voffA[g]));
+#pragma unroll
+    for (int g = 0; g < GB; ++g) asm volatile("" : "+v"(voffB[g]));
+#pragma unroll
+    for (int h = 0; h < SUB; ++h) asm volatile("" : "+v"(foff[h]));
 #pragma unroll 1
     for (; kt < kt_pf_end; ++kt) {
       retired += GA * (DL ? 2 : 1) + GB;         // loads of stage kt are the oldest outstanding ones
@@ -344,6 +353,7 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void seglinear_mfma_kernel(const G
             const float prev = first ? cneg * (float)old : __int_as_float(old);
             accn[DUAL ? i : 0][DUAL ? j : 0][v] = __float_as_int(prev + cpos * (float)accp[i][j][v]);
           }
+        __builtin_amdgcn_sched_barrier(0);
       }
     } else if (FSUM) {
       const float sp = tb.s_pos[ks], sn = tb.s_neg[ks];
@@ -360,6 +370,7 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void seglinear_mfma_kernel(const G
             if (DUAL) t += cneg * (float)accn[DUAL ? i : 0][DUAL ? j : 0][v];
             fsum[FSUM ? i : 0][FSUM ? j : 0][v] += t;
           }
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
 #pragma unroll
@@ -472,6 +483,22 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void seglinear_mfma_kernel(const G
     run_segment(std::integral_constant<bool, DUAL>{}, nkt);
     pin_accumulators();
     flush_last(0, DUAL, true);
+  } else if constexpr (SHARE) {
+    // the dual K-segment first (both accumulator sets), then the single-scale ones (one set + running sum)
+    {
+      const int ks = tb.seg_order[0];
+      run_segment(std::true_type{}, (tb.kseg_off[ks + 1] - tb.kseg_off[ks]) >> KSH);
+      pin_accumulators();
+      flush_mid(ks, true, true);
+    }
+#pragma unroll 1
+    for (int pos = 1; pos < tb.S; ++pos) {
+      const int ks = tb.seg_order[pos];
+      run_segment(std::false_type{}, (tb.kseg_off[ks + 1] - tb.kseg_off[ks]) >> KSH);
+      pin_accumulators();
+      if (pos == tb.S - 1) flush_last(ks, false, false);
+      else flush_mid(ks, false, false);
+    }
   } else {
 #pragma unroll 1
     for (int pos = 0; pos < tb.S; ++pos) {
