@@ -48,10 +48,9 @@ def _setup(name):
     wt = torch.from_numpy(w.w).to(dev)
     wq = torch.empty((w.N, w.K), dtype=torch.int8, device=dev)
     wscale = torch.empty((w.S, w.N), dtype=torch.float32, device=dev)
-    xp = torch.empty((w.M, w.K), dtype=torch.int8, device=dev)
-    xn = torch.empty((w.M, w.K), dtype=torch.int8, device=dev)
+    xq = torch.empty((w.M, w.K), dtype=torch.int8, device=dev)
     y = torch.empty((w.M, w.N), dtype=torch.bfloat16, device=dev)
-    return dict(w=w, layer=layer, x=x, wt=wt, wq=wq, wscale=wscale, xp=xp, xn=xn, y=y)
+    return dict(w=w, layer=layer, x=x, wt=wt, wq=wq, wscale=wscale, xq=xq, y=y)
 
 
 def _time_events(fn, iters):
@@ -81,10 +80,10 @@ def measure(name, steps, warmup, rotate_quant=True):
     t_wq = float(np.median(_time_events(lambda: sq.sq_quantize_weight(layer, s["wt"], s["wq"], s["wscale"]), 5)))
 
     def quant():
-        sq.sq_quantize_act(layer, s["x"], s["xp"], s["xn"])
+        sq.sq_quantize_act(layer, s["x"], s["xq"])
 
     def gemm():
-        sq.sq_seglinear(layer, s["xp"], s["xn"], s["wq"], s["wscale"], None, s["y"])
+        sq.sq_seglinear(layer, s["xq"], s["wq"], s["wscale"], None, s["y"])
 
     for _ in range(warmup):
         quant()
@@ -112,13 +111,12 @@ def measure(name, steps, warmup, rotate_quant=True):
     if rotate_quant and qbytes < 300e6:
         nrot = int(min(64, max(2, np.ceil(600e6 / qbytes))))
     xs = [s["x"]] + [s["x"].clone() for _ in range(nrot - 1)]
-    xps = [s["xp"]] + [torch.empty_like(s["xp"]) for _ in range(nrot - 1)]
-    xns = [s["xn"]] + [torch.empty_like(s["xn"]) for _ in range(nrot - 1)]
+    xqs = [s["xq"]] + [torch.empty_like(s["xq"]) for _ in range(nrot - 1)]
     reps = max(2, int(np.ceil(40 / nrot)))
 
     def quant_rot():
         for i in range(nrot):
-            sq.sq_quantize_act(layer, xs[i], xps[i], xns[i])
+            sq.sq_quantize_act(layer, xs[i], xqs[i])
 
     quant_rot()
     torch.cuda.synchronize()

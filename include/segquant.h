@@ -22,6 +22,12 @@
  *              contiguous: the transpose of the paper's k x n matrix); outputs Y[M][N].
  *   Streams    `stream` is a hipStream_t passed as void* (NULL = the default stream).  Kernels are
  *              enqueued; no call synchronises with the host.
+ *   Codes      X^_+ = Quant(max(X, 0)) >= 0 and X^_- = Quant(min(X, 0)) <= 0 are never both non-zero
+ *              at one element, so the library stores and consumes them as ONE int8 matrix
+ *              X^ = X^_+ + X^_- ("polarity-merged codes"): in a DualScale K-segment
+ *              X^_+ = max(X^, 0) and X^_- = min(X^, 0); in a single-scale K-segment X^ is the
+ *              symmetric code.  The kernels separate the two operands in registers, so the second
+ *              polarity path costs no memory traffic.
  *   Numbers    round() is round-half-to-even, the code range is [-127, 127], x / s is an IEEE
  *              fp32 division; all steps ("scales") are fp32.
  *   Errors     every call returns an sq_status and never throws or aborts.  Host-side checks:
@@ -81,39 +87,39 @@ sq_status sq_quantize_weight(const sq_layer* layer, const void* w, sq_dtype w_dt
 
 /*
  * Q_dual(X) with the polarity split fused in (Sec. 4.3.2).  For a dual K-segment:
- *   x <  0 : xq_neg = max(round(x / s_neg[ks]), -127), xq_pos = 0
- *   x >= 0 : xq_pos = min(round(x / s_pos[ks]),  127), xq_neg = 0
- * For a non-dual K-segment (Sec. 3, z = 0): xq_pos = clip(round(x / s_pos[ks]), -127, 127) and the
- * xq_neg columns of that segment are neither written here nor read by sq_seglinear.
+ *   x <  0 : X^_- = max(round(x / s_neg[ks]), -127), X^_+ = 0     -> xq = X^_-  (<= 0)
+ *   x >= 0 : X^_+ = min(round(x / s_pos[ks]),  127), X^_- = 0     -> xq = X^_+  (>= 0)
+ * For a non-dual K-segment (Sec. 3, z = 0): xq = clip(round(x / s_pos[ks]), -127, 127).
  *   x       dev, [M][K] of x_dt                           in
- *   xq_pos  dev, int8 [M][K]                              out
- *   xq_neg  dev, int8 [M][K]                              out (may be NULL if no segment is dual)
+ *   xq      dev, int8 [M][K], polarity-merged codes       out
  */
-sq_status sq_quantize_act(const sq_layer* layer, const void* x, sq_dtype x_dt, int8_t* xq_pos,
-                          int8_t* xq_neg, void* stream);
+sq_status sq_quantize_act(const sq_layer* layer, const void* x, sq_dtype x_dt, int8_t* xq,
+                          void* stream);
 
 /*
  * Dual-path integer GEMM with per-K-segment accumulators and the fused dequant epilogue
  * (Sec. 4.2.2 items 1-2 combined with the last display of Sec. 4.3.2):
- *   acc_+[ks][m][n] = sum_{k in ks} xq_pos[m][k] wq[n][k]            (int32, exact)
- *   acc_-[ks][m][n] = sum_{k in ks} xq_neg[m][k] wq[n][k]            (dual segments only)
+ *   acc_+[ks][m][n] = sum_{k in ks} X^_+[m][k] wq[n][k]              (int32, exact)
+ *   acc_-[ks][m][n] = sum_{k in ks} X^_-[m][k] wq[n][k]              (dual segments only)
+ * with X^_+ = max(xq, 0), X^_- = min(xq, 0) in dual segments and X^_+ = xq elsewhere,
  *   y[m][n] = sum_ks seg_scale[ks][ns(n)] wscale[ks][n] ( s_pos[ks] acc_+ + s_neg[ks] acc_- ) + bias[n]
- * evaluated in fp32 and stored as fp32 or bf16 (round-half-to-even).  The weight tile is read once
- * and feeds both accumulator sets.  M <= 64 selects the weight-streaming (bandwidth-bound) kernel.
- *   xq_pos, xq_neg dev int8 [M][K];  wq dev int8 [N][K];  wscale dev fp32 [S][N];
+ * evaluated in fp32 and stored as fp32 or bf16 (round-half-to-even).  Activation and weight tiles
+ * are read once and feed both accumulator sets.  M <= 64 selects the weight-streaming
+ * (bandwidth-bound) kernel.
+ *   xq dev int8 [M][K] (from sq_quantize_act);  wq dev int8 [N][K];  wscale dev fp32 [S][N];
  *   bias dev fp32 [N] or NULL;  y dev [M][N] of y_dt.
  */
-sq_status sq_seglinear(const sq_layer* layer, const int8_t* xq_pos, const int8_t* xq_neg,
-                       const int8_t* wq, const float* wscale, const float* bias, void* y,
-                       sq_dtype y_dt, void* stream);
+sq_status sq_seglinear(const sq_layer* layer, const int8_t* xq, const int8_t* wq,
+                       const float* wscale, const float* bias, void* y, sq_dtype y_dt,
+                       void* stream);
 
 /*
  * Parity instrument: runs the same main loop as sq_seglinear (same kernel selection) and stores the
  * raw int32 accumulators instead of the dequantized output.
  *   acc_pos, acc_neg  dev int32 [S][M][N];  acc_neg[ks] of a non-dual segment is written as 0.
  */
-sq_status sq_seglinear_debug_acc(const sq_layer* layer, const int8_t* xq_pos, const int8_t* xq_neg,
-                                 const int8_t* wq, int32_t* acc_pos, int32_t* acc_neg, void* stream);
+sq_status sq_seglinear_debug_acc(const sq_layer* layer, const int8_t* xq, const int8_t* wq,
+                                 int32_t* acc_pos, int32_t* acc_neg, void* stream);
 
 /* Human-readable name of a status code (static storage). */
 const char* sq_status_string(sq_status s);

@@ -58,9 +58,9 @@ def load_library() -> C.CDLL:
     vp, i32 = C.c_void_p, C.c_int
     lp = C.POINTER(sq_layer)
     lib.sq_quantize_weight.argtypes = [lp, vp, i32, vp, vp, vp]
-    lib.sq_quantize_act.argtypes = [lp, vp, i32, vp, vp, vp]
-    lib.sq_seglinear.argtypes = [lp, vp, vp, vp, vp, vp, vp, i32, vp]
-    lib.sq_seglinear_debug_acc.argtypes = [lp, vp, vp, vp, vp, vp, vp]
+    lib.sq_quantize_act.argtypes = [lp, vp, i32, vp, vp]
+    lib.sq_seglinear.argtypes = [lp, vp, vp, vp, vp, vp, i32, vp]
+    lib.sq_seglinear_debug_acc.argtypes = [lp, vp, vp, vp, vp, vp]
     for f in (lib.sq_quantize_weight, lib.sq_quantize_act, lib.sq_seglinear, lib.sq_seglinear_debug_acc):
         f.restype = i32
     lib.sq_status_string.argtypes = [i32]
@@ -149,20 +149,19 @@ def sq_quantize_weight(layer: Layer, w, wq, wscale, stream=None) -> None:
                                              _stream(stream)), "sq_quantize_weight")
 
 
-def sq_quantize_act(layer: Layer, x, xq_pos, xq_neg, stream=None) -> None:
-    """x [M][K] fp32/bf16 -> xq_pos, xq_neg int8 [M][K]."""
-    _check(load_library().sq_quantize_act(C.byref(layer.c), _dptr(x), _dt(x), _dptr(xq_pos), _dptr(xq_neg),
-                                          _stream(stream)), "sq_quantize_act")
+def sq_quantize_act(layer: Layer, x, xq, stream=None) -> None:
+    """x [M][K] fp32/bf16 -> xq int8 [M][K], polarity-merged codes (X^_+ = max(xq, 0), X^_- = min(xq, 0))."""
+    _check(load_library().sq_quantize_act(C.byref(layer.c), _dptr(x), _dt(x), _dptr(xq), _stream(stream)),
+           "sq_quantize_act")
 
 
-def sq_seglinear(layer: Layer, xq_pos, xq_neg, wq, wscale, bias, y, stream=None) -> None:
-    """int8 x int8 -> int32 per K-segment, dequantized into y [M][N] fp32/bf16."""
-    _check(load_library().sq_seglinear(C.byref(layer.c), _dptr(xq_pos), _dptr(xq_neg), _dptr(wq), _dptr(wscale),
-                                       _dptr(bias), _dptr(y), _dt(y), _stream(stream)), "sq_seglinear")
+def sq_seglinear(layer: Layer, xq, wq, wscale, bias, y, stream=None) -> None:
+    """int8 x int8 -> int32 per K-segment and polarity, dequantized into y [M][N] fp32/bf16."""
+    _check(load_library().sq_seglinear(C.byref(layer.c), _dptr(xq), _dptr(wq), _dptr(wscale), _dptr(bias),
+                                       _dptr(y), _dt(y), _stream(stream)), "sq_seglinear")
 
 
-def sq_seglinear_debug_acc(layer: Layer, xq_pos, xq_neg, wq, acc_pos, acc_neg, stream=None) -> None:
+def sq_seglinear_debug_acc(layer: Layer, xq, wq, acc_pos, acc_neg, stream=None) -> None:
     """Same main loop, raw int32 accumulators: acc_pos, acc_neg int32 [S][M][N]."""
-    _check(load_library().sq_seglinear_debug_acc(C.byref(layer.c), _dptr(xq_pos), _dptr(xq_neg), _dptr(wq),
-                                                 _dptr(acc_pos), _dptr(acc_neg), _stream(stream)),
-           "sq_seglinear_debug_acc")
+    _check(load_library().sq_seglinear_debug_acc(C.byref(layer.c), _dptr(xq), _dptr(wq), _dptr(acc_pos),
+                                                 _dptr(acc_neg), _stream(stream)), "sq_seglinear_debug_acc")

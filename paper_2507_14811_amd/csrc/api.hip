@@ -72,17 +72,13 @@ float safe_inv(float s) {
   return 1.0f / s;
 }
 
-sq_status run_gemm(const sq_layer* L, const int8_t* xq_pos, const int8_t* xq_neg, const int8_t* wq,
+sq_status run_gemm(const sq_layer* L, const int8_t* xq, const int8_t* wq,
                    const float* wscale, const float* bias, void* y, int32_t* acc_pos, int32_t* acc_neg,
                    sq::OutMode mode, void* stream) {
   sq::GemmTable tb;
   fill_gemm_table(L, tb);
-  bool any_dual = false;
-  for (int s = 0; s < L->S; ++s) any_dual = any_dual || L->dual[s];
-  if (any_dual && xq_neg == nullptr) return SQ_ERR_INVALID_ARG;
   sq::GemmArgs a{};
-  a.xp = xq_pos;
-  a.xn = any_dual ? xq_neg : xq_pos;   // never dereferenced for a non-dual layer; kept non-null
+  a.xq = xq;
   a.wq = wq;
   a.wscale = wscale;
   a.bias = bias;
@@ -132,48 +128,44 @@ sq_status sq_quantize_weight(const sq_layer* layer, const void* w, sq_dtype w_dt
   return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 
-sq_status sq_quantize_act(const sq_layer* layer, const void* x, sq_dtype x_dt, int8_t* xq_pos, int8_t* xq_neg,
-                          void* stream) {
+sq_status sq_quantize_act(const sq_layer* layer, const void* x, sq_dtype x_dt, int8_t* xq, void* stream) {
   sq_status st = check_layer(layer, true, true);
   if (st != SQ_OK) return st;
-  if (x == nullptr || xq_pos == nullptr) return SQ_ERR_INVALID_ARG;
+  if (x == nullptr || xq == nullptr) return SQ_ERR_INVALID_ARG;
   if (x_dt != SQ_F32 && x_dt != SQ_BF16) return SQ_ERR_INVALID_ARG;
   sq::ActTable tb;
   std::memset(&tb, 0, sizeof(tb));
   tb.S = layer->S;
-  bool any_dual = false;
   for (int s = 0; s <= layer->S; ++s) tb.kseg_off[s] = layer->kseg_off[s];
   for (int s = 0; s < layer->S; ++s) {
     tb.dual[s] = layer->dual[s] ? 1 : 0;
-    any_dual = any_dual || layer->dual[s];
     tb.s_pos[s] = layer->s_pos[s];
     tb.inv_pos[s] = safe_inv(layer->s_pos[s]);
     tb.s_neg[s] = layer->dual[s] ? layer->s_neg[s] : 1.0f;
     tb.inv_neg[s] = layer->dual[s] ? safe_inv(layer->s_neg[s]) : 1.0f;
   }
-  if (any_dual && xq_neg == nullptr) return SQ_ERR_INVALID_ARG;
-  hipError_t e = sq::launch_quantize_act(x, x_dt == SQ_BF16, xq_pos, xq_neg, layer->M, layer->K, tb,
+  hipError_t e = sq::launch_quantize_act(x, x_dt == SQ_BF16, xq, layer->M, layer->K, tb,
                                          reinterpret_cast<hipStream_t>(stream));
   return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 
-sq_status sq_seglinear(const sq_layer* layer, const int8_t* xq_pos, const int8_t* xq_neg, const int8_t* wq,
-                       const float* wscale, const float* bias, void* y, sq_dtype y_dt, void* stream) {
+sq_status sq_seglinear(const sq_layer* layer, const int8_t* xq, const int8_t* wq, const float* wscale,
+                       const float* bias, void* y, sq_dtype y_dt, void* stream) {
   sq_status st = check_layer(layer, true, true);
   if (st != SQ_OK) return st;
-  if (xq_pos == nullptr || wq == nullptr || wscale == nullptr || y == nullptr) return SQ_ERR_INVALID_ARG;
+  if (xq == nullptr || wq == nullptr || wscale == nullptr || y == nullptr) return SQ_ERR_INVALID_ARG;
   if (y_dt != SQ_F32 && y_dt != SQ_BF16) return SQ_ERR_INVALID_ARG;
-  return run_gemm(layer, xq_pos, xq_neg, wq, wscale, bias, y, nullptr, nullptr,
+  return run_gemm(layer, xq, wq, wscale, bias, y, nullptr, nullptr,
                   y_dt == SQ_BF16 ? sq::OUT_BF16 : sq::OUT_F32, stream);
 }
 
-sq_status sq_seglinear_debug_acc(const sq_layer* layer, const int8_t* xq_pos, const int8_t* xq_neg,
-                                 const int8_t* wq, int32_t* acc_pos, int32_t* acc_neg, void* stream) {
+sq_status sq_seglinear_debug_acc(const sq_layer* layer, const int8_t* xq, const int8_t* wq, int32_t* acc_pos,
+                                 int32_t* acc_neg, void* stream) {
   sq_status st = check_layer(layer, true, false);
   if (st != SQ_OK) return st;
-  if (xq_pos == nullptr || wq == nullptr || acc_pos == nullptr || acc_neg == nullptr) return SQ_ERR_INVALID_ARG;
+  if (xq == nullptr || wq == nullptr || acc_pos == nullptr || acc_neg == nullptr) return SQ_ERR_INVALID_ARG;
   if ((long long)layer->S * layer->M * layer->N > 0x7FFFFFFFll) return SQ_ERR_UNSUPPORTED;
-  return run_gemm(layer, xq_pos, xq_neg, wq, nullptr, nullptr, nullptr, acc_pos, acc_neg, sq::OUT_DEBUG_ACC, stream);
+  return run_gemm(layer, xq, wq, nullptr, nullptr, nullptr, acc_pos, acc_neg, sq::OUT_DEBUG_ACC, stream);
 }
 
 const char* sq_status_string(sq_status s) {
@@ -186,7 +178,7 @@ const char* sq_status_string(sq_status s) {
   }
 }
 
-int sq_version(void) { return 100; }
+int sq_version(void) { return 200; }
 
 sq_status sq_tuning_set(const char* key, int value) {
   if (key == nullptr) return SQ_ERR_INVALID_ARG;

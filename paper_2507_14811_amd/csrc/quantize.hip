@@ -6,32 +6,35 @@
 namespace sq {
 
 // ------------------------------------------------------------------------------------------------
-// Activation quantize, fast path: K and every K-segment boundary are multiples of 8, so a thread owns
-// 8 consecutive elements of one row and one segment: 16 B (bf16) or 32 B (fp32) in, 8 B out per
-// polarity.  A block streams 4 x 256 such chunks; all loads are issued before any arithmetic.
+// Activation quantize.  Output: one int8 code per element, X^ = X^_+ + X^_- ("polarity-merged"): in a
+// DualScale K-segment the element went through the s_+ branch of Q_dual when x >= 0 (code >= 0) and
+// through the s_- branch when x < 0 (code <= 0), so X^_+ = max(X^, 0) and X^_- = min(X^, 0) are recovered
+// exactly from the sign; in a single-scale segment the code is the symmetric one.
+//
+// Fast path: K and every K-segment boundary are multiples of 16, so a thread owns 16 consecutive elements
+// of one row and one segment: 32 B (bf16) or 64 B (fp32) in, 16 B out.  A block streams 4 x 256 such
+// chunks; all loads are issued before any arithmetic.
 // ------------------------------------------------------------------------------------------------
 constexpr int kActUnroll = 4;
+constexpr int kActChunk = 16;
 
 __device__ __forceinline__ uint32_t pack4(int c0, int c1, int c2, int c3) {
   return (uint32_t)(c0 & 0xFF) | ((uint32_t)(c1 & 0xFF) << 8) | ((uint32_t)(c2 & 0xFF) << 16) | ((uint32_t)c3 << 24);
 }
 
 template <bool BF16, bool ONESEG>
-__global__ __launch_bounds__(256) void quantize_act_fast_kernel(const void* __restrict__ x, int8_t* __restrict__ xq_pos,
-                                                                int8_t* __restrict__ xq_neg, uint32_t nchunks,
-                                                                uint32_t kchunks, uint32_t kmagic, const ActTable tb) {
+__global__ __launch_bounds__(256) void quantize_act_fast_kernel(const void* __restrict__ x, int8_t* __restrict__ xq,
+                                                                uint32_t nchunks, uint32_t kchunks, uint32_t kmagic,
+                                                                const ActTable tb) {
+  constexpr int NL = BF16 ? 2 : 4;                       // 16-byte loads per chunk
   const uint32_t base = blockIdx.x * (256u * kActUnroll) + threadIdx.x;
-  v4i raw[kActUnroll][BF16 ? 1 : 2];
+  v4i raw[kActUnroll][NL];
 #pragma unroll
   for (int j = 0; j < kActUnroll; ++j) {
     const uint32_t c = base + j * 256u;
     if (c < nchunks) {
-      if (BF16) {
-        raw[j][0] = reinterpret_cast<const v4i*>(x)[c];
-      } else {
-        raw[j][0] = reinterpret_cast<const v4i*>(x)[2 * (size_t)c];
-        raw[j][BF16 ? 0 : 1] = reinterpret_cast<const v4i*>(x)[2 * (size_t)c + 1];
-      }
+#pragma unroll
+      for (int l = 0; l < NL; ++l) raw[j][l] = reinterpret_cast<const v4i*>(x)[(size_t)NL * c + l];
     }
   }
 #pragma unroll
@@ -45,51 +48,44 @@ __global__ __launch_bounds__(256) void quantize_act_fast_kernel(const void* __re
       uint32_t q = __umulhi(c, kmagic);
       uint32_t r = c - q * kchunks;
       if (r >= kchunks) r -= kchunks;
-      const int col = (int)(r * 8u);
+      const int col = (int)(r * (uint32_t)kActChunk);
       for (int s = 1; s < tb.S; ++s) {
         if (col >= tb.kseg_off[s]) {
           sp = tb.s_pos[s]; sn = tb.s_neg[s]; ip = tb.inv_pos[s]; in = tb.inv_neg[s]; dual = tb.dual[s] != 0;
         }
       }
     }
-    float v[8];
-    if (BF16) {
+    v4i out;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {                        // four output dwords of four codes
+      float v[4];
+      if (BF16) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          const uint32_t u = (uint32_t)raw[j][BF16 ? g / 2 : 0][(g % 2) * 2 + i];
+          v[2 * i] = __uint_as_float(u << 16);
+          v[2 * i + 1] = __uint_as_float(u & 0xFFFF0000u);
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = __int_as_float(raw[j][BF16 ? 0 : g][i]);
+      }
+      int code[4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const uint32_t u = (uint32_t)raw[j][0][i];
-        v[2 * i] = __uint_as_float(u << 16);
-        v[2 * i + 1] = __uint_as_float(u & 0xFFFF0000u);
+        const bool ng = dual && (v[i] < 0.0f);          // X_- = min(X, 0) takes the s_- branch of Q_dual
+        code[i] = clip_code(round_quotient(v[i], ng ? sn : sp, ng ? in : ip));
       }
-    } else {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) v[i] = __int_as_float(raw[j][BF16 ? 0 : i / 4][i % 4]);
+      out[g] = (int)pack4(code[0], code[1], code[2], code[3]);
     }
-    int cp[8], cn[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const bool ng = dual && (v[i] < 0.0f);          // X_- = min(X, 0) takes the s_- branch of Q_dual
-      const float r = round_quotient(v[i], ng ? sn : sp, ng ? in : ip);
-      const int code = clip_code(r);
-      cp[i] = ng ? 0 : code;
-      cn[i] = ng ? code : 0;
-    }
-    v2i op, on;
-    op[0] = (int)pack4(cp[0], cp[1], cp[2], cp[3]);
-    op[1] = (int)pack4(cp[4], cp[5], cp[6], cp[7]);
-    reinterpret_cast<v2i*>(xq_pos)[c] = op;
-    if (dual) {
-      on[0] = (int)pack4(cn[0], cn[1], cn[2], cn[3]);
-      on[1] = (int)pack4(cn[4], cn[5], cn[6], cn[7]);
-      reinterpret_cast<v2i*>(xq_neg)[c] = on;
-    }
+    reinterpret_cast<v4i*>(xq)[c] = out;
   }
 }
 
 // Any K / segment alignment: one element per thread.
 template <bool BF16>
-__global__ __launch_bounds__(256) void quantize_act_generic_kernel(const void* __restrict__ x, int8_t* __restrict__ xq_pos,
-                                                                   int8_t* __restrict__ xq_neg, int M, int K,
-                                                                   const ActTable tb) {
+__global__ __launch_bounds__(256) void quantize_act_generic_kernel(const void* __restrict__ x, int8_t* __restrict__ xq,
+                                                                   int M, int K, const ActTable tb) {
   const size_t total = (size_t)M * K;
   for (size_t i = blockIdx.x * (size_t)256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
     const int col = (int)(i % (size_t)K);
@@ -102,33 +98,31 @@ __global__ __launch_bounds__(256) void quantize_act_generic_kernel(const void* _
     }
     const float v = BF16 ? bf16_to_f32(reinterpret_cast<const uint16_t*>(x)[i]) : reinterpret_cast<const float*>(x)[i];
     const bool ng = dual && (v < 0.0f);
-    const int code = clip_code(round_quotient(v, ng ? sn : sp, ng ? in : ip));
-    xq_pos[i] = (int8_t)(ng ? 0 : code);
-    if (dual) xq_neg[i] = (int8_t)(ng ? code : 0);
+    xq[i] = (int8_t)clip_code(round_quotient(v, ng ? sn : sp, ng ? in : ip));
   }
 }
 
-hipError_t launch_quantize_act(const void* x, bool x_is_bf16, int8_t* xq_pos, int8_t* xq_neg, int M, int K,
-                               const ActTable& tb, hipStream_t st) {
-  bool aligned = (K % 8 == 0) && (reinterpret_cast<uintptr_t>(x) % 16 == 0) &&
-                 (reinterpret_cast<uintptr_t>(xq_pos) % 8 == 0) && (reinterpret_cast<uintptr_t>(xq_neg) % 8 == 0);
-  for (int s = 0; s <= tb.S; ++s) aligned = aligned && (tb.kseg_off[s] % 8 == 0);
+hipError_t launch_quantize_act(const void* x, bool x_is_bf16, int8_t* xq, int M, int K, const ActTable& tb,
+                               hipStream_t st) {
+  bool aligned = (K % kActChunk == 0) && (reinterpret_cast<uintptr_t>(x) % 16 == 0) &&
+                 (reinterpret_cast<uintptr_t>(xq) % 16 == 0);
+  for (int s = 0; s <= tb.S; ++s) aligned = aligned && (tb.kseg_off[s] % kActChunk == 0);
   if (aligned) {
-    const uint32_t kchunks = (uint32_t)(K / 8);
-    const uint32_t nchunks = (uint32_t)(((size_t)M * K) / 8);
+    const uint32_t kchunks = (uint32_t)(K / kActChunk);
+    const uint32_t nchunks = (uint32_t)(((size_t)M * K) / kActChunk);
     const uint32_t kmagic = (uint32_t)(0x100000000ull / kchunks > 0xFFFFFFFFull ? 0xFFFFFFFFull : 0x100000000ull / kchunks);
     const unsigned blocks = (nchunks + 256u * kActUnroll - 1) / (256u * kActUnroll);
     const bool one = (tb.S == 1);
 #define SQ_LAUNCH_ACT(B, O) \
-  hipLaunchKernelGGL((quantize_act_fast_kernel<B, O>), dim3(blocks), dim3(256), 0, st, x, xq_pos, xq_neg, nchunks, kchunks, kmagic, tb)
+  hipLaunchKernelGGL((quantize_act_fast_kernel<B, O>), dim3(blocks), dim3(256), 0, st, x, xq, nchunks, kchunks, kmagic, tb)
     if (x_is_bf16) { if (one) SQ_LAUNCH_ACT(true, true); else SQ_LAUNCH_ACT(true, false); }
     else           { if (one) SQ_LAUNCH_ACT(false, true); else SQ_LAUNCH_ACT(false, false); }
 #undef SQ_LAUNCH_ACT
   } else {
     const size_t total = (size_t)M * K;
     const unsigned blocks = (unsigned)((total + 255) / 256 > 65536 ? 65536 : (total + 255) / 256);
-    if (x_is_bf16) hipLaunchKernelGGL((quantize_act_generic_kernel<true>), dim3(blocks), dim3(256), 0, st, x, xq_pos, xq_neg, M, K, tb);
-    else           hipLaunchKernelGGL((quantize_act_generic_kernel<false>), dim3(blocks), dim3(256), 0, st, x, xq_pos, xq_neg, M, K, tb);
+    if (x_is_bf16) hipLaunchKernelGGL((quantize_act_generic_kernel<true>), dim3(blocks), dim3(256), 0, st, x, xq, M, K, tb);
+    else           hipLaunchKernelGGL((quantize_act_generic_kernel<false>), dim3(blocks), dim3(256), 0, st, x, xq, M, K, tb);
   }
   return hipGetLastError();
 }

@@ -11,17 +11,16 @@ __global__ __launch_bounds__(256) void seglinear_generic_kernel(const GemmArgs a
   const int n = blockIdx.y * 64 + (threadIdx.x & 63);
   const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (n >= a.N || m >= a.M) return;
-  const int8_t* xp = a.xp + (size_t)m * a.K;
-  const int8_t* xn = a.xn + (size_t)m * a.K;
+  const int8_t* xr = a.xq + (size_t)m * a.K;
   const int8_t* wr = a.wq + (size_t)n * a.K;
   float y = 0.0f;
   for (int ks = 0; ks < tb.S; ++ks) {
     const bool dual = tb.dual[ks] != 0;
     int ap = 0, an = 0;
     for (int k = tb.kseg_off[ks]; k < tb.kseg_off[ks + 1]; ++k) {
-      const int wv = wr[k];
-      ap += (int)xp[k] * wv;
-      if (dual) an += (int)xn[k] * wv;
+      const int wv = wr[k], xv = xr[k];
+      if (dual && xv < 0) an += xv * wv;       // X^_- = min(X^, 0): negative codes belong to the s_- path
+      else ap += xv * wv;
     }
     if (MODE == OUT_DEBUG_ACC) {
       const size_t o = ((size_t)ks * a.M + m) * a.N + n;

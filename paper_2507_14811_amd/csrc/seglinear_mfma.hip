@@ -59,16 +59,15 @@ bool mfma_supported(const GemmArgs& a, const GemmTable& tb) {
   if (a.K % 64 != 0) return false;
   for (int s = 0; s <= tb.S; ++s)
     if (tb.kseg_off[s] % 64 != 0) return false;
-  if ((reinterpret_cast<uintptr_t>(a.xp) | reinterpret_cast<uintptr_t>(a.wq)) % 16 != 0) return false;
-  if (a.xn && reinterpret_cast<uintptr_t>(a.xn) % 16 != 0) return false;
+  if ((reinterpret_cast<uintptr_t>(a.xq) | reinterpret_cast<uintptr_t>(a.wq)) % 16 != 0) return false;
   return true;
 }
 
 // Automatic choice: occupancy of the last round of tiles (fill) times a relative efficiency of the tile
 // shape, measured on MI355X per layer class (single-path / dual / dual with several K-segments).
-static const float kEffSingle[kNumMfmaVariants] = {1.00f, 0.88f, 0.88f, 0.73f, 0.98f, 1.30f, 1.17f, 0.0f};
-static const float kEffDual[kNumMfmaVariants] = {1.00f, 0.90f, 0.93f, 0.82f, 0.00f, 0.82f, 0.83f, 0.0f};
-static const float kEffDualMulti[kNumMfmaVariants] = {0.87f, 1.00f, 1.00f, 0.79f, 0.00f, 0.87f, 0.87f, 0.0f};
+static const float kEffSingle[kNumMfmaVariants] = {1.00f, 0.88f, 0.86f, 0.70f, 0.86f, 1.25f, 1.10f, 0.0f};
+static const float kEffDual[kNumMfmaVariants] = {1.00f, 0.84f, 0.86f, 0.77f, 0.00f, 0.78f, 0.88f, 0.0f};
+static const float kEffDualMulti[kNumMfmaVariants] = {0.91f, 0.92f, 0.95f, 0.80f, 0.00f, 1.00f, 0.94f, 0.0f};
 
 int mfma_pick_variant(const GemmArgs& a, const GemmTable& tb, OutMode) {
   bool dual, multi, share;

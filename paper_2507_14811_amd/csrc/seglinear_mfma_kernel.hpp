@@ -4,6 +4,10 @@
 //   polarity products against the same quantized weight; Sec. 4.2.2 item 2: one product per K-segment)
 //   y = sum_ks c_+[ks][n] acc_+[ks] + c_-[ks][n] acc_-[ks] (+ bias)                  (dequant epilogue)
 //
+// X^_+ >= 0 and X^_- <= 0 have disjoint supports (Sec. 4.3.2: X_+ = max(X, 0), X_- = min(X, 0)), so both
+// travel as one int8 matrix X^ = X^_+ + X^_- and are separated again in registers, byte-wise by sign, just
+// before the MFMAs: X^_+ = max(X^, 0), X^_- = min(X^, 0).  The dual path therefore costs no operand bytes.
+//
 // Design (what is specific to CDNA4):
 //   * A workgroup owns a BM x BN output tile; its waves form a WM x WN grid, each wave a TM x TN
 //     sub-tile built from 32x32x32 int8 MFMAs.  X rows are the MFMA "A" operand (C rows), W rows the
@@ -13,8 +17,8 @@
 //     registers, and a ring of NSTAGE stages of SK bytes of K each.  SK = 128 makes every row of a
 //     stage one full 128-byte cache line (the default); SK = 64 serves layers whose K-segment
 //     boundaries are only 64-aligned.
-//   * One LDS stage holds [X^_+ rows][X^_- rows][W^ rows], SK bytes per row; the W^ fragments read from
-//     it feed both accumulator sets, so W^ is fetched and read once for the two polarity paths.
+//   * One LDS stage holds [X^ rows][W^ rows], SK bytes per row; the X^ and W^ fragments read from it feed
+//     both accumulator sets, so each operand is fetched and read once for the two polarity paths.
 //   * Inside a row the 16-byte chunks are XOR-swizzled with row bits chosen so that the 16 lanes the
 //     LDS serves per cycle (256 B/clk) fall on distinct bank groups for the MFMA fragment read pattern
 //     (lane -> row lane%32): chunk ^= (row >> 1) & 7 for 128-byte rows, (row >> 2) & 3 for 64-byte rows.
@@ -23,7 +27,7 @@
 //     operands use the same one, which they do.
 //   * int32 accumulators are exact; at a K-segment boundary they are scaled into an fp32 running sum
 //     (only instantiated when the layer has more than one K-segment) and cleared.  A non-dual segment
-//     neither loads X^_- nor issues its MFMAs.
+//     issues only the MFMAs of one set.
 //   * The epilogue stages each 32-row block of the wave's result through (now idle) LDS so that global
 //     stores are 16 bytes per lane along N (full cache lines) instead of 2-byte scatters.
 //   * Workgroup ids are remapped so that each XCD (ids are dealt round-robin to the 8 XCDs) works on a
@@ -74,17 +78,17 @@ struct MfmaCfg {
   static constexpr int THREADS = NW * 64;
   static constexpr int TM = BM / WM, TN = BN / WN;
   static constexpr int IM = TM / 32, JN = TN / 32;
-  static constexpr int AROWS = BM * (DUAL ? 2 : 1);
+  static constexpr int AROWS = BM;
   static constexpr int STAGE = (AROWS + BN) * SK;
   static constexpr int RPL = 1024 / SK;            // rows covered by one direct-load instruction
-  static constexpr int GA = BM / RPL / NW;         // load instructions per wave and stage, per polarity
+  static constexpr int GA = BM / RPL / NW;         // load instructions per wave and stage
   static constexpr int GB = BN / RPL / NW;
   static constexpr int SUB = SK / 32;              // 32-byte MFMA k-steps per stage
   static constexpr int CPR = SK / 16;              // 16-byte chunks per row
   static constexpr int EPI_ROW = TN * 4 + 16;      // staging row of the epilogue (fp32 worst case, padded)
   static constexpr int EPI = 32 * EPI_ROW;         // per wave
   static constexpr int LDS_BYTES = NSTAGE * STAGE;
-  static constexpr int LT = 2 * GA + GB;           // direct-load slots of one stage: X^_+ groups, X^_- groups, W^ groups
+  static constexpr int LT = GA + GB;               // direct-load slots of one stage: X^ groups, W^ groups
   static constexpr int NSLOT = SUB * IM;           // points inside a stage's MFMA stream where loads are interleaved
   static_assert(SK == 64 || SK == 128, "stage depth");
   static_assert(!SHARE || (DUAL && MULTI), "register sharing is a mode of dual multi-segment layers");
@@ -92,8 +96,17 @@ struct MfmaCfg {
   static_assert(BM % (RPL * NW) == 0 && BN % (RPL * NW) == 0, "load groups must divide evenly over the waves");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS ring exceeds 160 KB");
   static_assert(NW * EPI <= NSTAGE * STAGE, "epilogue staging must fit in the ring");
-  static_assert((NSTAGE - 1) * (2 * GA + GB) < 64, "vmcnt is a 6-bit counter");
+  static_assert(NSTAGE * (GA + GB) < 64, "vmcnt is a 6-bit counter");
 };
+
+// Polarity split of four packed int8 codes: pos keeps the bytes >= 0, neg the bytes < 0, the others become 0.
+//   t = sign bits; w = 0x7F in every negative byte (no borrow crosses a byte); neg = (x & w) | t; pos = x ^ neg
+__device__ __forceinline__ void split_polarity(const int x, int& pos, int& neg) {
+  const int t = x & (int)0x80808080;
+  const int w = t - (int)((unsigned)t >> 7);
+  neg = (x & w) | t;
+  pos = x ^ neg;
+}
 
 template <int SK> __device__ __forceinline__ int row_swizzle(int row) {
   return SK == 128 ? ((row >> 1) & 7) : ((row >> 2) & 3);
@@ -148,7 +161,6 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
   }
   const uint32_t lds0 = (uint32_t)(uintptr_t)SQ_LDS(smem);
   const uint32_t ldsA = lds0 + (uint32_t)(wave * GA) * 1024u;
-  const uint32_t ldsN = ldsA + (uint32_t)BM * SK;
   const uint32_t ldsB = lds0 + (uint32_t)C::AROWS * SK + (uint32_t)(wave * GB) * 1024u;
 
   // ---- per-lane fragment read offsets: row = lane%32, chunk = 2h + lane/32, swizzled ---------------
@@ -157,7 +169,6 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
 #pragma unroll
   for (int h = 0; h < SUB; ++h) foff[h] = frow * SK + (((2 * h + fhi) ^ fsw) << 4);
   const char* fragA = smem + (wm * C::TM) * SK;
-  const char* fragN = fragA + BM * SK;
   const char* fragB = smem + C::AROWS * SK + (wn * C::TN) * SK;
 
   v16i accp[IM][JN];
@@ -176,41 +187,33 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
 
   const int nkt = a.K >> KSH;
   // ---- direct loads of one stage, issued slot by slot ------------------------------------------------
-  // A stage's loads are a list of LT slots (X^_+ groups, X^_- groups, W^ groups).  The pipeline fill issues
-  // whole stages; in steady state the slots of the next stage are spread over the current stage's MFMA
-  // stream, so that a wave never sits in a burst of load issues while its MFMA pipe is idle.
-  // K-segments are visited in the order tb.seg_order (identity unless SHARE); stages are numbered in visit order.
+  // A stage's loads are a list of LT slots (X^ groups, then W^ groups), cut into SUB groups of slots: one
+  // group per 32-byte k-step, so that a wave never sits in a burst of load issues while its MFMA pipe idles.
+  // K-segments are visited in the order tb.seg_order (identity unless SHARE); stages are numbered in visit
+  // order; ikt is the next stage to issue.
   int issued = 0, ikt = 0;
   int ipos = 0, iks = tb.seg_order[0];
   int ik = tb.kseg_off[iks] >> KSH, ik_end = tb.kseg_off[iks + 1] >> KSH;
-  const int8_t* ipA = a.xp;    // operand base pointers of the stage being issued
-  const int8_t* ipN = a.xn;
+  const int8_t* ipA = a.xq;    // operand base pointers of the stage being issued
   const int8_t* ipB = a.wq;
-  bool idl = false;
   uint32_t iso = 0;
-  auto issue_begin = [&]() {
+  auto issue_begin = [&]() __attribute__((always_inline)) {
     const int k0 = ik << KSH;
-    idl = DUAL && (tb.dual[iks] != 0);
     iso = (uint32_t)(ikt % NSTAGE) * (uint32_t)STAGE;
-    ipA = a.xp + k0;
-    ipN = a.xn + k0;
+    ipA = a.xq + k0;
     ipB = a.wq + k0;
   };
-  auto issue_slot = [&](const int e) {          // e is a compile-time constant after unrolling
-    if (e < GA) {
-      glds16(ipA, voffA[e < GA ? e : 0], ldsA + iso + (uint32_t)e * 1024u);
-      ++issued;
-    } else if (e < 2 * GA) {
-      if (idl) {
-        glds16(ipN, voffA[(e - GA) < GA ? (e >= GA ? e - GA : 0) : 0], ldsN + iso + (uint32_t)(e - GA) * 1024u);
-        ++issued;
-      }
-    } else {
-      glds16(ipB, voffB[(e - 2 * GA) < GB ? (e >= 2 * GA ? e - 2 * GA : 0) : 0], ldsB + iso + (uint32_t)(e - 2 * GA) * 1024u);
-      ++issued;
-    }
+  auto issue_slot = [&](const int e) __attribute__((always_inline)) {          // e is a compile-time constant after unrolling
+    if (e < GA) glds16(ipA, voffA[e < GA ? e : 0], ldsA + iso + (uint32_t)e * 1024u);
+    else glds16(ipB, voffB[e >= GA ? e - GA : 0], ldsB + iso + (uint32_t)(e - GA) * 1024u);
+    ++issued;
   };
-  auto issue_end = [&]() {
+  auto issue_group = [&](const int g) __attribute__((always_inline)) {         // g is a compile-time constant after unrolling
+#pragma unroll
+    for (int e = 0; e < LT; ++e)
+      if (e * SUB / LT == g) issue_slot(e);
+  };
+  auto issue_end = [&]() __attribute__((always_inline)) {
     ++ikt;
     if (++ik == ik_end && ipos + 1 < tb.S) {
       iks = tb.seg_order[++ipos];
@@ -218,61 +221,129 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
       ik_end = tb.kseg_off[iks + 1] >> KSH;
     }
   };
+  // pipeline fill: every buffer of the ring
 #pragma unroll 1
-  for (int s = 0; s < NSTAGE - 1 && s < nkt; ++s) {
+  for (int s = 0; s < NSTAGE && s < nkt; ++s) {
     issue_begin();
 #pragma unroll
     for (int e = 0; e < LT; ++e) issue_slot(e);
     issue_end();
   }
+  // all loads of stage s have landed in this wave's view (loads return in order)
+  auto wait_landed = [&](const int s) __attribute__((always_inline)) {
+    wait_vmcnt<(NSTAGE - 2) * LT, (NSTAGE - 1) * LT>(issued - (s + 1) * LT);
+  };
 
-  // ---- main loop over one K-segment: DL = this segment runs both polarity paths ----------------------
-  int kt = 0, retired = 0;
-  // One stage of MFMAs; MORE = the next stage's direct loads are interleaved (one share per MFMA row).
-  auto compute_stage = [&](auto dl_tag, auto more_tag) {
+  // ---- fragments: two register sets, the one being multiplied and the one being fetched ----------------
+  v4i bfr[2][JN], afr[2][IM], nfr[2][DUAL ? IM : 1];
+  auto load_frags = [&](const int set, const int fo) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < IM; ++i) afr[set][i] = *reinterpret_cast<const v4i*>(fragA + i * (32 * SK) + fo);
+#pragma unroll
+    for (int j = 0; j < JN; ++j) bfr[set][j] = *reinterpret_cast<const v4i*>(fragB + j * (32 * SK) + fo);
+  };
+  // polarity separation of a fetched X^ fragment set: afr <- X^_+ codes, nfr <- X^_- codes
+  auto split_frags = [&](const int set) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < IM; ++i)
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        int pos, neg;
+        split_polarity(afr[set][i][d], pos, neg);
+        afr[set][i][d] = pos;
+        nfr[set][DUAL ? i : 0][d] = neg;
+      }
+  };
+  auto stage_off = [&](const int s) __attribute__((always_inline)) { return (s % NSTAGE) * STAGE; };
+
+  // One 32-byte k-step: the MFMAs of fragment set `cur`, while (PF) the fragments of the following k-step
+  // are fetched into the other set and separated by polarity, and (GRP >= 0) load group GRP of the stage
+  // being issued goes out.  The instruction order is fixed by hand, one MFMA per slot with full scheduling
+  // barriers between slots:
+  //   * LDS reads are spread over the MFMA stream, X^ fragments first (a burst of reads stalls MFMA issue:
+  //     measured 80 % of the MFMA rate with six reads in front of sixteen MFMAs, 94 % with one read per two);
+  //   * the separation's VALU work (5 instructions per dword) follows once its fragment had time to arrive,
+  //     a dword or two per MFMA, which the matrix pipe (8 issue slots per MFMA) absorbs;
+  //   * the direct loads of the group are spread evenly over the slots.
+  auto kstep = [&](auto dl_tag, auto pf_tag, auto grp_tag, const int cur, const int fo_next) __attribute__((always_inline)) {
     constexpr bool DL = decltype(dl_tag)::value;
-    constexpr bool MORE = decltype(more_tag)::value;
-    const int so = (kt % NSTAGE) * STAGE;
+    constexpr bool PF = decltype(pf_tag)::value;
+    constexpr int GRP = decltype(grp_tag)::value;
+    const int nxt = cur ^ 1;
+    constexpr int NM = IM * JN * (DL ? 2 : 1);               // MFMAs of this k-step
+    constexpr int NR = PF ? IM + JN : 0;                     // LDS reads (16 bytes per lane each)
+    constexpr int RPS = NR > NM ? (NR + NM - 1) / NM : 1;    // LDS reads per slot (1 unless the tile is tiny)
+    constexpr int RSTEP = NM * RPS >= 2 * NR ? 2 : 1;        // MFMA slots between reads
+    constexpr int ND = (PF && DL) ? IM * 4 : 0;              // dwords to separate
+    constexpr int QV_RAW = ((IM - 1) / RPS) * RSTEP + 6;     // first slot with separation work
+    constexpr int QV0 = QV_RAW < NM / 2 ? QV_RAW : NM / 2;
+    constexpr int DPS = ND ? (ND + (NM - QV0) - 1) / (NM - QV0) : 0;   // dwords per slot
+    constexpr int NG = GRP >= 0 ? ((GRP + 1) * LT + SUB - 1) / SUB - (GRP * LT + SUB - 1) / SUB : 0;   // loads of the group
 #pragma unroll
-    for (int h = 0; h < SUB; ++h) {
-      const int fo = so + foff[h];
-      v4i bf[JN], af[IM], nf[DL ? IM : 1];
-#pragma unroll
-      for (int j = 0; j < JN; ++j) bf[j] = *reinterpret_cast<const v4i*>(fragB + j * (32 * SK) + fo);
-#pragma unroll
-      for (int i = 0; i < IM; ++i) af[i] = *reinterpret_cast<const v4i*>(fragA + i * (32 * SK) + fo);
-      if (DL) {
-#pragma unroll
-        for (int i = 0; i < IM; ++i) nf[i] = *reinterpret_cast<const v4i*>(fragN + i * (32 * SK) + fo);
+    for (int q = 0; q < NM; ++q) {
+      {
+        const int idx = DL ? (q >> 1) : q;
+        const int i = idx / JN, j = idx % JN;
+        if (!DL || (q & 1) == 0)
+          accp[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(afr[cur][i], bfr[cur][j], accp[i][j], 0, 0, 0);
+        else
+          accn[DUAL ? i : 0][DUAL ? j : 0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
+              nfr[cur][DUAL ? i : 0], bfr[cur][j], accn[DUAL ? i : 0][DUAL ? j : 0], 0, 0, 0);
       }
+      __builtin_amdgcn_sched_barrier(0);
+      if (PF) {
 #pragma unroll
-      for (int i = 0; i < IM; ++i) {
+        for (int r = 0; r < NR; ++r)                         // read r goes out in slot (r / RPS) * RSTEP
+          if ((r / RPS) * RSTEP == q) {
+            if (r < IM) afr[nxt][r < IM ? r : 0] = *reinterpret_cast<const v4i*>(fragA + (r < IM ? r : 0) * (32 * SK) + fo_next);
+            else bfr[nxt][r >= IM ? r - IM : 0] = *reinterpret_cast<const v4i*>(fragB + (r >= IM ? r - IM : 0) * (32 * SK) + fo_next);
+          }
+      }
+      if (ND && q >= QV0) {
 #pragma unroll
-        for (int j = 0; j < JN; ++j) {
-          accp[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], accp[i][j], 0, 0, 0);
-          if (DL)
-            accn[DUAL ? i : 0][DUAL ? j : 0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
-                nf[DL ? i : 0], bf[j], accn[DUAL ? i : 0][DUAL ? j : 0], 0, 0, 0);
-        }
-        if (MORE) {
-#pragma unroll
-          for (int e = 0; e < LT; ++e)
-            if (e * NSLOT / LT == h * IM + i) issue_slot(e);
+        for (int t = 0; t < DPS; ++t) {
+          const int w = (q - QV0) * DPS + t;                 // dword index: fragment w / 4, element w % 4
+          if (w < ND) {
+            int pos, neg;
+            split_polarity(afr[nxt][w / 4][w % 4], pos, neg);
+            afr[nxt][w / 4][w % 4] = pos;
+            nfr[nxt][DUAL ? w / 4 : 0][w % 4] = neg;
+          }
         }
       }
+      if (GRP >= 0 && NG > 0) {
+        int cnt = 0;                                         // the group's loads, spread evenly over the slots
+#pragma unroll
+        for (int e = 0; e < LT; ++e)
+          if (e * SUB / LT == GRP) {
+            if (cnt * NM / (NG > 0 ? NG : 1) == q) issue_slot(e);
+            ++cnt;
+          }
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
 
   // ---- main loop over one K-segment: DL = this segment runs both polarity paths ----------------------
-  // Two plain loops (first the stages that still prefetch, then the last NSTAGE-1 stages of K that do not)
-  // rather than one loop with a branch: the accumulators then flow through a single MFMA block per loop and
-  // stay in accumulation registers.
-  auto run_segment = [&](auto dl_tag, const int nstages) {
+  // The loop is rotated by one k-step: an iteration starts at the barrier that publishes stage b+1 and frees
+  // the buffer of stage b, runs the last k-step of stage b (fetching the first fragments of stage b+1) and
+  // the first SUB-1 k-steps of stage b+1, and issues the refill of the freed buffer (stage b+NSTAGE) along
+  // the way.  Iterations that still refill and those at the very end of K that do not are separate plain
+  // loops, so that the accumulators flow through one MFMA block per loop and stay in accumulation registers.
+  int kt = 0;
+  auto tail_steps = [&](auto dl_tag, auto more_tag, const int s) __attribute__((always_inline)) {   // k-steps 0 .. SUB-2 of stage s
+    constexpr bool MORE = decltype(more_tag)::value;
+    const int so = stage_off(s);
+#pragma unroll
+    for (int h = 0; h + 1 < SUB; ++h) {
+      if (h == 0) kstep(dl_tag, std::true_type{}, std::integral_constant<int, MORE ? 1 : -1>{}, 0, so + foff[1]);
+      if (h == 1) kstep(dl_tag, std::true_type{}, std::integral_constant<int, MORE ? 2 : -1>{}, 1, so + foff[SUB > 2 ? 2 : 0]);
+      if (h == 2) kstep(dl_tag, std::true_type{}, std::integral_constant<int, MORE ? 3 : -1>{}, 0, so + foff[SUB > 3 ? 3 : 0]);
+    }
+  };
+  auto run_segment = [&](auto dl_tag, const int nstages) __attribute__((always_inline)) {
     constexpr bool DL = decltype(dl_tag)::value;
-    // stages of this segment that still prefetch (n_pf) and those at the very end of K that do not
-    const int pf_left = nkt - (NSTAGE - 1) - kt;
-    const int n_pf = pf_left < 0 ? 0 : (pf_left < nstages ? pf_left : nstages);
-    const int kt_pf_end = kt + n_pf;
+    constexpr int LASTSET = (SUB - 1) & 1;
     const int kt_end = kt + nstages;
     // Start fresh live ranges for the per-lane addresses here: if the register allocator has to spill them
     // around the (register-hungry) flush code, the reload then happens once in front of the loop.  A reload
@@ -283,28 +354,45 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
     for (int g = 0; g < GB; ++g) asm volatile("" : "+v"(voffB[g]));
 #pragma unroll
     for (int h = 0; h < SUB; ++h) asm volatile("" : "+v"(foff[h]));
+    // segment prologue: stage kt is published, the buffer of stage kt-1 is free; first fragments (exposed once)
+    wait_landed(kt);
+    __syncthreads();
+    load_frags(0, stage_off(kt) + foff[0]);
+    if (DL) split_frags(0);
+    if (kt > 0 && ikt < nkt) {
+      issue_begin();
+      issue_group(0);
+      tail_steps(dl_tag, std::true_type{}, kt);
+      issue_end();
+    } else {
+      tail_steps(dl_tag, std::false_type{}, kt);
+    }
+    int b = kt;
+    const int b_more_end = (kt_end - 1) < (nkt - NSTAGE) ? (kt_end - 1) : (nkt - NSTAGE);
 #pragma unroll 1
-    for (; kt < kt_pf_end; ++kt) {
-      retired += GA * (DL ? 2 : 1) + GB;         // loads of stage kt are the oldest outstanding ones
-      wait_vmcnt<(NSTAGE - 2) * (2 * GA + GB), (NSTAGE - 2) * (GA + GB)>(issued - retired);
-      __syncthreads();                           // stage kt visible to all waves; stage kt-1 free for reuse
-      issue_begin();                             // stage kt + NSTAGE - 1 goes into the buffer just freed
-      compute_stage(dl_tag, std::true_type{});
+    for (; b < b_more_end; ++b) {
+      wait_landed(b + 1);
+      __syncthreads();
+      issue_begin();
+      kstep(dl_tag, std::true_type{}, std::integral_constant<int, 0>{}, LASTSET, stage_off(b + 1) + foff[0]);
+      tail_steps(dl_tag, std::true_type{}, b + 1);
       issue_end();
     }
 #pragma unroll 1
-    for (; kt < kt_end; ++kt) {
-      retired += GA * (DL ? 2 : 1) + GB;
-      wait_vmcnt<(NSTAGE - 2) * (2 * GA + GB), (NSTAGE - 2) * (GA + GB)>(issued - retired);
+    for (; b < kt_end - 1; ++b) {
+      wait_landed(b + 1);
       __syncthreads();
-      compute_stage(dl_tag, std::false_type{});
+      kstep(dl_tag, std::true_type{}, std::integral_constant<int, -1>{}, LASTSET, stage_off(b + 1) + foff[0]);
+      tail_steps(dl_tag, std::false_type{}, b + 1);
     }
+    kstep(dl_tag, std::false_type{}, std::integral_constant<int, -1>{}, LASTSET, 0);
+    kt = kt_end;
   };
 
   // Keep the accumulators in accumulation registers at the end of the K loop.  Without this the register
   // allocator starts moving them to ordinary VGPRs inside the last stage (the epilogue's VALU code cannot
   // read AGPRs), which exhausts the VGPR file inside the loop and spills the loop's own address registers.
-  auto pin_accumulators = [&]() {
+  auto pin_accumulators = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < IM; ++i)
 #pragma unroll
@@ -318,7 +406,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
   // SHARE: the layer has exactly one dual K-segment and it is visited first.  Two int32 sets are live only
   // during that segment; at its end the X^_- set's registers are re-used for the fp32 running sum (its bits
   // are kept in accn), and every later segment accumulates in accp alone.  `first` = first visited segment.
-  auto flush_mid = [&](const int ks, const bool dl, const bool first) {
+  auto flush_mid = [&](const int ks, const bool dl, const bool first) __attribute__((always_inline)) {
     int ncol = n0 + wn * C::TN + (lane & 31);
     int mrow = m0 + wm * C::TM + 4 * (lane >> 5);
     asm volatile("" : "+v"(ncol), "+v"(mrow));   // keep this addressing out of the K loop's live ranges
@@ -338,6 +426,9 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
             }
           }
         }
+      // stores share the vector-memory counter with the direct loads but complete out of order with them:
+      // drain everything so that the load accounting of the K loop stays valid
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     } else if (SHARE) {
       const float sp = tb.s_pos[ks], sn = tb.s_neg[ks];
 #pragma unroll
@@ -383,7 +474,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
   };
 
   // ---- last K-segment: dequantize, add bias, store ----------------------------------------------------
-  auto flush_last = [&](const int ks, const bool dl, const bool first) {
+  auto flush_last = [&](const int ks, const bool dl, const bool first) __attribute__((always_inline)) {
     if (mode == OUT_DEBUG_ACC) { flush_mid(ks, dl, first); return; }
     int ncol = n0 + wn * C::TN + (lane & 31);
     int mrow = m0 + wm * C::TM + 4 * (lane >> 5);

@@ -1,7 +1,7 @@
 // Skinny-M (M <= 64) SegLinear + DualScale GEMM: modulation / adaLN-style layers (Sec. 4.2.2 item 1:
 // a linear followed by chunk; Sec. 4.3.2: its input comes from SiLU).  The layer is a single pass over
 // the int8 weight, so the kernel is an HBM stream: W^ is read exactly once and feeds both polarity
-// products; X^_+ / X^_- are tiny and stay L2-resident.
+// products; the (polarity-merged) X^ codes are tiny, stay L2-resident and are separated in registers.
 //
 // Design:
 //   * A workgroup (4 waves) owns NT 16-row tiles of W^ (16*NT output columns) and all M rows.  Inside
@@ -20,7 +20,7 @@ namespace sq {
 template <int MT, int NT, bool DUAL>
 struct SkinnyCfg {
   static constexpr int POL = DUAL ? 2 : 1;
-  static constexpr int SLOT = (NT + POL * MT) * 1024;
+  static constexpr int SLOT = (NT + MT) * 1024;
   static constexpr int RAW_R = (72 * 1024) / (4 * SLOT);
   static constexpr int R = RAW_R > 8 ? 8 : (RAW_R < 2 ? 2 : RAW_R);
   static constexpr int RED = 4 * POL * MT * NT * 1024;
@@ -72,18 +72,13 @@ __global__ __launch_bounds__(256) void seglinear_skinny_kernel(const GemmArgs a,
   seek(cc);
   int issued = 0, retired = 0, inflight = 0, islot = 0, cslot = 0;
   auto issue = [&]() {
-    const bool dl = DUAL && (tb.dual[ic.ks] != 0);
     const int k0 = ic.t << 6;
     const uint32_t so = ring_lds + (uint32_t)islot * (uint32_t)SLOT;
 #pragma unroll
     for (int t = 0; t < NT; ++t) glds16(a.wq + k0, voffW[t], so + t * 1024u);
 #pragma unroll
-    for (int t = 0; t < MT; ++t) glds16(a.xp + k0, voffX[t], so + (NT + t) * 1024u);
-    if (dl) {
-#pragma unroll
-      for (int t = 0; t < MT; ++t) glds16(a.xn + k0, voffX[t], so + (NT + MT + t) * 1024u);
-    }
-    issued += NT + MT * (dl ? 2 : 1);
+    for (int t = 0; t < MT; ++t) glds16(a.xq + k0, voffX[t], so + (NT + t) * 1024u);
+    issued += NT + MT;
     islot = (islot + 1 == R) ? 0 : islot + 1;
     ++inflight;
     ic.t += 4;
@@ -114,17 +109,24 @@ __global__ __launch_bounds__(256) void seglinear_skinny_kernel(const GemmArgs a,
 
 #pragma unroll 1
     while (cc.ks == ks) {
-      retired += NT + MT * (dl ? 2 : 1);
-      wait_vmcnt<(R - 1) * (NT + 2 * MT), (R - 1) * (NT + MT)>(issued - retired);
+      retired += NT + MT;
+      wait_vmcnt<(R - 1) * (NT + MT), (R - 2) * (NT + MT)>(issued - retired);
       const char* sp = ring + cslot * SLOT + foff;
       v4i wf[NT], xf[MT], nf[MT];
 #pragma unroll
       for (int t = 0; t < NT; ++t) wf[t] = *reinterpret_cast<const v4i*>(sp + t * 1024);
 #pragma unroll
       for (int t = 0; t < MT; ++t) xf[t] = *reinterpret_cast<const v4i*>(sp + (NT + t) * 1024);
-      if (dl) {
+      if (dl) {                                              // X^_+ = max(X^, 0), X^_- = min(X^, 0), byte-wise
 #pragma unroll
-        for (int t = 0; t < MT; ++t) nf[t] = *reinterpret_cast<const v4i*>(sp + (NT + MT + t) * 1024);
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+          for (int d = 0; d < 4; ++d) {
+            int pos, neg;
+            split_polarity(xf[t][d], pos, neg);
+            xf[t][d] = pos;
+            nf[t][d] = neg;
+          }
       }
 #pragma unroll
       for (int i = 0; i < NT; ++i)
@@ -200,8 +202,7 @@ bool skinny_supported(const GemmArgs& a, const GemmTable& tb) {
   if (a.M > 64 || a.K % 64 != 0) return false;
   for (int s = 0; s <= tb.S; ++s)
     if (tb.kseg_off[s] % 64 != 0) return false;
-  if ((reinterpret_cast<uintptr_t>(a.xp) | reinterpret_cast<uintptr_t>(a.wq)) % 16 != 0) return false;
-  if (a.xn && reinterpret_cast<uintptr_t>(a.xn) % 16 != 0) return false;
+  if ((reinterpret_cast<uintptr_t>(a.xq) | reinterpret_cast<uintptr_t>(a.wq)) % 16 != 0) return false;
   return true;
 }
 

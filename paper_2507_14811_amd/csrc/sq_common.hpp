@@ -43,8 +43,7 @@ struct GemmTable {                     // for the SegLinear GEMM kernels
 };
 
 struct GemmArgs {
-  const int8_t* xp;        // [M][K]
-  const int8_t* xn;        // [M][K] (unused columns of non-dual segments are never read)
+  const int8_t* xq;        // [M][K] polarity-merged activation codes
   const int8_t* wq;        // [N][K]
   const float* wscale;     // [S][N]
   const float* bias;       // [N] or nullptr

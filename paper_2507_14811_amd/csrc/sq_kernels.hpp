@@ -12,8 +12,8 @@ struct KsegTable {
 enum OutMode { OUT_F32 = 0, OUT_BF16 = 1, OUT_DEBUG_ACC = 2 };
 
 // quantize.hip
-hipError_t launch_quantize_act(const void* x, bool x_is_bf16, int8_t* xq_pos, int8_t* xq_neg, int M, int K,
-                               const ActTable& tb, hipStream_t st);
+hipError_t launch_quantize_act(const void* x, bool x_is_bf16, int8_t* xq, int M, int K, const ActTable& tb,
+                               hipStream_t st);
 hipError_t launch_quantize_weight(const void* w, bool w_is_bf16, int8_t* wq, float* wscale, int N, int K,
                                   const KsegTable& tb, hipStream_t st);
 

@@ -103,15 +103,15 @@ class Workload:
         return f32_to_bf16_bits(self.x)
 
     def quantize_act_bytes(self) -> int:
-        """Algorithmic HBM bytes of the activation quantize pass."""
-        ks = np.diff(self.kseg_off).astype(np.int64)
+        """Algorithmic HBM bytes of the activation quantize pass: the input once, one code byte out
+        (both polarity matrices travel in one int8 array: X^ = X^_+ + X^_-)."""
         in_b = 2 if self.x_dtype == "bf16" else 4
-        return int(self.M * np.sum(ks * (in_b + 1 + self.dual.astype(np.int64))))
+        return int(self.M * self.K * (in_b + 1))
 
     def seglinear_bytes(self, y_dtype: Optional[str] = None) -> int:
-        """Compulsory HBM bytes of the GEMM: x^ once per live polarity, W once, scales, Y once."""
+        """Compulsory HBM bytes of the GEMM: the merged codes X^ once, W^ once, scales, Y once."""
         yb = 2 if (y_dtype or self.y_dtype) == "bf16" else 4
-        return int(self.M * self.keff + self.N * self.K + 4 * self.S * self.N + self.M * self.N * yb)
+        return int(self.M * self.K + self.N * self.K + 4 * self.S * self.N + self.M * self.N * yb)
 
 
 def amax_scales(x: np.ndarray, kseg_off, dual):

@@ -35,8 +35,7 @@ class GpuLayer:
         fill = -77 if poison else 0
         self.wq = torch.full((w.N, w.K), fill, dtype=torch.int8, device=DEV)
         self.wscale = torch.full((w.S, w.N), float("nan"), dtype=torch.float32, device=DEV)
-        self.xq_pos = torch.full((w.M, w.K), fill, dtype=torch.int8, device=DEV)
-        self.xq_neg = torch.full((w.M, w.K), fill, dtype=torch.int8, device=DEV)
+        self.xq = torch.full((w.M, w.K), fill, dtype=torch.int8, device=DEV)
         self.bias = None if w.bias is None else torch.from_numpy(w.bias).to(DEV)
 
     def quantize_weight(self):
@@ -44,8 +43,12 @@ class GpuLayer:
         return self.wq.cpu().numpy(), self.wscale.cpu().numpy()
 
     def quantize_act(self):
-        sq.sq_quantize_act(self.layer, self.x, self.xq_pos, self.xq_neg)
-        return self.xq_pos.cpu().numpy(), self.xq_neg.cpu().numpy()
+        """Runs the activation quantizer; returns the library's polarity-merged codes unpacked into the two
+        matrices of Sec. 4.3.2 (X^_+, X^_-) plus the raw merged array."""
+        sq.sq_quantize_act(self.layer, self.x, self.xq)
+        xq = self.xq.cpu().numpy()
+        xp, xn = split_codes(self.w, xq)
+        return xp, xn, xq
 
     def seglinear(self, y_dtype="f32"):
         w = self.w
@@ -53,7 +56,7 @@ class GpuLayer:
             y = torch.full((w.M, w.N), float("nan"), dtype=torch.bfloat16, device=DEV)
         else:
             y = torch.full((w.M, w.N), float("nan"), dtype=torch.float32, device=DEV)
-        sq.sq_seglinear(self.layer, self.xq_pos, self.xq_neg, self.wq, self.wscale, self.bias, y)
+        sq.sq_seglinear(self.layer, self.xq, self.wq, self.wscale, self.bias, y)
         torch.cuda.synchronize()
         return bf16_tensor_bits(y) if y_dtype == "bf16" else y.cpu().numpy()
 
@@ -61,18 +64,29 @@ class GpuLayer:
         w = self.w
         ap = torch.full((w.S, w.M, w.N), 0x5A5A5A5A, dtype=torch.int32, device=DEV)
         an = torch.full((w.S, w.M, w.N), 0x5A5A5A5A, dtype=torch.int32, device=DEV)
-        sq.sq_seglinear_debug_acc(self.layer, self.xq_pos, self.xq_neg, self.wq, ap, an)
+        sq.sq_seglinear_debug_acc(self.layer, self.xq, self.wq, ap, an)
         torch.cuda.synchronize()
         return ap.cpu().numpy(), an.cpu().numpy()
 
 
 def dual_col_mask(w) -> np.ndarray:
-    """Columns of xq_neg that are defined (dual K-segments); the rest is don't-care."""
+    """Columns that belong to DualScale K-segments."""
     m = np.zeros(w.K, dtype=bool)
     for ks in range(w.S):
         if w.dual[ks]:
             m[w.kseg_off[ks]:w.kseg_off[ks + 1]] = True
     return m
+
+
+def split_codes(w, xq: np.ndarray):
+    """Documented decoding of the merged activation codes: in a dual K-segment X^_+ = max(xq, 0) and
+    X^_- = min(xq, 0); elsewhere X^_+ = xq and X^_- = 0 (index work only, none of the method's arithmetic)."""
+    mask = dual_col_mask(w)
+    xp = xq.copy()
+    xn = np.zeros_like(xq)
+    xp[:, mask] = np.maximum(xq[:, mask], 0)
+    xn[:, mask] = np.minimum(xq[:, mask], 0)
+    return xp, xn
 
 
 def check_bf16_against(y_bits: np.ndarray, ref32: np.ndarray, ref_bits: np.ndarray, tol_abs: float):

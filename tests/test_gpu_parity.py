@@ -79,12 +79,12 @@ def test_quantize_act(oracle, case, scales):
         w.s_pos = (w.s_pos / 50).astype(np.float32)
         w.s_neg = (w.s_neg / 50).astype(np.float32)
     gl = g.GpuLayer(w)
-    xp, xn = gl.quantize_act()
+    xp, xn, xq = gl.quantize_act()
     rp, rn = oracle.quantize_act(w.x, w.kseg_off, w.dual, w.s_pos, w.s_neg)
-    assert np.array_equal(xp, rp)
-    mask = g.dual_col_mask(w)
-    assert np.array_equal(xn[:, mask], rn[:, mask])
-    assert (xn[:, ~mask] == -77).all()                       # non-dual columns are left untouched
+    assert np.array_equal(xp, rp) and np.array_equal(xn, rn)
+    # the merged array is the sum of the two polarity matrices, which never overlap
+    assert not np.logical_and(rp != 0, rn != 0).any()
+    assert np.array_equal(xq.astype(np.int16), rp.astype(np.int16) + rn.astype(np.int16))
 
 
 def test_quantize_act_near_ties(oracle):
@@ -101,7 +101,7 @@ def test_quantize_act_near_ties(oracle):
     w.s_pos = np.array([s], np.float32)
     w.s_neg = np.array([s * np.float32(0.37)], np.float32)
     gl = g.GpuLayer(w)
-    xp, xn = gl.quantize_act()
+    xp, xn, _ = gl.quantize_act()
     rp, rn = oracle.quantize_act(w.x, w.kseg_off, w.dual, w.s_pos, w.s_neg)
     assert np.array_equal(xp, rp) and np.array_equal(xn, rn)
 
@@ -112,11 +112,10 @@ def test_quantize_act_near_ties(oracle):
 def _check_layer(oracle, g, w, path, variant=-1, rows=None, y_dtypes=("f32", "bf16")):
     gl = g.GpuLayer(w)
     wq, ws = gl.quantize_weight()
-    xp, xn = gl.quantize_act()
-    mask = g.dual_col_mask(w)
+    xp, xn, _ = gl.quantize_act()
     r = oracle.seglinear(w.x, w.w, w.kseg_off, w.nseg_off, w.dual, w.s_pos, w.s_neg, w.seg_scale, w.bias, rows)
     assert np.array_equal(wq, r.wq) and np.array_equal(ws.view(np.uint32), r.wscale.view(np.uint32))
-    assert np.array_equal(xp, r.xq_pos) and np.array_equal(xn[:, mask], r.xq_neg[:, mask])
+    assert np.array_equal(xp, r.xq_pos) and np.array_equal(xn, r.xq_neg)
     sq.sq_tuning_set("force_path", path)
     sq.sq_tuning_set("gemm_variant", variant)
     sel = slice(None) if rows is None else np.asarray(rows)

@@ -58,12 +58,12 @@ def _layer(sq, **kw):
 FAKE = C.c_void_p(0x1000)      # never dereferenced: every case below is rejected on the host
 
 
-def _act(sq, layer, x=FAKE, dt=1, xp=FAKE, xn=FAKE):
-    return sq.load_library().sq_quantize_act(C.byref(layer.c), x, dt, xp, xn, None)
+def _act(sq, layer, x=FAKE, dt=1, xq=FAKE):
+    return sq.load_library().sq_quantize_act(C.byref(layer.c), x, dt, xq, None)
 
 
-def _gemm(sq, layer, xp=FAKE, xn=FAKE, wq=FAKE, ws=FAKE, y=FAKE, dt=0):
-    return sq.load_library().sq_seglinear(C.byref(layer.c), xp, xn, wq, ws, None, y, dt, None)
+def _gemm(sq, layer, xq=FAKE, wq=FAKE, ws=FAKE, y=FAKE, dt=0):
+    return sq.load_library().sq_seglinear(C.byref(layer.c), xq, wq, ws, None, y, dt, None)
 
 
 def test_invalid_arguments_are_rejected_on_the_host(sq):
@@ -71,10 +71,9 @@ def test_invalid_arguments_are_rejected_on_the_host(sq):
     lib = sq.load_library()
     ok = _layer(sq)
     assert _act(sq, ok, x=None) == INVALID
-    assert _act(sq, ok, xp=None) == INVALID
-    assert _act(sq, ok, xn=None) == INVALID                       # dual segment needs xq_neg
+    assert _act(sq, ok, xq=None) == INVALID
     assert _act(sq, ok, dt=5) == INVALID
-    assert lib.sq_quantize_act(None, FAKE, 1, FAKE, FAKE, None) == INVALID
+    assert lib.sq_quantize_act(None, FAKE, 1, FAKE, None) == INVALID
     assert _act(sq, _layer(sq, kseg_off=[0, 64])) == INVALID      # off[S] != K
     assert _act(sq, _layer(sq, kseg_off=[0, 64, 64, 128], dual=[1, 1, 1], s_pos=[1, 1, 1], s_neg=[1, 1, 1])) == INVALID
     assert _act(sq, _layer(sq, nseg_off=[0, 8, 4, 16])) == INVALID

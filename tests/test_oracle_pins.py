@@ -336,4 +336,4 @@ def test_workload_recipes():
     assert c3.x_dtype == "bf16" and np.array_equal(wl.bf16_bits_to_f32(c3.x_bf16_bits()), c3.x)
     stds = [c3.w[j * 1152:(j + 1) * 1152].std() for j in range(6)]
     assert np.allclose(stds, c3.extra["sigma"], rtol=0.02)
-    assert c3.seglinear_bytes() == 16 * 2304 + 6912 * 1152 + 4 * 6912 + 16 * 6912 * 2
+    assert c3.seglinear_bytes() == 16 * 1152 + 6912 * 1152 + 4 * 6912 + 16 * 6912 * 2   # merged codes: X^ once
