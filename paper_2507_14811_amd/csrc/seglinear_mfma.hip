@@ -1,29 +1,24 @@
 // Variant table and selection heuristic of the large-M MFMA kernel; the kernels themselves are
 // instantiated one variant per translation unit (seglinear_mfma_inst.hip).
+#include <utility>
+
 #include "seglinear_mfma_variants.hpp"
 
 namespace sq {
 
-#define SQ_DECL(V) extern template hipError_t launch_mfma_variant<V>(const GemmArgs&, const GemmTable&, int, bool, bool, bool, hipStream_t);
-SQ_DECL(0) SQ_DECL(1) SQ_DECL(2) SQ_DECL(3) SQ_DECL(4) SQ_DECL(5) SQ_DECL(6) SQ_DECL(7)
-#undef SQ_DECL
-
-template <int V> static MfmaVariantInfo info_of() {
+// Per-variant launchers (defined in the per-variant translation units) and properties, as tables.
+using LaunchFn = hipError_t (*)(const GemmArgs&, const GemmTable&, int, bool, bool, bool, hipStream_t);
+template <int V> static constexpr MfmaVariantInfo info_of() {
   using P = MfmaVariant<V>;
   return {P::BM, P::BN, P::SK, P::MINB, P::DUAL_OK, P::MULTI_OK, P::MULTI_DUAL_OK, P::SHARE_OK};
 }
-static MfmaVariantInfo variant_info(int v) {
-  switch (v) {
-    case 0: return info_of<0>();
-    case 1: return info_of<1>();
-    case 2: return info_of<2>();
-    case 3: return info_of<3>();
-    case 4: return info_of<4>();
-    case 5: return info_of<5>();
-    case 6: return info_of<6>();
-    default: return info_of<7>();
-  }
-}
+template <int... V> struct VariantTables {
+  static constexpr LaunchFn launch[sizeof...(V)] = {&launch_mfma_variant<V>...};
+  static constexpr MfmaVariantInfo info[sizeof...(V)] = {info_of<V>()...};
+};
+template <int... V> static constexpr VariantTables<V...> tables_of(std::integer_sequence<int, V...>) { return {}; }
+using Tables = decltype(tables_of(std::make_integer_sequence<int, kNumMfmaVariants>{}));
+static MfmaVariantInfo variant_info(int v) { return Tables::info[v]; }
 int mfma_num_variants() { return kNumMfmaVariants; }
 
 // dual: some K-segment runs both polarity paths; multi: more than one K-segment; share: exactly one dual
@@ -65,9 +60,9 @@ bool mfma_supported(const GemmArgs& a, const GemmTable& tb) {
 
 // Automatic choice: occupancy of the last round of tiles (fill) times a relative efficiency of the tile
 // shape, measured on MI355X per layer class (single-path / dual / dual with several K-segments).
-static const float kEffSingle[kNumMfmaVariants] = {1.00f, 0.88f, 0.86f, 0.70f, 0.86f, 1.25f, 1.10f, 0.0f};
-static const float kEffDual[kNumMfmaVariants] = {1.00f, 0.84f, 0.86f, 0.77f, 0.00f, 0.78f, 0.88f, 0.0f};
-static const float kEffDualMulti[kNumMfmaVariants] = {0.91f, 0.92f, 0.95f, 0.80f, 0.00f, 1.00f, 0.94f, 0.0f};
+static const float kEffSingle[kNumMfmaVariants] = {1.00f, 0.88f, 0.86f, 0.70f, 0.86f, 1.25f, 1.10f};
+static const float kEffDual[kNumMfmaVariants] = {1.00f, 0.81f, 0.83f, 0.74f, 0.00f, 0.72f, 0.85f};
+static const float kEffDualMulti[kNumMfmaVariants] = {1.00f, 0.86f, 0.89f, 0.75f, 0.00f, 0.93f, 0.88f};
 
 int mfma_pick_variant(const GemmArgs& a, const GemmTable& tb, OutMode) {
   bool dual, multi, share;
@@ -107,16 +102,7 @@ hipError_t launch_seglinear_mfma(GemmArgs a, const GemmTable& tb_in, OutMode mod
   a.tiles_m = (a.M + i.BM - 1) / i.BM;
   a.tiles_n = (a.N + i.BN - 1) / i.BN;
   a.group_m = a.tiles_m < 8 ? a.tiles_m : 8;
-  switch (variant) {
-    case 0: return launch_mfma_variant<0>(a, tb, mode, dual, multi, share, st);
-    case 1: return launch_mfma_variant<1>(a, tb, mode, dual, multi, share, st);
-    case 2: return launch_mfma_variant<2>(a, tb, mode, dual, multi, share, st);
-    case 3: return launch_mfma_variant<3>(a, tb, mode, dual, multi, share, st);
-    case 4: return launch_mfma_variant<4>(a, tb, mode, dual, multi, share, st);
-    case 5: return launch_mfma_variant<5>(a, tb, mode, dual, multi, share, st);
-    case 6: return launch_mfma_variant<6>(a, tb, mode, dual, multi, share, st);
-    default: return launch_mfma_variant<7>(a, tb, mode, dual, multi, share, st);
-  }
+  return Tables::launch[variant](a, tb, mode, dual, multi, share, st);
 }
 
 }  // namespace sq

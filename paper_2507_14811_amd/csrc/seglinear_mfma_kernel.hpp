@@ -173,16 +173,14 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
 
   v16i accp[IM][JN];
   v16i accn[DUAL ? IM : 1][DUAL ? JN : 1];
-  float fsum[FSUM ? IM : 1][FSUM ? JN : 1][16];
+  v16f fsum[FSUM ? IM : 1][FSUM ? JN : 1];
 #pragma unroll
   for (int i = 0; i < IM; ++i)
 #pragma unroll
     for (int j = 0; j < JN; ++j) {
       accp[i][j] = (v16i)(0);
       if (DUAL) accn[i][j] = (v16i)(0);
-      if (FSUM)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) fsum[i][j][v] = 0.0f;
+      if (FSUM) fsum[i][j] = (v16f)(0.0f);
     }
 
   const int nkt = a.K >> KSH;
@@ -444,6 +442,10 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
             const float prev = first ? cneg * (float)old : __int_as_float(old);
             accn[DUAL ? i : 0][DUAL ? j : 0][v] = __float_as_int(prev + cpos * (float)accp[i][j][v]);
           }
+        // back into accumulation registers at once: left in ordinary VGPRs, the new sums would be spilled to
+        // scratch memory around the next K loop
+#pragma unroll
+        for (int i = 0; i < IM; ++i) asm volatile("" : "+a"(accn[DUAL ? i : 0][DUAL ? j : 0]));
         __builtin_amdgcn_sched_barrier(0);
       }
     } else if (FSUM) {

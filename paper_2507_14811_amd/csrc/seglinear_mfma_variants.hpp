@@ -15,16 +15,15 @@ template <int V> struct MfmaVariant;
     static constexpr bool DUAL_OK = DUAL_OK_, MULTI_OK = MULTI_OK_, MULTI_DUAL_OK = MULTI_DUAL_OK_,     \
                           SHARE_OK = SHARE_OK_;                                                    \
   };
-SQ_DEF_VARIANT(0, 128, 256, 2, 2, 2, 128, 1, true, true, false, true)   // wave tile 64 x 128, both polarities: 256 accumulator registers
+SQ_DEF_VARIANT(0, 128, 256, 2, 2, 3, 128, 1, true, true, false, true)   // wave tile 64 x 128, both polarities: 256 accumulator registers
 SQ_DEF_VARIANT(1, 128, 128, 2, 2, 3, 128, 1, true, true, true, true)    // wave tile 64 x 64
 SQ_DEF_VARIANT(2, 64, 256, 1, 4, 3, 128, 1, true, true, true, true)     // wave tile 64 x 64, wide-N blocks
 SQ_DEF_VARIANT(3, 64, 128, 2, 2, 4, 128, 1, true, true, true, true)     // wave tile 32 x 64, small problems
 SQ_DEF_VARIANT(4, 256, 256, 2, 2, 2, 128, 1, false, false, false, false)  // wave tile 128 x 128, single-path layers only
 SQ_DEF_VARIANT(5, 128, 256, 2, 4, 2, 128, 1, true, true, true, true)    // 8 waves (2 per SIMD), wave tile 64 x 64
 SQ_DEF_VARIANT(6, 128, 128, 2, 2, 4, 64, 1, true, true, true, true)     // 64-byte stages: K-segment boundaries that are only 64-aligned
-SQ_DEF_VARIANT(7, 128, 128, 2, 2, 3, 64, 2, true, false, false, false)   // two workgroups per CU: one tile's epilogue overlaps the other's K loop
 #undef SQ_DEF_VARIANT
-constexpr int kNumMfmaVariants = 8;
+constexpr int kNumMfmaVariants = 7;
 
 struct MfmaVariantInfo { int BM, BN, SK, MINB; bool dual_ok, multi_ok, multi_dual_ok, share_ok; };
 
