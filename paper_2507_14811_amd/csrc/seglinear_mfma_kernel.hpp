@@ -521,6 +521,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
       const int cpl = 16 / esz;                          // columns per 16-byte store
       const int lpr = C::TN / cpl;                       // lanes that cover one staged row
       const int rows_per_it = 64 / lpr;
+      const int erow = lane / lpr;                       // staged row this lane stores (lanes beyond rows_per_it * lpr idle)
       char* wbase = stg + (4 * (lane >> 5)) * rowb + (lane & 31) * esz;
       const char* rbase = stg + (lane / lpr) * rowb + (lane % lpr) * 16;
       const int mbase = m0 + wm * C::TM + lane / lpr;
@@ -543,7 +544,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
         for (int r0 = 0; r0 < 32; r0 += rows_per_it) {
           const v4i val = *reinterpret_cast<const v4i*>(rbase + r0 * rowb);
           const int m = mbase + i * 32 + r0;
-          if (m < a.M && nst < a.N)
+          if (erow < rows_per_it && r0 + erow < 32 && m < a.M && nst < a.N)
             *reinterpret_cast<v4i*>(reinterpret_cast<char*>(a.y) + ((size_t)m * a.N + nst) * esz) = val;
         }
         __builtin_amdgcn_sched_barrier(0);

@@ -22,8 +22,10 @@ SQ_DEF_VARIANT(3, 64, 128, 2, 2, 4, 128, 1, true, true, true, true)     // wave 
 SQ_DEF_VARIANT(4, 256, 256, 2, 2, 2, 128, 1, false, false, false, false)  // wave tile 128 x 128, single-path layers only
 SQ_DEF_VARIANT(5, 128, 256, 2, 4, 2, 128, 1, true, true, true, true)    // 8 waves (2 per SIMD), wave tile 64 x 64
 SQ_DEF_VARIANT(6, 128, 128, 2, 2, 4, 64, 1, true, true, true, true)     // 64-byte stages: K-segment boundaries that are only 64-aligned
+SQ_DEF_VARIANT(7, 64, 192, 2, 2, 4, 128, 1, true, true, true, true)     // wave tile 32 x 96: N = 192 * odd, mid-size problems
+SQ_DEF_VARIANT(8, 128, 192, 2, 2, 3, 128, 1, true, true, true, true)    // wave tile 64 x 96
 #undef SQ_DEF_VARIANT
-constexpr int kNumMfmaVariants = 7;
+constexpr int kNumMfmaVariants = 9;
 
 struct MfmaVariantInfo { int BM, BN, SK, MINB; bool dual_ok, multi_ok, multi_dual_ok, share_ok; };
 

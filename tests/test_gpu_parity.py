@@ -156,7 +156,7 @@ SMALL = [
 # both when exactly one K-segment is dual: its X^_- registers then double as the running sum)
 VARIANT_CAPS = {0: (128, True, True, False, True), 1: (128, True, True, True, True), 2: (128, True, True, True, True),
                 3: (128, True, True, True, True), 4: (128, False, False, False, False), 5: (128, True, True, True, True),
-                6: (64, True, True, True, True)}
+                6: (64, True, True, True, True), 7: (128, True, True, True, True), 8: (128, True, True, True, True)}
 
 
 @pytest.mark.parametrize("case", SMALL)
