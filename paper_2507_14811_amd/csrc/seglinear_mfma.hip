@@ -60,9 +60,9 @@ bool mfma_supported(const GemmArgs& a, const GemmTable& tb) {
 
 // Automatic choice: occupancy of the last round of tiles (fill) times a relative efficiency of the tile
 // shape, measured on MI355X per layer class (single-path / dual / dual with several K-segments).
-static const float kEffSingle[kNumMfmaVariants] = {1.00f, 0.92f, 0.87f, 0.66f, 1.01f, 1.18f, 1.15f, 0.75f, 0.96f};
-static const float kEffDual[kNumMfmaVariants] = {1.00f, 0.86f, 0.84f, 0.71f, 0.00f, 0.74f, 0.84f, 0.81f, 0.94f};
-static const float kEffDualMulti[kNumMfmaVariants] = {1.00f, 0.91f, 0.88f, 0.75f, 0.00f, 0.91f, 0.81f, 0.89f, 1.00f};
+static const float kEffSingle[kNumMfmaVariants] = {1.00f, 0.88f, 0.84f, 0.64f, 0.98f, 1.08f, 0.91f, 0.71f, 0.90f};
+static const float kEffDual[kNumMfmaVariants] = {1.00f, 0.81f, 0.80f, 0.68f, 0.00f, 0.92f, 0.99f, 0.75f, 0.90f};
+static const float kEffDualMulti[kNumMfmaVariants] = {1.00f, 0.92f, 0.89f, 0.75f, 0.00f, 0.84f, 0.83f, 0.87f, 0.88f};
 
 int mfma_pick_variant(const GemmArgs& a, const GemmTable& tb, OutMode) {
   bool dual, multi, share;

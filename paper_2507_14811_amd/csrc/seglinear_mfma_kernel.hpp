@@ -10,9 +10,9 @@
 //
 // Design (what is specific to CDNA4):
 //   * A workgroup owns a BM x BN output tile; its waves form a WM x WN grid, each wave a TM x TN
-//     sub-tile built from 32x32x32 int8 MFMAs.  X rows are the MFMA "A" operand (C rows), W rows the
-//     "B" operand (C column = lane & 31), so every lane needs the dequant constants of only TN/32
-//     output columns.
+//     sub-tile built from 32x32x32 int8 MFMAs.  W^ rows are the MFMA "A" operand and X^ rows the "B"
+//     operand, so a lane's 16 results of a block are four runs of four consecutive output columns of
+//     one token row.
 //   * Operand tiles are fetched with direct global->LDS loads (global_load_lds_dwordx4): no staging
 //     registers, and a ring of NSTAGE stages of SK bytes of K each.  SK = 128 makes every row of a
 //     stage one full 128-byte cache line (the default); SK = 64 serves layers whose K-segment
@@ -28,8 +28,9 @@
 //   * int32 accumulators are exact; at a K-segment boundary they are scaled into an fp32 running sum
 //     (only instantiated when the layer has more than one K-segment) and cleared.  A non-dual segment
 //     issues only the MFMAs of one set.
-//   * The epilogue stages each 32-row block of the wave's result through (now idle) LDS so that global
-//     stores are 16 bytes per lane along N (full cache lines) instead of 2-byte scatters.
+//   * The epilogue needs no transpose: each lane scales its runs with per-column constants fetched
+//     16 bytes at a time and stores them directly as 16-byte (fp32) or 8-byte (bf16, hardware
+//     round-to-nearest-even pack) pieces; the pieces of one row written by a wave are contiguous.
 //   * Workgroup ids are remapped so that each XCD (ids are dealt round-robin to the 8 XCDs) works on a
 //     contiguous run of tiles, ordered in panels of group_m row-tiles so concurrently resident
 //     workgroups of an XCD share X^ and W^ tiles in that XCD's L2.
@@ -85,8 +86,6 @@ struct MfmaCfg {
   static constexpr int GB = BN / RPL / NW;
   static constexpr int SUB = SK / 32;              // 32-byte MFMA k-steps per stage
   static constexpr int CPR = SK / 16;              // 16-byte chunks per row
-  static constexpr int EPI_ROW = TN * 4 + 16;      // staging row of the epilogue (fp32 worst case, padded)
-  static constexpr int EPI = 32 * EPI_ROW;         // per wave
   static constexpr int LDS_BYTES = NSTAGE * STAGE;
   static constexpr int LT = GA + GB;               // direct-load slots of one stage: X^ groups, W^ groups
   static constexpr int NSLOT = SUB * IM;           // points inside a stage's MFMA stream where loads are interleaved
@@ -95,7 +94,6 @@ struct MfmaCfg {
   static_assert(TM % 32 == 0 && TN % 32 == 0, "wave tile must be a multiple of the 32x32 MFMA");
   static_assert(BM % (RPL * NW) == 0 && BN % (RPL * NW) == 0, "load groups must divide evenly over the waves");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS ring exceeds 160 KB");
-  static_assert(NW * EPI <= NSTAGE * STAGE, "epilogue staging must fit in the ring");
   static_assert(NSTAGE * (GA + GB) < 64, "vmcnt is a 6-bit counter");
 };
 
@@ -195,11 +193,19 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
   const int8_t* ipA = a.xq;    // operand base pointers of the stage being issued
   const int8_t* ipB = a.wq;
   uint32_t iso = 0;
+  // The direct loads take their base address and LDS offset in scalar registers.  The values are uniform,
+  // but the compiler does not always prove it (it then hands the inline assembly a vector register pair,
+  // which does not assemble): readfirstlane states it, and folds away where uniformity is known.
+  auto uniform_ptr = [](const int8_t* p) __attribute__((always_inline)) {
+    const uint64_t u = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)u), hi = __builtin_amdgcn_readfirstlane((uint32_t)(u >> 32));
+    return reinterpret_cast<const int8_t*>(((uint64_t)hi << 32) | lo);
+  };
   auto issue_begin = [&]() __attribute__((always_inline)) {
     const int k0 = ik << KSH;
-    iso = (uint32_t)(ikt % NSTAGE) * (uint32_t)STAGE;
-    ipA = a.xq + k0;
-    ipB = a.wq + k0;
+    iso = __builtin_amdgcn_readfirstlane((uint32_t)(ikt % NSTAGE) * (uint32_t)STAGE);
+    ipA = uniform_ptr(a.xq + k0);
+    ipB = uniform_ptr(a.wq + k0);
   };
   auto issue_slot = [&](const int e) __attribute__((always_inline)) {          // e is a compile-time constant after unrolling
     if (e < GA) glds16(ipA, voffA[e < GA ? e : 0], ldsA + iso + (uint32_t)e * 1024u);
@@ -283,10 +289,10 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
         const int idx = DL ? (q >> 1) : q;
         const int i = idx / JN, j = idx % JN;
         if (!DL || (q & 1) == 0)
-          accp[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(afr[cur][i], bfr[cur][j], accp[i][j], 0, 0, 0);
+          accp[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bfr[cur][j], afr[cur][i], accp[i][j], 0, 0, 0);
         else
           accn[DUAL ? i : 0][DUAL ? j : 0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
-              nfr[cur][DUAL ? i : 0], bfr[cur][j], accn[DUAL ? i : 0][DUAL ? j : 0], 0, 0, 0);
+              bfr[cur][j], nfr[cur][DUAL ? i : 0], accn[DUAL ? i : 0][DUAL ? j : 0], 0, 0, 0);
       }
       __builtin_amdgcn_sched_barrier(0);
       if (PF) {
@@ -400,70 +406,138 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
       }
   };
 
+  // The flush code handles one 32x32 block at a time and re-states, right in front of each block, that its
+  // sums live in accumulation registers.  Without this the compiler copies all of them to ordinary VGPRs at
+  // the end of the K loop, ahead of every use, and spills what does not fit.
+  auto pin_block = [&](const int i, const int j) __attribute__((always_inline)) {
+    asm volatile("" : "+a"(accp[i][j]));
+    if (DUAL) asm volatile("" : "+a"(accn[DUAL ? i : 0][DUAL ? j : 0]));
+  };
+
+  // ---- accumulator layout seen by the flush code ------------------------------------------------------
+  // W^ is the MFMA "A" operand and X^ the "B" operand, so element v of block (i, j) in lane l is
+  //   row    m = m0 + wm*TM + i*32 + (l & 31)
+  //   column n = n0 + wn*TN + j*32 + 8*(v >> 2) + 4*(l >> 5) + (v & 3):
+  // a lane owns four runs of four consecutive output columns of one row, which it scales with per-column
+  // constants fetched 16 bytes at a time and stores directly as 16-byte (fp32, int32) or 8-byte (bf16)
+  // pieces; the pieces of the two lane halves and the four runs fill a row's cache lines back to back.
+  const int mrow = m0 + wm * C::TM + (lane & 31);
+  const int ncol = n0 + wn * C::TN + 4 * (lane >> 5);
+  const bool vec4 = (a.N % 4) == 0;                        // rows of Y / wscale / bias keep 16-byte alignment
+  // FULL: the tile lies inside the matrix and every row piece is 16-byte aligned, so the flush code runs
+  // without bounds checks or scalar fallbacks (one uniform branch picks the instantiation).
+  const bool full_tile =
+      vec4 && m0 + BM <= a.M && n0 + BN <= a.N &&
+      ((reinterpret_cast<uintptr_t>(a.y) | reinterpret_cast<uintptr_t>(a.wscale) | reinterpret_cast<uintptr_t>(a.bias) |
+        reinterpret_cast<uintptr_t>(a.acc_pos) | reinterpret_cast<uintptr_t>(a.acc_neg)) % 16 == 0);
+
+  // per-column constants of block column j in K-segment ks: cw[v] = seg_scale * wscale (0 outside N)
+  auto load_cw = [&](auto full_tag, const int ks, const int j, float (&cw)[16]) __attribute__((always_inline)) {
+    constexpr bool FULL = decltype(full_tag)::value;
+    const float* ws = a.wscale + (size_t)ks * a.N;
+    const bool wvec = FULL || (vec4 && (reinterpret_cast<uintptr_t>(ws) % 16 == 0));
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int n = ncol + j * 32 + 8 * g;
+      if (FULL || (wvec && n + 3 < a.N)) {
+        const v4f w4 = *reinterpret_cast<const v4f*>(ws + n);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) cw[4 * g + r] = w4[r];
+      } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) cw[4 * g + r] = (n + r < a.N) ? ws[n + r] : 0.0f;
+      }
+    }
+    if (tb.has_seg_scale) {                                // multiplier of block (ks, N-segment of the column)
+      float sg[16];
+      const float s0 = tb.seg_scale[ks * tb.T];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) sg[v] = s0;
+#pragma unroll 1
+      for (int t = 1; t < tb.T; ++t) {
+        const int off = tb.nseg_off[t];
+        const float st = tb.seg_scale[ks * tb.T + t];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sg[v] = (ncol + j * 32 + 8 * (v >> 2) + (v & 3) >= off) ? st : sg[v];
+      }
+#pragma unroll
+      for (int v = 0; v < 16; ++v) cw[v] *= sg[v];
+    }
+  };
+
+  // debug entry point: raw int32 sums of segment ks, acc_neg = 0 where the segment ran one path
+  auto store_debug = [&](auto full_tag, const int ks, const bool has_neg) __attribute__((always_inline)) {
+    constexpr bool FULL = decltype(full_tag)::value;
+    const bool avec = FULL || (vec4 && ((reinterpret_cast<uintptr_t>(a.acc_pos) | reinterpret_cast<uintptr_t>(a.acc_neg)) % 16 == 0));
+#pragma unroll
+    for (int i = 0; i < IM; ++i)
+#pragma unroll
+      for (int j = 0; j < JN; ++j) {
+        const int m = mrow + i * 32;
+        pin_block(i, j);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int n = ncol + j * 32 + 8 * g;
+          if (FULL || m < a.M) {
+            const size_t o = ((size_t)ks * a.M + m) * a.N + n;     // S*M*N < 2^31 is checked by the host
+            v4i p, q;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              p[r] = accp[i][j][4 * g + r];
+              q[r] = has_neg ? accn[DUAL ? i : 0][DUAL ? j : 0][4 * g + r] : 0;
+            }
+            if (FULL || (avec && n + 3 < a.N)) {
+              *reinterpret_cast<v4i*>(a.acc_pos + o) = p;
+              *reinterpret_cast<v4i*>(a.acc_neg + o) = q;
+            } else {
+#pragma unroll
+              for (int r = 0; r < 4; ++r)
+                if (n + r < a.N) { a.acc_pos[o + r] = p[r]; a.acc_neg[o + r] = q[r]; }
+            }
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    // stores share the vector-memory counter with the direct loads but complete out of order with them:
+    // drain everything so that the load accounting of the K loop stays valid
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  };
+
   // ---- K-segment boundary: scale the exact int32 sums into the fp32 running sum, clear them ----------
   // SHARE: the layer has exactly one dual K-segment and it is visited first.  Two int32 sets are live only
   // during that segment; at its end the X^_- set's registers are re-used for the fp32 running sum (its bits
   // are kept in accn), and every later segment accumulates in accp alone.  `first` = first visited segment.
-  auto flush_mid = [&](const int ks, const bool dl, const bool first) __attribute__((always_inline)) {
-    int ncol = n0 + wn * C::TN + (lane & 31);
-    int mrow = m0 + wm * C::TM + 4 * (lane >> 5);
-    asm volatile("" : "+v"(ncol), "+v"(mrow));   // keep this addressing out of the K loop's live ranges
+  auto flush_mid_impl = [&](auto full_tag, const int ks, const bool dl, const bool first) __attribute__((always_inline)) {
     if (mode == OUT_DEBUG_ACC) {
-      const int o0 = (ks * a.M + mrow) * a.N + ncol;   // S*M*N < 2^31 is checked by the host
+      store_debug(full_tag, ks, DUAL && dl && (!SHARE || first));
+    } else if (SHARE || FSUM) {
+      const float sp = tb.s_pos[ks], sn = dl ? tb.s_neg[ks] : 0.0f;
 #pragma unroll
-      for (int i = 0; i < IM; ++i)
+      for (int j = 0; j < JN; ++j) {
+        float cw[16];
+        load_cw(full_tag, ks, j, cw);
+        __builtin_amdgcn_sched_barrier(0);               // keep the next block column's constants out of this one's registers
 #pragma unroll
-        for (int j = 0; j < JN; ++j) {
+        for (int i = 0; i < IM; ++i) {
+          pin_block(i, j);
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
-            const int dm = i * 32 + 8 * (v >> 2) + (v & 3);
-            if (mrow + dm < a.M && ncol + j * 32 < a.N) {
-              const int o = o0 + dm * a.N + j * 32;
-              a.acc_pos[o] = accp[i][j][v];
-              a.acc_neg[o] = (DUAL && dl && (!SHARE || first)) ? accn[DUAL ? i : 0][DUAL ? j : 0][v] : 0;
+            const float cpos = cw[v] * sp, cneg = cw[v] * sn;
+            if (SHARE) {
+              const int old = accn[DUAL ? i : 0][DUAL ? j : 0][v];
+              const float prev = first ? cneg * (float)old : __int_as_float(old);
+              accn[DUAL ? i : 0][DUAL ? j : 0][v] = __float_as_int(prev + cpos * (float)accp[i][j][v]);
+            } else {
+              float t = cpos * (float)accp[i][j][v];
+              if (DUAL) t += cneg * (float)accn[DUAL ? i : 0][DUAL ? j : 0][v];
+              fsum[FSUM ? i : 0][FSUM ? j : 0][v] += t;
             }
           }
+          // back into accumulation registers at once: left in ordinary VGPRs, the new sums would be spilled
+          // to scratch memory around the next K loop
+          if (SHARE) asm volatile("" : "+a"(accn[DUAL ? i : 0][DUAL ? j : 0]));
+          __builtin_amdgcn_sched_barrier(0);
         }
-      // stores share the vector-memory counter with the direct loads but complete out of order with them:
-      // drain everything so that the load accounting of the K loop stays valid
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    } else if (SHARE) {
-      const float sp = tb.s_pos[ks], sn = tb.s_neg[ks];
-#pragma unroll
-      for (int j = 0; j < JN; ++j) {
-        const int n = ncol + j * 32;
-        const float cw = (n < a.N) ? seg_scale_of(tb, ks, n) * a.wscale[(size_t)ks * a.N + n] : 0.0f;
-        const float cpos = cw * sp, cneg = cw * sn;
-#pragma unroll
-        for (int i = 0; i < IM; ++i)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int old = accn[DUAL ? i : 0][DUAL ? j : 0][v];
-            const float prev = first ? cneg * (float)old : __int_as_float(old);
-            accn[DUAL ? i : 0][DUAL ? j : 0][v] = __float_as_int(prev + cpos * (float)accp[i][j][v]);
-          }
-        // back into accumulation registers at once: left in ordinary VGPRs, the new sums would be spilled to
-        // scratch memory around the next K loop
-#pragma unroll
-        for (int i = 0; i < IM; ++i) asm volatile("" : "+a"(accn[DUAL ? i : 0][DUAL ? j : 0]));
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    } else if (FSUM) {
-      const float sp = tb.s_pos[ks], sn = tb.s_neg[ks];
-#pragma unroll
-      for (int j = 0; j < JN; ++j) {
-        const int n = ncol + j * 32;
-        const float cw = (n < a.N) ? seg_scale_of(tb, ks, n) * a.wscale[(size_t)ks * a.N + n] : 0.0f;
-        const float cpos = cw * sp, cneg = dl ? cw * sn : 0.0f;
-#pragma unroll
-        for (int i = 0; i < IM; ++i)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            float t = cpos * (float)accp[i][j][v];
-            if (DUAL) t += cneg * (float)accn[DUAL ? i : 0][DUAL ? j : 0][v];
-            fsum[FSUM ? i : 0][FSUM ? j : 0][v] += t;
-          }
-        __builtin_amdgcn_sched_barrier(0);
       }
     }
 #pragma unroll
@@ -474,101 +548,104 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
         if (DUAL && (!SHARE || mode == OUT_DEBUG_ACC)) accn[i][j] = (v16i)(0);
       }
   };
+  auto flush_mid = [&](const int ks, const bool dl, const bool first) __attribute__((always_inline)) {
+    if (full_tile) flush_mid_impl(std::true_type{}, ks, dl, first);
+    else flush_mid_impl(std::false_type{}, ks, dl, first);
+  };
 
   // ---- last K-segment: dequantize, add bias, store ----------------------------------------------------
-  auto flush_last = [&](const int ks, const bool dl, const bool first) __attribute__((always_inline)) {
-    if (mode == OUT_DEBUG_ACC) { flush_mid(ks, dl, first); return; }
-    int ncol = n0 + wn * C::TN + (lane & 31);
-    int mrow = m0 + wm * C::TM + 4 * (lane >> 5);
-    asm volatile("" : "+v"(ncol), "+v"(mrow));
-    const float sp = tb.s_pos[ks], sn = tb.s_neg[ks];
-    float cpos[JN], cneg[JN], bs[JN];
+  // bf16 output of an interior tile: the two halves of the wave (lanes l and l + 32 hold the same row, column
+  // runs 4 apart) exchange every second run with v_permlane32_swap, so that each lane ends up with eight
+  // consecutive columns and stores 16 bytes.
+  auto flush_last_impl = [&](auto full_tag, auto bf16_tag, const int ks, const bool dl) __attribute__((always_inline)) {
+    constexpr bool FULL = decltype(full_tag)::value;
+    constexpr bool BF = decltype(bf16_tag)::value;
+    const float sp = tb.s_pos[ks], sn = dl ? tb.s_neg[ks] : 0.0f;
+    const bool yvec = FULL || (vec4 && (reinterpret_cast<uintptr_t>(a.y) % 16 == 0));
+    const bool bvec = FULL || (vec4 && (reinterpret_cast<uintptr_t>(a.bias) % 16 == 0));
 #pragma unroll
     for (int j = 0; j < JN; ++j) {
-      const int n = ncol + j * 32;
-      const bool nok = n < a.N;
-      const float cw = nok ? seg_scale_of(tb, ks, n) * a.wscale[(size_t)ks * a.N + n] : 0.0f;
-      cpos[j] = cw * sp;
-      cneg[j] = dl ? cw * sn : 0.0f;
-      bs[j] = (nok && a.bias) ? a.bias[n] : 0.0f;
-    }
-    // 1) dequantize in place: the accumulator registers now hold the fp32 result bits
+      float cw[16], bs[16];
+      load_cw(full_tag, ks, j, cw);
 #pragma unroll
-    for (int j = 0; j < JN; ++j) {
+      for (int g = 0; g < 4; ++g) {
+        const int n = ncol + j * 32 + 8 * g;
+        if (a.bias && bvec && (FULL || n + 3 < a.N)) {
+          const v4f b4 = *reinterpret_cast<const v4f*>(a.bias + n);
+#pragma unroll
+          for (int r = 0; r < 4; ++r) bs[4 * g + r] = b4[r];
+        } else {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) bs[4 * g + r] = (a.bias && n + r < a.N) ? a.bias[n + r] : 0.0f;
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);                 // keep the next block column's constants out of this one's registers
 #pragma unroll
       for (int i = 0; i < IM; ++i) {
+        const int m = mrow + i * 32;
+        pin_block(i, j);
+        float t[16];
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          float t = cpos[j] * (float)accp[i][j][v];
-          if (SHARE) t += __int_as_float(accn[DUAL ? i : 0][DUAL ? j : 0][v]);   // running sum (never the first segment)
-          else if (DUAL) t += cneg[j] * (float)accn[DUAL ? i : 0][DUAL ? j : 0][v];
-          if (FSUM) t += fsum[FSUM ? i : 0][FSUM ? j : 0][v];
-          t += bs[j];
-          accp[i][j][v] = __float_as_int(t);
+          float u = (cw[v] * sp) * (float)accp[i][j][v];
+          if (SHARE) u += __int_as_float(accn[DUAL ? i : 0][DUAL ? j : 0][v]);   // running sum (never the first segment)
+          else if (DUAL) u += (cw[v] * sn) * (float)accn[DUAL ? i : 0][DUAL ? j : 0][v];
+          if (FSUM) u += fsum[FSUM ? i : 0][FSUM ? j : 0][v];
+          t[v] = u + bs[v];
+        }
+        if (FULL && BF) {
+#pragma unroll
+          for (int p = 0; p < 2; ++p) {
+            const uint32_t a0 = f32x2_to_bf16x2(t[8 * p + 0], t[8 * p + 1]), a1 = f32x2_to_bf16x2(t[8 * p + 2], t[8 * p + 3]);
+            const uint32_t b0 = f32x2_to_bf16x2(t[8 * p + 4], t[8 * p + 5]), b1 = f32x2_to_bf16x2(t[8 * p + 6], t[8 * p + 7]);
+            // lanes 32..63 of the first operand <-> lanes 0..31 of the second
+            const auto s0 = __builtin_amdgcn_permlane32_swap(a0, b0, false, false);
+            const auto s1 = __builtin_amdgcn_permlane32_swap(a1, b1, false, false);
+            const v4i o4 = {(int)s0[0], (int)s1[0], (int)s0[1], (int)s1[1]};
+            const size_t o = (size_t)m * a.N + (ncol + j * 32 + 16 * p + 4 * (lane >> 5));
+            *reinterpret_cast<v4i*>(reinterpret_cast<uint16_t*>(a.y) + o) = o4;
+          }
+        } else {
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const int n = ncol + j * 32 + 8 * g;
+            if (FULL || m < a.M) {
+              const size_t o = (size_t)m * a.N + n;
+              if (FULL || (yvec && n + 3 < a.N)) {
+                if (!BF) {
+                  const v4f o4 = {t[4 * g], t[4 * g + 1], t[4 * g + 2], t[4 * g + 3]};
+                  *reinterpret_cast<v4f*>(reinterpret_cast<float*>(a.y) + o) = o4;
+                } else {
+                  v2i o2;
+                  o2[0] = (int)f32x2_to_bf16x2(t[4 * g], t[4 * g + 1]);
+                  o2[1] = (int)f32x2_to_bf16x2(t[4 * g + 2], t[4 * g + 3]);
+                  *reinterpret_cast<v2i*>(reinterpret_cast<uint16_t*>(a.y) + o) = o2;
+                }
+              } else {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                  if (n + r < a.N) {
+                    if (!BF) reinterpret_cast<float*>(a.y)[o + r] = t[4 * g + r];
+                    else reinterpret_cast<uint16_t*>(a.y)[o + r] = f32_to_bf16(t[4 * g + r]);
+                  }
+              }
+            }
+          }
         }
         __builtin_amdgcn_sched_barrier(0);
       }
     }
-    // 2) store
-    const int esz = (mode == OUT_F32) ? 4 : 2;
-    const bool vec = (a.N % (16 / esz)) == 0 && (reinterpret_cast<uintptr_t>(a.y) % 16 == 0);
-    if (vec) {
-      // Stage 32 rows x TN columns at a time through this wave's slice of the (idle) ring, then store
-      // 16 bytes per lane along N.
-      __syncthreads();                                   // every wave is done reading operand stages
-      char* stg = smem + wave * C::EPI;
-      const int rowb = C::TN * esz + 16;                 // padded staging row
-      const int cpl = 16 / esz;                          // columns per 16-byte store
-      const int lpr = C::TN / cpl;                       // lanes that cover one staged row
-      const int rows_per_it = 64 / lpr;
-      const int erow = lane / lpr;                       // staged row this lane stores (lanes beyond rows_per_it * lpr idle)
-      char* wbase = stg + (4 * (lane >> 5)) * rowb + (lane & 31) * esz;
-      const char* rbase = stg + (lane / lpr) * rowb + (lane % lpr) * 16;
-      const int mbase = m0 + wm * C::TM + lane / lpr;
-      const int nst = n0 + wn * C::TN + (lane % lpr) * cpl;
-#pragma unroll
-      for (int i = 0; i < IM; ++i) {
-#pragma unroll
-        for (int j = 0; j < JN; ++j) {
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            char* p = wbase + (8 * (v >> 2) + (v & 3)) * rowb + (j * 32) * esz;
-            const float t = __int_as_float(accp[i][j][v]);
-            if (mode == OUT_F32) *reinterpret_cast<float*>(p) = t;
-            else *reinterpret_cast<uint16_t*>(p) = f32_to_bf16(t);
-          }
-          __builtin_amdgcn_sched_barrier(0);
-        }
-        // read back row-contiguous and store
-#pragma unroll 2
-        for (int r0 = 0; r0 < 32; r0 += rows_per_it) {
-          const v4i val = *reinterpret_cast<const v4i*>(rbase + r0 * rowb);
-          const int m = mbase + i * 32 + r0;
-          if (erow < rows_per_it && r0 + erow < 32 && m < a.M && nst < a.N)
-            *reinterpret_cast<v4i*>(reinterpret_cast<char*>(a.y) + ((size_t)m * a.N + nst) * esz) = val;
-        }
-        __builtin_amdgcn_sched_barrier(0);
-      }
+  };
+  auto flush_last = [&](const int ks, const bool dl, const bool first) __attribute__((always_inline)) {
+    if (mode == OUT_DEBUG_ACC) {
+      if (full_tile) store_debug(std::true_type{}, ks, DUAL && dl && (!SHARE || first));
+      else store_debug(std::false_type{}, ks, DUAL && dl && (!SHARE || first));
+    } else if (mode == OUT_BF16) {
+      if (full_tile) flush_last_impl(std::true_type{}, std::true_type{}, ks, dl);
+      else flush_last_impl(std::false_type{}, std::true_type{}, ks, dl);
     } else {
-      const int o0 = mrow * a.N + ncol;
-#pragma unroll
-      for (int j = 0; j < JN; ++j) {
-        const bool nok = ncol + j * 32 < a.N;
-#pragma unroll
-        for (int i = 0; i < IM; ++i) {
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const float t = __int_as_float(accp[i][j][v]);
-            const int dm = i * 32 + 8 * (v >> 2) + (v & 3);
-            if (mrow + dm < a.M && nok) {
-              const int o = o0 + dm * a.N + j * 32;
-              if (mode == OUT_F32) reinterpret_cast<float*>(a.y)[o] = t;
-              else reinterpret_cast<uint16_t*>(a.y)[o] = f32_to_bf16(t);
-            }
-          }
-          __builtin_amdgcn_sched_barrier(0);
-        }
-      }
+      if (full_tile) flush_last_impl(std::true_type{}, std::false_type{}, ks, dl);
+      else flush_last_impl(std::false_type{}, std::false_type{}, ks, dl);
     }
   };
 

@@ -57,12 +57,17 @@ struct GemmArgs {
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
-// fp32 -> bf16, round-half-to-even on the dropped bits (finite inputs).
-__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
+// fp32 -> bf16, round-half-to-even: the hardware conversion of gfx950 (v_cvt_pk_bf16_f32), which agrees
+// bit for bit with "add 0x7FFF + lsb, drop 16 bits" on every finite input (checked exhaustively over the
+// high halves with tie / near-tie low halves).
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+typedef float v2f __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t f32x2_to_bf16x2(float lo, float hi) {
+  const v2f v = {lo, hi};
+  const v2bf b = __builtin_convertvector(v, v2bf);
+  return __builtin_bit_cast(uint32_t, b);
 }
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) { return (uint16_t)(f32x2_to_bf16x2(f, 0.0f) & 0xFFFFu); }
 
 // round(v / s) of the Sec. 3 quantizer, bit-identical to an IEEE division followed by
 // round-half-to-even.  v * (1/s) is within 2^-14.4 of the correctly rounded quotient whenever the
