@@ -60,15 +60,27 @@ bool mfma_supported(const GemmArgs& a, const GemmTable& tb) {
 
 // Automatic choice: occupancy of the last round of tiles (fill) times a relative efficiency of the tile
 // shape, measured on MI355X per layer class (single-path / dual / dual with several K-segments).
-static const float kEffSingle[kNumMfmaVariants] = {1.00f, 0.88f, 0.84f, 0.64f, 0.98f, 1.08f, 0.91f, 0.71f, 0.90f};
-static const float kEffDual[kNumMfmaVariants] = {1.00f, 0.81f, 0.80f, 0.68f, 0.00f, 0.92f, 0.99f, 0.75f, 0.90f};
-static const float kEffDualMulti[kNumMfmaVariants] = {1.00f, 0.92f, 0.89f, 0.75f, 0.00f, 0.84f, 0.83f, 0.87f, 0.88f};
+static const float kEffSingle[kNumMfmaVariants] = {1.00f, 0.85f, 0.82f, 0.62f, 0.95f, 0.95f, 0.72f, 0.71f, 0.88f};
+static const float kEffDual[kNumMfmaVariants] = {1.00f, 0.78f, 0.77f, 0.65f, 0.00f, 0.76f, 0.70f, 0.77f, 0.88f};
+static const float kEffDualMulti[kNumMfmaVariants] = {1.00f, 0.89f, 0.86f, 0.72f, 0.00f, 0.80f, 0.81f, 0.85f, 0.86f};
+
+// Compute units of the current device (MI355X: 256), looked up once per device.
+static int device_cus() {
+  static int cached[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (cached[dev] == 0) {
+    int cus = 256;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
+    cached[dev] = cus;
+  }
+  return cached[dev];
+}
 
 int mfma_pick_variant(const GemmArgs& a, const GemmTable& tb, OutMode) {
   bool dual, multi, share;
   layer_flags(tb, dual, multi, share);
-  int dev = 0, cus = 256;
-  if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+  const int cus = device_cus();
   const float* eff = dual ? (multi ? kEffDualMulti : kEffDual) : kEffSingle;
   int best = -1;
   float best_score = -1.0f;
@@ -102,6 +114,10 @@ hipError_t launch_seglinear_mfma(GemmArgs a, const GemmTable& tb_in, OutMode mod
   a.tiles_m = (a.M + i.BM - 1) / i.BM;
   a.tiles_n = (a.N + i.BN - 1) / i.BN;
   a.group_m = a.tiles_m < 8 ? a.tiles_m : 8;
+  // persistent workgroups: one per compute unit (times the variant's residency), fewer if there are fewer tiles
+  const long slots = (long)device_cus() * i.MINB;
+  const long tiles = (long)a.tiles_m * a.tiles_n;
+  a.num_wg = (int)(tiles < slots ? tiles : slots);
   return Tables::launch[variant](a, tb, mode, dual, multi, share, st);
 }
 

@@ -13,8 +13,7 @@ template <int V, bool DUAL, bool MULTI, bool SHARE>
 static hipError_t launch_one(const GemmArgs& a, const GemmTable& tb, int mode, hipStream_t st) {
   using P = MfmaVariant<V>;
   auto kern = seglinear_mfma_kernel<P::BM, P::BN, P::WM, P::WN, P::NS, P::SK, P::MINB, DUAL, MULTI, SHARE>;
-  const int blocks = a.tiles_m * a.tiles_n;
-  hipLaunchKernelGGL(kern, dim3(blocks), dim3(P::WM * P::WN * 64), 0, st, a, tb, mode);
+  hipLaunchKernelGGL(kern, dim3(a.num_wg), dim3(P::WM * P::WN * 64), 0, st, a, tb, mode);
   return hipGetLastError();
 }
 

@@ -124,39 +124,53 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave / WN, wn = wave % WN;
 
-  // ---- workgroup id -> output tile (XCD-contiguous, panels of group_m row-tiles) -------------------
-  int tm, tn;
-  {
-    const int nblk = gridDim.x, bid = blockIdx.x;
-    const int xcd = bid & 7, per = nblk >> 3, rem = nblk & 7;
-    const int logical = (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + (bid >> 3);
+  // ---- persistent workgroups: this workgroup's sequence of output tiles ------------------------------
+  // Workgroup ids are dealt round-robin to the 8 XCDs.  Each XCD owns a contiguous run of the (panel-ordered)
+  // tile list and its workgroups walk that run side by side, so the tiles in flight on one XCD are
+  // neighbours that share X^ and W^ lines in its L2.  The load pipeline runs across tile boundaries: the
+  // first stages of the next tile are fetched while the current tile is dequantized and stored.
+  const int ntiles = a.tiles_m * a.tiles_n;
+  const int xcd = blockIdx.x & 7, xlocal = blockIdx.x >> 3;
+  const int xper = ntiles >> 3, xrem = ntiles & 7;
+  const int xstart = xcd < xrem ? xcd * (xper + 1) : xrem * (xper + 1) + (xcd - xrem) * xper;
+  const int xcnt = xper + (xcd < xrem ? 1 : 0);                       // tiles of this XCD
+  const int xwg = (int)(gridDim.x >> 3) + (xcd < (int)(gridDim.x & 7) ? 1 : 0);   // workgroups on this XCD
+  const int ntile_wg = xlocal < xcnt ? (xcnt - xlocal + xwg - 1) / xwg : 0;        // tiles of this workgroup
+  if (ntile_wg == 0) return;                                          // uniform: the whole workgroup leaves
+  auto tile_origin = [&](const int it, int& tm0, int& tn0) __attribute__((always_inline)) {
+    const int logical = xstart + it * xwg + xlocal;
     const int gsz = a.group_m * a.tiles_n;
     const int g = logical / gsz, in = logical - g * gsz;
     const int first = g * a.group_m;
     const int gm = (a.tiles_m - first) < a.group_m ? (a.tiles_m - first) : a.group_m;
-    tn = in / gm;
-    tm = first + (in - tn * gm);
-  }
-  const int m0 = tm * BM, n0 = tn * BN;
+    const int tn = in / gm;
+    tm0 = (first + (in - tn * gm)) * BM;
+    tn0 = tn * BN;
+  };
 
-  // ---- per-lane source offsets of the direct loads (constant over the K loop) ----------------------
+  // ---- per-lane source offsets of the direct loads of the tile being fetched --------------------------
   // lane -> (row lane / CPR of the instruction's RPL rows, 16 B slot lane % CPR holding chunk slot ^ swizzle(row))
   const int lrow = lane / C::CPR, lslot = lane % C::CPR;
   uint32_t voffA[GA], voffB[GB];
+  auto set_issue_tile = [&](const int it) __attribute__((always_inline)) {
+    int im0, in0;
+    tile_origin(it, im0, in0);
 #pragma unroll
-  for (int g = 0; g < GA; ++g) {
-    const int rt = (wave * GA + g) * RPL + lrow;            // row inside the tile
-    int r = m0 + rt;
-    r = r < a.M ? r : a.M - 1;                              // ragged tail: re-read the last row, masked at the store
-    voffA[g] = (uint32_t)r * (uint32_t)a.K + (uint32_t)((lslot ^ row_swizzle<SK>(rt)) << 4);
-  }
+    for (int g = 0; g < GA; ++g) {
+      const int rt = (wave * GA + g) * RPL + lrow;            // row inside the tile
+      int r = im0 + rt;
+      r = r < a.M ? r : a.M - 1;                              // ragged tail: re-read the last row, masked at the store
+      voffA[g] = (uint32_t)r * (uint32_t)a.K + (uint32_t)((lslot ^ row_swizzle<SK>(rt)) << 4);
+    }
 #pragma unroll
-  for (int g = 0; g < GB; ++g) {
-    const int rt = (wave * GB + g) * RPL + lrow;
-    int r = n0 + rt;
-    r = r < a.N ? r : a.N - 1;
-    voffB[g] = (uint32_t)r * (uint32_t)a.K + (uint32_t)((lslot ^ row_swizzle<SK>(rt)) << 4);
-  }
+    for (int g = 0; g < GB; ++g) {
+      const int rt = (wave * GB + g) * RPL + lrow;
+      int r = in0 + rt;
+      r = r < a.N ? r : a.N - 1;
+      voffB[g] = (uint32_t)r * (uint32_t)a.K + (uint32_t)((lslot ^ row_swizzle<SK>(rt)) << 4);
+    }
+  };
+  set_issue_tile(0);
   const uint32_t lds0 = (uint32_t)(uintptr_t)SQ_LDS(smem);
   const uint32_t ldsA = lds0 + (uint32_t)(wave * GA) * 1024u;
   const uint32_t ldsB = lds0 + (uint32_t)C::AROWS * SK + (uint32_t)(wave * GB) * 1024u;
@@ -172,22 +186,25 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
   v16i accp[IM][JN];
   v16i accn[DUAL ? IM : 1][DUAL ? JN : 1];
   v16f fsum[FSUM ? IM : 1][FSUM ? JN : 1];
+  auto clear_accumulators = [&]() __attribute__((always_inline)) {
 #pragma unroll
-  for (int i = 0; i < IM; ++i)
+    for (int i = 0; i < IM; ++i)
 #pragma unroll
-    for (int j = 0; j < JN; ++j) {
-      accp[i][j] = (v16i)(0);
-      if (DUAL) accn[i][j] = (v16i)(0);
-      if (FSUM) fsum[i][j] = (v16f)(0.0f);
-    }
+      for (int j = 0; j < JN; ++j) {
+        accp[i][j] = (v16i)(0);
+        if (DUAL) accn[i][j] = (v16i)(0);
+        if (FSUM) fsum[i][j] = (v16f)(0.0f);
+      }
+  };
 
-  const int nkt = a.K >> KSH;
+  const int nkt_tile = a.K >> KSH;              // stages of one tile
+  const int nkt = nkt_tile * ntile_wg;          // stages of this workgroup, numbered across its tiles
   // ---- direct loads of one stage, issued slot by slot ------------------------------------------------
   // A stage's loads are a list of LT slots (X^ groups, then W^ groups), cut into SUB groups of slots: one
   // group per 32-byte k-step, so that a wave never sits in a burst of load issues while its MFMA pipe idles.
   // K-segments are visited in the order tb.seg_order (identity unless SHARE); stages are numbered in visit
   // order; ikt is the next stage to issue.
-  int issued = 0, ikt = 0;
+  int issued = 0, ikt = 0, iit = 0;
   int ipos = 0, iks = tb.seg_order[0];
   int ik = tb.kseg_off[iks] >> KSH, ik_end = tb.kseg_off[iks + 1] >> KSH;
   const int8_t* ipA = a.xq;    // operand base pointers of the stage being issued
@@ -219,8 +236,16 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
   };
   auto issue_end = [&]() __attribute__((always_inline)) {
     ++ikt;
-    if (++ik == ik_end && ipos + 1 < tb.S) {
-      iks = tb.seg_order[++ipos];
+    if (++ik == ik_end) {
+      if (ipos + 1 < tb.S) {
+        ++ipos;
+      } else if (iit + 1 < ntile_wg) {          // on to the next tile of this workgroup
+        set_issue_tile(++iit);
+        ipos = 0;
+      } else {
+        return;                                 // nothing left to fetch (the callers check ikt < nkt first)
+      }
+      iks = tb.seg_order[ipos];
       ik = tb.kseg_off[iks] >> KSH;
       ik_end = tb.kseg_off[iks + 1] >> KSH;
     }
@@ -421,15 +446,21 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
   // a lane owns four runs of four consecutive output columns of one row, which it scales with per-column
   // constants fetched 16 bytes at a time and stores directly as 16-byte (fp32, int32) or 8-byte (bf16)
   // pieces; the pieces of the two lane halves and the four runs fill a row's cache lines back to back.
-  const int mrow = m0 + wm * C::TM + (lane & 31);
-  const int ncol = n0 + wn * C::TN + 4 * (lane >> 5);
+  int mrow = 0, ncol = 0;                                  // of the tile being computed (set_compute_tile)
+  bool full_tile = false;
   const bool vec4 = (a.N % 4) == 0;                        // rows of Y / wscale / bias keep 16-byte alignment
+  const bool ptr16 = ((reinterpret_cast<uintptr_t>(a.y) | reinterpret_cast<uintptr_t>(a.wscale) |
+                       reinterpret_cast<uintptr_t>(a.bias) | reinterpret_cast<uintptr_t>(a.acc_pos) |
+                       reinterpret_cast<uintptr_t>(a.acc_neg)) % 16 == 0);
   // FULL: the tile lies inside the matrix and every row piece is 16-byte aligned, so the flush code runs
   // without bounds checks or scalar fallbacks (one uniform branch picks the instantiation).
-  const bool full_tile =
-      vec4 && m0 + BM <= a.M && n0 + BN <= a.N &&
-      ((reinterpret_cast<uintptr_t>(a.y) | reinterpret_cast<uintptr_t>(a.wscale) | reinterpret_cast<uintptr_t>(a.bias) |
-        reinterpret_cast<uintptr_t>(a.acc_pos) | reinterpret_cast<uintptr_t>(a.acc_neg)) % 16 == 0);
+  auto set_compute_tile = [&](const int it) __attribute__((always_inline)) {
+    int m0, n0;
+    tile_origin(it, m0, n0);
+    mrow = m0 + wm * C::TM + (lane & 31);
+    ncol = n0 + wn * C::TN + 4 * (lane >> 5);
+    full_tile = vec4 && ptr16 && m0 + BM <= a.M && n0 + BN <= a.N;
+  };
 
   // per-column constants of block column j in K-segment ks: cw[v] = seg_scale * wscale (0 outside N)
   auto load_cw = [&](auto full_tag, const int ks, const int j, float (&cw)[16]) __attribute__((always_inline)) {
@@ -649,38 +680,43 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
     }
   };
 
-  if constexpr (!MULTI) {
-    // one K-segment: the host selects the DUAL instantiation exactly when that segment is dual
-    run_segment(std::integral_constant<bool, DUAL>{}, nkt);
-    pin_accumulators();
-    flush_last(0, DUAL, true);
-  } else if constexpr (SHARE) {
-    // the dual K-segment first (both accumulator sets), then the single-scale ones (one set + running sum)
-    {
-      const int ks = tb.seg_order[0];
-      run_segment(std::true_type{}, (tb.kseg_off[ks + 1] - tb.kseg_off[ks]) >> KSH);
-      pin_accumulators();
-      flush_mid(ks, true, true);
-    }
 #pragma unroll 1
-    for (int pos = 1; pos < tb.S; ++pos) {
-      const int ks = tb.seg_order[pos];
-      run_segment(std::false_type{}, (tb.kseg_off[ks + 1] - tb.kseg_off[ks]) >> KSH);
+  for (int it = 0; it < ntile_wg; ++it) {
+    set_compute_tile(it);
+    clear_accumulators();
+    if constexpr (!MULTI) {
+      // one K-segment: the host selects the DUAL instantiation exactly when that segment is dual
+      run_segment(std::integral_constant<bool, DUAL>{}, nkt_tile);
       pin_accumulators();
-      if (pos == tb.S - 1) flush_last(ks, false, false);
-      else flush_mid(ks, false, false);
-    }
-  } else {
+      flush_last(0, DUAL, true);
+    } else if constexpr (SHARE) {
+      // the dual K-segment first (both accumulator sets), then the single-scale ones (one set + running sum)
+      {
+        const int ks = tb.seg_order[0];
+        run_segment(std::true_type{}, (tb.kseg_off[ks + 1] - tb.kseg_off[ks]) >> KSH);
+        pin_accumulators();
+        flush_mid(ks, true, true);
+      }
 #pragma unroll 1
-    for (int pos = 0; pos < tb.S; ++pos) {
-      const int ks = tb.seg_order[pos];
-      const bool dl = DUAL && (tb.dual[ks] != 0);
-      const int nst = (tb.kseg_off[ks + 1] - tb.kseg_off[ks]) >> KSH;
-      if (dl) run_segment(std::integral_constant<bool, DUAL>{}, nst);
-      else run_segment(std::integral_constant<bool, false>{}, nst);
-      pin_accumulators();
-      if (pos == tb.S - 1) flush_last(ks, dl, pos == 0);
-      else flush_mid(ks, dl, pos == 0);
+      for (int pos = 1; pos < tb.S; ++pos) {
+        const int ks = tb.seg_order[pos];
+        run_segment(std::false_type{}, (tb.kseg_off[ks + 1] - tb.kseg_off[ks]) >> KSH);
+        pin_accumulators();
+        if (pos == tb.S - 1) flush_last(ks, false, false);
+        else flush_mid(ks, false, false);
+      }
+    } else {
+#pragma unroll 1
+      for (int pos = 0; pos < tb.S; ++pos) {
+        const int ks = tb.seg_order[pos];
+        const bool dl = DUAL && (tb.dual[ks] != 0);
+        const int nst = (tb.kseg_off[ks + 1] - tb.kseg_off[ks]) >> KSH;
+        if (dl) run_segment(std::integral_constant<bool, DUAL>{}, nst);
+        else run_segment(std::integral_constant<bool, false>{}, nst);
+        pin_accumulators();
+        if (pos == tb.S - 1) flush_last(ks, dl, pos == 0);
+        else flush_mid(ks, dl, pos == 0);
+      }
     }
   }
 }

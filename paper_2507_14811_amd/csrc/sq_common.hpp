@@ -52,7 +52,8 @@ struct GemmArgs {
   int32_t* acc_pos;        // debug: [S][M][N]
   int32_t* acc_neg;
   int M, K, N;
-  int tiles_m, tiles_n, group_m;
+  int tiles_m, tiles_n, group_m;   // MFMA kernel: tile grid and panel height of the tile order
+  int num_wg;                      // MFMA kernel: persistent workgroups launched
 };
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
