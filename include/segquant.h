@@ -130,7 +130,8 @@ int sq_version(void);
 /*
  * Diagnostics hook for benchmarks and tests: process-wide override of kernel selection.
  *   key "gemm_variant": -1 = automatic (default), otherwise the index of a tile configuration
- *   key "force_path":   -1 = automatic, 0 = generic kernel, 1 = MFMA tile kernel, 2 = skinny kernel
+ *   key "force_path":   -1 = automatic, 0 = generic kernel, 1 = MFMA tile kernel, 2 = skinny kernel,
+ *                       3 = skinny weight-stream kernel
  * Returns SQ_ERR_INVALID_ARG for an unknown key or value.  Not thread-safe against running calls.
  */
 sq_status sq_tuning_set(const char* key, int value);

@@ -8,7 +8,7 @@
 namespace {
 
 int g_gemm_variant = -1;   // sq_tuning_set("gemm_variant", v)
-int g_force_path = -1;     // sq_tuning_set("force_path", p): 0 generic, 1 MFMA tiles, 2 skinny
+int g_force_path = -1;     // sq_tuning_set("force_path", p): 0 generic, 1 MFMA tiles, 2 skinny, 3 skinny weight stream
 
 bool offsets_ok(int n, int cnt, const int32_t* off) {
   if (cnt < 1 || cnt > SQ_MAX_SEGMENTS || off == nullptr) return false;
@@ -90,15 +90,23 @@ sq_status run_gemm(const sq_layer* L, const int8_t* xq, const int8_t* wq,
   a.N = L->N;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   int path = g_force_path;
+  if (path == 3 && !sq::stream_supported(a, tb)) return SQ_ERR_UNSUPPORTED;
   if (path == 2 && !sq::skinny_supported(a, tb)) return SQ_ERR_UNSUPPORTED;
   if (path == 1 && !sq::mfma_supported(a, tb)) return SQ_ERR_UNSUPPORTED;
   if (path < 0) {
-    if (sq::skinny_supported(a, tb)) path = 2;
+    // up to two 16-row tiles of tokens: the weight-stream kernel (measured 5.5 TB/s on wide layers); three or four
+    // tiles: the MFMA tile kernel with 64-row tiles is as fast or faster; the K-splitting skinny kernel serves
+    // the layers whose K-segments are only 64-aligned
+    if (a.M <= 32 && sq::stream_supported(a, tb)) path = 3;
+    else if (a.M <= 64 && a.M > 32 && sq::mfma_supported(a, tb)) path = 1;
+    else if (sq::skinny_supported(a, tb)) path = 2;
     else if (sq::mfma_supported(a, tb)) path = 1;
     else path = 0;
   }
   hipError_t e;
-  if (path == 2) {
+  if (path == 3) {
+    e = sq::launch_seglinear_stream(a, tb, mode, sq::device_cus(), st);
+  } else if (path == 2) {
     e = sq::launch_seglinear_skinny(a, tb, mode, st);
   } else if (path == 1) {
     int v = g_gemm_variant >= 0 ? g_gemm_variant : sq::mfma_pick_variant(a, tb, mode);
@@ -188,7 +196,7 @@ sq_status sq_tuning_set(const char* key, int value) {
     return SQ_OK;
   }
   if (std::strcmp(key, "force_path") == 0) {
-    if (value < -1 || value > 2) return SQ_ERR_INVALID_ARG;
+    if (value < -1 || value > 3) return SQ_ERR_INVALID_ARG;
     g_force_path = value;
     return SQ_OK;
   }

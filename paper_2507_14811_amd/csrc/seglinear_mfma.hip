@@ -65,7 +65,7 @@ static const float kEffDual[kNumMfmaVariants] = {1.00f, 0.78f, 0.77f, 0.65f, 0.0
 static const float kEffDualMulti[kNumMfmaVariants] = {1.00f, 0.89f, 0.86f, 0.72f, 0.00f, 0.80f, 0.81f, 0.85f, 0.86f};
 
 // Compute units of the current device (MI355X: 256), looked up once per device.
-static int device_cus() {
+int device_cus() {
   static int cached[64] = {0};
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;

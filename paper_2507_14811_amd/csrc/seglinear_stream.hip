@@ -1,0 +1,294 @@
+// Skinny-M (M <= 64) SegLinear + DualScale GEMM for wide layers: a persistent weight stream.
+//
+// Modulation / adaLN-style layers (Sec. 4.2.2 item 1: a linear followed by chunk; Sec. 4.3.2: its input comes
+// from SiLU) have a handful of token rows and a wide output, also when the modulation linears of all blocks
+// of a model are stacked along N into one call.  The layer is then one pass over the int8 weight, and this
+// kernel is built as an HBM stream:
+//   * X^ (polarity-merged codes, at most 64 rows) is copied once per workgroup into an LDS slab and stays there;
+//     rows are padded by 16 bytes so that the 16 rows of a fragment read fall on distinct bank groups.
+//   * Every wave owns a contiguous run of 16-column groups of the output and streams the 16 W^ rows of a group
+//     in steps of 128 bytes of K (full cache lines) through a private ring of direct global->LDS loads.  The
+//     ring runs ahead across group boundaries, so a wave always has RING-1 steps (2 KiB each) in flight; with
+//     eight waves per workgroup (two per SIMD, so one wave's LDS and MFMA latencies hide behind the other's
+//     work) and one workgroup per CU that is ~100 KB in flight per CU, which covers HBM latency at full
+//     bandwidth.  No workgroup barrier is needed after the slab is filled.
+//   * W^ rows are the MFMA "A" operand (v_mfma_i32_16x16x64_i8) and X^ rows the "B" operand, so a lane ends up
+//     with four consecutive output columns of one token row: scales are fetched and results stored 16 / 8
+//     bytes at a time.  Exact int32 sums per K-segment and polarity are scaled into an fp32 running sum at
+//     each segment boundary (Sec. 4.2.2 item 2, Sec. 4.3.2 last display).
+#include "seglinear_mfma_kernel.hpp"
+
+namespace sq {
+
+constexpr int kStreamWaves = 8;
+
+template <int MT, int SLAB_KB>
+struct StreamCfg {
+  static constexpr int SLAB = SLAB_KB * 1024;
+  static constexpr int STEP = 2048;                               // 16 W^ rows x 128 bytes of K
+  static constexpr int RAW = (156 * 1024 - SLAB) / (kStreamWaves * STEP);
+  static constexpr int RING = RAW > 28 ? 28 : RAW;                // 2 loads per step: stays below the 6-bit vmcnt
+  static constexpr int LDS = SLAB + kStreamWaves * RING * STEP;
+  static_assert(RING >= 4, "ring too shallow");
+  static_assert(LDS <= 160 * 1024, "LDS budget");
+};
+
+template <int MT, bool DUAL, int SLAB_KB>
+__global__ __launch_bounds__(kStreamWaves * 64) void seglinear_stream_kernel(const GemmArgs a, const GemmTable tb, const int mode) {
+  using C = StreamCfg<MT, SLAB_KB>;
+  constexpr int RING = C::RING, STEP = C::STEP;
+  __shared__ __attribute__((aligned(1024))) char smem[C::LDS];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+
+  // ---- this wave's run of 16-column groups ------------------------------------------------------------
+  const int ngroups = (a.N + 15) >> 4;
+  // waves are ranked workgroup-interleaved, so a layer with fewer groups than waves still spreads over all CUs
+  const int nwaves = gridDim.x * kStreamWaves, wid = wave * gridDim.x + blockIdx.x;
+  const int gper = ngroups / nwaves, grem = ngroups % nwaves;
+  const int g_begin = wid < grem ? wid * (gper + 1) : grem * (gper + 1) + (wid - grem) * gper;
+  const int g_cnt = gper + (wid < grem ? 1 : 0);
+  const int nstep = a.K >> 7;                                      // 128-byte steps per group
+  const int total = g_cnt * nstep;                                 // steps of this wave
+
+  // ---- direct loads: lane -> (row lane/8 of 8 rows, 16 B slot lane%8 holding chunk slot ^ swizzle(row)) -----
+  char* ring = smem + C::SLAB + wave * (RING * STEP);
+  const uint32_t ring_lds = (uint32_t)(uintptr_t)SQ_LDS(ring);
+  const int lrow = lane >> 3, lslot = lane & 7;
+  int ig = 0, it = 0, issued_steps = 0, islot = 0;
+  uint32_t voff[2];
+  auto set_issue_group = [&](const int g) __attribute__((always_inline)) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int rt = 8 * h + lrow;
+      int r = (g_begin + g) * 16 + rt;
+      r = r < a.N ? r : a.N - 1;                                   // ragged N: re-read the last row, masked at the store
+      voff[h] = (uint32_t)r * (uint32_t)a.K + (uint32_t)((lslot ^ row_swizzle<128>(rt)) << 4);
+    }
+  };
+  auto issue_step = [&]() __attribute__((always_inline)) {
+    const uint64_t u = reinterpret_cast<uint64_t>(a.wq + ((size_t)it << 7));
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)u), hi = __builtin_amdgcn_readfirstlane((uint32_t)(u >> 32));
+    const int8_t* base = reinterpret_cast<const int8_t*>(((uint64_t)hi << 32) | lo);
+    const uint32_t so = __builtin_amdgcn_readfirstlane(ring_lds + (uint32_t)islot * (uint32_t)STEP);
+    glds16(base, voff[0], so);
+    glds16(base, voff[1], so + 1024u);
+    ++issued_steps;
+    islot = (islot + 1 == RING) ? 0 : islot + 1;
+    if (++it == nstep) {
+      it = 0;
+      if (++ig < g_cnt) set_issue_group(ig);
+    }
+  };
+  if (g_cnt > 0) set_issue_group(0);
+#pragma unroll 1
+  while (issued_steps < RING - 1 && issued_steps < total) issue_step();
+
+  // ---- X^ slab: [16*MT rows][K + 16] bytes, rows beyond M repeat the last row (masked at the store) ----------
+  {
+    const int rowb = a.K + 16, cpr = a.K >> 4;                     // 16-byte chunks per row
+    const int nchunk = MT * 16 * cpr;
+    for (int c = threadIdx.x; c < nchunk; c += kStreamWaves * 64) {
+      const int r = c / cpr, cc = c - r * cpr;
+      const int rs = r < a.M ? r : a.M - 1;
+      const v4i v = *reinterpret_cast<const v4i*>(a.xq + (size_t)rs * a.K + cc * 16);
+      *reinterpret_cast<v4i*>(smem + r * rowb + cc * 16) = v;
+    }
+  }
+  __syncthreads();   // the only workgroup barrier: slab visible (the compiler drains this thread's loads here, the
+                     // direct loads above included; the stream refills right after)
+
+  // ---- fragment offsets ------------------------------------------------------------------------------------
+  const int frow = lane & 15, fq = lane >> 4;                      // fragment row, 16-byte k-chunk
+  // W^ step slot: row frow, chunk 4h + fq of 8, swizzled; X^ slab: row frow (+16 mt), byte 64*kk + 16*fq
+  int woff[2];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) woff[h] = frow * 128 + (((4 * h + fq) ^ row_swizzle<128>(frow)) << 4);
+  const int xrow = frow * (a.K + 16) + 16 * fq;
+
+  const int mlane = lane & 15;                                     // token row inside a 16-row tile
+  const bool vec4 = (a.N % 4) == 0 &&
+                    ((reinterpret_cast<uintptr_t>(a.y) | reinterpret_cast<uintptr_t>(a.wscale) | reinterpret_cast<uintptr_t>(a.bias) |
+                      reinterpret_cast<uintptr_t>(a.acc_pos) | reinterpret_cast<uintptr_t>(a.acc_neg)) % 16 == 0);
+
+  int done_steps = 0, cslot = 0;
+#pragma unroll 1
+  for (int g = 0; g < g_cnt; ++g) {
+    const int ncol = (g_begin + g) * 16 + 4 * fq;                  // this lane's four output columns
+    v4f fsum[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) fsum[mt] = (v4f)(0.0f);
+    int kk = 0;                                                    // 64-byte k-step inside the group
+#pragma unroll 1
+    for (int ks = 0; ks < tb.S; ++ks) {
+      const bool dl = DUAL && (tb.dual[ks] != 0);
+      const int kk_end = tb.kseg_off[ks + 1] >> 6;
+      // two accumulator sets, one per 64-byte half of a step: consecutive MFMAs do not wait on each other
+      v4i accp[MT], accn[MT], accp1[MT], accn1[MT];
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) { accp[mt] = (v4i)(0); accn[mt] = (v4i)(0); accp1[mt] = (v4i)(0); accn1[mt] = (v4i)(0); }
+#pragma unroll 1
+      while (kk < kk_end) {                                        // one 128-byte step = two MFMA k-steps
+        ++done_steps;
+        wait_vmcnt<2 * (RING - 2), 0>(2 * (issued_steps - done_steps));
+        v4i wf[2], xf[2][MT];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {                              // all fragment reads of the step first
+          wf[h] = *reinterpret_cast<const v4i*>(ring + cslot * STEP + woff[h]);
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt)
+            xf[h][mt] = *reinterpret_cast<const v4i*>(smem + mt * 16 * (a.K + 16) + xrow + (kk + h) * 64);
+        }
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) {
+            v4i pf = xf[h][mt];
+            if (dl) {                                              // X^_+ = max(X^, 0), X^_- = min(X^, 0), byte-wise
+              v4i nf;
+#pragma unroll
+              for (int d = 0; d < 4; ++d) {
+                int pos, neg;
+                split_polarity(pf[d], pos, neg);
+                pf[d] = pos;
+                nf[d] = neg;
+              }
+              if (h == 0) accn[mt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf[h], nf, accn[mt], 0, 0, 0);
+              else accn1[mt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf[h], nf, accn1[mt], 0, 0, 0);
+            }
+            if (h == 0) accp[mt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf[h], pf, accp[mt], 0, 0, 0);
+            else accp1[mt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf[h], pf, accp1[mt], 0, 0, 0);
+          }
+        // step consumed (its fragments are in registers): free the slot, keep the stream going
+        cslot = (cslot + 1 == RING) ? 0 : cslot + 1;
+        if (issued_steps < total) issue_step();
+        kk += 2;
+      }
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) { accp[mt] += accp1[mt]; accn[mt] += accn1[mt]; }
+      // ---- K-segment boundary (kseg boundaries are multiples of 128 here, so a step never straddles one) ------
+      if (mode == OUT_DEBUG_ACC) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          const int m = mt * 16 + mlane;
+          if (m < a.M) {
+            const size_t o = ((size_t)ks * a.M + m) * a.N + ncol;
+            const v4i q = dl ? accn[mt] : (v4i)(0);
+            if (vec4 && ncol + 3 < a.N) {
+              *reinterpret_cast<v4i*>(a.acc_pos + o) = accp[mt];
+              *reinterpret_cast<v4i*>(a.acc_neg + o) = q;
+            } else {
+#pragma unroll
+              for (int r = 0; r < 4; ++r)
+                if (ncol + r < a.N) { a.acc_pos[o + r] = accp[mt][r]; a.acc_neg[o + r] = q[r]; }
+            }
+          }
+        }
+      } else {
+        float cw[4];
+        const float* ws = a.wscale + (size_t)ks * a.N;
+        if (vec4 && ncol + 3 < a.N) {
+          const v4f w4 = *reinterpret_cast<const v4f*>(ws + ncol);
+#pragma unroll
+          for (int r = 0; r < 4; ++r) cw[r] = w4[r];
+        } else {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) cw[r] = (ncol + r < a.N) ? ws[ncol + r] : 0.0f;
+        }
+        if (tb.has_seg_scale) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) cw[r] *= seg_scale_of(tb, ks, ncol + r);
+        }
+        const float sp = tb.s_pos[ks], sn = dl ? tb.s_neg[ks] : 0.0f;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            float t = (cw[r] * sp) * (float)accp[mt][r];
+            if (DUAL) t += (cw[r] * sn) * (float)accn[mt][r];
+            fsum[mt][r] += t;
+          }
+      }
+    }
+    // ---- group done: bias, cast, store -------------------------------------------------------------------------
+    if (mode != OUT_DEBUG_ACC) {
+      float bs[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) bs[r] = (a.bias && ncol + r < a.N) ? a.bias[ncol + r] : 0.0f;
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const int m = mt * 16 + mlane;
+        if (m < a.M) {
+          const size_t o = (size_t)m * a.N + ncol;
+          float t[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) t[r] = fsum[mt][r] + bs[r];
+          if (vec4 && ncol + 3 < a.N) {
+            if (mode == OUT_F32) {
+              const v4f o4 = {t[0], t[1], t[2], t[3]};
+              *reinterpret_cast<v4f*>(reinterpret_cast<float*>(a.y) + o) = o4;
+            } else {
+              v2i o2;
+              o2[0] = (int)f32x2_to_bf16x2(t[0], t[1]);
+              o2[1] = (int)f32x2_to_bf16x2(t[2], t[3]);
+              *reinterpret_cast<v2i*>(reinterpret_cast<uint16_t*>(a.y) + o) = o2;
+            }
+          } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+              if (ncol + r < a.N) {
+                if (mode == OUT_F32) reinterpret_cast<float*>(a.y)[o + r] = t[r];
+                else reinterpret_cast<uint16_t*>(a.y)[o + r] = f32_to_bf16(t[r]);
+              }
+          }
+        }
+      }
+    }
+  }
+}
+
+// Wide skinny layers only: enough 16-column groups to give every wave of the chip a run of them; K and every
+// K-segment boundary multiples of 128 (a step is a full cache line per row); X^ slab within the LDS budget.
+static int stream_slab_kb(const GemmArgs& a) {
+  const int mt = (a.M + 15) / 16;
+  const long slab = (long)mt * 16 * (a.K + 16);
+  if (slab <= 24 * 1024) return 24;
+  if (slab <= 80 * 1024) return 80;
+  return 0;
+}
+
+bool stream_supported(const GemmArgs& a, const GemmTable& tb) {
+  if (a.M > 64 || a.K % 128 != 0) return false;
+  for (int s = 0; s <= tb.S; ++s)
+    if (tb.kseg_off[s] % 128 != 0) return false;
+  if ((reinterpret_cast<uintptr_t>(a.xq) | reinterpret_cast<uintptr_t>(a.wq)) % 16 != 0) return false;
+  if (stream_slab_kb(a) == 0) return false;
+  return true;
+}
+
+template <int MT, int SLAB_KB>
+static hipError_t launch_stream_ms(const GemmArgs& a, const GemmTable& tb, int mode, bool dual, int grid, hipStream_t st) {
+  if (dual) hipLaunchKernelGGL((seglinear_stream_kernel<MT, true, SLAB_KB>), dim3(grid), dim3(kStreamWaves * 64), 0, st, a, tb, mode);
+  else hipLaunchKernelGGL((seglinear_stream_kernel<MT, false, SLAB_KB>), dim3(grid), dim3(kStreamWaves * 64), 0, st, a, tb, mode);
+  return hipGetLastError();
+}
+
+hipError_t launch_seglinear_stream(const GemmArgs& a, const GemmTable& tb, OutMode mode, int cus, hipStream_t st) {
+  bool dual = false;
+  for (int s = 0; s < tb.S; ++s) dual = dual || tb.dual[s];
+  const int mt = (a.M + 15) / 16;
+  const int ngroups = (a.N + 15) / 16;
+  int grid = ngroups < cus ? ngroups : cus;
+  const int slab = stream_slab_kb(a);
+#define SQ_STREAM(MT_) \
+  (slab == 24 ? launch_stream_ms<MT_, 24>(a, tb, mode, dual, grid, st) : launch_stream_ms<MT_, 80>(a, tb, mode, dual, grid, st))
+  switch (mt) {
+    case 1: return SQ_STREAM(1);
+    case 2: return SQ_STREAM(2);
+    case 3: return SQ_STREAM(3);
+    default: return SQ_STREAM(4);
+  }
+#undef SQ_STREAM
+}
+
+}  // namespace sq

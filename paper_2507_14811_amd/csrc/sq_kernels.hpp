@@ -30,4 +30,11 @@ hipError_t launch_seglinear_mfma(GemmArgs a, const GemmTable& tb, OutMode mode, 
 bool skinny_supported(const GemmArgs& a, const GemmTable& tb);
 hipError_t launch_seglinear_skinny(const GemmArgs& a, const GemmTable& tb, OutMode mode, hipStream_t st);
 
+// seglinear_stream.hip : M <= 64 and a wide output: persistent weight stream.  K and K-segment boundaries % 128 == 0.
+bool stream_supported(const GemmArgs& a, const GemmTable& tb);
+hipError_t launch_seglinear_stream(const GemmArgs& a, const GemmTable& tb, OutMode mode, int cus, hipStream_t st);
+
+// compute units of the current device (cached)
+int device_cus();
+
 }  // namespace sq

@@ -202,6 +202,39 @@ def test_seglinear_skinny_small(oracle, case):
     _check_layer(oracle, g, w, path=2)
 
 
+STREAM = [
+    dict(M=16, K=1152, N=6912, kseg=[0, 1152], nseg=[0, 1152, 2304, 3456, 4608, 5760, 6912], dual=[1]),
+    dict(M=5, K=256, N=33, kseg=[0, 128, 256], nseg=[0, 33], dual=[1, 0]),          # ragged N, two K-segments
+    dict(M=33, K=384, N=100, kseg=[0, 384], nseg=[0, 100], dual=[0]),                # single path, three row tiles
+    dict(M=64, K=640, N=4100, kseg=[0, 128, 256, 640], nseg=[0, 4100], dual=[1, 1, 0]),
+    dict(M=1, K=128, N=16, kseg=[0, 128], nseg=[0, 16], dual=[1]),
+    dict(M=48, K=1280, N=18000, kseg=[0, 1280], nseg=[0, 9000, 18000], dual=[1]),   # several groups per wave, 80 KB slab
+    dict(M=16, K=1152, N=16 * 2100, kseg=[0, 1152], nseg=[0, 16 * 2100], dual=[1]),  # runs of groups, ring wraps
+]
+
+
+@pytest.mark.parametrize("case", STREAM)
+def test_seglinear_stream_small(oracle, case):
+    """Persistent weight-stream kernel of wide skinny layers (forced; automatic only for very wide N)."""
+    g = _gpu()
+    w = wl.random_layer(case["M"], case["K"], case["N"], case["kseg"], case["nseg"], case["dual"],
+                        seed=case["K"] + 11, x_dtype="bf16", act="silu", with_seg_scale=True, with_bias=True)
+    _check_layer(oracle, g, w, path=3)
+
+
+def test_stream_rejects_unaligned_k(oracle):
+    g = _gpu()
+    w = wl.random_layer(8, 192, 64, [0, 192], [0, 64], [1], seed=1, x_dtype="bf16", act="silu")
+    gl = g.GpuLayer(w)
+    gl.quantize_weight()
+    gl.quantize_act()
+    sq.sq_tuning_set("force_path", 3)
+    with pytest.raises(sq.SqError) as e:
+        gl.seglinear("f32")
+    assert e.value.status == 2
+    sq.sq_tuning_set("force_path", -1)
+
+
 GENERIC = [
     dict(M=7, K=100, N=13, kseg=[0, 37, 100], nseg=[0, 5, 13], dual=[1, 0]),
     dict(M=70, K=96, N=65, kseg=[0, 96], nseg=[0, 65], dual=[1]),
