@@ -27,9 +27,15 @@ sys.path.insert(0, ROOT)
 INT8_MFMA_PEAK_TOPS = 5033.2   # 256 CU x 2.4 GHz x 8192 int8 ops/clk/CU (dense)
 HBM_PEAK_GBS = 8000.0
 
-# HBM traffic per GEMM launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/), bytes.
-# None until a counter run for that workload has been committed.
-MEASURED_TRAFFIC = {}
+# Fabric-side traffic per GEMM launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by the
+# readings of a plain 256 MiB copy kernel (profiles/bench_all_kernels_rocprofv3.txt), bytes.  None for a
+# workload without a committed counter run.
+MEASURED_TRAFFIC = {
+    "cfg5_outproj": int(320803.7 * 1024 * 2.0 + 177236.7 * 1024 * 1.0),      # 838.5 MB (algorithmic 146.3 MB)
+    "cfg4d_qkv_dual": int(69520.1 * 1024 * 2.0 + 76536.3 * 1024 * 1.0),
+    "cfg4_qkv": int(69417.1 * 1024 * 2.0 + 76542.9 * 1024 * 1.0),
+    "cfg2_dit_fc2": int(19724.6 * 1024 * 2.0 + 4608.0 * 1024 * 1.0),
+}
 
 
 def _setup(name):
@@ -104,6 +110,16 @@ def measure(name, steps, warmup, rotate_quant=True):
     ms_step = (t1 - t0) * 1e3 / steps
     ms_gemm = float(np.mean([a.elapsed_time(b) for a, b in ev]))
 
+    # the GEMM kernel back to back (one event pair around `steps` launches): for kernels of a few microseconds
+    # the per-launch event pairs above mostly measure launch gaps
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        gemm()
+    e1.record()
+    torch.cuda.synchronize()
+    ms_gemm_b2b = e0.elapsed_time(e1) / steps
+
     # quantize pass alone (outside the step timing).  Small inputs would sit in the 256 MB Infinity
     # Cache between calls, so rotate over distinct buffers totalling > 512 MB to measure HBM.
     qbytes = w.quantize_act_bytes()
@@ -130,7 +146,8 @@ def measure(name, steps, warmup, rotate_quant=True):
         name=w.name, M=w.M, K=w.K, N=w.N, S=w.S, T=w.T, dual=[int(d) for d in w.dual],
         int8_ops=w.int8_ops, ms_step=ms_step, ms_gemm=ms_gemm, ms_quant=ms_quant, ms_quantize_weight=t_wq,
         gemm_tops=w.int8_ops / (ms_gemm * 1e-3) / 1e12, step_tops=w.int8_ops / (ms_step * 1e-3) / 1e12,
-        gemm_bytes=gbytes, gemm_gbs=gbytes / (ms_gemm * 1e-3) / 1e9,
+        ms_gemm_b2b=ms_gemm_b2b, gemm_tops_b2b=w.int8_ops / (ms_gemm_b2b * 1e-3) / 1e12,
+        gemm_bytes=gbytes, gemm_gbs=gbytes / (ms_gemm * 1e-3) / 1e9, gemm_gbs_b2b=gbytes / (ms_gemm_b2b * 1e-3) / 1e9,
         quant_bytes=qbytes, quant_gbs=qbytes / (ms_quant * 1e-3) / 1e9, quant_rotation=nrot,
     )
 
@@ -168,7 +185,7 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="cfg5", help="headline workload (cfg2 | cfg4 | cfg4d | cfg5)")
-    ap.add_argument("--others", default="cfg2,cfg3,cfg4,cfg4d", help="extra workloads summarised in the same line")
+    ap.add_argument("--others", default="cfg2,cfg3,cfg3x28,cfg4,cfg4d", help="extra workloads summarised in the same line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--variant", type=int, default=-1, help="force an MFMA tile variant (diagnostics)")
     args = ap.parse_args()
@@ -202,9 +219,10 @@ def main():
         r = measure(name, max(10, args.steps // 2), max(3, args.warmup // 2))
         skinny = r["M"] <= 64
         others[name] = {
-            "M": r["M"], "K": r["K"], "N": r["N"], "ms_gemm": round(r["ms_gemm"], 5), "ms_quant": round(r["ms_quant"], 5),
-            "gemm_tops": round(r["gemm_tops"], 2), "gemm_frac_mfma_peak": round(r["gemm_tops"] / INT8_MFMA_PEAK_TOPS, 4),
-            "gemm_gbs": round(r["gemm_gbs"], 1), "gemm_frac_hbm_peak": round(r["gemm_gbs"] / HBM_PEAK_GBS, 4),
+            "M": r["M"], "K": r["K"], "N": r["N"], "ms_gemm_in_step": round(r["ms_gemm"], 5),
+            "ms_gemm": round(r["ms_gemm_b2b"], 5), "ms_quant": round(r["ms_quant"], 5),
+            "gemm_tops": round(r["gemm_tops_b2b"], 2), "gemm_frac_mfma_peak": round(r["gemm_tops_b2b"] / INT8_MFMA_PEAK_TOPS, 4),
+            "gemm_gbs": round(r["gemm_gbs_b2b"], 1), "gemm_frac_hbm_peak": round(r["gemm_gbs_b2b"] / HBM_PEAK_GBS, 4),
             "gemm_bound": "hbm" if skinny else "mfma",
             "quant_gbs": round(r["quant_gbs"], 1), "quant_frac_hbm_peak": round(r["quant_gbs"] / HBM_PEAK_GBS, 4),
             "ms_quantize_weight": round(r["ms_quantize_weight"], 5),
@@ -234,6 +252,7 @@ def main():
             "unit": "TOP/s",
             "frac": round(head["gemm_tops"] / INT8_MFMA_PEAK_TOPS, 4),
             "ms_per_launch": round(head["ms_gemm"], 5),
+            "ms_per_launch_back_to_back": round(head["ms_gemm_b2b"], 5),
             "traffic": MEASURED_TRAFFIC.get(head["name"]),
         },
         "quantize_act": {"bound": "hbm", "achieved": round(head["quant_gbs"], 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",

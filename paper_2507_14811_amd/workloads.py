@@ -184,6 +184,23 @@ def cfg3_adaln(seed: int = 3) -> Workload:
                    sigma=sig.tolist())
 
 
+def cfg3_stacked(seed: int = 33, layers: int = 28) -> Workload:
+    """The adaLN modulation linears of all `layers` blocks of a DiT stacked along N into one call: they share
+    the conditioning input (M=16, K=1152, SiLU), so the stack is one skinny layer with N = layers x 6 x 1152
+    (223 MB of int8 weights for 28 blocks) and one N-segment per block.  Chunk-wise weight std as in cfg3."""
+    rng = np.random.default_rng(seed)
+    x = _silu(rng.standard_normal((16, 1152), dtype=np.float32))
+    n_layer = 6 * 1152
+    w = rng.standard_normal((layers * n_layer, 1152), dtype=np.float32)
+    base = np.array([0.01, 0.02, 0.05, 0.1, 0.2, 0.5])
+    for l in range(layers):
+        sig = base[rng.permutation(6)]
+        for j in range(6):
+            w[l * n_layer + j * 1152:l * n_layer + (j + 1) * 1152] *= np.float32(sig[j])
+    return _finish(f"cfg3_stacked_x{layers}", x, "bf16", w, [0, 1152], [n_layer * l for l in range(layers + 1)], [1], seed,
+                   "bf16")
+
+
 def cfg4_qkv(seed: int = 4, dual: bool = False) -> Workload:
     """Fused QKV: M=8500 ragged, K=1536 single segment with 15 outlier channels x20, N=3x1536."""
     rng = np.random.default_rng(seed)
@@ -209,6 +226,7 @@ CONFIGS = {
     "cfg1": cfg1_tiny,
     "cfg2": cfg2_dit_fc2,
     "cfg3": cfg3_adaln,
+    "cfg3x28": cfg3_stacked,
     "cfg4": cfg4_qkv,
     "cfg4d": lambda seed=4: cfg4_qkv(seed, dual=True),
     "cfg5": cfg5_outproj,
