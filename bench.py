@@ -26,6 +26,7 @@ sys.path.insert(0, ROOT)
 
 INT8_MFMA_PEAK_TOPS = 5033.2   # 256 CU x 2.4 GHz x 8192 int8 ops/clk/CU (dense)
 HBM_PEAK_GBS = 8000.0
+PREROLL_MS = 80.0              # untimed load before the warm-up steps, so that the device clocks have settled
 
 # Fabric-side traffic per GEMM launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by the
 # readings of a plain 256 MiB copy kernel (profiles/bench_all_kernels_rocprofv3.txt), bytes.  None for a
@@ -91,6 +92,19 @@ def measure(name, steps, warmup, rotate_quant=True):
     def gemm():
         sq.sq_seglinear(layer, s["xq"], s["wq"], s["wscale"], None, s["y"])
 
+    # Clock ramp: the device needs some tens of milliseconds of load before its clocks settle (the first 25 steps
+    # of cfg5 run 35 % slower than the steady state, which is reached after ~100 steps).  Untimed pre-roll of
+    # about PREROLL_MS of the same step, then the W warm-up steps the caller asked for.
+    t0 = time.perf_counter()
+    quant()
+    gemm()
+    torch.cuda.synchronize()
+    est = max(time.perf_counter() - t0, 1e-5)
+    preroll = int(min(2000, max(20, PREROLL_MS * 1e-3 / est)))
+    for _ in range(preroll):
+        quant()
+        gemm()
+    torch.cuda.synchronize()
     for _ in range(warmup):
         quant()
         gemm()
@@ -243,7 +257,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": head["name"], "M": head["M"], "K": head["K"], "N": head["N"],
                    "k_segments": head["S"], "n_segments": head["T"], "dual": head["dual"],
-                   "step": "sq_quantize_act + sq_seglinear (bf16 in, bf16 out); weights pre-quantized"},
+                   "step": "sq_quantize_act + sq_seglinear (bf16 in, bf16 out); weights pre-quantized",
+                   "preroll_ms": PREROLL_MS},
         "roofline": {
             "kernel": "seglinear_mfma_kernel",
             "bound": "mfma",
