@@ -156,14 +156,78 @@ def measure(name, steps, warmup, rotate_quant=True):
     torch.cuda.synchronize()
 
     gbytes = w.seglinear_bytes("bf16")
+
+    # Skinny layers are one pass over the weights: with a single weight set the pass is served by the 256 MB
+    # Infinity Cache, so also stream over a rotation of distinct (weights, scales) sets totalling > 512 MB.
+    ms_gemm_hbm, nsets = None, 1
+    if w.M <= 64:
+        wbytes = w.N * w.K
+        nsets = int(min(64, max(2, np.ceil(600e6 / wbytes))))
+        wqs = [s["wq"]] + [s["wq"].clone() for _ in range(nsets - 1)]
+        wss = [s["wscale"]] + [s["wscale"].clone() for _ in range(nsets - 1)]
+        reps = max(2, int(np.ceil(2 * steps / nsets)))
+
+        def rot():
+            for i in range(nsets):
+                sq.sq_seglinear(layer, s["xq"], wqs[i], wss[i], None, s["y"])
+
+        rot()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            rot()
+        e1.record()
+        torch.cuda.synchronize()
+        ms_gemm_hbm = e0.elapsed_time(e1) / (reps * nsets)
+        del wqs, wss
     return dict(
+        xq_codes=s["xq"].reshape(-1),
         name=w.name, M=w.M, K=w.K, N=w.N, S=w.S, T=w.T, dual=[int(d) for d in w.dual],
         int8_ops=w.int8_ops, ms_step=ms_step, ms_gemm=ms_gemm, ms_quant=ms_quant, ms_quantize_weight=t_wq,
         gemm_tops=w.int8_ops / (ms_gemm * 1e-3) / 1e12, step_tops=w.int8_ops / (ms_step * 1e-3) / 1e12,
         ms_gemm_b2b=ms_gemm_b2b, gemm_tops_b2b=w.int8_ops / (ms_gemm_b2b * 1e-3) / 1e12,
         gemm_bytes=gbytes, gemm_gbs=gbytes / (ms_gemm * 1e-3) / 1e9, gemm_gbs_b2b=gbytes / (ms_gemm_b2b * 1e-3) / 1e9,
+        ms_gemm_hbm=ms_gemm_hbm, weight_sets=nsets,
+        gemm_gbs_hbm=(gbytes / (ms_gemm_hbm * 1e-3) / 1e9) if ms_gemm_hbm else None,
         quant_bytes=qbytes, quant_gbs=qbytes / (ms_quant * 1e-3) / 1e9, quant_rotation=nrot,
     )
+
+
+def measured_ceilings(head_setup_codes):
+    """Ceilings measured on this device, reported next to the datasheet peaks: the sustained int8 MFMA rate of a
+    register-only loop (for all-zero operands and for operands distributed like the headline layer's codes) and a
+    plain device copy over 2 x 1 GiB."""
+    import torch
+
+    import paper_2507_14811_amd as sq
+
+    out = {}
+    zeros = torch.zeros(16 << 20, dtype=torch.int8, device="cuda:0")
+    for label, codes in (("zero_operands", zeros), ("layer_like_operands", head_setup_codes)):
+        iters = 20000
+        for _ in range(3):   # ~10 ms each: lets the clocks settle at this load
+            sq.sq_probe_mfma(codes, iters)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        ops = sq.sq_probe_mfma(codes, iters)
+        e1.record()
+        torch.cuda.synchronize()
+        out["mfma_int8_tops_" + label] = round(ops / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
+    src = torch.empty(1 << 30, dtype=torch.int8, device="cuda:0")
+    dst = torch.empty(1 << 30, dtype=torch.int8, device="cuda:0")
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    out["device_copy_gbs_read_plus_write"] = round(5 * 2 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+    return out
 
 
 def cpu_baseline(name, budget_s=15.0):
@@ -196,8 +260,8 @@ def cpu_baseline(name, budget_s=15.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="cfg5", help="headline workload (cfg2 | cfg4 | cfg4d | cfg5)")
     ap.add_argument("--others", default="cfg2,cfg3,cfg3x28,cfg4,cfg4d", help="extra workloads summarised in the same line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -227,6 +291,7 @@ def main():
     del cal
 
     head = measure(args.config, args.steps, args.warmup)
+    ceilings = measured_ceilings(head.pop("xq_codes"))
     others = {}
     for name in [n for n in args.others.split(",") if n and n != args.config]:
         sq.sq_tuning_set("gemm_variant", -1)
@@ -241,6 +306,12 @@ def main():
             "quant_gbs": round(r["quant_gbs"], 1), "quant_frac_hbm_peak": round(r["quant_gbs"] / HBM_PEAK_GBS, 4),
             "ms_quantize_weight": round(r["ms_quantize_weight"], 5),
         }
+        if skinny:   # the stream from HBM (rotation over distinct weight sets) is the figure for the HBM roofline
+            others[name].update({
+                "weight_sets_rotated": r["weight_sets"], "ms_gemm_from_hbm": round(r["ms_gemm_hbm"], 5),
+                "gemm_gbs_from_hbm": round(r["gemm_gbs_hbm"], 1),
+                "gemm_frac_hbm_peak_from_hbm": round(r["gemm_gbs_hbm"] / HBM_PEAK_GBS, 4),
+                "gemm_gbs_cache_resident": round(r["gemm_gbs_b2b"], 1)})
 
     line = {
         "metric": "int8 TOPS (both dual paths) of SegLinear+DualScale GEMM; % int8 MFMA peak",
@@ -275,6 +346,7 @@ def main():
                          "bytes": head["quant_bytes"]},
         "quantize_weight_ms": round(head["ms_quantize_weight"], 5),
         "other_workloads": others,
+        "measured_ceilings": ceilings,
     }
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(args.config)

@@ -7,6 +7,7 @@ from .binding import (  # noqa: F401
     Layer,
     SqError,
     load_library,
+    sq_probe_mfma,
     sq_quantize_act,
     sq_quantize_weight,
     sq_seglinear,

@@ -176,6 +176,14 @@ sq_status sq_seglinear_debug_acc(const sq_layer* layer, const int8_t* xq, const 
   return run_gemm(layer, xq, wq, nullptr, nullptr, nullptr, acc_pos, acc_neg, sq::OUT_DEBUG_ACC, stream);
 }
 
+sq_status sq_probe_mfma(const int8_t* codes, size_t bytes, int iters, double* ops, void* stream) {
+  if (codes == nullptr || bytes < 4096 || bytes > 0xFFFFFFFFull || iters < 1 || iters > (1 << 24)) return SQ_ERR_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(codes) % 16 != 0) return SQ_ERR_INVALID_ARG;
+  if (ops) *ops = (double)sq::device_cus() * 4.0 * (double)iters * 8.0 * 65536.0;   // 2*32*32*32 per MFMA
+  hipError_t e = sq::launch_probe_mfma(codes, bytes, iters, nullptr, reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
 const char* sq_status_string(sq_status s) {
   switch (s) {
     case SQ_OK: return "SQ_OK";

@@ -34,6 +34,9 @@ hipError_t launch_seglinear_skinny(const GemmArgs& a, const GemmTable& tb, OutMo
 bool stream_supported(const GemmArgs& a, const GemmTable& tb);
 hipError_t launch_seglinear_stream(const GemmArgs& a, const GemmTable& tb, OutMode mode, int cus, hipStream_t st);
 
+// probes.hip : register-only int8 MFMA loop on every CU (benchmark ceiling)
+hipError_t launch_probe_mfma(const void* codes, size_t bytes, int iters, int* sink, hipStream_t st);
+
 // compute units of the current device (cached)
 int device_cus();
 
