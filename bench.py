@@ -194,6 +194,63 @@ def measure(name, steps, warmup, rotate_quant=True):
     )
 
 
+def measure_grouped(layers=28, steps=50):
+    """The grouped skinny call: `layers` adaLN-shaped layers (cfg3's shape and weight recipe, separate weight
+    buffers) that share one quantized input, in one launch; weight sets rotated so the stream comes from HBM."""
+    import torch
+
+    import paper_2507_14811_amd as sq
+    from paper_2507_14811_amd import workloads as wl
+
+    dev = "cuda:0"
+    w = wl.make("cfg3")
+    layer = sq.Layer.from_workload(w)
+    x = torch.from_numpy(wl.f32_to_bf16_bits(w.x).view(np.int16)).view(torch.bfloat16).to(dev)
+    xq = torch.empty((w.M, w.K), dtype=torch.int8, device=dev)
+    sq.sq_quantize_act(layer, x, xq)
+    nsets = 3                                   # 3 x 28 x 8 MB = 669 MB of weights > 2 x Infinity Cache... of 256 MB
+    sets = []
+    for si in range(nsets):
+        items = []
+        for l in range(layers):
+            wl_l = wl.make("cfg3", seed=1000 + si * layers + l)
+            wt = torch.from_numpy(wl_l.w).to(dev)
+            wq = torch.empty((w.N, w.K), dtype=torch.int8, device=dev)
+            ws = torch.empty((w.S, w.N), dtype=torch.float32, device=dev)
+            sq.sq_quantize_weight(layer, wt, wq, ws)
+            items.append((wq, ws, None, torch.empty((w.M, w.N), dtype=torch.bfloat16, device=dev)))
+        sets.append(items)
+    torch.cuda.synchronize()
+
+    def run_all():
+        for items in sets:
+            sq.sq_seglinear_grouped(layer, xq, items)
+
+    for _ in range(20):
+        run_all()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        run_all()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / (steps * nsets)
+    byt = layers * w.seglinear_bytes("bf16")
+    # the same layers one call each, for comparison
+    e0.record()
+    for _ in range(max(2, steps // 5)):
+        for items in sets:
+            for (wq, ws, b, y) in items:
+                sq.sq_seglinear(layer, xq, wq, ws, b, y)
+    e1.record()
+    torch.cuda.synchronize()
+    ms_single = e0.elapsed_time(e1) / (max(2, steps // 5) * nsets)
+    return {"layers": layers, "M": w.M, "K": w.K, "N": w.N, "ms_per_launch": round(ms, 5), "bytes": byt,
+            "gbs_from_hbm": round(byt / (ms * 1e-3) / 1e9, 1), "frac_hbm_peak": round(byt / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "ms_same_layers_one_call_each": round(ms_single, 5), "weight_sets_rotated": nsets}
+
+
 def measured_ceilings(head_setup_codes):
     """Ceilings measured on this device, reported next to the datasheet peaks: the sustained int8 MFMA rate of a
     register-only loop (for all-zero operands and for operands distributed like the headline layer's codes) and a
@@ -292,6 +349,7 @@ def main():
 
     head = measure(args.config, args.steps, args.warmup)
     ceilings = measured_ceilings(head.pop("xq_codes"))
+    grouped = measure_grouped() if "cfg3" in args.others.split(",") else None
     others = {}
     for name in [n for n in args.others.split(",") if n and n != args.config]:
         sq.sq_tuning_set("gemm_variant", -1)
@@ -346,6 +404,7 @@ def main():
                          "bytes": head["quant_bytes"]},
         "quantize_weight_ms": round(head["ms_quantize_weight"], 5),
         "other_workloads": others,
+        "grouped_skinny": grouped,
         "measured_ceilings": ceilings,
     }
     if not args.no_cpu_baseline:

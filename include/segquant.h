@@ -52,6 +52,7 @@ extern "C" {
 #define SQ_MAX_SEGMENTS 64
 #define SQ_MAX_SEG_SCALE 512
 #define SQ_MAX_KSEG_LEN 133143
+#define SQ_MAX_GROUP 64
 
 typedef enum { SQ_OK = 0, SQ_ERR_INVALID_ARG = 1, SQ_ERR_UNSUPPORTED = 2, SQ_ERR_LAUNCH = 3 } sq_status;
 typedef enum { SQ_F32 = 0, SQ_BF16 = 1 } sq_dtype;
@@ -112,6 +113,28 @@ sq_status sq_quantize_act(const sq_layer* layer, const void* x, sq_dtype x_dt, i
 sq_status sq_seglinear(const sq_layer* layer, const int8_t* xq, const int8_t* wq,
                        const float* wscale, const float* bias, void* y, sq_dtype y_dt,
                        void* stream);
+
+/*
+ * Grouped skinny call: L linear layers of ONE shape (layer->M <= 32 tokens, K, N) that consume the SAME quantized
+ * input, e.g. the modulation (adaLN) linears of all blocks of a diffusion transformer, which share the SiLU of the
+ * conditioning vector (output-segmented, polarity-asymmetric layers of Sec. 4.2.2 item 1 / Sec. 4.3.2).  One
+ * launch streams all L weight matrices; per layer the arithmetic is exactly that of sq_seglinear.
+ *   layer   shape, K-segments, dual flags and activation steps shared by the L layers; seg_scale must be NULL
+ *   xq      dev int8 [M][K], from sq_quantize_act
+ *   items   HOST array of L entries {wq dev int8 [N][K], wscale dev fp32 [S][N], bias dev fp32 [N] or NULL,
+ *           y dev [M][N] of y_dt}; read during the call only; wq 16-byte aligned
+ * Returns SQ_ERR_UNSUPPORTED when M > 32, L > SQ_MAX_GROUP, K or a K-segment boundary is not a multiple of 128,
+ * seg_scale is given, or M*K exceeds the on-chip budget (call sq_seglinear per layer instead).
+ */
+typedef struct sq_group_item {
+  const int8_t* wq;
+  const float* wscale;
+  const float* bias;
+  void* y;
+} sq_group_item;
+
+sq_status sq_seglinear_grouped(const sq_layer* layer, const int8_t* xq, int32_t L, const sq_group_item* items,
+                               sq_dtype y_dt, void* stream);
 
 /*
  * Parity instrument: runs the same main loop as sq_seglinear (same kernel selection) and stores the

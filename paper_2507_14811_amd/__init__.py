@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     sq_quantize_weight,
     sq_seglinear,
     sq_seglinear_debug_acc,
+    sq_seglinear_grouped,
     sq_tuning_set,
     sq_version,
     status_string,

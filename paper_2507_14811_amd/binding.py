@@ -21,13 +21,17 @@ SQ_MAX_SEG_SCALE = 512
 SQ_MAX_KSEG_LEN = 133143
 
 EXPORTS = ("sq_quantize_weight", "sq_quantize_act", "sq_seglinear", "sq_seglinear_debug_acc",
-           "sq_status_string", "sq_version", "sq_tuning_set", "sq_probe_mfma")
+           "sq_status_string", "sq_version", "sq_tuning_set", "sq_probe_mfma", "sq_seglinear_grouped")
 
 
 class SqError(RuntimeError):
     def __init__(self, status: int, what: str):
         self.status = status
         super().__init__(f"{what}: {status_string(status)}")
+
+
+class sq_group_item(C.Structure):
+    _fields_ = [("wq", C.c_void_p), ("wscale", C.c_void_p), ("bias", C.c_void_p), ("y", C.c_void_p)]
 
 
 class sq_layer(C.Structure):
@@ -63,6 +67,8 @@ def load_library() -> C.CDLL:
     lib.sq_seglinear_debug_acc.argtypes = [lp, vp, vp, vp, vp, vp]
     for f in (lib.sq_quantize_weight, lib.sq_quantize_act, lib.sq_seglinear, lib.sq_seglinear_debug_acc):
         f.restype = i32
+    lib.sq_seglinear_grouped.argtypes = [lp, vp, i32, C.POINTER(sq_group_item), i32, vp]
+    lib.sq_seglinear_grouped.restype = i32
     lib.sq_probe_mfma.argtypes = [vp, C.c_size_t, i32, C.POINTER(C.c_double), vp]
     lib.sq_probe_mfma.restype = i32
     lib.sq_status_string.argtypes = [i32]
@@ -169,6 +175,18 @@ def sq_seglinear(layer: Layer, xq, wq, wscale, bias, y, stream=None) -> None:
     """int8 x int8 -> int32 per K-segment and polarity, dequantized into y [M][N] fp32/bf16."""
     _check(load_library().sq_seglinear(C.byref(layer.c), _dptr(xq), _dptr(wq), _dptr(wscale), _dptr(bias),
                                        _dptr(y), _dt(y), _stream(stream)), "sq_seglinear")
+
+
+def sq_seglinear_grouped(layer: Layer, xq, items, stream=None) -> None:
+    """L layers of one shape sharing xq in one launch.  items: sequence of (wq, wscale, bias or None, y) device tensors;
+    all y of one dtype."""
+    n = len(items)
+    arr = (sq_group_item * max(n, 1))()
+    for i, (wq, wscale, bias, y) in enumerate(items):
+        arr[i] = sq_group_item(wq.data_ptr(), wscale.data_ptr(), None if bias is None else bias.data_ptr(), y.data_ptr())
+    ydt = _dt(items[0][3]) if n else SQ_F32
+    _check(load_library().sq_seglinear_grouped(C.byref(layer.c), _dptr(xq), n, arr, ydt, _stream(stream)),
+           "sq_seglinear_grouped")
 
 
 def sq_seglinear_debug_acc(layer: Layer, xq, wq, acc_pos, acc_neg, stream=None) -> None:

@@ -167,6 +167,41 @@ sq_status sq_seglinear(const sq_layer* layer, const int8_t* xq, const int8_t* wq
                   y_dt == SQ_BF16 ? sq::OUT_BF16 : sq::OUT_F32, stream);
 }
 
+sq_status sq_seglinear_grouped(const sq_layer* layer, const int8_t* xq, int32_t L, const sq_group_item* items,
+                               sq_dtype y_dt, void* stream) {
+  sq_status st = check_layer(layer, true, true);
+  if (st != SQ_OK) return st;
+  if (xq == nullptr || items == nullptr || L < 1) return SQ_ERR_INVALID_ARG;
+  if (y_dt != SQ_F32 && y_dt != SQ_BF16) return SQ_ERR_INVALID_ARG;
+  if (L > SQ_MAX_GROUP || layer->seg_scale != nullptr) return SQ_ERR_UNSUPPORTED;
+  sq::GroupTable gt;
+  std::memset(&gt, 0, sizeof(gt));
+  gt.L = L;
+  for (int l = 0; l < L; ++l) {
+    if (items[l].wq == nullptr || items[l].wscale == nullptr || items[l].y == nullptr) return SQ_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(items[l].wq) % 16 != 0) return SQ_ERR_UNSUPPORTED;
+    gt.item[l] = {items[l].wq, items[l].wscale, items[l].bias, items[l].y};
+  }
+  sq::GroupSegTable tb;
+  std::memset(&tb, 0, sizeof(tb));
+  tb.S = layer->S;
+  for (int s = 0; s <= layer->S; ++s) tb.kseg_off[s] = layer->kseg_off[s];
+  for (int s = 0; s < layer->S; ++s) {
+    tb.dual[s] = layer->dual[s] ? 1 : 0;
+    tb.s_pos[s] = layer->s_pos[s];
+    tb.s_neg[s] = layer->dual[s] ? layer->s_neg[s] : 0.0f;
+  }
+  sq::GemmArgs a{};
+  a.xq = xq;
+  a.M = layer->M;
+  a.K = layer->K;
+  a.N = layer->N;
+  if (!sq::stream_grouped_supported(a, tb)) return SQ_ERR_UNSUPPORTED;
+  hipError_t e = sq::launch_seglinear_grouped(a, tb, gt, y_dt == SQ_BF16 ? sq::OUT_BF16 : sq::OUT_F32, sq::device_cus(),
+                                              reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
 sq_status sq_seglinear_debug_acc(const sq_layer* layer, const int8_t* xq, const int8_t* wq, int32_t* acc_pos,
                                  int32_t* acc_neg, void* stream) {
   sq_status st = check_layer(layer, true, false);

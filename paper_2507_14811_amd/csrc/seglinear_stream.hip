@@ -33,16 +33,22 @@ struct StreamCfg {
   static_assert(LDS <= 160 * 1024, "LDS budget");
 };
 
-template <int MT, bool DUAL, int SLAB_KB>
-__global__ __launch_bounds__(kStreamWaves * 64) void seglinear_stream_kernel(const GemmArgs a, const GemmTable tb, const int mode) {
+// TB: GemmTable (one layer; GT = NoGroups) or GroupSegTable (GT = GroupTable: L layers of the same shape that share
+// X^ and its steps; the 16-column groups of all layers form one list, layer = group / groups per layer).
+template <int MT, bool DUAL, int SLAB_KB, class TB, class GT>
+__global__ __launch_bounds__(kStreamWaves * 64) void seglinear_stream_kernel(const GemmArgs a, const TB tb, const GT gt, const int mode) {
   using C = StreamCfg<MT, SLAB_KB>;
+  constexpr bool GROUPED = std::is_same<GT, GroupTable>::value;
   constexpr int RING = C::RING, STEP = C::STEP;
   __shared__ __attribute__((aligned(1024))) char smem[C::LDS];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
   // ---- this wave's run of 16-column groups ------------------------------------------------------------
-  const int ngroups = (a.N + 15) >> 4;
+  const int gpl = (a.N + 15) >> 4;                                 // groups per layer
+  int nlayers = 1;
+  if constexpr (GROUPED) nlayers = gt.L;
+  const int ngroups = gpl * nlayers;
   // waves are ranked workgroup-interleaved, so a layer with fewer groups than waves still spreads over all CUs
   const int nwaves = gridDim.x * kStreamWaves, wid = wave * gridDim.x + blockIdx.x;
   const int gper = ngroups / nwaves, grem = ngroups % nwaves;
@@ -57,17 +63,24 @@ __global__ __launch_bounds__(kStreamWaves * 64) void seglinear_stream_kernel(con
   const int lrow = lane >> 3, lslot = lane & 7;
   int ig = 0, it = 0, issued_steps = 0, islot = 0;
   uint32_t voff[2];
+  const int8_t* iwq = a.wq;                                        // weights of the layer being fetched
   auto set_issue_group = [&](const int g) __attribute__((always_inline)) {
+    int gl = g_begin + g;
+    if constexpr (GROUPED) {
+      const int l = gl / gpl;
+      gl -= l * gpl;
+      iwq = gt.item[l].wq;
+    }
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       const int rt = 8 * h + lrow;
-      int r = (g_begin + g) * 16 + rt;
+      int r = gl * 16 + rt;
       r = r < a.N ? r : a.N - 1;                                   // ragged N: re-read the last row, masked at the store
       voff[h] = (uint32_t)r * (uint32_t)a.K + (uint32_t)((lslot ^ row_swizzle<128>(rt)) << 4);
     }
   };
   auto issue_step = [&]() __attribute__((always_inline)) {
-    const uint64_t u = reinterpret_cast<uint64_t>(a.wq + ((size_t)it << 7));
+    const uint64_t u = reinterpret_cast<uint64_t>(iwq + ((size_t)it << 7));
     const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)u), hi = __builtin_amdgcn_readfirstlane((uint32_t)(u >> 32));
     const int8_t* base = reinterpret_cast<const int8_t*>(((uint64_t)hi << 32) | lo);
     const uint32_t so = __builtin_amdgcn_readfirstlane(ring_lds + (uint32_t)islot * (uint32_t)STEP);
@@ -107,14 +120,27 @@ __global__ __launch_bounds__(kStreamWaves * 64) void seglinear_stream_kernel(con
   const int xrow = frow * (a.K + 16) + 16 * fq;
 
   const int mlane = lane & 15;                                     // token row inside a 16-row tile
-  const bool vec4 = (a.N % 4) == 0 &&
-                    ((reinterpret_cast<uintptr_t>(a.y) | reinterpret_cast<uintptr_t>(a.wscale) | reinterpret_cast<uintptr_t>(a.bias) |
-                      reinterpret_cast<uintptr_t>(a.acc_pos) | reinterpret_cast<uintptr_t>(a.acc_neg)) % 16 == 0);
+  bool vec4 = (a.N % 4) == 0 &&
+              ((reinterpret_cast<uintptr_t>(a.y) | reinterpret_cast<uintptr_t>(a.wscale) | reinterpret_cast<uintptr_t>(a.bias) |
+                reinterpret_cast<uintptr_t>(a.acc_pos) | reinterpret_cast<uintptr_t>(a.acc_neg)) % 16 == 0);
 
   int done_steps = 0, cslot = 0;
 #pragma unroll 1
   for (int g = 0; g < g_cnt; ++g) {
-    const int ncol = (g_begin + g) * 16 + 4 * fq;                  // this lane's four output columns
+    int gl = g_begin + g;                                          // group inside its layer
+    const float* l_wscale = a.wscale;
+    const float* l_bias = a.bias;
+    void* l_y = a.y;
+    if constexpr (GROUPED) {
+      const int l = gl / gpl;
+      gl -= l * gpl;
+      l_wscale = gt.item[l].wscale;
+      l_bias = gt.item[l].bias;
+      l_y = gt.item[l].y;
+      vec4 = (a.N % 4) == 0 && ((reinterpret_cast<uintptr_t>(l_y) | reinterpret_cast<uintptr_t>(l_wscale) |
+                                  reinterpret_cast<uintptr_t>(l_bias)) % 16 == 0);
+    }
+    const int ncol = gl * 16 + 4 * fq;                             // this lane's four output columns
     v4f fsum[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) fsum[mt] = (v4f)(0.0f);
@@ -186,7 +212,7 @@ __global__ __launch_bounds__(kStreamWaves * 64) void seglinear_stream_kernel(con
         }
       } else {
         float cw[4];
-        const float* ws = a.wscale + (size_t)ks * a.N;
+        const float* ws = l_wscale + (size_t)ks * a.N;
         if (vec4 && ncol + 3 < a.N) {
           const v4f w4 = *reinterpret_cast<const v4f*>(ws + ncol);
 #pragma unroll
@@ -195,9 +221,11 @@ __global__ __launch_bounds__(kStreamWaves * 64) void seglinear_stream_kernel(con
 #pragma unroll
           for (int r = 0; r < 4; ++r) cw[r] = (ncol + r < a.N) ? ws[ncol + r] : 0.0f;
         }
-        if (tb.has_seg_scale) {
+        if constexpr (!GROUPED) {
+          if (tb.has_seg_scale) {
 #pragma unroll
-          for (int r = 0; r < 4; ++r) cw[r] *= seg_scale_of(tb, ks, ncol + r);
+            for (int r = 0; r < 4; ++r) cw[r] *= seg_scale_of(tb, ks, ncol + r);
+          }
         }
         const float sp = tb.s_pos[ks], sn = dl ? tb.s_neg[ks] : 0.0f;
 #pragma unroll
@@ -214,7 +242,7 @@ __global__ __launch_bounds__(kStreamWaves * 64) void seglinear_stream_kernel(con
     if (mode != OUT_DEBUG_ACC) {
       float bs[4];
 #pragma unroll
-      for (int r = 0; r < 4; ++r) bs[r] = (a.bias && ncol + r < a.N) ? a.bias[ncol + r] : 0.0f;
+      for (int r = 0; r < 4; ++r) bs[r] = (l_bias && ncol + r < a.N) ? l_bias[ncol + r] : 0.0f;
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
         const int m = mt * 16 + mlane;
@@ -226,19 +254,19 @@ __global__ __launch_bounds__(kStreamWaves * 64) void seglinear_stream_kernel(con
           if (vec4 && ncol + 3 < a.N) {
             if (mode == OUT_F32) {
               const v4f o4 = {t[0], t[1], t[2], t[3]};
-              *reinterpret_cast<v4f*>(reinterpret_cast<float*>(a.y) + o) = o4;
+              *reinterpret_cast<v4f*>(reinterpret_cast<float*>(l_y) + o) = o4;
             } else {
               v2i o2;
               o2[0] = (int)f32x2_to_bf16x2(t[0], t[1]);
               o2[1] = (int)f32x2_to_bf16x2(t[2], t[3]);
-              *reinterpret_cast<v2i*>(reinterpret_cast<uint16_t*>(a.y) + o) = o2;
+              *reinterpret_cast<v2i*>(reinterpret_cast<uint16_t*>(l_y) + o) = o2;
             }
           } else {
 #pragma unroll
             for (int r = 0; r < 4; ++r)
               if (ncol + r < a.N) {
-                if (mode == OUT_F32) reinterpret_cast<float*>(a.y)[o + r] = t[r];
-                else reinterpret_cast<uint16_t*>(a.y)[o + r] = f32_to_bf16(t[r]);
+                if (mode == OUT_F32) reinterpret_cast<float*>(l_y)[o + r] = t[r];
+                else reinterpret_cast<uint16_t*>(l_y)[o + r] = f32_to_bf16(t[r]);
               }
           }
         }
@@ -268,8 +296,8 @@ bool stream_supported(const GemmArgs& a, const GemmTable& tb) {
 
 template <int MT, int SLAB_KB>
 static hipError_t launch_stream_ms(const GemmArgs& a, const GemmTable& tb, int mode, bool dual, int grid, hipStream_t st) {
-  if (dual) hipLaunchKernelGGL((seglinear_stream_kernel<MT, true, SLAB_KB>), dim3(grid), dim3(kStreamWaves * 64), 0, st, a, tb, mode);
-  else hipLaunchKernelGGL((seglinear_stream_kernel<MT, false, SLAB_KB>), dim3(grid), dim3(kStreamWaves * 64), 0, st, a, tb, mode);
+  if (dual) hipLaunchKernelGGL((seglinear_stream_kernel<MT, true, SLAB_KB, GemmTable, NoGroups>), dim3(grid), dim3(kStreamWaves * 64), 0, st, a, tb, NoGroups{}, mode);
+  else hipLaunchKernelGGL((seglinear_stream_kernel<MT, false, SLAB_KB, GemmTable, NoGroups>), dim3(grid), dim3(kStreamWaves * 64), 0, st, a, tb, NoGroups{}, mode);
   return hipGetLastError();
 }
 
@@ -289,6 +317,35 @@ hipError_t launch_seglinear_stream(const GemmArgs& a, const GemmTable& tb, OutMo
     default: return SQ_STREAM(4);
   }
 #undef SQ_STREAM
+}
+
+// Grouped call: L layers of one shape that share X^ (M <= 32).  a.wq / a.wscale / a.bias / a.y are unused.
+bool stream_grouped_supported(const GemmArgs& a, const GroupSegTable& tb) {
+  if (a.M > 32 || a.K % 128 != 0) return false;
+  for (int s = 0; s <= tb.S; ++s)
+    if (tb.kseg_off[s] % 128 != 0) return false;
+  if (reinterpret_cast<uintptr_t>(a.xq) % 16 != 0) return false;
+  return stream_slab_kb(a) != 0;
+}
+
+template <int MT, int SLAB_KB>
+static hipError_t launch_grouped_ms(const GemmArgs& a, const GroupSegTable& tb, const GroupTable& gt, int mode, bool dual,
+                                    int grid, hipStream_t st) {
+  if (dual) hipLaunchKernelGGL((seglinear_stream_kernel<MT, true, SLAB_KB, GroupSegTable, GroupTable>), dim3(grid), dim3(kStreamWaves * 64), 0, st, a, tb, gt, mode);
+  else hipLaunchKernelGGL((seglinear_stream_kernel<MT, false, SLAB_KB, GroupSegTable, GroupTable>), dim3(grid), dim3(kStreamWaves * 64), 0, st, a, tb, gt, mode);
+  return hipGetLastError();
+}
+
+hipError_t launch_seglinear_grouped(const GemmArgs& a, const GroupSegTable& tb, const GroupTable& gt, OutMode mode, int cus,
+                                    hipStream_t st) {
+  bool dual = false;
+  for (int s = 0; s < tb.S; ++s) dual = dual || tb.dual[s];
+  const int mt = (a.M + 15) / 16;
+  const long ngroups = (long)((a.N + 15) / 16) * gt.L;
+  const int grid = (int)(ngroups < cus ? ngroups : cus);
+  const int slab = stream_slab_kb(a);
+  if (mt == 1) return slab == 24 ? launch_grouped_ms<1, 24>(a, tb, gt, mode, dual, grid, st) : launch_grouped_ms<1, 80>(a, tb, gt, mode, dual, grid, st);
+  return slab == 24 ? launch_grouped_ms<2, 24>(a, tb, gt, mode, dual, grid, st) : launch_grouped_ms<2, 80>(a, tb, gt, mode, dual, grid, st);
 }
 
 }  // namespace sq

@@ -43,6 +43,27 @@ struct GemmTable {                     // for the SegLinear GEMM kernels
   float seg_scale[SQ_MAX_SEG_SCALE];   // [ks][ns], valid when has_seg_scale
 };
 
+// Slim segment table + per-layer pointers of the grouped skinny call (several layers that share X^ in one launch).
+struct GroupSegTable {
+  int S;
+  int kseg_off[SQ_MAX_SEGMENTS + 1];
+  float s_pos[SQ_MAX_SEGMENTS];
+  float s_neg[SQ_MAX_SEGMENTS];
+  int dual[SQ_MAX_SEGMENTS];
+  static constexpr int has_seg_scale = 0;     // the grouped call takes no per-block multiplier
+};
+struct GroupItem {
+  const int8_t* wq;      // [N][K]
+  const float* wscale;   // [S][N]
+  const float* bias;     // [N] or nullptr
+  void* y;               // [M][N]
+};
+struct GroupTable {
+  int L;
+  GroupItem item[SQ_MAX_GROUP];
+};
+struct NoGroups {};
+
 struct GemmArgs {
   const int8_t* xq;        // [M][K] polarity-merged activation codes
   const int8_t* wq;        // [N][K]

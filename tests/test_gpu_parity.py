@@ -235,6 +235,68 @@ def test_stream_rejects_unaligned_k(oracle):
     sq.sq_tuning_set("force_path", -1)
 
 
+GROUPED = [
+    dict(M=16, K=1152, N=1152, L=5, kseg=[0, 1152], dual=[1], ydt="bf16"),
+    dict(M=7, K=256, N=100, L=3, kseg=[0, 128, 256], dual=[1, 0], ydt="f32"),        # ragged N, two K-segments
+    dict(M=32, K=384, N=528, L=64, kseg=[0, 384], dual=[0], ydt="bf16"),              # the maximum group, single path
+    dict(M=1, K=128, N=16, L=1, kseg=[0, 128], dual=[1], ydt="f32"),
+    dict(M=16, K=640, N=4240, L=9, kseg=[0, 256, 640], dual=[0, 1], ydt="bf16"),     # runs of groups cross layer boundaries
+]
+
+
+@pytest.mark.parametrize("case", GROUPED)
+def test_seglinear_grouped(oracle, case):
+    """L layers that share the quantized input, one launch: every layer's output against the oracle's, layer by layer."""
+    import torch
+
+    g = _gpu()
+    M, K, N, L = case["M"], case["K"], case["N"], case["L"]
+    base = wl.random_layer(M, K, N, case["kseg"], [0, N], case["dual"], seed=K + L, x_dtype="bf16", act="silu", with_bias=True)
+    gl = g.GpuLayer(base)
+    gl.quantize_act()
+    rng = np.random.default_rng(L * 1000 + N)
+    tdt = torch.bfloat16 if case["ydt"] == "bf16" else torch.float32
+    items, hosts = [], []
+    for l in range(L):
+        wl_l = (rng.standard_normal((N, K)) * (0.01 * (1 + l % 5))).astype(np.float32)
+        bias_l = None if l % 3 == 2 else rng.standard_normal(N).astype(np.float32)
+        wt = torch.from_numpy(wl_l).to(g.DEV)
+        wq = torch.empty((N, K), dtype=torch.int8, device=g.DEV)
+        ws = torch.empty((base.S, N), dtype=torch.float32, device=g.DEV)
+        sq.sq_quantize_weight(gl.layer, wt, wq, ws)
+        y = torch.full((M, N), float("nan"), dtype=tdt, device=g.DEV)
+        items.append((wq, ws, None if bias_l is None else torch.from_numpy(bias_l).to(g.DEV), y))
+        hosts.append((wl_l, bias_l))
+    sq.sq_seglinear_grouped(gl.layer, gl.xq, items)
+    torch.cuda.synchronize()
+    for l in range(L):
+        wl_l, bias_l = hosts[l]
+        r = oracle.seglinear(base.x, wl_l, base.kseg_off, base.nseg_off, base.dual, base.s_pos, base.s_neg, None, bias_l)
+        assert np.array_equal(items[l][0].cpu().numpy(), r.wq)
+        ymax = float(np.abs(r.y32).max())
+        if case["ydt"] == "f32":
+            y = items[l][3].cpu().numpy()
+            assert not np.isnan(y).any()
+            err = float(np.abs(y.astype(np.float64) - r.y32.astype(np.float64)).max())
+            assert err <= RTOL * ymax, f"layer {l}: fp32 output error {err} > {RTOL} * {ymax}"
+        else:
+            g.check_bf16_against(g.bf16_tensor_bits(items[l][3]), r.y32, r.y_bf16_bits, RTOL * ymax)
+
+
+def test_grouped_rejects_what_it_cannot_run(oracle):
+    import torch
+
+    g = _gpu()
+    w = wl.random_layer(40, 256, 64, [0, 256], [0, 64], [1], seed=1, x_dtype="bf16", act="silu")   # M > 32
+    gl = g.GpuLayer(w)
+    gl.quantize_weight()
+    gl.quantize_act()
+    y = torch.empty((40, 64), dtype=torch.float32, device=g.DEV)
+    with pytest.raises(sq.SqError) as e:
+        sq.sq_seglinear_grouped(gl.layer, gl.xq, [(gl.wq, gl.wscale, None, y)])
+    assert e.value.status == 2
+
+
 GENERIC = [
     dict(M=7, K=100, N=13, kseg=[0, 37, 100], nseg=[0, 5, 13], dual=[1, 0]),
     dict(M=70, K=96, N=65, kseg=[0, 96], nseg=[0, 65], dual=[1]),

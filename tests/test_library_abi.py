@@ -102,6 +102,16 @@ def test_invalid_arguments_are_rejected_on_the_host(sq):
     assert lib.sq_quantize_weight(C.byref(w.c), None, 0, FAKE, FAKE, None) == INVALID
     assert lib.sq_quantize_weight(C.byref(w.c), FAKE, 3, FAKE, FAKE, None) == INVALID
     assert lib.sq_seglinear_debug_acc(C.byref(w.c), FAKE, FAKE, FAKE, None, FAKE, None) == INVALID
+    # grouped call: NULL item table, empty group, oversized group, NULL member, per-block multiplier
+    from paper_2507_14811_amd.binding import sq_group_item
+    one = (sq_group_item * 1)(sq_group_item(0x1000, 0x1000, None, 0x1000))
+    assert lib.sq_seglinear_grouped(C.byref(ok.c), FAKE, 1, None, 0, None) == INVALID
+    assert lib.sq_seglinear_grouped(C.byref(ok.c), FAKE, 0, one, 0, None) == INVALID
+    assert lib.sq_seglinear_grouped(C.byref(ok.c), FAKE, 65, one, 0, None) == UNSUPPORTED
+    bad = (sq_group_item * 1)(sq_group_item(0x1000, None, None, 0x1000))
+    assert lib.sq_seglinear_grouped(C.byref(ok.c), FAKE, 1, bad, 0, None) == INVALID
+    assert lib.sq_seglinear_grouped(C.byref(_layer(sq, seg_scale=[[1.0]]).c), FAKE, 1, one, 0, None) == UNSUPPORTED
+    assert lib.sq_seglinear_grouped(C.byref(ok.c), FAKE, 1, one, 7, None) == INVALID
 
 
 def test_missing_library_fails_loudly(monkeypatch, sq):
