@@ -297,6 +297,45 @@ def test_grouped_rejects_what_it_cannot_run(oracle):
     assert e.value.status == 2
 
 
+def test_graph_capture_and_replay(oracle):
+    """The calls allocate nothing and take their tables by value, so a step can be captured in a HIP graph.  Replay it
+    several times with eager work and synchronisations in between, on fresh inputs, and check every replay."""
+    import torch
+
+    g = _gpu()
+    w = wl.random_layer(300, 1024, 520, [0, 256, 1024], [0, 520], [0, 1], seed=21, x_dtype="bf16", act="gelu", with_bias=True)
+    gl = g.GpuLayer(w)
+    gl.quantize_weight()
+    sq.sq_tuning_set("force_path", -1)
+    sq.sq_tuning_set("gemm_variant", -1)
+    y = torch.zeros((w.M, w.N), dtype=torch.float32, device=g.DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):           # warm-up outside the capture
+        sq.sq_quantize_act(gl.layer, gl.x, gl.xq)
+        sq.sq_seglinear(gl.layer, gl.xq, gl.wq, gl.wscale, gl.bias, y)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        sq.sq_quantize_act(gl.layer, gl.x, gl.xq)
+        sq.sq_seglinear(gl.layer, gl.xq, gl.wq, gl.wscale, gl.bias, y)
+    rng = np.random.default_rng(5)
+    for rep in range(3):
+        xs = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits((w.x * (1.0 + 0.1 * rep) + 0.01 * rng.standard_normal(w.x.shape)).astype(np.float32)))
+        xs = np.clip(xs, w.x.min(), w.x.max()).astype(np.float32)       # stay inside the calibrated range: same steps
+        gl.x.copy_(torch.from_numpy(wl.f32_to_bf16_bits(xs).view(np.int16)).view(torch.bfloat16).to(g.DEV))
+        y.fill_(float("nan"))                                           # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        r = oracle.seglinear(xs, w.w, w.kseg_off, w.nseg_off, w.dual, w.s_pos, w.s_neg, None, w.bias)
+        xq = gl.xq.cpu().numpy()
+        assert np.array_equal(xq.astype(np.int16), r.xq_pos.astype(np.int16) + r.xq_neg.astype(np.int16)), f"replay {rep}"
+        err = float(np.abs(y.cpu().numpy().astype(np.float64) - r.y32).max())
+        assert err <= RTOL * float(np.abs(r.y32).max()), f"replay {rep}: {err}"
+
+
 GENERIC = [
     dict(M=7, K=100, N=13, kseg=[0, 37, 100], nseg=[0, 5, 13], dual=[1, 0]),
     dict(M=70, K=96, N=65, kseg=[0, 96], nseg=[0, 65], dual=[1]),
