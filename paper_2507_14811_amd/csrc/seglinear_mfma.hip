@@ -62,7 +62,7 @@ bool mfma_supported(const GemmArgs& a, const GemmTable& tb) {
 // shape, measured on MI355X per layer class (single-path / dual / dual with several K-segments).
 static const float kEffSingle[kNumMfmaVariants] = {1.00f, 0.85f, 0.82f, 0.62f, 0.95f, 0.95f, 0.72f, 0.71f, 0.88f};
 static const float kEffDual[kNumMfmaVariants] = {1.00f, 0.78f, 0.77f, 0.65f, 0.00f, 0.76f, 0.70f, 0.77f, 0.88f};
-static const float kEffDualMulti[kNumMfmaVariants] = {1.00f, 0.89f, 0.86f, 0.72f, 0.00f, 0.80f, 0.81f, 0.85f, 0.86f};
+static const float kEffDualMulti[kNumMfmaVariants] = {1.00f, 0.78f, 0.76f, 0.65f, 0.00f, 0.87f, 0.72f, 0.75f, 0.90f};
 
 // Compute units of the current device (MI355X: 256), looked up once per device.
 int device_cus() {

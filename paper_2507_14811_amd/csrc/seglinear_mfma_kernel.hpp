@@ -236,16 +236,20 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
   };
   auto issue_end = [&]() __attribute__((always_inline)) {
     ++ikt;
-    if (++ik == ik_end) {
-      if (ipos + 1 < tb.S) {
-        ++ipos;
-      } else if (iit + 1 < ntile_wg) {          // on to the next tile of this workgroup
-        set_issue_tile(++iit);
-        ipos = 0;
-      } else {
-        return;                                 // nothing left to fetch (the callers check ikt < nkt first)
-      }
-      iks = tb.seg_order[ipos];
+    if (++ik == ik_end && ipos + 1 < tb.S) {
+      iks = tb.seg_order[++ipos];
+      ik = tb.kseg_off[iks] >> KSH;
+      ik_end = tb.kseg_off[iks + 1] >> KSH;
+    }
+  };
+  // Moving the fetch cursor to the next tile recomputes the per-lane addresses.  It is kept out of the K loops
+  // (which run at most to the end of the tile being fetched, see run_segment): inside them the recomputation's
+  // spill reloads would come with compiler-inserted vmcnt waits that drain the direct-load pipeline every stage.
+  auto issue_next_tile_if_done = [&]() __attribute__((always_inline)) {
+    if (ikt == (iit + 1) * nkt_tile && iit + 1 < ntile_wg) {
+      set_issue_tile(++iit);
+      ipos = 0;
+      iks = tb.seg_order[0];
       ik = tb.kseg_off[iks] >> KSH;
       ik_end = tb.kseg_off[iks + 1] >> KSH;
     }
@@ -257,6 +261,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
 #pragma unroll
     for (int e = 0; e < LT; ++e) issue_slot(e);
     issue_end();
+    issue_next_tile_if_done();
   }
   // all loads of stage s have landed in this wave's view (loads return in order)
   auto wait_landed = [&](const int s) __attribute__((always_inline)) {
@@ -393,19 +398,27 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
       issue_group(0);
       tail_steps(dl_tag, std::true_type{}, kt);
       issue_end();
+      issue_next_tile_if_done();
     } else {
       tail_steps(dl_tag, std::false_type{}, kt);
     }
     int b = kt;
     const int b_more_end = (kt_end - 1) < (nkt - NSTAGE) ? (kt_end - 1) : (nkt - NSTAGE);
 #pragma unroll 1
-    for (; b < b_more_end; ++b) {
-      wait_landed(b + 1);
-      __syncthreads();
-      issue_begin();
-      kstep(dl_tag, std::true_type{}, std::integral_constant<int, 0>{}, LASTSET, stage_off(b + 1) + foff[0]);
-      tail_steps(dl_tag, std::true_type{}, b + 1);
-      issue_end();
+    while (b < b_more_end) {
+      // one run of the loop issues one stage per iteration and stays inside the tile being fetched
+      const int left = (iit + 1) * nkt_tile - ikt;
+      const int stop = (b + left) < b_more_end ? (b + left) : b_more_end;
+#pragma unroll 1
+      for (; b < stop; ++b) {
+        wait_landed(b + 1);
+        __syncthreads();
+        issue_begin();
+        kstep(dl_tag, std::true_type{}, std::integral_constant<int, 0>{}, LASTSET, stage_off(b + 1) + foff[0]);
+        tail_steps(dl_tag, std::true_type{}, b + 1);
+        issue_end();
+      }
+      issue_next_tile_if_done();
     }
 #pragma unroll 1
     for (; b < kt_end - 1; ++b) {
@@ -697,25 +710,40 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
         pin_accumulators();
         flush_mid(ks, true, true);
       }
+      // middle segments in a loop, the last one peeled: with the store epilogue as an alternative inside the
+      // loop the accumulators' register assignment has to agree on both ways round it, which costs spills
 #pragma unroll 1
-      for (int pos = 1; pos < tb.S; ++pos) {
+      for (int pos = 1; pos + 1 < tb.S; ++pos) {
         const int ks = tb.seg_order[pos];
         run_segment(std::false_type{}, (tb.kseg_off[ks + 1] - tb.kseg_off[ks]) >> KSH);
         pin_accumulators();
-        if (pos == tb.S - 1) flush_last(ks, false, false);
-        else flush_mid(ks, false, false);
+        flush_mid(ks, false, false);
+      }
+      {
+        const int ks = tb.seg_order[tb.S - 1];
+        run_segment(std::false_type{}, (tb.kseg_off[ks + 1] - tb.kseg_off[ks]) >> KSH);
+        pin_accumulators();
+        flush_last(ks, false, false);
       }
     } else {
 #pragma unroll 1
-      for (int pos = 0; pos < tb.S; ++pos) {
+      for (int pos = 0; pos + 1 < tb.S; ++pos) {
         const int ks = tb.seg_order[pos];
         const bool dl = DUAL && (tb.dual[ks] != 0);
         const int nst = (tb.kseg_off[ks + 1] - tb.kseg_off[ks]) >> KSH;
         if (dl) run_segment(std::integral_constant<bool, DUAL>{}, nst);
         else run_segment(std::integral_constant<bool, false>{}, nst);
         pin_accumulators();
-        if (pos == tb.S - 1) flush_last(ks, dl, pos == 0);
-        else flush_mid(ks, dl, pos == 0);
+        flush_mid(ks, dl, pos == 0);
+      }
+      {
+        const int ks = tb.seg_order[tb.S - 1];
+        const bool dl = DUAL && (tb.dual[ks] != 0);
+        const int nst = (tb.kseg_off[ks + 1] - tb.kseg_off[ks]) >> KSH;
+        if (dl) run_segment(std::integral_constant<bool, DUAL>{}, nst);
+        else run_segment(std::integral_constant<bool, false>{}, nst);
+        pin_accumulators();
+        flush_last(ks, dl, false);
       }
     }
   }
