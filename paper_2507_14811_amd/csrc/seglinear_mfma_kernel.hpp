@@ -298,7 +298,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
   //     measured 80 % of the MFMA rate with six reads in front of sixteen MFMAs, 94 % with one read per two);
   //   * the separation's VALU work (5 instructions per dword) follows once its fragment had time to arrive,
   //     a dword or two per MFMA, which the matrix pipe (8 issue slots per MFMA) absorbs;
-  //   * the direct loads of the group are spread evenly over the slots.
+  //   * the direct loads of the group go into the slots that carry neither an LDS read nor separation work.
   auto kstep = [&](auto dl_tag, auto pf_tag, auto grp_tag, const int cur, const int fo_next) __attribute__((always_inline)) {
     constexpr bool DL = decltype(dl_tag)::value;
     constexpr bool PF = decltype(pf_tag)::value;
@@ -346,11 +346,29 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
         }
       }
       if (GRP >= 0 && NG > 0) {
-        int cnt = 0;                                         // the group's loads, spread evenly over the slots
+        // The group's loads go into the slots that carry neither an LDS read nor separation work (a direct load
+        // occupies the wave's issue for ~20 clocks, which fits under one MFMA only if nothing else shares the
+        // slot); what does not fit there is spread evenly over all slots.
+        int nfree = 0, myfree = -1;
+#pragma unroll
+        for (int qq = 0; qq < NM; ++qq) {
+          const bool has_read = PF && (qq % RSTEP == 0) && (qq / RSTEP) * RPS < NR;
+          const bool has_valu = ND && qq >= QV0;
+          if (!has_read && !has_valu) {
+            if (qq == q) myfree = nfree;
+            ++nfree;
+          }
+        }
+        const int nplaced = nfree < NG ? nfree : NG;         // loads that get a free slot of their own
+        int cnt = 0;
 #pragma unroll
         for (int e = 0; e < LT; ++e)
           if (e * SUB / LT == GRP) {
-            if (cnt * NM / (NG > 0 ? NG : 1) == q) issue_slot(e);
+            if (cnt < nplaced) {
+              if (cnt == myfree) issue_slot(e);
+            } else if ((cnt - nplaced) * NM / (NG - nplaced > 0 ? NG - nplaced : 1) == q) {
+              issue_slot(e);
+            }
             ++cnt;
           }
       }
