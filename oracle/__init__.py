@@ -6,6 +6,7 @@ The product package never imports this.
 from .segquant_oracle import (  # noqa: F401
     OracleResult,
     build,
+    calibrate_act,
     cast_bf16,
     dequant,
     error_bound,
@@ -14,6 +15,7 @@ from .segquant_oracle import (  # noqa: F401
     num_threads,
     quantize_act,
     quantize_weight,
+    quantize_weight_block,
     seglinear,
     widen_bf16,
 )

@@ -310,3 +310,67 @@ int sqo_error_bound(const float* x, const float* w, int M, int K, int N, int S,
   (void)M;
   return 0;
 }
+
+/*
+ * Static activation steps from calibration data (Sec. 4.3.2, the two step definitions; App. B sensitivity
+ * study: the strict min/max rule, p = 1.0), one pair per K-segment (Sec. 4.2.2 item 2):
+ *   dual segment        amax_pos = max(0, max x),  amax_neg = max(0, -min x)
+ *   single-scale        amax_pos = max |x|,        amax_neg = 0
+ * The running maxima combine over calibration batches (accumulate != 0 keeps what amax_* already hold);
+ * steps: s = amax / 127, and 1.0 where amax is 0 (a polarity that never occurred).
+ *   x fp32 [M][K]    amax_pos, amax_neg, s_pos, s_neg fp32 [S]
+ */
+int sqo_calibrate_act(const float* x, int M, int K, int S, const int32_t* kseg_off, const uint8_t* dual,
+                      int accumulate, float* amax_pos, float* amax_neg, float* s_pos, float* s_neg) {
+  if (check_offsets(K, S, kseg_off)) return 1;
+  for (int ks = 0; ks < S; ++ks) {
+    float ap = accumulate ? amax_pos[ks] : 0.0f;
+    float an = accumulate ? amax_neg[ks] : 0.0f;
+    for (int m = 0; m < M; ++m) {
+      for (int k = kseg_off[ks]; k < kseg_off[ks + 1]; ++k) {
+        float v = x[(int64_t)m * K + k];
+        if (dual[ks]) {
+          if (v > ap) ap = v;
+          if (-v > an) an = -v;
+        } else {
+          float a = fabsf(v);
+          if (a > ap) ap = a;
+        }
+      }
+    }
+    amax_pos[ks] = ap;
+    amax_neg[ks] = an;
+    s_pos[ks] = (ap == 0.0f) ? 1.0f : ap / SQO_QMAX;
+    s_neg[ks] = (an == 0.0f) ? 1.0f : an / SQO_QMAX;
+  }
+  return 0;
+}
+
+/*
+ * Quant(W) at the paper's own granularity for 8 bit (App. B, quantization granularity: per-tensor, which
+ * under SegLinear means one step per weight segment): one step per (K-segment, N-segment) block,
+ *   a = max |W[n][k]| over n in ns, k in ks;  step = a / 127 (1.0 if the block is all zero),
+ * written to every channel of the block, so that wscale keeps its [S][N] shape.
+ */
+int sqo_quantize_weight_block(const float* w, int N, int K, int S, const int32_t* kseg_off, int T,
+                              const int32_t* nseg_off, int8_t* wq, float* wscale) {
+  if (fegetround() != FE_TONEAREST) return 2;
+  if (check_offsets(K, S, kseg_off) || check_offsets(N, T, nseg_off)) return 1;
+  for (int ks = 0; ks < S; ++ks) {
+    for (int ns = 0; ns < T; ++ns) {
+      float a = 0.0f;
+      for (int n = nseg_off[ns]; n < nseg_off[ns + 1]; ++n)
+        for (int k = kseg_off[ks]; k < kseg_off[ks + 1]; ++k) {
+          float v = fabsf(w[(int64_t)n * K + k]);
+          if (v > a) a = v;
+        }
+      float sw = (a == 0.0f) ? 1.0f : a / SQO_QMAX;
+      for (int n = nseg_off[ns]; n < nseg_off[ns + 1]; ++n) {
+        wscale[(int64_t)ks * N + n] = sw;
+        for (int k = kseg_off[ks]; k < kseg_off[ks + 1]; ++k)
+          wq[(int64_t)n * K + k] = quant_sym(w[(int64_t)n * K + k], sw);
+      }
+    }
+  }
+  return 0;
+}

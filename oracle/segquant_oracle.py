@@ -92,6 +92,36 @@ def quantize_weight(w: np.ndarray, kseg_off):
     return wq, ws
 
 
+def quantize_weight_block(w: np.ndarray, kseg_off, nseg_off):
+    """One step per (K-segment, N-segment) block -> (wq int8 [N][K], wscale fp32 [S][N], constant inside a block)"""
+    w = _f32(w)
+    N, K = w.shape
+    koff, noff = _i32(kseg_off), _i32(nseg_off)
+    S, T = len(koff) - 1, len(noff) - 1
+    wq = np.empty((N, K), dtype=np.int8)
+    ws = np.empty((S, N), dtype=np.float32)
+    _check(_load().sqo_quantize_weight_block(_p(w), N, K, S, _p(koff), T, _p(noff), _p(wq), _p(ws)),
+           "quantize_weight_block")
+    return wq, ws
+
+
+def calibrate_act(x: np.ndarray, kseg_off, dual, running=None):
+    """Min/max calibration of the activation steps.  running: (amax_pos, amax_neg) of earlier batches or None.
+    -> (s_pos, s_neg, amax_pos, amax_neg), fp32 [S] each."""
+    x = _f32(x)
+    M, K = x.shape
+    off, dual = _i32(kseg_off), _u8(dual)
+    S = len(off) - 1
+    if running is None:
+        ap, an, acc = np.zeros(S, np.float32), np.zeros(S, np.float32), 0
+    else:
+        ap, an, acc = _f32(running[0]).copy(), _f32(running[1]).copy(), 1
+    sp, sn = np.empty(S, np.float32), np.empty(S, np.float32)
+    _check(_load().sqo_calibrate_act(_p(x), M, K, S, _p(off), _p(dual), acc, _p(ap), _p(an), _p(sp), _p(sn)),
+           "calibrate_act")
+    return sp, sn, ap, an
+
+
 def quantize_act(x: np.ndarray, kseg_off, dual, s_pos, s_neg):
     """x fp32 [M][K] (bf16 inputs are widened first) -> (xq_pos, xq_neg) int8 [M][K]"""
     x = _f32(x)

@@ -337,3 +337,76 @@ def test_workload_recipes():
     stds = [c3.w[j * 1152:(j + 1) * 1152].std() for j in range(6)]
     assert np.allclose(stds, c3.extra["sigma"], rtol=0.02)
     assert c3.seglinear_bytes() == 16 * 1152 + 6912 * 1152 + 4 * 6912 + 16 * 6912 * 2   # merged codes: X^ once
+
+
+# ----------------------------------------------------------------------------------------------------
+# calibration of the activation steps (Sec. 4.3.2 step definitions, min/max rule) and the block-granular
+# weight quantizer (App. B: per-tensor 8-bit granularity, i.e. one step per weight segment)
+# ----------------------------------------------------------------------------------------------------
+def test_calibrate_act_handworked(oracle):
+    x = np.array([[-2.0, 0.5, 3.0, -0.25], [1.0, -4.0, 0.0, 2.0]], np.float32)
+    sp, sn, ap, an = oracle.calibrate_act(x, [0, 2, 4], [1, 0])
+    # segment 0 is dual: max x = 1, min x = -4; segment 1 is single-scale: max |x| = 3, no second step
+    assert ap.tolist() == [1.0, 3.0] and an.tolist() == [4.0, 0.0]
+    q = np.float32(127.0)
+    assert sp[0] == np.float32(1.0) / q and sn[0] == np.float32(4.0) / q and sp[1] == np.float32(3.0) / q
+    assert sn[1] == np.float32(1.0)               # a polarity that never occurs gets the neutral step
+    # a dual segment without negative values
+    sp, sn, _, an = oracle.calibrate_act(np.array([[0.5, 2.0]], np.float32), [0, 2], [1])
+    assert an[0] == 0.0 and sn[0] == 1.0 and sp[0] == np.float32(2.0) / q
+
+
+def test_calibrate_act_batches_and_extremes(oracle):
+    rng = np.random.default_rng(9)
+    x = (rng.standard_normal((60, 96)) * 3).astype(np.float32)
+    x[:, 32:64] = np.maximum(x[:, 32:64], -0.2)                      # a skewed (activation-like) segment
+    kseg, dual = [0, 32, 64, 96], [0, 1, 1]
+    whole = oracle.calibrate_act(x, kseg, dual)
+    first = oracle.calibrate_act(x[:25], kseg, dual)
+    both = oracle.calibrate_act(x[25:], kseg, dual, running=(first[2], first[3]))
+    for a, b in zip(whole, both):                                    # running maxima over batches = one pass over all
+        assert np.array_equal(a, b)
+    # the independent numpy recipe of the workload generators gives the same steps
+    sp2, sn2 = wl.amax_scales(x, kseg, dual)
+    assert np.array_equal(whole[0], sp2)
+    assert all(whole[1][ks] == sn2[ks] for ks in range(3) if dual[ks])
+    # with these steps the extreme values land exactly on the ends of the code range
+    xp, xn = oracle.quantize_act(x, kseg, dual, whole[0], whole[1])
+    for ks in range(3):
+        blk_p, blk_n = xp[:, kseg[ks]:kseg[ks + 1]], xn[:, kseg[ks]:kseg[ks + 1]]
+        if dual[ks]:
+            assert blk_p.max() == 127 and blk_n.min() == -127
+        else:
+            assert max(blk_p.max(), -blk_p.min()) == 127
+
+
+def test_block_weight_quantizer(oracle):
+    rng = np.random.default_rng(4)
+    w = (rng.standard_normal((12, 40)) * 0.05).astype(np.float32)
+    kseg, nseg = [0, 16, 40], [0, 5, 12]
+    wq, ws = oracle.quantize_weight_block(w, kseg, nseg)
+    for ks in range(2):
+        for ns in range(2):
+            blk = w[nseg[ns]:nseg[ns + 1], kseg[ks]:kseg[ks + 1]]
+            s = ws[ks, nseg[ns]:nseg[ns + 1]]
+            assert (s == s[0]).all()                                  # one step per block
+            a = Fraction(float(np.abs(blk).max()))
+            assert Fraction(float(s[0])) == Fraction(float(np.float32(float(a)) / np.float32(127.0)))
+            codes = wq[nseg[ns]:nseg[ns + 1], kseg[ks]:kseg[ks + 1]]
+            assert np.abs(codes).max() == 127                         # the block's largest weight sits on the grid end
+            for (i, j), v in np.ndenumerate(blk):                     # every code is the nearest grid point (exact rationals)
+                q = Fraction(float(v)) / Fraction(float(s[0]))
+                want = _clip(_rne_fraction(Fraction(float(np.float32(v) / s[0]))))
+                assert int(codes[i, j]) == want and abs(Fraction(int(codes[i, j])) - q) <= Fraction(1, 2) + Fraction(1, 10 ** 6)
+    # one block = per-tensor; rows with equal maxima: identical to the per-channel quantizer (pinned above)
+    w2 = w.copy()
+    w2[:, 0] = 0.3
+    w2[:, 20] = -0.3
+    a, sa = oracle.quantize_weight_block(w2, kseg, [0, 12])
+    b, sb = oracle.quantize_weight(w2, kseg)
+    assert np.array_equal(a, b) and np.array_equal(sa, sb)
+    # an all-zero block gets the neutral step
+    w3 = w.copy()
+    w3[0:5, 0:16] = 0.0
+    _, s3 = oracle.quantize_weight_block(w3, kseg, nseg)
+    assert (s3[0, 0:5] == 1.0).all()
