@@ -155,6 +155,19 @@ def measure(name, steps, warmup, rotate_quant=True):
     quant()
     torch.cuda.synchronize()
 
+    # calibration-side kernels on the same tensors: min/max steps (one read of the activations) and the
+    # block-granular weight quantizer
+    amax = torch.empty((2, w.S), dtype=torch.float32, device="cuda:0")
+    stp = torch.empty((2, w.S), dtype=torch.float32, device="cuda:0")
+    sq.sq_calibrate_act(layer, s["x"], amax, stp)
+    torch.cuda.synchronize()
+    ms_calib = float(np.median(_time_events(lambda: sq.sq_calibrate_act(layer, s["x"], amax, stp), 10)))
+    wq2, ws2 = torch.empty_like(s["wq"]), torch.empty_like(s["wscale"])
+    sq.sq_quantize_weight_block(layer, s["wt"], wq2, ws2)
+    torch.cuda.synchronize()
+    ms_wblock = float(np.median(_time_events(lambda: sq.sq_quantize_weight_block(layer, s["wt"], wq2, ws2), 5)))
+    del wq2, ws2
+
     gbytes = w.seglinear_bytes("bf16")
 
     # Skinny layers are one pass over the weights: with a single weight set the pass is served by the 256 MB
@@ -188,7 +201,8 @@ def measure(name, steps, warmup, rotate_quant=True):
         gemm_tops=w.int8_ops / (ms_gemm * 1e-3) / 1e12, step_tops=w.int8_ops / (ms_step * 1e-3) / 1e12,
         ms_gemm_b2b=ms_gemm_b2b, gemm_tops_b2b=w.int8_ops / (ms_gemm_b2b * 1e-3) / 1e12,
         gemm_bytes=gbytes, gemm_gbs=gbytes / (ms_gemm * 1e-3) / 1e9, gemm_gbs_b2b=gbytes / (ms_gemm_b2b * 1e-3) / 1e9,
-        ms_gemm_hbm=ms_gemm_hbm, weight_sets=nsets,
+        ms_gemm_hbm=ms_gemm_hbm, weight_sets=nsets, ms_calibrate=ms_calib, ms_quantize_weight_block=ms_wblock,
+        calib_gbs=(w.M * w.K * (2 if w.x_dtype == "bf16" else 4)) / (ms_calib * 1e-3) / 1e9,
         gemm_gbs_hbm=(gbytes / (ms_gemm_hbm * 1e-3) / 1e9) if ms_gemm_hbm else None,
         quant_bytes=qbytes, quant_gbs=qbytes / (ms_quant * 1e-3) / 1e9, quant_rotation=nrot,
     )
@@ -403,6 +417,10 @@ def main():
                          "frac": round(head["quant_gbs"] / HBM_PEAK_GBS, 4), "ms_per_launch": round(head["ms_quant"], 5),
                          "bytes": head["quant_bytes"]},
         "quantize_weight_ms": round(head["ms_quantize_weight"], 5),
+        "quantize_weight_block_ms": round(head["ms_quantize_weight_block"], 5),
+        "calibrate_act": {"bound": "hbm", "ms_per_call": round(head["ms_calibrate"], 5), "achieved": round(head["calib_gbs"], 1),
+                          "unit": "GB/s", "frac": round(head["calib_gbs"] / HBM_PEAK_GBS, 4),
+                          "note": "three launches (init, max-reduce, steps); cfg5's activations fit the Infinity Cache"},
         "other_workloads": others,
         "grouped_skinny": grouped,
         "measured_ceilings": ceilings,

@@ -87,6 +87,29 @@ sq_status sq_quantize_weight(const sq_layer* layer, const void* w, sq_dtype w_dt
                              float* wscale, void* stream);
 
 /*
+ * Quant(W) at the granularity the paper uses for 8 bit (App. B, quantization granularity: per tensor, i.e. one
+ * step per weight segment under SegLinear): one step per (K-segment, N-segment) block,
+ *   a = max |W[n][k]| over the block,  step = a / 127 (1.0 if a == 0),
+ * written to wscale[ks][n] of every channel n of the block, so sq_seglinear consumes it unchanged.
+ * Arguments as sq_quantize_weight; layer->nseg_off selects the blocks.  wscale is also the scratch of the call.
+ */
+sq_status sq_quantize_weight_block(const sq_layer* layer, const void* w, sq_dtype w_dt, int8_t* wq,
+                                   float* wscale, void* stream);
+
+/*
+ * Calibration of the static activation steps (Sec. 4.3.2: s_- = |min x| / q, s_+ = max x / q; App. B sensitivity
+ * study: the strict min/max rule, p = 1.0), one pair per K-segment, with running maxima over batches:
+ *   dual segment   amax_pos = max(0, max x), amax_neg = max(0, -min x);   single-scale: amax_pos = max |x|
+ *   steps[ks] = amax_pos[ks] / 127,  steps[S + ks] = amax_neg[ks] / 127,  1.0 where the maximum is 0.
+ *   x      dev, [M][K] of x_dt (one calibration batch)           in
+ *   amax   dev, fp32 [2][S] running maxima (pos, then neg)       in/out; ignored on input when accumulate == 0
+ *   steps  dev, fp32 [2][S] (s_pos, then s_neg)                  out; copy to the host to fill sq_layer
+ * layer->s_pos / s_neg are not read.
+ */
+sq_status sq_calibrate_act(const sq_layer* layer, const void* x, sq_dtype x_dt, float* amax, float* steps,
+                           int accumulate, void* stream);
+
+/*
  * Q_dual(X) with the polarity split fused in (Sec. 4.3.2).  For a dual K-segment:
  *   x <  0 : X^_- = max(round(x / s_neg[ks]), -127), X^_+ = 0     -> xq = X^_-  (<= 0)
  *   x >= 0 : X^_+ = min(round(x / s_pos[ks]),  127), X^_- = 0     -> xq = X^_+  (>= 0)

@@ -8,8 +8,10 @@ from .binding import (  # noqa: F401
     SqError,
     load_library,
     sq_probe_mfma,
+    sq_calibrate_act,
     sq_quantize_act,
     sq_quantize_weight,
+    sq_quantize_weight_block,
     sq_seglinear,
     sq_seglinear_debug_acc,
     sq_seglinear_grouped,

@@ -21,7 +21,8 @@ SQ_MAX_SEG_SCALE = 512
 SQ_MAX_KSEG_LEN = 133143
 
 EXPORTS = ("sq_quantize_weight", "sq_quantize_act", "sq_seglinear", "sq_seglinear_debug_acc",
-           "sq_status_string", "sq_version", "sq_tuning_set", "sq_probe_mfma", "sq_seglinear_grouped")
+           "sq_status_string", "sq_version", "sq_tuning_set", "sq_probe_mfma", "sq_seglinear_grouped",
+           "sq_quantize_weight_block", "sq_calibrate_act")
 
 
 class SqError(RuntimeError):
@@ -67,6 +68,10 @@ def load_library() -> C.CDLL:
     lib.sq_seglinear_debug_acc.argtypes = [lp, vp, vp, vp, vp, vp]
     for f in (lib.sq_quantize_weight, lib.sq_quantize_act, lib.sq_seglinear, lib.sq_seglinear_debug_acc):
         f.restype = i32
+    lib.sq_quantize_weight_block.argtypes = [lp, vp, i32, vp, vp, vp]
+    lib.sq_quantize_weight_block.restype = i32
+    lib.sq_calibrate_act.argtypes = [lp, vp, i32, vp, vp, i32, vp]
+    lib.sq_calibrate_act.restype = i32
     lib.sq_seglinear_grouped.argtypes = [lp, vp, i32, C.POINTER(sq_group_item), i32, vp]
     lib.sq_seglinear_grouped.restype = i32
     lib.sq_probe_mfma.argtypes = [vp, C.c_size_t, i32, C.POINTER(C.c_double), vp]
@@ -163,6 +168,18 @@ def sq_quantize_weight(layer: Layer, w, wq, wscale, stream=None) -> None:
     """w [N][K] fp32/bf16 -> wq int8 [N][K], wscale fp32 [S][N]  (device tensors, written in place)."""
     _check(load_library().sq_quantize_weight(C.byref(layer.c), _dptr(w), _dt(w), _dptr(wq), _dptr(wscale),
                                              _stream(stream)), "sq_quantize_weight")
+
+
+def sq_quantize_weight_block(layer: Layer, w, wq, wscale, stream=None) -> None:
+    """One step per (K-segment, N-segment) block: w [N][K] -> wq int8 [N][K], wscale fp32 [S][N] (constant per block)."""
+    _check(load_library().sq_quantize_weight_block(C.byref(layer.c), _dptr(w), _dt(w), _dptr(wq), _dptr(wscale),
+                                                   _stream(stream)), "sq_quantize_weight_block")
+
+
+def sq_calibrate_act(layer: Layer, x, amax, steps, accumulate: bool = False, stream=None) -> None:
+    """Min/max calibration over one batch: amax fp32 [2][S] running maxima (in/out), steps fp32 [2][S] (s_pos, s_neg)."""
+    _check(load_library().sq_calibrate_act(C.byref(layer.c), _dptr(x), _dt(x), _dptr(amax), _dptr(steps),
+                                           1 if accumulate else 0, _stream(stream)), "sq_calibrate_act")
 
 
 def sq_quantize_act(layer: Layer, x, xq, stream=None) -> None:

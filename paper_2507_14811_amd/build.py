@@ -26,7 +26,7 @@ FLAGS = [
     "-Wno-unknown-warning-option", "-Wno-unused-command-line-argument",
     f"-I{os.path.join(ROOT, 'include')}", f"-I{CSRC}",
 ]
-PLAIN_SOURCES = ["api.hip", "quantize.hip", "seglinear_generic.hip", "seglinear_skinny.hip", "seglinear_stream.hip", "probes.hip",
+PLAIN_SOURCES = ["api.hip", "quantize.hip", "seglinear_generic.hip", "seglinear_skinny.hip", "seglinear_stream.hip", "probes.hip", "calibrate.hip",
                  "seglinear_mfma.hip"]
 
 

@@ -136,6 +136,38 @@ sq_status sq_quantize_weight(const sq_layer* layer, const void* w, sq_dtype w_dt
   return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 
+sq_status sq_quantize_weight_block(const sq_layer* layer, const void* w, sq_dtype w_dt, int8_t* wq, float* wscale,
+                                   void* stream) {
+  sq_status st = check_layer(layer, false, false);
+  if (st != SQ_OK) return st;
+  if (w == nullptr || wq == nullptr || wscale == nullptr) return SQ_ERR_INVALID_ARG;
+  if (w_dt != SQ_F32 && w_dt != SQ_BF16) return SQ_ERR_INVALID_ARG;
+  sq::KsegTable kt, nt;
+  kt.S = layer->S;
+  for (int s = 0; s <= layer->S; ++s) kt.off[s] = layer->kseg_off[s];
+  nt.S = layer->T;
+  for (int t = 0; t <= layer->T; ++t) nt.off[t] = layer->nseg_off[t];
+  hipError_t e = sq::launch_quantize_weight_block(w, w_dt == SQ_BF16, wq, wscale, layer->N, layer->K, kt, nt,
+                                                  reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
+sq_status sq_calibrate_act(const sq_layer* layer, const void* x, sq_dtype x_dt, float* amax, float* steps, int accumulate,
+                           void* stream) {
+  sq_status st = check_layer(layer, true, false);
+  if (st != SQ_OK) return st;
+  if (x == nullptr || amax == nullptr || steps == nullptr) return SQ_ERR_INVALID_ARG;
+  if (x_dt != SQ_F32 && x_dt != SQ_BF16) return SQ_ERR_INVALID_ARG;
+  sq::ActTable tb;
+  std::memset(&tb, 0, sizeof(tb));
+  tb.S = layer->S;
+  for (int s = 0; s <= layer->S; ++s) tb.kseg_off[s] = layer->kseg_off[s];
+  for (int s = 0; s < layer->S; ++s) tb.dual[s] = layer->dual[s] ? 1 : 0;
+  hipError_t e = sq::launch_calibrate_act(x, x_dt == SQ_BF16, layer->M, layer->K, tb, amax, steps, accumulate != 0,
+                                          reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
 sq_status sq_quantize_act(const sq_layer* layer, const void* x, sq_dtype x_dt, int8_t* xq, void* stream) {
   sq_status st = check_layer(layer, true, true);
   if (st != SQ_OK) return st;

@@ -136,7 +136,9 @@ __device__ __forceinline__ float load_w(const void* w, size_t i) {
   return BF16 ? bf16_to_f32(reinterpret_cast<const uint16_t*>(w)[i]) : reinterpret_cast<const float*>(w)[i];
 }
 
-template <bool BF16, bool VEC4>
+// MODE 0: per output channel and K-segment, both passes fused.  MODE 1: first pass only, the row maximum goes to
+// wscale[ks][n].  MODE 2: second pass only, with the step found in wscale[ks][n] (block-granular quantizer).
+template <bool BF16, bool VEC4, int MODE>
 __global__ __launch_bounds__(256) void quantize_weight_kernel(const void* __restrict__ w, int8_t* __restrict__ wq,
                                                               float* __restrict__ wscale, int N, int K,
                                                               const KsegTable tb) {
@@ -148,19 +150,28 @@ __global__ __launch_bounds__(256) void quantize_weight_kernel(const void* __rest
   for (int s = 0; s < tb.S; ++s)
     if (s == ks) { k0 = tb.off[s]; k1 = tb.off[s + 1]; }
   const size_t row = (size_t)n * K;
-  float a = 0.0f;
-  if (VEC4) {
-    for (int k = k0 + 4 * lane; k < k1; k += 256) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) a = __builtin_fmaxf(a, __builtin_fabsf(load_w<BF16>(w, row + k + i)));
-    }
+  float sw;
+  if (MODE == 2) {
+    sw = wscale[(size_t)ks * N + n];
   } else {
-    for (int k = k0 + lane; k < k1; k += 64) a = __builtin_fmaxf(a, __builtin_fabsf(load_w<BF16>(w, row + k)));
-  }
+    float a = 0.0f;
+    if (VEC4) {
+      for (int k = k0 + 4 * lane; k < k1; k += 256) {
 #pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) a = __builtin_fmaxf(a, __shfl_xor(a, off, 64));
-  const float sw = (a == 0.0f) ? 1.0f : a / kQmax;
-  if (lane == 0) wscale[(size_t)ks * N + n] = sw;
+        for (int i = 0; i < 4; ++i) a = __builtin_fmaxf(a, __builtin_fabsf(load_w<BF16>(w, row + k + i)));
+      }
+    } else {
+      for (int k = k0 + lane; k < k1; k += 64) a = __builtin_fmaxf(a, __builtin_fabsf(load_w<BF16>(w, row + k)));
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) a = __builtin_fmaxf(a, __shfl_xor(a, off, 64));
+    if (MODE == 1) {
+      if (lane == 0) wscale[(size_t)ks * N + n] = a;
+      return;
+    }
+    sw = (a == 0.0f) ? 1.0f : a / kQmax;
+    if (lane == 0) wscale[(size_t)ks * N + n] = sw;
+  }
   if (VEC4) {
     for (int k = k0 + 4 * lane; k < k1; k += 256) {
       int c[4];
@@ -173,16 +184,52 @@ __global__ __launch_bounds__(256) void quantize_weight_kernel(const void* __rest
   }
 }
 
-hipError_t launch_quantize_weight(const void* w, bool w_is_bf16, int8_t* wq, float* wscale, int N, int K,
-                                  const KsegTable& tb, hipStream_t st) {
+template <int MODE>
+static void launch_weight_pass(const void* w, bool w_is_bf16, int8_t* wq, float* wscale, int N, int K, const KsegTable& tb,
+                               hipStream_t st) {
   bool vec = (K % 4 == 0) && (reinterpret_cast<uintptr_t>(w) % 16 == 0) && (reinterpret_cast<uintptr_t>(wq) % 4 == 0);
   for (int s = 0; s <= tb.S; ++s) vec = vec && (tb.off[s] % 4 == 0);
   const long items = (long)N * tb.S;
   const unsigned blocks = (unsigned)((items + 3) / 4);
-#define SQ_LAUNCH_W(B, V) hipLaunchKernelGGL((quantize_weight_kernel<B, V>), dim3(blocks), dim3(256), 0, st, w, wq, wscale, N, K, tb)
+#define SQ_LAUNCH_W(B, V) hipLaunchKernelGGL((quantize_weight_kernel<B, V, MODE>), dim3(blocks), dim3(256), 0, st, w, wq, wscale, N, K, tb)
   if (w_is_bf16) { if (vec) SQ_LAUNCH_W(true, true); else SQ_LAUNCH_W(true, false); }
   else           { if (vec) SQ_LAUNCH_W(false, true); else SQ_LAUNCH_W(false, false); }
 #undef SQ_LAUNCH_W
+}
+
+hipError_t launch_quantize_weight(const void* w, bool w_is_bf16, int8_t* wq, float* wscale, int N, int K,
+                                  const KsegTable& tb, hipStream_t st) {
+  launch_weight_pass<0>(w, w_is_bf16, wq, wscale, N, K, tb, st);
+  return hipGetLastError();
+}
+
+// Block-granular steps: wscale[ks][n] holds the row maxima on entry; one workgroup per (K-segment, N-segment) block
+// reduces them and writes the block's step back to every channel of the block.
+__global__ __launch_bounds__(256) void weight_block_step_kernel(float* __restrict__ wscale, int N, const KsegTable nt) {
+  const int ks = blockIdx.y, ns = blockIdx.x;
+  int n0 = 0, n1 = 0;
+  for (int t = 0; t < nt.S; ++t)
+    if (t == ns) { n0 = nt.off[t]; n1 = nt.off[t + 1]; }
+  float* row = wscale + (size_t)ks * N;
+  float a = 0.0f;
+  for (int n = n0 + threadIdx.x; n < n1; n += 256) a = __builtin_fmaxf(a, row[n]);
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) a = __builtin_fmaxf(a, __shfl_xor(a, off, 64));
+  __shared__ float red[4];
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = a;
+  __syncthreads();
+  a = __builtin_fmaxf(__builtin_fmaxf(red[0], red[1]), __builtin_fmaxf(red[2], red[3]));
+  const float sw = (a == 0.0f) ? 1.0f : a / kQmax;
+  __syncthreads();                                       // every thread has read the maxima before they are overwritten
+  for (int n = n0 + threadIdx.x; n < n1; n += 256) row[n] = sw;
+}
+
+// One step per (K-segment, N-segment) block: row maxima, block reduce + broadcast, quantize with the block's step.
+hipError_t launch_quantize_weight_block(const void* w, bool w_is_bf16, int8_t* wq, float* wscale, int N, int K,
+                                        const KsegTable& kt, const KsegTable& nt, hipStream_t st) {
+  launch_weight_pass<1>(w, w_is_bf16, wq, wscale, N, K, kt, st);
+  hipLaunchKernelGGL(weight_block_step_kernel, dim3(nt.S, kt.S), dim3(256), 0, st, wscale, N, nt);
+  launch_weight_pass<2>(w, w_is_bf16, wq, wscale, N, K, kt, st);
   return hipGetLastError();
 }
 

@@ -17,6 +17,13 @@ hipError_t launch_quantize_act(const void* x, bool x_is_bf16, int8_t* xq, int M,
 hipError_t launch_quantize_weight(const void* w, bool w_is_bf16, int8_t* wq, float* wscale, int N, int K,
                                   const KsegTable& tb, hipStream_t st);
 
+hipError_t launch_quantize_weight_block(const void* w, bool w_is_bf16, int8_t* wq, float* wscale, int N, int K,
+                                        const KsegTable& kt, const KsegTable& nt, hipStream_t st);
+
+// calibrate.hip : min/max activation steps per K-segment, running maxima over batches
+hipError_t launch_calibrate_act(const void* x, bool x_is_bf16, int M, int K, const ActTable& tb, float* amax, float* steps,
+                                bool accumulate, hipStream_t st);
+
 // seglinear_generic.hip : any shape / alignment, one thread per output element
 hipError_t launch_seglinear_generic(const GemmArgs& a, const GemmTable& tb, OutMode mode, hipStream_t st);
 

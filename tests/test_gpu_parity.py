@@ -336,6 +336,73 @@ def test_graph_capture_and_replay(oracle):
         assert err <= RTOL * float(np.abs(r.y32).max()), f"replay {rep}: {err}"
 
 
+CALIB = [
+    dict(M=300, K=1024, kseg=[0, 256, 1024], dual=[0, 1], x_dtype="bf16"),
+    dict(M=37, K=100, kseg=[0, 37, 100], dual=[1, 0], x_dtype="f32"),            # unaligned: scalar path
+    dict(M=64, K=256, kseg=[0, 128, 256], dual=[1, 1], x_dtype="f32"),
+    dict(M=5, K=64, kseg=[0, 64], dual=[1], x_dtype="bf16"),
+]
+
+
+@pytest.mark.parametrize("case", CALIB)
+def test_calibrate_act(oracle, case):
+    """Device min/max calibration: running maxima over two batches and the steps, bit-exact against the oracle."""
+    import torch
+
+    g = _gpu()
+    M, K = case["M"], case["K"]
+    w = wl.random_layer(M, K, 16, case["kseg"], [0, 16], case["dual"], seed=M + K, x_dtype=case["x_dtype"], act="gelu")
+    S = w.S
+    gl = g.GpuLayer(w)
+    amax = torch.full((2, S), float("nan"), dtype=torch.float32, device=g.DEV)      # poisoned: the call must initialise it
+    steps = torch.full((2, S), float("nan"), dtype=torch.float32, device=g.DEV)
+    half = max(1, M // 2)
+    lay_a = sq.Layer(half, K, 16, w.kseg_off, [0, 16], w.dual)
+    lay_b = sq.Layer(M - half, K, 16, w.kseg_off, [0, 16], w.dual) if M > half else None
+    sq.sq_calibrate_act(lay_a, gl.x[:half].contiguous(), amax, steps, accumulate=False)
+    r1 = oracle.calibrate_act(w.x[:half], w.kseg_off, w.dual)
+    torch.cuda.synchronize()
+    assert np.array_equal(amax.cpu().numpy().view(np.uint32), np.stack([r1[2], r1[3]]).view(np.uint32))
+    assert np.array_equal(steps.cpu().numpy().view(np.uint32), np.stack([r1[0], r1[1]]).view(np.uint32))
+    if lay_b is not None:
+        sq.sq_calibrate_act(lay_b, gl.x[half:].contiguous(), amax, steps, accumulate=True)
+        r2 = oracle.calibrate_act(w.x[half:], w.kseg_off, w.dual, running=(r1[2], r1[3]))
+        torch.cuda.synchronize()
+        assert np.array_equal(amax.cpu().numpy().view(np.uint32), np.stack([r2[2], r2[3]]).view(np.uint32))
+        assert np.array_equal(steps.cpu().numpy().view(np.uint32), np.stack([r2[0], r2[1]]).view(np.uint32))
+        whole = oracle.calibrate_act(w.x, w.kseg_off, w.dual)
+        assert np.array_equal(steps.cpu().numpy()[0], whole[0])
+
+
+WBLOCK = [
+    dict(N=384, K=256, kseg=[0, 128, 256], nseg=[0, 128, 256, 384], w_dtype="f32"),
+    dict(N=70, K=100, kseg=[0, 37, 100], nseg=[0, 5, 70], w_dtype="f32"),           # unaligned
+    dict(N=1152, K=1152, kseg=[0, 1152], nseg=[0, 1152], w_dtype="bf16"),            # one block: per tensor
+    dict(N=600, K=512, kseg=[0, 512], nseg=[0, 100, 300, 600], w_dtype="bf16"),      # segments longer than a workgroup
+]
+
+
+@pytest.mark.parametrize("case", WBLOCK)
+def test_quantize_weight_block(oracle, case):
+    import torch
+
+    g = _gpu()
+    N, K = case["N"], case["K"]
+    S = len(case["kseg"]) - 1
+    w = wl.random_layer(4, K, N, case["kseg"], case["nseg"], [0] * S, seed=N + K, x_dtype="f32")
+    ww = w.w.copy()
+    ww[case["nseg"][0]:case["nseg"][1], case["kseg"][0]:case["kseg"][1]] *= 3.0          # blocks with different ranges
+    if case["w_dtype"] == "bf16":
+        ww = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(ww))
+    w.w = ww
+    gl = g.GpuLayer(w, w_dtype=case["w_dtype"])
+    sq.sq_quantize_weight_block(gl.layer, gl.wt, gl.wq, gl.wscale)
+    torch.cuda.synchronize()
+    rq, rs = oracle.quantize_weight_block(ww, case["kseg"], case["nseg"])
+    assert np.array_equal(gl.wscale.cpu().numpy().view(np.uint32), rs.view(np.uint32))
+    assert np.array_equal(gl.wq.cpu().numpy(), rq)
+
+
 GENERIC = [
     dict(M=7, K=100, N=13, kseg=[0, 37, 100], nseg=[0, 5, 13], dual=[1, 0]),
     dict(M=70, K=96, N=65, kseg=[0, 96], nseg=[0, 65], dual=[1]),

@@ -102,6 +102,11 @@ def test_invalid_arguments_are_rejected_on_the_host(sq):
     assert lib.sq_quantize_weight(C.byref(w.c), None, 0, FAKE, FAKE, None) == INVALID
     assert lib.sq_quantize_weight(C.byref(w.c), FAKE, 3, FAKE, FAKE, None) == INVALID
     assert lib.sq_seglinear_debug_acc(C.byref(w.c), FAKE, FAKE, FAKE, None, FAKE, None) == INVALID
+    assert lib.sq_quantize_weight_block(C.byref(w.c), None, 0, FAKE, FAKE, None) == INVALID
+    assert lib.sq_quantize_weight_block(C.byref(w.c), FAKE, 0, FAKE, None, None) == INVALID
+    assert lib.sq_calibrate_act(C.byref(ok.c), None, 1, FAKE, FAKE, 0, None) == INVALID
+    assert lib.sq_calibrate_act(C.byref(ok.c), FAKE, 1, None, FAKE, 0, None) == INVALID
+    assert lib.sq_calibrate_act(C.byref(ok.c), FAKE, 4, FAKE, FAKE, 0, None) == INVALID
     # grouped call: NULL item table, empty group, oversized group, NULL member, per-block multiplier
     from paper_2507_14811_amd.binding import sq_group_item
     one = (sq_group_item * 1)(sq_group_item(0x1000, 0x1000, None, 0x1000))
