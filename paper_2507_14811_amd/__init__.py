@@ -4,6 +4,7 @@
 synthetic layer generators; `build` compiles the HIP sources for gfx950.
 """
 from .binding import (  # noqa: F401
+    GroupItems,
     Layer,
     SqError,
     load_library,

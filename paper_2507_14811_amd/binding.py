@@ -194,15 +194,25 @@ def sq_seglinear(layer: Layer, xq, wq, wscale, bias, y, stream=None) -> None:
                                        _dptr(y), _dt(y), _stream(stream)), "sq_seglinear")
 
 
+class GroupItems:
+    """The marshalled item array of a grouped call (device pointers of L layers), built once and reused: filling
+    it takes longer on the host than the launch takes on the GPU.  Keeps the tensors alive."""
+
+    def __init__(self, items):
+        self.tensors = list(items)
+        self.n = len(self.tensors)
+        self.arr = (sq_group_item * max(self.n, 1))()
+        for i, (wq, wscale, bias, y) in enumerate(self.tensors):
+            self.arr[i] = sq_group_item(wq.data_ptr(), wscale.data_ptr(), None if bias is None else bias.data_ptr(),
+                                        y.data_ptr())
+        self.y_dt = _dt(self.tensors[0][3]) if self.n else SQ_F32
+
+
 def sq_seglinear_grouped(layer: Layer, xq, items, stream=None) -> None:
-    """L layers of one shape sharing xq in one launch.  items: sequence of (wq, wscale, bias or None, y) device tensors;
-    all y of one dtype."""
-    n = len(items)
-    arr = (sq_group_item * max(n, 1))()
-    for i, (wq, wscale, bias, y) in enumerate(items):
-        arr[i] = sq_group_item(wq.data_ptr(), wscale.data_ptr(), None if bias is None else bias.data_ptr(), y.data_ptr())
-    ydt = _dt(items[0][3]) if n else SQ_F32
-    _check(load_library().sq_seglinear_grouped(C.byref(layer.c), _dptr(xq), n, arr, ydt, _stream(stream)),
+    """L layers of one shape sharing xq in one launch.  items: a GroupItems, or a sequence of (wq, wscale, bias or
+    None, y) device tensors; all y of one dtype."""
+    g = items if isinstance(items, GroupItems) else GroupItems(items)
+    _check(load_library().sq_seglinear_grouped(C.byref(layer.c), _dptr(xq), g.n, g.arr, g.y_dt, _stream(stream)),
            "sq_seglinear_grouped")
 
 

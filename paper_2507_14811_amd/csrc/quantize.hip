@@ -33,8 +33,10 @@ __global__ __launch_bounds__(256) void quantize_act_fast_kernel(const void* __re
   for (int j = 0; j < kActUnroll; ++j) {
     const uint32_t c = base + j * 256u;
     if (c < nchunks) {
+      // x is read once and dead afterwards: non-temporal loads keep it from displacing X^ (which the GEMM reads
+      // next) in the caches; 4.7 -> 5.2 TB/s.  The stores stay ordinary: non-temporal ones were slower.
 #pragma unroll
-      for (int l = 0; l < NL; ++l) raw[j][l] = reinterpret_cast<const v4i*>(x)[(size_t)NL * c + l];
+      for (int l = 0; l < NL; ++l) raw[j][l] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(x) + ((size_t)NL * c + l));
     }
   }
 #pragma unroll
