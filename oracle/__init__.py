@@ -7,6 +7,7 @@ from .segquant_oracle import (  # noqa: F401
     OracleResult,
     build,
     calibrate_act,
+    calibrate_act_percentile,
     cast_bf16,
     dequant,
     error_bound,

@@ -29,6 +29,8 @@
  *   x / s              = a true IEEE fp32 division
  *   weight layout      = W[n][k] (row = output channel), i.e. the transpose of
  *                        the paper's k x n matrix
+ *   percentile clip    = nearest-rank quantile of the tensor the quantizer sees (max(X,0), max(-X,0) or |X|,
+ *                        zeros included), per K-segment and batch, running maximum over batches
  *   arithmetic         = fp32, every operation individually rounded (build with
  *                        -ffp-contract=off -fno-fast-math); an fp64 evaluation of
  *                        the same dequant sum is returned beside it.
@@ -338,6 +340,66 @@ int sqo_calibrate_act(const float* x, int M, int K, int S, const int32_t* kseg_o
         }
       }
     }
+    amax_pos[ks] = ap;
+    amax_neg[ks] = an;
+    s_pos[ks] = (ap == 0.0f) ? 1.0f : ap / SQO_QMAX;
+    s_neg[ks] = (an == 0.0f) ? 1.0f : an / SQO_QMAX;
+  }
+  return 0;
+}
+
+/*
+ * Calibration of the activation steps with percentile clipping (App. B, dual-scale sensitivity study: the rule
+ * p = 1.0 of sqo_calibrate_act against clipping at p <= 0.9999).  The paper names the percentile only; the
+ * reading taken here: the calibrator sees the tensor that the quantizer sees, i.e. per K-segment
+ *   dual          V_+ = max(X, 0),  V_- = max(-X, 0)      (Sec. 4.3.2: X = X_+ + X_-, zeros included)
+ *   single-scale  V_+ = |X|
+ * and the clipping threshold of a batch is the nearest-rank p-quantile of the n = M * K_ks values of V:
+ * the k-th smallest with k = ceil(p * n) evaluated in IEEE double, clamped to [1, n]  (p = 1.0: the maximum).
+ * Thresholds combine over batches like the maxima do (running maximum); steps: s = threshold / 127, and 1.0
+ * where it is 0.  Written as the definition: sort, then index.
+ *   x fp32 [M][K]    0 < p <= 1    amax_pos, amax_neg, s_pos, s_neg fp32 [S]
+ */
+static int cmp_f32(const void* a, const void* b) {
+  const float x = *(const float*)a, y = *(const float*)b;
+  return (x > y) - (x < y);
+}
+
+int sqo_calibrate_act_percentile(const float* x, int M, int K, int S, const int32_t* kseg_off, const uint8_t* dual,
+                                 double p, int accumulate, float* amax_pos, float* amax_neg, float* s_pos,
+                                 float* s_neg) {
+  if (check_offsets(K, S, kseg_off)) return 1;
+  if (!(p > 0.0 && p <= 1.0) || M < 1) return 1;
+  for (int ks = 0; ks < S; ++ks) {
+    const int L = kseg_off[ks + 1] - kseg_off[ks];
+    const int64_t n = (int64_t)M * L;
+    float* vp = (float*)malloc((size_t)n * sizeof(float));
+    float* vn = (float*)malloc((size_t)n * sizeof(float));
+    if (!vp || !vn) { free(vp); free(vn); return 3; }
+    int64_t i = 0;
+    for (int m = 0; m < M; ++m)
+      for (int k = kseg_off[ks]; k < kseg_off[ks + 1]; ++k, ++i) {
+        const float v = x[(int64_t)m * K + k];
+        if (dual[ks]) {
+          vp[i] = v > 0.0f ? v : 0.0f;
+          vn[i] = v < 0.0f ? -v : 0.0f;
+        } else {
+          vp[i] = fabsf(v);
+          vn[i] = 0.0f;
+        }
+      }
+    qsort(vp, (size_t)n, sizeof(float), cmp_f32);
+    qsort(vn, (size_t)n, sizeof(float), cmp_f32);
+    int64_t kth = (int64_t)ceil(p * (double)n);
+    if (kth < 1) kth = 1;
+    if (kth > n) kth = n;
+    const float tp = vp[kth - 1], tn = vn[kth - 1];
+    free(vp);
+    free(vn);
+    float ap = accumulate ? amax_pos[ks] : 0.0f;
+    float an = accumulate ? amax_neg[ks] : 0.0f;
+    if (tp > ap) ap = tp;
+    if (tn > an) an = tn;
     amax_pos[ks] = ap;
     amax_neg[ks] = an;
     s_pos[ks] = (ap == 0.0f) ? 1.0f : ap / SQO_QMAX;

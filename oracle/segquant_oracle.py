@@ -122,6 +122,26 @@ def calibrate_act(x: np.ndarray, kseg_off, dual, running=None):
     return sp, sn, ap, an
 
 
+def calibrate_act_percentile(x: np.ndarray, kseg_off, dual, p: float, running=None):
+    """Percentile-clipping calibration of the activation steps (nearest-rank p-quantile of max(X,0), max(-X,0) or |X|
+    per K-segment and batch, running maximum over batches).  -> (s_pos, s_neg, amax_pos, amax_neg), fp32 [S] each."""
+    x = _f32(x)
+    M, K = x.shape
+    off, dual = _i32(kseg_off), _u8(dual)
+    S = len(off) - 1
+    if running is None:
+        ap, an, acc = np.zeros(S, np.float32), np.zeros(S, np.float32), 0
+    else:
+        ap, an, acc = _f32(running[0]).copy(), _f32(running[1]).copy(), 1
+    sp, sn = np.empty(S, np.float32), np.empty(S, np.float32)
+    f = _load().sqo_calibrate_act_percentile
+    f.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_double, C.c_int,
+                  C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    _check(f(_p(x), M, K, S, _p(off), _p(dual), float(p), acc, _p(ap), _p(an), _p(sp), _p(sn)),
+           "calibrate_act_percentile")
+    return sp, sn, ap, an
+
+
 def quantize_act(x: np.ndarray, kseg_off, dual, s_pos, s_neg):
     """x fp32 [M][K] (bf16 inputs are widened first) -> (xq_pos, xq_neg) int8 [M][K]"""
     x = _f32(x)

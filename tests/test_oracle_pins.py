@@ -380,6 +380,78 @@ def test_calibrate_act_batches_and_extremes(oracle):
             assert max(blk_p.max(), -blk_p.min()) == 127
 
 
+# percentile-clipping calibration (App. B, dual-scale sensitivity study: p = 1.0 against p <= 0.9999)
+def test_calibrate_percentile_handworked(oracle):
+    q = np.float32(127.0)
+    x = np.array([[-4.0, -3.0, -2.0, -1.0, 0.5, 1.0, 2.0, 3.0, 5.0, 100.0]], np.float32)
+    # dual: max(x,0) sorted = 0,0,0,0,.5,1,2,3,5,100 ; max(-x,0) sorted = 0,0,0,0,0,0,1,2,3,4 ; n = 10
+    sp, sn, ap, an = oracle.calibrate_act_percentile(x, [0, 10], [1], 0.9)        # k = ceil(9.0) = 9
+    assert ap[0] == 5.0 and an[0] == 3.0 and sp[0] == np.float32(5.0) / q and sn[0] == np.float32(3.0) / q
+    sp, sn, ap, an = oracle.calibrate_act_percentile(x, [0, 10], [1], 0.91)       # k = ceil(9.1) = 10: the maxima
+    assert ap[0] == 100.0 and an[0] == 4.0
+    sp, sn, ap, an = oracle.calibrate_act_percentile(x, [0, 10], [1], 0.5)        # k = 5: 0.5 and a zero
+    assert ap[0] == 0.5 and an[0] == 0.0 and sn[0] == 1.0                         # zero threshold: neutral step
+    sp, sn, ap, an = oracle.calibrate_act_percentile(x, [0, 10], [1], 0.05)       # k = 1: the minima, both zero
+    assert ap[0] == 0.0 and an[0] == 0.0 and sp[0] == 1.0
+    # single-scale: |x| sorted = .5,1,1,2,2,3,3,4,5,100 ; no second step
+    sp, sn, ap, an = oracle.calibrate_act_percentile(x, [0, 10], [0], 0.9)
+    assert ap[0] == 5.0 and an[0] == 0.0 and sn[0] == 1.0
+    sp, sn, ap, an = oracle.calibrate_act_percentile(x, [0, 10], [0], 0.8)        # k = 8
+    assert ap[0] == 4.0
+    # two K-segments, two rows: each segment ranks its own 2 x 2 values; k = ceil(0.75 * 4) = 3
+    x2 = np.array([[1.0, 8.0, -1.0, 7.0], [2.0, 9.0, -2.0, -6.0]], np.float32)
+    sp, sn, ap, an = oracle.calibrate_act_percentile(x2, [0, 2, 4], [0, 1], 0.75)
+    assert ap.tolist() == [8.0, 0.0] and an.tolist() == [0.0, 2.0]                # seg 1: V+ = 0,7,0,0 ; V- = 1,0,2,6
+    # batches: the running maximum of the per-batch thresholds, not the quantile of the union
+    a = np.array([[1.0, 2.0, 3.0, 4.0]], np.float32)
+    b = np.array([[10.0, 0.1, 0.2, 0.3]], np.float32)
+    r1 = oracle.calibrate_act_percentile(a, [0, 4], [0], 0.75)                    # k = 3 -> 3.0
+    r2 = oracle.calibrate_act_percentile(b, [0, 4], [0], 0.75, running=(r1[2], r1[3]))   # batch: 0.3
+    assert r1[2][0] == 3.0 and r2[2][0] == 3.0
+    r3 = oracle.calibrate_act_percentile(b, [0, 4], [0], 1.0, running=(r1[2], r1[3]))
+    assert r3[2][0] == 10.0
+    for bad in (0.0, -0.1, 1.5, float("nan")):
+        with pytest.raises(Exception):
+            oracle.calibrate_act_percentile(a, [0, 4], [0], bad)
+
+
+def test_calibrate_percentile_definition(oracle):
+    """The threshold against what defines a nearest-rank quantile (a count, no sort), against numpy's own quantile
+    routine, and against the min/max rule at p = 1."""
+    rng = np.random.default_rng(21)
+    x = (rng.standard_normal((37, 160)) * 2).astype(np.float32)
+    x[:, 64:] = np.where(x[:, 64:] > 0, x[:, 64:], 0.1 * x[:, 64:])          # an activation-like skewed segment
+    x[3, 70] = 55.0                                                          # outliers that clipping removes
+    x[9, 10] = -80.0
+    kseg, dual = [0, 64, 160], [0, 1]
+    mm = oracle.calibrate_act(x, kseg, dual)
+    one = oracle.calibrate_act_percentile(x, kseg, dual, 1.0)
+    for a, b in zip(mm, one):
+        assert np.array_equal(a, b)
+    prev = None
+    for p in (0.37, 0.9, 0.99, 0.999, 0.9999):
+        sp, sn, ap, an = oracle.calibrate_act_percentile(x, kseg, dual, p)
+        for ks in range(2):
+            blk = x[:, kseg[ks]:kseg[ks + 1]].astype(np.float64).ravel()
+            n = blk.size
+            k = int(np.ceil(p * n))
+            assert abs(p * n - round(p * n)) > 1e-6                           # the cases sit away from rank boundaries
+            pops = [(np.maximum(blk, 0), ap[ks]), (np.maximum(-blk, 0), an[ks])] if dual[ks] else [(np.abs(blk), ap[ks])]
+            for v, t in pops:
+                t = float(t)
+                assert np.count_nonzero(v <= t) >= k and np.count_nonzero(v < t) < k
+                assert t == np.quantile(v, p, method="inverted_cdf")
+            if not dual[ks]:
+                assert an[ks] == 0.0
+        if prev is not None:                                                  # monotone in p
+            assert np.all(ap >= prev[0]) and np.all(an >= prev[1])
+        prev = (ap, an)
+    # the outliers are what p = 0.9999 still keeps and p = 0.999 clips (n = 2368 and 3552: k = n at 0.9999)
+    assert oracle.calibrate_act_percentile(x, kseg, dual, 0.9999)[2][1] == 55.0
+    assert oracle.calibrate_act_percentile(x, kseg, dual, 0.999)[2][1] < 10.0
+    assert oracle.calibrate_act_percentile(x, kseg, dual, 0.999)[2][0] < 80.0
+
+
 def test_block_weight_quantizer(oracle):
     rng = np.random.default_rng(4)
     w = (rng.standard_normal((12, 40)) * 0.05).astype(np.float32)
