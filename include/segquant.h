@@ -110,6 +110,25 @@ sq_status sq_calibrate_act(const sq_layer* layer, const void* x, sq_dtype x_dt, 
                            int accumulate, void* stream);
 
 /*
+ * The same calibration with percentile clipping (App. B, dual-scale sensitivity study: p <= 0.9999 against the
+ * min/max rule p = 1.0).  The paper names the percentile only; the rule implemented: per K-segment and polarity
+ * the clipping threshold of a batch is the nearest-rank p-quantile of the tensor the quantizer sees,
+ *   dual segment  V_+ = max(x, 0), V_- = max(-x, 0)  (zeros included);   single-scale: V_+ = |x|,
+ * i.e. the k-th smallest of its n = M * K_ks values, k = ceil(p * n) in IEEE double, clamped to [1, n];
+ * thresholds combine over batches as running maxima, steps = threshold / 127 (1.0 where it is 0).  p = 1.0 gives
+ * sq_calibrate_act.  The order statistic is exact (radix select on the fp32 bit patterns); inputs must be finite.
+ *   p          host, 0 < p <= 1
+ *   workspace  dev, at least sq_calibrate_workspace_bytes() bytes, 4-byte aligned, contents irrelevant on entry;
+ *              owned by the caller, used only during the call (calls that share it must not overlap)
+ *   others as sq_calibrate_act.
+ * SQ_ERR_INVALID_ARG for p outside (0, 1], a missing or short workspace.
+ */
+size_t sq_calibrate_workspace_bytes(void);
+sq_status sq_calibrate_act_percentile(const sq_layer* layer, const void* x, sq_dtype x_dt, double p, float* amax,
+                                      float* steps, void* workspace, size_t workspace_bytes, int accumulate,
+                                      void* stream);
+
+/*
  * Q_dual(X) with the polarity split fused in (Sec. 4.3.2).  For a dual K-segment:
  *   x <  0 : X^_- = max(round(x / s_neg[ks]), -127), X^_+ = 0     -> xq = X^_-  (<= 0)
  *   x >= 0 : X^_+ = min(round(x / s_pos[ks]),  127), X^_- = 0     -> xq = X^_+  (>= 0)

@@ -10,6 +10,8 @@ from .binding import (  # noqa: F401
     load_library,
     sq_probe_mfma,
     sq_calibrate_act,
+    sq_calibrate_act_percentile,
+    sq_calibrate_workspace_bytes,
     sq_quantize_act,
     sq_quantize_weight,
     sq_quantize_weight_block,

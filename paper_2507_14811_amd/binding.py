@@ -22,7 +22,8 @@ SQ_MAX_KSEG_LEN = 133143
 
 EXPORTS = ("sq_quantize_weight", "sq_quantize_act", "sq_seglinear", "sq_seglinear_debug_acc",
            "sq_status_string", "sq_version", "sq_tuning_set", "sq_probe_mfma", "sq_seglinear_grouped",
-           "sq_quantize_weight_block", "sq_calibrate_act")
+           "sq_quantize_weight_block", "sq_calibrate_act", "sq_calibrate_act_percentile",
+           "sq_calibrate_workspace_bytes")
 
 
 class SqError(RuntimeError):
@@ -72,6 +73,10 @@ def load_library() -> C.CDLL:
     lib.sq_quantize_weight_block.restype = i32
     lib.sq_calibrate_act.argtypes = [lp, vp, i32, vp, vp, i32, vp]
     lib.sq_calibrate_act.restype = i32
+    lib.sq_calibrate_act_percentile.argtypes = [lp, vp, i32, C.c_double, vp, vp, vp, C.c_size_t, i32, vp]
+    lib.sq_calibrate_act_percentile.restype = i32
+    lib.sq_calibrate_workspace_bytes.argtypes = []
+    lib.sq_calibrate_workspace_bytes.restype = C.c_size_t
     lib.sq_seglinear_grouped.argtypes = [lp, vp, i32, C.POINTER(sq_group_item), i32, vp]
     lib.sq_seglinear_grouped.restype = i32
     lib.sq_probe_mfma.argtypes = [vp, C.c_size_t, i32, C.POINTER(C.c_double), vp]
@@ -180,6 +185,22 @@ def sq_calibrate_act(layer: Layer, x, amax, steps, accumulate: bool = False, str
     """Min/max calibration over one batch: amax fp32 [2][S] running maxima (in/out), steps fp32 [2][S] (s_pos, s_neg)."""
     _check(load_library().sq_calibrate_act(C.byref(layer.c), _dptr(x), _dt(x), _dptr(amax), _dptr(steps),
                                            1 if accumulate else 0, _stream(stream)), "sq_calibrate_act")
+
+
+def sq_calibrate_workspace_bytes() -> int:
+    """Device bytes sq_calibrate_act_percentile needs as workspace."""
+    return int(load_library().sq_calibrate_workspace_bytes())
+
+
+def sq_calibrate_act_percentile(layer: Layer, x, p: float, amax, steps, workspace, accumulate: bool = False,
+                                stream=None) -> None:
+    """Percentile-clipping calibration over one batch (nearest-rank p-quantile per K-segment and polarity); amax,
+    steps as sq_calibrate_act; workspace: a device byte tensor of at least sq_calibrate_workspace_bytes()."""
+    _check(load_library().sq_calibrate_act_percentile(C.byref(layer.c), _dptr(x), _dt(x), float(p), _dptr(amax),
+                                                      _dptr(steps), _dptr(workspace),
+                                                      workspace.numel() * workspace.element_size(),
+                                                      1 if accumulate else 0, _stream(stream)),
+           "sq_calibrate_act_percentile")
 
 
 def sq_quantize_act(layer: Layer, x, xq, stream=None) -> None:

@@ -168,6 +168,28 @@ sq_status sq_calibrate_act(const sq_layer* layer, const void* x, sq_dtype x_dt, 
   return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 
+size_t sq_calibrate_workspace_bytes(void) { return sq::calibrate_workspace_bytes(); }
+
+sq_status sq_calibrate_act_percentile(const sq_layer* layer, const void* x, sq_dtype x_dt, double p, float* amax,
+                                      float* steps, void* workspace, size_t workspace_bytes, int accumulate,
+                                      void* stream) {
+  sq_status st = check_layer(layer, true, false);
+  if (st != SQ_OK) return st;
+  if (x == nullptr || amax == nullptr || steps == nullptr || workspace == nullptr) return SQ_ERR_INVALID_ARG;
+  if (x_dt != SQ_F32 && x_dt != SQ_BF16) return SQ_ERR_INVALID_ARG;
+  if (!(p > 0.0 && p <= 1.0)) return SQ_ERR_INVALID_ARG;
+  if (workspace_bytes < sq::calibrate_workspace_bytes() || reinterpret_cast<uintptr_t>(workspace) % 4 != 0)
+    return SQ_ERR_INVALID_ARG;
+  sq::ActTable tb;
+  std::memset(&tb, 0, sizeof(tb));
+  tb.S = layer->S;
+  for (int s = 0; s <= layer->S; ++s) tb.kseg_off[s] = layer->kseg_off[s];
+  for (int s = 0; s < layer->S; ++s) tb.dual[s] = layer->dual[s] ? 1 : 0;
+  hipError_t e = sq::launch_calibrate_act_percentile(x, x_dt == SQ_BF16, layer->M, layer->K, tb, p, amax, steps, workspace,
+                                                     accumulate != 0, reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
 sq_status sq_quantize_act(const sq_layer* layer, const void* x, sq_dtype x_dt, int8_t* xq, void* stream) {
   sq_status st = check_layer(layer, true, true);
   if (st != SQ_OK) return st;

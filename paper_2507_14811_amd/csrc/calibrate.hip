@@ -3,6 +3,8 @@
 // the activations, HBM-bandwidth-bound.
 #include "sq_kernels.hpp"
 
+#include <cmath>
+
 namespace sq {
 
 constexpr int kCalibRows = 8;   // token rows per workgroup
@@ -109,6 +111,187 @@ hipError_t launch_calibrate_act(const void* x, bool x_is_bf16, int M, int K, con
   else           { if (vec) SQ_CALIB(false, true); else SQ_CALIB(false, false); }
 #undef SQ_CALIB
   hipLaunchKernelGGL(calib_steps_kernel, dim3(1), dim3(128), 0, st, amax, steps, n);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------------------
+// Percentile clipping (App. B, dual-scale sensitivity study: p <= 0.9999 against the min/max rule).  Per K-segment
+// and polarity the threshold is the nearest-rank quantile of max(x,0), max(-x,0) or |x| over the batch, zeros
+// included.  The values are >= 0, so their fp32 bit patterns order like unsigned integers and the exact order
+// statistic comes from a radix select on those bits, most significant digit first: a histogram pass over the
+// activations per digit (one pass per 8 bits: two for bf16 inputs, four for fp32), each followed by a tiny kernel
+// that walks the 256 bins from the top, picks the bin holding the wanted rank and narrows the search to it.
+// Digit 0 is never counted (it would make the zeros of the other polarity one hot bin): its count is the rest of
+// the bucket.
+// ------------------------------------------------------------------------------------------------------------
+struct PctState {                                 // the caller's workspace
+  unsigned int hist[SQ_MAX_SEGMENTS][2][256];     // [ks][polarity][digit], zero between passes
+  unsigned int rank[SQ_MAX_SEGMENTS][2];          // wanted rank from the top (1 = largest) inside the bucket
+  unsigned int bucket[SQ_MAX_SEGMENTS][2];        // elements that share the prefix found so far
+  unsigned int prefix[SQ_MAX_SEGMENTS][2];        // magnitude bits found so far
+};
+struct PctRanks {                                 // per K-segment: elements of a batch, rank from the top
+  unsigned int n[SQ_MAX_SEGMENTS];
+  unsigned int r[SQ_MAX_SEGMENTS];
+};
+
+size_t calibrate_workspace_bytes() { return sizeof(PctState); }
+
+__global__ void pct_init_kernel(PctState* __restrict__ st, const PctRanks rk, int S) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < S * 2 * 256) (&st->hist[0][0][0])[i] = 0u;
+  if (i < S * 2) {
+    const int ks = i >> 1, pol = i & 1;
+    st->rank[ks][pol] = rk.r[ks];
+    st->bucket[ks][pol] = rk.n[ks];
+    st->prefix[ks][pol] = 0u;
+  }
+}
+
+// grid: (row blocks, K-segments), as the maximum pass.  Counts digit (bits >> shift) & dmask of every value whose
+// bits above the digit (himask) equal the prefix found so far.
+template <bool BF16, bool VEC8>
+__global__ __launch_bounds__(256) void pct_hist_kernel(const void* __restrict__ x, int M, int K, const ActTable tb,
+                                                       PctState* __restrict__ st, int shift, unsigned int dmask,
+                                                       unsigned int himask) {
+  const int ks = blockIdx.y;
+  int k0 = 0, k1 = 0;
+  bool dual = false;
+  for (int s = 0; s < tb.S; ++s)
+    if (s == ks) { k0 = tb.kseg_off[s]; k1 = tb.kseg_off[s + 1]; dual = tb.dual[s] != 0; }
+  const int L = k1 - k0;
+  const int r0 = blockIdx.x * kCalibRows;
+  const int nrows = (M - r0) < kCalibRows ? (M - r0) : kCalibRows;
+  __shared__ unsigned int h[2][256];
+  h[0][threadIdx.x] = 0u;
+  h[1][threadIdx.x] = 0u;
+  const unsigned int pre_p = st->prefix[ks][0], pre_n = st->prefix[ks][1];
+  __syncthreads();
+  auto count = [&](int pol, unsigned int bits, unsigned int pre) {
+    if ((bits & himask) == pre) {
+      const unsigned int d = (bits >> shift) & dmask;
+      if (d != 0u) atomicAdd(&h[pol][d], 1u);
+    }
+  };
+  auto take = [&](float v) {
+    const unsigned int bits = __float_as_uint(v), mag = bits & 0x7FFFFFFFu;
+    if (dual) {
+      count(0, v > 0.0f ? bits : 0u, pre_p);
+      count(1, v < 0.0f ? mag : 0u, pre_n);
+    } else {
+      count(0, mag, pre_p);
+    }
+  };
+  if (VEC8) {
+    const int cpr = L >> 3;
+    for (int cc = threadIdx.x; cc < cpr; cc += 256) {
+      v4i raw[kCalibRows][BF16 ? 1 : 2];
+#pragma unroll
+      for (int r = 0; r < kCalibRows; ++r) {
+        const int rr = r < nrows ? r : nrows - 1;           // ragged M: in-bounds load, not counted below
+        const size_t e = (size_t)(r0 + rr) * K + k0 + cc * 8;
+        if (BF16) {
+          raw[r][0] = *reinterpret_cast<const v4i*>(reinterpret_cast<const uint16_t*>(x) + e);
+        } else {
+          raw[r][0] = *reinterpret_cast<const v4i*>(reinterpret_cast<const float*>(x) + e);
+          raw[r][BF16 ? 0 : 1] = *reinterpret_cast<const v4i*>(reinterpret_cast<const float*>(x) + e + 4);
+        }
+      }
+#pragma unroll
+      for (int r = 0; r < kCalibRows; ++r) {
+        if (r >= nrows) continue;
+        if (BF16) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const uint32_t u = (uint32_t)raw[r][0][i];
+            take(__uint_as_float(u << 16));
+            take(__uint_as_float(u & 0xFFFF0000u));
+          }
+        } else {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) { take(__int_as_float(raw[r][0][i])); take(__int_as_float(raw[r][BF16 ? 0 : 1][i])); }
+        }
+      }
+    }
+  } else {
+    for (int c = threadIdx.x; c < nrows * L; c += 256) {
+      const int r = c / L, cc = c - r * L;
+      const size_t e = (size_t)(r0 + r) * K + k0 + cc;
+      take(BF16 ? bf16_to_f32(reinterpret_cast<const uint16_t*>(x)[e]) : reinterpret_cast<const float*>(x)[e]);
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int pol = 0; pol < 2; ++pol) {
+    const unsigned int c = h[pol][threadIdx.x];
+    if (c != 0u) atomicAdd(&st->hist[ks][pol][threadIdx.x], c);
+  }
+}
+
+// One thread per (K-segment, polarity): pick the digit, narrow the bucket, clear the histogram for the next pass.
+// After the last digit the prefix is the threshold: fold it into the running maxima and write the steps
+// (amax, steps: [2][S], as the min/max calibration).
+__global__ void pct_select_kernel(PctState* __restrict__ st, int S, int shift, int last, int accumulate,
+                                  float* __restrict__ amax, float* __restrict__ steps) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= 2 * S) return;
+  const int pol = i / S, ks = i - pol * S;
+  unsigned int* h = st->hist[ks][pol];
+  const unsigned int r = st->rank[ks][pol];
+  unsigned int cum = 0u;
+  int d = 255;
+  for (; d >= 1; --d) {
+    const unsigned int c = h[d];
+    if (cum + c >= r) break;
+    cum += c;
+  }
+  // d >= 1: the rank falls into bin d.  d == 0: it falls into the uncounted digit 0, which holds the rest.
+  st->rank[ks][pol] = r - cum;
+  st->bucket[ks][pol] = d >= 1 ? h[d] : st->bucket[ks][pol] - cum;
+  const unsigned int pre = st->prefix[ks][pol] | ((unsigned int)d << shift);
+  st->prefix[ks][pol] = pre;
+  for (int b = 0; b < 256; ++b) h[b] = 0u;
+  if (last) {
+    const float t = __uint_as_float(pre);
+    float a = accumulate ? amax[i] : 0.0f;
+    a = __builtin_fmaxf(a, t);
+    amax[i] = a;
+    steps[i] = (a == 0.0f) ? 1.0f : a / kQmax;
+  }
+}
+
+hipError_t launch_calibrate_act_percentile(const void* x, bool x_is_bf16, int M, int K, const ActTable& tb, double p,
+                                           float* amax, float* steps, void* workspace, bool accumulate, hipStream_t st) {
+  PctState* ws = reinterpret_cast<PctState*>(workspace);
+  PctRanks rk;
+  for (int s = 0; s < tb.S; ++s) {
+    const long long n = (long long)M * (tb.kseg_off[s + 1] - tb.kseg_off[s]);
+    long long k = (long long)std::ceil(p * (double)n);      // nearest rank, in IEEE double
+    k = k < 1 ? 1 : (k > n ? n : k);
+    rk.n[s] = (unsigned int)n;
+    rk.r[s] = (unsigned int)(n - k + 1);                    // k-th smallest = (n - k + 1)-th largest
+  }
+  const int nclear = tb.S * 2 * 256;
+  hipLaunchKernelGGL(pct_init_kernel, dim3((nclear + 255) / 256), dim3(256), 0, st, ws, rk, tb.S);
+  bool vec = (K % 8 == 0) && (reinterpret_cast<uintptr_t>(x) % 16 == 0);
+  for (int s = 0; s <= tb.S; ++s) vec = vec && (tb.kseg_off[s] % 8 == 0);
+  dim3 grid((M + kCalibRows - 1) / kCalibRows, tb.S);
+  // digits of the magnitude bits, most significant first; a bf16 value has nothing below bit 16
+  static const int kShift[4] = {23, 15, 7, 0};
+  static const unsigned int kMask[4] = {0xFFu, 0xFFu, 0xFFu, 0x7Fu};
+  const int npass = x_is_bf16 ? 2 : 4;
+  for (int ps = 0; ps < npass; ++ps) {
+    int shift = kShift[ps];
+    unsigned int dmask = kMask[ps];
+    if (x_is_bf16 && ps == 1) { shift = 16; dmask = 0x7Fu; }
+    const unsigned int himask = 0x7FFFFFFFu & ~((dmask << shift) | ((1u << shift) - 1u));
+#define SQ_PCT(B, V) hipLaunchKernelGGL((pct_hist_kernel<B, V>), grid, dim3(256), 0, st, x, M, K, tb, ws, shift, dmask, himask)
+    if (x_is_bf16) { if (vec) SQ_PCT(true, true); else SQ_PCT(true, false); }
+    else           { if (vec) SQ_PCT(false, true); else SQ_PCT(false, false); }
+#undef SQ_PCT
+    hipLaunchKernelGGL(pct_select_kernel, dim3(1), dim3(2 * SQ_MAX_SEGMENTS), 0, st, ws, tb.S, shift,
+                       ps == npass - 1 ? 1 : 0, accumulate ? 1 : 0, amax, steps);
+  }
   return hipGetLastError();
 }
 

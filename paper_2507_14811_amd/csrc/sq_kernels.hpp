@@ -24,6 +24,12 @@ hipError_t launch_quantize_weight_block(const void* w, bool w_is_bf16, int8_t* w
 hipError_t launch_calibrate_act(const void* x, bool x_is_bf16, int M, int K, const ActTable& tb, float* amax, float* steps,
                                 bool accumulate, hipStream_t st);
 
+// percentile clipping instead of the maximum: exact nearest-rank quantile by radix select; workspace of
+// calibrate_workspace_bytes() device bytes
+size_t calibrate_workspace_bytes();
+hipError_t launch_calibrate_act_percentile(const void* x, bool x_is_bf16, int M, int K, const ActTable& tb, double p,
+                                           float* amax, float* steps, void* workspace, bool accumulate, hipStream_t st);
+
 // seglinear_generic.hip : any shape / alignment, one thread per output element
 hipError_t launch_seglinear_generic(const GemmArgs& a, const GemmTable& tb, OutMode mode, hipStream_t st);
 

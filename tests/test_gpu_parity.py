@@ -374,6 +374,50 @@ def test_calibrate_act(oracle, case):
         assert np.array_equal(steps.cpu().numpy()[0], whole[0])
 
 
+PCTL = [
+    dict(M=300, K=1024, kseg=[0, 256, 1024], dual=[0, 1], x_dtype="bf16", ps=(0.9999, 0.999, 0.5)),
+    dict(M=37, K=100, kseg=[0, 37, 100], dual=[1, 0], x_dtype="f32", ps=(0.99, 0.03)),         # unaligned: scalar path
+    dict(M=67, K=256, kseg=[0, 128, 256], dual=[1, 1], x_dtype="f32", ps=(0.9999, 0.9, 1.0)),   # ragged row block
+    dict(M=5, K=64, kseg=[0, 64], dual=[1], x_dtype="bf16", ps=(0.75, 1.0)),
+    dict(M=1500, K=3072, kseg=[0, 1024, 3072], dual=[1, 0], x_dtype="bf16", ps=(0.9999, 0.99)),  # many workgroups
+]
+
+
+@pytest.mark.parametrize("case", PCTL)
+def test_calibrate_act_percentile(oracle, case):
+    """Device percentile-clipping calibration (exact radix select): thresholds, running maxima over two batches and
+    the steps, bit-exact against the oracle's sort-and-index definition."""
+    import torch
+
+    g = _gpu()
+    M, K = case["M"], case["K"]
+    w = wl.random_layer(M, K, 16, case["kseg"], [0, 16], case["dual"], seed=7 * M + K, x_dtype=case["x_dtype"], act="gelu")
+    x = w.x.copy()
+    x[0, 0], x[M - 1, K - 1] = 77.0, -91.0                                         # outliers for the clipping to act on
+    if case["x_dtype"] == "bf16":
+        xd = torch.from_numpy(wl.f32_to_bf16_bits(x).view(np.int16)).view(torch.bfloat16).to(g.DEV)
+    else:
+        xd = torch.from_numpy(x).to(g.DEV)
+    S = w.S
+    ws = torch.full((sq.sq_calibrate_workspace_bytes(),), 0x5A, dtype=torch.uint8, device=g.DEV)   # dirty on entry
+    half = max(1, M // 2)
+    lay_a = sq.Layer(half, K, 16, w.kseg_off, [0, 16], w.dual)
+    lay_b = sq.Layer(M - half, K, 16, w.kseg_off, [0, 16], w.dual)
+    for p in case["ps"]:
+        amax = torch.full((2, S), float("nan"), dtype=torch.float32, device=g.DEV)  # poisoned: the call must initialise it
+        steps = torch.full((2, S), float("nan"), dtype=torch.float32, device=g.DEV)
+        sq.sq_calibrate_act_percentile(lay_a, xd[:half].contiguous(), p, amax, steps, ws, accumulate=False)
+        r1 = oracle.calibrate_act_percentile(x[:half], w.kseg_off, w.dual, p)
+        torch.cuda.synchronize()
+        assert np.array_equal(amax.cpu().numpy().view(np.uint32), np.stack([r1[2], r1[3]]).view(np.uint32)), (p, "first batch")
+        assert np.array_equal(steps.cpu().numpy().view(np.uint32), np.stack([r1[0], r1[1]]).view(np.uint32))
+        sq.sq_calibrate_act_percentile(lay_b, xd[half:].contiguous(), p, amax, steps, ws, accumulate=True)
+        r2 = oracle.calibrate_act_percentile(x[half:], w.kseg_off, w.dual, p, running=(r1[2], r1[3]))
+        torch.cuda.synchronize()
+        assert np.array_equal(amax.cpu().numpy().view(np.uint32), np.stack([r2[2], r2[3]]).view(np.uint32)), (p, "second batch")
+        assert np.array_equal(steps.cpu().numpy().view(np.uint32), np.stack([r2[0], r2[1]]).view(np.uint32))
+
+
 WBLOCK = [
     dict(N=384, K=256, kseg=[0, 128, 256], nseg=[0, 128, 256, 384], w_dtype="f32"),
     dict(N=70, K=100, kseg=[0, 37, 100], nseg=[0, 5, 70], w_dtype="f32"),           # unaligned

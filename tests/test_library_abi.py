@@ -107,6 +107,11 @@ def test_invalid_arguments_are_rejected_on_the_host(sq):
     assert lib.sq_calibrate_act(C.byref(ok.c), None, 1, FAKE, FAKE, 0, None) == INVALID
     assert lib.sq_calibrate_act(C.byref(ok.c), FAKE, 1, None, FAKE, 0, None) == INVALID
     assert lib.sq_calibrate_act(C.byref(ok.c), FAKE, 4, FAKE, FAKE, 0, None) == INVALID
+    need = lib.sq_calibrate_workspace_bytes()
+    assert 0 < need < (1 << 20)
+    pct = lambda p, ws=FAKE, nbytes=need, x=FAKE: lib.sq_calibrate_act_percentile(C.byref(ok.c), x, 1, p, FAKE, FAKE, ws, nbytes, 0, None)
+    assert pct(0.0) == INVALID and pct(1.5) == INVALID and pct(float("nan")) == INVALID and pct(-0.5) == INVALID
+    assert pct(0.999, ws=None) == INVALID and pct(0.999, nbytes=need - 1) == INVALID and pct(0.999, x=None) == INVALID
     # grouped call: NULL item table, empty group, oversized group, NULL member, per-block multiplier
     from paper_2507_14811_amd.binding import sq_group_item
     one = (sq_group_item * 1)(sq_group_item(0x1000, 0x1000, None, 0x1000))
