@@ -4,7 +4,11 @@ Importable from tests, the smoke check and the benchmark's cpu_baseline leg.
 The product package never imports this.
 """
 from .segquant_oracle import (  # noqa: F401
+    ACT_GELU,
+    ACT_NONE,
+    ACT_SILU,
     OracleResult,
+    activation,
     build,
     calibrate_act,
     calibrate_act_percentile,
@@ -15,6 +19,7 @@ from .segquant_oracle import (  # noqa: F401
     int_gemm,
     num_threads,
     quantize_act,
+    quantize_act_fused,
     quantize_weight,
     quantize_weight_block,
     seglinear,

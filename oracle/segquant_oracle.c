@@ -349,6 +349,72 @@ int sqo_calibrate_act(const float* x, int M, int K, int S, const int32_t* kseg_o
 }
 
 /*
+ * The polarity-asymmetric activation in front of a DualScale layer (Sec. 4.3.1: SiLU, GELU), fused with the
+ * quantizer: xq = Q_dual(act(h)).  The codes are integers decided by floating point, so the activation is
+ * specified to the bit, in fp32 (the precision the kernels compute in), every operation individually rounded:
+ *   exp32(t):  +inf for t > 88;  t <- max(t, -87);  n = round_half_even(t * 1.44269504);
+ *              r = fma(n, -0.693145751953125, t);  r = fma(n, -1.42860682e-6, r)         (ln 2 in two parts)
+ *              p = 1/5040;  p = fma(p, r, c) for c = 1/720, 1/120, 1/24, 1/6, 1/2, 1, 1   (Taylor, |r| <= ln2/2)
+ *              exp32 = p * 2^n
+ *   SiLU(x)      = x / (1 + exp32(-x))
+ *   GELU(x)      = x / (1 + exp32(-z)),  z = (1.59576912 * x) * fma(0.044715, x * x, 1)
+ *                  (the tanh form 0.5 x (1 + tanh(sqrt(2/pi) (x + 0.044715 x^3))), written with
+ *                   0.5 (1 + tanh(u)) = 1 / (1 + e^(-2u)))
+ * One activation code per K-segment: 0 none, 1 SiLU, 2 GELU.  The activation's value is quantized as the fp32
+ * number it is (no rounding to bf16 in between).
+ */
+static float exp32(float t) {
+  if (t > 88.0f) return INFINITY;
+  t = fmaxf(t, -87.0f);
+  const float n = nearbyintf(t * 1.44269504f);
+  float r = fmaf(n, -0.693145751953125f, t);
+  r = fmaf(n, -1.42860682e-6f, r);
+  float p = 1.0f / 5040.0f;
+  p = fmaf(p, r, 1.0f / 720.0f);
+  p = fmaf(p, r, 1.0f / 120.0f);
+  p = fmaf(p, r, 1.0f / 24.0f);
+  p = fmaf(p, r, 1.0f / 6.0f);
+  p = fmaf(p, r, 0.5f);
+  p = fmaf(p, r, 1.0f);
+  p = fmaf(p, r, 1.0f);
+  return ldexpf(p, (int)n);
+}
+
+float sqo_silu(float x) { return x / (1.0f + exp32(-x)); }
+
+float sqo_gelu(float x) {
+  const float z = (1.59576912f * x) * fmaf(0.044715f, x * x, 1.0f);
+  return x / (1.0f + exp32(-z));
+}
+
+/* a[m][k] = act_ks(h[m][k]), act[ks] in {0 none, 1 SiLU, 2 GELU};  h, a fp32 [M][K] */
+int sqo_activation(const float* h, int M, int K, int S, const int32_t* kseg_off, const int32_t* act, float* a) {
+  if (fegetround() != FE_TONEAREST) return 2;
+  if (check_offsets(K, S, kseg_off)) return 1;
+  for (int ks = 0; ks < S; ++ks)
+    if (act[ks] < 0 || act[ks] > 2) return 1;
+  for (int m = 0; m < M; ++m)
+    for (int ks = 0; ks < S; ++ks)
+      for (int k = kseg_off[ks]; k < kseg_off[ks + 1]; ++k) {
+        const float v = h[(int64_t)m * K + k];
+        a[(int64_t)m * K + k] = act[ks] == 1 ? sqo_silu(v) : act[ks] == 2 ? sqo_gelu(v) : v;
+      }
+  return 0;
+}
+
+/* xq = Q_dual(act(h)): the activation above, then sqo_quantize_act on its result. */
+int sqo_quantize_act_fused(const float* h, int M, int K, int S, const int32_t* kseg_off, const uint8_t* dual,
+                           const int32_t* act, const float* s_pos, const float* s_neg, int8_t* xq_pos,
+                           int8_t* xq_neg) {
+  float* a = (float*)malloc((size_t)M * K * sizeof(float));
+  if (!a) return 3;
+  int rc = sqo_activation(h, M, K, S, kseg_off, act, a);
+  if (rc == 0) rc = sqo_quantize_act(a, M, K, S, kseg_off, dual, s_pos, s_neg, xq_pos, xq_neg);
+  free(a);
+  return rc;
+}
+
+/*
  * Calibration of the activation steps with percentile clipping (App. B, dual-scale sensitivity study: the rule
  * p = 1.0 of sqo_calibrate_act against clipping at p <= 0.9999).  The paper names the percentile only; the
  * reading taken here: the calibrator sees the tensor that the quantizer sees, i.e. per K-segment

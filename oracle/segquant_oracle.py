@@ -155,6 +155,31 @@ def quantize_act(x: np.ndarray, kseg_off, dual, s_pos, s_neg):
     return xp, xn
 
 
+ACT_NONE, ACT_SILU, ACT_GELU = 0, 1, 2
+
+
+def activation(h: np.ndarray, kseg_off, act):
+    """a = act_ks(h) per K-segment (0 none, 1 SiLU, 2 tanh-form GELU), in the bit-specified fp32 arithmetic."""
+    h = _f32(h)
+    M, K = h.shape
+    off, act = _i32(kseg_off), _i32(act)
+    a = np.empty((M, K), dtype=np.float32)
+    _check(_load().sqo_activation(_p(h), M, K, len(off) - 1, _p(off), _p(act), _p(a)), "activation")
+    return a
+
+
+def quantize_act_fused(h: np.ndarray, kseg_off, dual, act, s_pos, s_neg):
+    """h fp32 [M][K] pre-activation -> (xq_pos, xq_neg) int8 [M][K] of Q_dual(act(h))"""
+    h = _f32(h)
+    M, K = h.shape
+    off, dual, act, s_pos, s_neg = _i32(kseg_off), _u8(dual), _i32(act), _f32(s_pos), _f32(s_neg)
+    xp = np.empty((M, K), dtype=np.int8)
+    xn = np.empty((M, K), dtype=np.int8)
+    _check(_load().sqo_quantize_act_fused(_p(h), M, K, len(off) - 1, _p(off), _p(dual), _p(act), _p(s_pos), _p(s_neg),
+                                          _p(xp), _p(xn)), "quantize_act_fused")
+    return xp, xn
+
+
 def int_gemm(xq_pos, xq_neg, wq, kseg_off, dual, rows=None):
     """-> (acc_pos, acc_neg) int32 [S][nrows][N]; rows = subset of token rows or None (all)."""
     xq_pos = np.ascontiguousarray(xq_pos, dtype=np.int8)

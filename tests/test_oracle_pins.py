@@ -380,6 +380,82 @@ def test_calibrate_act_batches_and_extremes(oracle):
             assert max(blk_p.max(), -blk_p.min()) == 127
 
 
+# the activation in front of a DualScale layer, specified to the bit in fp32 and fused with the quantizer
+# (Sec. 4.3.1: SiLU and GELU are the polarity-asymmetric activations the scheme is built for)
+def _act_inputs():
+    rng = np.random.default_rng(33)
+    grid = np.linspace(-20.0, 20.0, 8001)
+    rnd = rng.standard_normal(20000) * 3
+    edge = np.array([0.0, -0.0, 1e-30, -1e-30, 1e-6, -1e-6, 0.5, -0.5, 86.9, -86.9, 87.5, -87.5, 88.5, -88.5, 100.0, -100.0,
+                     1e4, -1e4, 3e19, -3e19, 1e38, -1e38, -0.7517916, -1.2784645])        # incl. the two minima
+    return np.concatenate([grid, rnd, edge]).astype(np.float32)
+
+
+def test_activation_against_closed_forms(oracle):
+    """The fp32 activation against the closed forms in fp64 and against torch's own routines."""
+    import torch
+
+    x = _act_inputs()
+    x64 = x.astype(np.float64)
+    one = np.zeros((1, x.size), np.float32)
+    one[0] = x
+    silu = oracle.activation(one, [0, x.size], [oracle.ACT_SILU])[0].astype(np.float64)
+    gelu = oracle.activation(one, [0, x.size], [oracle.ACT_GELU])[0].astype(np.float64)
+    same = oracle.activation(one, [0, x.size], [oracle.ACT_NONE])[0]
+    assert np.array_equal(same.view(np.uint32), x.view(np.uint32))
+    with np.errstate(over="ignore"):
+        silu_ref = x64 / (1.0 + np.exp(-x64))
+        u = np.sqrt(2.0 / np.pi) * (x64 + 0.044715 * x64 ** 3)
+        gelu_tanh_form = 0.5 * x64 * (1.0 + np.tanh(u))          # the textbook form; cancels in the negative tail
+        gelu_ref = x64 / (1.0 + np.exp(-2.0 * u))                # the same function without the cancellation
+    t = torch.from_numpy(x64)
+    assert np.allclose(silu_ref, torch.nn.functional.silu(t).numpy(), rtol=1e-12, atol=1e-300)
+    mid = np.abs(x64) < 1e3
+    assert np.allclose(gelu_ref[mid], gelu_tanh_form[mid], rtol=0, atol=2e-15 * (1 + np.abs(x64[mid]).max()))
+    assert np.allclose(gelu_tanh_form[mid], torch.nn.functional.gelu(t, approximate="tanh").numpy()[mid], rtol=0, atol=1e-12)
+    with np.errstate(over="ignore", invalid="ignore"):
+        zarg = np.nan_to_num(np.minimum(np.abs(2.0 * u), 90.0), nan=90.0)
+    for got, ref, cond, name in ((silu, silu_ref, 0.0 * zarg, "silu"), (gelu, gelu_ref, zarg, "gelu")):
+        assert np.all(np.isfinite(got)), name
+        # a few fp32 roundings (exp32 is good to ~1.5 ulp, then an add, a division): 6e-7 relative.  GELU's exponent
+        # z is itself a rounded fp32 number (three roundings, 2e-7 relative), which e^z turns into 2e-7 |z| relative.
+        # Deep in the negative tail the result underflows towards -0 and only an absolute bound is meaningful.
+        err = np.abs(got - ref)
+        tol = (6e-7 + 2e-7 * cond) * np.abs(ref) + 1e-30
+        assert np.all(err <= tol), (name, float(np.max(err / tol)))
+    # landmarks: fixed points and the sign structure the DualScale split relies on
+    assert np.all(silu[x == 0.0] == 0.0) and np.all(gelu[x == 0.0] == 0.0) and np.count_nonzero(x == 0.0) >= 2
+    assert np.all(silu[x > 0] > 0) and np.all(silu[(x < 0) & (x > -80)] < 0)
+    assert silu.min() > -0.27847 and silu.min() < -0.27845            # min of SiLU = -0.278465 at x = -1.27846
+    assert gelu.min() > -0.17005 and gelu.min() < -0.17003            # min of tanh-GELU = -0.170041 at x = -0.75179
+    big = x > 30
+    assert np.array_equal(silu[big], x64[big]) and np.array_equal(gelu[big], x64[big])   # identity for large x
+
+
+def test_fused_quantizer_is_activation_then_quantizer(oracle):
+    rng = np.random.default_rng(5)
+    h = (rng.standard_normal((9, 48)) * 2).astype(np.float32)
+    kseg, dual, act = [0, 16, 32, 48], [0, 1, 1], [oracle.ACT_NONE, oracle.ACT_GELU, oracle.ACT_SILU]
+    a = oracle.activation(h, kseg, act)
+    assert np.array_equal(a[:, :16], h[:, :16])
+    assert np.array_equal(a[:, 16:32], oracle.activation(h[:, 16:32], [0, 16], [oracle.ACT_GELU]))
+    assert np.array_equal(a[:, 32:], oracle.activation(h[:, 32:], [0, 16], [oracle.ACT_SILU]))
+    sp, sn, _, _ = oracle.calibrate_act(a, kseg, dual)
+    xp, xn = oracle.quantize_act_fused(h, kseg, dual, act, sp, sn)
+    xp2, xn2 = oracle.quantize_act(a, kseg, dual, sp, sn)
+    assert np.array_equal(xp, xp2) and np.array_equal(xn, xn2)
+    # the negative lobe of the activation fills the negative code range: that is what the second step is for
+    assert xn[:, 16:32].min() == -127 and xp[:, 16:32].max() == 127
+    # hand-worked: SiLU(1) = 0.7310586, SiLU(-1) = -0.2689414 ; steps 0.01 and 0.005 -> codes 73 and -54
+    xp, xn = oracle.quantize_act_fused(np.array([[1.0, -1.0]], np.float32), [0, 2], [1], [oracle.ACT_SILU], [0.01], [0.005])
+    assert xp.tolist() == [[73, 0]] and xn.tolist() == [[0, -54]]
+    # GELU(1) = 0.841192, GELU(-1) = -0.158808 -> 84 and -32
+    xp, xn = oracle.quantize_act_fused(np.array([[1.0, -1.0]], np.float32), [0, 2], [1], [oracle.ACT_GELU], [0.01], [0.005])
+    assert xp.tolist() == [[84, 0]] and xn.tolist() == [[0, -32]]
+    with pytest.raises(Exception):
+        oracle.quantize_act_fused(h, kseg, dual, [0, 3, 1], sp, sn)
+
+
 # percentile-clipping calibration (App. B, dual-scale sensitivity study: p = 1.0 against p <= 0.9999)
 def test_calibrate_percentile_handworked(oracle):
     q = np.float32(127.0)
