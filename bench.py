@@ -162,6 +162,17 @@ def measure(name, steps, warmup, rotate_quant=True):
     sq.sq_calibrate_act(layer, s["x"], amax, stp)
     torch.cuda.synchronize()
     ms_calib = float(np.median(_time_events(lambda: sq.sq_calibrate_act(layer, s["x"], amax, stp), 10)))
+    # the activation fused in front of the quantizer: GELU on the dual K-segments (the headline layer's MLP half)
+    codes = [sq.SQ_ACT_GELU if d else sq.SQ_ACT_NONE for d in w.dual]
+    xq_f = torch.empty_like(s["xq"])
+    sq.sq_quantize_act_fused(layer, s["x"], codes, xq_f)
+    torch.cuda.synchronize()
+    ms_quant_fused = float(np.median(_time_events(lambda: sq.sq_quantize_act_fused(layer, s["x"], codes, xq_f), 20)))
+    fws = torch.empty((sq.sq_quantize_act_fused_workspace_bytes(layer),), dtype=torch.uint8, device="cuda:0")
+    sq.sq_quantize_act_fused(layer, s["x"], codes, xq_f, workspace=fws)
+    torch.cuda.synchronize()
+    ms_quant_fused_lut = float(np.median(_time_events(lambda: sq.sq_quantize_act_fused(layer, s["x"], codes, xq_f, workspace=fws), 20)))
+    del xq_f
     pws = torch.empty((sq.sq_calibrate_workspace_bytes(),), dtype=torch.uint8, device="cuda:0")
     sq.sq_calibrate_act_percentile(layer, s["x"], 0.9999, amax, stp, pws)
     torch.cuda.synchronize()
@@ -205,7 +216,7 @@ def measure(name, steps, warmup, rotate_quant=True):
         gemm_tops=w.int8_ops / (ms_gemm * 1e-3) / 1e12, step_tops=w.int8_ops / (ms_step * 1e-3) / 1e12,
         ms_gemm_b2b=ms_gemm_b2b, gemm_tops_b2b=w.int8_ops / (ms_gemm_b2b * 1e-3) / 1e12,
         gemm_bytes=gbytes, gemm_gbs=gbytes / (ms_gemm * 1e-3) / 1e9, gemm_gbs_b2b=gbytes / (ms_gemm_b2b * 1e-3) / 1e9,
-        ms_gemm_hbm=ms_gemm_hbm, weight_sets=nsets, ms_calibrate=ms_calib, ms_calibrate_percentile=ms_calib_pct, ms_quantize_weight_block=ms_wblock,
+        ms_gemm_hbm=ms_gemm_hbm, weight_sets=nsets, ms_quant_fused=ms_quant_fused, ms_quant_fused_lut=ms_quant_fused_lut, ms_calibrate=ms_calib, ms_calibrate_percentile=ms_calib_pct, ms_quantize_weight_block=ms_wblock,
         calib_gbs=(w.M * w.K * (2 if w.x_dtype == "bf16" else 4)) / (ms_calib * 1e-3) / 1e9,
         gemm_gbs_hbm=(gbytes / (ms_gemm_hbm * 1e-3) / 1e9) if ms_gemm_hbm else None,
         quant_bytes=qbytes, quant_gbs=qbytes / (ms_quant * 1e-3) / 1e9, quant_rotation=nrot,
@@ -420,6 +431,13 @@ def main():
         "quantize_act": {"bound": "hbm", "achieved": round(head["quant_gbs"], 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                          "frac": round(head["quant_gbs"] / HBM_PEAK_GBS, 4), "ms_per_launch": round(head["ms_quant"], 5),
                          "bytes": head["quant_bytes"]},
+        "quantize_act_fused": {"bound": "hbm", "activation": "GELU (tanh form) on the dual K-segments",
+                               "path": "code tables in LDS (bf16 input, two launches: table fill + stream)",
+                               "ms_per_call": round(head["ms_quant_fused_lut"], 5),
+                               "achieved": round(head["quant_bytes"] / (head["ms_quant_fused_lut"] * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS,
+                               "unit": "GB/s", "frac": round(head["quant_bytes"] / (head["ms_quant_fused_lut"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                               "bytes": head["quant_bytes"],
+                               "ms_per_launch_arithmetic_path": round(head["ms_quant_fused"], 5)},
         "quantize_weight_ms": round(head["ms_quantize_weight"], 5),
         "quantize_weight_block_ms": round(head["ms_quantize_weight_block"], 5),
         "calibrate_act": {"bound": "hbm", "ms_per_call": round(head["ms_calibrate"], 5), "achieved": round(head["calib_gbs"], 1),

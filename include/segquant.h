@@ -140,6 +140,37 @@ sq_status sq_quantize_act(const sq_layer* layer, const void* x, sq_dtype x_dt, i
                           void* stream);
 
 /*
+ * sq_quantize_act with the polarity-asymmetric activation fused in front of it (Sec. 4.3.1: the layer's input comes
+ * from SiLU / GELU; Sec. 4.3.2): xq = Q_dual(act(h)), one pass over the pre-activation instead of an activation
+ * pass that writes what the quantizer then reads.  One activation code per K-segment (a concatenated input may
+ * carry an activation on one part only).  The codes are integers decided by floating point, so the activation is
+ * specified to the bit, in fp32, every operation individually rounded:
+ *   exp32(t) = +inf for t > 88;  t <- max(t, -87);  n = round_half_even(t * 1.44269504);
+ *              r = fma(n, -0.693145751953125, t);  r = fma(n, -1.42860682e-6, r);
+ *              p = 1/5040;  p = fma(p, r, c) for c = 1/720, 1/120, 1/24, 1/6, 1/2, 1, 1;  exp32 = p * 2^n
+ *   SQ_ACT_SILU  x / (1 + exp32(-x))
+ *   SQ_ACT_GELU  x / (1 + exp32(-z)),  z = (1.59576912 * x) * fma(0.044715, x * x, 1)      (the tanh form)
+ * The activation's fp32 value is quantized as it is (no rounding to bf16 in between).
+ *   h    dev, [M][K] of h_dt (pre-activation)                in
+ *   act  host, int32 [S], SQ_ACT_* per K-segment             in
+ *   xq   dev, int8 [M][K], polarity-merged codes             out
+ *   workspace  dev or NULL.  With a workspace of at least sq_quantize_act_fused_workspace_bytes(layer) bytes
+ *        (16-byte aligned, contents irrelevant on entry, owned by the caller, used only during the call; calls
+ *        that share it must not overlap) a bf16 input with 16-aligned K-segments is served by table: the
+ *        65536-entry map  bf16 pattern -> code  of every K-segment is filled first with the arithmetic above and
+ *        the pass becomes one table read per element (same codes, HBM-bound instead of ALU-bound).  NULL, fp32
+ *        input or unaligned segments: the arithmetic runs per element.
+ * SQ_ERR_INVALID_ARG for an unknown activation code or a workspace that is too small or misaligned; otherwise as
+ * sq_quantize_act.
+ */
+#define SQ_ACT_NONE 0
+#define SQ_ACT_SILU 1
+#define SQ_ACT_GELU 2
+size_t sq_quantize_act_fused_workspace_bytes(const sq_layer* layer);
+sq_status sq_quantize_act_fused(const sq_layer* layer, const void* h, sq_dtype h_dt, const int32_t* act, int8_t* xq,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Dual-path integer GEMM with per-K-segment accumulators and the fused dequant epilogue
  * (Sec. 4.2.2 items 1-2 combined with the last display of Sec. 4.3.2):
  *   acc_+[ks][m][n] = sum_{k in ks} X^_+[m][k] wq[n][k]              (int32, exact)

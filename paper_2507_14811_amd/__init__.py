@@ -12,7 +12,12 @@ from .binding import (  # noqa: F401
     sq_calibrate_act,
     sq_calibrate_act_percentile,
     sq_calibrate_workspace_bytes,
+    SQ_ACT_GELU,
+    SQ_ACT_NONE,
+    SQ_ACT_SILU,
     sq_quantize_act,
+    sq_quantize_act_fused,
+    sq_quantize_act_fused_workspace_bytes,
     sq_quantize_weight,
     sq_quantize_weight_block,
     sq_seglinear,

@@ -23,7 +23,8 @@ SQ_MAX_KSEG_LEN = 133143
 EXPORTS = ("sq_quantize_weight", "sq_quantize_act", "sq_seglinear", "sq_seglinear_debug_acc",
            "sq_status_string", "sq_version", "sq_tuning_set", "sq_probe_mfma", "sq_seglinear_grouped",
            "sq_quantize_weight_block", "sq_calibrate_act", "sq_calibrate_act_percentile",
-           "sq_calibrate_workspace_bytes")
+           "sq_calibrate_workspace_bytes", "sq_quantize_act_fused",
+           "sq_quantize_act_fused_workspace_bytes")
 
 
 class SqError(RuntimeError):
@@ -73,6 +74,10 @@ def load_library() -> C.CDLL:
     lib.sq_quantize_weight_block.restype = i32
     lib.sq_calibrate_act.argtypes = [lp, vp, i32, vp, vp, i32, vp]
     lib.sq_calibrate_act.restype = i32
+    lib.sq_quantize_act_fused.argtypes = [lp, vp, i32, C.POINTER(C.c_int32), vp, vp, C.c_size_t, vp]
+    lib.sq_quantize_act_fused_workspace_bytes.argtypes = [lp]
+    lib.sq_quantize_act_fused_workspace_bytes.restype = C.c_size_t
+    lib.sq_quantize_act_fused.restype = i32
     lib.sq_calibrate_act_percentile.argtypes = [lp, vp, i32, C.c_double, vp, vp, vp, C.c_size_t, i32, vp]
     lib.sq_calibrate_act_percentile.restype = i32
     lib.sq_calibrate_workspace_bytes.argtypes = []
@@ -207,6 +212,25 @@ def sq_quantize_act(layer: Layer, x, xq, stream=None) -> None:
     """x [M][K] fp32/bf16 -> xq int8 [M][K], polarity-merged codes (X^_+ = max(xq, 0), X^_- = min(xq, 0))."""
     _check(load_library().sq_quantize_act(C.byref(layer.c), _dptr(x), _dt(x), _dptr(xq), _stream(stream)),
            "sq_quantize_act")
+
+
+SQ_ACT_NONE, SQ_ACT_SILU, SQ_ACT_GELU = 0, 1, 2
+
+
+def sq_quantize_act_fused_workspace_bytes(layer: Layer) -> int:
+    """Device bytes of the optional workspace of sq_quantize_act_fused (code tables, 64 KiB per K-segment)."""
+    return int(load_library().sq_quantize_act_fused_workspace_bytes(C.byref(layer.c)))
+
+
+def sq_quantize_act_fused(layer: Layer, h, act, xq, workspace=None, stream=None) -> None:
+    """xq = Q_dual(act(h)): h [M][K] fp32/bf16 pre-activation, act: SQ_ACT_* per K-segment (host sequence);
+    workspace: optional device byte tensor (bf16 inputs are then served by code tables)."""
+    codes = (C.c_int32 * max(len(act), 1))(*[int(a) for a in act])
+    if len(act) != layer.c.S:
+        raise ValueError("one activation code per K-segment")
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load_library().sq_quantize_act_fused(C.byref(layer.c), _dptr(h), _dt(h), codes, _dptr(xq), _dptr(workspace),
+                                                nbytes, _stream(stream)), "sq_quantize_act_fused")
 
 
 def sq_seglinear(layer: Layer, xq, wq, wscale, bias, y, stream=None) -> None:

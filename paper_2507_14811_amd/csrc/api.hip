@@ -190,7 +190,8 @@ sq_status sq_calibrate_act_percentile(const sq_layer* layer, const void* x, sq_d
   return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 
-sq_status sq_quantize_act(const sq_layer* layer, const void* x, sq_dtype x_dt, int8_t* xq, void* stream) {
+static sq_status quantize_act_common(const sq_layer* layer, const void* x, sq_dtype x_dt, const int32_t* act, int8_t* xq,
+                                     void* workspace, size_t workspace_bytes, void* stream) {
   sq_status st = check_layer(layer, true, true);
   if (st != SQ_OK) return st;
   if (x == nullptr || xq == nullptr) return SQ_ERR_INVALID_ARG;
@@ -205,10 +206,40 @@ sq_status sq_quantize_act(const sq_layer* layer, const void* x, sq_dtype x_dt, i
     tb.inv_pos[s] = safe_inv(layer->s_pos[s]);
     tb.s_neg[s] = layer->dual[s] ? layer->s_neg[s] : 1.0f;
     tb.inv_neg[s] = layer->dual[s] ? safe_inv(layer->s_neg[s]) : 1.0f;
+    tb.act[s] = SQ_ACT_NONE;
+    if (act != nullptr) {
+      if (act[s] != SQ_ACT_NONE && act[s] != SQ_ACT_SILU && act[s] != SQ_ACT_GELU) return SQ_ERR_INVALID_ARG;
+      tb.act[s] = act[s];
+    }
   }
-  hipError_t e = sq::launch_quantize_act(x, x_dt == SQ_BF16, xq, layer->M, layer->K, tb,
-                                         reinterpret_cast<hipStream_t>(stream));
+  hipStream_t hs = reinterpret_cast<hipStream_t>(stream);
+  hipError_t e;
+  if (workspace != nullptr) {
+    if (workspace_bytes < sq::quantize_act_fused_workspace_bytes(layer->S) || reinterpret_cast<uintptr_t>(workspace) % 16 != 0)
+      return SQ_ERR_INVALID_ARG;
+    if (sq::quantize_act_lut_usable(x, x_dt == SQ_BF16, xq, layer->K, tb))
+      e = sq::launch_quantize_act_lut(x, xq, layer->M, layer->K, tb, workspace, sq::device_cus(), hs);
+    else
+      e = sq::launch_quantize_act(x, x_dt == SQ_BF16, xq, layer->M, layer->K, tb, hs);
+  } else {
+    e = sq::launch_quantize_act(x, x_dt == SQ_BF16, xq, layer->M, layer->K, tb, hs);
+  }
   return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
+sq_status sq_quantize_act(const sq_layer* layer, const void* x, sq_dtype x_dt, int8_t* xq, void* stream) {
+  return quantize_act_common(layer, x, x_dt, nullptr, xq, nullptr, 0, stream);
+}
+
+size_t sq_quantize_act_fused_workspace_bytes(const sq_layer* layer) {
+  if (layer == nullptr || layer->S < 1 || layer->S > SQ_MAX_SEGMENTS) return 0;
+  return sq::quantize_act_fused_workspace_bytes(layer->S);
+}
+
+sq_status sq_quantize_act_fused(const sq_layer* layer, const void* h, sq_dtype h_dt, const int32_t* act, int8_t* xq,
+                                void* workspace, size_t workspace_bytes, void* stream) {
+  if (act == nullptr) return SQ_ERR_INVALID_ARG;
+  return quantize_act_common(layer, h, h_dt, act, xq, workspace, workspace_bytes, stream);
 }
 
 sq_status sq_seglinear(const sq_layer* layer, const int8_t* xq, const int8_t* wq, const float* wscale,

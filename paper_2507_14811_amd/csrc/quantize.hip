@@ -22,7 +22,7 @@ __device__ __forceinline__ uint32_t pack4(int c0, int c1, int c2, int c3) {
   return (uint32_t)(c0 & 0xFF) | ((uint32_t)(c1 & 0xFF) << 8) | ((uint32_t)(c2 & 0xFF) << 16) | ((uint32_t)c3 << 24);
 }
 
-template <bool BF16, bool ONESEG>
+template <bool BF16, bool ONESEG, bool ACT>
 __global__ __launch_bounds__(256) void quantize_act_fast_kernel(const void* __restrict__ x, int8_t* __restrict__ xq,
                                                                 uint32_t nchunks, uint32_t kchunks, uint32_t kmagic,
                                                                 const ActTable tb) {
@@ -45,6 +45,7 @@ __global__ __launch_bounds__(256) void quantize_act_fast_kernel(const void* __re
     if (c >= nchunks) continue;
     float sp = tb.s_pos[0], sn = tb.s_neg[0], ip = tb.inv_pos[0], in = tb.inv_neg[0];
     bool dual = tb.dual[0] != 0;
+    int acode = ACT ? tb.act[0] : SQ_ACT_NONE;
     if (!ONESEG) {
       // column of this chunk: c mod kchunks via a reciprocal multiply (q is exact or one too small)
       uint32_t q = __umulhi(c, kmagic);
@@ -54,6 +55,7 @@ __global__ __launch_bounds__(256) void quantize_act_fast_kernel(const void* __re
       for (int s = 1; s < tb.S; ++s) {
         if (col >= tb.kseg_off[s]) {
           sp = tb.s_pos[s]; sn = tb.s_neg[s]; ip = tb.inv_pos[s]; in = tb.inv_neg[s]; dual = tb.dual[s] != 0;
+          if (ACT) acode = tb.act[s];
         }
       }
     }
@@ -72,6 +74,10 @@ __global__ __launch_bounds__(256) void quantize_act_fast_kernel(const void* __re
 #pragma unroll
         for (int i = 0; i < 4; ++i) v[i] = __int_as_float(raw[j][BF16 ? 0 : g][i]);
       }
+      if (ACT) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = activate(acode, v[i]);
+      }
       int code[4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
@@ -85,7 +91,7 @@ __global__ __launch_bounds__(256) void quantize_act_fast_kernel(const void* __re
 }
 
 // Any K / segment alignment: one element per thread.
-template <bool BF16>
+template <bool BF16, bool ACT>
 __global__ __launch_bounds__(256) void quantize_act_generic_kernel(const void* __restrict__ x, int8_t* __restrict__ xq,
                                                                    int M, int K, const ActTable tb) {
   const size_t total = (size_t)M * K;
@@ -93,19 +99,23 @@ __global__ __launch_bounds__(256) void quantize_act_generic_kernel(const void* _
     const int col = (int)(i % (size_t)K);
     float sp = tb.s_pos[0], sn = tb.s_neg[0], ip = tb.inv_pos[0], in = tb.inv_neg[0];
     bool dual = tb.dual[0] != 0;
+    int acode = ACT ? tb.act[0] : SQ_ACT_NONE;
     for (int s = 1; s < tb.S; ++s) {
       if (col >= tb.kseg_off[s]) {
         sp = tb.s_pos[s]; sn = tb.s_neg[s]; ip = tb.inv_pos[s]; in = tb.inv_neg[s]; dual = tb.dual[s] != 0;
+        if (ACT) acode = tb.act[s];
       }
     }
-    const float v = BF16 ? bf16_to_f32(reinterpret_cast<const uint16_t*>(x)[i]) : reinterpret_cast<const float*>(x)[i];
+    float v = BF16 ? bf16_to_f32(reinterpret_cast<const uint16_t*>(x)[i]) : reinterpret_cast<const float*>(x)[i];
+    if (ACT) v = activate(acode, v);
     const bool ng = dual && (v < 0.0f);
     xq[i] = (int8_t)clip_code(round_quotient(v, ng ? sn : sp, ng ? in : ip));
   }
 }
 
-hipError_t launch_quantize_act(const void* x, bool x_is_bf16, int8_t* xq, int M, int K, const ActTable& tb,
-                               hipStream_t st) {
+template <bool ACT>
+static hipError_t launch_quantize_act_impl(const void* x, bool x_is_bf16, int8_t* xq, int M, int K, const ActTable& tb,
+                                           hipStream_t st) {
   bool aligned = (K % kActChunk == 0) && (reinterpret_cast<uintptr_t>(x) % 16 == 0) &&
                  (reinterpret_cast<uintptr_t>(xq) % 16 == 0);
   for (int s = 0; s <= tb.S; ++s) aligned = aligned && (tb.kseg_off[s] % kActChunk == 0);
@@ -116,17 +126,130 @@ hipError_t launch_quantize_act(const void* x, bool x_is_bf16, int8_t* xq, int M,
     const unsigned blocks = (nchunks + 256u * kActUnroll - 1) / (256u * kActUnroll);
     const bool one = (tb.S == 1);
 #define SQ_LAUNCH_ACT(B, O) \
-  hipLaunchKernelGGL((quantize_act_fast_kernel<B, O>), dim3(blocks), dim3(256), 0, st, x, xq, nchunks, kchunks, kmagic, tb)
+  hipLaunchKernelGGL((quantize_act_fast_kernel<B, O, ACT>), dim3(blocks), dim3(256), 0, st, x, xq, nchunks, kchunks, kmagic, tb)
     if (x_is_bf16) { if (one) SQ_LAUNCH_ACT(true, true); else SQ_LAUNCH_ACT(true, false); }
     else           { if (one) SQ_LAUNCH_ACT(false, true); else SQ_LAUNCH_ACT(false, false); }
 #undef SQ_LAUNCH_ACT
   } else {
     const size_t total = (size_t)M * K;
     const unsigned blocks = (unsigned)((total + 255) / 256 > 65536 ? 65536 : (total + 255) / 256);
-    if (x_is_bf16) hipLaunchKernelGGL((quantize_act_generic_kernel<true>), dim3(blocks), dim3(256), 0, st, x, xq, M, K, tb);
-    else           hipLaunchKernelGGL((quantize_act_generic_kernel<false>), dim3(blocks), dim3(256), 0, st, x, xq, M, K, tb);
+    if (x_is_bf16) hipLaunchKernelGGL((quantize_act_generic_kernel<true, ACT>), dim3(blocks), dim3(256), 0, st, x, xq, M, K, tb);
+    else           hipLaunchKernelGGL((quantize_act_generic_kernel<false, ACT>), dim3(blocks), dim3(256), 0, st, x, xq, M, K, tb);
   }
   return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// Fused activation + quantizer for bf16 inputs by table: a bf16 number has 65536 bit patterns, so per K-segment
+// the whole map  h -> code of Q_dual(act(h))  is a 64 KiB table.  A small kernel fills the tables with the very
+// arithmetic of the direct path (so the codes are the same to the bit); the streaming kernel keeps one segment's
+// table in LDS (two workgroups of 64 KiB per CU) and turns every element into one LDS byte read.  The direct path
+// costs ~45 ALU instructions per element and is ALU-bound at twice the HBM time; this one is a stream again.
+// ------------------------------------------------------------------------------------------------
+constexpr int kLutBytes = 65536;
+constexpr int kLutThreads = 512;
+
+__global__ __launch_bounds__(256) void act_lut_build_kernel(const ActTable tb, int8_t* __restrict__ lut) {
+  const int ks = blockIdx.y;
+  const uint32_t bits = blockIdx.x * 256u + threadIdx.x;                    // grid.x = 256
+  float sp = 1.0f, sn = 1.0f, ip = 1.0f, in = 1.0f;
+  bool dual = false;
+  int acode = SQ_ACT_NONE;
+  for (int s = 0; s < tb.S; ++s)
+    if (s == ks) { sp = tb.s_pos[s]; sn = tb.s_neg[s]; ip = tb.inv_pos[s]; in = tb.inv_neg[s]; dual = tb.dual[s] != 0; acode = tb.act[s]; }
+  const float v = activate(acode, __uint_as_float(bits << 16));
+  const bool ng = dual && (v < 0.0f);
+  lut[(size_t)ks * kLutBytes + bits] = (int8_t)clip_code(round_quotient(v, ng ? sn : sp, ng ? in : ip));
+}
+
+struct LutPlan {                         // workgroups [wg_begin[s], wg_begin[s+1]) stream K-segment s
+  int wg_begin[SQ_MAX_SEGMENTS + 1];
+};
+
+__global__ __launch_bounds__(kLutThreads) void quantize_act_lut_kernel(const uint16_t* __restrict__ h, int8_t* __restrict__ xq,
+                                                                       int M, int K, const ActTable tb, const LutPlan plan,
+                                                                       const int8_t* __restrict__ lut) {
+  __shared__ __attribute__((aligned(16))) uint8_t table[kLutBytes];
+  int ks = 0;
+  for (int s = 1; s < tb.S; ++s)
+    if ((int)blockIdx.x >= plan.wg_begin[s]) ks = s;
+  int k0 = 0, k1 = 0, wg0 = 0, wg1 = 1;
+  for (int s = 0; s < tb.S; ++s)
+    if (s == ks) { k0 = tb.kseg_off[s]; k1 = tb.kseg_off[s + 1]; wg0 = plan.wg_begin[s]; wg1 = plan.wg_begin[s + 1]; }
+  {
+    const v4i* src = reinterpret_cast<const v4i*>(lut + (size_t)ks * kLutBytes);
+    for (int i = threadIdx.x; i < kLutBytes / 16; i += kLutThreads) reinterpret_cast<v4i*>(table)[i] = src[i];
+  }
+  __syncthreads();
+  const uint32_t cps = (uint32_t)(k1 - k0) / kActChunk;                    // 16-element chunks per row of the segment
+  const uint32_t nchunks = (uint32_t)M * cps;
+  const uint32_t stride = (uint32_t)(wg1 - wg0) * kLutThreads;
+  constexpr int U = 4;
+  for (uint32_t c0 = (uint32_t)((int)blockIdx.x - wg0) * kLutThreads + threadIdx.x; c0 < nchunks; c0 += U * stride) {
+    v4i raw[U][2];
+    size_t eoff[U];
+#pragma unroll
+    for (int j = 0; j < U; ++j) {
+      const uint32_t c = c0 + j * stride;
+      if (c < nchunks) {
+        const uint32_t r = c / cps, cc = c - r * cps;
+        eoff[j] = (size_t)r * K + k0 + (size_t)cc * kActChunk;
+        const v4i* p = reinterpret_cast<const v4i*>(h + eoff[j]);
+        raw[j][0] = __builtin_nontemporal_load(p);
+        raw[j][1] = __builtin_nontemporal_load(p + 1);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < U; ++j) {
+      const uint32_t c = c0 + j * stride;
+      if (c >= nchunks) continue;
+      v4i out;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const uint32_t u0 = (uint32_t)raw[j][g / 2][(g % 2) * 2], u1 = (uint32_t)raw[j][g / 2][(g % 2) * 2 + 1];
+        const uint32_t b0 = table[u0 & 0xFFFFu], b1 = table[u0 >> 16], b2 = table[u1 & 0xFFFFu], b3 = table[u1 >> 16];
+        out[g] = (int)(b0 | (b1 << 8) | (b2 << 16) | (b3 << 24));
+      }
+      *reinterpret_cast<v4i*>(xq + eoff[j]) = out;
+    }
+  }
+}
+
+size_t quantize_act_fused_workspace_bytes(int S) { return (size_t)S * kLutBytes; }
+
+bool quantize_act_lut_usable(const void* h, bool h_is_bf16, const int8_t* xq, int K, const ActTable& tb) {
+  bool ok = h_is_bf16 && (K % kActChunk == 0) && (reinterpret_cast<uintptr_t>(h) % 16 == 0) &&
+            (reinterpret_cast<uintptr_t>(xq) % 16 == 0);
+  for (int s = 0; s <= tb.S; ++s) ok = ok && (tb.kseg_off[s] % kActChunk == 0);
+  return ok;
+}
+
+hipError_t launch_quantize_act_lut(const void* h, int8_t* xq, int M, int K, const ActTable& tb, void* workspace, int cus,
+                                   hipStream_t st) {
+  int8_t* lut = reinterpret_cast<int8_t*>(workspace);
+  hipLaunchKernelGGL(act_lut_build_kernel, dim3(256, tb.S), dim3(256), 0, st, tb, lut);
+  // two workgroups per CU, dealt to the K-segments in proportion to their share of the matrix (at least one each)
+  const int total = 2 * cus > tb.S ? 2 * cus : tb.S;
+  LutPlan plan;
+  int given = 0;
+  for (int s = 0; s < tb.S; ++s) {
+    plan.wg_begin[s] = given;
+    const long long share = (long long)(total - tb.S) * (tb.kseg_off[s + 1] - tb.kseg_off[s]) / K;
+    given += 1 + (int)share;
+  }
+  plan.wg_begin[tb.S] = given;
+  hipLaunchKernelGGL(quantize_act_lut_kernel, dim3(given), dim3(kLutThreads), 0, st, reinterpret_cast<const uint16_t*>(h), xq,
+                     M, K, tb, plan, lut);
+  return hipGetLastError();
+}
+
+// tb.act is read only when some K-segment has an activation fused in front of it (sq_quantize_act_fused)
+hipError_t launch_quantize_act(const void* x, bool x_is_bf16, int8_t* xq, int M, int K, const ActTable& tb,
+                               hipStream_t st) {
+  bool any = false;
+  for (int s = 0; s < tb.S; ++s) any = any || tb.act[s] != SQ_ACT_NONE;
+  return any ? launch_quantize_act_impl<true>(x, x_is_bf16, xq, M, K, tb, st)
+             : launch_quantize_act_impl<false>(x, x_is_bf16, xq, M, K, tb, st);
 }
 
 // ------------------------------------------------------------------------------------------------

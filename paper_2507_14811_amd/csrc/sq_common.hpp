@@ -29,6 +29,7 @@ struct ActTable {                      // for the activation quantize pass
   float inv_pos[SQ_MAX_SEGMENTS];      // 1 / s (NaN = reciprocal not usable, always divide)
   float inv_neg[SQ_MAX_SEGMENTS];
   int dual[SQ_MAX_SEGMENTS];           // 32-bit on purpose, see the note below
+  int act[SQ_MAX_SEGMENTS];            // activation fused in front of the quantizer: SQ_ACT_* per K-segment
 };
 
 struct GemmTable {                     // for the SegLinear GEMM kernels
@@ -101,6 +102,40 @@ __device__ __forceinline__ float round_quotient(float v, float s, float inv) {
   float t = q0 - r;
   if (!(__builtin_fabsf(t) < 0.4998779296875f)) r = __builtin_rintf(v / s);
   return r;
+}
+
+// The activation in front of a DualScale layer (Sec. 4.3.1: SiLU, GELU), evaluated in fp32 with a fixed
+// operation sequence, every operation individually rounded (contraction is switched off in these functions), so that the
+// codes decided from its result are reproducible to the bit:
+//   exp32(t) = +inf for t > 88; t <- max(t, -87); n = rint(t log2 e); r = t - n ln2 (ln2 in two parts, fma);
+//              degree-7 Taylor polynomial in r by Horner with fma; times 2^n
+//   SiLU(x) = x / (1 + exp32(-x));   GELU(x) = x / (1 + exp32(-z)), z = (1.59576912 x) fma(0.044715, x x, 1),
+//   the tanh form of GELU written with 0.5 (1 + tanh u) = 1 / (1 + e^(-2u)).
+__device__ __forceinline__ float exp32(float t) {
+#pragma clang fp contract(off)
+  const bool over = t > 88.0f;
+  t = __builtin_fminf(__builtin_fmaxf(t, -87.0f), 88.0f);
+  const float n = __builtin_rintf(__fmul_rn(t, 1.44269504f));
+  float r = __fmaf_rn(n, -0.693145751953125f, t);
+  r = __fmaf_rn(n, -1.42860682e-6f, r);
+  float p = 1.0f / 5040.0f;
+  p = __fmaf_rn(p, r, 1.0f / 720.0f);
+  p = __fmaf_rn(p, r, 1.0f / 120.0f);
+  p = __fmaf_rn(p, r, 1.0f / 24.0f);
+  p = __fmaf_rn(p, r, 1.0f / 6.0f);
+  p = __fmaf_rn(p, r, 0.5f);
+  p = __fmaf_rn(p, r, 1.0f);
+  p = __fmaf_rn(p, r, 1.0f);
+  const float two_n = __uint_as_float((uint32_t)((int)n + 127) << 23);     // n in [-126, 127]
+  return over ? __builtin_inff() : __fmul_rn(p, two_n);
+}
+
+__device__ __forceinline__ float activate(int code, float x) {
+#pragma clang fp contract(off)
+  if (code == SQ_ACT_NONE) return x;
+  float z = x;
+  if (code == SQ_ACT_GELU) z = __fmul_rn(__fmul_rn(1.59576912f, x), __fmaf_rn(0.044715f, __fmul_rn(x, x), 1.0f));
+  return __fdiv_rn(x, __fadd_rn(1.0f, exp32(-z)));
 }
 
 __device__ __forceinline__ int clip_code(float r) {

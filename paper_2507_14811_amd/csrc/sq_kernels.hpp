@@ -14,6 +14,11 @@ enum OutMode { OUT_F32 = 0, OUT_BF16 = 1, OUT_DEBUG_ACC = 2 };
 // quantize.hip
 hipError_t launch_quantize_act(const void* x, bool x_is_bf16, int8_t* xq, int M, int K, const ActTable& tb,
                                hipStream_t st);
+// bf16 inputs of the fused activation + quantizer: per-K-segment code tables (S x 64 KiB of workspace), LDS lookups
+size_t quantize_act_fused_workspace_bytes(int S);
+bool quantize_act_lut_usable(const void* h, bool h_is_bf16, const int8_t* xq, int K, const ActTable& tb);
+hipError_t launch_quantize_act_lut(const void* h, int8_t* xq, int M, int K, const ActTable& tb, void* workspace, int cus,
+                                   hipStream_t st);
 hipError_t launch_quantize_weight(const void* w, bool w_is_bf16, int8_t* wq, float* wscale, int N, int K,
                                   const KsegTable& tb, hipStream_t st);
 

@@ -106,6 +106,94 @@ def test_quantize_act_near_ties(oracle):
     assert np.array_equal(xp, rp) and np.array_equal(xn, rn)
 
 
+FUSED = [
+    dict(M=70, K=512, kseg=[0, 128, 512], dual=[0, 1], act=[0, 2], h_dtype="bf16"),          # concat(plain, GELU(.))
+    dict(M=1100, K=3072, kseg=[0, 512, 3072], dual=[0, 1], act=[0, 2], h_dtype="bf16"),       # many chunks per workgroup
+    dict(M=3, K=1040, kseg=[0, 16, 1040], dual=[1, 1], act=[2, 1], h_dtype="bf16"),           # fewer chunks than threads
+    dict(M=70, K=512, kseg=[0, 128, 512], dual=[1, 1], act=[1, 2], h_dtype="f32"),
+    dict(M=13, K=100, kseg=[0, 37, 100], dual=[1, 1], act=[2, 1], h_dtype="bf16"),           # unaligned: generic kernel
+    dict(M=300, K=2048, kseg=[0, 2048], dual=[1], act=[1], h_dtype="bf16"),
+    dict(M=129, K=1024, kseg=[0, 16, 32, 48, 1024], dual=[1, 0, 1, 1], act=[1, 0, 2, 1], h_dtype="f32"),
+    dict(M=64, K=256, kseg=[0, 256], dual=[0], act=[2], h_dtype="f32"),                      # single-scale after an activation
+]
+
+
+@pytest.mark.parametrize("case", FUSED)
+@pytest.mark.parametrize("spread", ["unit", "wide"])
+def test_quantize_act_fused(oracle, case, spread):
+    """xq = Q_dual(act(h)) with the bit-specified fp32 SiLU / GELU: codes bit-exact against the oracle."""
+    import torch
+
+    g = _gpu()
+    M, K = case["M"], case["K"]
+    rng = np.random.default_rng(M * 31 + K)
+    h = rng.standard_normal((M, K)) * (1.0 if spread == "unit" else 12.0)
+    h = h.astype(np.float32)
+    if spread == "wide":                      # exercise the clamps of the exponential and exact zeros
+        h[0, :8] = [0.0, -0.0, 95.0, -95.0, 1e4, -1e4, 88.25, -88.25]
+    if case["h_dtype"] == "bf16":
+        h = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(h))
+        hd = torch.from_numpy(wl.f32_to_bf16_bits(h).view(np.int16)).view(torch.bfloat16).to(g.DEV)
+    else:
+        hd = torch.from_numpy(h).to(g.DEV)
+    a = oracle.activation(h, case["kseg"], case["act"])
+    sp, sn, _, _ = oracle.calibrate_act(a, case["kseg"], case["dual"])
+    layer = sq.Layer(M, K, 4, case["kseg"], [0, 4], case["dual"], sp, sn)
+    xq = torch.full((M, K), 99, dtype=torch.int8, device=g.DEV)
+    sq.sq_quantize_act_fused(layer, hd, case["act"], xq)
+    torch.cuda.synchronize()
+    rp, rn = oracle.quantize_act_fused(h, case["kseg"], case["dual"], case["act"], sp, sn)
+    got = xq.cpu().numpy()
+    want = (rp.astype(np.int16) + rn.astype(np.int16)).astype(np.int8)
+    bad = np.argwhere(got != want)
+    assert bad.size == 0, (len(bad), bad[:5], h[tuple(bad[0])], got[tuple(bad[0])], want[tuple(bad[0])])
+    # with a workspace (bf16 inputs with aligned segments go through the code tables): the same codes
+    ws = torch.full((sq.sq_quantize_act_fused_workspace_bytes(layer),), 0x33, dtype=torch.uint8, device=g.DEV)
+    xq_t = torch.full((M, K), 99, dtype=torch.int8, device=g.DEV)
+    sq.sq_quantize_act_fused(layer, hd, case["act"], xq_t, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(xq_t, xq)
+    # all-none codes: the plain quantizer
+    sq.sq_quantize_act_fused(layer, hd, [0] * len(case["act"]), xq)
+    xq2 = torch.empty_like(xq)
+    sq.sq_quantize_act(layer, hd, xq2)
+    torch.cuda.synchronize()
+    assert torch.equal(xq, xq2)
+
+
+@pytest.mark.parametrize("act", [1, 2])
+def test_quantize_act_fused_exhaustive_bf16_and_dense_f32(oracle, act):
+    """Every finite bf16 value, and 4 M fp32 values spread over the magnitudes that matter, through the fused pass."""
+    import torch
+
+    g = _gpu()
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    vals = wl.bf16_bits_to_f32(bits)
+    vals = vals[np.isfinite(vals)]
+    vals = np.concatenate([vals, np.zeros(65536 - vals.size, np.float32)]).reshape(64, 1024)
+    rng = np.random.default_rng(act)
+    mag = np.exp(rng.uniform(np.log(1e-4), np.log(120.0), size=(2048, 2048)))
+    dense = (mag * rng.choice([-1.0, 1.0], size=mag.shape)).astype(np.float32)
+    for h, dt in ((vals, "bf16"), (dense, "f32")):
+        M, K = h.shape
+        if dt == "bf16":
+            hd = torch.from_numpy(wl.f32_to_bf16_bits(h).view(np.int16)).view(torch.bfloat16).to(g.DEV)
+        else:
+            hd = torch.from_numpy(h).to(g.DEV)
+        sp, sn = np.array([0.011], np.float32), np.array([0.0021], np.float32)
+        layer = sq.Layer(M, K, 4, [0, K], [0, 4], [1], sp, sn)
+        xq = torch.empty((M, K), dtype=torch.int8, device=g.DEV)
+        ws = torch.empty((sq.sq_quantize_act_fused_workspace_bytes(layer),), dtype=torch.uint8, device=g.DEV) if dt == "bf16" else None
+        sq.sq_quantize_act_fused(layer, hd, [act], xq, workspace=ws)     # bf16: by table; fp32: arithmetic per element
+        torch.cuda.synchronize()
+        rp, rn = oracle.quantize_act_fused(h, [0, K], [1], [act], sp, sn)
+        want = (rp.astype(np.int16) + rn.astype(np.int16)).astype(np.int8)
+        got = xq.cpu().numpy()
+        bad = np.argwhere(got != want)
+        assert bad.size == 0, (dt, len(bad), h[tuple(bad[0])], got[tuple(bad[0])], want[tuple(bad[0])])
+        assert len(np.unique(want)) > 200                 # the sample really spans the code range
+
+
 # ----------------------------------------------------------------------------------------------------
 # SegLinear GEMM on small / ragged shapes, every kernel path
 # ----------------------------------------------------------------------------------------------------

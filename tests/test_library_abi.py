@@ -107,6 +107,13 @@ def test_invalid_arguments_are_rejected_on_the_host(sq):
     assert lib.sq_calibrate_act(C.byref(ok.c), None, 1, FAKE, FAKE, 0, None) == INVALID
     assert lib.sq_calibrate_act(C.byref(ok.c), FAKE, 1, None, FAKE, 0, None) == INVALID
     assert lib.sq_calibrate_act(C.byref(ok.c), FAKE, 4, FAKE, FAKE, 0, None) == INVALID
+    codes = (C.c_int32 * 1)(1)
+    fused = lambda h=FAKE, act=codes, ws=None, nbytes=0: lib.sq_quantize_act_fused(C.byref(ok.c), h, 1, act, FAKE, ws, nbytes, None)
+    assert fused(act=None) == INVALID and fused(h=None) == INVALID
+    assert fused(act=(C.c_int32 * 1)(3)) == INVALID and fused(act=(C.c_int32 * 1)(-1)) == INVALID
+    wneed = lib.sq_quantize_act_fused_workspace_bytes(C.byref(ok.c))
+    assert wneed == 65536 * ok.c.S and lib.sq_quantize_act_fused_workspace_bytes(None) == 0
+    assert fused(ws=FAKE, nbytes=wneed - 1) == INVALID and fused(ws=C.c_void_p(0x1008), nbytes=wneed) == INVALID
     need = lib.sq_calibrate_workspace_bytes()
     assert 0 < need < (1 << 20)
     pct = lambda p, ws=FAKE, nbytes=need, x=FAKE: lib.sq_calibrate_act_percentile(C.byref(ok.c), x, 1, p, FAKE, FAKE, ws, nbytes, 0, None)
