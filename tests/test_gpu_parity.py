@@ -591,3 +591,57 @@ def test_named_configs(oracle, name):
         rows = np.unique(np.concatenate([np.arange(0, 8), np.arange(w.M - 8, w.M), rng.integers(0, w.M, 48)]))
     out = _check_layer(oracle, g, w, path=-1, rows=rows)
     print(name, out)
+
+
+def test_headline_config_calibration_and_fused_quantizer(oracle):
+    """The entry points beyond the hot path, at the headline layer's full size (cfg5: 4608 x 15360 bf16, a plain
+    K-segment and a dual one), in the launch configuration the benchmark times: min/max steps against the oracle,
+    percentile thresholds through the counting definition of a quantile (valid at any size), and the fused
+    GELU + quantizer (table path and per-element path) against the oracle on sampled token rows."""
+    import torch
+
+    g = _gpu()
+    w = wl.make("cfg5")
+    M, K, S = w.M, w.K, w.S
+    xd = torch.from_numpy(wl.f32_to_bf16_bits(w.x).view(np.int16)).view(torch.bfloat16).to(g.DEV)
+    layer = sq.Layer.from_workload(w)
+    amax = torch.empty((2, S), dtype=torch.float32, device=g.DEV)
+    steps = torch.empty((2, S), dtype=torch.float32, device=g.DEV)
+    sq.sq_calibrate_act(layer, xd, amax, steps)
+    r = oracle.calibrate_act(w.x, w.kseg_off, w.dual)
+    torch.cuda.synchronize()
+    assert np.array_equal(steps.cpu().numpy().view(np.uint32), np.stack([r[0], r[1]]).view(np.uint32))
+    # percentile clipping
+    ws = torch.empty((sq.sq_calibrate_workspace_bytes(),), dtype=torch.uint8, device=g.DEV)
+    p = 0.9999
+    sq.sq_calibrate_act_percentile(layer, xd, p, amax, steps, ws)
+    torch.cuda.synchronize()
+    thr = amax.cpu().numpy()
+    for ks in range(S):
+        blk = w.x[:, w.kseg_off[ks]:w.kseg_off[ks + 1]]
+        n = blk.size
+        k = min(max(int(np.ceil(p * n)), 1), n)
+        pops = [(np.maximum(blk, 0), thr[0, ks]), (np.maximum(-blk, 0), thr[1, ks])] if w.dual[ks] else [(np.abs(blk), thr[0, ks])]
+        for v, t in pops:
+            assert np.count_nonzero(v <= t) >= k and np.count_nonzero(v < t) < k, (ks, float(t))
+        if not w.dual[ks]:
+            assert thr[1, ks] == 0.0
+    # fused GELU + quantizer on the dual segment, steps from the activation's own range
+    rng = np.random.default_rng(11)
+    h = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits((rng.standard_normal((M, K)) * 1.5).astype(np.float32)))
+    hd = torch.from_numpy(wl.f32_to_bf16_bits(h).view(np.int16)).view(torch.bfloat16).to(g.DEV)
+    act = [sq.SQ_ACT_GELU if d else sq.SQ_ACT_NONE for d in w.dual]
+    rows = np.unique(np.concatenate([np.arange(0, 4), np.arange(M - 4, M), rng.integers(0, M, 24)]))
+    a_s = oracle.activation(h[rows], w.kseg_off, act)
+    sp, sn, _, _ = oracle.calibrate_act(a_s, w.kseg_off, w.dual)
+    lay = sq.Layer(M, K, w.N, w.kseg_off, w.nseg_off, w.dual, sp, sn)
+    rp, rn = oracle.quantize_act_fused(h[rows], w.kseg_off, w.dual, act, sp, sn)
+    want = (rp.astype(np.int16) + rn.astype(np.int16)).astype(np.int8)
+    fws = torch.empty((sq.sq_quantize_act_fused_workspace_bytes(lay),), dtype=torch.uint8, device=g.DEV)
+    xq_t = torch.empty((M, K), dtype=torch.int8, device=g.DEV)
+    xq_e = torch.empty((M, K), dtype=torch.int8, device=g.DEV)
+    sq.sq_quantize_act_fused(lay, hd, act, xq_t, workspace=fws)
+    sq.sq_quantize_act_fused(lay, hd, act, xq_e)
+    torch.cuda.synchronize()
+    assert torch.equal(xq_t, xq_e)                                   # the two device paths agree everywhere
+    assert np.array_equal(xq_t.cpu().numpy()[rows], want)            # and with the oracle on the sampled rows
