@@ -135,6 +135,8 @@ struct PctRanks {                                 // per K-segment: elements of 
   unsigned int r[SQ_MAX_SEGMENTS];
 };
 
+constexpr int kPctCopies = 8;
+
 size_t calibrate_workspace_bytes() { return sizeof(PctState); }
 
 __global__ void pct_init_kernel(PctState* __restrict__ st, const PctRanks rk, int S) {
@@ -162,15 +164,17 @@ __global__ __launch_bounds__(256) void pct_hist_kernel(const void* __restrict__ 
   const int L = k1 - k0;
   const int r0 = blockIdx.x * kCalibRows;
   const int nrows = (M - r0) < kCalibRows ? (M - r0) : kCalibRows;
-  __shared__ unsigned int h[2][256];
-  h[0][threadIdx.x] = 0u;
-  h[1][threadIdx.x] = 0u;
+  // kPctCopies copies of every bin, consecutive in LDS (so in different banks), one per lane class: activations
+  // put a third of a wave's lanes on one exponent bin, and same-address LDS atomics serialize
+  __shared__ unsigned int h[2][256][kPctCopies];
+  for (int i = threadIdx.x; i < 2 * 256 * kPctCopies; i += 256) (&h[0][0][0])[i] = 0u;
   const unsigned int pre_p = st->prefix[ks][0], pre_n = st->prefix[ks][1];
+  const int copy = threadIdx.x & (kPctCopies - 1);
   __syncthreads();
   auto count = [&](int pol, unsigned int bits, unsigned int pre) {
     if ((bits & himask) == pre) {
       const unsigned int d = (bits >> shift) & dmask;
-      if (d != 0u) atomicAdd(&h[pol][d], 1u);
+      if (d != 0u) atomicAdd(&h[pol][d][copy], 1u);
     }
   };
   auto take = [&](float v) {
@@ -223,40 +227,53 @@ __global__ __launch_bounds__(256) void pct_hist_kernel(const void* __restrict__ 
   __syncthreads();
 #pragma unroll
   for (int pol = 0; pol < 2; ++pol) {
-    const unsigned int c = h[pol][threadIdx.x];
+    unsigned int c = 0u;
+#pragma unroll
+    for (int i = 0; i < kPctCopies; ++i) c += h[pol][threadIdx.x][i];
     if (c != 0u) atomicAdd(&st->hist[ks][pol][threadIdx.x], c);
   }
 }
 
-// One thread per (K-segment, polarity): pick the digit, narrow the bucket, clear the histogram for the next pass.
-// After the last digit the prefix is the threshold: fold it into the running maxima and write the steps
-// (amax, steps: [2][S], as the min/max calibration).
-__global__ void pct_select_kernel(PctState* __restrict__ st, int S, int shift, int last, int accumulate,
-                                  float* __restrict__ amax, float* __restrict__ steps) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= 2 * S) return;
+// One 256-thread workgroup per (K-segment, polarity): suffix sums of the 256 bins from the top (a log-step scan in
+// LDS); the bin d >= 1 whose suffix sum first reaches the wanted rank holds it, else it lies in the uncounted digit 0.
+// The bucket is narrowed to that bin and the histogram cleared for the next pass.  After the last digit the prefix is
+// the threshold: fold it into the running maxima and write the steps (amax, steps: [2][S], as the min/max calibration).
+__global__ __launch_bounds__(256) void pct_select_kernel(PctState* __restrict__ st, int S, int shift, int last, int accumulate,
+                                                         float* __restrict__ amax, float* __restrict__ steps) {
+  const int i = blockIdx.x;                                  // grid: 2 S
   const int pol = i / S, ks = i - pol * S;
+  const int d = threadIdx.x;
   unsigned int* h = st->hist[ks][pol];
-  const unsigned int r = st->rank[ks][pol];
-  unsigned int cum = 0u;
-  int d = 255;
-  for (; d >= 1; --d) {
-    const unsigned int c = h[d];
-    if (cum + c >= r) break;
-    cum += c;
+  __shared__ unsigned int suf[256];
+  const unsigned int own = d >= 1 ? h[d] : 0u;               // digit 0 is not counted
+  h[d] = 0u;
+  suf[d] = own;
+  __syncthreads();
+  for (int off = 1; off < 256; off <<= 1) {                  // suf[d] = sum of bins d .. 255
+    const unsigned int add = d + off < 256 ? suf[d + off] : 0u;
+    __syncthreads();
+    suf[d] += add;
+    __syncthreads();
   }
-  // d >= 1: the rank falls into bin d.  d == 0: it falls into the uncounted digit 0, which holds the rest.
-  st->rank[ks][pol] = r - cum;
-  st->bucket[ks][pol] = d >= 1 ? h[d] : st->bucket[ks][pol] - cum;
-  const unsigned int pre = st->prefix[ks][pol] | ((unsigned int)d << shift);
-  st->prefix[ks][pol] = pre;
-  for (int b = 0; b < 256; ++b) h[b] = 0u;
-  if (last) {
-    const float t = __uint_as_float(pre);
-    float a = accumulate ? amax[i] : 0.0f;
-    a = __builtin_fmaxf(a, t);
-    amax[i] = a;
-    steps[i] = (a == 0.0f) ? 1.0f : a / kQmax;
+  const unsigned int r = st->rank[ks][pol], bucket = st->bucket[ks][pol], pre = st->prefix[ks][pol];
+  const unsigned int above = d < 255 ? suf[d + 1] : 0u;      // elements in bins above d
+  const unsigned int total = suf[1];                         // all counted elements (bins 1 .. 255)
+  __syncthreads();
+  // exactly one thread holds the rank: bin d >= 1 with above < r <= above + own, or d == 0 when r > total
+  const bool mine = d >= 1 ? (above < r && r <= above + own) : (r > total);
+  if (mine) {
+    const unsigned int taken = d >= 1 ? above : total;
+    const unsigned int npre = pre | ((unsigned int)d << shift);
+    st->rank[ks][pol] = r - taken;
+    st->bucket[ks][pol] = d >= 1 ? own : bucket - total;
+    st->prefix[ks][pol] = npre;
+    if (last) {
+      const float t = __uint_as_float(npre);
+      float a = accumulate ? amax[i] : 0.0f;
+      a = __builtin_fmaxf(a, t);
+      amax[i] = a;
+      steps[i] = (a == 0.0f) ? 1.0f : a / kQmax;
+    }
   }
 }
 
@@ -289,7 +306,7 @@ hipError_t launch_calibrate_act_percentile(const void* x, bool x_is_bf16, int M,
     if (x_is_bf16) { if (vec) SQ_PCT(true, true); else SQ_PCT(true, false); }
     else           { if (vec) SQ_PCT(false, true); else SQ_PCT(false, false); }
 #undef SQ_PCT
-    hipLaunchKernelGGL(pct_select_kernel, dim3(1), dim3(2 * SQ_MAX_SEGMENTS), 0, st, ws, tb.S, shift,
+    hipLaunchKernelGGL(pct_select_kernel, dim3(2 * tb.S), dim3(256), 0, st, ws, tb.S, shift,
                        ps == npass - 1 ? 1 : 0, accumulate ? 1 : 0, amax, steps);
   }
   return hipGetLastError();
