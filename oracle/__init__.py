@@ -22,6 +22,8 @@ from .segquant_oracle import (  # noqa: F401
     quantize_act_fused,
     quantize_weight,
     quantize_weight_block,
+    quantize_weight_w4,
+    pack_w4,
     seglinear,
     widen_bf16,
 )

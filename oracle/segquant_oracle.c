@@ -123,6 +123,54 @@ int sqo_quantize_weight(const float* w, int N, int K, int S, const int32_t* kseg
 }
 
 /*
+ * 4-bit weights (App. B, granularity of the 4-bit settings: weights per output channel): the Sec. 3 quantizer
+ * with q_max = 7, per output channel n and K-segment ks,
+ *   a = max_k |W[n][k]|,  wscale[ks][n] = a / 7 (1.0 if a == 0),  wq[n][k] = clip(round(W[n][k] / wscale), -7, 7).
+ * The codes are returned unpacked (one int8 per weight), so the integer GEMM and DeQuant above apply unchanged.
+ */
+int sqo_quantize_weight_w4(const float* w, int N, int K, int S, const int32_t* kseg_off, int8_t* wq,
+                           float* wscale) {
+  if (fegetround() != FE_TONEAREST) return 2;
+  if (check_offsets(K, S, kseg_off)) return 1;
+  for (int n = 0; n < N; ++n) {
+    for (int ks = 0; ks < S; ++ks) {
+      float a = 0.0f;
+      for (int k = kseg_off[ks]; k < kseg_off[ks + 1]; ++k) {
+        float v = fabsf(w[(int64_t)n * K + k]);
+        if (v > a) a = v;
+      }
+      float sw = (a == 0.0f) ? 1.0f : a / 7.0f;
+      wscale[(int64_t)ks * N + n] = sw;
+      for (int k = kseg_off[ks]; k < kseg_off[ks + 1]; ++k) {
+        float q = nearbyintf(w[(int64_t)n * K + k] / sw);
+        if (q > 7.0f) q = 7.0f;
+        if (q < -7.0f) q = -7.0f;
+        wq[(int64_t)n * K + k] = (int8_t)q;
+      }
+    }
+  }
+  return 0;
+}
+
+/*
+ * Storage format of 4-bit weight codes, two per byte (a layout of this library, not of the paper): K is a multiple
+ * of 128; inside every aligned block of 128 codes of a row, byte j (0 <= j < 64) holds code 128 b + j in its low
+ * nibble and code 128 b + 64 + j in its high nibble, each as a 4-bit two's-complement number.
+ *   wq int8 [N][K] with values in [-8, 7]   ->   packed uint8 [N][K / 2]
+ */
+int sqo_pack_w4(const int8_t* wq, int N, int K, uint8_t* packed) {
+  if (K < 128 || K % 128 != 0) return 1;
+  for (int n = 0; n < N; ++n)
+    for (int b = 0; b < K / 128; ++b)
+      for (int j = 0; j < 64; ++j) {
+        const int lo = wq[(int64_t)n * K + 128 * b + j], hi = wq[(int64_t)n * K + 128 * b + 64 + j];
+        if (lo < -8 || lo > 7 || hi < -8 || hi > 7) return 3;
+        packed[(int64_t)n * (K / 2) + 64 * b + j] = (uint8_t)((lo & 0xF) | ((hi & 0xF) << 4));
+      }
+  return 0;
+}
+
+/*
  * Activation quantization.  Dual segment (Sec. 4.3.2): X_+ = max(X, 0), X_- = min(X, 0);
  * x < 0 -> code round(x / s_-) in xq_neg (clipped at -127), x >= 0 -> code
  * round(x / s_+) in xq_pos (clipped at 127); the other polarity's code is 0.

@@ -92,6 +92,27 @@ def quantize_weight(w: np.ndarray, kseg_off):
     return wq, ws
 
 
+def quantize_weight_w4(w: np.ndarray, kseg_off):
+    """4-bit weights per output channel and K-segment (q_max = 7) -> (wq int8 [N][K] in [-7, 7], wscale fp32 [S][N])"""
+    w = _f32(w)
+    N, K = w.shape
+    off = _i32(kseg_off)
+    S = len(off) - 1
+    wq = np.empty((N, K), dtype=np.int8)
+    ws = np.empty((S, N), dtype=np.float32)
+    _check(_load().sqo_quantize_weight_w4(_p(w), N, K, S, _p(off), _p(wq), _p(ws)), "quantize_weight_w4")
+    return wq, ws
+
+
+def pack_w4(wq: np.ndarray):
+    """int8 codes [N][K] in [-8, 7] -> the packed storage format, uint8 [N][K/2]"""
+    wq = np.ascontiguousarray(wq, dtype=np.int8)
+    N, K = wq.shape
+    out = np.empty((N, K // 2), dtype=np.uint8)
+    _check(_load().sqo_pack_w4(_p(wq), N, K, _p(out)), "pack_w4")
+    return out
+
+
 def quantize_weight_block(w: np.ndarray, kseg_off, nseg_off):
     """One step per (K-segment, N-segment) block -> (wq int8 [N][K], wscale fp32 [S][N], constant inside a block)"""
     w = _f32(w)
@@ -257,9 +278,9 @@ class OracleResult:
         return cast_bf16(self.y32)
 
 
-def seglinear(x, w, kseg_off, nseg_off, dual, s_pos, s_neg, seg_scale=None, bias=None, rows=None) -> OracleResult:
-    """The whole layer, step by step: Quant(W), Q_dual(X), integer GEMM, DeQuant."""
-    wq, ws = quantize_weight(w, kseg_off)
+def seglinear(x, w, kseg_off, nseg_off, dual, s_pos, s_neg, seg_scale=None, bias=None, rows=None, wbits=8) -> OracleResult:
+    """The whole layer, step by step: Quant(W) (8-bit, or 4-bit codes when wbits == 4), Q_dual(X), integer GEMM, DeQuant."""
+    wq, ws = quantize_weight(w, kseg_off) if wbits == 8 else quantize_weight_w4(w, kseg_off)
     xp, xn = quantize_act(x, kseg_off, dual, s_pos, s_neg)
     ap, an = int_gemm(xp, xn, wq, kseg_off, dual, rows)
     y32, y64 = dequant(ap, an, nseg_off, dual, s_pos, s_neg, ws, seg_scale, bias)

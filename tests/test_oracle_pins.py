@@ -558,3 +558,67 @@ def test_block_weight_quantizer(oracle):
     w3[0:5, 0:16] = 0.0
     _, s3 = oracle.quantize_weight_block(w3, kseg, nseg)
     assert (s3[0, 0:5] == 1.0).all()
+
+
+# 4-bit weights (App. B: per-channel weights in the 4-bit settings) and their packed storage format
+def test_w4_quantizer_and_packing(oracle):
+    from fractions import Fraction
+
+    rng = np.random.default_rng(12)
+    w = (rng.standard_normal((6, 256)) * 0.05).astype(np.float32)
+    w[2, :128] = 0.0                                              # an all-zero row segment: neutral step
+    kseg = [0, 128, 256]
+    wq, ws = oracle.quantize_weight_w4(w, kseg)
+    assert wq.min() >= -7 and wq.max() <= 7
+    for n in range(6):
+        for ks in range(2):
+            seg = w[n, kseg[ks]:kseg[ks + 1]]
+            a = np.abs(seg).max()
+            step = np.float32(1.0) if a == 0 else np.float32(a) / np.float32(7.0)
+            assert ws[ks, n] == step
+            # nearest code in exact rational arithmetic (ties do not occur in this sample)
+            for k in range(0, 128, 7):
+                q = Fraction(float(seg[k])) / Fraction(float(step))
+                near = int(np.floor(q + Fraction(1, 2)))
+                assert abs(q - near) != Fraction(1, 2)
+                assert wq[n, kseg[ks] + k] == max(-7, min(7, near))
+            if a > 0:                                             # the extreme value takes the end of the code range
+                assert np.abs(wq[n, kseg[ks]:kseg[ks + 1]]).max() == 7
+    assert np.all(wq[2, :128] == 0) and ws[0, 2] == 1.0
+    # hand-worked: step 0.7 / 7 = 0.1 ; 0.25 / 0.1 = 2.5 -> 2 (ties to even), 0.35 -> 3.5 -> 4, -0.7 -> -7
+    row = np.zeros((1, 128), np.float32)
+    row[0, :4] = [0.25, 0.35, -0.7, 0.04]
+    q1, s1 = oracle.quantize_weight_w4(row, [0, 128])
+    assert s1[0, 0] == np.float32(0.7) / np.float32(7.0)
+    expect = [int(np.rint(np.float32(v) / s1[0, 0])) for v in (0.25, 0.35, -0.7, 0.04)]
+    assert q1[0, :4].tolist() == expect and expect[2] == -7 and expect[3] == 0
+    # packing: byte j of a 128-block = code j (low nibble) | code 64 + j (high nibble), two's complement
+    codes = np.zeros((1, 256), np.int8)
+    codes[0, 0], codes[0, 64], codes[0, 1], codes[0, 65] = 3, -2, -8, 7
+    codes[0, 128 + 63], codes[0, 128 + 127] = -1, 5
+    pk = oracle.pack_w4(codes)
+    assert pk.shape == (1, 128)
+    assert pk[0, 0] == (3 | (0xE << 4)) and pk[0, 1] == (0x8 | (7 << 4)) and pk[0, 64 + 63] == (0xF | (5 << 4))
+    # round trip through an independent unpacker
+    pk = oracle.pack_w4(wq)
+    lo = (pk & 0xF).astype(np.int8)
+    hi = (pk >> 4).astype(np.int8)
+    lo = np.where(lo > 7, lo - 16, lo)
+    hi = np.where(hi > 7, hi - 16, hi)
+    back = np.empty_like(wq)
+    for b in range(2):
+        back[:, 128 * b:128 * b + 64] = lo[:, 64 * b:64 * b + 64]
+        back[:, 128 * b + 64:128 * b + 128] = hi[:, 64 * b:64 * b + 64]
+    assert np.array_equal(back, wq)
+    with pytest.raises(Exception):
+        oracle.pack_w4(np.zeros((2, 100), np.int8))               # K must be a multiple of 128
+    with pytest.raises(Exception):
+        oracle.pack_w4(np.full((1, 128), 9, np.int8))             # not a 4-bit code
+    # the layer with 4-bit weights is the same integer GEMM and DeQuant on these codes: against a float64 matmul
+    x = (rng.standard_normal((5, 256))).astype(np.float32)
+    sp, sn, _, _ = oracle.calibrate_act(x, kseg, [1, 0])
+    r = oracle.seglinear(x, w, kseg, [0, 6], [1, 0], sp, sn, wbits=4)
+    assert np.array_equal(r.wq, wq)
+    xq = r.xq_pos.astype(np.float64) * np.repeat(sp, 128)[None, :] + r.xq_neg.astype(np.float64) * np.repeat(sn, 128)[None, :]
+    wd = wq.astype(np.float64) * np.repeat(ws.T, 128, axis=1)
+    assert np.allclose(r.y64, xq @ wd.T, rtol=1e-12, atol=1e-12)
