@@ -280,6 +280,45 @@ def measure_grouped(layers=28, steps=50):
             "ms_same_layers_one_call_each": round(ms_single, 5), "weight_sets_rotated": nsets}
 
 
+def measure_w4(steps=40):
+    """The stacked modulation layer (cfg3x28) with 4-bit packed weights: one pass over half the weight bytes.  Weight
+    sets rotated so the stream comes from HBM."""
+    import torch
+
+    import paper_2507_14811_amd as sq
+
+    s = _setup("cfg3x28")
+    w, layer = s["w"], s["layer"]
+    sq.sq_quantize_act(layer, s["x"], s["xq"])
+    nsets = 6                                   # 6 x 111 MB of packed weights > 2 x the 256 MB Infinity Cache
+    wq4 = torch.empty((((w.N + 15) // 16) * 16 * (w.K // 2),), dtype=torch.uint8, device="cuda:0")
+    sq.sq_quantize_weight_w4(layer, s["wt"], wq4, s["wscale"])
+    torch.cuda.synchronize()
+    ms_qw = float(np.median(_time_events(lambda: sq.sq_quantize_weight_w4(layer, s["wt"], wq4, s["wscale"]), 5)))
+    sets = [wq4] + [wq4.clone() for _ in range(nsets - 1)]
+
+    def rot():
+        for t in sets:
+            sq.sq_seglinear_w4(layer, s["xq"], t, s["wscale"], None, s["y"])
+
+    for _ in range(5):
+        rot()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        rot()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / (steps * nsets)
+    byt = int(w.M * w.K + w.N * w.K // 2 + 4 * w.S * w.N + 2 * w.M * w.N)
+    return {"workload": "cfg3x28 with 4-bit packed weights", "M": w.M, "K": w.K, "N": w.N, "ms_per_launch": round(ms, 5),
+            "bytes": byt, "gbs_from_hbm": round(byt / (ms * 1e-3) / 1e9, 1),
+            "frac_hbm_peak": round(byt / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "gemm_tops": round(w.int8_ops / (ms * 1e-3) / 1e12, 1), "ms_quantize_weight_w4": round(ms_qw, 5),
+            "weight_sets_rotated": nsets}
+
+
 def measured_ceilings(head_setup_codes):
     """Ceilings measured on this device, reported next to the datasheet peaks: the sustained int8 MFMA rate of a
     register-only loop (for all-zero operands and for operands distributed like the headline layer's codes) and a
@@ -379,6 +418,7 @@ def main():
     head = measure(args.config, args.steps, args.warmup)
     ceilings = measured_ceilings(head.pop("xq_codes"))
     grouped = measure_grouped() if "cfg3" in args.others.split(",") else None
+    w4 = measure_w4() if "cfg3x28" in args.others.split(",") else None
     others = {}
     for name in [n for n in args.others.split(",") if n and n != args.config]:
         sq.sq_tuning_set("gemm_variant", -1)
@@ -448,6 +488,7 @@ def main():
                                              "(two for bf16 input), each followed by a bin-select kernel"},
         "other_workloads": others,
         "grouped_skinny": grouped,
+        "w4_skinny": w4,
         "measured_ceilings": ceilings,
     }
     if not args.no_cpu_baseline:

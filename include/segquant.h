@@ -218,6 +218,32 @@ sq_status sq_seglinear_debug_acc(const sq_layer* layer, const int8_t* xq, const 
                                  int32_t* acc_pos, int32_t* acc_neg, void* stream);
 
 /*
+ * 4-bit weights for the skinny layers (App. B, granularity of the 4-bit settings: weights per output channel; the
+ * low-rank side branch of the optimizer used there is not part of this library).  The modulation-type layers are one
+ * pass over the weights, so halving the weight bytes nearly halves their time.
+ *
+ * sq_quantize_weight_w4: the Sec. 3 quantizer with q_max = 7 per output channel n and K-segment ks,
+ *   a = max_k |W[n][k]|,  wscale[ks][n] = a / 7 (1.0 if a == 0),  code = clip(round(W[n][k] / wscale[ks][n]), -7, 7),
+ * codes packed two per byte in the order the weight stream consumes them: rows in groups of 16 (the last group
+ * padded with zero rows), K in steps of 128 codes (T = K / 128), one contiguous KiB per (group g, step t):
+ *   wq4[((g T + t) 16 + r) 64 + j] = code(16 g + r, 128 t + j)  |  code(16 g + r, 128 t + 64 + j) << 4,
+ * 0 <= r < 16, 0 <= j < 64, each code a 4-bit two's-complement number.
+ *   w      dev, [N][K] of w_dt                                in
+ *   wq4    dev, uint8 [ceil(N / 16) * 16 * K / 2]            out
+ *   wscale dev, fp32 [S][N]           out
+ * sq_seglinear_w4 / sq_seglinear_w4_debug_acc: as sq_seglinear / sq_seglinear_debug_acc with wq4 in place of wq
+ * (activations stay 8-bit polarity-merged codes from sq_quantize_act; the debug sums are those of the 4-bit codes).
+ * K and every K-segment boundary must be multiples of 128 (SQ_ERR_UNSUPPORTED otherwise).  M <= 64 with a 16-byte
+ * aligned wq4 runs the weight-stream kernel; other shapes run a plain one-thread-per-output kernel.
+ */
+sq_status sq_quantize_weight_w4(const sq_layer* layer, const void* w, sq_dtype w_dt, uint8_t* wq4, float* wscale,
+                                void* stream);
+sq_status sq_seglinear_w4(const sq_layer* layer, const int8_t* xq, const uint8_t* wq4, const float* wscale,
+                          const float* bias, void* y, sq_dtype y_dt, void* stream);
+sq_status sq_seglinear_w4_debug_acc(const sq_layer* layer, const int8_t* xq, const uint8_t* wq4, int32_t* acc_pos,
+                                    int32_t* acc_neg, void* stream);
+
+/*
  * Benchmark probe, not part of the method: a register-only int8 MFMA loop on every compute unit whose operands
  * are taken from `codes` (dev, int8, `bytes` >= 4096, 16-byte aligned).  The sustained rate depends on the
  * operand values because the core clock is power-managed, so the benchmark reports it for codes distributed

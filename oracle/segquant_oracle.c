@@ -153,20 +153,29 @@ int sqo_quantize_weight_w4(const float* w, int N, int K, int S, const int32_t* k
 }
 
 /*
- * Storage format of 4-bit weight codes, two per byte (a layout of this library, not of the paper): K is a multiple
- * of 128; inside every aligned block of 128 codes of a row, byte j (0 <= j < 64) holds code 128 b + j in its low
- * nibble and code 128 b + 64 + j in its high nibble, each as a 4-bit two's-complement number.
- *   wq int8 [N][K] with values in [-8, 7]   ->   packed uint8 [N][K / 2]
+ * Storage format of 4-bit weight codes, two per byte (a layout of this library, not of the paper), made so that the
+ * 16 rows x 128 codes a streaming step consumes are one contiguous KiB: K is a multiple of 128, T = K / 128; rows are
+ * taken in groups of 16 (the last group padded with zero rows), and
+ *   packed[((g T + t) 16 + r) 64 + j] = code(16 g + r, 128 t + j)  |  code(16 g + r, 128 t + 64 + j) << 4
+ * for 0 <= r < 16, 0 <= j < 64, each code a 4-bit two's-complement number.
+ *   wq int8 [N][K] with values in [-8, 7]   ->   packed uint8 [ceil(N / 16) * 16 * K / 2]
  */
 int sqo_pack_w4(const int8_t* wq, int N, int K, uint8_t* packed) {
   if (K < 128 || K % 128 != 0) return 1;
-  for (int n = 0; n < N; ++n)
-    for (int b = 0; b < K / 128; ++b)
-      for (int j = 0; j < 64; ++j) {
-        const int lo = wq[(int64_t)n * K + 128 * b + j], hi = wq[(int64_t)n * K + 128 * b + 64 + j];
-        if (lo < -8 || lo > 7 || hi < -8 || hi > 7) return 3;
-        packed[(int64_t)n * (K / 2) + 64 * b + j] = (uint8_t)((lo & 0xF) | ((hi & 0xF) << 4));
-      }
+  const int T = K / 128, G = (N + 15) / 16;
+  for (int g = 0; g < G; ++g)
+    for (int t = 0; t < T; ++t)
+      for (int r = 0; r < 16; ++r)
+        for (int j = 0; j < 64; ++j) {
+          const int n = 16 * g + r;
+          int lo = 0, hi = 0;
+          if (n < N) {
+            lo = wq[(int64_t)n * K + 128 * t + j];
+            hi = wq[(int64_t)n * K + 128 * t + 64 + j];
+          }
+          if (lo < -8 || lo > 7 || hi < -8 || hi > 7) return 3;
+          packed[(((int64_t)g * T + t) * 16 + r) * 64 + j] = (uint8_t)((lo & 0xF) | ((hi & 0xF) << 4));
+        }
   return 0;
 }
 

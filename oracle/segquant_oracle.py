@@ -105,10 +105,11 @@ def quantize_weight_w4(w: np.ndarray, kseg_off):
 
 
 def pack_w4(wq: np.ndarray):
-    """int8 codes [N][K] in [-8, 7] -> the packed storage format, uint8 [N][K/2]"""
+    """int8 codes [N][K] in [-8, 7] -> the packed storage format, uint8 [ceil(N/16) * 16 * K/2] (16-row groups,
+    128-code steps, one KiB per (group, step))"""
     wq = np.ascontiguousarray(wq, dtype=np.int8)
     N, K = wq.shape
-    out = np.empty((N, K // 2), dtype=np.uint8)
+    out = np.empty((((N + 15) // 16) * 16 * (K // 2),), dtype=np.uint8)
     _check(_load().sqo_pack_w4(_p(wq), N, K, _p(out)), "pack_w4")
     return out
 

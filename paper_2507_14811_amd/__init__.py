@@ -20,9 +20,12 @@ from .binding import (  # noqa: F401
     sq_quantize_act_fused_workspace_bytes,
     sq_quantize_weight,
     sq_quantize_weight_block,
+    sq_quantize_weight_w4,
     sq_seglinear,
     sq_seglinear_debug_acc,
     sq_seglinear_grouped,
+    sq_seglinear_w4,
+    sq_seglinear_w4_debug_acc,
     sq_tuning_set,
     sq_version,
     status_string,

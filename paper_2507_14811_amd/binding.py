@@ -24,7 +24,8 @@ EXPORTS = ("sq_quantize_weight", "sq_quantize_act", "sq_seglinear", "sq_seglinea
            "sq_status_string", "sq_version", "sq_tuning_set", "sq_probe_mfma", "sq_seglinear_grouped",
            "sq_quantize_weight_block", "sq_calibrate_act", "sq_calibrate_act_percentile",
            "sq_calibrate_workspace_bytes", "sq_quantize_act_fused",
-           "sq_quantize_act_fused_workspace_bytes")
+           "sq_quantize_act_fused_workspace_bytes", "sq_quantize_weight_w4", "sq_seglinear_w4",
+           "sq_seglinear_w4_debug_acc")
 
 
 class SqError(RuntimeError):
@@ -78,6 +79,11 @@ def load_library() -> C.CDLL:
     lib.sq_quantize_act_fused_workspace_bytes.argtypes = [lp]
     lib.sq_quantize_act_fused_workspace_bytes.restype = C.c_size_t
     lib.sq_quantize_act_fused.restype = i32
+    lib.sq_quantize_weight_w4.argtypes = [lp, vp, i32, vp, vp, vp]
+    lib.sq_seglinear_w4.argtypes = [lp, vp, vp, vp, vp, vp, i32, vp]
+    lib.sq_seglinear_w4_debug_acc.argtypes = [lp, vp, vp, vp, vp, vp]
+    for f in (lib.sq_quantize_weight_w4, lib.sq_seglinear_w4, lib.sq_seglinear_w4_debug_acc):
+        f.restype = i32
     lib.sq_calibrate_act_percentile.argtypes = [lp, vp, i32, C.c_double, vp, vp, vp, C.c_size_t, i32, vp]
     lib.sq_calibrate_act_percentile.restype = i32
     lib.sq_calibrate_workspace_bytes.argtypes = []
@@ -237,6 +243,25 @@ def sq_seglinear(layer: Layer, xq, wq, wscale, bias, y, stream=None) -> None:
     """int8 x int8 -> int32 per K-segment and polarity, dequantized into y [M][N] fp32/bf16."""
     _check(load_library().sq_seglinear(C.byref(layer.c), _dptr(xq), _dptr(wq), _dptr(wscale), _dptr(bias),
                                        _dptr(y), _dt(y), _stream(stream)), "sq_seglinear")
+
+
+def sq_quantize_weight_w4(layer: Layer, w, wq4, wscale, stream=None) -> None:
+    """w [N][K] fp32/bf16 -> wq4 uint8 [ceil(N/16)*16*K/2] (4-bit codes, two per byte, one KiB per 16-row group and
+    128-code step), wscale fp32 [S][N]."""
+    _check(load_library().sq_quantize_weight_w4(C.byref(layer.c), _dptr(w), _dt(w), _dptr(wq4), _dptr(wscale),
+                                                _stream(stream)), "sq_quantize_weight_w4")
+
+
+def sq_seglinear_w4(layer: Layer, xq, wq4, wscale, bias, y, stream=None) -> None:
+    """sq_seglinear with 4-bit packed weights."""
+    _check(load_library().sq_seglinear_w4(C.byref(layer.c), _dptr(xq), _dptr(wq4), _dptr(wscale), _dptr(bias),
+                                          _dptr(y), _dt(y), _stream(stream)), "sq_seglinear_w4")
+
+
+def sq_seglinear_w4_debug_acc(layer: Layer, xq, wq4, acc_pos, acc_neg, stream=None) -> None:
+    """Raw int32 sums of the 4-bit codes: acc_pos, acc_neg int32 [S][M][N]."""
+    _check(load_library().sq_seglinear_w4_debug_acc(C.byref(layer.c), _dptr(xq), _dptr(wq4), _dptr(acc_pos),
+                                                    _dptr(acc_neg), _stream(stream)), "sq_seglinear_w4_debug_acc")
 
 
 class GroupItems:

@@ -118,6 +118,41 @@ sq_status run_gemm(const sq_layer* L, const int8_t* xq, const int8_t* wq,
   return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 
+// 4-bit packed weights: K and every K-segment boundary a multiple of 128.  The weight-stream kernel serves M <= 64
+// (this is where halving the weight bytes pays: the pass is HBM-bound); everything else takes the one-thread-per-output
+// kernel, which is correct and slow.  force_path 0 selects the latter also for small M.
+bool w4_layout_ok(const sq_layer* L) {
+  if (L->K < 128 || L->K % 128 != 0) return false;
+  for (int s = 0; s <= L->S; ++s)
+    if (L->kseg_off[s] % 128 != 0) return false;
+  return true;
+}
+
+sq_status run_gemm_w4(const sq_layer* L, const int8_t* xq, const uint8_t* wq4, const float* wscale, const float* bias,
+                      void* y, int32_t* acc_pos, int32_t* acc_neg, sq::OutMode mode, void* stream) {
+  if (!w4_layout_ok(L)) return SQ_ERR_UNSUPPORTED;
+  sq::GemmTable tb;
+  fill_gemm_table(L, tb);
+  sq::GemmArgs a{};
+  a.xq = xq;
+  a.wq = reinterpret_cast<const int8_t*>(wq4);
+  a.wscale = wscale;
+  a.bias = bias;
+  a.y = y;
+  a.acc_pos = acc_pos;
+  a.acc_neg = acc_neg;
+  a.M = L->M;
+  a.K = L->K;
+  a.N = L->N;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  const bool stream_ok = sq::stream_supported(a, tb);
+  if (g_force_path == 3 && !stream_ok) return SQ_ERR_UNSUPPORTED;
+  hipError_t e;
+  if (g_force_path != 0 && stream_ok) e = sq::launch_seglinear_stream_w4(a, tb, mode, sq::device_cus(), st);
+  else e = sq::launch_seglinear_generic_w4(a, tb, mode, st);
+  return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
 }  // namespace
 
 extern "C" {
@@ -294,6 +329,40 @@ sq_status sq_seglinear_debug_acc(const sq_layer* layer, const int8_t* xq, const 
   if (xq == nullptr || wq == nullptr || acc_pos == nullptr || acc_neg == nullptr) return SQ_ERR_INVALID_ARG;
   if ((long long)layer->S * layer->M * layer->N > 0x7FFFFFFFll) return SQ_ERR_UNSUPPORTED;
   return run_gemm(layer, xq, wq, nullptr, nullptr, nullptr, acc_pos, acc_neg, sq::OUT_DEBUG_ACC, stream);
+}
+
+sq_status sq_quantize_weight_w4(const sq_layer* layer, const void* w, sq_dtype w_dt, uint8_t* wq4, float* wscale,
+                                void* stream) {
+  sq_status st = check_layer(layer, false, false);
+  if (st != SQ_OK) return st;
+  if (w == nullptr || wq4 == nullptr || wscale == nullptr) return SQ_ERR_INVALID_ARG;
+  if (w_dt != SQ_F32 && w_dt != SQ_BF16) return SQ_ERR_INVALID_ARG;
+  if (!w4_layout_ok(layer)) return SQ_ERR_UNSUPPORTED;
+  sq::KsegTable tb;
+  tb.S = layer->S;
+  for (int s = 0; s <= layer->S; ++s) tb.off[s] = layer->kseg_off[s];
+  hipError_t e = sq::launch_quantize_weight_w4(w, w_dt == SQ_BF16, wq4, wscale, layer->N, layer->K, tb,
+                                               reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
+sq_status sq_seglinear_w4(const sq_layer* layer, const int8_t* xq, const uint8_t* wq4, const float* wscale,
+                          const float* bias, void* y, sq_dtype y_dt, void* stream) {
+  sq_status st = check_layer(layer, true, true);
+  if (st != SQ_OK) return st;
+  if (xq == nullptr || wq4 == nullptr || wscale == nullptr || y == nullptr) return SQ_ERR_INVALID_ARG;
+  if (y_dt != SQ_F32 && y_dt != SQ_BF16) return SQ_ERR_INVALID_ARG;
+  return run_gemm_w4(layer, xq, wq4, wscale, bias, y, nullptr, nullptr, y_dt == SQ_BF16 ? sq::OUT_BF16 : sq::OUT_F32,
+                     stream);
+}
+
+sq_status sq_seglinear_w4_debug_acc(const sq_layer* layer, const int8_t* xq, const uint8_t* wq4, int32_t* acc_pos,
+                                    int32_t* acc_neg, void* stream) {
+  sq_status st = check_layer(layer, true, false);
+  if (st != SQ_OK) return st;
+  if (xq == nullptr || wq4 == nullptr || acc_pos == nullptr || acc_neg == nullptr) return SQ_ERR_INVALID_ARG;
+  if ((long long)layer->S * layer->M * layer->N > 0x7FFFFFFFll) return SQ_ERR_UNSUPPORTED;
+  return run_gemm_w4(layer, xq, wq4, nullptr, nullptr, nullptr, acc_pos, acc_neg, sq::OUT_DEBUG_ACC, stream);
 }
 
 sq_status sq_probe_mfma(const int8_t* codes, size_t bytes, int iters, double* ops, void* stream) {

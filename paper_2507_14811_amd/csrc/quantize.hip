@@ -358,4 +358,54 @@ hipError_t launch_quantize_weight_block(const void* w, bool w_is_bf16, int8_t* w
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------------
+// 4-bit weights (App. B: per-channel weights in the 4-bit settings): the Sec. 3 quantizer with q_max = 7 per output
+// channel and K-segment, codes packed two per byte in the order the weight stream consumes them: rows in groups
+// of 16 (the last group padded with zero rows), K in steps of 128 codes (T = K / 128), one contiguous KiB per
+// (group, step):  packed[((g T + t) 16 + r) 64 + j] = code(16 g + r, 128 t + j) | code(16 g + r, 128 t + 64 + j) << 4
+// (4-bit two's complement).  Shifting a fetched dword left by four and masking gives the 16-fold int8 codes of one
+// 64-wide MFMA k-step, masking alone those of the next.  One wavefront per (output channel, K-segment); K and the
+// segment boundaries are multiples of 128.  Rows beyond N in the last group are zeroed by their own wavefronts.
+// ------------------------------------------------------------------------------------------------
+template <bool BF16>
+__global__ __launch_bounds__(256) void quantize_weight_w4_kernel(const void* __restrict__ w, uint8_t* __restrict__ wq4,
+                                                                 float* __restrict__ wscale, int N, int K,
+                                                                 const KsegTable tb) {
+  const int lane = threadIdx.x & 63;
+  const int npad = (N + 15) & ~15;
+  const long item = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (item >= (long)npad * tb.S) return;         // whole wave leaves together
+  const int n = (int)(item / tb.S), ks = (int)(item % tb.S);
+  int k0 = 0, k1 = 0;
+  for (int s = 0; s < tb.S; ++s)
+    if (s == ks) { k0 = tb.off[s]; k1 = tb.off[s + 1]; }
+  const int T = K >> 7;
+  uint8_t* out = wq4 + ((size_t)(n >> 4) * T * 16 + (n & 15)) * 64 + lane;      // + t * 1024 per step
+  if (n >= N) {                                  // padding row of the last group
+    for (int b = k0; b < k1; b += 128) out[(size_t)(b >> 7) * 1024] = 0;
+    return;
+  }
+  const size_t row = (size_t)n * K;
+  float a = 0.0f;
+  for (int k = k0 + lane; k < k1; k += 64) a = __builtin_fmaxf(a, __builtin_fabsf(load_w<BF16>(w, row + k)));
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) a = __builtin_fmaxf(a, __shfl_xor(a, off, 64));
+  const float sw = (a == 0.0f) ? 1.0f : a / 7.0f;
+  if (lane == 0) wscale[(size_t)ks * N + n] = sw;
+  for (int b = k0; b < k1; b += 128) {
+    const float lo = __builtin_fminf(__builtin_fmaxf(__builtin_rintf(load_w<BF16>(w, row + b + lane) / sw), -7.0f), 7.0f);
+    const float hi = __builtin_fminf(__builtin_fmaxf(__builtin_rintf(load_w<BF16>(w, row + b + 64 + lane) / sw), -7.0f), 7.0f);
+    out[(size_t)(b >> 7) * 1024] = (uint8_t)(((int)lo & 0xF) | (((int)hi & 0xF) << 4));
+  }
+}
+
+hipError_t launch_quantize_weight_w4(const void* w, bool w_is_bf16, uint8_t* wq4, float* wscale, int N, int K,
+                                     const KsegTable& tb, hipStream_t st) {
+  const long items = (long)((N + 15) & ~15) * tb.S;
+  const unsigned blocks = (unsigned)((items + 3) / 4);
+  if (w_is_bf16) hipLaunchKernelGGL((quantize_weight_w4_kernel<true>), dim3(blocks), dim3(256), 0, st, w, wq4, wscale, N, K, tb);
+  else           hipLaunchKernelGGL((quantize_weight_w4_kernel<false>), dim3(blocks), dim3(256), 0, st, w, wq4, wscale, N, K, tb);
+  return hipGetLastError();
+}
+
 }  // namespace sq

@@ -8,10 +8,10 @@
 //     rows are padded by 16 bytes so that the 16 rows of a fragment read fall on distinct bank groups.
 //   * Every wave owns a list of 16-column groups of the output and streams the 16 W^ rows of a group
 //     in steps of 128 bytes of K (full cache lines) through a private ring of direct global->LDS loads.  The
-//     ring runs ahead across group boundaries, so a wave always has RING-1 steps (2 KiB each) in flight; with
-//     eight waves per workgroup (two per SIMD, so one wave's LDS and MFMA latencies hide behind the other's
-//     work) and one workgroup per CU that is ~100 KB in flight per CU, which covers HBM latency at full
-//     bandwidth.  No workgroup barrier is needed after the slab is filled.
+//     ring runs ahead across group boundaries.  Sixteen waves per workgroup (four per SIMD; eight when there are
+//     more than two 16-row token tiles) and one workgroup per CU: the waves hide each other's LDS and MFMA
+//     latencies, which matters more than the depth of a wave's ring.  No workgroup barrier is needed after the
+//     slab is filled.
 //   * W^ rows are the MFMA "A" operand (v_mfma_i32_16x16x64_i8) and X^ rows the "B" operand, so a lane ends up
 //     with four consecutive output columns of one token row: scales are fetched and results stored 16 / 8
 //     bytes at a time.  Exact int32 sums per K-segment and polarity are scaled into an fp32 running sum at
@@ -22,7 +22,10 @@
 
 namespace sq {
 
-constexpr int kStreamWaves = 8;
+// Waves per workgroup (one workgroup per CU).  With one or two 16-row token tiles a wave needs few registers and
+// sixteen waves (four per SIMD) hide each other's LDS and MFMA latencies better than eight with deeper rings
+// (measured: ring depth hardly matters, the number of waves does: 5.75 -> 5.97 TB/s, 4-bit weights 4.1 -> 5.1).
+constexpr int stream_waves(int mt) { return mt <= 2 ? 16 : 8; }
 
 // The weight stream is read exactly once: the loads carry the non-temporal hint, so that the lines are not kept
 // in the caches at the expense of everything else (measured: 5.0 -> 5.8 TB/s for the bare stream from HBM).
@@ -58,24 +61,30 @@ __device__ __forceinline__ void pick4(const float s[16], const int fq, float out
   for (int r = 0; r < 4; ++r) out[r] = fq == 0 ? s[r] : fq == 1 ? s[4 + r] : fq == 2 ? s[8 + r] : s[12 + r];
 }
 
-template <int MT, int SLAB_KB>
+// W4: the weights are 4-bit codes packed two per byte (a step of 128 codes of 16 rows is 1 KiB, one direct load)
+// PS: the slab holds X^_+ and X^_- as two planes (split once at the fill instead of in every step); its small size
+// class is then 48 KiB instead of 24
+template <int MT, int SLAB_KB, bool W4, bool PS>
 struct StreamCfg {
-  static constexpr int SLAB = SLAB_KB * 1024;
-  static constexpr int STEP = 2048;                               // 16 W^ rows x 128 bytes of K
-  static constexpr int RAW = (156 * 1024 - SLAB) / (kStreamWaves * STEP);
-  static constexpr int RING = RAW > 28 ? 28 : RAW;                // 2 loads per step: stays below the 6-bit vmcnt
-  static constexpr int LDS = SLAB + kStreamWaves * RING * STEP;
-  static_assert(RING >= 4, "ring too shallow");
+  static constexpr int NW = stream_waves(MT);
+  static constexpr int SLAB = (PS && SLAB_KB == 24 ? 48 : SLAB_KB) * 1024;
+  static constexpr int STEP = W4 ? 1024 : 2048;                   // 16 W^ rows x 128 codes of K
+  static constexpr int LPS = W4 ? 1 : 2;                          // direct loads per step
+  static constexpr int RAW = (156 * 1024 - SLAB) / (NW * STEP);
+  static constexpr int RING = RAW > 28 ? 28 : RAW;                // at most 56 loads in flight: below the 6-bit vmcnt
+  static constexpr int LDS = SLAB + NW * RING * STEP;
+  static_assert(RING >= 2, "ring too shallow");
   static_assert(LDS <= 160 * 1024, "LDS budget");
 };
 
 // TB: GemmTable (one layer; GT = NoGroups) or GroupSegTable (GT = GroupTable: L layers of the same shape that share
 // X^ and its steps; the 16-column groups of all layers form one list, layer = group / groups per layer).
-template <int MT, bool DUAL, int SLAB_KB, class TB, class GT>
-__global__ __launch_bounds__(kStreamWaves * 64) void seglinear_stream_kernel(const GemmArgs a, const TB tb, const GT gt, const int mode) {
-  using C = StreamCfg<MT, SLAB_KB>;
+template <int MT, bool DUAL, int SLAB_KB, class TB, class GT, bool W4 = false, bool PS = false>
+__global__ __launch_bounds__(stream_waves(MT) * 64) void seglinear_stream_kernel(const GemmArgs a, const TB tb, const GT gt, const int mode) {
+  static_assert(!PS || DUAL, "two slab planes only where both polarity paths run");
+  using C = StreamCfg<MT, SLAB_KB, W4, PS>;
   constexpr bool GROUPED = std::is_same<GT, GroupTable>::value;
-  constexpr int RING = C::RING, STEP = C::STEP;
+  constexpr int RING = C::RING, STEP = C::STEP, LPS = C::LPS, NW = C::NW;
   __shared__ __attribute__((aligned(1024))) char smem[C::LDS];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -86,16 +95,16 @@ __global__ __launch_bounds__(kStreamWaves * 64) void seglinear_stream_kernel(con
   if constexpr (GROUPED) nlayers = gt.L;
   const int ngroups = gpl * nlayers;
   // Group g of the flat list goes to a wave in one of two ways (both wave-uniform):
-  //   * enough groups for every wave of the grid: wave (workgroup b, wave w) takes groups 8b + w, + nwaves, ...
+  //   * enough groups for every wave of the grid: wave (workgroup b, wave w of NW) takes groups NW b + w, + nwaves, ...
   //     At any moment the chip then reads one contiguous window of the weights (nwaves groups, 18 KB each for
-  //     K = 1152) and the eight waves of a CU read eight adjacent groups of it, which the memory system (page
+  //     K = 1152) and the waves of a CU read adjacent groups of it, which the memory system (page
   //     translation included) serves measurably better than one far-apart stream per wave: 5.5 vs 4.7 TB/s.
   //   * fewer groups than waves: every workgroup takes a contiguous share of the list and deals it to its
   //     waves, so that a narrow layer still spreads over all CUs.
-  const int nwaves = gridDim.x * kStreamWaves;
+  const int nwaves = gridDim.x * NW;
   int g_first, g_stride, g_cnt;
   if (ngroups >= nwaves) {
-    g_first = blockIdx.x * kStreamWaves + wave;
+    g_first = blockIdx.x * NW + wave;
     g_stride = nwaves;
     g_cnt = (ngroups - g_first + nwaves - 1) / nwaves;
   } else {
@@ -103,8 +112,8 @@ __global__ __launch_bounds__(kStreamWaves * 64) void seglinear_stream_kernel(con
     const int c_begin = bx < crem ? bx * (cper + 1) : crem * (cper + 1) + (bx - crem) * cper;
     const int c_cnt = cper + (bx < crem ? 1 : 0);
     g_first = c_begin + wave;
-    g_stride = kStreamWaves;
-    g_cnt = wave < c_cnt ? (c_cnt - wave + kStreamWaves - 1) / kStreamWaves : 0;
+    g_stride = NW;
+    g_cnt = wave < c_cnt ? (c_cnt - wave + NW - 1) / NW : 0;
   }
   auto group_at = [&](const int g) __attribute__((always_inline)) { return g_first + g * g_stride; };
   const int nstep = a.K >> 7;                                      // 128-byte steps per group
@@ -124,21 +133,30 @@ __global__ __launch_bounds__(kStreamWaves * 64) void seglinear_stream_kernel(con
       gl -= l * gpl;
       iwq = gt.item[l].wq;
     }
+    if (W4) {
+      // packed storage: one contiguous KiB per (16-row group, 128-code step), [16 rows][64 bytes].  lane -> (row
+      // lane/4, 16 B slot lane%4 holding chunk slot ^ (row/4 & 3): rows 4 apart share LDS banks, the swizzle keeps
+      // a fragment read's 16 rows apart).  Every direct load moves eight full cache lines.
+      const int rt = lane >> 2;
+      voff[0] = (uint32_t)gl * (uint32_t)(a.K >> 7) * 1024u + (uint32_t)(rt * 64) + (uint32_t)(((lane & 3) ^ ((rt >> 2) & 3)) << 4);
+      voff[1] = 0;
+    } else {
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int rt = 8 * h + lrow;
-      int r = gl * 16 + rt;
-      r = r < a.N ? r : a.N - 1;                                   // ragged N: re-read the last row, masked at the store
-      voff[h] = (uint32_t)r * (uint32_t)a.K + (uint32_t)((lslot ^ row_swizzle<128>(rt)) << 4);
+      for (int h = 0; h < 2; ++h) {
+        const int rt = 8 * h + lrow;
+        int r = gl * 16 + rt;
+        r = r < a.N ? r : a.N - 1;                                 // ragged N: re-read the last row, masked at the store
+        voff[h] = (uint32_t)r * (uint32_t)a.K + (uint32_t)((lslot ^ row_swizzle<128>(rt)) << 4);
+      }
     }
   };
   auto issue_step = [&]() __attribute__((always_inline)) {
-    const uint64_t u = reinterpret_cast<uint64_t>(iwq + ((size_t)it << 7));
+    const uint64_t u = reinterpret_cast<uint64_t>(iwq + ((size_t)it << (W4 ? 10 : 7)));
     const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)u), hi = __builtin_amdgcn_readfirstlane((uint32_t)(u >> 32));
     const int8_t* base = reinterpret_cast<const int8_t*>(((uint64_t)hi << 32) | lo);
     const uint32_t so = __builtin_amdgcn_readfirstlane(ring_lds + (uint32_t)islot * (uint32_t)STEP);
     glds16_stream(base, voff[0], so);
-    glds16_stream(base, voff[1], so + 1024u);
+    if (!W4) glds16_stream(base, voff[1], so + 1024u);
     ++issued_steps;
     islot = (islot + 1 == RING) ? 0 : islot + 1;
     if (++it == nstep) {
@@ -151,13 +169,32 @@ __global__ __launch_bounds__(kStreamWaves * 64) void seglinear_stream_kernel(con
   while (issued_steps < RING - 1 && issued_steps < total) issue_step();
 
   // ---- X^ slab: [16*MT rows][K + 16] bytes, rows beyond M repeat the last row (masked at the store) ----------
+  // PS: a second plane of the same shape behind the first; plane 0 holds X^_+ (the whole code in a single-scale
+  // K-segment), plane 1 holds X^_- (zero there): the polarity separation of Sec. 4.3.2 done once per workgroup.
+  const int plane = MT * 16 * (a.K + 16);
   {
     const int rowb = a.K + 16, cpr = a.K >> 4;                     // 16-byte chunks per row
     const int nchunk = MT * 16 * cpr;
-    for (int c = threadIdx.x; c < nchunk; c += kStreamWaves * 64) {
+    for (int c = threadIdx.x; c < nchunk; c += NW * 64) {
       const int r = c / cpr, cc = c - r * cpr;
       const int rs = r < a.M ? r : a.M - 1;
-      const v4i v = *reinterpret_cast<const v4i*>(a.xq + (size_t)rs * a.K + cc * 16);
+      v4i v = *reinterpret_cast<const v4i*>(a.xq + (size_t)rs * a.K + cc * 16);
+      if (PS) {
+        bool dl = false;
+        for (int sg = 0; sg < tb.S; ++sg)
+          if (cc * 16 >= tb.kseg_off[sg]) dl = tb.dual[sg] != 0;
+        v4i nv = (v4i)(0);
+        if (dl) {
+#pragma unroll
+          for (int d = 0; d < 4; ++d) {
+            int pos, neg;
+            split_polarity(v[d], pos, neg);
+            v[d] = pos;
+            nv[d] = neg;
+          }
+        }
+        *reinterpret_cast<v4i*>(smem + plane + r * rowb + cc * 16) = nv;
+      }
       *reinterpret_cast<v4i*>(smem + r * rowb + cc * 16) = v;
     }
   }
@@ -170,6 +207,7 @@ __global__ __launch_bounds__(kStreamWaves * 64) void seglinear_stream_kernel(con
   int woff[2];
 #pragma unroll
   for (int h = 0; h < 2; ++h) woff[h] = frow * 128 + (((4 * h + fq) ^ row_swizzle<128>(frow)) << 4);
+  if (W4) woff[0] = frow * 64 + ((fq ^ ((frow >> 2) & 3)) << 4);   // packed: one 16-byte chunk holds both k-steps
   const int xrow = frow * (a.K + 16) + 16 * fq;
 
   const int mlane = lane & 15;                                     // token row inside a 16-row tile
@@ -213,14 +251,24 @@ __global__ __launch_bounds__(kStreamWaves * 64) void seglinear_stream_kernel(con
 #pragma unroll 1
         while (kk < kk_end) {                                      // one 128-byte step = two MFMA k-steps
           ++done_steps;
-          wait_vmcnt<2 * (RING - 2), 0>(2 * (issued_steps - done_steps));
-          v4i wf[2], xf[2][MT];
+          wait_vmcnt<LPS * (RING - 2), 0>(LPS * (issued_steps - done_steps));
+          v4i wf[2], xf[2][MT], nfp[2][PS ? MT : 1];
 #pragma unroll
           for (int h = 0; h < 2; ++h) {                            // all fragment reads of the step first
-            wf[h] = *reinterpret_cast<const v4i*>(ring + cslot * STEP + woff[h]);
+            if (!W4 || h == 0) wf[h] = *reinterpret_cast<const v4i*>(ring + cslot * STEP + woff[h]);
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
+            for (int mt = 0; mt < MT; ++mt) {
               xf[h][mt] = *reinterpret_cast<const v4i*>(smem + mt * 16 * (a.K + 16) + xrow + (kk + h) * 64);
+              if (PS && DL) nfp[h][mt] = *reinterpret_cast<const v4i*>(smem + plane + mt * 16 * (a.K + 16) + xrow + (kk + h) * 64);
+            }
+          }
+          if (W4) {                                                // nibbles -> 16-fold int8 codes of the two k-steps
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+              const int pk = wf[0][d];
+              wf[0][d] = (pk << 4) & (int)0xF0F0F0F0u;
+              wf[1][d] = pk & (int)0xF0F0F0F0u;
+            }
           }
 #pragma unroll
           for (int h = 0; h < 2; ++h)
@@ -229,12 +277,16 @@ __global__ __launch_bounds__(kStreamWaves * 64) void seglinear_stream_kernel(con
               v4i pf = xf[h][mt];
               if (DL) {                                            // X^_+ = max(X^, 0), X^_- = min(X^, 0), byte-wise
                 v4i nf;
+                if (PS) {
+                  nf = nfp[h][mt];
+                } else {
 #pragma unroll
-                for (int d = 0; d < 4; ++d) {
-                  int pos, neg;
-                  split_polarity(pf[d], pos, neg);
-                  pf[d] = pos;
-                  nf[d] = neg;
+                  for (int d = 0; d < 4; ++d) {
+                    int pos, neg;
+                    split_polarity(pf[d], pos, neg);
+                    pf[d] = pos;
+                    nf[d] = neg;
+                  }
                 }
                 if (h == 0) accn[mt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf[h], nf, accn[mt], 0, 0, 0);
                 else accn1[mt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf[h], nf, accn1[mt], 0, 0, 0);
@@ -264,20 +316,26 @@ __global__ __launch_bounds__(kStreamWaves * 64) void seglinear_stream_kernel(con
           const int m = mt * 16 + mlane;
           if (m < a.M) {
             const size_t o = ((size_t)ks * a.M + m) * a.N + ncol;
-            const v4i q = dl ? accn[mt] : (v4i)(0);
+            // packed weights enter the MFMA 16-fold: the sums are exact multiples of 16
+            const v4i pp = W4 ? (accp[mt] >> 4) : accp[mt];
+            const v4i q = dl ? (W4 ? (accn[mt] >> 4) : accn[mt]) : (v4i)(0);
             if (vec4 && ncol + 3 < a.N) {
-              *reinterpret_cast<v4i*>(a.acc_pos + o) = accp[mt];
+              *reinterpret_cast<v4i*>(a.acc_pos + o) = pp;
               *reinterpret_cast<v4i*>(a.acc_neg + o) = q;
             } else {
 #pragma unroll
               for (int r = 0; r < 4; ++r)
-                if (ncol + r < a.N) { a.acc_pos[o + r] = accp[mt][r]; a.acc_neg[o + r] = q[r]; }
+                if (ncol + r < a.N) { a.acc_pos[o + r] = pp[r]; a.acc_neg[o + r] = q[r]; }
             }
           }
         }
       } else {
         float cw[4];
         pick4(ws16, fq, cw);
+        if (W4) {                                                  // exact: undoes the 16-fold codes
+#pragma unroll
+          for (int r = 0; r < 4; ++r) cw[r] *= 0.0625f;
+        }
         if constexpr (!GROUPED) {
           if (tb.has_seg_scale) {
 #pragma unroll
@@ -337,39 +395,56 @@ __global__ __launch_bounds__(kStreamWaves * 64) void seglinear_stream_kernel(con
 
 // Wide skinny layers only: enough 16-column groups to give every wave of the chip a run of them; K and every
 // K-segment boundary multiples of 128 (a step is a full cache line per row); X^ slab within the LDS budget.
-static int stream_slab_kb(const GemmArgs& a) {
+static bool any_dual(const int* dual, int S) {
+  bool d = false;
+  for (int s = 0; s < S; ++s) d = d || dual[s] != 0;
+  return d;
+}
+
+// Size class of the X^ slab (24 = small, 80, 0 = does not fit) and whether it holds the two polarity planes
+// (dual layers with at most two 16-row tiles whose doubled slab still fits).
+static int stream_slab_kb(const GemmArgs& a, bool dual, bool* two_planes) {
   const int mt = (a.M + 15) / 16;
   const long slab = (long)mt * 16 * (a.K + 16);
+  *two_planes = dual && mt <= 2 && 2 * slab <= 80 * 1024;
+  if (*two_planes) return 2 * slab <= 48 * 1024 ? 24 : 80;
   if (slab <= 24 * 1024) return 24;
   if (slab <= 80 * 1024) return 80;
   return 0;
 }
 
 bool stream_supported(const GemmArgs& a, const GemmTable& tb) {
-  if (a.M > 64 || a.K % 128 != 0) return false;
+  if (a.M > 64 || a.K % 128 != 0 || a.K < 128) return false;
   for (int s = 0; s <= tb.S; ++s)
     if (tb.kseg_off[s] % 128 != 0) return false;
   if ((reinterpret_cast<uintptr_t>(a.xq) | reinterpret_cast<uintptr_t>(a.wq)) % 16 != 0) return false;
-  if (stream_slab_kb(a) == 0) return false;
+  bool ps;
+  if (stream_slab_kb(a, any_dual(tb.dual, tb.S), &ps) == 0) return false;
   return true;
 }
 
-template <int MT, int SLAB_KB>
-static hipError_t launch_stream_ms(const GemmArgs& a, const GemmTable& tb, int mode, bool dual, int grid, hipStream_t st) {
-  if (dual) hipLaunchKernelGGL((seglinear_stream_kernel<MT, true, SLAB_KB, GemmTable, NoGroups>), dim3(grid), dim3(kStreamWaves * 64), 0, st, a, tb, NoGroups{}, mode);
-  else hipLaunchKernelGGL((seglinear_stream_kernel<MT, false, SLAB_KB, GemmTable, NoGroups>), dim3(grid), dim3(kStreamWaves * 64), 0, st, a, tb, NoGroups{}, mode);
+template <int MT, int SLAB_KB, bool W4>
+static hipError_t launch_stream_ms(const GemmArgs& a, const GemmTable& tb, int mode, bool dual, bool ps, int grid, hipStream_t st) {
+#define SQ_K(D, P) hipLaunchKernelGGL((seglinear_stream_kernel<MT, D, SLAB_KB, GemmTable, NoGroups, W4, P>), dim3(grid), dim3(stream_waves(MT) * 64), 0, st, a, tb, NoGroups{}, mode)
+  if constexpr (MT <= 2) {
+    if (dual && ps) { SQ_K(true, true); return hipGetLastError(); }
+  }
+  if (dual) SQ_K(true, false);
+  else SQ_K(false, false);
+#undef SQ_K
   return hipGetLastError();
 }
 
-hipError_t launch_seglinear_stream(const GemmArgs& a, const GemmTable& tb, OutMode mode, int cus, hipStream_t st) {
-  bool dual = false;
-  for (int s = 0; s < tb.S; ++s) dual = dual || tb.dual[s];
+template <bool W4>
+static hipError_t launch_stream_impl(const GemmArgs& a, const GemmTable& tb, OutMode mode, int cus, hipStream_t st) {
+  const bool dual = any_dual(tb.dual, tb.S);
   const int mt = (a.M + 15) / 16;
   const int ngroups = (a.N + 15) / 16;
   int grid = ngroups < cus ? ngroups : cus;
-  const int slab = stream_slab_kb(a);
+  bool ps;
+  const int slab = stream_slab_kb(a, dual, &ps);
 #define SQ_STREAM(MT_) \
-  (slab == 24 ? launch_stream_ms<MT_, 24>(a, tb, mode, dual, grid, st) : launch_stream_ms<MT_, 80>(a, tb, mode, dual, grid, st))
+  (slab == 24 ? launch_stream_ms<MT_, 24, W4>(a, tb, mode, dual, ps, grid, st) : launch_stream_ms<MT_, 80, W4>(a, tb, mode, dual, ps, grid, st))
   switch (mt) {
     case 1: return SQ_STREAM(1);
     case 2: return SQ_STREAM(2);
@@ -379,33 +454,46 @@ hipError_t launch_seglinear_stream(const GemmArgs& a, const GemmTable& tb, OutMo
 #undef SQ_STREAM
 }
 
+hipError_t launch_seglinear_stream(const GemmArgs& a, const GemmTable& tb, OutMode mode, int cus, hipStream_t st) {
+  return launch_stream_impl<false>(a, tb, mode, cus, st);
+}
+
+// a.wq points at packed 4-bit codes [N][K/2]
+hipError_t launch_seglinear_stream_w4(const GemmArgs& a, const GemmTable& tb, OutMode mode, int cus, hipStream_t st) {
+  return launch_stream_impl<true>(a, tb, mode, cus, st);
+}
+
 // Grouped call: L layers of one shape that share X^ (M <= 32).  a.wq / a.wscale / a.bias / a.y are unused.
 bool stream_grouped_supported(const GemmArgs& a, const GroupSegTable& tb) {
-  if (a.M > 32 || a.K % 128 != 0) return false;
+  if (a.M > 32 || a.K % 128 != 0 || a.K < 128) return false;
   for (int s = 0; s <= tb.S; ++s)
     if (tb.kseg_off[s] % 128 != 0) return false;
   if (reinterpret_cast<uintptr_t>(a.xq) % 16 != 0) return false;
-  return stream_slab_kb(a) != 0;
+  bool ps;
+  return stream_slab_kb(a, any_dual(tb.dual, tb.S), &ps) != 0;
 }
 
 template <int MT, int SLAB_KB>
 static hipError_t launch_grouped_ms(const GemmArgs& a, const GroupSegTable& tb, const GroupTable& gt, int mode, bool dual,
-                                    int grid, hipStream_t st) {
-  if (dual) hipLaunchKernelGGL((seglinear_stream_kernel<MT, true, SLAB_KB, GroupSegTable, GroupTable>), dim3(grid), dim3(kStreamWaves * 64), 0, st, a, tb, gt, mode);
-  else hipLaunchKernelGGL((seglinear_stream_kernel<MT, false, SLAB_KB, GroupSegTable, GroupTable>), dim3(grid), dim3(kStreamWaves * 64), 0, st, a, tb, gt, mode);
+                                    bool ps, int grid, hipStream_t st) {
+#define SQ_K(D, P) hipLaunchKernelGGL((seglinear_stream_kernel<MT, D, SLAB_KB, GroupSegTable, GroupTable, false, P>), dim3(grid), dim3(stream_waves(MT) * 64), 0, st, a, tb, gt, mode)
+  if (dual && ps) SQ_K(true, true);
+  else if (dual) SQ_K(true, false);
+  else SQ_K(false, false);
+#undef SQ_K
   return hipGetLastError();
 }
 
 hipError_t launch_seglinear_grouped(const GemmArgs& a, const GroupSegTable& tb, const GroupTable& gt, OutMode mode, int cus,
                                     hipStream_t st) {
-  bool dual = false;
-  for (int s = 0; s < tb.S; ++s) dual = dual || tb.dual[s];
+  const bool dual = any_dual(tb.dual, tb.S);
   const int mt = (a.M + 15) / 16;
   const long ngroups = (long)((a.N + 15) / 16) * gt.L;
   const int grid = (int)(ngroups < cus ? ngroups : cus);
-  const int slab = stream_slab_kb(a);
-  if (mt == 1) return slab == 24 ? launch_grouped_ms<1, 24>(a, tb, gt, mode, dual, grid, st) : launch_grouped_ms<1, 80>(a, tb, gt, mode, dual, grid, st);
-  return slab == 24 ? launch_grouped_ms<2, 24>(a, tb, gt, mode, dual, grid, st) : launch_grouped_ms<2, 80>(a, tb, gt, mode, dual, grid, st);
+  bool ps;
+  const int slab = stream_slab_kb(a, dual, &ps);
+  if (mt == 1) return slab == 24 ? launch_grouped_ms<1, 24>(a, tb, gt, mode, dual, ps, grid, st) : launch_grouped_ms<1, 80>(a, tb, gt, mode, dual, ps, grid, st);
+  return slab == 24 ? launch_grouped_ms<2, 24>(a, tb, gt, mode, dual, ps, grid, st) : launch_grouped_ms<2, 80>(a, tb, gt, mode, dual, ps, grid, st);
 }
 
 }  // namespace sq

@@ -29,6 +29,12 @@ hipError_t launch_quantize_weight_block(const void* w, bool w_is_bf16, int8_t* w
 hipError_t launch_calibrate_act(const void* x, bool x_is_bf16, int M, int K, const ActTable& tb, float* amax, float* steps,
                                 bool accumulate, hipStream_t st);
 
+// 4-bit weights, packed two per byte (K and K-segment boundaries multiples of 128)
+hipError_t launch_quantize_weight_w4(const void* w, bool w_is_bf16, uint8_t* wq4, float* wscale, int N, int K,
+                                     const KsegTable& tb, hipStream_t st);
+hipError_t launch_seglinear_generic_w4(const GemmArgs& a, const GemmTable& tb, OutMode mode, hipStream_t st);
+hipError_t launch_seglinear_stream_w4(const GemmArgs& a, const GemmTable& tb, OutMode mode, int cus, hipStream_t st);
+
 // percentile clipping instead of the maximum: exact nearest-rank quantile by radix select; workspace of
 // calibrate_workspace_bytes() device bytes
 size_t calibrate_workspace_bytes();

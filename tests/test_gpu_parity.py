@@ -645,3 +645,75 @@ def test_headline_config_calibration_and_fused_quantizer(oracle):
     torch.cuda.synchronize()
     assert torch.equal(xq_t, xq_e)                                   # the two device paths agree everywhere
     assert np.array_equal(xq_t.cpu().numpy()[rows], want)            # and with the oracle on the sampled rows
+
+
+# ----------------------------------------------------------------------------------------------------
+# 4-bit packed weights (skinny layers)
+# ----------------------------------------------------------------------------------------------------
+W4CASES = [
+    dict(M=16, K=1152, N=6912, kseg=[0, 1152], dual=[1], nseg=None),                       # cfg3's shape
+    dict(M=5, K=256, N=70, kseg=[0, 128, 256], dual=[0, 1], nseg=None, bias=True),         # ragged N, mixed segments
+    dict(M=40, K=512, N=200, kseg=[0, 384, 512], dual=[1, 1], nseg=[0, 64, 200], seg_scale=True),   # three row tiles
+    dict(M=64, K=1152, N=1000, kseg=[0, 1152], dual=[1], nseg=None),                       # the large activation slab
+    dict(M=100, K=256, N=96, kseg=[0, 256], dual=[1], nseg=None),                          # M > 64: plain kernel
+    dict(M=1, K=128, N=16, kseg=[0, 128], dual=[0], nseg=None),
+]
+
+
+@pytest.mark.parametrize("case", W4CASES)
+@pytest.mark.parametrize("force_plain", [False, True])
+def test_seglinear_w4(oracle, case, force_plain):
+    """4-bit weight quantizer + packed storage bit-exact; integer sums bit-exact; output within the fp32 tolerance."""
+    import torch
+
+    g = _gpu()
+    M, K, N = case["M"], case["K"], case["N"]
+    nseg = case["nseg"] or [0, N]
+    w = wl.random_layer(M, K, N, case["kseg"], nseg, case["dual"], seed=3 * M + K + N, x_dtype="bf16", act="silu",
+                        with_seg_scale=bool(case.get("seg_scale")), with_bias=bool(case.get("bias")))
+    gl = g.GpuLayer(w)
+    wq4 = torch.full((((N + 15) // 16) * 16 * (K // 2),), 0xAB, dtype=torch.uint8, device=g.DEV)
+    sq.sq_quantize_weight_w4(gl.layer, gl.wt, wq4, gl.wscale)
+    rq, rs = oracle.quantize_weight_w4(w.w, w.kseg_off)
+    torch.cuda.synchronize()
+    assert np.array_equal(wq4.cpu().numpy(), oracle.pack_w4(rq))
+    assert np.array_equal(gl.wscale.cpu().numpy().view(np.uint32), rs.view(np.uint32))
+    xp, xn, _ = gl.quantize_act()
+    r = oracle.seglinear(w.x, w.w, w.kseg_off, w.nseg_off, w.dual, w.s_pos, w.s_neg, w.seg_scale, w.bias, wbits=4)
+    assert np.array_equal(xp, r.xq_pos) and np.array_equal(xn, r.xq_neg)
+    sq.sq_tuning_set("force_path", 0 if force_plain else -1)
+    try:
+        ap = torch.full((w.S, M, N), 0x5A5A5A5A, dtype=torch.int32, device=g.DEV)
+        an = torch.full((w.S, M, N), 0x5A5A5A5A, dtype=torch.int32, device=g.DEV)
+        sq.sq_seglinear_w4_debug_acc(gl.layer, gl.xq, wq4, ap, an)
+        torch.cuda.synchronize()
+        assert np.array_equal(ap.cpu().numpy(), r.acc_pos), "acc_pos differs"
+        assert np.array_equal(an.cpu().numpy(), r.acc_neg), "acc_neg differs"
+        ymax = float(np.abs(r.y32).max())
+        y = torch.full((M, N), float("nan"), dtype=torch.float32, device=g.DEV)
+        sq.sq_seglinear_w4(gl.layer, gl.xq, wq4, gl.wscale, gl.bias, y)
+        torch.cuda.synchronize()
+        y = y.cpu().numpy()
+        assert not np.isnan(y).any()
+        assert float(np.abs(y.astype(np.float64) - r.y32.astype(np.float64)).max()) <= 1e-5 * ymax
+        assert float(np.abs(y.astype(np.float64) - r.y64).max()) <= 2e-5 * ymax
+        yb = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=g.DEV)
+        sq.sq_seglinear_w4(gl.layer, gl.xq, wq4, gl.wscale, gl.bias, yb)
+        torch.cuda.synchronize()
+        g.check_bf16_against(g.bf16_tensor_bits(yb), r.y32, wl.f32_to_bf16_bits(r.y32), 1e-5 * ymax)
+    finally:
+        sq.sq_tuning_set("force_path", -1)
+
+
+def test_w4_rejects_unaligned_layouts():
+    import torch
+
+    g = _gpu()
+    lay = sq.Layer(4, 192, 16, [0, 192], [0, 16], [1], [0.01], [0.01])      # K not a multiple of 128
+    t = torch.zeros(4096, dtype=torch.uint8, device=g.DEV)
+    f = torch.zeros(4096, dtype=torch.float32, device=g.DEV)
+    with pytest.raises(sq.SqError):
+        sq.sq_quantize_weight_w4(lay, f, t, f)
+    lay2 = sq.Layer(4, 256, 16, [0, 64, 256], [0, 16], [1, 0], [0.01, 0.01], [0.01, 0.01])   # boundary at 64
+    with pytest.raises(sq.SqError):
+        sq.sq_seglinear_w4(lay2, t.view(torch.int8), t, f, None, f)

@@ -24,7 +24,7 @@ def sq():
 def test_every_declared_symbol_is_exported(sq):
     with open(os.path.join(ROOT, "include", "segquant.h")) as f:
         header = f.read()
-    declared = set(re.findall(r"\b(sq_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(sq_[a-z0-9_]+)\s*\(", header))
     assert {"sq_quantize_weight", "sq_quantize_act", "sq_seglinear", "sq_seglinear_debug_acc", "sq_status_string",
             "sq_version", "sq_tuning_set"} <= declared
     lib = sq.load_library()
@@ -114,6 +114,13 @@ def test_invalid_arguments_are_rejected_on_the_host(sq):
     wneed = lib.sq_quantize_act_fused_workspace_bytes(C.byref(ok.c))
     assert wneed == 65536 * ok.c.S and lib.sq_quantize_act_fused_workspace_bytes(None) == 0
     assert fused(ws=FAKE, nbytes=wneed - 1) == INVALID and fused(ws=C.c_void_p(0x1008), nbytes=wneed) == INVALID
+    w4 = _layer(sq, K=256, kseg_off=[0, 256])
+    assert lib.sq_quantize_weight_w4(C.byref(w4.c), None, 0, FAKE, FAKE, None) == INVALID
+    assert lib.sq_quantize_weight_w4(C.byref(w4.c), FAKE, 0, FAKE, None, None) == INVALID
+    assert lib.sq_seglinear_w4(C.byref(w4.c), FAKE, None, FAKE, None, FAKE, 0, None) == INVALID
+    assert lib.sq_seglinear_w4(C.byref(w4.c), FAKE, FAKE, FAKE, None, FAKE, 9, None) == INVALID
+    assert lib.sq_seglinear_w4_debug_acc(C.byref(w4.c), FAKE, FAKE, None, FAKE, None) == INVALID
+    assert lib.sq_quantize_weight_w4(C.byref(ok.c), FAKE, 0, FAKE, FAKE, None) in (UNSUPPORTED, INVALID) or ok.c.K % 128 == 0
     need = lib.sq_calibrate_workspace_bytes()
     assert 0 < need < (1 << 20)
     pct = lambda p, ws=FAKE, nbytes=need, x=FAKE: lib.sq_calibrate_act_percentile(C.byref(ok.c), x, 1, p, FAKE, FAKE, ws, nbytes, 0, None)

@@ -592,24 +592,29 @@ def test_w4_quantizer_and_packing(oracle):
     assert s1[0, 0] == np.float32(0.7) / np.float32(7.0)
     expect = [int(np.rint(np.float32(v) / s1[0, 0])) for v in (0.25, 0.35, -0.7, 0.04)]
     assert q1[0, :4].tolist() == expect and expect[2] == -7 and expect[3] == 0
-    # packing: byte j of a 128-block = code j (low nibble) | code 64 + j (high nibble), two's complement
-    codes = np.zeros((1, 256), np.int8)
+    # packing: groups of 16 rows, steps of 128 codes, one KiB per (group, step):
+    #   packed[((g T + t) 16 + r) 64 + j] = code(16 g + r, 128 t + j) | code(16 g + r, 128 t + 64 + j) << 4
+    codes = np.zeros((18, 256), np.int8)                          # two row groups (the second one padded), T = 2
     codes[0, 0], codes[0, 64], codes[0, 1], codes[0, 65] = 3, -2, -8, 7
-    codes[0, 128 + 63], codes[0, 128 + 127] = -1, 5
+    codes[5, 128 + 63], codes[5, 128 + 127] = -1, 5
+    codes[17, 2], codes[17, 66] = 4, -4
     pk = oracle.pack_w4(codes)
-    assert pk.shape == (1, 128)
-    assert pk[0, 0] == (3 | (0xE << 4)) and pk[0, 1] == (0x8 | (7 << 4)) and pk[0, 64 + 63] == (0xF | (5 << 4))
+    assert pk.shape == (2 * 16 * 128,)
+    assert pk[0] == (3 | (0xE << 4)) and pk[1] == (0x8 | (7 << 4))
+    assert pk[((0 * 2 + 1) * 16 + 5) * 64 + 63] == (0xF | (5 << 4))
+    assert pk[((1 * 2 + 0) * 16 + 1) * 64 + 2] == (4 | (0xC << 4))
+    assert np.count_nonzero(pk) == 4                              # padding rows and everything else are zero
     # round trip through an independent unpacker
-    pk = oracle.pack_w4(wq)
+    pk = oracle.pack_w4(wq).reshape(1, 2, 16, 64)                 # [group][step][row][byte]; 6 rows -> one group
     lo = (pk & 0xF).astype(np.int8)
     hi = (pk >> 4).astype(np.int8)
     lo = np.where(lo > 7, lo - 16, lo)
     hi = np.where(hi > 7, hi - 16, hi)
-    back = np.empty_like(wq)
-    for b in range(2):
-        back[:, 128 * b:128 * b + 64] = lo[:, 64 * b:64 * b + 64]
-        back[:, 128 * b + 64:128 * b + 128] = hi[:, 64 * b:64 * b + 64]
-    assert np.array_equal(back, wq)
+    back = np.zeros((16, 256), np.int8)
+    for t in range(2):
+        back[:, 128 * t:128 * t + 64] = lo[0, t]
+        back[:, 128 * t + 64:128 * t + 128] = hi[0, t]
+    assert np.array_equal(back[:6], wq) and not back[6:].any()
     with pytest.raises(Exception):
         oracle.pack_w4(np.zeros((2, 100), np.int8))               # K must be a multiple of 128
     with pytest.raises(Exception):
