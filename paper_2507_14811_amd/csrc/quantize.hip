@@ -15,7 +15,7 @@ namespace sq {
 // of one row and one segment: 32 B (bf16) or 64 B (fp32) in, 16 B out.  A block streams 4 x 256 such
 // chunks; all loads are issued before any arithmetic.
 // ------------------------------------------------------------------------------------------------
-constexpr int kActUnroll = 4;
+constexpr int kActUnroll = 1;     // measured on the headline layer: 37.4 us with 1, 39.6 with 2, 44 with 4, 52.6 with 8 chunks per thread
 constexpr int kActChunk = 16;
 
 __device__ __forceinline__ uint32_t pack4(int c0, int c1, int c2, int c3) {
@@ -147,7 +147,7 @@ static hipError_t launch_quantize_act_impl(const void* x, bool x_is_bf16, int8_t
 // costs ~45 ALU instructions per element and is ALU-bound at twice the HBM time; this one is a stream again.
 // ------------------------------------------------------------------------------------------------
 constexpr int kLutBytes = 65536;
-constexpr int kLutThreads = 512;
+constexpr int kLutThreads = 512;    // 256 and 1024 measured slower
 
 __global__ __launch_bounds__(256) void act_lut_build_kernel(const ActTable tb, int8_t* __restrict__ lut) {
   const int ks = blockIdx.y;
@@ -184,7 +184,7 @@ __global__ __launch_bounds__(kLutThreads) void quantize_act_lut_kernel(const uin
   const uint32_t cps = (uint32_t)(k1 - k0) / kActChunk;                    // 16-element chunks per row of the segment
   const uint32_t nchunks = (uint32_t)M * cps;
   const uint32_t stride = (uint32_t)(wg1 - wg0) * kLutThreads;
-  constexpr int U = 4;
+  constexpr int U = 1;                                                // chunks in flight per thread: more only hurt (measured)
   for (uint32_t c0 = (uint32_t)((int)blockIdx.x - wg0) * kLutThreads + threadIdx.x; c0 < nchunks; c0 += U * stride) {
     v4i raw[U][2];
     size_t eoff[U];
