@@ -19,11 +19,13 @@ from .segquant_oracle import (  # noqa: F401
     int_gemm,
     num_threads,
     quantize_act,
+    quantize_act_dynamic,
     quantize_act_fused,
     quantize_weight,
     quantize_weight_block,
     quantize_weight_w4,
     pack_w4,
     seglinear,
+    seglinear_dynamic,
     widen_bf16,
 )

@@ -286,3 +286,36 @@ def seglinear(x, w, kseg_off, nseg_off, dual, s_pos, s_neg, seg_scale=None, bias
     ap, an = int_gemm(xp, xn, wq, kseg_off, dual, rows)
     y32, y64 = dequant(ap, an, nseg_off, dual, s_pos, s_neg, ws, seg_scale, bias)
     return OracleResult(wq, ws, xp, xn, None if rows is None else np.asarray(rows), ap, an, y32, y64)
+
+
+def quantize_act_dynamic(x, kseg_off, dual):
+    """Dynamic per-token steps (App. B: in the 4-bit settings activations are quantized dynamically per token): every
+    token row is calibrated on its own with the min/max rule (calibrate_act on that row) and quantized with its own
+    steps.  -> (xq_pos, xq_neg int8 [M][K], s_pos, s_neg fp32 [M][S])"""
+    x = _f32(x)
+    M, K = x.shape
+    S = len(kseg_off) - 1
+    xp = np.empty((M, K), np.int8)
+    xn = np.empty((M, K), np.int8)
+    sp = np.empty((M, S), np.float32)
+    sn = np.empty((M, S), np.float32)
+    for m in range(M):
+        sp[m], sn[m], _, _ = calibrate_act(x[m:m + 1], kseg_off, dual)
+        xp[m:m + 1], xn[m:m + 1] = quantize_act(x[m:m + 1], kseg_off, dual, sp[m], sn[m])
+    return xp, xn, sp, sn
+
+
+def seglinear_dynamic(x, w, kseg_off, nseg_off, dual, seg_scale=None, bias=None, wbits=8) -> OracleResult:
+    """The layer with dynamic per-token activation steps: the steps of the dequantization are those of the token."""
+    wq, ws = quantize_weight(w, kseg_off) if wbits == 8 else quantize_weight_w4(w, kseg_off)
+    xp, xn, sp, sn = quantize_act_dynamic(x, kseg_off, dual)
+    ap, an = int_gemm(xp, xn, wq, kseg_off, dual)
+    M, N = x.shape[0], w.shape[0]
+    y32 = np.empty((M, N), np.float32)
+    y64 = np.empty((M, N), np.float64)
+    for m in range(M):
+        a, b = dequant(ap[:, m:m + 1], an[:, m:m + 1], nseg_off, dual, sp[m], sn[m], ws, seg_scale, bias)
+        y32[m], y64[m] = a[0], b[0]
+    r = OracleResult(wq, ws, xp, xn, None, ap, an, y32, y64)
+    r.tok_steps = np.stack([sp, sn])            # [2][M][S]
+    return r

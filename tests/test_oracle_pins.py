@@ -627,3 +627,42 @@ def test_w4_quantizer_and_packing(oracle):
     xq = r.xq_pos.astype(np.float64) * np.repeat(sp, 128)[None, :] + r.xq_neg.astype(np.float64) * np.repeat(sn, 128)[None, :]
     wd = wq.astype(np.float64) * np.repeat(ws.T, 128, axis=1)
     assert np.allclose(r.y64, xq @ wd.T, rtol=1e-12, atol=1e-12)
+
+
+# dynamic per-token activation steps (App. B: activations of the 4-bit settings)
+def test_dynamic_per_token_steps(oracle):
+    rng = np.random.default_rng(8)
+    kseg, dual = [0, 128, 256], [0, 1]
+    x = (rng.standard_normal((6, 256)) * rng.uniform(0.2, 5.0, size=(6, 1))).astype(np.float32)   # rows of different scale
+    x[:, 128:] = np.where(x[:, 128:] > 0, x[:, 128:], 0.1 * x[:, 128:])
+    w = (rng.standard_normal((10, 256)) * 0.05).astype(np.float32)
+    xp, xn, sp, sn = oracle.quantize_act_dynamic(x, kseg, dual)
+    q = np.float32(127.0)
+    for m in range(6):
+        assert sp[m, 0] == np.abs(x[m, :128]).max() / q and sn[m, 0] == 1.0          # single-scale segment
+        assert sp[m, 1] == x[m, 128:].max() / q and sn[m, 1] == (-x[m, 128:].min()) / q
+        # every token uses its whole code range
+        assert max(xp[m, :128].max(), -xp[m, :128].min()) == 127
+        assert xp[m, 128:].max() == 127 and xn[m, 128:].min() == -127
+    # a row on its own gives the same codes: tokens do not interact
+    a, b, c, d = oracle.quantize_act_dynamic(x[3:4], kseg, dual)
+    assert np.array_equal(a[0], xp[3]) and np.array_equal(b[0], xn[3]) and np.array_equal(c[0], sp[3])
+    r = oracle.seglinear_dynamic(x, w, kseg, [0, 10], dual)
+    # rows that share their extremes with the whole batch: static calibration of that batch is the same layer
+    same = np.tile(x[2:3], (3, 1))
+    rs = oracle.seglinear_dynamic(same, w, kseg, [0, 10], dual)
+    s_sp, s_sn, _, _ = oracle.calibrate_act(same, kseg, dual)
+    st = oracle.seglinear(same, w, kseg, [0, 10], dual, s_sp, s_sn)
+    assert np.array_equal(rs.y32, st.y32) and np.array_equal(rs.acc_pos, st.acc_pos)
+    assert np.array_equal(rs.y32[0], r.y32[2])
+    # against a float64 evaluation with every token's own steps
+    xd = (r.xq_pos.astype(np.float64) * np.repeat(sp.astype(np.float64), 128, axis=1)
+          + r.xq_neg.astype(np.float64) * np.repeat(sn.astype(np.float64), 128, axis=1))
+    wd = r.wq.astype(np.float64) * np.repeat(r.wscale.T.astype(np.float64), 128, axis=1)
+    assert np.allclose(r.y64, xd @ wd.T, rtol=1e-12, atol=1e-12)
+    # dynamic steps are never worse than static ones of the batch, and better for the small-scale tokens
+    ref = x.astype(np.float64) @ w.astype(np.float64).T
+    g_sp, g_sn, _, _ = oracle.calibrate_act(x, kseg, dual)
+    stat = oracle.seglinear(x, w, kseg, [0, 10], dual, g_sp, g_sn)
+    small = int(np.argmin(np.abs(x).max(axis=1)))
+    assert np.abs(r.y64[small] - ref[small]).max() < np.abs(stat.y64[small] - ref[small]).max()
