@@ -244,6 +244,28 @@ sq_status sq_seglinear_w4_debug_acc(const sq_layer* layer, const int8_t* xq, con
                                     int32_t* acc_neg, void* stream);
 
 /*
+ * Dynamic per-token activation steps (App. B, granularity of the 4-bit settings: activations are quantized dynamically
+ * per token).  Every token row m is calibrated on its own with the min/max rule of Sec. 4.3.2, per K-segment ks:
+ *   dual          s_pos[m][ks] = max(0, max_k x) / 127,  s_neg[m][ks] = max(0, -min_k x) / 127
+ *   single-scale  s_pos[m][ks] = max_k |x| / 127,        s_neg[m][ks] = 1
+ * (1.0 where the extreme is 0), quantized with these steps as in sq_quantize_act, and dequantized with them:
+ *   y[m][n] = sum_ks seg_scale * wscale[ks][n] * (s_pos[m][ks] acc_pos + s_neg[m][ks] acc_neg) + bias[n].
+ * layer->s_pos / s_neg are not read.
+ *   x          dev, [M][K] of x_dt                                  in
+ *   xq         dev, int8 [M][K], polarity-merged codes              out (sq_quantize_act_dynamic) / in
+ *   tok_steps  dev, fp32 [2][M][S]: s_pos, then s_neg               out (sq_quantize_act_dynamic) / in
+ *   wq         dev, int8 [N][K] (w_bits == 8) or the packed 4-bit codes of sq_quantize_weight_w4 (w_bits == 4)
+ *   others as sq_seglinear.
+ * M <= 64 with at most 8 K-segments (and the alignment the weight stream needs) runs the weight-stream kernel; every
+ * other shape runs a plain one-thread-per-output kernel.  SQ_ERR_INVALID_ARG for w_bits other than 4 or 8.
+ */
+sq_status sq_quantize_act_dynamic(const sq_layer* layer, const void* x, sq_dtype x_dt, int8_t* xq, float* tok_steps,
+                                  void* stream);
+sq_status sq_seglinear_dynamic(const sq_layer* layer, const int8_t* xq, const float* tok_steps, const void* wq,
+                               int32_t w_bits, const float* wscale, const float* bias, void* y, sq_dtype y_dt,
+                               void* stream);
+
+/*
  * Benchmark probe, not part of the method: a register-only int8 MFMA loop on every compute unit whose operands
  * are taken from `codes` (dev, int8, `bytes` >= 4096, 16-byte aligned).  The sustained rate depends on the
  * operand values because the core clock is power-managed, so the benchmark reports it for codes distributed

@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     SQ_ACT_NONE,
     SQ_ACT_SILU,
     sq_quantize_act,
+    sq_quantize_act_dynamic,
     sq_quantize_act_fused,
     sq_quantize_act_fused_workspace_bytes,
     sq_quantize_weight,
@@ -23,6 +24,7 @@ from .binding import (  # noqa: F401
     sq_quantize_weight_w4,
     sq_seglinear,
     sq_seglinear_debug_acc,
+    sq_seglinear_dynamic,
     sq_seglinear_grouped,
     sq_seglinear_w4,
     sq_seglinear_w4_debug_acc,

@@ -25,7 +25,7 @@ EXPORTS = ("sq_quantize_weight", "sq_quantize_act", "sq_seglinear", "sq_seglinea
            "sq_quantize_weight_block", "sq_calibrate_act", "sq_calibrate_act_percentile",
            "sq_calibrate_workspace_bytes", "sq_quantize_act_fused",
            "sq_quantize_act_fused_workspace_bytes", "sq_quantize_weight_w4", "sq_seglinear_w4",
-           "sq_seglinear_w4_debug_acc")
+           "sq_seglinear_w4_debug_acc", "sq_quantize_act_dynamic", "sq_seglinear_dynamic")
 
 
 class SqError(RuntimeError):
@@ -84,6 +84,10 @@ def load_library() -> C.CDLL:
     lib.sq_seglinear_w4_debug_acc.argtypes = [lp, vp, vp, vp, vp, vp]
     for f in (lib.sq_quantize_weight_w4, lib.sq_seglinear_w4, lib.sq_seglinear_w4_debug_acc):
         f.restype = i32
+    lib.sq_quantize_act_dynamic.argtypes = [lp, vp, i32, vp, vp, vp]
+    lib.sq_quantize_act_dynamic.restype = i32
+    lib.sq_seglinear_dynamic.argtypes = [lp, vp, vp, vp, i32, vp, vp, vp, i32, vp]
+    lib.sq_seglinear_dynamic.restype = i32
     lib.sq_calibrate_act_percentile.argtypes = [lp, vp, i32, C.c_double, vp, vp, vp, C.c_size_t, i32, vp]
     lib.sq_calibrate_act_percentile.restype = i32
     lib.sq_calibrate_workspace_bytes.argtypes = []
@@ -262,6 +266,19 @@ def sq_seglinear_w4_debug_acc(layer: Layer, xq, wq4, acc_pos, acc_neg, stream=No
     """Raw int32 sums of the 4-bit codes: acc_pos, acc_neg int32 [S][M][N]."""
     _check(load_library().sq_seglinear_w4_debug_acc(C.byref(layer.c), _dptr(xq), _dptr(wq4), _dptr(acc_pos),
                                                     _dptr(acc_neg), _stream(stream)), "sq_seglinear_w4_debug_acc")
+
+
+def sq_quantize_act_dynamic(layer: Layer, x, xq, tok_steps, stream=None) -> None:
+    """Per-token min/max steps and codes: xq int8 [M][K], tok_steps fp32 [2][M][S] (s_pos, then s_neg)."""
+    _check(load_library().sq_quantize_act_dynamic(C.byref(layer.c), _dptr(x), _dt(x), _dptr(xq), _dptr(tok_steps),
+                                                  _stream(stream)), "sq_quantize_act_dynamic")
+
+
+def sq_seglinear_dynamic(layer: Layer, xq, tok_steps, wq, w_bits: int, wscale, bias, y, stream=None) -> None:
+    """The layer with per-token steps; wq: int8 [N][K] (w_bits 8) or packed 4-bit codes (w_bits 4)."""
+    _check(load_library().sq_seglinear_dynamic(C.byref(layer.c), _dptr(xq), _dptr(tok_steps), _dptr(wq), int(w_bits),
+                                               _dptr(wscale), _dptr(bias), _dptr(y), _dt(y), _stream(stream)),
+           "sq_seglinear_dynamic")
 
 
 class GroupItems:

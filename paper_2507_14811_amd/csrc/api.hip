@@ -36,11 +36,11 @@ sq_status check_layer(const sq_layer* L, bool need_m, bool need_scales) {
         if (L->s_neg == nullptr || !step_ok(L->s_neg[s])) return SQ_ERR_INVALID_ARG;
       }
     }
-    if (L->seg_scale) {
-      if ((long)L->S * L->T > SQ_MAX_SEG_SCALE) return SQ_ERR_UNSUPPORTED;
-      for (int i = 0; i < L->S * L->T; ++i)
-        if (!std::isfinite(L->seg_scale[i])) return SQ_ERR_INVALID_ARG;
-    }
+  }
+  if (L->seg_scale) {                      // read (copied into the kernel's table) by every GEMM entry point
+    if ((long)L->S * L->T > SQ_MAX_SEG_SCALE) return SQ_ERR_UNSUPPORTED;
+    for (int i = 0; i < L->S * L->T; ++i)
+      if (!std::isfinite(L->seg_scale[i])) return SQ_ERR_INVALID_ARG;
   }
   for (int s = 0; s < L->S; ++s)
     if (L->kseg_off[s + 1] - L->kseg_off[s] > SQ_MAX_KSEG_LEN) return SQ_ERR_UNSUPPORTED;
@@ -126,6 +126,37 @@ bool w4_layout_ok(const sq_layer* L) {
   for (int s = 0; s <= L->S; ++s)
     if (L->kseg_off[s] % 128 != 0) return false;
   return true;
+}
+
+// Dynamic per-token steps: the weight-stream kernel (M <= 64, at most 8 K-segments: its step table is 4 KiB of LDS) or the
+// one-thread-per-output kernel; 8-bit or 4-bit packed weights.
+sq_status run_gemm_dynamic(const sq_layer* L, const int8_t* xq, const float* tok_steps, const void* wq, int w_bits,
+                           const float* wscale, const float* bias, void* y, sq::OutMode mode, void* stream) {
+  if (w_bits == 4 && !w4_layout_ok(L)) return SQ_ERR_UNSUPPORTED;
+  sq::GemmTable tb;
+  fill_gemm_table(L, tb);
+  for (int s = 0; s < L->S; ++s) { tb.s_pos[s] = 1.0f; tb.s_neg[s] = L->dual[s] ? 1.0f : 0.0f; }
+  sq::GemmArgs a{};
+  a.xq = xq;
+  a.wq = reinterpret_cast<const int8_t*>(wq);
+  a.wscale = wscale;
+  a.bias = bias;
+  a.y = y;
+  a.M = L->M;
+  a.K = L->K;
+  a.N = L->N;
+  a.tok_steps = tok_steps;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  const bool stream_ok = L->S <= 8 && sq::stream_supported(a, tb);
+  if (g_force_path == 3 && !stream_ok) return SQ_ERR_UNSUPPORTED;
+  hipError_t e;
+  if (g_force_path != 0 && stream_ok) {
+    e = w_bits == 4 ? sq::launch_seglinear_stream_w4(a, tb, mode, sq::device_cus(), st)
+                    : sq::launch_seglinear_stream(a, tb, mode, sq::device_cus(), st);
+  } else {
+    e = w_bits == 4 ? sq::launch_seglinear_generic_w4(a, tb, mode, st) : sq::launch_seglinear_generic(a, tb, mode, st);
+  }
+  return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 
 sq_status run_gemm_w4(const sq_layer* L, const int8_t* xq, const uint8_t* wq4, const float* wscale, const float* bias,
@@ -363,6 +394,34 @@ sq_status sq_seglinear_w4_debug_acc(const sq_layer* layer, const int8_t* xq, con
   if (xq == nullptr || wq4 == nullptr || acc_pos == nullptr || acc_neg == nullptr) return SQ_ERR_INVALID_ARG;
   if ((long long)layer->S * layer->M * layer->N > 0x7FFFFFFFll) return SQ_ERR_UNSUPPORTED;
   return run_gemm_w4(layer, xq, wq4, nullptr, nullptr, nullptr, acc_pos, acc_neg, sq::OUT_DEBUG_ACC, stream);
+}
+
+sq_status sq_quantize_act_dynamic(const sq_layer* layer, const void* x, sq_dtype x_dt, int8_t* xq, float* tok_steps,
+                                  void* stream) {
+  sq_status st = check_layer(layer, true, false);
+  if (st != SQ_OK) return st;
+  if (x == nullptr || xq == nullptr || tok_steps == nullptr) return SQ_ERR_INVALID_ARG;
+  if (x_dt != SQ_F32 && x_dt != SQ_BF16) return SQ_ERR_INVALID_ARG;
+  sq::ActTable tb;
+  std::memset(&tb, 0, sizeof(tb));
+  tb.S = layer->S;
+  for (int s = 0; s <= layer->S; ++s) tb.kseg_off[s] = layer->kseg_off[s];
+  for (int s = 0; s < layer->S; ++s) tb.dual[s] = layer->dual[s] ? 1 : 0;
+  hipError_t e = sq::launch_quantize_act_dynamic(x, x_dt == SQ_BF16, xq, tok_steps, layer->M, layer->K, tb,
+                                                 reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
+sq_status sq_seglinear_dynamic(const sq_layer* layer, const int8_t* xq, const float* tok_steps, const void* wq,
+                               int32_t w_bits, const float* wscale, const float* bias, void* y, sq_dtype y_dt,
+                               void* stream) {
+  sq_status st = check_layer(layer, true, false);
+  if (st != SQ_OK) return st;
+  if (xq == nullptr || tok_steps == nullptr || wq == nullptr || wscale == nullptr || y == nullptr) return SQ_ERR_INVALID_ARG;
+  if (y_dt != SQ_F32 && y_dt != SQ_BF16) return SQ_ERR_INVALID_ARG;
+  if (w_bits != 8 && w_bits != 4) return SQ_ERR_INVALID_ARG;
+  return run_gemm_dynamic(layer, xq, tok_steps, wq, w_bits, wscale, bias, y, y_dt == SQ_BF16 ? sq::OUT_BF16 : sq::OUT_F32,
+                          stream);
 }
 
 sq_status sq_probe_mfma(const int8_t* codes, size_t bytes, int iters, double* ops, void* stream) {

@@ -358,6 +358,67 @@ hipError_t launch_quantize_weight_block(const void* w, bool w_is_bf16, int8_t* w
 }
 
 // ------------------------------------------------------------------------------------------------
+// Dynamic per-token activation steps (App. B: in the 4-bit settings activations are quantized dynamically per
+// token): one workgroup per token row; per K-segment the row's extremes give its steps by the min/max rule
+// (Sec. 4.3.2: s_+ = max x / 127, s_- = |min x| / 127, 1.0 where the extreme is 0), then the row is quantized with
+// them.  A row is read twice (the second time from cache).  tok_steps: [2][M][S], s_pos then s_neg.
+// ------------------------------------------------------------------------------------------------
+template <bool BF16>
+__global__ __launch_bounds__(256) void quantize_act_dynamic_kernel(const void* __restrict__ x, int8_t* __restrict__ xq,
+                                                                   float* __restrict__ tok_steps, int M, int K,
+                                                                   const ActTable tb) {
+  const int m = blockIdx.x;
+  const size_t row = (size_t)m * K;
+  __shared__ float red[2][4];
+  __shared__ float stp[2];
+  for (int ks = 0; ks < tb.S; ++ks) {
+    const int k0 = tb.kseg_off[ks], k1 = tb.kseg_off[ks + 1];
+    const bool dual = tb.dual[ks] != 0;
+    float mp = 0.0f, mn = 0.0f;
+    for (int k = k0 + threadIdx.x; k < k1; k += 256) {
+      const float v = load_w<BF16>(x, row + k);
+      if (dual) {
+        mp = __builtin_fmaxf(mp, v);
+        mn = __builtin_fmaxf(mn, -v);
+      } else {
+        mp = __builtin_fmaxf(mp, __builtin_fabsf(v));
+      }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+      mp = __builtin_fmaxf(mp, __shfl_xor(mp, off, 64));
+      mn = __builtin_fmaxf(mn, __shfl_xor(mn, off, 64));
+    }
+    if ((threadIdx.x & 63) == 0) { red[0][threadIdx.x >> 6] = mp; red[1][threadIdx.x >> 6] = mn; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      mp = __builtin_fmaxf(__builtin_fmaxf(red[0][0], red[0][1]), __builtin_fmaxf(red[0][2], red[0][3]));
+      mn = __builtin_fmaxf(__builtin_fmaxf(red[1][0], red[1][1]), __builtin_fmaxf(red[1][2], red[1][3]));
+      const float sp = (mp == 0.0f) ? 1.0f : mp / kQmax, sn = (mn == 0.0f) ? 1.0f : mn / kQmax;
+      stp[0] = sp;
+      stp[1] = sn;
+      tok_steps[(size_t)m * tb.S + ks] = sp;
+      tok_steps[((size_t)M + m) * tb.S + ks] = sn;
+    }
+    __syncthreads();
+    const float sp = stp[0], sn = stp[1];
+    for (int k = k0 + threadIdx.x; k < k1; k += 256) {
+      const float v = load_w<BF16>(x, row + k);
+      const bool ng = dual && (v < 0.0f);
+      xq[row + k] = (int8_t)clip_code(__builtin_rintf(v / (ng ? sn : sp)));
+    }
+    __syncthreads();                                      // stp and red are reused by the next segment
+  }
+}
+
+hipError_t launch_quantize_act_dynamic(const void* x, bool x_is_bf16, int8_t* xq, float* tok_steps, int M, int K,
+                                       const ActTable& tb, hipStream_t st) {
+  if (x_is_bf16) hipLaunchKernelGGL((quantize_act_dynamic_kernel<true>), dim3(M), dim3(256), 0, st, x, xq, tok_steps, M, K, tb);
+  else           hipLaunchKernelGGL((quantize_act_dynamic_kernel<false>), dim3(M), dim3(256), 0, st, x, xq, tok_steps, M, K, tb);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
 // 4-bit weights (App. B: per-channel weights in the 4-bit settings): the Sec. 3 quantizer with q_max = 7 per output
 // channel and K-segment, codes packed two per byte in the order the weight stream consumes them: rows in groups
 // of 16 (the last group padded with zero rows), K in steps of 128 codes (T = K / 128), one contiguous KiB per

@@ -38,8 +38,13 @@ __global__ __launch_bounds__(256) void seglinear_generic_kernel(const GemmArgs a
       a.acc_neg[o] = an;
     } else {
       const float c = seg_scale_of(tb, ks, n) * a.wscale[(size_t)ks * a.N + n];
-      float t = tb.s_pos[ks] * (float)ap;
-      if (dual) t += tb.s_neg[ks] * (float)an;
+      float sp = tb.s_pos[ks], sn = tb.s_neg[ks];
+      if (a.tok_steps) {                                            // dynamic per-token steps
+        sp = a.tok_steps[(size_t)m * tb.S + ks];
+        sn = a.tok_steps[((size_t)a.M + m) * tb.S + ks];
+      }
+      float t = sp * (float)ap;
+      if (dual) t += sn * (float)an;
       y += c * t;
     }
   }

@@ -73,8 +73,9 @@ struct StreamCfg {
   static constexpr int RAW = (156 * 1024 - SLAB) / (NW * STEP);
   static constexpr int RING = RAW > 28 ? 28 : RAW;                // at most 56 loads in flight: below the 6-bit vmcnt
   static constexpr int LDS = SLAB + NW * RING * STEP;
+  static constexpr int TOK = 4096;                                // table of dynamic per-token steps: [64 rows][8 segments][2]
   static_assert(RING >= 2, "ring too shallow");
-  static_assert(LDS <= 160 * 1024, "LDS budget");
+  static_assert(LDS + 4096 <= 160 * 1024, "LDS budget");
 };
 
 // TB: GemmTable (one layer; GT = NoGroups) or GroupSegTable (GT = GroupTable: L layers of the same shape that share
@@ -85,9 +86,10 @@ __global__ __launch_bounds__(stream_waves(MT) * 64) void seglinear_stream_kernel
   using C = StreamCfg<MT, SLAB_KB, W4, PS>;
   constexpr bool GROUPED = std::is_same<GT, GroupTable>::value;
   constexpr int RING = C::RING, STEP = C::STEP, LPS = C::LPS, NW = C::NW;
-  __shared__ __attribute__((aligned(1024))) char smem[C::LDS];
+  __shared__ __attribute__((aligned(1024))) char smem[C::LDS + C::TOK];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  float* tok = reinterpret_cast<float*>(smem + C::LDS);            // [row][ks][polarity], filled when a.tok_steps is set
 
   // ---- this wave's run of 16-column groups ------------------------------------------------------------
   const int gpl = (a.N + 15) >> 4;                                 // groups per layer
@@ -196,6 +198,14 @@ __global__ __launch_bounds__(stream_waves(MT) * 64) void seglinear_stream_kernel
         *reinterpret_cast<v4i*>(smem + plane + r * rowb + cc * 16) = nv;
       }
       *reinterpret_cast<v4i*>(smem + r * rowb + cc * 16) = v;
+    }
+  }
+  if (a.tok_steps) {                                               // dynamic per-token steps (host: S <= 8)
+    for (int i = threadIdx.x; i < MT * 16 * tb.S; i += NW * 64) {
+      const int r = i / tb.S, ks = i - r * tb.S;
+      const int rs = r < a.M ? r : a.M - 1;
+      tok[2 * i] = a.tok_steps[(size_t)rs * tb.S + ks];
+      tok[2 * i + 1] = a.tok_steps[((size_t)a.M + rs) * tb.S + ks];
     }
   }
   __syncthreads();   // the only workgroup barrier: slab visible (the compiler drains this thread's loads here, the
@@ -342,15 +352,22 @@ __global__ __launch_bounds__(stream_waves(MT) * 64) void seglinear_stream_kernel
             for (int r = 0; r < 4; ++r) cw[r] *= seg_scale_of(tb, ks, ncol + r);
           }
         }
-        const float sp = tb.s_pos[ks], sn = dl ? tb.s_neg[ks] : 0.0f;
+        const bool dyn = a.tok_steps != nullptr;
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
+        for (int mt = 0; mt < MT; ++mt) {
+          float sp = tb.s_pos[ks], sn = dl ? tb.s_neg[ks] : 0.0f;
+          if (dyn) {                                               // this lane's token row
+            const int ti = 2 * ((mt * 16 + mlane) * tb.S + ks);
+            sp = tok[ti];
+            sn = dl ? tok[ti + 1] : 0.0f;
+          }
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
             float t = (cw[r] * sp) * (float)accp[mt][r];
             if (DUAL) t += (cw[r] * sn) * (float)accn[mt][r];
             fsum[mt][r] += t;
           }
+        }
       }
     }
     // ---- group done: bias, cast, store -------------------------------------------------------------------------

@@ -76,6 +76,7 @@ struct GemmArgs {
   int M, K, N;
   int tiles_m, tiles_n, group_m;   // MFMA kernel: tile grid and panel height of the tile order
   int num_wg;                      // MFMA kernel: persistent workgroups launched
+  const float* tok_steps;          // dynamic per-token steps [2][M][S] (s_pos, then s_neg) or nullptr: the layer's static steps
 };
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }

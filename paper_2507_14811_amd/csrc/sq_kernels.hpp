@@ -29,6 +29,10 @@ hipError_t launch_quantize_weight_block(const void* w, bool w_is_bf16, int8_t* w
 hipError_t launch_calibrate_act(const void* x, bool x_is_bf16, int M, int K, const ActTable& tb, float* amax, float* steps,
                                 bool accumulate, hipStream_t st);
 
+// dynamic per-token activation steps: tok_steps [2][M][S]
+hipError_t launch_quantize_act_dynamic(const void* x, bool x_is_bf16, int8_t* xq, float* tok_steps, int M, int K,
+                                       const ActTable& tb, hipStream_t st);
+
 // 4-bit weights, packed two per byte (K and K-segment boundaries multiples of 128)
 hipError_t launch_quantize_weight_w4(const void* w, bool w_is_bf16, uint8_t* wq4, float* wscale, int N, int K,
                                      const KsegTable& tb, hipStream_t st);

@@ -717,3 +717,63 @@ def test_w4_rejects_unaligned_layouts():
     lay2 = sq.Layer(4, 256, 16, [0, 64, 256], [0, 16], [1, 0], [0.01, 0.01], [0.01, 0.01])   # boundary at 64
     with pytest.raises(sq.SqError):
         sq.sq_seglinear_w4(lay2, t.view(torch.int8), t, f, None, f)
+
+
+# ----------------------------------------------------------------------------------------------------
+# dynamic per-token activation steps
+# ----------------------------------------------------------------------------------------------------
+DYNCASES = [
+    dict(M=16, K=1152, N=6912, kseg=[0, 1152], dual=[1], x_dtype="bf16"),
+    dict(M=5, K=256, N=70, kseg=[0, 128, 256], dual=[0, 1], x_dtype="f32", bias=True),
+    dict(M=40, K=512, N=200, kseg=[0, 384, 512], dual=[1, 1], nseg=[0, 64, 200], seg_scale=True, x_dtype="bf16"),
+    dict(M=100, K=256, N=96, kseg=[0, 256], dual=[1], x_dtype="bf16"),                      # M > 64: plain kernel
+    dict(M=7, K=100, N=33, kseg=[0, 37, 100], dual=[1, 0], x_dtype="f32", bits=(8,)),       # unaligned: plain kernel, 8-bit only
+]
+
+
+@pytest.mark.parametrize("case", DYNCASES)
+def test_seglinear_dynamic(oracle, case):
+    """Per-token steps: codes and steps bit-exact against the oracle, outputs within the fp32 tolerance, for 8-bit and
+    4-bit weights."""
+    import torch
+
+    g = _gpu()
+    M, K, N = case["M"], case["K"], case["N"]
+    nseg = case.get("nseg") or [0, N]
+    w = wl.random_layer(M, K, N, case["kseg"], nseg, case["dual"], seed=5 * M + K + N, x_dtype=case["x_dtype"], act="gelu",
+                        with_seg_scale=bool(case.get("seg_scale")), with_bias=bool(case.get("bias")))
+    w.x = (w.x * np.random.default_rng(M).uniform(0.1, 8.0, size=(M, 1))).astype(np.float32)   # tokens of different scale
+    if case["x_dtype"] == "bf16":
+        w.x = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(w.x))
+    gl = g.GpuLayer(w)
+    S = w.S
+    tok = torch.full((2, M, S), float("nan"), dtype=torch.float32, device=g.DEV)
+    sq.sq_quantize_act_dynamic(gl.layer, gl.x, gl.xq, tok)
+    torch.cuda.synchronize()
+    for bits in case.get("bits", (8, 4)):
+        r = oracle.seglinear_dynamic(w.x, w.w, w.kseg_off, w.nseg_off, w.dual, w.seg_scale, w.bias, wbits=bits)
+        xp, xn = g.split_codes(w, gl.xq.cpu().numpy())
+        assert np.array_equal(xp, r.xq_pos) and np.array_equal(xn, r.xq_neg)
+        assert np.array_equal(tok.cpu().numpy().view(np.uint32), r.tok_steps.view(np.uint32))
+        if bits == 8:
+            wq, _ = gl.quantize_weight()
+            wdev = gl.wq
+        else:
+            wdev = torch.empty((((N + 15) // 16) * 16 * (K // 2),), dtype=torch.uint8, device=g.DEV)
+            sq.sq_quantize_weight_w4(gl.layer, gl.wt, wdev, gl.wscale)
+        ymax = float(np.abs(r.y32).max())
+        for forced in (-1, 0):
+            sq.sq_tuning_set("force_path", forced)
+            try:
+                y = torch.full((M, N), float("nan"), dtype=torch.float32, device=g.DEV)
+                sq.sq_seglinear_dynamic(gl.layer, gl.xq, tok, wdev, bits, gl.wscale, gl.bias, y)
+                torch.cuda.synchronize()
+                y = y.cpu().numpy()
+                assert not np.isnan(y).any()
+                assert float(np.abs(y.astype(np.float64) - r.y32.astype(np.float64)).max()) <= 1e-5 * ymax, (bits, forced)
+                yb = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=g.DEV)
+                sq.sq_seglinear_dynamic(gl.layer, gl.xq, tok, wdev, bits, gl.wscale, gl.bias, yb)
+                torch.cuda.synchronize()
+                g.check_bf16_against(g.bf16_tensor_bits(yb), r.y32, wl.f32_to_bf16_bits(r.y32), 1e-5 * ymax)
+            finally:
+                sq.sq_tuning_set("force_path", -1)

@@ -121,6 +121,11 @@ def test_invalid_arguments_are_rejected_on_the_host(sq):
     assert lib.sq_seglinear_w4(C.byref(w4.c), FAKE, FAKE, FAKE, None, FAKE, 9, None) == INVALID
     assert lib.sq_seglinear_w4_debug_acc(C.byref(w4.c), FAKE, FAKE, None, FAKE, None) == INVALID
     assert lib.sq_quantize_weight_w4(C.byref(ok.c), FAKE, 0, FAKE, FAKE, None) in (UNSUPPORTED, INVALID) or ok.c.K % 128 == 0
+    assert lib.sq_quantize_act_dynamic(C.byref(ok.c), FAKE, 1, FAKE, None, None) == INVALID
+    assert lib.sq_quantize_act_dynamic(C.byref(ok.c), None, 1, FAKE, FAKE, None) == INVALID
+    assert lib.sq_seglinear_dynamic(C.byref(ok.c), FAKE, None, FAKE, 8, FAKE, None, FAKE, 0, None) == INVALID
+    assert lib.sq_seglinear_dynamic(C.byref(ok.c), FAKE, FAKE, FAKE, 5, FAKE, None, FAKE, 0, None) == INVALID
+    assert lib.sq_seglinear_dynamic(C.byref(_layer(sq, K=192, kseg_off=[0, 192]).c), FAKE, FAKE, FAKE, 4, FAKE, None, FAKE, 0, None) == UNSUPPORTED
     need = lib.sq_calibrate_workspace_bytes()
     assert 0 < need < (1 << 20)
     pct = lambda p, ws=FAKE, nbytes=need, x=FAKE: lib.sq_calibrate_act_percentile(C.byref(ok.c), x, 1, p, FAKE, FAKE, ws, nbytes, 0, None)
