@@ -275,7 +275,34 @@ def measure_grouped(layers=28, steps=50):
     e1.record()
     torch.cuda.synchronize()
     ms_single = e0.elapsed_time(e1) / (max(2, steps // 5) * nsets)
-    return {"layers": layers, "M": w.M, "K": w.K, "N": w.N, "ms_per_launch": round(ms, 5), "bytes": byt,
+
+    # Linear(SiLU(c)) from the raw conditioning input: activation + Q_dual inside the weight-stream kernel (one launch)
+    # against sq_quantize_act_fused followed by the grouped call (two launches)
+    def timed(fn):
+        for _ in range(5):
+            fn()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / (steps * nsets)
+
+    silu = [sq.SQ_ACT_SILU] * w.S
+
+    def one_launch():
+        for items in sets:
+            sq.sq_seglinear_grouped_fused(layer, x, silu, items)
+
+    def two_launches():
+        for items in sets:
+            sq.sq_quantize_act_fused(layer, x, silu, xq)
+            sq.sq_seglinear_grouped(layer, xq, items)
+
+    ms_one, ms_two = timed(one_launch), timed(two_launches)
+    return {"layers": layers, "silu_in_front": {"ms_one_launch_raw_input": round(ms_one, 5),
+                                                "ms_quantize_then_grouped": round(ms_two, 5)}, "M": w.M, "K": w.K, "N": w.N, "ms_per_launch": round(ms, 5), "bytes": byt,
             "gbs_from_hbm": round(byt / (ms * 1e-3) / 1e9, 1), "frac_hbm_peak": round(byt / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
             "ms_same_layers_one_call_each": round(ms_single, 5), "weight_sets_rotated": nsets}
 

@@ -210,6 +210,25 @@ sq_status sq_seglinear_grouped(const sq_layer* layer, const int8_t* xq, int32_t 
                                sq_dtype y_dt, void* stream);
 
 /*
+ * Skinny layers fed with raw activations: y = SegLinear(Q_dual(act(x))) in ONE launch.  The weight-stream kernel
+ * computes the activation in front of the layer (App. B: SiLU / GELU), the polarity split and both quantizers of
+ * Sec. 4.3.2 while it fills its on-chip copy of the input, so the code tensor X^ never exists in device memory and
+ * the separate quantize launch goes away.  Element by element the codes are those of sq_quantize_act_fused (the same
+ * fp32 operation sequence), hence y equals sq_seglinear(sq_quantize_act_fused(x)) bit for bit.
+ *   x     dev [M][K] of x_dt (fp32 / bf16), 16-byte aligned      in
+ *   act   host, int32 [S], SQ_ACT_* per K-segment, or NULL (no activation)   in
+ *   wq, wscale, bias, y   as for sq_seglinear
+ * sq_seglinear_grouped_fused is the same for L layers that share x (items as for sq_seglinear_grouped).
+ * Returns SQ_ERR_UNSUPPORTED where the weight-stream kernel does not apply (M > 64, or M > 32 for the grouped call, K
+ * or a K-segment boundary not a multiple of 128, misaligned pointers, M*K beyond the on-chip budget): run
+ * sq_quantize_act_fused + sq_seglinear instead.
+ */
+sq_status sq_seglinear_fused(const sq_layer* layer, const void* x, sq_dtype x_dt, const int32_t* act, const int8_t* wq,
+                             const float* wscale, const float* bias, void* y, sq_dtype y_dt, void* stream);
+sq_status sq_seglinear_grouped_fused(const sq_layer* layer, const void* x, sq_dtype x_dt, const int32_t* act, int32_t L,
+                                     const sq_group_item* items, sq_dtype y_dt, void* stream);
+
+/*
  * Parity instrument: runs the same main loop as sq_seglinear (same kernel selection) and stores the
  * raw int32 accumulators instead of the dequantized output.
  *   acc_pos, acc_neg  dev int32 [S][M][N];  acc_neg[ks] of a non-dual segment is written as 0.

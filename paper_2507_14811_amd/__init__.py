@@ -26,6 +26,8 @@ from .binding import (  # noqa: F401
     sq_seglinear_debug_acc,
     sq_seglinear_dynamic,
     sq_seglinear_grouped,
+    sq_seglinear_fused,
+    sq_seglinear_grouped_fused,
     sq_seglinear_w4,
     sq_seglinear_w4_debug_acc,
     sq_tuning_set,

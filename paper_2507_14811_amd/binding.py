@@ -25,7 +25,8 @@ EXPORTS = ("sq_quantize_weight", "sq_quantize_act", "sq_seglinear", "sq_seglinea
            "sq_quantize_weight_block", "sq_calibrate_act", "sq_calibrate_act_percentile",
            "sq_calibrate_workspace_bytes", "sq_quantize_act_fused",
            "sq_quantize_act_fused_workspace_bytes", "sq_quantize_weight_w4", "sq_seglinear_w4",
-           "sq_seglinear_w4_debug_acc", "sq_quantize_act_dynamic", "sq_seglinear_dynamic")
+           "sq_seglinear_w4_debug_acc", "sq_quantize_act_dynamic", "sq_seglinear_dynamic",
+           "sq_seglinear_fused", "sq_seglinear_grouped_fused")
 
 
 class SqError(RuntimeError):
@@ -94,6 +95,10 @@ def load_library() -> C.CDLL:
     lib.sq_calibrate_workspace_bytes.restype = C.c_size_t
     lib.sq_seglinear_grouped.argtypes = [lp, vp, i32, C.POINTER(sq_group_item), i32, vp]
     lib.sq_seglinear_grouped.restype = i32
+    lib.sq_seglinear_fused.argtypes = [lp, vp, i32, C.POINTER(C.c_int32), vp, vp, vp, vp, i32, vp]
+    lib.sq_seglinear_fused.restype = i32
+    lib.sq_seglinear_grouped_fused.argtypes = [lp, vp, i32, C.POINTER(C.c_int32), i32, C.POINTER(sq_group_item), i32, vp]
+    lib.sq_seglinear_grouped_fused.restype = i32
     lib.sq_probe_mfma.argtypes = [vp, C.c_size_t, i32, C.POINTER(C.c_double), vp]
     lib.sq_probe_mfma.restype = i32
     lib.sq_status_string.argtypes = [i32]
@@ -301,6 +306,29 @@ def sq_seglinear_grouped(layer: Layer, xq, items, stream=None) -> None:
     g = items if isinstance(items, GroupItems) else GroupItems(items)
     _check(load_library().sq_seglinear_grouped(C.byref(layer.c), _dptr(xq), g.n, g.arr, g.y_dt, _stream(stream)),
            "sq_seglinear_grouped")
+
+
+def _act_codes(layer: Layer, act):
+    if act is None:
+        return None
+    if len(act) != layer.c.S:
+        raise ValueError("one activation code per K-segment")
+    return (C.c_int32 * max(len(act), 1))(*[int(a) for a in act])
+
+
+def sq_seglinear_fused(layer: Layer, x, act, wq, wscale, bias, y, stream=None) -> None:
+    """y = SegLinear(Q_dual(act(x))) in one launch (skinny layers): x [M][K] fp32/bf16 raw activations, act: SQ_ACT_*
+    per K-segment or None."""
+    _check(load_library().sq_seglinear_fused(C.byref(layer.c), _dptr(x), _dt(x), _act_codes(layer, act), _dptr(wq),
+                                             _dptr(wscale), _dptr(bias), _dptr(y), _dt(y), _stream(stream)),
+           "sq_seglinear_fused")
+
+
+def sq_seglinear_grouped_fused(layer: Layer, x, act, items, stream=None) -> None:
+    """sq_seglinear_fused for L layers of one shape that share x; items as for sq_seglinear_grouped."""
+    g = items if isinstance(items, GroupItems) else GroupItems(items)
+    _check(load_library().sq_seglinear_grouped_fused(C.byref(layer.c), _dptr(x), _dt(x), _act_codes(layer, act), g.n,
+                                                     g.arr, g.y_dt, _stream(stream)), "sq_seglinear_grouped_fused")
 
 
 def sq_seglinear_debug_acc(layer: Layer, xq, wq, acc_pos, acc_neg, stream=None) -> None:

@@ -50,6 +50,12 @@ sq_status check_layer(const sq_layer* L, bool need_m, bool need_scales) {
   return SQ_OK;
 }
 
+// Reciprocal used by the fast path of round(x / s); NaN tells the kernel to always divide.
+float safe_inv(float s) {
+  if (!(s >= 1e-30f && s <= 1e30f)) return std::nanf("");
+  return 1.0f / s;
+}
+
 void fill_gemm_table(const sq_layer* L, sq::GemmTable& tb) {
   std::memset(&tb, 0, sizeof(tb));
   tb.S = L->S;
@@ -61,15 +67,11 @@ void fill_gemm_table(const sq_layer* L, sq::GemmTable& tb) {
     tb.seg_order[s] = s;
     tb.s_pos[s] = L->s_pos ? L->s_pos[s] : 1.0f;
     tb.s_neg[s] = (L->dual[s] && L->s_neg) ? L->s_neg[s] : 0.0f;
+    tb.inv_pos[s] = safe_inv(tb.s_pos[s]);
+    tb.inv_neg[s] = safe_inv(tb.s_neg[s]);
   }
   tb.has_seg_scale = L->seg_scale != nullptr;
   if (L->seg_scale) std::memcpy(tb.seg_scale, L->seg_scale, sizeof(float) * L->S * L->T);
-}
-
-// Reciprocal used by the fast path of round(x / s); NaN tells the kernel to always divide.
-float safe_inv(float s) {
-  if (!(s >= 1e-30f && s <= 1e30f)) return std::nanf("");
-  return 1.0f / s;
 }
 
 sq_status run_gemm(const sq_layer* L, const int8_t* xq, const int8_t* wq,
@@ -318,11 +320,43 @@ sq_status sq_seglinear(const sq_layer* layer, const int8_t* xq, const int8_t* wq
                   y_dt == SQ_BF16 ? sq::OUT_BF16 : sq::OUT_F32, stream);
 }
 
-sq_status sq_seglinear_grouped(const sq_layer* layer, const int8_t* xq, int32_t L, const sq_group_item* items,
-                               sq_dtype y_dt, void* stream) {
+sq_status sq_seglinear_fused(const sq_layer* layer, const void* x, sq_dtype x_dt, const int32_t* act, const int8_t* wq,
+                             const float* wscale, const float* bias, void* y, sq_dtype y_dt, void* stream) {
   sq_status st = check_layer(layer, true, true);
   if (st != SQ_OK) return st;
-  if (xq == nullptr || items == nullptr || L < 1) return SQ_ERR_INVALID_ARG;
+  if (x == nullptr || wq == nullptr || wscale == nullptr || y == nullptr) return SQ_ERR_INVALID_ARG;
+  if ((x_dt != SQ_F32 && x_dt != SQ_BF16) || (y_dt != SQ_F32 && y_dt != SQ_BF16)) return SQ_ERR_INVALID_ARG;
+  sq::GemmTable tb;
+  fill_gemm_table(layer, tb);
+  for (int s = 0; s < layer->S; ++s) {
+    tb.act[s] = SQ_ACT_NONE;
+    if (act != nullptr) {
+      if (act[s] != SQ_ACT_NONE && act[s] != SQ_ACT_SILU && act[s] != SQ_ACT_GELU) return SQ_ERR_INVALID_ARG;
+      tb.act[s] = act[s];
+    }
+  }
+  sq::GemmArgs a{};
+  a.wq = wq;
+  a.wscale = wscale;
+  a.bias = bias;
+  a.y = y;
+  a.M = layer->M;
+  a.K = layer->K;
+  a.N = layer->N;
+  a.x_raw = x;
+  a.x_raw_bf16 = x_dt == SQ_BF16 ? 1 : 0;
+  if (reinterpret_cast<uintptr_t>(x) % 16 != 0 || !sq::stream_supported(a, tb)) return SQ_ERR_UNSUPPORTED;
+  hipError_t e = sq::launch_seglinear_stream(a, tb, y_dt == SQ_BF16 ? sq::OUT_BF16 : sq::OUT_F32, sq::device_cus(),
+                                             reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
+static sq_status grouped_common(const sq_layer* layer, const int8_t* xq, const void* x_raw, sq_dtype x_dt, const int32_t* act,
+                                int32_t L, const sq_group_item* items, sq_dtype y_dt, void* stream) {
+  sq_status st = check_layer(layer, true, true);
+  if (st != SQ_OK) return st;
+  if ((xq == nullptr && x_raw == nullptr) || items == nullptr || L < 1) return SQ_ERR_INVALID_ARG;
+  if (x_raw != nullptr && x_dt != SQ_F32 && x_dt != SQ_BF16) return SQ_ERR_INVALID_ARG;
   if (y_dt != SQ_F32 && y_dt != SQ_BF16) return SQ_ERR_INVALID_ARG;
   if (L > SQ_MAX_GROUP || layer->seg_scale != nullptr) return SQ_ERR_UNSUPPORTED;
   sq::GroupTable gt;
@@ -341,9 +375,19 @@ sq_status sq_seglinear_grouped(const sq_layer* layer, const int8_t* xq, int32_t 
     tb.dual[s] = layer->dual[s] ? 1 : 0;
     tb.s_pos[s] = layer->s_pos[s];
     tb.s_neg[s] = layer->dual[s] ? layer->s_neg[s] : 0.0f;
+    tb.inv_pos[s] = safe_inv(tb.s_pos[s]);
+    tb.inv_neg[s] = safe_inv(tb.s_neg[s]);
+    tb.act[s] = SQ_ACT_NONE;
+    if (act != nullptr) {
+      if (act[s] != SQ_ACT_NONE && act[s] != SQ_ACT_SILU && act[s] != SQ_ACT_GELU) return SQ_ERR_INVALID_ARG;
+      tb.act[s] = act[s];
+    }
   }
   sq::GemmArgs a{};
   a.xq = xq;
+  a.x_raw = x_raw;
+  a.x_raw_bf16 = x_dt == SQ_BF16 ? 1 : 0;
+  if (x_raw != nullptr && reinterpret_cast<uintptr_t>(x_raw) % 16 != 0) return SQ_ERR_UNSUPPORTED;
   a.M = layer->M;
   a.K = layer->K;
   a.N = layer->N;
@@ -351,6 +395,18 @@ sq_status sq_seglinear_grouped(const sq_layer* layer, const int8_t* xq, int32_t 
   hipError_t e = sq::launch_seglinear_grouped(a, tb, gt, y_dt == SQ_BF16 ? sq::OUT_BF16 : sq::OUT_F32, sq::device_cus(),
                                               reinterpret_cast<hipStream_t>(stream));
   return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
+sq_status sq_seglinear_grouped(const sq_layer* layer, const int8_t* xq, int32_t L, const sq_group_item* items,
+                               sq_dtype y_dt, void* stream) {
+  if (xq == nullptr) return SQ_ERR_INVALID_ARG;
+  return grouped_common(layer, xq, nullptr, SQ_F32, nullptr, L, items, y_dt, stream);
+}
+
+sq_status sq_seglinear_grouped_fused(const sq_layer* layer, const void* x, sq_dtype x_dt, const int32_t* act, int32_t L,
+                                     const sq_group_item* items, sq_dtype y_dt, void* stream) {
+  if (x == nullptr) return SQ_ERR_INVALID_ARG;
+  return grouped_common(layer, nullptr, x, x_dt, act, L, items, y_dt, stream);
 }
 
 sq_status sq_seglinear_debug_acc(const sq_layer* layer, const int8_t* xq, const int8_t* wq, int32_t* acc_pos,

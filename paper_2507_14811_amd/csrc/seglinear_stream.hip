@@ -166,15 +166,110 @@ __global__ __launch_bounds__(stream_waves(MT) * 64) void seglinear_stream_kernel
       if (++ig < g_cnt) set_issue_group(ig);
     }
   };
+  // ---- raw activations (a.x_raw): the activation in front of the layer and Q_dual (Sec. 4.3.2) happen on the way into
+  // the slab, in items of four elements.  Every workgroup quantizes the whole of X for itself (M <= 64 rows).  Each
+  // thread's first RAWPRE items are requested before the ring is primed, with loads the compiler does not track, and
+  // waited for with a count that leaves the ring's direct loads in flight (vector memory loads complete in order), so
+  // that the latency of X, the latency of the first weights and the arithmetic overlap.
+  constexpr int RAWPRE = 5, NT = NW * 64;
+  constexpr int PRIME_LOADS = (RING - 1) * (W4 ? 1 : 2);           // direct loads of a fully primed ring
+  static_assert(PRIME_LOADS <= 63, "the wait count is a 6-bit field");
+  const int kq = a.K >> 2;                                         // items per row
+  const int nitem = a.x_raw ? a.M * kq : 0;
+  uint64_t raw2[RAWPRE];                                           // bf16 items: 8 bytes
+  v4i raw4[RAWPRE];                                                // fp32 items: 16 bytes
+#pragma unroll
+  for (int j = 0; j < RAWPRE; ++j) {
+    const int c = threadIdx.x + j * NT;
+    raw2[j] = 0;
+    raw4[j] = (v4i)(0);
+    if (c < nitem) {
+      if (a.x_raw_bf16)
+        asm volatile("global_load_dwordx2 %0, %1, off" : "=v"(raw2[j]) : "v"(reinterpret_cast<const uint16_t*>(a.x_raw) + (size_t)c * 4) : "memory");
+      else
+        asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(raw4[j]) : "v"(reinterpret_cast<const float*>(a.x_raw) + (size_t)c * 4) : "memory");
+    }
+  }
+
   if (g_cnt > 0) set_issue_group(0);
 #pragma unroll 1
   while (issued_steps < RING - 1 && issued_steps < total) issue_step();
+
+  if (a.x_raw) {
+#define SQ_RAW_OPERANDS "+v"(raw2[0]), "+v"(raw2[1]), "+v"(raw2[2]), "+v"(raw2[3]), "+v"(raw2[4]), \
+                        "+v"(raw4[0]), "+v"(raw4[1]), "+v"(raw4[2]), "+v"(raw4[3]), "+v"(raw4[4])
+    static_assert(RAWPRE == 5, "operand list above");
+    // One statement carries the registers (a second one on another path would make the compiler merge the two sets
+    // with copies, and a copy placed before the wait reads a register the load has not written yet).
+    if (issued_steps != RING - 1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // ring not fully primed
+    asm volatile("s_waitcnt vmcnt(%[cnt])" : SQ_RAW_OPERANDS : [cnt] "n"(PRIME_LOADS) : "memory");
+#undef SQ_RAW_OPERANDS
+  }
 
   // ---- X^ slab: [16*MT rows][K + 16] bytes, rows beyond M repeat the last row (masked at the store) ----------
   // PS: a second plane of the same shape behind the first; plane 0 holds X^_+ (the whole code in a single-scale
   // K-segment), plane 1 holds X^_- (zero there): the polarity separation of Sec. 4.3.2 done once per workgroup.
   const int plane = MT * 16 * (a.K + 16);
-  {
+  if (a.x_raw != nullptr) {
+    const int rowb = a.K + 16;
+    auto quantize_item = [&](const int c, const uint32_t (&w)[4]) __attribute__((always_inline)) {
+      const int r = c / kq, col = (c - r * kq) << 2;
+      float sp = 1.0f, sn = 1.0f, ip = 1.0f, in = 1.0f;
+      bool dl = false;
+      int acode = SQ_ACT_NONE;
+      for (int sg = 0; sg < tb.S; ++sg)
+        if (col >= tb.kseg_off[sg]) {
+          sp = tb.s_pos[sg]; sn = tb.s_neg[sg]; ip = tb.inv_pos[sg]; in = tb.inv_neg[sg]; dl = tb.dual[sg] != 0; acode = tb.act[sg];
+        }
+      float xv[4];
+      if (a.x_raw_bf16) {
+        xv[0] = __uint_as_float(w[0] << 16); xv[1] = __uint_as_float(w[0] & 0xFFFF0000u);
+        xv[2] = __uint_as_float(w[1] << 16); xv[3] = __uint_as_float(w[1] & 0xFFFF0000u);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) xv[i] = __uint_as_float(w[i]);
+      }
+      uint32_t pk = 0;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float av = activate(acode, xv[i]);
+        const bool ng = dl && (av < 0.0f);                 // X_- = min(X, 0) takes the s_- branch of Q_dual
+        const int code = clip_code(round_quotient(av, ng ? sn : sp, ng ? in : ip));
+        pk |= (uint32_t)(code & 0xFF) << (8 * i);
+      }
+      int pos = (int)pk, neg = 0;
+      if (PS) {
+        if (dl) split_polarity((int)pk, pos, neg);
+        *reinterpret_cast<int*>(smem + plane + r * rowb + col) = neg;
+      }
+      *reinterpret_cast<int*>(smem + r * rowb + col) = pos;
+    };
+#pragma unroll
+    for (int j = 0; j < RAWPRE; ++j) {
+      const int c = threadIdx.x + j * NT;
+      uint32_t w[4] = {(uint32_t)raw4[j][0], (uint32_t)raw4[j][1], (uint32_t)raw4[j][2], (uint32_t)raw4[j][3]};
+      if (a.x_raw_bf16) { w[0] = (uint32_t)raw2[j]; w[1] = (uint32_t)(raw2[j] >> 32); }
+      if (c < nitem) quantize_item(c, w);
+    }
+#pragma unroll 1
+    for (int c = threadIdx.x + RAWPRE * NT; c < nitem; c += NT) {  // larger X: plain loads (each wait drains the ring)
+      uint32_t w[4];
+      if (a.x_raw_bf16) {
+        const uint2 t = *reinterpret_cast<const uint2*>(reinterpret_cast<const uint16_t*>(a.x_raw) + (size_t)c * 4);
+        w[0] = t.x; w[1] = t.y; w[2] = 0; w[3] = 0;
+      } else {
+        const uint4 t = *reinterpret_cast<const uint4*>(reinterpret_cast<const float*>(a.x_raw) + (size_t)c * 4);
+        w[0] = t.x; w[1] = t.y; w[2] = t.z; w[3] = t.w;
+      }
+      quantize_item(c, w);
+    }
+    const int cpr = a.K >> 4;                                      // rows beyond M: zero codes (masked at the store)
+    for (int c = a.M * cpr + threadIdx.x; c < MT * 16 * cpr; c += NT) {
+      const int r = c / cpr, cc = c - r * cpr;
+      *reinterpret_cast<v4i*>(smem + r * rowb + cc * 16) = (v4i)(0);
+      if (PS) *reinterpret_cast<v4i*>(smem + plane + r * rowb + cc * 16) = (v4i)(0);
+    }
+  } else {
     const int rowb = a.K + 16, cpr = a.K >> 4;                     // 16-byte chunks per row
     const int nchunk = MT * 16 * cpr;
     for (int c = threadIdx.x; c < nchunk; c += NW * 64) {

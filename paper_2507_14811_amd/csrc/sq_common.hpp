@@ -42,6 +42,9 @@ struct GemmTable {                     // for the SegLinear GEMM kernels
   int dual[SQ_MAX_SEGMENTS];
   int seg_order[SQ_MAX_SEGMENTS];      // order in which the MFMA kernel visits the K-segments
   float seg_scale[SQ_MAX_SEG_SCALE];   // [ks][ns], valid when has_seg_scale
+  int act[SQ_MAX_SEGMENTS];            // weight-stream kernel fed with raw activations: SQ_ACT_* per K-segment
+  float inv_pos[SQ_MAX_SEGMENTS];      //   and the reciprocals of the steps for round_quotient (NaN: always divide)
+  float inv_neg[SQ_MAX_SEGMENTS];
 };
 
 // Slim segment table + per-layer pointers of the grouped skinny call (several layers that share X^ in one launch).
@@ -51,6 +54,9 @@ struct GroupSegTable {
   float s_pos[SQ_MAX_SEGMENTS];
   float s_neg[SQ_MAX_SEGMENTS];
   int dual[SQ_MAX_SEGMENTS];
+  int act[SQ_MAX_SEGMENTS];                   // raw activations: SQ_ACT_* per K-segment
+  float inv_pos[SQ_MAX_SEGMENTS];             //   and the reciprocals of the steps for round_quotient
+  float inv_neg[SQ_MAX_SEGMENTS];
   static constexpr int has_seg_scale = 0;     // the grouped call takes no per-block multiplier
 };
 struct GroupItem {
@@ -77,6 +83,8 @@ struct GemmArgs {
   int tiles_m, tiles_n, group_m;   // MFMA kernel: tile grid and panel height of the tile order
   int num_wg;                      // MFMA kernel: persistent workgroups launched
   const float* tok_steps;          // dynamic per-token steps [2][M][S] (s_pos, then s_neg) or nullptr: the layer's static steps
+  const void* x_raw;               // weight-stream kernel: activations [M][K] (bf16 or fp32) to be quantized (after the
+  int x_raw_bf16;                  // table's activation) into the LDS slab by the kernel itself; nullptr: xq holds codes
 };
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }

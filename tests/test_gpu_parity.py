@@ -777,3 +777,101 @@ def test_seglinear_dynamic(oracle, case):
                 g.check_bf16_against(g.bf16_tensor_bits(yb), r.y32, wl.f32_to_bf16_bits(r.y32), 1e-5 * ymax)
             finally:
                 sq.sq_tuning_set("force_path", -1)
+
+
+FUSEDGEMM = [
+    dict(M=16, K=1152, N=6912, kseg=[0, 1152], dual=[1], act=[1], h_dtype="bf16", L=3),       # adaLN: Linear(SiLU(c))
+    dict(M=5, K=256, N=33, kseg=[0, 128, 256], dual=[1, 0], act=[2, 0], h_dtype="f32", L=2),    # ragged N, mixed segments
+    dict(M=33, K=384, N=100, kseg=[0, 384], dual=[0], act=[2], h_dtype="bf16", L=0),           # three row tiles: single only
+    dict(M=1, K=128, N=16, kseg=[0, 128], dual=[1], act=[0], h_dtype="f32", L=1),               # no activation
+    dict(M=32, K=640, N=4240, kseg=[0, 256, 640], dual=[1, 1], act=[1, 2], h_dtype="bf16", L=9),
+    dict(M=64, K=1152, N=520, kseg=[0, 1152], dual=[1], act=[1], h_dtype="f32", L=0),          # four row tiles
+]
+
+
+@pytest.mark.parametrize("case", FUSEDGEMM)
+def test_seglinear_fused(oracle, case):
+    """Raw activations in, y out, one launch: activation, polarity split and quantizers inside the weight-stream kernel.
+    Against the oracle (activation -> Q_dual -> SegLinear) to the fp32 bar, and bit for bit against the two-launch path."""
+    import torch
+
+    g = _gpu()
+    M, K, N = case["M"], case["K"], case["N"]
+    rng = np.random.default_rng(M * 7 + K + N)
+    h = (rng.standard_normal((M, K)) * 3.0).astype(np.float32)
+    h[0, :4] = [0.0, -0.0, 95.0, -95.0]
+    if case["h_dtype"] == "bf16":
+        h = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(h))
+        hd = torch.from_numpy(wl.f32_to_bf16_bits(h).view(np.int16)).view(torch.bfloat16).to(g.DEV)
+    else:
+        hd = torch.from_numpy(h).to(g.DEV)
+    a = oracle.activation(h, case["kseg"], case["act"])
+    sp, sn, _, _ = oracle.calibrate_act(a, case["kseg"], case["dual"])
+    layer = sq.Layer(M, K, N, case["kseg"], [0, N], case["dual"], sp, sn)
+    S = len(case["dual"])
+
+    def make(l):
+        w = (rng.standard_normal((N, K)) * (0.02 * (1 + l % 3))).astype(np.float32)
+        b = None if l % 2 else rng.standard_normal(N).astype(np.float32)
+        wq = torch.empty((N, K), dtype=torch.int8, device=g.DEV)
+        ws = torch.empty((S, N), dtype=torch.float32, device=g.DEV)
+        sq.sq_quantize_weight(layer, torch.from_numpy(w).to(g.DEV), wq, ws)
+        return w, b, wq, ws, None if b is None else torch.from_numpy(b).to(g.DEV)
+
+    def compare(y, w, b, what):
+        r = oracle.seglinear(a, w, case["kseg"], [0, N], case["dual"], sp, sn, None, b)
+        ymax = float(np.abs(r.y32).max())
+        yh = y.cpu().numpy()
+        assert not np.isnan(yh).any(), what
+        err = float(np.abs(yh.astype(np.float64) - r.y32.astype(np.float64)).max())
+        assert err <= RTOL * ymax, f"{what}: fp32 output error {err} > {RTOL} * {ymax}"
+
+    w, b, wq, ws, bd = make(0)
+    y = torch.full((M, N), float("nan"), dtype=torch.float32, device=g.DEV)
+    sq.sq_seglinear_fused(layer, hd, case["act"], wq, ws, bd, y)
+    torch.cuda.synchronize()
+    compare(y, w, b, "single")
+    # the two-launch path gives the same bits (same codes, same kernel)
+    xq = torch.empty((M, K), dtype=torch.int8, device=g.DEV)
+    sq.sq_quantize_act_fused(layer, hd, case["act"], xq)
+    y2 = torch.full((M, N), float("nan"), dtype=torch.float32, device=g.DEV)
+    sq.sq_tuning_set("force_path", 3)
+    sq.sq_seglinear(layer, xq, wq, ws, bd, y2)
+    sq.sq_tuning_set("force_path", -1)
+    torch.cuda.synchronize()
+    assert torch.equal(y.view(torch.int32), y2.view(torch.int32))
+    # bf16 output
+    yb = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=g.DEV)
+    sq.sq_seglinear_fused(layer, hd, case["act"], wq, ws, bd, yb)
+    torch.cuda.synchronize()
+    r = oracle.seglinear(a, w, case["kseg"], [0, N], case["dual"], sp, sn, None, b)
+    g.check_bf16_against(g.bf16_tensor_bits(yb), r.y32, r.y_bf16_bits, RTOL * float(np.abs(r.y32).max()))
+    if case["L"] == 0:
+        with pytest.raises(sq.SqError) as e:                 # the grouped call stops at 32 tokens
+            sq.sq_seglinear_grouped_fused(layer, hd, case["act"], [(wq, ws, bd, y)])
+        assert e.value.status == 2
+        return
+    items, hosts = [], []
+    for l in range(case["L"]):
+        w, b, wq, ws, bd = make(l + 1)
+        items.append((wq, ws, bd, torch.full((M, N), float("nan"), dtype=torch.float32, device=g.DEV)))
+        hosts.append((w, b))
+    sq.sq_seglinear_grouped_fused(layer, hd, case["act"], items)
+    torch.cuda.synchronize()
+    for l, (w, b) in enumerate(hosts):
+        compare(items[l][3], w, b, f"grouped layer {l}")
+
+
+def test_seglinear_fused_rejects_what_the_stream_kernel_cannot_run():
+    import torch
+
+    g = _gpu()
+    for (M, K, kseg) in [(65, 256, [0, 256]), (8, 192, [0, 192]), (8, 256, [0, 64, 256])]:
+        layer = sq.Layer(M, K, 64, kseg, [0, 64], [1] * (len(kseg) - 1), [0.1] * (len(kseg) - 1), [0.1] * (len(kseg) - 1))
+        x = torch.zeros((M, K), dtype=torch.float32, device=g.DEV)
+        wq = torch.zeros((64, K), dtype=torch.int8, device=g.DEV)
+        ws = torch.ones((len(kseg) - 1, 64), dtype=torch.float32, device=g.DEV)
+        y = torch.empty((M, 64), dtype=torch.float32, device=g.DEV)
+        with pytest.raises(sq.SqError) as e:
+            sq.sq_seglinear_fused(layer, x, None, wq, ws, None, y)
+        assert e.value.status == 2

@@ -141,6 +141,20 @@ def test_invalid_arguments_are_rejected_on_the_host(sq):
     assert lib.sq_seglinear_grouped(C.byref(ok.c), FAKE, 1, bad, 0, None) == INVALID
     assert lib.sq_seglinear_grouped(C.byref(_layer(sq, seg_scale=[[1.0]]).c), FAKE, 1, one, 0, None) == UNSUPPORTED
     assert lib.sq_seglinear_grouped(C.byref(ok.c), FAKE, 1, one, 7, None) == INVALID
+    # raw-activation entry points: NULL input, unknown dtype, unknown activation code, shapes the stream kernel cannot run
+    codes = lambda *a: (C.c_int32 * len(a))(*a)
+    assert lib.sq_seglinear_fused(C.byref(ok.c), None, 1, None, FAKE, FAKE, None, FAKE, 0, None) == INVALID
+    assert lib.sq_seglinear_fused(C.byref(ok.c), FAKE, 5, None, FAKE, FAKE, None, FAKE, 0, None) == INVALID
+    assert lib.sq_seglinear_fused(C.byref(ok.c), FAKE, 1, codes(3), FAKE, FAKE, None, FAKE, 0, None) == INVALID
+    assert lib.sq_seglinear_fused(C.byref(ok.c), FAKE, 1, codes(1), FAKE, None, None, FAKE, 0, None) == INVALID
+    assert lib.sq_seglinear_fused(C.byref(_layer(sq, K=192, kseg_off=[0, 192]).c), FAKE, 1, codes(1), FAKE, FAKE, None, FAKE, 0, None) == UNSUPPORTED
+    assert lib.sq_seglinear_fused(C.byref(_layer(sq, M=65).c), FAKE, 1, codes(1), FAKE, FAKE, None, FAKE, 0, None) == UNSUPPORTED
+    assert lib.sq_seglinear_fused(C.byref(ok.c), C.c_void_p(0x1004), 0, None, FAKE, FAKE, None, FAKE, 0, None) == UNSUPPORTED
+    assert lib.sq_seglinear_grouped_fused(C.byref(ok.c), None, 1, None, 1, one, 0, None) == INVALID
+    assert lib.sq_seglinear_grouped_fused(C.byref(ok.c), FAKE, 7, None, 1, one, 0, None) == INVALID
+    assert lib.sq_seglinear_grouped_fused(C.byref(ok.c), FAKE, 1, codes(-1), 1, one, 0, None) == INVALID
+    assert lib.sq_seglinear_grouped_fused(C.byref(ok.c), FAKE, 1, None, 65, one, 0, None) == UNSUPPORTED
+    assert lib.sq_seglinear_grouped_fused(C.byref(_layer(sq, M=40).c), FAKE, 1, None, 1, one, 0, None) == UNSUPPORTED
 
 
 def test_missing_library_fails_loudly(monkeypatch, sq):
