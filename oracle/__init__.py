@@ -20,6 +20,8 @@ from .segquant_oracle import (  # noqa: F401
     num_threads,
     quantize_act,
     quantize_act_dynamic,
+    geglu,
+    quantize_act_geglu,
     quantize_act_fused,
     quantize_weight,
     quantize_weight_block,

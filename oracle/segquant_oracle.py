@@ -202,6 +202,24 @@ def quantize_act_fused(h: np.ndarray, kseg_off, dual, act, s_pos, s_neg):
     return xp, xn
 
 
+def geglu(h: np.ndarray) -> np.ndarray:
+    """GEGLU in front of a DualScale layer (App. B names it next to SiLU and GELU): h fp32 [M][2K] = [value | gate]
+    -> value * GELU(gate), fp32 [M][K].  GELU is the bit-specified tanh form of `activation`; the product is one
+    IEEE fp32 multiplication (round to nearest even)."""
+    h = _f32(h)
+    M, K2 = h.shape
+    if K2 % 2:
+        raise ValueError("GEGLU input has an even number of columns")
+    K = K2 // 2
+    g = activation(np.ascontiguousarray(h[:, K:]), [0, K], [ACT_GELU])
+    return (np.ascontiguousarray(h[:, :K]) * g).astype(np.float32)
+
+
+def quantize_act_geglu(h: np.ndarray, kseg_off, dual, s_pos, s_neg):
+    """h fp32 [M][2K] -> (xq_pos, xq_neg) int8 [M][K] of Q_dual(GEGLU(h)); the K-segments are those of the output."""
+    return quantize_act(geglu(h), kseg_off, dual, s_pos, s_neg)
+
+
 def int_gemm(xq_pos, xq_neg, wq, kseg_off, dual, rows=None):
     """-> (acc_pos, acc_neg) int32 [S][nrows][N]; rows = subset of token rows or None (all)."""
     xq_pos = np.ascontiguousarray(xq_pos, dtype=np.int8)

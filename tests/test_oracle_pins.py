@@ -666,3 +666,46 @@ def test_dynamic_per_token_steps(oracle):
     stat = oracle.seglinear(x, w, kseg, [0, 10], dual, g_sp, g_sn)
     small = int(np.argmin(np.abs(x).max(axis=1)))
     assert np.abs(r.y64[small] - ref[small]).max() < np.abs(stat.y64[small] - ref[small]).max()
+
+
+def test_geglu_against_closed_form_and_landmarks(oracle):
+    """GEGLU (App. B lists it with SiLU and GELU): value * GELU(gate) with [value | gate] the two halves of a row.
+    Closed form in fp64, torch's own routines, which half is gated, exact landmarks, and the composed quantizer."""
+    import torch
+
+    rng = np.random.default_rng(77)
+    M, K = 9, 40
+    h = (rng.standard_normal((M, 2 * K)) * 2.5).astype(np.float32)
+    h[0, :6] = [2.0, -3.0, 0.5, 7.0, -1.0, 4.0]              # values
+    h[0, K:K + 6] = [0.0, -0.0, 40.0, -40.0, 35.0, 1.0]      # their gates
+    out = oracle.geglu(h)
+    assert out.shape == (M, K) and out.dtype == np.float32
+    v, g = h[:, :K].astype(np.float64), h[:, K:].astype(np.float64)
+    u = np.sqrt(2.0 / np.pi) * (g + 0.044715 * g ** 3)
+    with np.errstate(over="ignore"):
+        ref = v * (g / (1.0 + np.exp(-2.0 * u)))
+    tref = (torch.from_numpy(v) * torch.nn.functional.gelu(torch.from_numpy(g), approximate="tanh")).numpy()
+    assert np.allclose(ref, tref, rtol=0, atol=1e-12 * (1 + np.abs(ref).max()))
+    cond = np.minimum(np.abs(2.0 * u), 90.0)
+    tol = (7e-7 + 2e-7 * cond) * np.abs(ref) + 1e-30          # the GELU's few roundings plus one product
+    assert np.all(np.abs(out - ref) <= tol)
+    # landmarks: GELU(0) = 0, GELU(g) = g for large g, GELU(g) = -0 for very negative g
+    assert out[0, 0] == 0.0 and out[0, 1] == 0.0
+    assert out[0, 2] == np.float32(0.5) * np.float32(40.0) and out[0, 4] == np.float32(-35.0)
+    assert out[0, 3] == 0.0
+    # which half is gated: swapping the halves is a different function (value * GELU(gate) is not symmetric)
+    swapped = oracle.geglu(np.concatenate([h[:, K:], h[:, :K]], axis=1))
+    assert not np.allclose(swapped, out, atol=1e-3)
+    assert swapped[0, 5] == np.float32(1.0) * oracle.activation(np.array([[4.0]], np.float32), [0, 1], [oracle.ACT_GELU])[0, 0]
+    # the product is a single fp32 rounding of the exact product of the two fp32 factors
+    gl = oracle.activation(np.ascontiguousarray(h[:, K:]), [0, K], [oracle.ACT_GELU])
+    exact = h[:, :K].astype(np.float64) * gl.astype(np.float64)
+    assert np.array_equal(out, exact.astype(np.float32))
+    # composed quantizer: the codes are those of the plain quantizer applied to GEGLU(h), K-segments over the output
+    kseg, dual = [0, 16, K], [1, 0]
+    sp, sn, _, _ = oracle.calibrate_act(out, kseg, dual)
+    xp, xn = oracle.quantize_act_geglu(h, kseg, dual, sp, sn)
+    rp, rn = oracle.quantize_act(out, kseg, dual, sp, sn)
+    assert np.array_equal(xp, rp) and np.array_equal(xn, rn) and xp.max() == 127 and xn[:, :16].min() == -127
+    with pytest.raises(ValueError):
+        oracle.geglu(np.zeros((2, 5), np.float32))
