@@ -307,6 +307,26 @@ def measure_grouped(layers=28, steps=50):
             "ms_same_layers_one_call_each": round(ms_single, 5), "weight_sets_rotated": nsets}
 
 
+def measure_geglu(M=4096, K=5120, steps=20):
+    """GEGLU in front of the quantizer at the shape of a GEGLU feed-forward (inner width 4 x 1280, a 64 x 64 latent's
+    tokens): h [M][2K] bf16 -> codes [M][K]."""
+    import torch
+
+    import paper_2507_14811_amd as sq
+
+    gen = torch.Generator(device="cuda:0").manual_seed(5)
+    h = (torch.randn((M, 2 * K), device="cuda:0", generator=gen) * 1.5).to(torch.bfloat16)
+    layer = sq.Layer(M, K, 16, [0, K], [0, 16], [1], [4.0 / 127], [0.25 / 127])
+    xq = torch.empty((M, K), dtype=torch.int8, device="cuda:0")
+    sq.sq_quantize_act_geglu(layer, h, xq)
+    torch.cuda.synchronize()
+    ms = float(np.median(_time_events(lambda: sq.sq_quantize_act_geglu(layer, h, xq), steps)))
+    byt = M * K * 5
+    return {"M": M, "K": K, "ms_per_launch": round(ms, 5), "bytes": byt, "achieved": round(byt / (ms * 1e-3) / 1e9, 1),
+            "unit": "GB/s", "frac_hbm_peak": round(byt / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "note": "bound by the gate's fp32 arithmetic (bit-specified GELU), not by HBM"}
+
+
 def measure_w4(steps=40):
     """The stacked modulation layer (cfg3x28) with 4-bit packed weights: one pass over half the weight bytes.  Weight
     sets rotated so the stream comes from HBM."""
@@ -465,6 +485,7 @@ def main():
     ceilings = measured_ceilings(head.pop("xq_codes"))
     grouped = measure_grouped() if "cfg3" in args.others.split(",") else None
     w4 = measure_w4() if "cfg3x28" in args.others.split(",") else None
+    geglu = measure_geglu()
     others = {}
     for name in [n for n in args.others.split(",") if n and n != args.config]:
         sq.sq_tuning_set("gemm_variant", -1)
@@ -524,6 +545,7 @@ def main():
                                "unit": "GB/s", "frac": round(head["quant_bytes"] / (head["ms_quant_fused_lut"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                                "bytes": head["quant_bytes"],
                                "ms_per_launch_arithmetic_path": round(head["ms_quant_fused"], 5)},
+        "quantize_act_geglu": geglu,
         "quantize_weight_ms": round(head["ms_quantize_weight"], 5),
         "quantize_weight_block_ms": round(head["ms_quantize_weight_block"], 5),
         "calibrate_act": {"bound": "hbm", "ms_per_call": round(head["ms_calibrate"], 5), "achieved": round(head["calib_gbs"], 1),

@@ -171,6 +171,18 @@ sq_status sq_quantize_act_fused(const sq_layer* layer, const void* h, sq_dtype h
                                 void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * GEGLU in front of the quantizer (App. B names GEGLU with SiLU and GELU as the polarity-sensitive activations):
+ * the producing projection's output h holds [value | gate] side by side in every row, and
+ *   xq[m][k] = Q_dual( value[m][k] * GELU(gate[m][k]) ),   value = h[m][k], gate = h[m][K + k],
+ * with the GELU of sq_quantize_act_fused (same fp32 operation sequence), the product one fp32 multiplication
+ * (round to nearest even), and the quantizers of sq_quantize_act.  layer->K and the K-segments are those of the
+ * OUTPUT (the consuming layer's input features).
+ *   h    dev [M][2K] of h_dt (fp32 / bf16)      in
+ *   xq   dev int8 [M][K]                        out
+ */
+sq_status sq_quantize_act_geglu(const sq_layer* layer, const void* h, sq_dtype h_dt, int8_t* xq, void* stream);
+
+/*
  * Dual-path integer GEMM with per-K-segment accumulators and the fused dequant epilogue
  * (Sec. 4.2.2 items 1-2 combined with the last display of Sec. 4.3.2):
  *   acc_+[ks][m][n] = sum_{k in ks} X^_+[m][k] wq[n][k]              (int32, exact)

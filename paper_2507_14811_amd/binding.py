@@ -26,7 +26,7 @@ EXPORTS = ("sq_quantize_weight", "sq_quantize_act", "sq_seglinear", "sq_seglinea
            "sq_calibrate_workspace_bytes", "sq_quantize_act_fused",
            "sq_quantize_act_fused_workspace_bytes", "sq_quantize_weight_w4", "sq_seglinear_w4",
            "sq_seglinear_w4_debug_acc", "sq_quantize_act_dynamic", "sq_seglinear_dynamic",
-           "sq_seglinear_fused", "sq_seglinear_grouped_fused")
+           "sq_seglinear_fused", "sq_seglinear_grouped_fused", "sq_quantize_act_geglu")
 
 
 class SqError(RuntimeError):
@@ -95,6 +95,8 @@ def load_library() -> C.CDLL:
     lib.sq_calibrate_workspace_bytes.restype = C.c_size_t
     lib.sq_seglinear_grouped.argtypes = [lp, vp, i32, C.POINTER(sq_group_item), i32, vp]
     lib.sq_seglinear_grouped.restype = i32
+    lib.sq_quantize_act_geglu.argtypes = [lp, vp, i32, vp, vp]
+    lib.sq_quantize_act_geglu.restype = i32
     lib.sq_seglinear_fused.argtypes = [lp, vp, i32, C.POINTER(C.c_int32), vp, vp, vp, vp, i32, vp]
     lib.sq_seglinear_fused.restype = i32
     lib.sq_seglinear_grouped_fused.argtypes = [lp, vp, i32, C.POINTER(C.c_int32), i32, C.POINTER(sq_group_item), i32, vp]
@@ -246,6 +248,12 @@ def sq_quantize_act_fused(layer: Layer, h, act, xq, workspace=None, stream=None)
     nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load_library().sq_quantize_act_fused(C.byref(layer.c), _dptr(h), _dt(h), codes, _dptr(xq), _dptr(workspace),
                                                 nbytes, _stream(stream)), "sq_quantize_act_fused")
+
+
+def sq_quantize_act_geglu(layer: Layer, h, xq, stream=None) -> None:
+    """xq [M][K] = Q_dual(value * GELU(gate)): h [M][2K] fp32/bf16 = [value | gate]; the layer's K-segments are those of xq."""
+    _check(load_library().sq_quantize_act_geglu(C.byref(layer.c), _dptr(h), _dt(h), _dptr(xq), _stream(stream)),
+           "sq_quantize_act_geglu")
 
 
 def sq_seglinear(layer: Layer, xq, wq, wscale, bias, y, stream=None) -> None:

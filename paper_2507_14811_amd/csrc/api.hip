@@ -259,7 +259,7 @@ sq_status sq_calibrate_act_percentile(const sq_layer* layer, const void* x, sq_d
 }
 
 static sq_status quantize_act_common(const sq_layer* layer, const void* x, sq_dtype x_dt, const int32_t* act, int8_t* xq,
-                                     void* workspace, size_t workspace_bytes, void* stream) {
+                                     void* workspace, size_t workspace_bytes, void* stream, bool geglu = false) {
   sq_status st = check_layer(layer, true, true);
   if (st != SQ_OK) return st;
   if (x == nullptr || xq == nullptr) return SQ_ERR_INVALID_ARG;
@@ -282,7 +282,9 @@ static sq_status quantize_act_common(const sq_layer* layer, const void* x, sq_dt
   }
   hipStream_t hs = reinterpret_cast<hipStream_t>(stream);
   hipError_t e;
-  if (workspace != nullptr) {
+  if (geglu) {
+    e = sq::launch_quantize_act_geglu(x, x_dt == SQ_BF16, xq, layer->M, layer->K, tb, sq::device_cus(), hs);
+  } else if (workspace != nullptr) {
     if (workspace_bytes < sq::quantize_act_fused_workspace_bytes(layer->S) || reinterpret_cast<uintptr_t>(workspace) % 16 != 0)
       return SQ_ERR_INVALID_ARG;
     if (sq::quantize_act_lut_usable(x, x_dt == SQ_BF16, xq, layer->K, tb))
@@ -308,6 +310,10 @@ sq_status sq_quantize_act_fused(const sq_layer* layer, const void* h, sq_dtype h
                                 void* workspace, size_t workspace_bytes, void* stream) {
   if (act == nullptr) return SQ_ERR_INVALID_ARG;
   return quantize_act_common(layer, h, h_dt, act, xq, workspace, workspace_bytes, stream);
+}
+
+sq_status sq_quantize_act_geglu(const sq_layer* layer, const void* h, sq_dtype h_dt, int8_t* xq, void* stream) {
+  return quantize_act_common(layer, h, h_dt, nullptr, xq, nullptr, 0, stream, true);
 }
 
 sq_status sq_seglinear(const sq_layer* layer, const int8_t* xq, const int8_t* wq, const float* wscale,

@@ -419,6 +419,96 @@ hipError_t launch_quantize_act_dynamic(const void* x, bool x_is_bf16, int8_t* xq
 }
 
 // ------------------------------------------------------------------------------------------------
+// GEGLU in front of the quantizer (App. B lists GEGLU with SiLU and GELU): h [M][2K] = [value | gate],
+// xq[m][k] = Q_dual(value[m][k] * GELU(gate[m][k])) with the bit-specified GELU of activate() and one fp32 product.
+// VEC: a thread owns 16 consecutive outputs (K, the K-segment boundaries multiples of 16, pointers 16-byte aligned);
+// otherwise one output per thread.  HBM-bound where the gate's arithmetic lets it: 2 x 2 (bf16) or 2 x 4 bytes in,
+// 1 byte out per element.
+// ------------------------------------------------------------------------------------------------
+template <bool BF16, bool VEC>
+__global__ __launch_bounds__(256) void quantize_act_geglu_kernel(const void* __restrict__ h, int8_t* __restrict__ xq,
+                                                                 int M, int K, const ActTable tb) {
+#pragma clang fp contract(off)
+  constexpr int W = VEC ? 16 : 1;
+  const size_t nitem = (size_t)M * (size_t)(K / W);
+  const int per_row = K / W;
+  for (size_t c = blockIdx.x * (size_t)256 + threadIdx.x; c < nitem; c += (size_t)gridDim.x * 256) {
+    const size_t m = c / per_row;
+    const int col = (int)(c - m * per_row) * W;
+    float sp = tb.s_pos[0], sn = tb.s_neg[0], ip = tb.inv_pos[0], in = tb.inv_neg[0];
+    bool dual = tb.dual[0] != 0;
+    for (int s = 1; s < tb.S; ++s) {
+      if (col >= tb.kseg_off[s]) {
+        sp = tb.s_pos[s]; sn = tb.s_neg[s]; ip = tb.inv_pos[s]; in = tb.inv_neg[s]; dual = tb.dual[s] != 0;
+      }
+    }
+    const size_t ev = m * 2 * (size_t)K + col, eg = ev + K;       // value and gate of the first output
+    float v[W], g[W];
+    if (VEC) {
+      if (BF16) {
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+          const v4i rv = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(reinterpret_cast<const uint16_t*>(h) + ev + 8 * q));
+          const v4i rg = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(reinterpret_cast<const uint16_t*>(h) + eg + 8 * q));
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            v[8 * q + 2 * i] = __uint_as_float((uint32_t)rv[i] << 16);
+            v[8 * q + 2 * i + 1] = __uint_as_float((uint32_t)rv[i] & 0xFFFF0000u);
+            g[8 * q + 2 * i] = __uint_as_float((uint32_t)rg[i] << 16);
+            g[8 * q + 2 * i + 1] = __uint_as_float((uint32_t)rg[i] & 0xFFFF0000u);
+          }
+        }
+      } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const v4i rv = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(reinterpret_cast<const float*>(h) + ev + 4 * q));
+          const v4i rg = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(reinterpret_cast<const float*>(h) + eg + 4 * q));
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            v[4 * q + i] = __int_as_float(rv[i]);
+            g[4 * q + i] = __int_as_float(rg[i]);
+          }
+        }
+      }
+    } else {
+      v[0] = BF16 ? bf16_to_f32(reinterpret_cast<const uint16_t*>(h)[ev]) : reinterpret_cast<const float*>(h)[ev];
+      g[0] = BF16 ? bf16_to_f32(reinterpret_cast<const uint16_t*>(h)[eg]) : reinterpret_cast<const float*>(h)[eg];
+    }
+    int code[W];
+#pragma unroll
+    for (int i = 0; i < W; ++i) {
+      const float a = __fmul_rn(v[i], activate(SQ_ACT_GELU, g[i]));
+      const bool ng = dual && (a < 0.0f);                 // X_- = min(X, 0) takes the s_- branch of Q_dual
+      code[i] = clip_code(round_quotient(a, ng ? sn : sp, ng ? in : ip));
+    }
+    if (VEC) {
+      v4i out;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) out[q] = (int)pack4(code[4 * q], code[4 * q + 1], code[4 * q + 2], code[4 * q + 3]);
+      *reinterpret_cast<v4i*>(xq + m * (size_t)K + col) = out;
+    } else {
+      xq[m * (size_t)K + col] = (int8_t)code[0];
+    }
+  }
+}
+
+hipError_t launch_quantize_act_geglu(const void* h, bool h_is_bf16, int8_t* xq, int M, int K, const ActTable& tb, int cus,
+                                     hipStream_t st) {
+  bool vec = K % 16 == 0 && (reinterpret_cast<uintptr_t>(h) | reinterpret_cast<uintptr_t>(xq)) % 16 == 0;
+  for (int s = 0; s <= tb.S; ++s) vec = vec && tb.kseg_off[s] % 16 == 0;
+  const size_t nitem = (size_t)M * (size_t)(vec ? K / 16 : K);
+  if (nitem == 0) return hipSuccess;
+  size_t blocks = (nitem + 255) / 256;
+  const size_t cap = (size_t)cus * 64;
+  if (blocks > cap) blocks = cap;
+#define SQ_G(B, V) hipLaunchKernelGGL((quantize_act_geglu_kernel<B, V>), dim3((unsigned)blocks), dim3(256), 0, st, h, xq, M, K, tb)
+  if (h_is_bf16) { if (vec) SQ_G(true, true); else SQ_G(true, false); }
+  else           { if (vec) SQ_G(false, true); else SQ_G(false, false); }
+#undef SQ_G
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
 // 4-bit weights (App. B: per-channel weights in the 4-bit settings): the Sec. 3 quantizer with q_max = 7 per output
 // channel and K-segment, codes packed two per byte in the order the weight stream consumes them: rows in groups
 // of 16 (the last group padded with zero rows), K in steps of 128 codes (T = K / 128), one contiguous KiB per

@@ -875,3 +875,44 @@ def test_seglinear_fused_rejects_what_the_stream_kernel_cannot_run():
         with pytest.raises(sq.SqError) as e:
             sq.sq_seglinear_fused(layer, x, None, wq, ws, None, y)
         assert e.value.status == 2
+
+
+GEGLU = [
+    dict(M=70, K=512, kseg=[0, 128, 512], dual=[0, 1], h_dtype="bf16"),
+    dict(M=1100, K=1280, kseg=[0, 1280], dual=[1], h_dtype="bf16"),            # many chunks per workgroup
+    dict(M=129, K=1024, kseg=[0, 16, 48, 1024], dual=[1, 0, 1], h_dtype="f32"),
+    dict(M=13, K=100, kseg=[0, 37, 100], dual=[1, 1], h_dtype="bf16"),         # unaligned: one output per thread
+    dict(M=5, K=24, kseg=[0, 24], dual=[1], h_dtype="f32"),
+    dict(M=1, K=16, kseg=[0, 16], dual=[0], h_dtype="bf16"),
+]
+
+
+@pytest.mark.parametrize("case", GEGLU)
+@pytest.mark.parametrize("spread", ["unit", "wide"])
+def test_quantize_act_geglu(oracle, case, spread):
+    """xq = Q_dual(value * GELU(gate)) over the two halves of every row: codes bit-exact against the oracle."""
+    import torch
+
+    g = _gpu()
+    M, K = case["M"], case["K"]
+    rng = np.random.default_rng(M * 13 + K)
+    h = (rng.standard_normal((M, 2 * K)) * (1.0 if spread == "unit" else 9.0)).astype(np.float32)
+    if spread == "wide" and K >= 8:
+        h[0, K:K + 8] = [0.0, -0.0, 95.0, -95.0, 1e4, -1e4, 30.0, -9.0]
+    if case["h_dtype"] == "bf16":
+        h = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(h))
+        hd = torch.from_numpy(wl.f32_to_bf16_bits(h).view(np.int16)).view(torch.bfloat16).to(g.DEV)
+    else:
+        hd = torch.from_numpy(h).to(g.DEV)
+    a = oracle.geglu(h)
+    sp, sn, _, _ = oracle.calibrate_act(a, case["kseg"], case["dual"])
+    layer = sq.Layer(M, K, 4, case["kseg"], [0, 4], case["dual"], sp, sn)
+    xq = torch.full((M, K), 99, dtype=torch.int8, device=g.DEV)
+    sq.sq_quantize_act_geglu(layer, hd, xq)
+    torch.cuda.synchronize()
+    rp, rn = oracle.quantize_act_geglu(h, case["kseg"], case["dual"], sp, sn)
+    got = xq.cpu().numpy()
+    want = (rp.astype(np.int16) + rn.astype(np.int16)).astype(np.int8)
+    bad = np.argwhere(got != want)
+    assert bad.size == 0, (len(bad), bad[:5], got[tuple(bad[0])], want[tuple(bad[0])])
+    assert np.abs(want).max() == 127

@@ -141,6 +141,10 @@ def test_invalid_arguments_are_rejected_on_the_host(sq):
     assert lib.sq_seglinear_grouped(C.byref(ok.c), FAKE, 1, bad, 0, None) == INVALID
     assert lib.sq_seglinear_grouped(C.byref(_layer(sq, seg_scale=[[1.0]]).c), FAKE, 1, one, 0, None) == UNSUPPORTED
     assert lib.sq_seglinear_grouped(C.byref(ok.c), FAKE, 1, one, 7, None) == INVALID
+    assert lib.sq_quantize_act_geglu(C.byref(ok.c), None, 1, FAKE, None) == INVALID
+    assert lib.sq_quantize_act_geglu(C.byref(ok.c), FAKE, 1, None, None) == INVALID
+    assert lib.sq_quantize_act_geglu(C.byref(ok.c), FAKE, 9, FAKE, None) == INVALID
+    assert lib.sq_quantize_act_geglu(C.byref(_layer(sq, s_pos=[0.0]).c), FAKE, 1, FAKE, None) == INVALID
     # raw-activation entry points: NULL input, unknown dtype, unknown activation code, shapes the stream kernel cannot run
     codes = lambda *a: (C.c_int32 * len(a))(*a)
     assert lib.sq_seglinear_fused(C.byref(ok.c), None, 1, None, FAKE, FAKE, None, FAKE, 0, None) == INVALID
