@@ -173,6 +173,20 @@ def measure(name, steps, warmup, rotate_quant=True):
     torch.cuda.synchronize()
     ms_quant_fused_lut = float(np.median(_time_events(lambda: sq.sq_quantize_act_fused(layer, s["x"], codes, xq_f, workspace=fws), 20)))
     del xq_f
+    # dynamic per-token activation steps (the 4-bit settings' activation rule) on the same layer: quantizer that also
+    # writes every row's steps, and the GEMM that reads them in its flushes (8-bit weights)
+    ms_quant_dyn = ms_gemm_dyn = None
+    if w.M > 64:
+        tok = torch.empty((2, w.M, w.S), dtype=torch.float32, device="cuda:0")
+        xq_d = torch.empty_like(s["xq"])
+        y_d = torch.empty_like(s["y"])
+        sq.sq_quantize_act_dynamic(layer, s["x"], xq_d, tok)
+        sq.sq_seglinear_dynamic(layer, xq_d, tok, s["wq"], 8, s["wscale"], None, y_d)
+        torch.cuda.synchronize()
+        ms_quant_dyn = float(np.median(_time_events(lambda: sq.sq_quantize_act_dynamic(layer, s["x"], xq_d, tok), 10)))
+        ms_gemm_dyn = float(np.median(_time_events(
+            lambda: sq.sq_seglinear_dynamic(layer, xq_d, tok, s["wq"], 8, s["wscale"], None, y_d), 10)))
+        del xq_d, y_d, tok
     pws = torch.empty((sq.sq_calibrate_workspace_bytes(),), dtype=torch.uint8, device="cuda:0")
     sq.sq_calibrate_act_percentile(layer, s["x"], 0.9999, amax, stp, pws)
     torch.cuda.synchronize()
@@ -216,7 +230,7 @@ def measure(name, steps, warmup, rotate_quant=True):
         gemm_tops=w.int8_ops / (ms_gemm * 1e-3) / 1e12, step_tops=w.int8_ops / (ms_step * 1e-3) / 1e12,
         ms_gemm_b2b=ms_gemm_b2b, gemm_tops_b2b=w.int8_ops / (ms_gemm_b2b * 1e-3) / 1e12,
         gemm_bytes=gbytes, gemm_gbs=gbytes / (ms_gemm * 1e-3) / 1e9, gemm_gbs_b2b=gbytes / (ms_gemm_b2b * 1e-3) / 1e9,
-        ms_gemm_hbm=ms_gemm_hbm, weight_sets=nsets, ms_quant_fused=ms_quant_fused, ms_quant_fused_lut=ms_quant_fused_lut, ms_calibrate=ms_calib, ms_calibrate_percentile=ms_calib_pct, ms_quantize_weight_block=ms_wblock,
+        ms_gemm_hbm=ms_gemm_hbm, weight_sets=nsets, ms_quant_fused=ms_quant_fused, ms_quant_fused_lut=ms_quant_fused_lut, ms_quant_dyn=ms_quant_dyn, ms_gemm_dyn=ms_gemm_dyn, ms_calibrate=ms_calib, ms_calibrate_percentile=ms_calib_pct, ms_quantize_weight_block=ms_wblock,
         calib_gbs=(w.M * w.K * (2 if w.x_dtype == "bf16" else 4)) / (ms_calib * 1e-3) / 1e9,
         gemm_gbs_hbm=(gbytes / (ms_gemm_hbm * 1e-3) / 1e9) if ms_gemm_hbm else None,
         quant_bytes=qbytes, quant_gbs=qbytes / (ms_quant * 1e-3) / 1e9, quant_rotation=nrot,
@@ -546,6 +560,9 @@ def main():
                                "bytes": head["quant_bytes"],
                                "ms_per_launch_arithmetic_path": round(head["ms_quant_fused"], 5)},
         "quantize_act_geglu": geglu,
+        "dynamic_token_steps": {"workload": head["name"], "ms_quantize_act_dynamic": None if head["ms_quant_dyn"] is None else round(head["ms_quant_dyn"], 5),
+                                "ms_seglinear_dynamic": None if head["ms_gemm_dyn"] is None else round(head["ms_gemm_dyn"], 5),
+                                "note": "per-token steps written by the quantizer and read by the GEMM's flushes; 8-bit weights"},
         "quantize_weight_ms": round(head["ms_quantize_weight"], 5),
         "quantize_weight_block_ms": round(head["ms_quantize_weight_block"], 5),
         "calibrate_act": {"bound": "hbm", "ms_per_call": round(head["ms_calibrate"], 5), "achieved": round(head["calib_gbs"], 1),

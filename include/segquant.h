@@ -287,8 +287,10 @@ sq_status sq_seglinear_w4_debug_acc(const sq_layer* layer, const int8_t* xq, con
  *   tok_steps  dev, fp32 [2][M][S]: s_pos, then s_neg               out (sq_quantize_act_dynamic) / in
  *   wq         dev, int8 [N][K] (w_bits == 8) or the packed 4-bit codes of sq_quantize_weight_w4 (w_bits == 4)
  *   others as sq_seglinear.
- * M <= 64 with at most 8 K-segments (and the alignment the weight stream needs) runs the weight-stream kernel; every
- * other shape runs a plain one-thread-per-output kernel.  SQ_ERR_INVALID_ARG for w_bits other than 4 or 8.
+ * M <= 64 with at most 8 K-segments (and the alignment the weight stream needs) runs the weight-stream kernel; larger
+ * M with 8-bit weights runs the MFMA tile kernel (K and the K-segment boundaries multiples of 64), whose flushes read
+ * the steps of their token rows; every other shape (4-bit weights at large M included) runs a plain
+ * one-thread-per-output kernel.  SQ_ERR_INVALID_ARG for w_bits other than 4 or 8.
  */
 sq_status sq_quantize_act_dynamic(const sq_layer* layer, const void* x, sq_dtype x_dt, int8_t* xq, float* tok_steps,
                                   void* stream);

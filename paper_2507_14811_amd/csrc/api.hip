@@ -130,8 +130,9 @@ bool w4_layout_ok(const sq_layer* L) {
   return true;
 }
 
-// Dynamic per-token steps: the weight-stream kernel (M <= 64, at most 8 K-segments: its step table is 4 KiB of LDS) or the
-// one-thread-per-output kernel; 8-bit or 4-bit packed weights.
+// Dynamic per-token steps: the weight-stream kernel (M <= 64, at most 8 K-segments: its step table is 4 KiB of LDS), the
+// MFMA tile kernel (8-bit weights, its alignment rules) or the one-thread-per-output kernel (any shape, 4-bit weights at
+// large M).
 sq_status run_gemm_dynamic(const sq_layer* L, const int8_t* xq, const float* tok_steps, const void* wq, int w_bits,
                            const float* wscale, const float* bias, void* y, sq::OutMode mode, void* stream) {
   if (w_bits == 4 && !w4_layout_ok(L)) return SQ_ERR_UNSUPPORTED;
@@ -150,11 +151,17 @@ sq_status run_gemm_dynamic(const sq_layer* L, const int8_t* xq, const float* tok
   a.tok_steps = tok_steps;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   const bool stream_ok = L->S <= 8 && sq::stream_supported(a, tb);
+  const bool mfma_ok = w_bits == 8 && sq::mfma_supported(a, tb) && sq::mfma_pick_variant(a, tb, mode) >= 0;
   if (g_force_path == 3 && !stream_ok) return SQ_ERR_UNSUPPORTED;
+  if (g_force_path == 1 && !mfma_ok) return SQ_ERR_UNSUPPORTED;
   hipError_t e;
-  if (g_force_path != 0 && stream_ok) {
+  if (g_force_path != 0 && g_force_path != 1 && stream_ok) {
     e = w_bits == 4 ? sq::launch_seglinear_stream_w4(a, tb, mode, sq::device_cus(), st)
                     : sq::launch_seglinear_stream(a, tb, mode, sq::device_cus(), st);
+  } else if (g_force_path != 0 && mfma_ok) {           // large M, 8-bit weights: the MFMA tile kernel with per-row steps
+    int v = g_gemm_variant >= 0 ? g_gemm_variant : sq::mfma_pick_variant(a, tb, mode);
+    e = sq::launch_seglinear_mfma(a, tb, mode, v, st);
+    if (e == hipErrorInvalidConfiguration) return SQ_ERR_UNSUPPORTED;
   } else {
     e = w_bits == 4 ? sq::launch_seglinear_generic_w4(a, tb, mode, st) : sq::launch_seglinear_generic(a, tb, mode, st);
   }

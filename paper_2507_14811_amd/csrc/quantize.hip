@@ -361,7 +361,8 @@ hipError_t launch_quantize_weight_block(const void* w, bool w_is_bf16, int8_t* w
 // Dynamic per-token activation steps (App. B: in the 4-bit settings activations are quantized dynamically per
 // token): one workgroup per token row; per K-segment the row's extremes give its steps by the min/max rule
 // (Sec. 4.3.2: s_+ = max x / 127, s_- = |min x| / 127, 1.0 where the extreme is 0), then the row is quantized with
-// them.  A row is read twice (the second time from cache).  tok_steps: [2][M][S], s_pos then s_neg.
+// them.  This kernel takes any shape; a row is read twice (the second time from cache).  tok_steps: [2][M][S], s_pos
+// then s_neg.
 // ------------------------------------------------------------------------------------------------
 template <bool BF16>
 __global__ __launch_bounds__(256) void quantize_act_dynamic_kernel(const void* __restrict__ x, int8_t* __restrict__ xq,
@@ -411,8 +412,161 @@ __global__ __launch_bounds__(256) void quantize_act_dynamic_kernel(const void* _
   }
 }
 
+// The same for rows of 16-element chunks (K, the K-segment boundaries multiples of 16, 16-byte aligned pointers, K <=
+// 4096 NCH): a thread keeps its NCH chunks of the row in registers between the two passes, so the row is read once
+// (at large M the rows in flight on an XCD exceed its L2 and a second read goes back to memory), the loads are 16 bytes
+// wide and streaming, the quotient is the reciprocal product of round_quotient (bit-identical to the division) and the
+// codes leave as 16-byte stores.
+template <bool BF16, int NCH>
+__global__ __launch_bounds__(256) void quantize_act_dynamic_fast_kernel(const void* __restrict__ x, int8_t* __restrict__ xq,
+                                                                        float* __restrict__ tok_steps, int M, int K,
+                                                                        const ActTable tb) {
+  constexpr int NL = BF16 ? 2 : 4;                       // 16-byte loads per chunk
+  const int m = blockIdx.x;
+  const size_t row = (size_t)m * K;
+  const int nch = K >> 4;
+  __shared__ float red[2][4];
+  __shared__ float stp[SQ_MAX_SEGMENTS][4];              // s_+, s_-, and their reciprocals (NaN: always divide)
+  v4i raw[NCH][NL];
+#pragma unroll
+  for (int j = 0; j < NCH; ++j) {
+    const int c = threadIdx.x + 256 * j;
+#pragma unroll
+    for (int l = 0; l < NL; ++l) raw[j][l] = (v4i)(0);
+    if (c < nch) {
+      const v4i* src = BF16 ? reinterpret_cast<const v4i*>(reinterpret_cast<const uint16_t*>(x) + row + 16 * (size_t)c)
+                            : reinterpret_cast<const v4i*>(reinterpret_cast<const float*>(x) + row + 16 * (size_t)c);
+#pragma unroll
+      for (int l = 0; l < NL; ++l) raw[j][l] = __builtin_nontemporal_load(src + l);
+    }
+  }
+  auto value = [&](const int j, const int e) __attribute__((always_inline)) -> float {   // element e of chunk j (constants)
+    if (BF16) {
+      const uint32_t u = (uint32_t)raw[j][e >> 3][(e >> 1) & 3];
+      return __uint_as_float((e & 1) ? (u & 0xFFFF0000u) : (u << 16));
+    }
+    return __int_as_float(raw[j][BF16 ? 0 : (e >> 2)][e & 3]);
+  };
+  for (int ks = 0; ks < tb.S; ++ks) {
+    const int k0 = tb.kseg_off[ks], k1 = tb.kseg_off[ks + 1];
+    const bool dual = tb.dual[ks] != 0;
+    float mp = 0.0f, mn = 0.0f;
+    if (BF16) {
+      // Extremes on the bit patterns, two elements per instruction: as signed 16-bit integers the positive bf16 numbers
+      // keep their order and every negative one is below zero (max with 0 = pattern of max(x, 0)); as unsigned ones the
+      // negative numbers lie above all positive ones, ordered by magnitude (a maximum >= 0x8000 is the pattern of min x).
+      typedef short s16x2 __attribute__((ext_vector_type(2)));
+      typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+      s16x2 hi_s = {0, 0};
+      u16x2 hi_u = {0, 0};
+#pragma unroll
+      for (int j = 0; j < NCH; ++j) {
+        const int col = (threadIdx.x + 256 * j) << 4;
+        if (col < K && col >= k0 && col < k1) {
+#pragma unroll
+          for (int l = 0; l < 2; ++l)
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+              const int w = raw[j][BF16 ? l : 0][d];
+              if (dual) {
+                hi_s = __builtin_elementwise_max(hi_s, __builtin_bit_cast(s16x2, w));
+                hi_u = __builtin_elementwise_max(hi_u, __builtin_bit_cast(u16x2, w));
+              } else {
+                hi_u = __builtin_elementwise_max(hi_u, __builtin_bit_cast(u16x2, w & 0x7FFF7FFF));
+              }
+            }
+        }
+      }
+      const uint32_t us = (uint32_t)(hi_s[0] > hi_s[1] ? hi_s[0] : hi_s[1]);
+      const uint32_t uu = (uint32_t)(hi_u[0] > hi_u[1] ? hi_u[0] : hi_u[1]);
+      if (dual) {
+        mp = __uint_as_float(us << 16);
+        mn = uu >= 0x8000u ? __uint_as_float((uu & 0x7FFFu) << 16) : 0.0f;
+      } else {
+        mp = __uint_as_float(uu << 16);
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < NCH; ++j) {
+        const int col = (threadIdx.x + 256 * j) << 4;
+        if (col < K && col >= k0 && col < k1) {
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const float v = value(j, e);
+            if (dual) {
+              mp = __builtin_fmaxf(mp, v);
+              mn = __builtin_fmaxf(mn, -v);
+            } else {
+              mp = __builtin_fmaxf(mp, __builtin_fabsf(v));
+            }
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+      mp = __builtin_fmaxf(mp, __shfl_xor(mp, off, 64));
+      mn = __builtin_fmaxf(mn, __shfl_xor(mn, off, 64));
+    }
+    if ((threadIdx.x & 63) == 0) { red[0][threadIdx.x >> 6] = mp; red[1][threadIdx.x >> 6] = mn; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      mp = __builtin_fmaxf(__builtin_fmaxf(red[0][0], red[0][1]), __builtin_fmaxf(red[0][2], red[0][3]));
+      mn = __builtin_fmaxf(__builtin_fmaxf(red[1][0], red[1][1]), __builtin_fmaxf(red[1][2], red[1][3]));
+      const float sp = (mp == 0.0f) ? 1.0f : mp / kQmax, sn = (mn == 0.0f) ? 1.0f : mn / kQmax;
+      stp[ks][0] = sp;
+      stp[ks][1] = sn;
+      stp[ks][2] = (sp >= 1e-30f && sp <= 1e30f) ? 1.0f / sp : __builtin_nanf("");
+      stp[ks][3] = (sn >= 1e-30f && sn <= 1e30f) ? 1.0f / sn : __builtin_nanf("");
+      tok_steps[(size_t)m * tb.S + ks] = sp;
+      tok_steps[((size_t)M + m) * tb.S + ks] = sn;
+    }
+    __syncthreads();                                      // red is reused by the next segment; stp is complete after the last
+#pragma unroll
+    for (int j = 0; j < NCH; ++j)                         // keep the row as loaded: widened copies held across the passes
+#pragma unroll
+      for (int l = 0; l < NL; ++l) asm volatile("" : "+v"(raw[j][l]));   // would cost half the occupancy
+  }
+#pragma unroll
+  for (int j = 0; j < NCH; ++j) {
+    const int c = threadIdx.x + 256 * j;
+    if (c >= nch) continue;
+    const int col = c << 4;
+    int ks = 0;
+    for (int sg = 1; sg < tb.S; ++sg)
+      if (col >= tb.kseg_off[sg]) ks = sg;
+    bool dual = false;
+    for (int sg = 0; sg < tb.S; ++sg)
+      if (sg == ks) dual = tb.dual[sg] != 0;
+    const float sp = stp[ks][0], sn = stp[ks][1], ip = stp[ks][2], in = stp[ks][3];
+    v4i out;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      int code[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float v = value(j, 4 * q + i);
+        const bool ng = dual && (v < 0.0f);
+        code[i] = clip_code(round_quotient(v, ng ? sn : sp, ng ? in : ip));
+      }
+      out[q] = (int)pack4(code[0], code[1], code[2], code[3]);
+    }
+    *reinterpret_cast<v4i*>(xq + row + col) = out;
+  }
+}
+
 hipError_t launch_quantize_act_dynamic(const void* x, bool x_is_bf16, int8_t* xq, float* tok_steps, int M, int K,
                                        const ActTable& tb, hipStream_t st) {
+  bool fast = K % 16 == 0 && K <= 4096 * 8 && (reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(xq)) % 16 == 0;
+  for (int s = 0; s <= tb.S; ++s) fast = fast && tb.kseg_off[s] % 16 == 0;
+  if (fast) {
+#define SQ_D(B, N) hipLaunchKernelGGL((quantize_act_dynamic_fast_kernel<B, N>), dim3(M), dim3(256), 0, st, x, xq, tok_steps, M, K, tb)
+#define SQ_DN(B) do { if (K <= 4096) SQ_D(B, 1); else if (K <= 8192) SQ_D(B, 2); else if (K <= 16384) SQ_D(B, 4); else SQ_D(B, 8); } while (0)
+    if (x_is_bf16) SQ_DN(true); else SQ_DN(false);
+#undef SQ_DN
+#undef SQ_D
+    return hipGetLastError();
+  }
   if (x_is_bf16) hipLaunchKernelGGL((quantize_act_dynamic_kernel<true>), dim3(M), dim3(256), 0, st, x, xq, tok_steps, M, K, tb);
   else           hipLaunchKernelGGL((quantize_act_dynamic_kernel<false>), dim3(M), dim3(256), 0, st, x, xq, tok_steps, M, K, tb);
   return hipGetLastError();

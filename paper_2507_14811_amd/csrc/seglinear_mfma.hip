@@ -10,7 +10,7 @@ namespace sq {
 using LaunchFn = hipError_t (*)(const GemmArgs&, const GemmTable&, int, bool, bool, bool, hipStream_t);
 template <int V> static constexpr MfmaVariantInfo info_of() {
   using P = MfmaVariant<V>;
-  return {P::BM, P::BN, P::SK, P::MINB, P::DUAL_OK, P::MULTI_OK, P::MULTI_DUAL_OK, P::SHARE_OK};
+  return {P::BM, P::BN, P::SK, P::MINB, P::DUAL_OK, P::MULTI_OK, P::MULTI_DUAL_OK, P::SHARE_OK, P::TOK_OK};
 }
 template <int... V> struct VariantTables {
   static constexpr LaunchFn launch[sizeof...(V)] = {&launch_mfma_variant<V>...};
@@ -40,9 +40,10 @@ static int k_alignment(const GemmArgs& a, const GemmTable& tb) {
   return al;
 }
 
-static bool variant_ok(int v, bool dual, bool multi, bool share, int kalign) {
+static bool variant_ok(int v, bool dual, bool multi, bool share, int kalign, bool tok) {
   if (v < 0 || v >= kNumMfmaVariants) return false;
   const MfmaVariantInfo i = variant_info(v);
+  if (tok && !i.tok_ok) return false;
   if (i.SK > kalign) return false;
   if (dual && !i.dual_ok) return false;
   if (dual && multi && !(i.multi_dual_ok || (share && i.share_ok))) return false;
@@ -85,7 +86,7 @@ int mfma_pick_variant(const GemmArgs& a, const GemmTable& tb, OutMode) {
   int best = -1;
   float best_score = -1.0f;
   for (int v = 0; v < kNumMfmaVariants; ++v) {
-    if (!variant_ok(v, dual, multi, share, k_alignment(a, tb))) continue;
+    if (!variant_ok(v, dual, multi, share, k_alignment(a, tb), a.tok_steps != nullptr)) continue;
     const MfmaVariantInfo i = variant_info(v);
     const long tiles = (long)((a.M + i.BM - 1) / i.BM) * ((a.N + i.BN - 1) / i.BN);
     const long slots = (long)cus * i.MINB;
@@ -100,7 +101,7 @@ int mfma_pick_variant(const GemmArgs& a, const GemmTable& tb, OutMode) {
 hipError_t launch_seglinear_mfma(GemmArgs a, const GemmTable& tb_in, OutMode mode, int variant, hipStream_t st) {
   bool dual, multi, share;
   layer_flags(tb_in, dual, multi, share);
-  if (!variant_ok(variant, dual, multi, share, k_alignment(a, tb_in))) return hipErrorInvalidConfiguration;
+  if (!variant_ok(variant, dual, multi, share, k_alignment(a, tb_in), a.tok_steps != nullptr)) return hipErrorInvalidConfiguration;
   const MfmaVariantInfo i = variant_info(variant);
   GemmTable tb = tb_in;
   share = share && i.share_ok;        // prefer the register-sharing mode wherever the tile supports it

@@ -12,6 +12,15 @@ namespace sq {
 template <int V, bool DUAL, bool MULTI, bool SHARE>
 static hipError_t launch_one(const GemmArgs& a, const GemmTable& tb, int mode, hipStream_t st) {
   using P = MfmaVariant<V>;
+  if (a.tok_steps != nullptr) {                      // dynamic per-token steps: built for the tiles listed in TOK_OK
+    if constexpr (P::TOK_OK) {
+      auto kern = seglinear_mfma_kernel<P::BM, P::BN, P::WM, P::WN, P::NS, P::SK, P::MINB, DUAL, MULTI, SHARE, true>;
+      hipLaunchKernelGGL(kern, dim3(a.num_wg), dim3(P::WM * P::WN * 64), 0, st, a, tb, mode);
+      return hipGetLastError();
+    } else {
+      return hipErrorInvalidConfiguration;
+    }
+  }
   auto kern = seglinear_mfma_kernel<P::BM, P::BN, P::WM, P::WN, P::NS, P::SK, P::MINB, DUAL, MULTI, SHARE>;
   hipLaunchKernelGGL(kern, dim3(a.num_wg), dim3(P::WM * P::WN * 64), 0, st, a, tb, mode);
   return hipGetLastError();

@@ -110,7 +110,9 @@ template <int SK> __device__ __forceinline__ int row_swizzle(int row) {
   return SK == 128 ? ((row >> 1) & 7) : ((row >> 2) & 3);
 }
 
-template <int BM, int BN, int WM, int WN, int NSTAGE, int SK, int MINB, bool DUAL, bool MULTI, bool SHARE>
+// TOK: dynamic per-token activation steps (App. B, 4-bit settings): the flushes take s_+ / s_- of every lane's own token
+// rows from a.tok_steps [2][M][S] instead of the layer's static steps.
+template <int BM, int BN, int WM, int WN, int NSTAGE, int SK, int MINB, bool DUAL, bool MULTI, bool SHARE, bool TOK = false>
 __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(const GemmArgs a, const GemmTable tb,
                                                                          const int mode) {
   using C = MfmaCfg<BM, BN, WM, WN, NSTAGE, SK, DUAL, MULTI, SHARE>;
@@ -527,6 +529,22 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
     }
   };
 
+  // activation steps of this lane's token rows for K-segment ks: the layer's, or (TOK) each row's own
+  auto row_steps = [&](const int ks, const bool dl, float (&spr)[IM], float (&snr)[IM]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < IM; ++i) {
+      if (TOK) {
+        int m = mrow + i * 32;
+        m = m < a.M ? m : a.M - 1;                       // rows beyond M are masked at the store
+        spr[i] = a.tok_steps[(size_t)m * tb.S + ks];
+        snr[i] = dl ? a.tok_steps[((size_t)a.M + m) * tb.S + ks] : 0.0f;
+      } else {
+        spr[i] = tb.s_pos[ks];
+        snr[i] = dl ? tb.s_neg[ks] : 0.0f;
+      }
+    }
+  };
+
   // debug entry point: raw int32 sums of segment ks, acc_neg = 0 where the segment ran one path
   auto store_debug = [&](auto full_tag, const int ks, const bool has_neg) __attribute__((always_inline)) {
     constexpr bool FULL = decltype(full_tag)::value;
@@ -573,7 +591,8 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
     if (mode == OUT_DEBUG_ACC) {
       store_debug(full_tag, ks, DUAL && dl && (!SHARE || first));
     } else if (SHARE || FSUM) {
-      const float sp = tb.s_pos[ks], sn = dl ? tb.s_neg[ks] : 0.0f;
+      float spr[IM], snr[IM];
+      row_steps(ks, dl, spr, snr);
 #pragma unroll
       for (int j = 0; j < JN; ++j) {
         float cw[16];
@@ -584,7 +603,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
           pin_block(i, j);
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
-            const float cpos = cw[v] * sp, cneg = cw[v] * sn;
+            const float cpos = cw[v] * spr[i], cneg = cw[v] * snr[i];
             if (SHARE) {
               const int old = accn[DUAL ? i : 0][DUAL ? j : 0][v];
               const float prev = first ? cneg * (float)old : __int_as_float(old);
@@ -622,7 +641,8 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
   auto flush_last_impl = [&](auto full_tag, auto bf16_tag, const int ks, const bool dl) __attribute__((always_inline)) {
     constexpr bool FULL = decltype(full_tag)::value;
     constexpr bool BF = decltype(bf16_tag)::value;
-    const float sp = tb.s_pos[ks], sn = dl ? tb.s_neg[ks] : 0.0f;
+    float spr[IM], snr[IM];
+    row_steps(ks, dl, spr, snr);
     const bool yvec = FULL || (vec4 && (reinterpret_cast<uintptr_t>(a.y) % 16 == 0));
     const bool bvec = FULL || (vec4 && (reinterpret_cast<uintptr_t>(a.bias) % 16 == 0));
 #pragma unroll
@@ -649,9 +669,9 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
         float t[16];
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          float u = (cw[v] * sp) * (float)accp[i][j][v];
+          float u = (cw[v] * spr[i]) * (float)accp[i][j][v];
           if (SHARE) u += __int_as_float(accn[DUAL ? i : 0][DUAL ? j : 0][v]);   // running sum (never the first segment)
-          else if (DUAL) u += (cw[v] * sn) * (float)accn[DUAL ? i : 0][DUAL ? j : 0][v];
+          else if (DUAL) u += (cw[v] * snr[i]) * (float)accn[DUAL ? i : 0][DUAL ? j : 0][v];
           if (FSUM) u += fsum[FSUM ? i : 0][FSUM ? j : 0][v];
           t[v] = u + bs[v];
         }

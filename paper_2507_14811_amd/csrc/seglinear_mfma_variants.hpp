@@ -14,6 +14,7 @@ template <int V> struct MfmaVariant;
     static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, NS = NS_, SK = SK_, MINB = MINB_;                   \
     static constexpr bool DUAL_OK = DUAL_OK_, MULTI_OK = MULTI_OK_, MULTI_DUAL_OK = MULTI_DUAL_OK_,     \
                           SHARE_OK = SHARE_OK_;                                                    \
+    static constexpr bool TOK_OK = (V == 0 || V == 1 || V == 3);   /* instantiated with per-token activation steps */ \
   };
 SQ_DEF_VARIANT(0, 128, 256, 2, 2, 3, 128, 1, true, true, false, true)   // wave tile 64 x 128, both polarities: 256 accumulator registers
 SQ_DEF_VARIANT(1, 128, 128, 2, 2, 3, 128, 1, true, true, true, true)    // wave tile 64 x 64
@@ -27,7 +28,7 @@ SQ_DEF_VARIANT(8, 128, 192, 2, 2, 3, 128, 1, true, true, true, true)    // wave 
 #undef SQ_DEF_VARIANT
 constexpr int kNumMfmaVariants = 9;
 
-struct MfmaVariantInfo { int BM, BN, SK, MINB; bool dual_ok, multi_ok, multi_dual_ok, share_ok; };
+struct MfmaVariantInfo { int BM, BN, SK, MINB; bool dual_ok, multi_ok, multi_dual_ok, share_ok, tok_ok; };
 
 template <int V>
 hipError_t launch_mfma_variant(const GemmArgs& a, const GemmTable& tb, int mode, bool dual, bool multi, bool share,

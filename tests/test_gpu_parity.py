@@ -728,6 +728,16 @@ DYNCASES = [
     dict(M=40, K=512, N=200, kseg=[0, 384, 512], dual=[1, 1], nseg=[0, 64, 200], seg_scale=True, x_dtype="bf16"),
     dict(M=100, K=256, N=96, kseg=[0, 256], dual=[1], x_dtype="bf16"),                      # M > 64: plain kernel
     dict(M=7, K=100, N=33, kseg=[0, 37, 100], dual=[1, 0], x_dtype="f32", bits=(8,)),       # unaligned: plain kernel, 8-bit only
+    # large M, 8-bit weights: the MFMA tile kernel with per-row steps (4-bit weights: plain kernel)
+    dict(M=300, K=512, N=520, kseg=[0, 256, 512], dual=[0, 1], x_dtype="bf16", bias=True),  # one dual segment: shared registers
+    dict(M=257, K=384, N=130, kseg=[0, 128, 384], dual=[1, 1], x_dtype="f32", bits=(8,)),   # two dual segments, ragged tiles
+    dict(M=200, K=256, N=256, kseg=[0, 256], dual=[0], x_dtype="bf16", bits=(8,)),          # single path
+    dict(M=150, K=256, N=192, kseg=[0, 128, 256], dual=[0, 0], nseg=[0, 64, 192], seg_scale=True, x_dtype="bf16", bits=(8,)),
+    # long rows: two, four and eight chunks per thread in the row-resident quantizer
+    dict(M=3, K=4608, N=16, kseg=[0, 4608], dual=[1], x_dtype="f32", bits=(8,)),
+    dict(M=5, K=9216, N=16, kseg=[0, 1024, 9216], dual=[1, 0], x_dtype="bf16", bits=(8,)),
+    dict(M=2, K=20480, N=16, kseg=[0, 4096, 20480], dual=[0, 1], x_dtype="bf16", bits=(8,)),
+    dict(M=2, K=17408, N=16, kseg=[0, 17408], dual=[1], x_dtype="f32", bits=(8,)),
 ]
 
 
@@ -762,11 +772,17 @@ def test_seglinear_dynamic(oracle, case):
             wdev = torch.empty((((N + 15) // 16) * 16 * (K // 2),), dtype=torch.uint8, device=g.DEV)
             sq.sq_quantize_weight_w4(gl.layer, gl.wt, wdev, gl.wscale)
         ymax = float(np.abs(r.y32).max())
-        for forced in (-1, 0):
+        runs = [(-1, -1), (0, -1)] + ([(1, v) for v in (0, 1, 3)] if bits == 8 and M > 64 else [])
+        for forced, variant in runs:
             sq.sq_tuning_set("force_path", forced)
+            sq.sq_tuning_set("gemm_variant", variant)
             try:
                 y = torch.full((M, N), float("nan"), dtype=torch.float32, device=g.DEV)
-                sq.sq_seglinear_dynamic(gl.layer, gl.xq, tok, wdev, bits, gl.wscale, gl.bias, y)
+                try:
+                    sq.sq_seglinear_dynamic(gl.layer, gl.xq, tok, wdev, bits, gl.wscale, gl.bias, y)
+                except sq.SqError as e:
+                    assert e.status == 2 and variant >= 0          # a tile shape that does not take this layer class
+                    continue
                 torch.cuda.synchronize()
                 y = y.cpu().numpy()
                 assert not np.isnan(y).any()
@@ -777,6 +793,7 @@ def test_seglinear_dynamic(oracle, case):
                 g.check_bf16_against(g.bf16_tensor_bits(yb), r.y32, wl.f32_to_bf16_bits(r.y32), 1e-5 * ymax)
             finally:
                 sq.sq_tuning_set("force_path", -1)
+                sq.sq_tuning_set("gemm_variant", -1)
 
 
 FUSEDGEMM = [
