@@ -32,10 +32,10 @@ PREROLL_MS = 80.0              # untimed load before the warm-up steps, so that 
 # readings of a plain 256 MiB copy kernel (profiles/bench_all_kernels_rocprofv3.txt), bytes.  None for a
 # workload without a committed counter run.
 MEASURED_TRAFFIC = {
-    "cfg5_outproj": int(287457.4 * 1024 * 2.0 + 51727.5 * 1024 * 1.0),       # 641.7 MB (algorithmic 146.3 MB)
-    "cfg4d_qkv_dual": int(69468.8 * 1024 * 2.0 + 76535.1 * 1024 * 1.0),
-    "cfg4_qkv": int(69420.2 * 1024 * 2.0 + 76537.7 * 1024 * 1.0),
-    "cfg2_dit_fc2": int(19732.0 * 1024 * 2.0 + 4608.0 * 1024 * 1.0),
+    "cfg5_outproj": int(287549.4 * 1024 * 2.0 + 51730.0 * 1024 * 1.0),       # 641.9 MB (algorithmic 146.3 MB)
+    "cfg4d_qkv_dual": int(69503.7 * 1024 * 2.0 + 76538.6 * 1024 * 1.0),
+    "cfg4_qkv": int(69416.8 * 1024 * 2.0 + 76544.2 * 1024 * 1.0),
+    "cfg2_dit_fc2": int(19732.5 * 1024 * 2.0 + 4608.0 * 1024 * 1.0),
 }
 
 
