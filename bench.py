@@ -390,12 +390,29 @@ def measure_w4(steps=40):
     torch.cuda.synchronize()
     ms_dyn = e0.elapsed_time(e1) / (steps * nsets)
     ms_qdyn = float(np.median(_time_events(lambda: sq.sq_quantize_act_dynamic(layer, s["x"], s["xq"], tok), 10)))
+
+    # the same from the raw input in ONE launch: SiLU, per-token steps, codes and the W4 stream (s["x"] stands for the
+    # pre-activation here: the timing does not depend on the values)
+    def rot_fused_dyn():
+        for t in sets:
+            sq.sq_seglinear_fused_dynamic(layer, s["x"], [sq.SQ_ACT_SILU] * w.S, t, 4, s["wscale"], None, s["y"])
+
+    for _ in range(5):
+        rot_fused_dyn()
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(steps):
+        rot_fused_dyn()
+    e1.record()
+    torch.cuda.synchronize()
+    ms_fused_dyn = e0.elapsed_time(e1) / (steps * nsets)
     byt = int(w.M * w.K + w.N * w.K // 2 + 4 * w.S * w.N + 2 * w.M * w.N)
     return {"workload": "cfg3x28 with 4-bit packed weights", "M": w.M, "K": w.K, "N": w.N, "ms_per_launch": round(ms, 5),
             "bytes": byt, "gbs_from_hbm": round(byt / (ms * 1e-3) / 1e9, 1),
             "frac_hbm_peak": round(byt / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
             "gemm_tops": round(w.int8_ops / (ms * 1e-3) / 1e12, 1), "ms_quantize_weight_w4": round(ms_qw, 5),
             "ms_per_launch_dynamic_token_steps": round(ms_dyn, 5), "ms_quantize_act_dynamic": round(ms_qdyn, 5),
+            "ms_one_launch_raw_input_silu_dynamic": round(ms_fused_dyn, 5),
             "weight_sets_rotated": nsets}
 
 

@@ -241,6 +241,18 @@ sq_status sq_seglinear_grouped_fused(const sq_layer* layer, const void* x, sq_dt
                                      const sq_group_item* items, sq_dtype y_dt, void* stream);
 
 /*
+ * The same with dynamic per-token activation steps (App. B, 4-bit settings: per-channel 4-bit weights, activations
+ * quantized dynamically per token): one launch computes act(x), every token row's steps per K-segment by the min/max rule
+ * (as sq_quantize_act_dynamic), the codes, and the GEMM with 8-bit (w_bits == 8, wq int8 [N][K]) or packed 4-bit weights
+ * (w_bits == 4, wq from sq_quantize_weight_w4).  y equals sq_seglinear_dynamic(sq_quantize_act_dynamic(act(x))) bit for
+ * bit.  layer->s_pos / s_neg are not read.  Returns SQ_ERR_UNSUPPORTED where the weight-stream kernel does not apply or
+ * the layer has more than 8 K-segments; SQ_ERR_INVALID_ARG for w_bits other than 4 or 8.
+ */
+sq_status sq_seglinear_fused_dynamic(const sq_layer* layer, const void* x, sq_dtype x_dt, const int32_t* act, const void* wq,
+                                     int32_t w_bits, const float* wscale, const float* bias, void* y, sq_dtype y_dt,
+                                     void* stream);
+
+/*
  * Parity instrument: runs the same main loop as sq_seglinear (same kernel selection) and stores the
  * raw int32 accumulators instead of the dequantized output.
  *   acc_pos, acc_neg  dev int32 [S][M][N];  acc_neg[ks] of a non-dual segment is written as 0.

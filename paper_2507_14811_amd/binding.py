@@ -26,7 +26,8 @@ EXPORTS = ("sq_quantize_weight", "sq_quantize_act", "sq_seglinear", "sq_seglinea
            "sq_calibrate_workspace_bytes", "sq_quantize_act_fused",
            "sq_quantize_act_fused_workspace_bytes", "sq_quantize_weight_w4", "sq_seglinear_w4",
            "sq_seglinear_w4_debug_acc", "sq_quantize_act_dynamic", "sq_seglinear_dynamic",
-           "sq_seglinear_fused", "sq_seglinear_grouped_fused", "sq_quantize_act_geglu")
+           "sq_seglinear_fused", "sq_seglinear_grouped_fused", "sq_quantize_act_geglu",
+           "sq_seglinear_fused_dynamic")
 
 
 class SqError(RuntimeError):
@@ -99,6 +100,8 @@ def load_library() -> C.CDLL:
     lib.sq_quantize_act_geglu.restype = i32
     lib.sq_seglinear_fused.argtypes = [lp, vp, i32, C.POINTER(C.c_int32), vp, vp, vp, vp, i32, vp]
     lib.sq_seglinear_fused.restype = i32
+    lib.sq_seglinear_fused_dynamic.argtypes = [lp, vp, i32, C.POINTER(C.c_int32), vp, i32, vp, vp, vp, i32, vp]
+    lib.sq_seglinear_fused_dynamic.restype = i32
     lib.sq_seglinear_grouped_fused.argtypes = [lp, vp, i32, C.POINTER(C.c_int32), i32, C.POINTER(sq_group_item), i32, vp]
     lib.sq_seglinear_grouped_fused.restype = i32
     lib.sq_probe_mfma.argtypes = [vp, C.c_size_t, i32, C.POINTER(C.c_double), vp]
@@ -330,6 +333,14 @@ def sq_seglinear_fused(layer: Layer, x, act, wq, wscale, bias, y, stream=None) -
     _check(load_library().sq_seglinear_fused(C.byref(layer.c), _dptr(x), _dt(x), _act_codes(layer, act), _dptr(wq),
                                              _dptr(wscale), _dptr(bias), _dptr(y), _dt(y), _stream(stream)),
            "sq_seglinear_fused")
+
+
+def sq_seglinear_fused_dynamic(layer: Layer, x, act, wq, w_bits, wscale, bias, y, stream=None) -> None:
+    """sq_seglinear_fused with per-token activation steps found inside the launch; wq: int8 [N][K] (w_bits 8) or the packed
+    4-bit codes of sq_quantize_weight_w4 (w_bits 4)."""
+    _check(load_library().sq_seglinear_fused_dynamic(C.byref(layer.c), _dptr(x), _dt(x), _act_codes(layer, act), _dptr(wq),
+                                                     int(w_bits), _dptr(wscale), _dptr(bias), _dptr(y), _dt(y),
+                                                     _stream(stream)), "sq_seglinear_fused_dynamic")
 
 
 def sq_seglinear_grouped_fused(layer: Layer, x, act, items, stream=None) -> None:

@@ -493,6 +493,45 @@ sq_status sq_seglinear_dynamic(const sq_layer* layer, const int8_t* xq, const fl
                           stream);
 }
 
+sq_status sq_seglinear_fused_dynamic(const sq_layer* layer, const void* x, sq_dtype x_dt, const int32_t* act, const void* wq,
+                                     int32_t w_bits, const float* wscale, const float* bias, void* y, sq_dtype y_dt,
+                                     void* stream) {
+  sq_status st = check_layer(layer, true, false);
+  if (st != SQ_OK) return st;
+  if (x == nullptr || wq == nullptr || wscale == nullptr || y == nullptr) return SQ_ERR_INVALID_ARG;
+  if ((x_dt != SQ_F32 && x_dt != SQ_BF16) || (y_dt != SQ_F32 && y_dt != SQ_BF16)) return SQ_ERR_INVALID_ARG;
+  if (w_bits != 8 && w_bits != 4) return SQ_ERR_INVALID_ARG;
+  if (w_bits == 4 && !w4_layout_ok(layer)) return SQ_ERR_UNSUPPORTED;
+  sq::GemmTable tb;
+  fill_gemm_table(layer, tb);
+  for (int s = 0; s < layer->S; ++s) {
+    tb.s_pos[s] = 1.0f;                                  // the kernel finds every row's steps itself
+    tb.s_neg[s] = layer->dual[s] ? 1.0f : 0.0f;
+    tb.act[s] = SQ_ACT_NONE;
+    if (act != nullptr) {
+      if (act[s] != SQ_ACT_NONE && act[s] != SQ_ACT_SILU && act[s] != SQ_ACT_GELU) return SQ_ERR_INVALID_ARG;
+      tb.act[s] = act[s];
+    }
+  }
+  sq::GemmArgs a{};
+  a.wq = reinterpret_cast<const int8_t*>(wq);
+  a.wscale = wscale;
+  a.bias = bias;
+  a.y = y;
+  a.M = layer->M;
+  a.K = layer->K;
+  a.N = layer->N;
+  a.x_raw = x;
+  a.x_raw_bf16 = x_dt == SQ_BF16 ? 1 : 0;
+  a.x_raw_dynamic = 1;
+  if (layer->S > 8 || reinterpret_cast<uintptr_t>(x) % 16 != 0 || !sq::stream_supported(a, tb)) return SQ_ERR_UNSUPPORTED;
+  const sq::OutMode mode = y_dt == SQ_BF16 ? sq::OUT_BF16 : sq::OUT_F32;
+  hipStream_t hs = reinterpret_cast<hipStream_t>(stream);
+  hipError_t e = w_bits == 4 ? sq::launch_seglinear_stream_w4(a, tb, mode, sq::device_cus(), hs)
+                             : sq::launch_seglinear_stream(a, tb, mode, sq::device_cus(), hs);
+  return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
 sq_status sq_probe_mfma(const int8_t* codes, size_t bytes, int iters, double* ops, void* stream) {
   if (codes == nullptr || bytes < 4096 || bytes > 0xFFFFFFFFull || iters < 1 || iters > (1 << 24)) return SQ_ERR_INVALID_ARG;
   if (reinterpret_cast<uintptr_t>(codes) % 16 != 0) return SQ_ERR_INVALID_ARG;

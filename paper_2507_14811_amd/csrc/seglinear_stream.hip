@@ -34,6 +34,12 @@ __device__ __forceinline__ void glds16_stream(const void* sbase, uint32_t voff, 
                : "memory");
 }
 
+// Workgroup barrier that orders LDS traffic only: unlike __syncthreads() it does not wait for outstanding vector memory
+// operations, i.e. it leaves the ring's direct loads in flight.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 // Per-column scales and biases of a 16-column group sit at a wave-uniform address and are never written by the
 // kernel: they are fetched through the scalar cache (constant address space).  A vector load here would make the
 // compiler wait for vmcnt(0) before its first use, which drains the whole ring of direct loads once per group.
@@ -244,16 +250,7 @@ __global__ __launch_bounds__(stream_waves(MT) * 64) void seglinear_stream_kernel
       }
       *reinterpret_cast<int*>(smem + r * rowb + col) = pos;
     };
-#pragma unroll
-    for (int j = 0; j < RAWPRE; ++j) {
-      const int c = threadIdx.x + j * NT;
-      uint32_t w[4] = {(uint32_t)raw4[j][0], (uint32_t)raw4[j][1], (uint32_t)raw4[j][2], (uint32_t)raw4[j][3]};
-      if (a.x_raw_bf16) { w[0] = (uint32_t)raw2[j]; w[1] = (uint32_t)(raw2[j] >> 32); }
-      if (c < nitem) quantize_item(c, w);
-    }
-#pragma unroll 1
-    for (int c = threadIdx.x + RAWPRE * NT; c < nitem; c += NT) {  // larger X: plain loads (each wait drains the ring)
-      uint32_t w[4];
+    auto load_item = [&](const int c, uint32_t (&w)[4]) __attribute__((always_inline)) {
       if (a.x_raw_bf16) {
         const uint2 t = *reinterpret_cast<const uint2*>(reinterpret_cast<const uint16_t*>(a.x_raw) + (size_t)c * 4);
         w[0] = t.x; w[1] = t.y; w[2] = 0; w[3] = 0;
@@ -261,7 +258,125 @@ __global__ __launch_bounds__(stream_waves(MT) * 64) void seglinear_stream_kernel
         const uint4 t = *reinterpret_cast<const uint4*>(reinterpret_cast<const float*>(a.x_raw) + (size_t)c * 4);
         w[0] = t.x; w[1] = t.y; w[2] = t.z; w[3] = t.w;
       }
-      quantize_item(c, w);
+    };
+    if (a.x_raw_dynamic) {
+      // Dynamic per-token steps (App. B, 4-bit settings) found here as well: extremes of act(x) per (token row, K-segment,
+      // polarity) through LDS maxima on the bit patterns (non-negative floats order like unsigned integers), the steps by
+      // the min/max rule of Sec. 4.3.2 (1.0 where the extreme is 0) into the table the flushes read, then the codes.
+      // The activated values of the preloaded items replace the raw ones in their registers between the two passes.
+      uint32_t* amax = reinterpret_cast<uint32_t*>(tok);
+      const int ntab = MT * 16 * tb.S * 2;
+      for (int i = threadIdx.x; i < ntab; i += NT) amax[i] = 0u;
+      lds_barrier();
+      auto scan_item = [&](const int c, const uint32_t (&w)[4], float (&av)[4]) __attribute__((always_inline)) {
+        const int r = c / kq, col = (c - r * kq) << 2;
+        int ks = 0, acode = SQ_ACT_NONE;
+        bool dl = false;
+        for (int sg = 0; sg < tb.S; ++sg)
+          if (col >= tb.kseg_off[sg]) { ks = sg; dl = tb.dual[sg] != 0; acode = tb.act[sg]; }
+        float mp = 0.0f, mn = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          float xv;
+          if (a.x_raw_bf16) xv = __uint_as_float((i & 1) ? (w[i >> 1] & 0xFFFF0000u) : (w[i >> 1] << 16));
+          else xv = __uint_as_float(w[i]);
+          av[i] = activate(acode, xv);
+          if (dl) {
+            mp = __builtin_fmaxf(mp, av[i]);
+            mn = __builtin_fmaxf(mn, -av[i]);
+          } else {
+            mp = __builtin_fmaxf(mp, __builtin_fabsf(av[i]));
+          }
+        }
+        const int ti = 2 * (r * tb.S + ks);
+        if (mp > 0.0f) atomicMax(&amax[ti], __float_as_uint(mp));
+        if (mn > 0.0f) atomicMax(&amax[ti + 1], __float_as_uint(mn));
+      };
+#pragma unroll
+      for (int j = 0; j < RAWPRE; ++j) {
+        const int c = threadIdx.x + j * NT;
+        uint32_t w[4] = {(uint32_t)raw4[j][0], (uint32_t)raw4[j][1], (uint32_t)raw4[j][2], (uint32_t)raw4[j][3]};
+        if (a.x_raw_bf16) { w[0] = (uint32_t)raw2[j]; w[1] = (uint32_t)(raw2[j] >> 32); }
+        float av[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (c < nitem) scan_item(c, w, av);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) raw4[j][i] = __float_as_int(av[i]);
+      }
+#pragma unroll 1
+      for (int c = threadIdx.x + RAWPRE * NT; c < nitem; c += NT) {
+        uint32_t w[4];
+        float av[4];
+        load_item(c, w);
+        scan_item(c, w, av);
+      }
+      lds_barrier();
+      for (int i = threadIdx.x; i < ntab; i += NT) {
+        const float m = __uint_as_float(amax[i]);
+        tok[i] = (m == 0.0f) ? 1.0f : m / kQmax;
+      }
+      lds_barrier();
+      auto code_item = [&](const int c, const float (&av)[4]) __attribute__((always_inline)) {
+        const int r = c / kq, col = (c - r * kq) << 2;
+        int ks = 0;
+        bool dl = false;
+        for (int sg = 0; sg < tb.S; ++sg)
+          if (col >= tb.kseg_off[sg]) { ks = sg; dl = tb.dual[sg] != 0; }
+        const float sp = tok[2 * (r * tb.S + ks)], sn = tok[2 * (r * tb.S + ks) + 1];
+        const float ip = (sp >= 1e-30f && sp <= 1e30f) ? 1.0f / sp : __builtin_nanf("");
+        const float in = (sn >= 1e-30f && sn <= 1e30f) ? 1.0f / sn : __builtin_nanf("");
+        uint32_t pk = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const bool ng = dl && (av[i] < 0.0f);
+          const int code = clip_code(round_quotient(av[i], ng ? sn : sp, ng ? in : ip));
+          pk |= (uint32_t)(code & 0xFF) << (8 * i);
+        }
+        int pos = (int)pk, neg = 0;
+        if (PS) {
+          if (dl) split_polarity((int)pk, pos, neg);
+          *reinterpret_cast<int*>(smem + plane + r * rowb + col) = neg;
+        }
+        *reinterpret_cast<int*>(smem + r * rowb + col) = pos;
+      };
+#pragma unroll
+      for (int j = 0; j < RAWPRE; ++j) {
+        const int c = threadIdx.x + j * NT;
+        const float av[4] = {__int_as_float(raw4[j][0]), __int_as_float(raw4[j][1]), __int_as_float(raw4[j][2]),
+                             __int_as_float(raw4[j][3])};
+        if (c < nitem) code_item(c, av);
+      }
+#pragma unroll 1
+      for (int c = threadIdx.x + RAWPRE * NT; c < nitem; c += NT) {
+        uint32_t w[4];
+        float av[4];
+        load_item(c, w);
+        const int r = c / kq, col = (c - r * kq) << 2;
+        int acode = SQ_ACT_NONE;
+        for (int sg = 0; sg < tb.S; ++sg)
+          if (col >= tb.kseg_off[sg]) acode = tb.act[sg];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          float xv;
+          if (a.x_raw_bf16) xv = __uint_as_float((i & 1) ? (w[i >> 1] & 0xFFFF0000u) : (w[i >> 1] << 16));
+          else xv = __uint_as_float(w[i]);
+          av[i] = activate(acode, xv);
+        }
+        code_item(c, av);
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < RAWPRE; ++j) {
+        const int c = threadIdx.x + j * NT;
+        uint32_t w[4] = {(uint32_t)raw4[j][0], (uint32_t)raw4[j][1], (uint32_t)raw4[j][2], (uint32_t)raw4[j][3]};
+        if (a.x_raw_bf16) { w[0] = (uint32_t)raw2[j]; w[1] = (uint32_t)(raw2[j] >> 32); }
+        if (c < nitem) quantize_item(c, w);
+      }
+#pragma unroll 1
+      for (int c = threadIdx.x + RAWPRE * NT; c < nitem; c += NT) {  // larger X: plain loads (each wait drains the ring)
+        uint32_t w[4];
+        load_item(c, w);
+        quantize_item(c, w);
+      }
     }
     const int cpr = a.K >> 4;                                      // rows beyond M: zero codes (masked at the store)
     for (int c = a.M * cpr + threadIdx.x; c < MT * 16 * cpr; c += NT) {
@@ -447,7 +562,7 @@ __global__ __launch_bounds__(stream_waves(MT) * 64) void seglinear_stream_kernel
             for (int r = 0; r < 4; ++r) cw[r] *= seg_scale_of(tb, ks, ncol + r);
           }
         }
-        const bool dyn = a.tok_steps != nullptr;
+        const bool dyn = a.tok_steps != nullptr || a.x_raw_dynamic != 0;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
           float sp = tb.s_pos[ks], sn = dl ? tb.s_neg[ks] : 0.0f;

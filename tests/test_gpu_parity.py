@@ -933,3 +933,69 @@ def test_quantize_act_geglu(oracle, case, spread):
     bad = np.argwhere(got != want)
     assert bad.size == 0, (len(bad), bad[:5], got[tuple(bad[0])], want[tuple(bad[0])])
     assert np.abs(want).max() == 127
+
+
+FUSEDDYN = [
+    dict(M=16, K=1152, N=6912, kseg=[0, 1152], dual=[1], act=[1], h_dtype="bf16"),                 # adaLN in the 4-bit setting
+    dict(M=5, K=256, N=70, kseg=[0, 128, 256], dual=[0, 1], act=[0, 2], h_dtype="f32", bias=True),
+    dict(M=40, K=512, N=200, kseg=[0, 384, 512], dual=[1, 1], act=[1, 1], h_dtype="bf16"),          # three row tiles
+    dict(M=1, K=128, N=16, kseg=[0, 128], dual=[1], act=[0], h_dtype="f32"),
+    dict(M=9, K=3072, N=48, kseg=[0, 1024, 3072], dual=[1, 0], act=[2, 0], h_dtype="bf16"),         # more items than preloaded
+]
+
+
+@pytest.mark.parametrize("case", FUSEDDYN)
+def test_seglinear_fused_dynamic(oracle, case):
+    """Raw activations in, per-token steps found inside the launch (4-bit settings): against the oracle's
+    activation -> dynamic Q_dual -> SegLinear, and bit for bit against quantize_act_dynamic + seglinear_dynamic."""
+    import torch
+
+    g = _gpu()
+    M, K, N = case["M"], case["K"], case["N"]
+    rng = np.random.default_rng(M * 3 + K + N)
+    h = (rng.standard_normal((M, K)) * rng.uniform(0.2, 6.0, size=(M, 1))).astype(np.float32)   # tokens of different scale
+    h[0, :4] = [0.0, -0.0, 50.0, -50.0]
+    if case["h_dtype"] == "bf16":
+        h = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(h))
+        hd = torch.from_numpy(wl.f32_to_bf16_bits(h).view(np.int16)).view(torch.bfloat16).to(g.DEV)
+    else:
+        hd = torch.from_numpy(h).to(g.DEV)
+    a = oracle.activation(h, case["kseg"], case["act"])
+    S = len(case["dual"])
+    layer = sq.Layer(M, K, N, case["kseg"], [0, N], case["dual"], [1.0] * S, [1.0] * S)
+    w = (rng.standard_normal((N, K)) * 0.03).astype(np.float32)
+    b = rng.standard_normal(N).astype(np.float32) if case.get("bias") else None
+    bd = None if b is None else torch.from_numpy(b).to(g.DEV)
+    wt = torch.from_numpy(w).to(g.DEV)
+    ad = torch.from_numpy(a).to(g.DEV)                         # the activation's fp32 result, for the two-launch path
+    for bits in (8, 4):
+        ws = torch.empty((S, N), dtype=torch.float32, device=g.DEV)
+        if bits == 8:
+            wq = torch.empty((N, K), dtype=torch.int8, device=g.DEV)
+            sq.sq_quantize_weight(layer, wt, wq, ws)
+        else:
+            wq = torch.empty((((N + 15) // 16) * 16 * (K // 2),), dtype=torch.uint8, device=g.DEV)
+            sq.sq_quantize_weight_w4(layer, wt, wq, ws)
+        r = oracle.seglinear_dynamic(a, w, case["kseg"], [0, N], case["dual"], None, b, wbits=bits)
+        ymax = float(np.abs(r.y32).max())
+        y = torch.full((M, N), float("nan"), dtype=torch.float32, device=g.DEV)
+        sq.sq_seglinear_fused_dynamic(layer, hd, case["act"], wq, bits, ws, bd, y)
+        torch.cuda.synchronize()
+        yh = y.cpu().numpy()
+        assert not np.isnan(yh).any()
+        err = float(np.abs(yh.astype(np.float64) - r.y32.astype(np.float64)).max())
+        assert err <= RTOL * ymax, (bits, err, ymax)
+        # two launches on the activated values: same steps, same codes, same kernel -> same bits
+        xq = torch.empty((M, K), dtype=torch.int8, device=g.DEV)
+        tok = torch.empty((2, M, S), dtype=torch.float32, device=g.DEV)
+        sq.sq_quantize_act_dynamic(layer, ad, xq, tok)
+        y2 = torch.full((M, N), float("nan"), dtype=torch.float32, device=g.DEV)
+        sq.sq_seglinear_dynamic(layer, xq, tok, wq, bits, ws, bd, y2)
+        torch.cuda.synchronize()
+        assert np.array_equal(tok.cpu().numpy().view(np.uint32), r.tok_steps.view(np.uint32))
+        if M <= 32:                                            # above, the two-launch path takes another kernel
+            assert torch.equal(y.view(torch.int32), y2.view(torch.int32)), bits
+        yb = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=g.DEV)
+        sq.sq_seglinear_fused_dynamic(layer, hd, case["act"], wq, bits, ws, bd, yb)
+        torch.cuda.synchronize()
+        g.check_bf16_against(g.bf16_tensor_bits(yb), r.y32, wl.f32_to_bf16_bits(r.y32), RTOL * ymax)

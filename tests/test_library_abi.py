@@ -154,6 +154,14 @@ def test_invalid_arguments_are_rejected_on_the_host(sq):
     assert lib.sq_seglinear_fused(C.byref(_layer(sq, K=192, kseg_off=[0, 192]).c), FAKE, 1, codes(1), FAKE, FAKE, None, FAKE, 0, None) == UNSUPPORTED
     assert lib.sq_seglinear_fused(C.byref(_layer(sq, M=65).c), FAKE, 1, codes(1), FAKE, FAKE, None, FAKE, 0, None) == UNSUPPORTED
     assert lib.sq_seglinear_fused(C.byref(ok.c), C.c_void_p(0x1004), 0, None, FAKE, FAKE, None, FAKE, 0, None) == UNSUPPORTED
+    fd = lambda layer=ok, x=FAKE, dt=1, act=None, wq=FAKE, bits=8, ws=FAKE, y=FAKE: lib.sq_seglinear_fused_dynamic(
+        C.byref(layer.c), x, dt, act, wq, bits, ws, None, y, 0, None)
+    assert fd(x=None) == INVALID and fd(wq=None) == INVALID and fd(ws=None) == INVALID and fd(y=None) == INVALID
+    assert fd(dt=7) == INVALID and fd(bits=5) == INVALID and fd(act=codes(9)) == INVALID
+    assert fd(layer=_layer(sq, K=192, kseg_off=[0, 192])) == UNSUPPORTED and fd(layer=_layer(sq, M=65)) == UNSUPPORTED
+    assert fd(layer=_layer(sq, K=192, kseg_off=[0, 192]), bits=4) == UNSUPPORTED
+    nine = _layer(sq, K=128 * 9, kseg_off=[128 * i for i in range(10)], dual=[1] * 9, s_pos=[0.5] * 9, s_neg=[0.5] * 9)
+    assert fd(layer=nine) == UNSUPPORTED
     assert lib.sq_seglinear_grouped_fused(C.byref(ok.c), None, 1, None, 1, one, 0, None) == INVALID
     assert lib.sq_seglinear_grouped_fused(C.byref(ok.c), FAKE, 7, None, 1, one, 0, None) == INVALID
     assert lib.sq_seglinear_grouped_fused(C.byref(ok.c), FAKE, 1, codes(-1), 1, one, 0, None) == INVALID
