@@ -406,8 +406,15 @@ def measure_w4(steps=40):
     e1.record()
     torch.cuda.synchronize()
     ms_fused_dyn = e0.elapsed_time(e1) / (steps * nsets)
+    # packed codes back to one int8 code per byte (what a layer with many token rows feeds to the int8 tile kernel)
+    wq8 = torch.empty((w.N, w.K), dtype=torch.int8, device="cuda:0")
+    sq.sq_unpack_w4(layer, sets[0], wq8)
+    torch.cuda.synchronize()
+    ms_unpack = float(np.median(_time_events(lambda: sq.sq_unpack_w4(layer, sets[0], wq8), 10)))
+    del wq8
     byt = int(w.M * w.K + w.N * w.K // 2 + 4 * w.S * w.N + 2 * w.M * w.N)
-    return {"workload": "cfg3x28 with 4-bit packed weights", "M": w.M, "K": w.K, "N": w.N, "ms_per_launch": round(ms, 5),
+    return {"workload": "cfg3x28 with 4-bit packed weights", "ms_unpack_w4": round(ms_unpack, 5),
+            "unpack_w4_gbs": round(1.5 * w.N * w.K / (ms_unpack * 1e-3) / 1e9, 1), "M": w.M, "K": w.K, "N": w.N, "ms_per_launch": round(ms, 5),
             "bytes": byt, "gbs_from_hbm": round(byt / (ms * 1e-3) / 1e9, 1),
             "frac_hbm_peak": round(byt / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
             "gemm_tops": round(w.int8_ops / (ms * 1e-3) / 1e12, 1), "ms_quantize_weight_w4": round(ms_qw, 5),

@@ -283,6 +283,16 @@ sq_status sq_quantize_weight_w4(const sq_layer* layer, const void* w, sq_dtype w
                                 void* stream);
 sq_status sq_seglinear_w4(const sq_layer* layer, const int8_t* xq, const uint8_t* wq4, const float* wscale,
                           const float* bias, void* y, sq_dtype y_dt, void* stream);
+/*
+ * Packed 4-bit weight codes back to int8, one code per byte, [N][K] row-major: the operand of sq_seglinear /
+ * sq_seglinear_dynamic (w_bits == 8) with the SAME wscale.  For layers with many token rows, where the GEMM is bound by
+ * the matrix units and the 4-bit format saves memory, not time: keep the packed codes resident and unpack a layer into a
+ * reusable buffer right before its GEMM.  The result of the GEMM is that of sq_seglinear_w4.
+ *   wq4  dev uint8, packed codes of sq_quantize_weight_w4, 16-byte aligned     in
+ *   wq   dev int8 [N][K], 16-byte aligned                                      out
+ * SQ_ERR_UNSUPPORTED for layouts sq_quantize_weight_w4 does not take or misaligned pointers.
+ */
+sq_status sq_unpack_w4(const sq_layer* layer, const uint8_t* wq4, int8_t* wq, void* stream);
 sq_status sq_seglinear_w4_debug_acc(const sq_layer* layer, const int8_t* xq, const uint8_t* wq4, int32_t* acc_pos,
                                     int32_t* acc_neg, void* stream);
 

@@ -27,6 +27,7 @@ from .binding import (  # noqa: F401
     sq_seglinear_dynamic,
     sq_seglinear_grouped,
     sq_seglinear_fused,
+    sq_unpack_w4,
     sq_seglinear_fused_dynamic,
     sq_quantize_act_geglu,
     sq_seglinear_grouped_fused,

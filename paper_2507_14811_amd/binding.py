@@ -27,7 +27,7 @@ EXPORTS = ("sq_quantize_weight", "sq_quantize_act", "sq_seglinear", "sq_seglinea
            "sq_quantize_act_fused_workspace_bytes", "sq_quantize_weight_w4", "sq_seglinear_w4",
            "sq_seglinear_w4_debug_acc", "sq_quantize_act_dynamic", "sq_seglinear_dynamic",
            "sq_seglinear_fused", "sq_seglinear_grouped_fused", "sq_quantize_act_geglu",
-           "sq_seglinear_fused_dynamic")
+           "sq_seglinear_fused_dynamic", "sq_unpack_w4")
 
 
 class SqError(RuntimeError):
@@ -100,6 +100,8 @@ def load_library() -> C.CDLL:
     lib.sq_quantize_act_geglu.restype = i32
     lib.sq_seglinear_fused.argtypes = [lp, vp, i32, C.POINTER(C.c_int32), vp, vp, vp, vp, i32, vp]
     lib.sq_seglinear_fused.restype = i32
+    lib.sq_unpack_w4.argtypes = [lp, vp, vp, vp]
+    lib.sq_unpack_w4.restype = i32
     lib.sq_seglinear_fused_dynamic.argtypes = [lp, vp, i32, C.POINTER(C.c_int32), vp, i32, vp, vp, vp, i32, vp]
     lib.sq_seglinear_fused_dynamic.restype = i32
     lib.sq_seglinear_grouped_fused.argtypes = [lp, vp, i32, C.POINTER(C.c_int32), i32, C.POINTER(sq_group_item), i32, vp]
@@ -253,6 +255,11 @@ def sq_quantize_act_fused(layer: Layer, h, act, xq, workspace=None, stream=None)
                                                 nbytes, _stream(stream)), "sq_quantize_act_fused")
 
 
+def sq_unpack_w4(layer: Layer, wq4, wq, stream=None) -> None:
+    """Packed 4-bit codes (sq_quantize_weight_w4) -> int8 [N][K], for the int8 GEMM entry points with the same wscale."""
+    _check(load_library().sq_unpack_w4(C.byref(layer.c), _dptr(wq4), _dptr(wq), _stream(stream)), "sq_unpack_w4")
+
+
 def sq_quantize_act_geglu(layer: Layer, h, xq, stream=None) -> None:
     """xq [M][K] = Q_dual(value * GELU(gate)): h [M][2K] fp32/bf16 = [value | gate]; the layer's K-segments are those of xq."""
     _check(load_library().sq_quantize_act_geglu(C.byref(layer.c), _dptr(h), _dt(h), _dptr(xq), _stream(stream)),
@@ -340,7 +347,7 @@ def sq_seglinear_fused_dynamic(layer: Layer, x, act, wq, w_bits, wscale, bias, y
     4-bit codes of sq_quantize_weight_w4 (w_bits 4)."""
     _check(load_library().sq_seglinear_fused_dynamic(C.byref(layer.c), _dptr(x), _dt(x), _act_codes(layer, act), _dptr(wq),
                                                      int(w_bits), _dptr(wscale), _dptr(bias), _dptr(y), _dt(y),
-                                                     _stream(stream)), "sq_seglinear_fused_dynamic")
+                                                     _stream(stream)), "sq_seglinear_fused_dynamic", "sq_unpack_w4")
 
 
 def sq_seglinear_grouped_fused(layer: Layer, x, act, items, stream=None) -> None:

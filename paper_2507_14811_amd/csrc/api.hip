@@ -446,6 +446,16 @@ sq_status sq_quantize_weight_w4(const sq_layer* layer, const void* w, sq_dtype w
   return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 
+sq_status sq_unpack_w4(const sq_layer* layer, const uint8_t* wq4, int8_t* wq, void* stream) {
+  sq_status st = check_layer(layer, false, false);
+  if (st != SQ_OK) return st;
+  if (wq4 == nullptr || wq == nullptr) return SQ_ERR_INVALID_ARG;
+  if (!w4_layout_ok(layer)) return SQ_ERR_UNSUPPORTED;
+  if ((reinterpret_cast<uintptr_t>(wq4) | reinterpret_cast<uintptr_t>(wq)) % 16 != 0) return SQ_ERR_UNSUPPORTED;
+  hipError_t e = sq::launch_unpack_w4(wq4, wq, layer->N, layer->K, sq::device_cus(), reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
 sq_status sq_seglinear_w4(const sq_layer* layer, const int8_t* xq, const uint8_t* wq4, const float* wscale,
                           const float* bias, void* y, sq_dtype y_dt, void* stream) {
   sq_status st = check_layer(layer, true, true);

@@ -712,4 +712,40 @@ hipError_t launch_quantize_weight_w4(const void* w, bool w_is_bf16, uint8_t* wq4
   return hipGetLastError();
 }
 
+// Packed 4-bit codes back to one int8 code per byte, [N][K] row-major: what the large-M tile kernel consumes (there the
+// GEMM is MFMA-bound and 4-bit weights save memory, not time; a caller unpacks a layer into a reusable buffer right
+// before its GEMM).  One thread per 16 packed bytes: the low nibbles are 16 consecutive codes of one row, the high nibbles
+// the 16 codes 64 columns further on.  Sign extension of a nibble u per byte: u | (u & 8) * 0x1E.
+__global__ __launch_bounds__(256) void unpack_w4_kernel(const uint8_t* __restrict__ wq4, int8_t* __restrict__ wq, int N, int K) {
+  const int T = K >> 7;
+  const long nitem = (long)((N + 15) >> 4) * T * 16 * 4;           // (group, step, row, 16-byte chunk)
+  for (long c = blockIdx.x * 256L + threadIdx.x; c < nitem; c += (long)gridDim.x * 256) {
+    const int q = (int)(c & 3), r = (int)((c >> 2) & 15);
+    const long gt = c >> 6;
+    const int t = (int)(gt % T);
+    const long n = (gt / T) * 16 + r;
+    if (n >= N) continue;                                          // rows of the last group beyond N hold padding
+    const v4i p = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(wq4) + c);
+    v4i lo, hi;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      const uint32_t ul = (uint32_t)p[d] & 0x0F0F0F0Fu, uh = ((uint32_t)p[d] >> 4) & 0x0F0F0F0Fu;
+      lo[d] = (int)(ul | ((ul & 0x08080808u) * 0x1Eu));
+      hi[d] = (int)(uh | ((uh & 0x08080808u) * 0x1Eu));
+    }
+    int8_t* dst = wq + n * K + 128 * t + 16 * q;
+    *reinterpret_cast<v4i*>(dst) = lo;
+    *reinterpret_cast<v4i*>(dst + 64) = hi;
+  }
+}
+
+hipError_t launch_unpack_w4(const uint8_t* wq4, int8_t* wq, int N, int K, int cus, hipStream_t st) {
+  const long nitem = (long)((N + 15) >> 4) * (K >> 7) * 64;
+  if (nitem == 0) return hipSuccess;
+  long blocks = (nitem + 255) / 256;
+  if (blocks > (long)cus * 32) blocks = (long)cus * 32;
+  hipLaunchKernelGGL(unpack_w4_kernel, dim3((unsigned)blocks), dim3(256), 0, st, wq4, wq, N, K);
+  return hipGetLastError();
+}
+
 }  // namespace sq

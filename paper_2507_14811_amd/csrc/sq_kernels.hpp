@@ -30,6 +30,7 @@ hipError_t launch_calibrate_act(const void* x, bool x_is_bf16, int M, int K, con
                                 bool accumulate, hipStream_t st);
 
 // dynamic per-token activation steps: tok_steps [2][M][S]
+hipError_t launch_unpack_w4(const uint8_t* wq4, int8_t* wq, int N, int K, int cus, hipStream_t st);
 hipError_t launch_quantize_act_geglu(const void* h, bool h_is_bf16, int8_t* xq, int M, int K, const ActTable& tb, int cus,
                                      hipStream_t st);
 hipError_t launch_quantize_act_dynamic(const void* x, bool x_is_bf16, int8_t* xq, float* tok_steps, int M, int K,

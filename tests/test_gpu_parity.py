@@ -657,6 +657,7 @@ W4CASES = [
     dict(M=64, K=1152, N=1000, kseg=[0, 1152], dual=[1], nseg=None),                       # the large activation slab
     dict(M=100, K=256, N=96, kseg=[0, 256], dual=[1], nseg=None),                          # M > 64: plain kernel
     dict(M=1, K=128, N=16, kseg=[0, 128], dual=[0], nseg=None),
+    dict(M=300, K=640, N=330, kseg=[0, 256, 640], dual=[1, 0], nseg=None, bias=True),      # many token rows, ragged last group
 ]
 
 
@@ -701,6 +702,16 @@ def test_seglinear_w4(oracle, case, force_plain):
         sq.sq_seglinear_w4(gl.layer, gl.xq, wq4, gl.wscale, gl.bias, yb)
         torch.cuda.synchronize()
         g.check_bf16_against(g.bf16_tensor_bits(yb), r.y32, wl.f32_to_bf16_bits(r.y32), 1e-5 * ymax)
+        # unpacked to one code per byte: the oracle's 4-bit codes exactly, and the int8 entry point (whatever kernel it
+        # picks for this shape) gives the 4-bit layer's output with the same scales
+        wq8 = torch.full((N, K), 99, dtype=torch.int8, device=g.DEV)
+        sq.sq_unpack_w4(gl.layer, wq4, wq8)
+        torch.cuda.synchronize()
+        assert np.array_equal(wq8.cpu().numpy(), rq)
+        y8 = torch.full((M, N), float("nan"), dtype=torch.float32, device=g.DEV)
+        sq.sq_seglinear(gl.layer, gl.xq, wq8, gl.wscale, gl.bias, y8)
+        torch.cuda.synchronize()
+        assert float(np.abs(y8.cpu().numpy().astype(np.float64) - r.y32.astype(np.float64)).max()) <= 1e-5 * ymax
     finally:
         sq.sq_tuning_set("force_path", -1)
 

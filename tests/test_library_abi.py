@@ -154,6 +154,9 @@ def test_invalid_arguments_are_rejected_on_the_host(sq):
     assert lib.sq_seglinear_fused(C.byref(_layer(sq, K=192, kseg_off=[0, 192]).c), FAKE, 1, codes(1), FAKE, FAKE, None, FAKE, 0, None) == UNSUPPORTED
     assert lib.sq_seglinear_fused(C.byref(_layer(sq, M=65).c), FAKE, 1, codes(1), FAKE, FAKE, None, FAKE, 0, None) == UNSUPPORTED
     assert lib.sq_seglinear_fused(C.byref(ok.c), C.c_void_p(0x1004), 0, None, FAKE, FAKE, None, FAKE, 0, None) == UNSUPPORTED
+    assert lib.sq_unpack_w4(C.byref(w4.c), None, FAKE, None) == INVALID and lib.sq_unpack_w4(C.byref(w4.c), FAKE, None, None) == INVALID
+    assert lib.sq_unpack_w4(C.byref(_layer(sq, K=192, kseg_off=[0, 192]).c), FAKE, FAKE, None) == UNSUPPORTED
+    assert lib.sq_unpack_w4(C.byref(w4.c), C.c_void_p(0x1008), FAKE, None) == UNSUPPORTED
     fd = lambda layer=ok, x=FAKE, dt=1, act=None, wq=FAKE, bits=8, ws=FAKE, y=FAKE: lib.sq_seglinear_fused_dynamic(
         C.byref(layer.c), x, dt, act, wq, bits, ws, None, y, 0, None)
     assert fd(x=None) == INVALID and fd(wq=None) == INVALID and fd(ws=None) == INVALID and fd(y=None) == INVALID
