@@ -243,14 +243,14 @@ sq_status sq_seglinear_grouped_fused(const sq_layer* layer, const void* x, sq_dt
 /*
  * The same with dynamic per-token activation steps (App. B, 4-bit settings: per-channel 4-bit weights, activations
  * quantized dynamically per token): one launch computes act(x), every token row's steps per K-segment by the min/max rule
- * (as sq_quantize_act_dynamic), the codes, and the GEMM with 8-bit (w_bits == 8, wq int8 [N][K]) or packed 4-bit weights
+ * (as sq_quantize_act_dynamic_bits with the same a_bits, 8 or 4), the codes, and the GEMM with 8-bit (w_bits == 8, wq int8 [N][K]) or packed 4-bit weights
  * (w_bits == 4, wq from sq_quantize_weight_w4).  y equals sq_seglinear_dynamic(sq_quantize_act_dynamic(act(x))) bit for
  * bit.  layer->s_pos / s_neg are not read.  Returns SQ_ERR_UNSUPPORTED where the weight-stream kernel does not apply or
- * the layer has more than 8 K-segments; SQ_ERR_INVALID_ARG for w_bits other than 4 or 8.
+ * the layer has more than 8 K-segments; SQ_ERR_INVALID_ARG for a_bits or w_bits other than 4 or 8.
  */
-sq_status sq_seglinear_fused_dynamic(const sq_layer* layer, const void* x, sq_dtype x_dt, const int32_t* act, const void* wq,
-                                     int32_t w_bits, const float* wscale, const float* bias, void* y, sq_dtype y_dt,
-                                     void* stream);
+sq_status sq_seglinear_fused_dynamic(const sq_layer* layer, const void* x, sq_dtype x_dt, const int32_t* act, int32_t a_bits,
+                                     const void* wq, int32_t w_bits, const float* wscale, const float* bias, void* y,
+                                     sq_dtype y_dt, void* stream);
 
 /*
  * Parity instrument: runs the same main loop as sq_seglinear (same kernel selection) and stores the
@@ -316,6 +316,12 @@ sq_status sq_seglinear_w4_debug_acc(const sq_layer* layer, const int8_t* xq, con
  */
 sq_status sq_quantize_act_dynamic(const sq_layer* layer, const void* x, sq_dtype x_dt, int8_t* xq, float* tok_steps,
                                   void* stream);
+/* The same with a_bits-wide activation codes (Sec. 3: q_max = 2^(a_bits-1) - 1): a_bits == 8 is sq_quantize_act_dynamic,
+ * a_bits == 4 gives the 4-bit activations of the paper's W4A4 setting (steps = row extreme / 7, codes in [-7, 7], still
+ * one code per byte: the matrix units of this device have no 4-bit integer operands, so the codes run through the int8
+ * kernels unchanged and sq_seglinear_dynamic needs no a_bits of its own).  SQ_ERR_INVALID_ARG for other widths. */
+sq_status sq_quantize_act_dynamic_bits(const sq_layer* layer, const void* x, sq_dtype x_dt, int32_t a_bits, int8_t* xq,
+                                       float* tok_steps, void* stream);
 sq_status sq_seglinear_dynamic(const sq_layer* layer, const int8_t* xq, const float* tok_steps, const void* wq,
                                int32_t w_bits, const float* wscale, const float* bias, void* y, sq_dtype y_dt,
                                void* stream);

@@ -306,27 +306,33 @@ def seglinear(x, w, kseg_off, nseg_off, dual, s_pos, s_neg, seg_scale=None, bias
     return OracleResult(wq, ws, xp, xn, None if rows is None else np.asarray(rows), ap, an, y32, y64)
 
 
-def quantize_act_dynamic(x, kseg_off, dual):
+def quantize_act_dynamic(x, kseg_off, dual, abits: int = 8):
     """Dynamic per-token steps (App. B: in the 4-bit settings activations are quantized dynamically per token): every
     token row is calibrated on its own with the min/max rule (calibrate_act on that row) and quantized with its own
-    steps.  -> (xq_pos, xq_neg int8 [M][K], s_pos, s_neg fp32 [M][S])"""
+    steps.  abits: width of the activation codes, q_max = 2^(abits-1) - 1 (Sec. 3; 127, or 7 for 4-bit activations):
+    steps = row extreme / q_max, codes clipped to [-q_max, q_max].
+    -> (xq_pos, xq_neg int8 [M][K], s_pos, s_neg fp32 [M][S])"""
     x = _f32(x)
     M, K = x.shape
     S = len(kseg_off) - 1
+    q = np.float32(2 ** (abits - 1) - 1)
     xp = np.empty((M, K), np.int8)
     xn = np.empty((M, K), np.int8)
     sp = np.empty((M, S), np.float32)
     sn = np.empty((M, S), np.float32)
     for m in range(M):
-        sp[m], sn[m], _, _ = calibrate_act(x[m:m + 1], kseg_off, dual)
+        sp[m], sn[m], ap, an = calibrate_act(x[m:m + 1], kseg_off, dual)
+        if abits != 8:
+            sp[m] = np.where(ap == 0, np.float32(1.0), ap / q)
+            sn[m] = np.where(an == 0, np.float32(1.0), an / q)
         xp[m:m + 1], xn[m:m + 1] = quantize_act(x[m:m + 1], kseg_off, dual, sp[m], sn[m])
-    return xp, xn, sp, sn
+    return np.clip(xp, -int(q), int(q)), np.clip(xn, -int(q), int(q)), sp, sn
 
 
-def seglinear_dynamic(x, w, kseg_off, nseg_off, dual, seg_scale=None, bias=None, wbits=8) -> OracleResult:
+def seglinear_dynamic(x, w, kseg_off, nseg_off, dual, seg_scale=None, bias=None, wbits=8, abits=8) -> OracleResult:
     """The layer with dynamic per-token activation steps: the steps of the dequantization are those of the token."""
     wq, ws = quantize_weight(w, kseg_off) if wbits == 8 else quantize_weight_w4(w, kseg_off)
-    xp, xn, sp, sn = quantize_act_dynamic(x, kseg_off, dual)
+    xp, xn, sp, sn = quantize_act_dynamic(x, kseg_off, dual, abits)
     ap, an = int_gemm(xp, xn, wq, kseg_off, dual)
     M, N = x.shape[0], w.shape[0]
     y32 = np.empty((M, N), np.float32)

@@ -27,7 +27,7 @@ EXPORTS = ("sq_quantize_weight", "sq_quantize_act", "sq_seglinear", "sq_seglinea
            "sq_quantize_act_fused_workspace_bytes", "sq_quantize_weight_w4", "sq_seglinear_w4",
            "sq_seglinear_w4_debug_acc", "sq_quantize_act_dynamic", "sq_seglinear_dynamic",
            "sq_seglinear_fused", "sq_seglinear_grouped_fused", "sq_quantize_act_geglu",
-           "sq_seglinear_fused_dynamic", "sq_unpack_w4")
+           "sq_seglinear_fused_dynamic", "sq_unpack_w4", "sq_quantize_act_dynamic_bits")
 
 
 class SqError(RuntimeError):
@@ -102,7 +102,9 @@ def load_library() -> C.CDLL:
     lib.sq_seglinear_fused.restype = i32
     lib.sq_unpack_w4.argtypes = [lp, vp, vp, vp]
     lib.sq_unpack_w4.restype = i32
-    lib.sq_seglinear_fused_dynamic.argtypes = [lp, vp, i32, C.POINTER(C.c_int32), vp, i32, vp, vp, vp, i32, vp]
+    lib.sq_seglinear_fused_dynamic.argtypes = [lp, vp, i32, C.POINTER(C.c_int32), i32, vp, i32, vp, vp, vp, i32, vp]
+    lib.sq_quantize_act_dynamic_bits.argtypes = [lp, vp, i32, i32, vp, vp, vp]
+    lib.sq_quantize_act_dynamic_bits.restype = i32
     lib.sq_seglinear_fused_dynamic.restype = i32
     lib.sq_seglinear_grouped_fused.argtypes = [lp, vp, i32, C.POINTER(C.c_int32), i32, C.POINTER(sq_group_item), i32, vp]
     lib.sq_seglinear_grouped_fused.restype = i32
@@ -297,6 +299,12 @@ def sq_quantize_act_dynamic(layer: Layer, x, xq, tok_steps, stream=None) -> None
                                                   _stream(stream)), "sq_quantize_act_dynamic")
 
 
+def sq_quantize_act_dynamic_bits(layer: Layer, x, a_bits: int, xq, tok_steps, stream=None) -> None:
+    """sq_quantize_act_dynamic with a_bits-wide activation codes (8, or 4: codes in [-7, 7], one per byte)."""
+    _check(load_library().sq_quantize_act_dynamic_bits(C.byref(layer.c), _dptr(x), _dt(x), int(a_bits), _dptr(xq),
+                                                       _dptr(tok_steps), _stream(stream)), "sq_quantize_act_dynamic_bits")
+
+
 def sq_seglinear_dynamic(layer: Layer, xq, tok_steps, wq, w_bits: int, wscale, bias, y, stream=None) -> None:
     """The layer with per-token steps; wq: int8 [N][K] (w_bits 8) or packed 4-bit codes (w_bits 4)."""
     _check(load_library().sq_seglinear_dynamic(C.byref(layer.c), _dptr(xq), _dptr(tok_steps), _dptr(wq), int(w_bits),
@@ -342,12 +350,12 @@ def sq_seglinear_fused(layer: Layer, x, act, wq, wscale, bias, y, stream=None) -
            "sq_seglinear_fused")
 
 
-def sq_seglinear_fused_dynamic(layer: Layer, x, act, wq, w_bits, wscale, bias, y, stream=None) -> None:
+def sq_seglinear_fused_dynamic(layer: Layer, x, act, wq, w_bits, wscale, bias, y, a_bits=8, stream=None) -> None:
     """sq_seglinear_fused with per-token activation steps found inside the launch; wq: int8 [N][K] (w_bits 8) or the packed
-    4-bit codes of sq_quantize_weight_w4 (w_bits 4)."""
-    _check(load_library().sq_seglinear_fused_dynamic(C.byref(layer.c), _dptr(x), _dt(x), _act_codes(layer, act), _dptr(wq),
-                                                     int(w_bits), _dptr(wscale), _dptr(bias), _dptr(y), _dt(y),
-                                                     _stream(stream)), "sq_seglinear_fused_dynamic", "sq_unpack_w4")
+    4-bit codes of sq_quantize_weight_w4 (w_bits 4); a_bits: width of the activation codes (8 or 4)."""
+    _check(load_library().sq_seglinear_fused_dynamic(C.byref(layer.c), _dptr(x), _dt(x), _act_codes(layer, act), int(a_bits),
+                                                     _dptr(wq), int(w_bits), _dptr(wscale), _dptr(bias), _dptr(y), _dt(y),
+                                                     _stream(stream)), "sq_seglinear_fused_dynamic")
 
 
 def sq_seglinear_grouped_fused(layer: Layer, x, act, items, stream=None) -> None:

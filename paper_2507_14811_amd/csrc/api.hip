@@ -475,20 +475,29 @@ sq_status sq_seglinear_w4_debug_acc(const sq_layer* layer, const int8_t* xq, con
   return run_gemm_w4(layer, xq, wq4, nullptr, nullptr, nullptr, acc_pos, acc_neg, sq::OUT_DEBUG_ACC, stream);
 }
 
-sq_status sq_quantize_act_dynamic(const sq_layer* layer, const void* x, sq_dtype x_dt, int8_t* xq, float* tok_steps,
-                                  void* stream) {
+// Largest code of a_bits-wide symmetric activation codes (Sec. 3: q_max = 2^(b-1) - 1); 0 for widths not offered.
+static float act_qmax(int32_t a_bits) { return a_bits == 8 ? 127.0f : a_bits == 4 ? 7.0f : 0.0f; }
+
+sq_status sq_quantize_act_dynamic_bits(const sq_layer* layer, const void* x, sq_dtype x_dt, int32_t a_bits, int8_t* xq,
+                                       float* tok_steps, void* stream) {
   sq_status st = check_layer(layer, true, false);
   if (st != SQ_OK) return st;
   if (x == nullptr || xq == nullptr || tok_steps == nullptr) return SQ_ERR_INVALID_ARG;
   if (x_dt != SQ_F32 && x_dt != SQ_BF16) return SQ_ERR_INVALID_ARG;
+  if (act_qmax(a_bits) == 0.0f) return SQ_ERR_INVALID_ARG;
   sq::ActTable tb;
   std::memset(&tb, 0, sizeof(tb));
   tb.S = layer->S;
   for (int s = 0; s <= layer->S; ++s) tb.kseg_off[s] = layer->kseg_off[s];
   for (int s = 0; s < layer->S; ++s) tb.dual[s] = layer->dual[s] ? 1 : 0;
-  hipError_t e = sq::launch_quantize_act_dynamic(x, x_dt == SQ_BF16, xq, tok_steps, layer->M, layer->K, tb,
+  hipError_t e = sq::launch_quantize_act_dynamic(x, x_dt == SQ_BF16, xq, tok_steps, layer->M, layer->K, tb, act_qmax(a_bits),
                                                  reinterpret_cast<hipStream_t>(stream));
   return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
+sq_status sq_quantize_act_dynamic(const sq_layer* layer, const void* x, sq_dtype x_dt, int8_t* xq, float* tok_steps,
+                                  void* stream) {
+  return sq_quantize_act_dynamic_bits(layer, x, x_dt, 8, xq, tok_steps, stream);
 }
 
 sq_status sq_seglinear_dynamic(const sq_layer* layer, const int8_t* xq, const float* tok_steps, const void* wq,
@@ -503,14 +512,14 @@ sq_status sq_seglinear_dynamic(const sq_layer* layer, const int8_t* xq, const fl
                           stream);
 }
 
-sq_status sq_seglinear_fused_dynamic(const sq_layer* layer, const void* x, sq_dtype x_dt, const int32_t* act, const void* wq,
-                                     int32_t w_bits, const float* wscale, const float* bias, void* y, sq_dtype y_dt,
-                                     void* stream) {
+sq_status sq_seglinear_fused_dynamic(const sq_layer* layer, const void* x, sq_dtype x_dt, const int32_t* act, int32_t a_bits,
+                                     const void* wq, int32_t w_bits, const float* wscale, const float* bias, void* y,
+                                     sq_dtype y_dt, void* stream) {
   sq_status st = check_layer(layer, true, false);
   if (st != SQ_OK) return st;
   if (x == nullptr || wq == nullptr || wscale == nullptr || y == nullptr) return SQ_ERR_INVALID_ARG;
   if ((x_dt != SQ_F32 && x_dt != SQ_BF16) || (y_dt != SQ_F32 && y_dt != SQ_BF16)) return SQ_ERR_INVALID_ARG;
-  if (w_bits != 8 && w_bits != 4) return SQ_ERR_INVALID_ARG;
+  if ((w_bits != 8 && w_bits != 4) || act_qmax(a_bits) == 0.0f) return SQ_ERR_INVALID_ARG;
   if (w_bits == 4 && !w4_layout_ok(layer)) return SQ_ERR_UNSUPPORTED;
   sq::GemmTable tb;
   fill_gemm_table(layer, tb);
@@ -534,6 +543,7 @@ sq_status sq_seglinear_fused_dynamic(const sq_layer* layer, const void* x, sq_dt
   a.x_raw = x;
   a.x_raw_bf16 = x_dt == SQ_BF16 ? 1 : 0;
   a.x_raw_dynamic = 1;
+  a.act_qmax = act_qmax(a_bits);
   if (layer->S > 8 || reinterpret_cast<uintptr_t>(x) % 16 != 0 || !sq::stream_supported(a, tb)) return SQ_ERR_UNSUPPORTED;
   const sq::OutMode mode = y_dt == SQ_BF16 ? sq::OUT_BF16 : sq::OUT_F32;
   hipStream_t hs = reinterpret_cast<hipStream_t>(stream);

@@ -367,7 +367,7 @@ hipError_t launch_quantize_weight_block(const void* w, bool w_is_bf16, int8_t* w
 template <bool BF16>
 __global__ __launch_bounds__(256) void quantize_act_dynamic_kernel(const void* __restrict__ x, int8_t* __restrict__ xq,
                                                                    float* __restrict__ tok_steps, int M, int K,
-                                                                   const ActTable tb) {
+                                                                   const ActTable tb, const float qmax) {
   const int m = blockIdx.x;
   const size_t row = (size_t)m * K;
   __shared__ float red[2][4];
@@ -395,7 +395,7 @@ __global__ __launch_bounds__(256) void quantize_act_dynamic_kernel(const void* _
     if (threadIdx.x == 0) {
       mp = __builtin_fmaxf(__builtin_fmaxf(red[0][0], red[0][1]), __builtin_fmaxf(red[0][2], red[0][3]));
       mn = __builtin_fmaxf(__builtin_fmaxf(red[1][0], red[1][1]), __builtin_fmaxf(red[1][2], red[1][3]));
-      const float sp = (mp == 0.0f) ? 1.0f : mp / kQmax, sn = (mn == 0.0f) ? 1.0f : mn / kQmax;
+      const float sp = (mp == 0.0f) ? 1.0f : mp / qmax, sn = (mn == 0.0f) ? 1.0f : mn / qmax;
       stp[0] = sp;
       stp[1] = sn;
       tok_steps[(size_t)m * tb.S + ks] = sp;
@@ -420,7 +420,7 @@ __global__ __launch_bounds__(256) void quantize_act_dynamic_kernel(const void* _
 template <bool BF16, int NCH>
 __global__ __launch_bounds__(256) void quantize_act_dynamic_fast_kernel(const void* __restrict__ x, int8_t* __restrict__ xq,
                                                                         float* __restrict__ tok_steps, int M, int K,
-                                                                        const ActTable tb) {
+                                                                        const ActTable tb, const float qmax) {
   constexpr int NL = BF16 ? 2 : 4;                       // 16-byte loads per chunk
   const int m = blockIdx.x;
   const size_t row = (size_t)m * K;
@@ -513,7 +513,7 @@ __global__ __launch_bounds__(256) void quantize_act_dynamic_fast_kernel(const vo
     if (threadIdx.x == 0) {
       mp = __builtin_fmaxf(__builtin_fmaxf(red[0][0], red[0][1]), __builtin_fmaxf(red[0][2], red[0][3]));
       mn = __builtin_fmaxf(__builtin_fmaxf(red[1][0], red[1][1]), __builtin_fmaxf(red[1][2], red[1][3]));
-      const float sp = (mp == 0.0f) ? 1.0f : mp / kQmax, sn = (mn == 0.0f) ? 1.0f : mn / kQmax;
+      const float sp = (mp == 0.0f) ? 1.0f : mp / qmax, sn = (mn == 0.0f) ? 1.0f : mn / qmax;
       stp[ks][0] = sp;
       stp[ks][1] = sn;
       stp[ks][2] = (sp >= 1e-30f && sp <= 1e30f) ? 1.0f / sp : __builtin_nanf("");
@@ -556,19 +556,19 @@ __global__ __launch_bounds__(256) void quantize_act_dynamic_fast_kernel(const vo
 }
 
 hipError_t launch_quantize_act_dynamic(const void* x, bool x_is_bf16, int8_t* xq, float* tok_steps, int M, int K,
-                                       const ActTable& tb, hipStream_t st) {
+                                       const ActTable& tb, float qmax, hipStream_t st) {
   bool fast = K % 16 == 0 && K <= 4096 * 8 && (reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(xq)) % 16 == 0;
   for (int s = 0; s <= tb.S; ++s) fast = fast && tb.kseg_off[s] % 16 == 0;
   if (fast) {
-#define SQ_D(B, N) hipLaunchKernelGGL((quantize_act_dynamic_fast_kernel<B, N>), dim3(M), dim3(256), 0, st, x, xq, tok_steps, M, K, tb)
+#define SQ_D(B, N) hipLaunchKernelGGL((quantize_act_dynamic_fast_kernel<B, N>), dim3(M), dim3(256), 0, st, x, xq, tok_steps, M, K, tb, qmax)
 #define SQ_DN(B) do { if (K <= 4096) SQ_D(B, 1); else if (K <= 8192) SQ_D(B, 2); else if (K <= 16384) SQ_D(B, 4); else SQ_D(B, 8); } while (0)
     if (x_is_bf16) SQ_DN(true); else SQ_DN(false);
 #undef SQ_DN
 #undef SQ_D
     return hipGetLastError();
   }
-  if (x_is_bf16) hipLaunchKernelGGL((quantize_act_dynamic_kernel<true>), dim3(M), dim3(256), 0, st, x, xq, tok_steps, M, K, tb);
-  else           hipLaunchKernelGGL((quantize_act_dynamic_kernel<false>), dim3(M), dim3(256), 0, st, x, xq, tok_steps, M, K, tb);
+  if (x_is_bf16) hipLaunchKernelGGL((quantize_act_dynamic_kernel<true>), dim3(M), dim3(256), 0, st, x, xq, tok_steps, M, K, tb, qmax);
+  else           hipLaunchKernelGGL((quantize_act_dynamic_kernel<false>), dim3(M), dim3(256), 0, st, x, xq, tok_steps, M, K, tb, qmax);
   return hipGetLastError();
 }
 

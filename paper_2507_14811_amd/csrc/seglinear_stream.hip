@@ -312,7 +312,7 @@ __global__ __launch_bounds__(stream_waves(MT) * 64) void seglinear_stream_kernel
       lds_barrier();
       for (int i = threadIdx.x; i < ntab; i += NT) {
         const float m = __uint_as_float(amax[i]);
-        tok[i] = (m == 0.0f) ? 1.0f : m / kQmax;
+        tok[i] = (m == 0.0f) ? 1.0f : m / a.act_qmax;
       }
       lds_barrier();
       auto code_item = [&](const int c, const float (&av)[4]) __attribute__((always_inline)) {

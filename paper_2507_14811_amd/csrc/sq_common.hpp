@@ -86,6 +86,7 @@ struct GemmArgs {
   const void* x_raw;               // weight-stream kernel: activations [M][K] (bf16 or fp32) to be quantized (after the
   int x_raw_bf16;                  // table's activation) into the LDS slab by the kernel itself; nullptr: xq holds codes
   int x_raw_dynamic;               // with x_raw: per-token steps found by the kernel (min/max rule per row and K-segment)
+  float act_qmax;                  //   largest activation code of those steps (127, or 7 for 4-bit activation codes)
 };
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }

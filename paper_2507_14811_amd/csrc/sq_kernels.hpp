@@ -34,7 +34,7 @@ hipError_t launch_unpack_w4(const uint8_t* wq4, int8_t* wq, int N, int K, int cu
 hipError_t launch_quantize_act_geglu(const void* h, bool h_is_bf16, int8_t* xq, int M, int K, const ActTable& tb, int cus,
                                      hipStream_t st);
 hipError_t launch_quantize_act_dynamic(const void* x, bool x_is_bf16, int8_t* xq, float* tok_steps, int M, int K,
-                                       const ActTable& tb, hipStream_t st);
+                                       const ActTable& tb, float qmax, hipStream_t st);
 
 // 4-bit weights, packed two per byte (K and K-segment boundaries multiples of 128)
 hipError_t launch_quantize_weight_w4(const void* w, bool w_is_bf16, uint8_t* wq4, float* wscale, int N, int K,

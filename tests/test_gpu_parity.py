@@ -769,6 +769,19 @@ def test_seglinear_dynamic(oracle, case):
     gl = g.GpuLayer(w)
     S = w.S
     tok = torch.full((2, M, S), float("nan"), dtype=torch.float32, device=g.DEV)
+    # 4-bit activation codes first (the W4A4 setting): codes and steps bit-exact, the layer through the same GEMM
+    xq4 = torch.full((M, K), 99, dtype=torch.int8, device=g.DEV)
+    sq.sq_quantize_act_dynamic_bits(gl.layer, gl.x, 4, xq4, tok)
+    torch.cuda.synchronize()
+    r4 = oracle.seglinear_dynamic(w.x, w.w, w.kseg_off, w.nseg_off, w.dual, w.seg_scale, w.bias, wbits=8, abits=4)
+    xp4, xn4 = g.split_codes(w, xq4.cpu().numpy())
+    assert np.array_equal(xp4, r4.xq_pos) and np.array_equal(xn4, r4.xq_neg) and np.abs(xq4.cpu().numpy()).max() == 7
+    assert np.array_equal(tok.cpu().numpy().view(np.uint32), r4.tok_steps.view(np.uint32))
+    gl.quantize_weight()
+    y4 = torch.full((M, N), float("nan"), dtype=torch.float32, device=g.DEV)
+    sq.sq_seglinear_dynamic(gl.layer, xq4, tok, gl.wq, 8, gl.wscale, gl.bias, y4)
+    torch.cuda.synchronize()
+    assert float(np.abs(y4.cpu().numpy().astype(np.float64) - r4.y32.astype(np.float64)).max()) <= 1e-5 * float(np.abs(r4.y32).max())
     sq.sq_quantize_act_dynamic(gl.layer, gl.x, gl.xq, tok)
     torch.cuda.synchronize()
     for bits in case.get("bits", (8, 4)):
@@ -987,6 +1000,12 @@ def test_seglinear_fused_dynamic(oracle, case):
         else:
             wq = torch.empty((((N + 15) // 16) * 16 * (K // 2),), dtype=torch.uint8, device=g.DEV)
             sq.sq_quantize_weight_w4(layer, wt, wq, ws)
+        r4 = oracle.seglinear_dynamic(a, w, case["kseg"], [0, N], case["dual"], None, b, wbits=bits, abits=4)
+        y = torch.full((M, N), float("nan"), dtype=torch.float32, device=g.DEV)
+        sq.sq_seglinear_fused_dynamic(layer, hd, case["act"], wq, bits, ws, bd, y, a_bits=4)      # the W4A4 / W8A4 settings
+        torch.cuda.synchronize()
+        err4 = float(np.abs(y.cpu().numpy().astype(np.float64) - r4.y32.astype(np.float64)).max())
+        assert err4 <= RTOL * float(np.abs(r4.y32).max()), (bits, err4)
         r = oracle.seglinear_dynamic(a, w, case["kseg"], [0, N], case["dual"], None, b, wbits=bits)
         ymax = float(np.abs(r.y32).max())
         y = torch.full((M, N), float("nan"), dtype=torch.float32, device=g.DEV)

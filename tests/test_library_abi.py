@@ -157,10 +157,12 @@ def test_invalid_arguments_are_rejected_on_the_host(sq):
     assert lib.sq_unpack_w4(C.byref(w4.c), None, FAKE, None) == INVALID and lib.sq_unpack_w4(C.byref(w4.c), FAKE, None, None) == INVALID
     assert lib.sq_unpack_w4(C.byref(_layer(sq, K=192, kseg_off=[0, 192]).c), FAKE, FAKE, None) == UNSUPPORTED
     assert lib.sq_unpack_w4(C.byref(w4.c), C.c_void_p(0x1008), FAKE, None) == UNSUPPORTED
-    fd = lambda layer=ok, x=FAKE, dt=1, act=None, wq=FAKE, bits=8, ws=FAKE, y=FAKE: lib.sq_seglinear_fused_dynamic(
-        C.byref(layer.c), x, dt, act, wq, bits, ws, None, y, 0, None)
+    fd = lambda layer=ok, x=FAKE, dt=1, act=None, abits=8, wq=FAKE, bits=8, ws=FAKE, y=FAKE: lib.sq_seglinear_fused_dynamic(
+        C.byref(layer.c), x, dt, act, abits, wq, bits, ws, None, y, 0, None)
     assert fd(x=None) == INVALID and fd(wq=None) == INVALID and fd(ws=None) == INVALID and fd(y=None) == INVALID
-    assert fd(dt=7) == INVALID and fd(bits=5) == INVALID and fd(act=codes(9)) == INVALID
+    assert fd(dt=7) == INVALID and fd(bits=5) == INVALID and fd(act=codes(9)) == INVALID and fd(abits=6) == INVALID
+    assert lib.sq_quantize_act_dynamic_bits(C.byref(ok.c), FAKE, 1, 5, FAKE, FAKE, None) == INVALID
+    assert lib.sq_quantize_act_dynamic_bits(C.byref(ok.c), FAKE, 1, 4, FAKE, None, None) == INVALID
     assert fd(layer=_layer(sq, K=192, kseg_off=[0, 192])) == UNSUPPORTED and fd(layer=_layer(sq, M=65)) == UNSUPPORTED
     assert fd(layer=_layer(sq, K=192, kseg_off=[0, 192]), bits=4) == UNSUPPORTED
     nine = _layer(sq, K=128 * 9, kseg_off=[128 * i for i in range(10)], dual=[1] * 9, s_pos=[0.5] * 9, s_neg=[0.5] * 9)

@@ -709,3 +709,34 @@ def test_geglu_against_closed_form_and_landmarks(oracle):
     assert np.array_equal(xp, rp) and np.array_equal(xn, rn) and xp.max() == 127 and xn[:, :16].min() == -127
     with pytest.raises(ValueError):
         oracle.geglu(np.zeros((2, 5), np.float32))
+
+
+def test_dynamic_steps_with_4bit_activation_codes(oracle):
+    """a_bits = 4 (the W4A4 setting): q_max = 2^3 - 1 = 7 (Sec. 3), steps = row extreme / 7, the extreme itself gets code
+    +-7, nothing leaves [-7, 7], the dequantized value is within half a step, and 8 bits is the default unchanged."""
+    rng = np.random.default_rng(4)
+    x = (rng.standard_normal((6, 96)) * rng.uniform(0.5, 4.0, size=(6, 1))).astype(np.float32)
+    kseg, dual = [0, 32, 96], [1, 0]
+    xp, xn, sp, sn = oracle.quantize_act_dynamic(x, kseg, dual, abits=4)
+    xp8, xn8, sp8, sn8 = oracle.quantize_act_dynamic(x, kseg, dual)
+    d8 = oracle.quantize_act_dynamic(x, kseg, dual, abits=8)
+    assert all(np.array_equal(a, b) for a, b in zip((xp8, xn8, sp8, sn8), d8))
+    assert xp.max() == 7 and xp[:, :32].min() >= 0 and xn.min() == -7 and xn.max() <= 0 and not xn[:, 32:].any()
+    assert np.abs(xp[:, 32:].astype(int) + xn[:, 32:].astype(int)).max() == 7          # single-scale segment: |code| <= 7
+    q7, q127 = np.float32(7), np.float32(127)
+    for m in range(6):
+        assert sp[m, 0] == x[m, :32].max() / q7 and sn[m, 0] == (-x[m, :32].min()) / q7
+        assert sp[m, 1] == np.abs(x[m, 32:]).max() / q7 and sn[m, 1] == 1.0
+        assert sp8[m, 0] == x[m, :32].max() / q127
+        k = int(np.argmax(x[m, :32]))
+        assert xp[m, k] == 7 and xn[m, int(np.argmin(x[m, :32]))] == -7
+        deq = xp[m, :32] * np.float64(sp[m, 0]) + xn[m, :32] * np.float64(sn[m, 0])
+        half = np.where(x[m, :32] >= 0, sp[m, 0], sn[m, 0]) / 2
+        assert np.all(np.abs(deq - x[m, :32]) <= half * (1 + 1e-6))
+    # the layer: with 4-bit codes the error grows (coarser steps) but stays inside its bound direction
+    w = (rng.standard_normal((40, 96)) * 0.05).astype(np.float32)
+    r4 = oracle.seglinear_dynamic(x, w, kseg, [0, 40], dual, abits=4)
+    r8 = oracle.seglinear_dynamic(x, w, kseg, [0, 40], dual, abits=8)
+    yfp = oracle.fp_reference(x, w)
+    e4, e8 = np.linalg.norm(r4.y64 - yfp), np.linalg.norm(r8.y64 - yfp)
+    assert e8 < e4 < 40 * e8
