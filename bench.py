@@ -252,17 +252,23 @@ def measure_grouped(layers=28, steps=50):
     xq = torch.empty((w.M, w.K), dtype=torch.int8, device=dev)
     sq.sq_quantize_act(layer, x, xq)
     nsets = 3                                   # 3 x 28 x 8 MB = 669 MB of weights > 2 x Infinity Cache... of 256 MB
-    sets = []
+    sets, sets4 = [], []
     for si in range(nsets):
-        items = []
+        items, items4 = [], []
         for l in range(layers):
             wl_l = wl.make("cfg3", seed=1000 + si * layers + l)
             wt = torch.from_numpy(wl_l.w).to(dev)
             wq = torch.empty((w.N, w.K), dtype=torch.int8, device=dev)
             ws = torch.empty((w.S, w.N), dtype=torch.float32, device=dev)
             sq.sq_quantize_weight(layer, wt, wq, ws)
-            items.append((wq, ws, None, torch.empty((w.M, w.N), dtype=torch.bfloat16, device=dev)))
+            y = torch.empty((w.M, w.N), dtype=torch.bfloat16, device=dev)
+            items.append((wq, ws, None, y))
+            wq4 = torch.empty((((w.N + 15) // 16) * 16 * (w.K // 2),), dtype=torch.uint8, device=dev)
+            ws4 = torch.empty((w.S, w.N), dtype=torch.float32, device=dev)
+            sq.sq_quantize_weight_w4(layer, wt, wq4, ws4)
+            items4.append((wq4, ws4, None, y))
         sets.append(sq.GroupItems(items))       # marshalled once: filling 28 items costs more host time than the launch
+        sets4.append(sq.GroupItems(items4))
     torch.cuda.synchronize()
 
     def run_all():
@@ -315,8 +321,24 @@ def measure_grouped(layers=28, steps=50):
             sq.sq_seglinear_grouped(layer, xq, items)
 
     ms_one, ms_two = timed(one_launch), timed(two_launches)
+
+    # the same group with packed 4-bit weights, static and per-token steps (3 sets = 334 MB: above the Infinity Cache)
+    tok = torch.empty((2, w.M, w.S), dtype=torch.float32, device=dev)
+    xq_d = torch.empty_like(xq)
+    sq.sq_quantize_act_dynamic(layer, x, xq_d, tok)
+
+    def w4_static():
+        for items in sets4:
+            sq.sq_seglinear_grouped_w4(layer, xq, items)
+
+    def w4_dynamic():
+        for items in sets4:
+            sq.sq_seglinear_grouped_w4(layer, xq_d, items, tok_steps=tok)
+
+    ms_w4, ms_w4_dyn = timed(w4_static), timed(w4_dynamic)
     return {"layers": layers, "silu_in_front": {"ms_one_launch_raw_input": round(ms_one, 5),
-                                                "ms_quantize_then_grouped": round(ms_two, 5)}, "M": w.M, "K": w.K, "N": w.N, "ms_per_launch": round(ms, 5), "bytes": byt,
+                                                "ms_quantize_then_grouped": round(ms_two, 5)},
+            "w4": {"ms_per_launch": round(ms_w4, 5), "ms_per_launch_dynamic_token_steps": round(ms_w4_dyn, 5)}, "M": w.M, "K": w.K, "N": w.N, "ms_per_launch": round(ms, 5), "bytes": byt,
             "gbs_from_hbm": round(byt / (ms * 1e-3) / 1e9, 1), "frac_hbm_peak": round(byt / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
             "ms_same_layers_one_call_each": round(ms_single, 5), "weight_sets_rotated": nsets}
 

@@ -241,6 +241,16 @@ sq_status sq_seglinear_grouped_fused(const sq_layer* layer, const void* x, sq_dt
                                      const sq_group_item* items, sq_dtype y_dt, void* stream);
 
 /*
+ * The grouped call of the 4-bit settings (App. B): the items' wq point to the packed 4-bit codes of sq_quantize_weight_w4
+ * (cast to const int8_t*), wscale are its per-channel scales.  tok_steps: NULL for the layer's static activation steps,
+ * or the fp32 [2][M][S] per-token steps of sq_quantize_act_dynamic(_bits) that produced xq (then layer->s_pos / s_neg are
+ * not read, and at most 8 K-segments).  Per layer the arithmetic is that of sq_seglinear_w4 / sq_seglinear_dynamic.
+ * Limits as for sq_seglinear_grouped.
+ */
+sq_status sq_seglinear_grouped_w4(const sq_layer* layer, const int8_t* xq, const float* tok_steps, int32_t L,
+                                  const sq_group_item* items, sq_dtype y_dt, void* stream);
+
+/*
  * The same with dynamic per-token activation steps (App. B, 4-bit settings: per-channel 4-bit weights, activations
  * quantized dynamically per token): one launch computes act(x), every token row's steps per K-segment by the min/max rule
  * (as sq_quantize_act_dynamic_bits with the same a_bits, 8 or 4), the codes, and the GEMM with 8-bit (w_bits == 8, wq int8 [N][K]) or packed 4-bit weights

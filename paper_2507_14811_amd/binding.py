@@ -27,7 +27,7 @@ EXPORTS = ("sq_quantize_weight", "sq_quantize_act", "sq_seglinear", "sq_seglinea
            "sq_quantize_act_fused_workspace_bytes", "sq_quantize_weight_w4", "sq_seglinear_w4",
            "sq_seglinear_w4_debug_acc", "sq_quantize_act_dynamic", "sq_seglinear_dynamic",
            "sq_seglinear_fused", "sq_seglinear_grouped_fused", "sq_quantize_act_geglu",
-           "sq_seglinear_fused_dynamic", "sq_unpack_w4", "sq_quantize_act_dynamic_bits")
+           "sq_seglinear_fused_dynamic", "sq_unpack_w4", "sq_quantize_act_dynamic_bits", "sq_seglinear_grouped_w4")
 
 
 class SqError(RuntimeError):
@@ -106,6 +106,8 @@ def load_library() -> C.CDLL:
     lib.sq_quantize_act_dynamic_bits.argtypes = [lp, vp, i32, i32, vp, vp, vp]
     lib.sq_quantize_act_dynamic_bits.restype = i32
     lib.sq_seglinear_fused_dynamic.restype = i32
+    lib.sq_seglinear_grouped_w4.argtypes = [lp, vp, vp, i32, C.POINTER(sq_group_item), i32, vp]
+    lib.sq_seglinear_grouped_w4.restype = i32
     lib.sq_seglinear_grouped_fused.argtypes = [lp, vp, i32, C.POINTER(C.c_int32), i32, C.POINTER(sq_group_item), i32, vp]
     lib.sq_seglinear_grouped_fused.restype = i32
     lib.sq_probe_mfma.argtypes = [vp, C.c_size_t, i32, C.POINTER(C.c_double), vp]
@@ -356,6 +358,14 @@ def sq_seglinear_fused_dynamic(layer: Layer, x, act, wq, w_bits, wscale, bias, y
     _check(load_library().sq_seglinear_fused_dynamic(C.byref(layer.c), _dptr(x), _dt(x), _act_codes(layer, act), int(a_bits),
                                                      _dptr(wq), int(w_bits), _dptr(wscale), _dptr(bias), _dptr(y), _dt(y),
                                                      _stream(stream)), "sq_seglinear_fused_dynamic")
+
+
+def sq_seglinear_grouped_w4(layer: Layer, xq, items, tok_steps=None, stream=None) -> None:
+    """sq_seglinear_grouped with packed 4-bit weights in the items (wq4 of sq_quantize_weight_w4); tok_steps: None for
+    the layer's static steps, or the per-token steps [2][M][S] that belong to xq."""
+    g = items if isinstance(items, GroupItems) else GroupItems(items)
+    _check(load_library().sq_seglinear_grouped_w4(C.byref(layer.c), _dptr(xq), _dptr(tok_steps), g.n, g.arr, g.y_dt,
+                                                  _stream(stream)), "sq_seglinear_grouped_w4")
 
 
 def sq_seglinear_grouped_fused(layer: Layer, x, act, items, stream=None) -> None:

@@ -365,9 +365,13 @@ sq_status sq_seglinear_fused(const sq_layer* layer, const void* x, sq_dtype x_dt
 }
 
 static sq_status grouped_common(const sq_layer* layer, const int8_t* xq, const void* x_raw, sq_dtype x_dt, const int32_t* act,
-                                int32_t L, const sq_group_item* items, sq_dtype y_dt, void* stream) {
-  sq_status st = check_layer(layer, true, true);
+                                int32_t L, const sq_group_item* items, sq_dtype y_dt, void* stream, int w_bits = 8,
+                                const float* tok_steps = nullptr) {
+  sq_status st = check_layer(layer, true, tok_steps == nullptr);
   if (st != SQ_OK) return st;
+  if (w_bits != 8 && w_bits != 4) return SQ_ERR_INVALID_ARG;
+  if (w_bits == 4 && !w4_layout_ok(layer)) return SQ_ERR_UNSUPPORTED;
+  if (tok_steps != nullptr && layer->S > 8) return SQ_ERR_UNSUPPORTED;      // the kernel's step table holds 8 K-segments
   if ((xq == nullptr && x_raw == nullptr) || items == nullptr || L < 1) return SQ_ERR_INVALID_ARG;
   if (x_raw != nullptr && x_dt != SQ_F32 && x_dt != SQ_BF16) return SQ_ERR_INVALID_ARG;
   if (y_dt != SQ_F32 && y_dt != SQ_BF16) return SQ_ERR_INVALID_ARG;
@@ -386,8 +390,8 @@ static sq_status grouped_common(const sq_layer* layer, const int8_t* xq, const v
   for (int s = 0; s <= layer->S; ++s) tb.kseg_off[s] = layer->kseg_off[s];
   for (int s = 0; s < layer->S; ++s) {
     tb.dual[s] = layer->dual[s] ? 1 : 0;
-    tb.s_pos[s] = layer->s_pos[s];
-    tb.s_neg[s] = layer->dual[s] ? layer->s_neg[s] : 0.0f;
+    tb.s_pos[s] = tok_steps ? 1.0f : layer->s_pos[s];
+    tb.s_neg[s] = layer->dual[s] ? (tok_steps ? 1.0f : layer->s_neg[s]) : 0.0f;
     tb.inv_pos[s] = safe_inv(tb.s_pos[s]);
     tb.inv_neg[s] = safe_inv(tb.s_neg[s]);
     tb.act[s] = SQ_ACT_NONE;
@@ -404,9 +408,10 @@ static sq_status grouped_common(const sq_layer* layer, const int8_t* xq, const v
   a.M = layer->M;
   a.K = layer->K;
   a.N = layer->N;
+  a.tok_steps = tok_steps;
   if (!sq::stream_grouped_supported(a, tb)) return SQ_ERR_UNSUPPORTED;
   hipError_t e = sq::launch_seglinear_grouped(a, tb, gt, y_dt == SQ_BF16 ? sq::OUT_BF16 : sq::OUT_F32, sq::device_cus(),
-                                              reinterpret_cast<hipStream_t>(stream));
+                                              reinterpret_cast<hipStream_t>(stream), w_bits == 4);
   return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 
@@ -414,6 +419,12 @@ sq_status sq_seglinear_grouped(const sq_layer* layer, const int8_t* xq, int32_t 
                                sq_dtype y_dt, void* stream) {
   if (xq == nullptr) return SQ_ERR_INVALID_ARG;
   return grouped_common(layer, xq, nullptr, SQ_F32, nullptr, L, items, y_dt, stream);
+}
+
+sq_status sq_seglinear_grouped_w4(const sq_layer* layer, const int8_t* xq, const float* tok_steps, int32_t L,
+                                  const sq_group_item* items, sq_dtype y_dt, void* stream) {
+  if (xq == nullptr) return SQ_ERR_INVALID_ARG;
+  return grouped_common(layer, xq, nullptr, SQ_F32, nullptr, L, items, y_dt, stream, 4, tok_steps);
 }
 
 sq_status sq_seglinear_grouped_fused(const sq_layer* layer, const void* x, sq_dtype x_dt, const int32_t* act, int32_t L,

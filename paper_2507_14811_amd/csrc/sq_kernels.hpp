@@ -66,7 +66,7 @@ bool stream_supported(const GemmArgs& a, const GemmTable& tb);
 hipError_t launch_seglinear_stream(const GemmArgs& a, const GemmTable& tb, OutMode mode, int cus, hipStream_t st);
 bool stream_grouped_supported(const GemmArgs& a, const GroupSegTable& tb);
 hipError_t launch_seglinear_grouped(const GemmArgs& a, const GroupSegTable& tb, const GroupTable& gt, OutMode mode, int cus,
-                                    hipStream_t st);
+                                    hipStream_t st, bool w4 = false);
 
 // probes.hip : register-only int8 MFMA loop on every CU (benchmark ceiling)
 hipError_t launch_probe_mfma(const void* codes, size_t bytes, int iters, int* sink, hipStream_t st);

@@ -1029,3 +1029,58 @@ def test_seglinear_fused_dynamic(oracle, case):
         sq.sq_seglinear_fused_dynamic(layer, hd, case["act"], wq, bits, ws, bd, yb)
         torch.cuda.synchronize()
         g.check_bf16_against(g.bf16_tensor_bits(yb), r.y32, wl.f32_to_bf16_bits(r.y32), RTOL * ymax)
+
+
+GROUPEDW4 = [
+    dict(M=16, K=1152, N=1152, L=4, kseg=[0, 1152], dual=[1], ydt="bf16"),
+    dict(M=7, K=256, N=100, L=3, kseg=[0, 128, 256], dual=[1, 0], ydt="f32"),          # ragged N (padded last group)
+    dict(M=32, K=384, N=528, L=6, kseg=[0, 384], dual=[0], ydt="f32"),
+    dict(M=1, K=128, N=16, L=1, kseg=[0, 128], dual=[1], ydt="f32"),
+]
+
+
+@pytest.mark.parametrize("case", GROUPEDW4)
+@pytest.mark.parametrize("dynamic", [False, True])
+def test_seglinear_grouped_w4(oracle, case, dynamic):
+    """L layers with packed 4-bit weights that share the quantized input, one launch, static or per-token steps
+    (8- and 4-bit activation codes): every layer against the oracle."""
+    import torch
+
+    g = _gpu()
+    M, K, N, L = case["M"], case["K"], case["N"], case["L"]
+    base = wl.random_layer(M, K, N, case["kseg"], [0, N], case["dual"], seed=K + L + 1, x_dtype="bf16", act="silu", with_bias=True)
+    gl = g.GpuLayer(base)
+    rng = np.random.default_rng(L * 77 + N)
+    tdt = torch.bfloat16 if case["ydt"] == "bf16" else torch.float32
+    items, hosts = [], []
+    for l in range(L):
+        wl_l = (rng.standard_normal((N, K)) * (0.01 * (1 + l % 4))).astype(np.float32)
+        bias_l = None if l % 2 else rng.standard_normal(N).astype(np.float32)
+        wq4 = torch.empty((((N + 15) // 16) * 16 * (K // 2),), dtype=torch.uint8, device=g.DEV)
+        ws = torch.empty((base.S, N), dtype=torch.float32, device=g.DEV)
+        sq.sq_quantize_weight_w4(gl.layer, torch.from_numpy(wl_l).to(g.DEV), wq4, ws)
+        y = torch.full((M, N), float("nan"), dtype=tdt, device=g.DEV)
+        items.append((wq4, ws, None if bias_l is None else torch.from_numpy(bias_l).to(g.DEV), y))
+        hosts.append((wl_l, bias_l))
+    for abits in ((8, 4) if dynamic else (None,)):
+        if dynamic:
+            tok = torch.empty((2, M, base.S), dtype=torch.float32, device=g.DEV)
+            sq.sq_quantize_act_dynamic_bits(gl.layer, gl.x, abits, gl.xq, tok)
+            sq.sq_seglinear_grouped_w4(gl.layer, gl.xq, items, tok_steps=tok)
+        else:
+            gl.quantize_act()
+            sq.sq_seglinear_grouped_w4(gl.layer, gl.xq, items)
+        torch.cuda.synchronize()
+        for l, (wl_l, bias_l) in enumerate(hosts):
+            if dynamic:
+                r = oracle.seglinear_dynamic(base.x, wl_l, base.kseg_off, base.nseg_off, base.dual, None, bias_l, wbits=4, abits=abits)
+            else:
+                r = oracle.seglinear(base.x, wl_l, base.kseg_off, base.nseg_off, base.dual, base.s_pos, base.s_neg, None, bias_l, wbits=4)
+            ymax = float(np.abs(r.y32).max())
+            if case["ydt"] == "f32":
+                y = items[l][3].cpu().numpy()
+                assert not np.isnan(y).any()
+                err = float(np.abs(y.astype(np.float64) - r.y32.astype(np.float64)).max())
+                assert err <= RTOL * ymax, f"layer {l} (a_bits {abits}): fp32 output error {err} > {RTOL} * {ymax}"
+            else:
+                g.check_bf16_against(g.bf16_tensor_bits(items[l][3]), r.y32, r.y_bf16_bits, RTOL * ymax)

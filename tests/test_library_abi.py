@@ -157,6 +157,10 @@ def test_invalid_arguments_are_rejected_on_the_host(sq):
     assert lib.sq_unpack_w4(C.byref(w4.c), None, FAKE, None) == INVALID and lib.sq_unpack_w4(C.byref(w4.c), FAKE, None, None) == INVALID
     assert lib.sq_unpack_w4(C.byref(_layer(sq, K=192, kseg_off=[0, 192]).c), FAKE, FAKE, None) == UNSUPPORTED
     assert lib.sq_unpack_w4(C.byref(w4.c), C.c_void_p(0x1008), FAKE, None) == UNSUPPORTED
+    assert lib.sq_seglinear_grouped_w4(C.byref(w4.c), None, None, 1, one, 0, None) == INVALID
+    assert lib.sq_seglinear_grouped_w4(C.byref(w4.c), FAKE, None, 1, None, 0, None) == INVALID
+    assert lib.sq_seglinear_grouped_w4(C.byref(_layer(sq, K=192, kseg_off=[0, 192]).c), FAKE, None, 1, one, 0, None) == UNSUPPORTED
+    assert lib.sq_seglinear_grouped_w4(C.byref(w4.c), FAKE, None, 65, one, 0, None) == UNSUPPORTED
     fd = lambda layer=ok, x=FAKE, dt=1, act=None, abits=8, wq=FAKE, bits=8, ws=FAKE, y=FAKE: lib.sq_seglinear_fused_dynamic(
         C.byref(layer.c), x, dt, act, abits, wq, bits, ws, None, y, 0, None)
     assert fd(x=None) == INVALID and fd(wq=None) == INVALID and fd(ws=None) == INVALID and fd(y=None) == INVALID
@@ -181,3 +185,27 @@ def test_missing_library_fails_loudly(monkeypatch, sq):
     monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/libsegquant.so")
     with pytest.raises(RuntimeError, match="no CPU fallback"):
         binding.load_library()
+
+
+def test_binding_wrappers_are_well_formed():
+    """Every wrapper of the binding passes exactly (status, its own name) to _check, names a function the header declares,
+    and every declared entry point has a wrapper or is listed in EXPORTS."""
+    import ast
+    import re
+
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    src = open(os.path.join(root, "paper_2507_14811_amd", "binding.py")).read()
+    header = open(os.path.join(root, "include", "segquant.h")).read()
+    declared = set(re.findall(r"\b(sq_[a-z0-9_]+)\s*\(", header))
+    tree = ast.parse(src)
+    seen = 0
+    for fn in [n for n in ast.walk(tree) if isinstance(n, ast.FunctionDef)]:
+        for call in [n for n in ast.walk(fn) if isinstance(n, ast.Call) and getattr(n.func, "id", None) == "_check"]:
+            if fn.name in ("_check",):
+                continue
+            seen += 1
+            assert len(call.args) == 2 and not call.keywords, fn.name
+            name = call.args[1]
+            assert isinstance(name, ast.Constant) and name.value == fn.name, (fn.name, ast.dump(name))
+            assert fn.name in declared, fn.name
+    assert seen >= 20
