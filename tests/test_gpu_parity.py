@@ -1084,3 +1084,61 @@ def test_seglinear_grouped_w4(oracle, case, dynamic):
                 assert err <= RTOL * ymax, f"layer {l} (a_bits {abits}): fp32 output error {err} > {RTOL} * {ymax}"
             else:
                 g.check_bf16_against(g.bf16_tensor_bits(items[l][3]), r.y32, r.y_bf16_bits, RTOL * ymax)
+
+
+def test_graph_capture_dynamic_and_fused_paths(oracle):
+    """The entry points with per-token steps keep nothing between calls either: a skinny layer fed with raw activations
+    (SiLU, per-token steps, packed 4-bit weights: one launch) and a layer with many token rows (dynamic quantizer + tile
+    kernel) captured in one HIP graph, replayed on fresh inputs with eager work in between, every replay checked."""
+    import torch
+
+    g = _gpu()
+    rng = np.random.default_rng(31)
+    # skinny layer
+    M1, K1, N1 = 16, 512, 330
+    h = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits((rng.standard_normal((M1, K1)) * 2).astype(np.float32)))
+    w1 = (rng.standard_normal((N1, K1)) * 0.03).astype(np.float32)
+    l1 = sq.Layer(M1, K1, N1, [0, K1], [0, N1], [1], [1.0], [1.0])
+    hd = torch.from_numpy(wl.f32_to_bf16_bits(h).view(np.int16)).view(torch.bfloat16).to(g.DEV)
+    wq4 = torch.empty((((N1 + 15) // 16) * 16 * (K1 // 2),), dtype=torch.uint8, device=g.DEV)
+    ws1 = torch.empty((1, N1), dtype=torch.float32, device=g.DEV)
+    sq.sq_quantize_weight_w4(l1, torch.from_numpy(w1).to(g.DEV), wq4, ws1)
+    y1 = torch.zeros((M1, N1), dtype=torch.float32, device=g.DEV)
+    # layer with many token rows
+    w2 = wl.random_layer(300, 512, 260, [0, 256, 512], [0, 260], [0, 1], seed=23, x_dtype="bf16", act="gelu", with_bias=True)
+    gl = g.GpuLayer(w2)
+    gl.quantize_weight()
+    tok = torch.zeros((2, w2.M, w2.S), dtype=torch.float32, device=g.DEV)
+    y2 = torch.zeros((w2.M, w2.N), dtype=torch.float32, device=g.DEV)
+
+    def step():
+        sq.sq_seglinear_fused_dynamic(l1, hd, [sq.SQ_ACT_SILU], wq4, 4, ws1, None, y1)
+        sq.sq_quantize_act_dynamic(gl.layer, gl.x, gl.xq, tok)
+        sq.sq_seglinear_dynamic(gl.layer, gl.xq, tok, gl.wq, 8, gl.wscale, gl.bias, y2)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):           # warm-up outside the capture
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(3):
+        hs = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits((h * (1.0 + 0.3 * rep) + 0.05 * rng.standard_normal(h.shape)).astype(np.float32)))
+        xs = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits((w2.x * (1.0 + 0.2 * rep) + 0.02 * rng.standard_normal(w2.x.shape)).astype(np.float32)))
+        hd.copy_(torch.from_numpy(wl.f32_to_bf16_bits(hs).view(np.int16)).view(torch.bfloat16).to(g.DEV))
+        gl.x.copy_(torch.from_numpy(wl.f32_to_bf16_bits(xs).view(np.int16)).view(torch.bfloat16).to(g.DEV))
+        y1.fill_(float("nan"))                                          # eager work between replays
+        y2.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        r1 = oracle.seglinear_dynamic(oracle.activation(hs, [0, K1], [oracle.ACT_SILU]), w1, [0, K1], [0, N1], [1], None, None, wbits=4)
+        e1 = float(np.abs(y1.cpu().numpy().astype(np.float64) - r1.y32).max())
+        assert e1 <= RTOL * float(np.abs(r1.y32).max()), f"replay {rep}: skinny layer {e1}"
+        r2 = oracle.seglinear_dynamic(xs, w2.w, w2.kseg_off, w2.nseg_off, w2.dual, None, w2.bias)
+        assert np.array_equal(tok.cpu().numpy().view(np.uint32), r2.tok_steps.view(np.uint32)), f"replay {rep}"
+        e2 = float(np.abs(y2.cpu().numpy().astype(np.float64) - r2.y32).max())
+        assert e2 <= RTOL * float(np.abs(r2.y32).max()), f"replay {rep}: large layer {e2}"
