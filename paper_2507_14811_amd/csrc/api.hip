@@ -581,7 +581,7 @@ const char* sq_status_string(sq_status s) {
   }
 }
 
-int sq_version(void) { return 200; }
+int sq_version(void) { return 300; }
 
 sq_status sq_tuning_set(const char* key, int value) {
   if (key == nullptr) return SQ_ERR_INVALID_ARG;
