@@ -14,7 +14,7 @@ template <int V> struct MfmaVariant;
     static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, NS = NS_, SK = SK_, MINB = MINB_;                   \
     static constexpr bool DUAL_OK = DUAL_OK_, MULTI_OK = MULTI_OK_, MULTI_DUAL_OK = MULTI_DUAL_OK_,     \
                           SHARE_OK = SHARE_OK_;                                                    \
-    static constexpr bool TOK_OK = (V == 0 || V == 1 || V == 3);   /* instantiated with per-token activation steps */ \
+    static constexpr bool TOK_OK = (V == 0 || V == 1 || V == 3 || V == 7 || V == 8);   /* instantiated with per-token activation steps */ \
   };
 SQ_DEF_VARIANT(0, 128, 256, 2, 2, 3, 128, 1, true, true, false, true)   // wave tile 64 x 128, both polarities: 256 accumulator registers
 SQ_DEF_VARIANT(1, 128, 128, 2, 2, 3, 128, 1, true, true, true, true)    // wave tile 64 x 64

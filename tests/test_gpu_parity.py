@@ -796,7 +796,7 @@ def test_seglinear_dynamic(oracle, case):
             wdev = torch.empty((((N + 15) // 16) * 16 * (K // 2),), dtype=torch.uint8, device=g.DEV)
             sq.sq_quantize_weight_w4(gl.layer, gl.wt, wdev, gl.wscale)
         ymax = float(np.abs(r.y32).max())
-        runs = [(-1, -1), (0, -1)] + ([(1, v) for v in (0, 1, 3)] if bits == 8 and M > 64 else [])
+        runs = [(-1, -1), (0, -1)] + ([(1, v) for v in (0, 1, 3, 7, 8)] if bits == 8 and M > 64 else [])
         for forced, variant in runs:
             sq.sq_tuning_set("force_path", forced)
             sq.sq_tuning_set("gemm_variant", variant)
