@@ -1142,3 +1142,48 @@ def test_graph_capture_dynamic_and_fused_paths(oracle):
         assert np.array_equal(tok.cpu().numpy().view(np.uint32), r2.tok_steps.view(np.uint32)), f"replay {rep}"
         e2 = float(np.abs(y2.cpu().numpy().astype(np.float64) - r2.y32).max())
         assert e2 <= RTOL * float(np.abs(r2.y32).max()), f"replay {rep}: large layer {e2}"
+
+
+def test_near_the_size_limit(oracle):
+    """M*K just below 2^31 (the documented limit): static and per-token quantizer and GEMM on sampled rows, which the
+    oracle computes one by one.  Inputs are drawn on the device (the oracle only ever sees the sampled rows)."""
+    import torch
+
+    g = _gpu()
+    M, K, N = 32768, 65408, 64
+    assert 0 < 2 ** 31 - M * K <= 2 ** 22
+    kseg, dual = [0, 16384, K], [0, 1]
+    gen = torch.Generator(device=g.DEV).manual_seed(1)
+    x = torch.empty((M, K), dtype=torch.bfloat16, device=g.DEV)
+    for i in range(0, M, 4096):
+        x[i:i + 4096] = (torch.randn((4096, K), device=g.DEV, generator=gen) * 1.5).to(torch.bfloat16)
+    x[:, 16384:] = torch.nn.functional.gelu(x[:, 16384:].float(), approximate="tanh").to(torch.bfloat16)
+    w = (np.random.default_rng(2).standard_normal((N, K)) * 0.02).astype(np.float32)
+    sp, sn = [6.0 / 127, 7.0 / 127], [1.0, 0.17 / 127]
+    layer = sq.Layer(M, K, N, kseg, [0, N], dual, sp, sn)
+    wq = torch.empty((N, K), dtype=torch.int8, device=g.DEV)
+    ws = torch.empty((2, N), dtype=torch.float32, device=g.DEV)
+    sq.sq_quantize_weight(layer, torch.from_numpy(w).to(g.DEV), wq, ws)
+    xq = torch.full((M, K), 99, dtype=torch.int8, device=g.DEV)
+    y = torch.full((M, N), float("nan"), dtype=torch.float32, device=g.DEV)
+    sq.sq_quantize_act(layer, x, xq)
+    sq.sq_seglinear(layer, xq, wq, ws, None, y)
+    torch.cuda.synchronize()
+    rows = [0, 1, 127, 128, 4095, 16384, 20000, M - 129, M - 2, M - 1]
+    xs = x[rows].float().cpu().numpy()
+    r = oracle.seglinear(xs, w, kseg, [0, N], dual, layer.s_pos, layer.s_neg)
+    want = (r.xq_pos.astype(np.int16) + r.xq_neg.astype(np.int16)).astype(np.int8)
+    assert np.array_equal(xq[rows].cpu().numpy(), want)
+    assert not torch.isnan(y).any()
+    err = float(np.abs(y[rows].cpu().numpy().astype(np.float64) - r.y32.astype(np.float64)).max())
+    assert err <= RTOL * float(np.abs(r.y32).max())
+    tok = torch.empty((2, M, 2), dtype=torch.float32, device=g.DEV)
+    y.fill_(float("nan"))
+    sq.sq_quantize_act_dynamic(layer, x, xq, tok)
+    sq.sq_seglinear_dynamic(layer, xq, tok, wq, 8, ws, None, y)
+    torch.cuda.synchronize()
+    rd = oracle.seglinear_dynamic(xs, w, kseg, [0, N], dual)
+    assert np.array_equal(tok[:, rows].cpu().numpy().view(np.uint32), rd.tok_steps.view(np.uint32))
+    assert not torch.isnan(y).any()
+    err = float(np.abs(y[rows].cpu().numpy().astype(np.float64) - rd.y32.astype(np.float64)).max())
+    assert err <= RTOL * float(np.abs(rd.y32).max())
