@@ -1187,3 +1187,42 @@ def test_near_the_size_limit(oracle):
     assert not torch.isnan(y).any()
     err = float(np.abs(y[rows].cpu().numpy().astype(np.float64) - rd.y32.astype(np.float64)).max())
     assert err <= RTOL * float(np.abs(rd.y32).max())
+
+
+@pytest.mark.parametrize("shape", [(16, 1152, 1864000), (16, 65408, 32768), (40, 65408, 32768)])
+def test_weights_near_the_size_limit(oracle, shape):
+    """N*K just below 2^31: weight quantizer and GEMM (weight-stream kernel for the first shape, tile kernel for the long
+    rows) on sampled output channels, whose weight rows the oracle gets one by one.  Weights are drawn on the device."""
+    import torch
+
+    g = _gpu()
+    M, K, N = shape
+    assert 0 < 2 ** 31 - N * K <= 2 ** 23
+    kseg, dual = [0, K], [1]
+    base = wl.random_layer(M, K, 8, kseg, [0, 8], dual, seed=K + M, x_dtype="bf16", act="silu")
+    layer = sq.Layer(M, K, N, kseg, [0, N], dual, base.s_pos, base.s_neg)
+    gen = torch.Generator(device=g.DEV).manual_seed(3)
+    wt = torch.empty((N, K), dtype=torch.float32, device=g.DEV)
+    step = max(1, (1 << 28) // K)
+    for i in range(0, N, step):
+        n = min(step, N - i)
+        wt[i:i + n] = torch.randn((n, K), device=g.DEV, generator=gen) * 0.02
+    wq = torch.full((N, K), 99, dtype=torch.int8, device=g.DEV)
+    ws = torch.full((1, N), float("nan"), dtype=torch.float32, device=g.DEV)
+    sq.sq_quantize_weight(layer, wt, wq, ws)
+    xd = g.to_dev_x(base)
+    xq = torch.empty((M, K), dtype=torch.int8, device=g.DEV)
+    sq.sq_quantize_act(layer, xd, xq)
+    y = torch.full((M, N), float("nan"), dtype=torch.float32, device=g.DEV)
+    sq.sq_seglinear(layer, xq, wq, ws, None, y)
+    torch.cuda.synchronize()
+    cols = [0, 1, 15, 16, 255, N // 3, N // 2 + 7, N - 17, N - 2, N - 1]
+    wc = wt[cols].cpu().numpy()
+    del wt
+    r = oracle.seglinear(base.x, wc, kseg, [0, len(cols)], dual, base.s_pos, base.s_neg)
+    assert np.array_equal(wq[cols].cpu().numpy(), r.wq)
+    assert np.array_equal(ws[:, cols].cpu().numpy().view(np.uint32), r.wscale.view(np.uint32))
+    assert not torch.isnan(y).any()
+    yc = y[:, cols].cpu().numpy().astype(np.float64)
+    err = float(np.abs(yc - r.y32.astype(np.float64)).max())
+    assert err <= RTOL * float(np.abs(r.y32).max())
