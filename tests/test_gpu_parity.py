@@ -1226,3 +1226,37 @@ def test_weights_near_the_size_limit(oracle, shape):
     yc = y[:, cols].cpu().numpy().astype(np.float64)
     err = float(np.abs(yc - r.y32.astype(np.float64)).max())
     assert err <= RTOL * float(np.abs(r.y32).max())
+
+
+@pytest.mark.parametrize("ydt", ["f32", "bf16"])
+def test_output_near_the_size_limit(oracle, ydt):
+    """M*N just below 2^31 (a short K): the store epilogue's offsets, on sampled token rows."""
+    import torch
+
+    g = _gpu()
+    M, K, N = 32768, 128, 65504
+    assert 0 < 2 ** 31 - M * N <= 2 ** 21
+    kseg, dual = [0, K], [1]
+    rng = np.random.default_rng(8)
+    w = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    gen = torch.Generator(device=g.DEV).manual_seed(4)
+    x = torch.nn.functional.silu(torch.randn((M, K), device=g.DEV, generator=gen) * 1.5).to(torch.bfloat16)
+    sp, sn = [6.5 / 127], [0.279 / 127]
+    layer = sq.Layer(M, K, N, kseg, [0, N], dual, sp, sn)
+    wq = torch.empty((N, K), dtype=torch.int8, device=g.DEV)
+    ws = torch.empty((1, N), dtype=torch.float32, device=g.DEV)
+    sq.sq_quantize_weight(layer, torch.from_numpy(w).to(g.DEV), wq, ws)
+    xq = torch.empty((M, K), dtype=torch.int8, device=g.DEV)
+    sq.sq_quantize_act(layer, x, xq)
+    y = torch.full((M, N), float("nan"), dtype=torch.float32 if ydt == "f32" else torch.bfloat16, device=g.DEV)
+    sq.sq_seglinear(layer, xq, wq, ws, None, y)
+    torch.cuda.synchronize()
+    rows = [0, 1, 127, 128, 9999, 16384, M - 129, M - 2, M - 1]
+    r = oracle.seglinear(x[rows].float().cpu().numpy(), w, kseg, [0, N], dual, layer.s_pos, layer.s_neg)
+    assert not torch.isnan(y.float().sum(dim=1)).any()
+    ymax = float(np.abs(r.y32).max())
+    if ydt == "f32":
+        err = float(np.abs(y[rows].cpu().numpy().astype(np.float64) - r.y32.astype(np.float64)).max())
+        assert err <= RTOL * ymax
+    else:
+        g.check_bf16_against(g.bf16_tensor_bits(y[rows]), r.y32, r.y_bf16_bits, RTOL * ymax)
