@@ -925,6 +925,8 @@ GEGLU = [
     dict(M=13, K=100, kseg=[0, 37, 100], dual=[1, 1], h_dtype="bf16"),         # unaligned: one output per thread
     dict(M=5, K=24, kseg=[0, 24], dual=[1], h_dtype="f32"),
     dict(M=1, K=16, kseg=[0, 16], dual=[0], h_dtype="bf16"),
+    dict(M=2100, K=2560, kseg=[0, 512, 2560], dual=[1, 0], h_dtype="bf16"),    # more chunks than threads in flight
+    dict(M=4096, K=1024, kseg=[0, 1024], dual=[1], h_dtype="bf16"),
 ]
 
 
@@ -940,6 +942,9 @@ def test_quantize_act_geglu(oracle, case, spread):
     h = (rng.standard_normal((M, 2 * K)) * (1.0 if spread == "unit" else 9.0)).astype(np.float32)
     if spread == "wide" and K >= 8:
         h[0, K:K + 8] = [0.0, -0.0, 95.0, -95.0, 1e4, -1e4, 30.0, -9.0]
+    if K >= 16:                               # tiny and large gates next to ordinary ones
+        h[M - 1, K:K + 8] = [2.0 ** -14, -(2.0 ** -14), 2.0 ** -15, -3e-5, 7.96875, -7.96875, 8.0, -8.0]
+        h[M - 1, :8] = [3.0, -2.0, 1e3, 5.0, 1.5, -1.5, 0.25, 4.0]
     if case["h_dtype"] == "bf16":
         h = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(h))
         hd = torch.from_numpy(wl.f32_to_bf16_bits(h).view(np.int16)).view(torch.bfloat16).to(g.DEV)
