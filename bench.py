@@ -360,7 +360,7 @@ def measure_geglu(M=4096, K=5120, steps=20):
     byt = M * K * 5
     return {"M": M, "K": K, "ms_per_launch": round(ms, 5), "bytes": byt, "achieved": round(byt / (ms * 1e-3) / 1e9, 1),
             "unit": "GB/s", "frac_hbm_peak": round(byt / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-            "note": "bound by the gate's fp32 arithmetic (bit-specified GELU), not by HBM"}
+            "note": "4 B in + 1 B out per output (bf16); two input streams per row and the bit-specified GELU of the gate"}
 
 
 def measure_w4(steps=40):
