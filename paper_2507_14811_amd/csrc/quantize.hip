@@ -646,12 +646,100 @@ __global__ __launch_bounds__(256) void quantize_act_geglu_kernel(const void* __r
   }
 }
 
+// bf16 input, 16-element chunks: GELU(gate) by table.  A bf16 gate has 2^16 bit patterns, and all but a sliver of a
+// layer's gates have magnitudes in [2^-14, 8): the results for the kGegluExps * 128 * 2 patterns of that window (17 KiB
+// of fp32, computed by each workgroup with activate(), i.e. the very bits the arithmetic path produces) sit in LDS, and a
+// gate costs one ds_read_b32 instead of the ~35-instruction sequence.  A chunk with a gate outside the window (tiny,
+// huge, non-finite) is redone with the sequence, in a block of its own so that the common path stays free of it.
+// Persistent workgroups (two per CU) so that filling the table is a small part of their work.
+constexpr int kGegluExpLo = 113, kGegluExps = 17;        // biased exponents 113 ... 129: 2^-14 <= |gate| < 2^3
+constexpr int kGegluThreads = 1024;
+__global__ __launch_bounds__(kGegluThreads) void quantize_act_geglu_tab_kernel(const uint16_t* __restrict__ h,
+                                                                               int8_t* __restrict__ xq, int M, int K,
+                                                                               const ActTable tb, const uint32_t kmagic) {
+#pragma clang fp contract(off)
+  __shared__ float gelu_tab[2 * kGegluExps * 128];
+  for (int i = threadIdx.x; i < 2 * kGegluExps * 128; i += kGegluThreads) {
+    const uint32_t sign = (uint32_t)i / (kGegluExps * 128), rest = (uint32_t)i % (kGegluExps * 128);
+    const uint32_t bits = (sign << 15) | (((rest >> 7) + kGegluExpLo) << 7) | (rest & 127u);
+    gelu_tab[i] = activate(SQ_ACT_GELU, __uint_as_float(bits << 16));
+  }
+  __syncthreads();
+  const uint32_t per_row = (uint32_t)K >> 4;
+  const uint32_t nitem = (uint32_t)M * per_row;                    // M * K < 2^31 (checked by the host)
+  for (uint32_t c = blockIdx.x * (uint32_t)kGegluThreads + threadIdx.x; c < nitem; c += gridDim.x * (uint32_t)kGegluThreads) {
+    uint32_t m = __umulhi(c, kmagic);                              // c / per_row by reciprocal multiply: exact or one too small
+    uint32_t rr = c - m * per_row;
+    if (rr >= per_row) { rr -= per_row; ++m; }
+    const int col = (int)(rr << 4);
+    const size_t ev = (size_t)m * 2 * (size_t)K + col, eg = ev + K;
+    v4i cv[2], cg[2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      cv[q] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(h + ev + 8 * q));
+      cg[q] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(h + eg + 8 * q));
+    }
+    float sp = tb.s_pos[0], sn = tb.s_neg[0], ip = tb.inv_pos[0], in = tb.inv_neg[0];
+    bool dual = tb.dual[0] != 0;
+    for (int s = 1; s < tb.S; ++s) {
+      if (col >= tb.kseg_off[s]) {
+        sp = tb.s_pos[s]; sn = tb.s_neg[s]; ip = tb.inv_pos[s]; in = tb.inv_neg[s]; dual = tb.dual[s] != 0;
+      }
+    }
+    float v[16], g[16];
+    uint32_t gb[16];
+    bool all_in = true;
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        v[8 * q + 2 * d] = __uint_as_float((uint32_t)cv[q][d] << 16);
+        v[8 * q + 2 * d + 1] = __uint_as_float((uint32_t)cv[q][d] & 0xFFFF0000u);
+        gb[8 * q + 2 * d] = (uint32_t)cg[q][d] & 0xFFFFu;
+        gb[8 * q + 2 * d + 1] = (uint32_t)cg[q][d] >> 16;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const uint32_t rel = ((gb[i] >> 7) & 0xFFu) - (uint32_t)kGegluExpLo;
+      const bool inside = rel < (uint32_t)kGegluExps;
+      all_in = all_in && inside;
+      const uint32_t idx = inside ? (gb[i] >> 15) * (kGegluExps * 128) + rel * 128 + (gb[i] & 127u) : 0u;
+      g[i] = gelu_tab[idx];
+    }
+    if (__builtin_expect(!all_in, 0)) {                            // rare: the whole chunk by the sequence
+#pragma unroll 1
+      for (int i = 0; i < 16; ++i) g[i] = activate(SQ_ACT_GELU, __uint_as_float(gb[i] << 16));
+    }
+    v4i out;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      int code[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float a = __fmul_rn(v[4 * q + i], g[4 * q + i]);
+        const bool ng = dual && (a < 0.0f);
+        code[i] = clip_code(round_quotient(a, ng ? sn : sp, ng ? in : ip));
+      }
+      out[q] = (int)pack4(code[0], code[1], code[2], code[3]);
+    }
+    *reinterpret_cast<v4i*>(xq + (size_t)m * (size_t)K + col) = out;
+  }
+}
+
 hipError_t launch_quantize_act_geglu(const void* h, bool h_is_bf16, int8_t* xq, int M, int K, const ActTable& tb, int cus,
                                      hipStream_t st) {
   bool vec = K % 16 == 0 && (reinterpret_cast<uintptr_t>(h) | reinterpret_cast<uintptr_t>(xq)) % 16 == 0;
   for (int s = 0; s <= tb.S; ++s) vec = vec && tb.kseg_off[s] % 16 == 0;
   const size_t nitem = (size_t)M * (size_t)(vec ? K / 16 : K);
   if (nitem == 0) return hipSuccess;
+  if (vec && h_is_bf16 && nitem >= (size_t)cus * 2 * kGegluThreads) {      // enough chunks to pay for the tables
+    const uint64_t per_row = (uint64_t)K >> 4;
+    const uint32_t kmagic = (uint32_t)(0x100000000ull / per_row > 0xFFFFFFFFull ? 0xFFFFFFFFull : 0x100000000ull / per_row);
+    hipLaunchKernelGGL(quantize_act_geglu_tab_kernel, dim3((unsigned)cus * 2), dim3(kGegluThreads), 0, st,
+                       reinterpret_cast<const uint16_t*>(h), xq, M, K, tb, kmagic);
+    return hipGetLastError();
+  }
   size_t blocks = (nitem + 255) / 256;
   const size_t cap = (size_t)cus * 64;
   if (blocks > cap) blocks = cap;
