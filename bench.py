@@ -32,7 +32,7 @@ PREROLL_MS = 80.0              # untimed load before the warm-up steps, so that 
 # readings of a plain 256 MiB copy kernel (profiles/bench_all_kernels_rocprofv3.txt), bytes.  None for a
 # workload without a committed counter run.
 MEASURED_TRAFFIC = {
-    "cfg5_outproj": int(287507.7 * 1024 * 2.0 + 51718.7 * 1024 * 1.0),       # 641.8 MB (algorithmic 146.3 MB)
+    "cfg5_outproj": int(287525.1 * 1024 * 2.0 + 51711.2 * 1024 * 1.0),       # 641.8 MB (algorithmic 146.3 MB)
     "cfg4d_qkv_dual": int(69502.6 * 1024 * 2.0 + 76534.9 * 1024 * 1.0),
     "cfg4_qkv": int(69365.0 * 1024 * 2.0 + 76558.4 * 1024 * 1.0),
     "cfg2_dit_fc2": int(19735.5 * 1024 * 2.0 + 4608.0 * 1024 * 1.0),
