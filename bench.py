@@ -520,7 +520,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-              "(the path shards along M without any exchange; see DESIGN.md)", file=sys.stderr)
+              "(token rows are independent: a second GPU would take its own share of M, with no exchange)", file=sys.stderr)
         sys.exit(2)
 
     import torch
