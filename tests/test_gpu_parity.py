@@ -1265,3 +1265,77 @@ def test_output_near_the_size_limit(oracle, ydt):
         assert err <= RTOL * ymax
     else:
         g.check_bf16_against(g.bf16_tensor_bits(y[rows]), r.y32, r.y_bf16_bits, RTOL * ymax)
+
+
+def _random_segments(rng, total, align, maxs):
+    units = total // align
+    n = int(rng.integers(1, min(maxs, units) + 1))
+    cuts = sorted(rng.choice(np.arange(1, units), size=n - 1, replace=False).tolist()) if n > 1 else []
+    return [0] + [c * align for c in cuts] + [total]
+
+
+def test_random_shapes_against_oracle(oracle):
+    """A seeded walk over legal shapes, segmentations, input types and forced kernels (the committed slice of a much longer
+    one-off sweep): quantizers bit-exact, integer sums bit-exact, outputs within the fp32 tolerance, static and per-token."""
+    import torch
+
+    g = _gpu()
+    rng = np.random.default_rng(20250714)
+    ran = 0
+    for n in range(160):
+        align = int(rng.choice([128, 128, 64, 16, 1]))
+        M = int(rng.choice([1, 3, 16, 17, 31, 33, 64, 65, 100, 129, 200, 300, 385]))
+        K = align * int(rng.integers(1, max(2, 1536 // align))) if align > 1 else int(rng.integers(5, 700))
+        N = int(rng.choice([7, 16, 33, 64, 100, 128, 130, 192, 256, 300, 520]))
+        kseg = _random_segments(rng, K, align, 4)
+        nseg = _random_segments(rng, N, 1, 3)
+        dual = [int(rng.integers(0, 2)) for _ in kseg[:-1]]
+        xdt = str(rng.choice(["bf16", "f32"]))
+        act = str(rng.choice(["silu", "gelu", "normal", "relu", "neg"]))
+        path = int(rng.choice([-1, -1, 0, 1, 2, 3]))
+        what = dict(case=n, M=M, K=K, N=N, kseg=kseg, nseg=nseg, dual=dual, xdt=xdt, act=act, path=path)
+        w = wl.random_layer(M, K, N, kseg, nseg, dual, seed=7000 + n, x_dtype=xdt, act=act,
+                            with_seg_scale=bool(rng.integers(0, 2)), with_bias=bool(rng.integers(0, 2)))
+        gl = g.GpuLayer(w)
+        wq, ws = gl.quantize_weight()
+        xp, xn, _ = gl.quantize_act()
+        r = oracle.seglinear(w.x, w.w, w.kseg_off, w.nseg_off, w.dual, w.s_pos, w.s_neg, w.seg_scale, w.bias)
+        assert np.array_equal(wq, r.wq) and np.array_equal(ws.view(np.uint32), r.wscale.view(np.uint32)), what
+        assert np.array_equal(xp, r.xq_pos) and np.array_equal(xn, r.xq_neg), what
+        sq.sq_tuning_set("force_path", path)
+        try:
+            ap = torch.full((w.S, M, N), 0x5A5A5A5A, dtype=torch.int32, device=g.DEV)
+            an = torch.full_like(ap, 0x5A5A5A5A)
+            try:
+                sq.sq_seglinear_debug_acc(gl.layer, gl.xq, gl.wq, ap, an)
+            except sq.SqError as e:
+                assert e.status == 2 and path > 0, what           # a forced kernel that does not take this shape
+                continue
+            y = torch.full((M, N), float("nan"), dtype=torch.float32, device=g.DEV)
+            sq.sq_seglinear(gl.layer, gl.xq, gl.wq, gl.wscale, gl.bias, y)
+            tok = torch.empty((2, M, w.S), dtype=torch.float32, device=g.DEV)
+            xqd = torch.empty_like(gl.xq)
+            sq.sq_quantize_act_dynamic(gl.layer, gl.x, xqd, tok)
+            yd = torch.full((M, N), float("nan"), dtype=torch.float32, device=g.DEV)
+            dyn = True
+            try:
+                sq.sq_seglinear_dynamic(gl.layer, xqd, tok, gl.wq, 8, gl.wscale, gl.bias, yd)
+            except sq.SqError as e:
+                assert e.status == 2 and path > 0, what           # the forced kernel has no per-token form for this layer
+                dyn = False
+            torch.cuda.synchronize()
+            assert np.array_equal(ap.cpu().numpy(), r.acc_pos) and np.array_equal(an.cpu().numpy(), r.acc_neg), what
+            err = float(np.abs(y.cpu().numpy().astype(np.float64) - r.y32.astype(np.float64)).max())
+            assert err <= RTOL * float(np.abs(r.y32).max()), (what, err)
+            ran += 1
+            if not dyn:
+                continue
+            rd = oracle.seglinear_dynamic(w.x, w.w, w.kseg_off, w.nseg_off, w.dual, w.seg_scale, w.bias)
+            xpd, xnd = g.split_codes(w, xqd.cpu().numpy())
+            assert np.array_equal(xpd, rd.xq_pos) and np.array_equal(xnd, rd.xq_neg), what
+            assert np.array_equal(tok.cpu().numpy().view(np.uint32), rd.tok_steps.view(np.uint32)), what
+            errd = float(np.abs(yd.cpu().numpy().astype(np.float64) - rd.y32.astype(np.float64)).max())
+            assert errd <= RTOL * float(np.abs(rd.y32).max()), (what, errd)
+        finally:
+            sq.sq_tuning_set("force_path", -1)
+    assert ran >= 100
