@@ -583,14 +583,63 @@ def test_saturated_accumulators(oracle):
 # ----------------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4", "cfg4d", "cfg5"])
 def test_named_configs(oracle, name):
+    """Every element of every named configuration: codes, weight steps, both int32 accumulator sets of every K-segment,
+    fp32 and bf16 outputs, against the oracle's full matrices."""
     g = _gpu()
     w = wl.make(name)
-    rows = None
-    if w.M > 256:   # the oracle evaluates sampled token rows one by one: first / last tiles and a random draw
-        rng = np.random.default_rng(w.seed)
-        rows = np.unique(np.concatenate([np.arange(0, 8), np.arange(w.M - 8, w.M), rng.integers(0, w.M, 48)]))
-    out = _check_layer(oracle, g, w, path=-1, rows=rows)
+    out = _check_layer(oracle, g, w, path=-1)
     print(name, out)
+
+
+@pytest.mark.parametrize("name", ["cfg2", "cfg4d", "cfg5"])
+def test_named_configs_per_token_steps(oracle, name):
+    """The same layers with dynamic per-token activation steps (App. B, 4-bit settings), every element: codes and
+    steps bit-exact, outputs of the tile kernel's per-token instantiation within the fp32 tolerance."""
+    import torch
+
+    g = _gpu()
+    w = wl.make(name)
+    gl = g.GpuLayer(w)
+    gl.quantize_weight()
+    tok = torch.full((2, w.M, w.S), float("nan"), dtype=torch.float32, device=g.DEV)
+    sq.sq_quantize_act_dynamic(gl.layer, gl.x, gl.xq, tok)
+    torch.cuda.synchronize()
+    r = oracle.seglinear_dynamic(w.x, w.w, w.kseg_off, w.nseg_off, w.dual, w.seg_scale, w.bias, wbits=8)
+    xp, xn = g.split_codes(w, gl.xq.cpu().numpy())
+    assert np.array_equal(xp, r.xq_pos) and np.array_equal(xn, r.xq_neg)
+    assert np.array_equal(tok.cpu().numpy().view(np.uint32), r.tok_steps.view(np.uint32))
+    ymax = float(np.abs(r.y32).max())
+    y = torch.full((w.M, w.N), float("nan"), dtype=torch.float32, device=g.DEV)
+    sq.sq_seglinear_dynamic(gl.layer, gl.xq, tok, gl.wq, 8, gl.wscale, gl.bias, y)
+    torch.cuda.synchronize()
+    y = y.cpu().numpy()
+    assert not np.isnan(y).any()
+    assert float(np.abs(y.astype(np.float64) - r.y32.astype(np.float64)).max()) <= RTOL * ymax
+    yb = torch.full((w.M, w.N), float("nan"), dtype=torch.bfloat16, device=g.DEV)
+    sq.sq_seglinear_dynamic(gl.layer, gl.xq, tok, gl.wq, 8, gl.wscale, gl.bias, yb)
+    torch.cuda.synchronize()
+    g.check_bf16_against(g.bf16_tensor_bits(yb), r.y32, wl.f32_to_bf16_bits(r.y32), RTOL * ymax)
+
+
+# Several rounds of tiles per persistent workgroup (more tiles than the chip has compute units), every element:
+# the load pipeline then runs across tile boundaries.  Two K-segments; `dual` picks the register-sharing
+# instantiation (one dual segment) or the one with a separate fp32 running sum (two dual segments).
+MULTIROUND = [
+    dict(M=4096, K=512, N=2560, kseg=[0, 256, 512], dual=[0, 1], variant=1),     # 640 tiles of 128 x 128, shared registers
+    dict(M=4096, K=512, N=2560, kseg=[0, 256, 512], dual=[1, 1], variant=1),     # separate running sum
+    dict(M=4100, K=384, N=2570, kseg=[0, 128, 384], dual=[1, 0], variant=0),     # 128 x 256 tiles, ragged edges, shared registers
+    dict(M=4100, K=384, N=2570, kseg=[0, 384], dual=[1], variant=3),             # 64 x 128 tiles: 1365 tiles, five rounds
+    dict(M=4100, K=256, N=2570, kseg=[0, 256], dual=[0], variant=4),             # 256 x 256 single path
+]
+
+
+@pytest.mark.parametrize("case", MULTIROUND)
+def test_seglinear_mfma_many_tiles(oracle, case):
+    g = _gpu()
+    w = wl.random_layer(case["M"], case["K"], case["N"], case["kseg"], [0, case["N"] // 2, case["N"]], case["dual"],
+                        seed=case["M"] + case["K"] + 3 * case["variant"], x_dtype="bf16", act="gelu", with_seg_scale=True,
+                        with_bias=True)
+    _check_layer(oracle, g, w, path=1, variant=case["variant"])
 
 
 def test_headline_config_calibration_and_fused_quantizer(oracle):
