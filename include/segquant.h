@@ -135,6 +135,8 @@ sq_status sq_calibrate_act_percentile(const sq_layer* layer, const void* x, sq_d
  * For a non-dual K-segment (Sec. 3, z = 0): xq = clip(round(x / s_pos[ks]), -127, 127).
  *   x       dev, [M][K] of x_dt                           in
  *   xq      dev, int8 [M][K], polarity-merged codes       out
+ * The two matrices of Sec. 4.3.2 never overlap (X^_+ >= 0 where x >= 0, X^_- <= 0 where x < 0), so they leave as one:
+ * the supported decoding is X^_+ = max(xq, 0), X^_- = min(xq, 0) in a dual K-segment, X^_+ = xq elsewhere.
  */
 sq_status sq_quantize_act(const sq_layer* layer, const void* x, sq_dtype x_dt, int8_t* xq,
                           void* stream);
@@ -190,8 +192,10 @@ sq_status sq_quantize_act_geglu(const sq_layer* layer, const void* h, sq_dtype h
  * with X^_+ = max(xq, 0), X^_- = min(xq, 0) in dual segments and X^_+ = xq elsewhere,
  *   y[m][n] = sum_ks seg_scale[ks][ns(n)] wscale[ks][n] ( s_pos[ks] acc_+ + s_neg[ks] acc_- ) + bias[n]
  * evaluated in fp32 and stored as fp32 or bf16 (round-half-to-even).  Activation and weight tiles
- * are read once and feed both accumulator sets.  M <= 64 selects the weight-streaming
- * (bandwidth-bound) kernel.
+ * are read once and feed both accumulator sets.  Kernel selection: M <= 32 with K and the K-segment boundaries
+ * multiples of 128 runs the weight-streaming (bandwidth-bound) kernel; M = 33..64 the MFMA tile kernel with 64-row
+ * tiles (K and the boundaries multiples of 64), else the K-splitting skinny kernel; larger M the MFMA tile kernel;
+ * shapes none of them takes (unaligned K or boundaries) a plain one-thread-per-output kernel.
  *   xq dev int8 [M][K] (from sq_quantize_act);  wq dev int8 [N][K];  wscale dev fp32 [S][N];
  *   bias dev fp32 [N] or NULL;  y dev [M][N] of y_dt.
  */

@@ -22,6 +22,7 @@ bool step_ok(float s) { return std::isfinite(s) && s > 0.0f; }
 
 // Shape / table checks shared by every entry point.  need_scales: s_pos / s_neg are used by the call.
 sq_status check_layer(const sq_layer* L, bool need_m, bool need_scales) {
+  (void)hipGetLastError();   // every entry point starts here: an error left by an unrelated earlier call is not this call's
   if (L == nullptr) return SQ_ERR_INVALID_ARG;
   if (L->K < 1 || L->N < 1 || (need_m && L->M < 1)) return SQ_ERR_INVALID_ARG;
   if (L->S < 1 || L->T < 1) return SQ_ERR_INVALID_ARG;

@@ -495,8 +495,10 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
     full_tile = vec4 && ptr16 && m0 + BM <= a.M && n0 + BN <= a.N;
   };
 
-  // per-column constants of block column j in K-segment ks: cw[v] = seg_scale * wscale (0 outside N)
-  auto load_cw = [&](auto full_tag, const int ks, const int j, float (&cw)[16]) __attribute__((always_inline)) {
+  // per-column constants of block column j in K-segment ks: cw[v] = seg_scale * wscale (0 outside N).  fetch_cw only
+  // issues the loads of wscale, scale_cw applies the multiplier: the flush code fetches block column j + 1 before it
+  // works on block column j, so a tile pays one memory latency for its constants, not one per block column.
+  auto fetch_cw = [&](auto full_tag, const int ks, const int j, float (&cw)[16]) __attribute__((always_inline)) {
     constexpr bool FULL = decltype(full_tag)::value;
     const float* ws = a.wscale + (size_t)ks * a.N;
     const bool wvec = FULL || (vec4 && (reinterpret_cast<uintptr_t>(ws) % 16 == 0));
@@ -512,6 +514,8 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
         for (int r = 0; r < 4; ++r) cw[4 * g + r] = (n + r < a.N) ? ws[n + r] : 0.0f;
       }
     }
+  };
+  auto scale_cw = [&](const int ks, const int j, float (&cw)[16]) __attribute__((always_inline)) {
     if (tb.has_seg_scale) {                                // multiplier of block (ks, N-segment of the column)
       float sg[16];
       const float s0 = tb.seg_scale[ks * tb.T];
@@ -526,6 +530,23 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
       }
 #pragma unroll
       for (int v = 0; v < 16; ++v) cw[v] *= sg[v];
+    }
+  };
+
+  auto fetch_bias = [&](auto full_tag, const int j, float (&bs)[16]) __attribute__((always_inline)) {
+    constexpr bool FULL = decltype(full_tag)::value;
+    const bool bvec = FULL || (vec4 && (reinterpret_cast<uintptr_t>(a.bias) % 16 == 0));
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int n = ncol + j * 32 + 8 * g;
+      if (a.bias && bvec && (FULL || n + 3 < a.N)) {
+        const v4f b4 = *reinterpret_cast<const v4f*>(a.bias + n);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) bs[4 * g + r] = b4[r];
+      } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) bs[4 * g + r] = (a.bias && n + r < a.N) ? a.bias[n + r] : 0.0f;
+      }
     }
   };
 
@@ -593,11 +614,14 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
     } else if (SHARE || FSUM) {
       float spr[IM], snr[IM];
       row_steps(ks, dl, spr, snr);
+      float cwb[2][16];
+      fetch_cw(full_tag, ks, 0, cwb[0]);
 #pragma unroll
       for (int j = 0; j < JN; ++j) {
-        float cw[16];
-        load_cw(full_tag, ks, j, cw);
-        __builtin_amdgcn_sched_barrier(0);               // keep the next block column's constants out of this one's registers
+        if (j + 1 < JN) fetch_cw(full_tag, ks, j + 1, cwb[(j + 1) & 1]);
+        __builtin_amdgcn_sched_barrier(0);               // the next block column's loads are out, nothing else moves up
+        float (&cw)[16] = cwb[j & 1];
+        scale_cw(ks, j, cw);
 #pragma unroll
         for (int i = 0; i < IM; ++i) {
           pin_block(i, j);
@@ -644,24 +668,19 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
     float spr[IM], snr[IM];
     row_steps(ks, dl, spr, snr);
     const bool yvec = FULL || (vec4 && (reinterpret_cast<uintptr_t>(a.y) % 16 == 0));
-    const bool bvec = FULL || (vec4 && (reinterpret_cast<uintptr_t>(a.bias) % 16 == 0));
+    float cwb[2][16], bsb[2][16];
+    fetch_cw(full_tag, ks, 0, cwb[0]);
+    fetch_bias(full_tag, 0, bsb[0]);
 #pragma unroll
     for (int j = 0; j < JN; ++j) {
-      float cw[16], bs[16];
-      load_cw(full_tag, ks, j, cw);
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int n = ncol + j * 32 + 8 * g;
-        if (a.bias && bvec && (FULL || n + 3 < a.N)) {
-          const v4f b4 = *reinterpret_cast<const v4f*>(a.bias + n);
-#pragma unroll
-          for (int r = 0; r < 4; ++r) bs[4 * g + r] = b4[r];
-        } else {
-#pragma unroll
-          for (int r = 0; r < 4; ++r) bs[4 * g + r] = (a.bias && n + r < a.N) ? a.bias[n + r] : 0.0f;
-        }
+      if (j + 1 < JN) {
+        fetch_cw(full_tag, ks, j + 1, cwb[(j + 1) & 1]);
+        fetch_bias(full_tag, j + 1, bsb[(j + 1) & 1]);
       }
-      __builtin_amdgcn_sched_barrier(0);                 // keep the next block column's constants out of this one's registers
+      __builtin_amdgcn_sched_barrier(0);                 // the next block column's loads are out, nothing else moves up
+      float (&cw)[16] = cwb[j & 1];
+      float (&bs)[16] = bsb[j & 1];
+      scale_cw(ks, j, cw);
 #pragma unroll
       for (int i = 0; i < IM; ++i) {
         const int m = mrow + i * 32;

@@ -51,7 +51,7 @@ hipError_t launch_calibrate_act_percentile(const void* x, bool x_is_bf16, int M,
 // seglinear_generic.hip : any shape / alignment, one thread per output element
 hipError_t launch_seglinear_generic(const GemmArgs& a, const GemmTable& tb, OutMode mode, hipStream_t st);
 
-// seglinear_mfma.hip : large-M int8 MFMA tile kernel.  Needs K % 16 == 0 and every K-segment boundary % 64 == 0.
+// seglinear_mfma.hip : large-M int8 MFMA tile kernel.  Needs K % 64 == 0 and every K-segment boundary % 64 == 0.
 int mfma_num_variants();
 bool mfma_supported(const GemmArgs& a, const GemmTable& tb);
 int mfma_pick_variant(const GemmArgs& a, const GemmTable& tb, OutMode mode);
