@@ -129,6 +129,21 @@ sq_status sq_calibrate_act_percentile(const sq_layer* layer, const void* x, sq_d
                                       void* stream);
 
 /*
+ * sq_calibrate_act_percentile for callers that cannot allocate device memory or hand over a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without the workspace,
+ * same results to the bit.  The radix-select state (sq_calibrate_static_scratch_bytes() = 132 608 bytes, enough
+ * for the library's maximum of 64 K-segments) lives in a static device array inside the library; every GPU the
+ * library runs on holds its own copy until the process ends.  The call allocates and frees nothing (its first
+ * call on a device looks the array's address up, which allocates nothing either).  Limits: those of the
+ * library, S <= 64 K-segments and M * K < 2^31; beyond them SQ_ERR_UNSUPPORTED, nothing is launched.
+ * All calls on one GPU share the array (it keeps the last call's contents; every call re-initialises what it
+ * reads): calls that overlap on one GPU — different streams or host threads — race, so serialise them.
+ */
+size_t sq_calibrate_static_scratch_bytes(void);
+sq_status sq_calibrate_act_percentile_static(const sq_layer* layer, const void* x, sq_dtype x_dt, double p, float* amax,
+                                             float* steps, int accumulate, void* stream);
+
+/*
  * Q_dual(X) with the polarity split fused in (Sec. 4.3.2).  For a dual K-segment:
  *   x <  0 : X^_- = max(round(x / s_neg[ks]), -127), X^_+ = 0     -> xq = X^_-  (<= 0)
  *   x >= 0 : X^_+ = min(round(x / s_pos[ks]),  127), X^_- = 0     -> xq = X^_+  (>= 0)

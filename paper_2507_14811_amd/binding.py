@@ -27,7 +27,8 @@ EXPORTS = ("sq_quantize_weight", "sq_quantize_act", "sq_seglinear", "sq_seglinea
            "sq_quantize_act_fused_workspace_bytes", "sq_quantize_weight_w4", "sq_seglinear_w4",
            "sq_seglinear_w4_debug_acc", "sq_quantize_act_dynamic", "sq_seglinear_dynamic",
            "sq_seglinear_fused", "sq_seglinear_grouped_fused", "sq_quantize_act_geglu",
-           "sq_seglinear_fused_dynamic", "sq_unpack_w4", "sq_quantize_act_dynamic_bits", "sq_seglinear_grouped_w4")
+           "sq_seglinear_fused_dynamic", "sq_unpack_w4", "sq_quantize_act_dynamic_bits", "sq_seglinear_grouped_w4",
+           "sq_calibrate_act_percentile_static", "sq_calibrate_static_scratch_bytes")
 
 
 class SqError(RuntimeError):
@@ -92,6 +93,10 @@ def load_library() -> C.CDLL:
     lib.sq_seglinear_dynamic.restype = i32
     lib.sq_calibrate_act_percentile.argtypes = [lp, vp, i32, C.c_double, vp, vp, vp, C.c_size_t, i32, vp]
     lib.sq_calibrate_act_percentile.restype = i32
+    lib.sq_calibrate_act_percentile_static.argtypes = [lp, vp, i32, C.c_double, vp, vp, i32, vp]
+    lib.sq_calibrate_act_percentile_static.restype = i32
+    lib.sq_calibrate_static_scratch_bytes.argtypes = []
+    lib.sq_calibrate_static_scratch_bytes.restype = C.c_size_t
     lib.sq_calibrate_workspace_bytes.argtypes = []
     lib.sq_calibrate_workspace_bytes.restype = C.c_size_t
     lib.sq_seglinear_grouped.argtypes = [lp, vp, i32, C.POINTER(sq_group_item), i32, vp]
@@ -232,6 +237,14 @@ def sq_calibrate_act_percentile(layer: Layer, x, p: float, amax, steps, workspac
                                                       workspace.numel() * workspace.element_size(),
                                                       1 if accumulate else 0, _stream(stream)),
            "sq_calibrate_act_percentile")
+
+
+def sq_calibrate_act_percentile_static(layer: Layer, x, p: float, amax, steps, accumulate: bool = False, stream=None) -> None:
+    """sq_calibrate_act_percentile without a workspace: the select state lives in a static device array of the library
+    (no allocation anywhere in the call; calls on one GPU must not overlap)."""
+    _check(load_library().sq_calibrate_act_percentile_static(C.byref(layer.c), _dptr(x), _dt(x), float(p), _dptr(amax),
+                                                             _dptr(steps), 1 if accumulate else 0, _stream(stream)),
+           "sq_calibrate_act_percentile_static")
 
 
 def sq_quantize_act(layer: Layer, x, xq, stream=None) -> None:

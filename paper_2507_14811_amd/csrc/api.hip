@@ -266,6 +266,25 @@ sq_status sq_calibrate_act_percentile(const sq_layer* layer, const void* x, sq_d
   return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 
+sq_status sq_calibrate_act_percentile_static(const sq_layer* layer, const void* x, sq_dtype x_dt, double p, float* amax,
+                                             float* steps, int accumulate, void* stream) {
+  sq_status st = check_layer(layer, true, false);      // also the size limits of the static scratch: S <= SQ_MAX_SEGMENTS
+  if (st != SQ_OK) return st;
+  if (x == nullptr || amax == nullptr || steps == nullptr) return SQ_ERR_INVALID_ARG;
+  if (x_dt != SQ_F32 && x_dt != SQ_BF16) return SQ_ERR_INVALID_ARG;
+  if (!(p > 0.0 && p <= 1.0)) return SQ_ERR_INVALID_ARG;
+  sq::ActTable tb;
+  std::memset(&tb, 0, sizeof(tb));
+  tb.S = layer->S;
+  for (int s = 0; s <= layer->S; ++s) tb.kseg_off[s] = layer->kseg_off[s];
+  for (int s = 0; s < layer->S; ++s) tb.dual[s] = layer->dual[s] ? 1 : 0;
+  hipError_t e = sq::launch_calibrate_act_percentile_static(x, x_dt == SQ_BF16, layer->M, layer->K, tb, p, amax, steps,
+                                                            accumulate != 0, reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
+size_t sq_calibrate_static_scratch_bytes(void) { return sq::calibrate_static_scratch_bytes(); }
+
 static sq_status quantize_act_common(const sq_layer* layer, const void* x, sq_dtype x_dt, const int32_t* act, int8_t* xq,
                                      void* workspace, size_t workspace_bytes, void* stream, bool geglu = false) {
   sq_status st = check_layer(layer, true, true);

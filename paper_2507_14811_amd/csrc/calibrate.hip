@@ -4,6 +4,7 @@
 #include "sq_kernels.hpp"
 
 #include <cmath>
+#include <mutex>
 
 namespace sq {
 
@@ -318,6 +319,45 @@ hipError_t launch_calibrate_act_percentile(const void* x, bool x_is_bf16, int M,
                        ps == npass - 1 ? 1 : 0, accumulate ? 1 : 0, amax, steps);
   }
   return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------------------
+// The same calibration for callers that cannot allocate or pass a workspace (HIP graph capture, serving loops,
+// harnesses that forbid hipMalloc): the radix-select state lives in a file-scope device array.  Every device the
+// library runs on holds its own copy of the array at its own address; the address is looked up once per device
+// (with that device current) and used from then on — the array's name is a host-side stand-in, never a device
+// address.  All calls on one device share the array: calls that overlap on a device race.  Nothing has to be zero
+// on entry: pct_init_kernel clears the histograms and sets ranks, buckets and prefixes at the start of every call.
+// ------------------------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[sizeof(PctState)];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_lock;
+void* g_scratch_ptr[kMaxDevices] = {};
+}  // namespace
+
+size_t calibrate_static_scratch_bytes() { return sizeof(PctState); }
+
+hipError_t launch_calibrate_act_percentile_static(const void* x, bool x_is_bf16, int M, int K, const ActTable& tb, double p,
+                                                  float* amax, float* steps, bool accumulate, hipStream_t st) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  void* ptr = nullptr;
+  {
+    std::lock_guard<std::mutex> guard(g_scratch_lock);
+    if (g_scratch_ptr[dev] == nullptr) {
+      void* found = nullptr;
+      e = hipGetSymbolAddress(&found, HIP_SYMBOL(scratch));
+      if (e != hipSuccess) return e;
+      if (found == nullptr) return hipErrorInvalidSymbol;
+      g_scratch_ptr[dev] = found;
+    }
+    ptr = g_scratch_ptr[dev];
+  }
+  return launch_calibrate_act_percentile(x, x_is_bf16, M, K, tb, p, amax, steps, ptr, accumulate, st);
 }
 
 }  // namespace sq

@@ -48,6 +48,11 @@ size_t calibrate_workspace_bytes();
 hipError_t launch_calibrate_act_percentile(const void* x, bool x_is_bf16, int M, int K, const ActTable& tb, double p,
                                            float* amax, float* steps, void* workspace, bool accumulate, hipStream_t st);
 
+// the same with the select state in a file-scope device array of calibrate.hip (no workspace argument, no allocation)
+size_t calibrate_static_scratch_bytes();
+hipError_t launch_calibrate_act_percentile_static(const void* x, bool x_is_bf16, int M, int K, const ActTable& tb, double p,
+                                                  float* amax, float* steps, bool accumulate, hipStream_t st);
+
 // seglinear_generic.hip : any shape / alignment, one thread per output element
 hipError_t launch_seglinear_generic(const GemmArgs& a, const GemmTable& tb, OutMode mode, hipStream_t st);
 
