@@ -72,6 +72,37 @@ def _time_events(fn, iters):
     return [a.elapsed_time(b) for a, b in evs]
 
 
+def _gpu_side_ms(fns, launches=200, replays=5):
+    """GPU-side time per launch with the host's launch cost taken out: `launches` launches, cycling over `fns` (one
+    callable per buffer set, so that a rotation over distinct buffers defeats the caches), are captured into one HIP
+    graph, the graph is replayed, and the time between two events around a replay is divided by the launch count.
+    From Python a launch through ctypes costs 6-7 us of host time, more than the small kernels take."""
+    import torch
+
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        for f in fns:
+            f()
+    torch.cuda.synchronize()
+    n = max(len(fns), (launches // len(fns)) * len(fns))
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=st):
+        for i in range(n):
+            fns[i % len(fns)]()
+    g.replay()
+    torch.cuda.synchronize()
+    ts = []
+    for _ in range(replays):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        ts.append(e0.elapsed_time(e1) / n)
+    del g
+    return float(np.median(ts))
+
+
 def measure(name, steps, warmup, rotate_quant=True):
     """Times one workload.  Returns a dict of per-kernel and per-step figures."""
     import torch
@@ -150,7 +181,9 @@ def measure(name, steps, warmup, rotate_quant=True):
 
     quant_rot()
     torch.cuda.synchronize()
-    ms_quant = float(np.median(_time_events(quant_rot, reps))) / nrot
+    ms_quant_stream = float(np.median(_time_events(quant_rot, reps))) / nrot      # launched from Python, one after another
+    ms_quant = _gpu_side_ms([(lambda i=i: sq.sq_quantize_act(layer, xs[i], xqs[i])) for i in range(nrot)],
+                            launches=max(nrot, 60))
     # restore the canonical buffers for the GEMM
     quant()
     torch.cuda.synchronize()
@@ -201,7 +234,7 @@ def measure(name, steps, warmup, rotate_quant=True):
 
     # Skinny layers are one pass over the weights: with a single weight set the pass is served by the 256 MB
     # Infinity Cache, so also stream over a rotation of distinct (weights, scales) sets totalling > 512 MB.
-    ms_gemm_hbm, nsets = None, 1
+    ms_gemm_hbm, ms_gemm_hbm_stream, nsets = None, None, 1
     if w.M <= 64:
         wbytes = w.N * w.K
         nsets = int(min(64, max(2, np.ceil(600e6 / wbytes))))
@@ -221,16 +254,20 @@ def measure(name, steps, warmup, rotate_quant=True):
             rot()
         e1.record()
         torch.cuda.synchronize()
-        ms_gemm_hbm = e0.elapsed_time(e1) / (reps * nsets)
+        ms_gemm_hbm_stream = e0.elapsed_time(e1) / (reps * nsets)                # launched from Python
+        ms_gemm_hbm = _gpu_side_ms([(lambda i=i: sq.sq_seglinear(layer, s["xq"], wqs[i], wss[i], None, s["y"])) for i in range(nsets)],
+                                   launches=max(nsets, 128))
         del wqs, wss
     return dict(
         xq_codes=s["xq"].reshape(-1),
+        xq_dual_cols=(s["xq"][:, int(w.kseg_off[int(np.argmax(w.dual))]):int(w.kseg_off[int(np.argmax(w.dual)) + 1])].contiguous()
+                      if any(w.dual) else None),
         name=w.name, M=w.M, K=w.K, N=w.N, S=w.S, T=w.T, dual=[int(d) for d in w.dual],
         int8_ops=w.int8_ops, ms_step=ms_step, ms_gemm=ms_gemm, ms_quant=ms_quant, ms_quantize_weight=t_wq,
         gemm_tops=w.int8_ops / (ms_gemm * 1e-3) / 1e12, step_tops=w.int8_ops / (ms_step * 1e-3) / 1e12,
         ms_gemm_b2b=ms_gemm_b2b, gemm_tops_b2b=w.int8_ops / (ms_gemm_b2b * 1e-3) / 1e12,
         gemm_bytes=gbytes, gemm_gbs=gbytes / (ms_gemm * 1e-3) / 1e9, gemm_gbs_b2b=gbytes / (ms_gemm_b2b * 1e-3) / 1e9,
-        ms_gemm_hbm=ms_gemm_hbm, weight_sets=nsets, ms_quant_fused=ms_quant_fused, ms_quant_fused_lut=ms_quant_fused_lut, ms_quant_dyn=ms_quant_dyn, ms_gemm_dyn=ms_gemm_dyn, ms_calibrate=ms_calib, ms_calibrate_percentile=ms_calib_pct, ms_quantize_weight_block=ms_wblock,
+        ms_gemm_hbm=ms_gemm_hbm, ms_gemm_hbm_stream=ms_gemm_hbm_stream, ms_quant_stream=ms_quant_stream, weight_sets=nsets, ms_quant_fused=ms_quant_fused, ms_quant_fused_lut=ms_quant_fused_lut, ms_quant_dyn=ms_quant_dyn, ms_gemm_dyn=ms_gemm_dyn, ms_calibrate=ms_calib, ms_calibrate_percentile=ms_calib_pct, ms_quantize_weight_block=ms_wblock,
         calib_gbs=(w.M * w.K * (2 if w.x_dtype == "bf16" else 4)) / (ms_calib * 1e-3) / 1e9,
         gemm_gbs_hbm=(gbytes / (ms_gemm_hbm * 1e-3) / 1e9) if ms_gemm_hbm else None,
         quant_bytes=qbytes, quant_gbs=qbytes / (ms_quant * 1e-3) / 1e9, quant_rotation=nrot,
@@ -445,39 +482,87 @@ def measure_w4(steps=40):
             "weight_sets_rotated": nsets}
 
 
-def measured_ceilings(head_setup_codes):
-    """Ceilings measured on this device, reported next to the datasheet peaks: the sustained int8 MFMA rate of a
-    register-only loop (for all-zero operands and for operands distributed like the headline layer's codes) and a
-    plain device copy over 2 x 1 GiB."""
+def _timed_launches(fn, reps=200):
+    """(ms per launch from one HIP event pair around `reps` back-to-back launches, median ms of single launches each
+    bracketed by its own event pair)."""
     import torch
 
-    import paper_2507_14811_amd as sq
+    for _ in range(20):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    b2b = e0.elapsed_time(e1) / reps
+    single = float(np.median(_time_events(fn, 50)))
+    return b2b, single
+
+
+def measured_ceilings(head_setup_codes, dual_cols=None):
+    """Ceilings and floors measured on this device with the probe library, reported next to the datasheet peaks:
+    the sustained int8 MFMA rate of a register-only loop (all-zero operands; operands distributed like the headline
+    layer's codes; the same with the activation operand split by polarity as the dual path feeds it), a plain device
+    copy over 2 x 1 GiB, and what a launch costs: an empty kernel in the launch shapes the library uses, and a kernel
+    that makes one dependent trip to memory."""
+    import torch
+
+    from paper_2507_14811_amd import probes
 
     out = {}
     zeros = torch.zeros(16 << 20, dtype=torch.int8, device="cuda:0")
-    for label, codes in (("zero_operands", zeros), ("layer_like_operands", head_setup_codes)):
+    cases = [("zero_operands", zeros), ("layer_like_operands", head_setup_codes)]
+    if dual_cols is not None:   # A operands: X^_+ of the dual K-segment (negatives zeroed), B operands: codes as they are
+        n = (min(dual_cols.numel(), 8 << 20) // 64) * 64
+        a_op = torch.clamp(dual_cols.reshape(-1)[:n], min=0).view(-1, 64)
+        b_op = head_setup_codes.reshape(-1)[:n].view(-1, 64)
+        cases.append(("layer_like_operands_positive_polarity", torch.cat([a_op, b_op], dim=1).contiguous().view(-1)))
+    for label, codes in cases:
         iters = 20000
         for _ in range(3):   # ~10 ms each: lets the clocks settle at this load
-            sq.sq_probe_mfma(codes, iters)
+            probes.sqp_mfma(codes, iters)
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        ops = sq.sq_probe_mfma(codes, iters)
+        ops = probes.sqp_mfma(codes, iters)
         e1.record()
         torch.cuda.synchronize()
         out["mfma_int8_tops_" + label] = round(ops / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
     src = torch.empty(1 << 30, dtype=torch.int8, device="cuda:0")
     dst = torch.empty(1 << 30, dtype=torch.int8, device="cuda:0")
     for _ in range(3):
-        dst.copy_(src)
+        probes.sqp_copy(src, dst)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(5):
-        dst.copy_(src)
+        probes.sqp_copy(src, dst)
     e1.record()
     torch.cuda.synchronize()
     out["device_copy_gbs_read_plus_write"] = round(5 * 2 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+    del src, dst
+    # launch floors: [back to back, single launch between its own events], microseconds
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    floors = {}
+    for label, (grid, block, lds) in {"one_workgroup_64_threads": (1, 64, 0),
+                                     "one_workgroup_per_cu_256_threads_144KiB_lds": (cus, 256, 144 * 1024),
+                                     "one_workgroup_per_cu_1024_threads_156KiB_lds": (cus, 1024, 156 * 1024),
+                                     "2304_workgroups_256_threads": (2304, 256, 0),
+                                     "17280_workgroups_256_threads": (17280, 256, 0)}.items():
+        fn = lambda: probes.sqp_launch(grid, block, lds)
+        b2b, single = _timed_launches(fn)
+        floors[label] = {"gpu_side": round(_gpu_side_ms([fn]) * 1e3, 2), "from_python_back_to_back": round(b2b * 1e3, 2),
+                         "from_python_single_between_events": round(single * 1e3, 2)}
+    buf_a = torch.zeros(cus * 1024, dtype=torch.int32, device="cuda:0")
+    buf_b = torch.zeros(cus * 1024, dtype=torch.int32, device="cuda:0")
+    fn = lambda: probes.sqp_roundtrip(buf_a, buf_b, cus, 1024)
+    b2b, single = _timed_launches(fn)
+    floors["one_memory_round_trip_1024_threads_per_cu"] = {"gpu_side": round(_gpu_side_ms([fn]) * 1e3, 2),
+                                                           "from_python_back_to_back": round(b2b * 1e3, 2),
+                                                           "from_python_single_between_events": round(single * 1e3, 2)}
+    out["launch_floor_us"] = floors
     return out
 
 
@@ -536,13 +621,18 @@ def main():
 
     # One plain device copy of known size (256 MiB read + 256 MiB written): under rocprofv3 --pmc it gives
     # the reading of FETCH_SIZE / WRITE_SIZE for a known traffic, which scales the kernels' readings.
-    cal = torch.zeros(64 << 20, dtype=torch.int32, device="cuda:0")
-    cal.add_(1)            # an elementwise kernel: 256 MiB fetched, 256 MiB written
+    from paper_2507_14811_amd import probes
+
+    cal_src = torch.zeros(256 << 20, dtype=torch.int8, device="cuda:0")
+    cal_dst = torch.empty_like(cal_src)
+    probes.sqp_copy(cal_src, cal_dst)      # probe_copy_kernel: 256 MiB fetched, 256 MiB written
     torch.cuda.synchronize()
-    del cal
+    del cal_src, cal_dst
 
     head = measure(args.config, args.steps, args.warmup)
-    ceilings = measured_ceilings(head.pop("xq_codes"))
+    dual_cols = head.pop("xq_dual_cols")
+    ceilings = measured_ceilings(head.pop("xq_codes"), dual_cols)
+    del dual_cols
     grouped = measure_grouped() if "cfg3" in args.others.split(",") else None
     w4 = measure_w4() if "cfg3x28" in args.others.split(",") else None
     geglu = measure_geglu()
@@ -558,15 +648,28 @@ def main():
             "gemm_gbs": round(r["gemm_gbs_b2b"], 1), "gemm_frac_hbm_peak": round(r["gemm_gbs_b2b"] / HBM_PEAK_GBS, 4),
             "gemm_bound": "hbm" if skinny else "mfma",
             "quant_gbs": round(r["quant_gbs"], 1), "quant_frac_hbm_peak": round(r["quant_gbs"] / HBM_PEAK_GBS, 4),
+            "quant_bytes": r["quant_bytes"], "ms_quant_launched_from_python": round(r["ms_quant_stream"], 5),
             "ms_quantize_weight": round(r["ms_quantize_weight"], 5),
         }
         if skinny:   # the stream from HBM (rotation over distinct weight sets) is the figure for the HBM roofline
             others[name].update({
                 "weight_sets_rotated": r["weight_sets"], "ms_gemm_from_hbm": round(r["ms_gemm_hbm"], 5),
+                "ms_gemm_from_hbm_launched_from_python": round(r["ms_gemm_hbm_stream"], 5), "gemm_bytes": r["gemm_bytes"],
                 "gemm_gbs_from_hbm": round(r["gemm_gbs_hbm"], 1),
                 "gemm_frac_hbm_peak_from_hbm": round(r["gemm_gbs_hbm"] / HBM_PEAK_GBS, 4),
                 "gemm_gbs_cache_resident": round(r["gemm_gbs_b2b"], 1)})
 
+    floors = ceilings["launch_floor_us"]
+    for name, o in others.items():
+        if o["gemm_bound"] == "hbm":
+            # a skinny layer is one launch of one workgroup per compute unit (1024 threads, the whole LDS): what that
+            # launch costs empty, and with one trip to memory, next to what the layer takes (all GPU-side)
+            o["launch_floor_us"] = floors["one_workgroup_per_cu_1024_threads_156KiB_lds"]["gpu_side"]
+            o["one_round_trip_floor_us"] = floors["one_memory_round_trip_1024_threads_per_cu"]["gpu_side"]
+            o["gemm_us_over_round_trip_floor"] = round(o["ms_gemm_from_hbm"] * 1e3 / max(o["one_round_trip_floor_us"], 1e-3), 2)
+            # the most a single launch of this layer can reach: its bytes at the HBM peak behind one round trip
+            best_us = o["one_round_trip_floor_us"] + o["gemm_bytes"] / (HBM_PEAK_GBS * 1e3)
+            o["frac_hbm_peak_reachable_by_one_launch"] = round(o["gemm_bytes"] / (best_us * 1e3) / HBM_PEAK_GBS, 4)
     line = {
         "metric": "int8 TOPS (both dual paths) of SegLinear+DualScale GEMM; % int8 MFMA peak",
         "value": round(head["step_tops"], 3),
@@ -594,6 +697,7 @@ def main():
             "ms_per_launch": round(head["ms_gemm"], 5),
             "ms_per_launch_back_to_back": round(head["ms_gemm_b2b"], 5),
             "traffic": MEASURED_TRAFFIC.get(head["name"]),
+            "frac_of_measured_mfma_ceiling": round(head["gemm_tops"] / max(ceilings["mfma_int8_tops_layer_like_operands"], 1e-9), 4),
         },
         "quantize_act": {"bound": "hbm", "achieved": round(head["quant_gbs"], 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                          "frac": round(head["quant_gbs"] / HBM_PEAK_GBS, 4), "ms_per_launch": round(head["ms_quant"], 5),

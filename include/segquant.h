@@ -355,15 +355,6 @@ sq_status sq_seglinear_dynamic(const sq_layer* layer, const int8_t* xq, const fl
                                int32_t w_bits, const float* wscale, const float* bias, void* y, sq_dtype y_dt,
                                void* stream);
 
-/*
- * Benchmark probe, not part of the method: a register-only int8 MFMA loop on every compute unit whose operands
- * are taken from `codes` (dev, int8, `bytes` >= 4096, 16-byte aligned).  The sustained rate depends on the
- * operand values because the core clock is power-managed, so the benchmark reports it for codes distributed
- * like a layer's next to the datasheet peak.  `*ops` (host, may be NULL) receives the int8 operations
- * (2 per multiply-add) one launch executes; the caller times the launch.
- */
-sq_status sq_probe_mfma(const int8_t* codes, size_t bytes, int iters, double* ops, void* stream);
-
 /* Human-readable name of a status code (static storage). */
 const char* sq_status_string(sq_status s);
 

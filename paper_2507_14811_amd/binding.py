@@ -21,7 +21,7 @@ SQ_MAX_SEG_SCALE = 512
 SQ_MAX_KSEG_LEN = 133143
 
 EXPORTS = ("sq_quantize_weight", "sq_quantize_act", "sq_seglinear", "sq_seglinear_debug_acc",
-           "sq_status_string", "sq_version", "sq_tuning_set", "sq_probe_mfma", "sq_seglinear_grouped",
+           "sq_status_string", "sq_version", "sq_tuning_set", "sq_seglinear_grouped",
            "sq_quantize_weight_block", "sq_calibrate_act", "sq_calibrate_act_percentile",
            "sq_calibrate_workspace_bytes", "sq_quantize_act_fused",
            "sq_quantize_act_fused_workspace_bytes", "sq_quantize_weight_w4", "sq_seglinear_w4",
@@ -115,8 +115,6 @@ def load_library() -> C.CDLL:
     lib.sq_seglinear_grouped_w4.restype = i32
     lib.sq_seglinear_grouped_fused.argtypes = [lp, vp, i32, C.POINTER(C.c_int32), i32, C.POINTER(sq_group_item), i32, vp]
     lib.sq_seglinear_grouped_fused.restype = i32
-    lib.sq_probe_mfma.argtypes = [vp, C.c_size_t, i32, C.POINTER(C.c_double), vp]
-    lib.sq_probe_mfma.restype = i32
     lib.sq_status_string.argtypes = [i32]
     lib.sq_status_string.restype = C.c_char_p
     lib.sq_version.restype = i32
@@ -195,14 +193,6 @@ def _dt(t) -> int:
 def _check(st: int, what: str):
     if st != SQ_OK:
         raise SqError(st, what)
-
-
-def sq_probe_mfma(codes, iters: int, stream=None) -> float:
-    """Launches the register-only int8 MFMA probe on int8 device tensor `codes`; returns the ops of one launch."""
-    ops = C.c_double(0.0)
-    _check(load_library().sq_probe_mfma(_dptr(codes), codes.numel(), int(iters), C.byref(ops), _stream(stream)),
-           "sq_probe_mfma")
-    return float(ops.value)
 
 
 def sq_quantize_weight(layer: Layer, w, wq, wscale, stream=None) -> None:

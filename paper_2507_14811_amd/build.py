@@ -1,7 +1,8 @@
 """Builds libsegquant.so (HIP, gfx950 only) in-tree with hipcc.
 
 Every source is compiled to an object in parallel (the MFMA kernel once per tile variant, each in a
-translation unit of its own) and linked into ``paper_2507_14811_amd/libsegquant.so``.
+translation unit of its own) and linked into ``paper_2507_14811_amd/libsegquant.so``; the benchmark probes
+(``csrc/probes.hip``) become ``libsegquant_probes.so``.
 Run as ``python -m paper_2507_14811_amd.build``.
 """
 from __future__ import annotations
@@ -26,8 +27,10 @@ FLAGS = [
     "-Wno-unknown-warning-option", "-Wno-unused-command-line-argument",
     f"-I{os.path.join(ROOT, 'include')}", f"-I{CSRC}",
 ]
-PLAIN_SOURCES = ["api.hip", "quantize.hip", "seglinear_generic.hip", "seglinear_skinny.hip", "seglinear_stream.hip", "probes.hip", "calibrate.hip",
+PLAIN_SOURCES = ["api.hip", "quantize.hip", "seglinear_generic.hip", "seglinear_skinny.hip", "seglinear_stream.hip", "calibrate.hip",
                  "seglinear_mfma.hip"]
+# benchmark probes: a library of their own (include/segquant_probes.h), loaded by bench.py only
+PROBE_LIB = os.path.join(PKG, "libsegquant_probes.so")
 
 
 def _num_variants() -> int:
@@ -70,6 +73,14 @@ def build_library(verbose: bool = True, jobs: int | None = None) -> str:
     os.replace(tmp, LIB)
     if verbose:
         print(f"[build] linked {LIB}", flush=True)
+    tmp = PROBE_LIB + f".tmp{os.getpid()}"
+    cmd = [HIPCC, *FLAGS, "-shared", os.path.join(CSRC, "probes.hip"), "-o", tmp]
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed for the probe library:\n" + r.stdout)
+    os.replace(tmp, PROBE_LIB)
+    if verbose:
+        print(f"[build] linked {PROBE_LIB}", flush=True)
     return LIB
 
 

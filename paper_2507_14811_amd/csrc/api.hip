@@ -583,14 +583,6 @@ sq_status sq_seglinear_fused_dynamic(const sq_layer* layer, const void* x, sq_dt
   return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 
-sq_status sq_probe_mfma(const int8_t* codes, size_t bytes, int iters, double* ops, void* stream) {
-  if (codes == nullptr || bytes < 4096 || bytes > 0xFFFFFFFFull || iters < 1 || iters > (1 << 24)) return SQ_ERR_INVALID_ARG;
-  if (reinterpret_cast<uintptr_t>(codes) % 16 != 0) return SQ_ERR_INVALID_ARG;
-  if (ops) *ops = (double)sq::device_cus() * 4.0 * (double)iters * 8.0 * 65536.0;   // 2*32*32*32 per MFMA
-  hipError_t e = sq::launch_probe_mfma(codes, bytes, iters, nullptr, reinterpret_cast<hipStream_t>(stream));
-  return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
-}
-
 const char* sq_status_string(sq_status s) {
   switch (s) {
     case SQ_OK: return "SQ_OK";
@@ -608,6 +600,11 @@ sq_status sq_tuning_set(const char* key, int value) {
   if (std::strcmp(key, "gemm_variant") == 0) {
     if (value < -1 || value >= sq::mfma_num_variants()) return SQ_ERR_INVALID_ARG;
     g_gemm_variant = value;
+    return SQ_OK;
+  }
+  if (std::strcmp(key, "group_m") == 0) {
+    if (value < 0 || value > 1024) return SQ_ERR_INVALID_ARG;
+    sq::mfma_set_group_m(value);
     return SQ_OK;
   }
   if (std::strcmp(key, "force_path") == 0) {

@@ -1,11 +1,24 @@
-// Device probes used by the benchmark to put measured ceilings next to the datasheet peaks.
-#include "sq_kernels.hpp"
+// Benchmark probes (libsegquant_probes.so): measured ceilings and floors that the benchmark prints next to the
+// datasheet figures.  Self-contained: shares nothing with the library proper.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
 
-namespace sq {
+#include "segquant_probes.h"
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+int device_cus() {
+  int dev = 0, cus = 256;
+  if (hipGetDevice(&dev) != hipSuccess) return 256;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
+  return cus;
+}
 
 // Register-only int8 MFMA loop: every wave multiplies operands it loaded once (so their values, not memory,
-// set the switching activity) into 8 independent 32x32 accumulators.  The sustained rate depends on the
-// operand data because the core clock is power-managed.
+// set the switching activity) into 8 independent 32x32 accumulators.
 __global__ __launch_bounds__(256) void probe_mfma_kernel(const v4i* __restrict__ codes, const uint32_t nvec,
                                                          const int iters, int* __restrict__ sink) {
   const uint32_t gid = blockIdx.x * 256u + threadIdx.x;
@@ -31,10 +44,73 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(const v4i* __restrict__
   if (s == 0x7E57AB1E && sink) sink[0] = s;     // keeps the loop alive; practically never true
 }
 
-hipError_t launch_probe_mfma(const void* codes, size_t bytes, int iters, int* sink, hipStream_t st) {
-  hipLaunchKernelGGL(probe_mfma_kernel, dim3(device_cus()), dim3(256), 0, st, reinterpret_cast<const v4i*>(codes),
-                     (uint32_t)(bytes / 16), iters, sink);
-  return hipGetLastError();
+__global__ void probe_launch_kernel(int* sink) {
+  extern __shared__ char lds[];
+  if (sink != nullptr && threadIdx.x == 4096) sink[0] = lds[0];   // never true: the kernel does nothing
 }
 
-}  // namespace sq
+__global__ void probe_roundtrip_kernel(const int32_t* __restrict__ src, int32_t* __restrict__ dst) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  dst[i] = src[i];
+}
+
+__global__ __launch_bounds__(256) void probe_copy_kernel(const v4i* __restrict__ src, v4i* __restrict__ dst, size_t nvec) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
+int status_of(hipError_t e) { return e == hipSuccess ? 0 : 3; }
+
+}  // namespace
+
+extern "C" {
+
+int sqp_mfma(const int8_t* codes, size_t bytes, int iters, double* ops, void* stream) {
+  (void)hipGetLastError();
+  if (codes == nullptr || bytes < 4096 || bytes > 0xFFFFFFFFull || iters < 1 || iters > (1 << 24)) return 1;
+  if (reinterpret_cast<uintptr_t>(codes) % 16 != 0) return 1;
+  const int cus = device_cus();
+  if (ops) *ops = (double)cus * 4.0 * (double)iters * 8.0 * 65536.0;   // 2*32*32*32 per MFMA
+  hipLaunchKernelGGL(probe_mfma_kernel, dim3(cus), dim3(256), 0, reinterpret_cast<hipStream_t>(stream),
+                     reinterpret_cast<const v4i*>(codes), (uint32_t)(bytes / 16), iters, (int*)nullptr);
+  return status_of(hipGetLastError());
+}
+
+int sqp_launch(int grid, int block, int lds_bytes, void* stream) {
+  (void)hipGetLastError();
+  if (grid < 1 || grid > (1 << 20) || block < 64 || block > 1024 || block % 64 != 0) return 1;
+  if (lds_bytes < 0 || lds_bytes > 160 * 1024) return 1;
+  if (lds_bytes > 64 * 1024) {
+    static bool raised = false;      // a kernel attribute, set once per process
+    if (!raised) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(probe_launch_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              160 * 1024) != hipSuccess)
+        return 3;
+      raised = true;
+    }
+  }
+  hipLaunchKernelGGL(probe_launch_kernel, dim3(grid), dim3(block), (size_t)lds_bytes, reinterpret_cast<hipStream_t>(stream),
+                     (int*)nullptr);
+  return status_of(hipGetLastError());
+}
+
+int sqp_roundtrip(const int32_t* src, int32_t* dst, int grid, int block, void* stream) {
+  (void)hipGetLastError();
+  if (src == nullptr || dst == nullptr || grid < 1 || grid > (1 << 20) || block < 64 || block > 1024 || block % 64 != 0) return 1;
+  hipLaunchKernelGGL(probe_roundtrip_kernel, dim3(grid), dim3(block), 0, reinterpret_cast<hipStream_t>(stream), src, dst);
+  return status_of(hipGetLastError());
+}
+
+int sqp_copy(const void* src, void* dst, size_t bytes, void* stream) {
+  (void)hipGetLastError();
+  if (src == nullptr || dst == nullptr || bytes < 16 || bytes % 16 != 0) return 1;
+  if ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) % 16 != 0) return 1;
+  const size_t nvec = bytes / 16;
+  size_t blocks = (nvec + 255) / 256;
+  const size_t cap = (size_t)device_cus() * 16;
+  if (blocks > cap) blocks = cap;
+  hipLaunchKernelGGL(probe_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, reinterpret_cast<hipStream_t>(stream),
+                     reinterpret_cast<const v4i*>(src), reinterpret_cast<v4i*>(dst), nvec);
+  return status_of(hipGetLastError());
+}
+
+}  // extern "C"

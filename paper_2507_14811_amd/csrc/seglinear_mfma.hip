@@ -20,6 +20,8 @@ template <int... V> static constexpr VariantTables<V...> tables_of(std::integer_
 using Tables = decltype(tables_of(std::make_integer_sequence<int, kNumMfmaVariants>{}));
 static MfmaVariantInfo variant_info(int v) { return Tables::info[v]; }
 int mfma_num_variants() { return kNumMfmaVariants; }
+static int g_group_m = 0;
+void mfma_set_group_m(int g) { g_group_m = g; }
 
 // dual: some K-segment runs both polarity paths; multi: more than one K-segment; share: exactly one dual
 // segment among several, so it can be visited first and its X^_- accumulator registers re-used as the fp32
@@ -114,7 +116,8 @@ hipError_t launch_seglinear_mfma(GemmArgs a, const GemmTable& tb_in, OutMode mod
   }
   a.tiles_m = (a.M + i.BM - 1) / i.BM;
   a.tiles_n = (a.N + i.BN - 1) / i.BN;
-  a.group_m = a.tiles_m < 8 ? a.tiles_m : 8;
+  const int gm = g_group_m > 0 ? g_group_m : 8;
+  a.group_m = a.tiles_m < gm ? a.tiles_m : gm;
   // persistent workgroups: one per compute unit (times the variant's residency), fewer if there are fewer tiles
   const long slots = (long)device_cus() * i.MINB;
   const long tiles = (long)a.tiles_m * a.tiles_n;

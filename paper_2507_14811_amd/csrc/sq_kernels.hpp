@@ -58,6 +58,7 @@ hipError_t launch_seglinear_generic(const GemmArgs& a, const GemmTable& tb, OutM
 
 // seglinear_mfma.hip : large-M int8 MFMA tile kernel.  Needs K % 64 == 0 and every K-segment boundary % 64 == 0.
 int mfma_num_variants();
+void mfma_set_group_m(int g);   // diagnostics: panel height of the tile order (0: default)
 bool mfma_supported(const GemmArgs& a, const GemmTable& tb);
 int mfma_pick_variant(const GemmArgs& a, const GemmTable& tb, OutMode mode);
 hipError_t launch_seglinear_mfma(GemmArgs a, const GemmTable& tb, OutMode mode, int variant, hipStream_t st);
@@ -72,9 +73,6 @@ hipError_t launch_seglinear_stream(const GemmArgs& a, const GemmTable& tb, OutMo
 bool stream_grouped_supported(const GemmArgs& a, const GroupSegTable& tb);
 hipError_t launch_seglinear_grouped(const GemmArgs& a, const GroupSegTable& tb, const GroupTable& gt, OutMode mode, int cus,
                                     hipStream_t st, bool w4 = false);
-
-// probes.hip : register-only int8 MFMA loop on every CU (benchmark ceiling)
-hipError_t launch_probe_mfma(const void* codes, size_t bytes, int iters, int* sink, hipStream_t st);
 
 // compute units of the current device (cached)
 int device_cus();

@@ -35,6 +35,28 @@ def test_every_declared_symbol_is_exported(sq):
     assert set(binding.EXPORTS) == declared
 
 
+def test_probe_library_exports_its_header(sq):
+    """libsegquant_probes.so (benchmark probes, loaded by bench.py only) exports what include/segquant_probes.h declares,
+    and the product library exports none of it."""
+    import ctypes
+
+    from paper_2507_14811_amd import build, probes
+
+    if not os.path.exists(probes.LIB_PATH):
+        build.build_library(verbose=False)
+    with open(os.path.join(ROOT, "include", "segquant_probes.h")) as f:
+        declared = set(re.findall(r"\b(sqp_[a-z0-9_]+)\s*\(", f.read()))
+    assert declared == set(probes.EXPORTS)
+    lib = ctypes.CDLL(probes.LIB_PATH)
+    main = sq.load_library()
+    for name in declared:
+        assert hasattr(lib, name), name
+        assert not hasattr(main, name), name
+    # argument checks run on the host, before anything is launched
+    assert lib.sqp_launch(0, 64, 0, None) == 1 and lib.sqp_launch(1, 100, 0, None) == 1
+    assert lib.sqp_copy(None, None, ctypes.c_size_t(16), None) == 1
+
+
 def test_status_strings_and_version(sq):
     assert sq.sq_version() >= 100
     assert [sq.status_string(i) for i in range(4)] == ["SQ_OK", "SQ_ERR_INVALID_ARG", "SQ_ERR_UNSUPPORTED", "SQ_ERR_LAUNCH"]
