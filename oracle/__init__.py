@@ -30,4 +30,8 @@ from .segquant_oracle import (  # noqa: F401
     seglinear,
     seglinear_dynamic,
     widen_bf16,
+    channel_amax,
+    smooth_factors,
+    quantize_weight_smoothed,
+    smooth_act,
 )

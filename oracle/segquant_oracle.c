@@ -559,3 +559,75 @@ int sqo_quantize_weight_block(const float* w, int N, int K, int S, const int32_t
   }
   return 0;
 }
+
+/*
+ * Per-segment smoothing in front of the quantizers (Sec. 4.2.2, last paragraph: SegLinear shares the migration
+ * strength alpha of SmoothQuant across a semantically coherent channel group; App. B: SmoothQuant is the optimizer of
+ * the 8-bit settings, alpha swept per layer).  The published SmoothQuant rule, one alpha per K-segment:
+ *   a_x[k] = max_m |X[m][k]|  over the calibration batches,   a_w[k] = max_n |W[n][k]|,
+ *   s[k]   = a_x[k]^alpha / a_w[k]^(1 - alpha)   for k in K-segment ks, alpha = alpha[ks],
+ *   X' = X diag(s)^-1,   W' = W diag(s)   (per input channel k), so that X' W'^T = X W^T,
+ * after which X' and W' go through the ordinary quantizers.
+ * Readings: the powers are evaluated in double and rounded once to fp32; a channel whose a_x or a_w is 0, or whose
+ * factor is not a finite positive fp32 number, keeps s = 1; the activation side multiplies by the fp32 reciprocal
+ * r[k] = 1 / s[k] (one IEEE division, then one multiplication per element: the form in which the factor is folded
+ * into the operator in front of the layer).
+ */
+int sqo_channel_amax(const float* x, int M, int K, float* amax, int accumulate) {
+  for (int k = 0; k < K; ++k) {
+    float a = accumulate ? amax[k] : 0.0f;
+    for (int m = 0; m < M; ++m) {
+      float v = fabsf(x[(int64_t)m * K + k]);
+      if (v > a) a = v;
+    }
+    amax[k] = a;
+  }
+  return 0;
+}
+
+int sqo_smooth_factors(const float* amax_x, const float* amax_w, int K, int S, const int32_t* kseg_off,
+                       const float* alpha, float* smooth, float* smooth_inv) {
+  if (check_offsets(K, S, kseg_off)) return 1;
+  for (int ks = 0; ks < S; ++ks) {
+    if (!(alpha[ks] >= 0.0f && alpha[ks] <= 1.0f)) return 3;
+    for (int k = kseg_off[ks]; k < kseg_off[ks + 1]; ++k) {
+      float s = 1.0f;
+      if (amax_x[k] > 0.0f && amax_w[k] > 0.0f) {
+        double d = pow((double)amax_x[k], (double)alpha[ks]) / pow((double)amax_w[k], 1.0 - (double)alpha[ks]);
+        s = (float)d;
+        if (!(s > 0.0f) || !isfinite(s) || !isfinite(1.0f / s)) s = 1.0f;
+      }
+      smooth[k] = s;
+      smooth_inv[k] = 1.0f / s;
+    }
+  }
+  return 0;
+}
+
+/* W'[n][k] = W[n][k] * s[k] (one fp32 multiplication), then the per-channel, per-K-segment quantizer. */
+int sqo_quantize_weight_smoothed(const float* w, int N, int K, int S, const int32_t* kseg_off, const float* smooth,
+                                 int8_t* wq, float* wscale) {
+  if (fegetround() != FE_TONEAREST) return 2;
+  if (check_offsets(K, S, kseg_off)) return 1;
+  for (int n = 0; n < N; ++n) {
+    for (int ks = 0; ks < S; ++ks) {
+      float a = 0.0f;
+      for (int k = kseg_off[ks]; k < kseg_off[ks + 1]; ++k) {
+        float v = fabsf(w[(int64_t)n * K + k] * smooth[k]);
+        if (v > a) a = v;
+      }
+      float sw = (a == 0.0f) ? 1.0f : a / SQO_QMAX;
+      wscale[(int64_t)ks * N + n] = sw;
+      for (int k = kseg_off[ks]; k < kseg_off[ks + 1]; ++k)
+        wq[(int64_t)n * K + k] = quant_sym(w[(int64_t)n * K + k] * smooth[k], sw);
+    }
+  }
+  return 0;
+}
+
+/* X'[m][k] = X[m][k] * r[k] (one fp32 multiplication), written to xs; Q_dual(X') is sqo_quantize_act on xs. */
+int sqo_smooth_act(const float* x, int M, int K, const float* smooth_inv, float* xs) {
+  for (int m = 0; m < M; ++m)
+    for (int k = 0; k < K; ++k) xs[(int64_t)m * K + k] = x[(int64_t)m * K + k] * smooth_inv[k];
+  return 0;
+}

@@ -1,7 +1,8 @@
 """numpy front-end of the plain-C CPU oracle (test infrastructure only).
 
-Argument marshalling only: every arithmetic step is in ``segquant_oracle.c``
-next to this file.  ``build()`` compiles it with gcc; the shared object is
+Argument marshalling, with two exceptions that are plain numpy here and say so where they stand: the GEGLU product
+(one fp32 multiplication per element) and the per-token steps of the dynamic rule with 4-bit activation codes (row
+extremes divided by q_max = 7).  Every other arithmetic step is in ``segquant_oracle.c`` next to this file.  ``build()`` compiles it with gcc; the shared object is
 loaded lazily and rebuilt when the source is newer.
 """
 from __future__ import annotations
@@ -343,3 +344,43 @@ def seglinear_dynamic(x, w, kseg_off, nseg_off, dual, seg_scale=None, bias=None,
     r = OracleResult(wq, ws, xp, xn, None, ap, an, y32, y64)
     r.tok_steps = np.stack([sp, sn])            # [2][M][S]
     return r
+
+
+def channel_amax(x: np.ndarray, running=None) -> np.ndarray:
+    """max_m |X[m][k]| per input channel k (fp32 [K]), folded into `running` if given."""
+    x = _f32(x)
+    M, K = x.shape
+    a = np.zeros(K, np.float32) if running is None else _f32(running).copy()
+    _check(_load().sqo_channel_amax(_p(x), C.c_int(M), C.c_int(K), _p(a), C.c_int(0 if running is None else 1)),
+           "channel_amax")
+    return a
+
+
+def smooth_factors(amax_x, amax_w, kseg_off, alpha):
+    """SmoothQuant factors with one migration strength per K-segment: s[k] = a_x^alpha / a_w^(1 - alpha).
+    -> (smooth fp32 [K], smooth_inv fp32 [K] = 1 / smooth)."""
+    ax, aw, off, al = _f32(amax_x), _f32(amax_w), _i32(kseg_off), _f32(alpha)
+    K, S = len(ax), len(off) - 1
+    s, r = np.empty(K, np.float32), np.empty(K, np.float32)
+    _check(_load().sqo_smooth_factors(_p(ax), _p(aw), C.c_int(K), C.c_int(S), _p(off), _p(al), _p(s), _p(r)), "smooth_factors")
+    return s, r
+
+
+def quantize_weight_smoothed(w: np.ndarray, kseg_off, smooth):
+    """Quant(W diag(s)): -> (wq int8 [N][K], wscale fp32 [S][N])."""
+    w, off, sm = _f32(w), _i32(kseg_off), _f32(smooth)
+    N, K = w.shape
+    S = len(off) - 1
+    wq, ws = np.empty((N, K), np.int8), np.empty((S, N), np.float32)
+    _check(_load().sqo_quantize_weight_smoothed(_p(w), C.c_int(N), C.c_int(K), C.c_int(S), _p(off), _p(sm), _p(wq), _p(ws)),
+           "quantize_weight_smoothed")
+    return wq, ws
+
+
+def smooth_act(x: np.ndarray, smooth_inv) -> np.ndarray:
+    """X diag(s)^-1 as one fp32 multiplication by r[k] = 1 / s[k] per element."""
+    x, r = _f32(x), _f32(smooth_inv)
+    M, K = x.shape
+    out = np.empty((M, K), np.float32)
+    _check(_load().sqo_smooth_act(_p(x), C.c_int(M), C.c_int(K), _p(r), _p(out)), "smooth_act")
+    return out

@@ -740,3 +740,136 @@ def test_dynamic_steps_with_4bit_activation_codes(oracle):
     yfp = oracle.fp_reference(x, w)
     e4, e8 = np.linalg.norm(r4.y64 - yfp), np.linalg.norm(r8.y64 - yfp)
     assert e8 < e4 < 40 * e8
+
+
+# ----------------------------------------------------------------------------------------------------
+# SmoothQuant factors with one migration strength per K-segment (Sec. 4.2.2 last paragraph; App. B)
+# ----------------------------------------------------------------------------------------------------
+def test_smooth_factors_closed_forms(oracle):
+    """s = a_x^alpha / a_w^(1 - alpha): hand-worked values, the two ends of alpha, the geometric mean in the middle,
+    the neutral factor for a dead channel, one alpha per K-segment."""
+    ax = np.array([16.0, 16.0, 9.0, 0.0, 2.0, 5.0], np.float32)
+    aw = np.array([4.0, 4.0, 0.25, 3.0, 0.0, 0.125], np.float32)
+    s, r = oracle.smooth_factors(ax, aw, [0, 6], [0.5])
+    assert s[0] == 2.0 and s[2] == 6.0                       # sqrt(16)/sqrt(4), sqrt(9)/sqrt(0.25)
+    assert s[3] == 1.0 and s[4] == 1.0                       # a_x = 0 or a_w = 0: the channel is left alone
+    assert np.array_equal(r, (np.float32(1.0) / s).astype(np.float32))
+    s0, _ = oracle.smooth_factors(ax, aw, [0, 6], [0.0])     # alpha = 0: everything migrates to the activation side
+    assert s0[0] == 0.25 and s0[5] == 8.0
+    s1, _ = oracle.smooth_factors(ax, aw, [0, 6], [1.0])     # alpha = 1: s = a_x
+    assert s1[0] == 16.0 and s1[5] == 5.0
+    sq, _ = oracle.smooth_factors(ax, aw, [0, 6], [0.25])    # 16^0.25 / 4^0.75 = 2 / 2^1.5 = 2^-0.5
+    assert abs(float(sq[0]) - 2.0 ** -0.5) <= 2.0 ** -25
+    # one alpha per K-segment: each segment is the single-segment rule with its own alpha
+    s2, _ = oracle.smooth_factors(ax, aw, [0, 2, 6], [0.0, 1.0])
+    assert np.array_equal(s2[:2], s0[:2]) and np.array_equal(s2[2:], s1[2:])
+    rng = np.random.default_rng(0)
+    ax = rng.uniform(0.01, 50, 300).astype(np.float32)
+    aw = rng.uniform(0.001, 2, 300).astype(np.float32)
+    for a in (0.1, 0.3, 0.5, 0.8):
+        s, r = oracle.smooth_factors(ax, aw, [0, 300], [a])
+        want = ax.astype(np.float64) ** np.float64(np.float32(a)) / aw.astype(np.float64) ** (1 - np.float64(np.float32(a)))
+        assert np.all(np.abs(s - want) <= np.abs(want) * 2.0 ** -23)
+        assert np.all(np.abs(r.astype(np.float64) * s - 1) <= 2.0 ** -22)
+    with pytest.raises(RuntimeError):
+        oracle.smooth_factors(ax, aw, [0, 300], [1.5])
+
+
+def test_channel_amax(oracle):
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal((37, 50)).astype(np.float32)
+    a = oracle.channel_amax(x)
+    assert np.array_equal(a, np.abs(x).max(axis=0))
+    x2 = (3 * rng.standard_normal((5, 50))).astype(np.float32)
+    b = oracle.channel_amax(x2, running=a)
+    assert np.array_equal(b, np.maximum(np.abs(x).max(axis=0), np.abs(x2).max(axis=0)))
+    z = np.zeros((4, 3), np.float32)
+    assert np.array_equal(oracle.channel_amax(z), np.zeros(3, np.float32))
+
+
+def test_smoothing_migrates_range_between_the_operands(oracle):
+    """Which operand is divided and which is multiplied: alpha = 1 normalises every activation channel to a maximum of
+    1 (and gives the weights the activation's range), alpha = 0 normalises every weight channel; the product of the two
+    smoothed operands is the product of the original ones."""
+    rng = np.random.default_rng(2)
+    M, K, N = 40, 24, 9
+    x = (rng.standard_normal((M, K)) * rng.uniform(0.1, 30, K)).astype(np.float32)
+    w = (rng.standard_normal((N, K)) * 0.05).astype(np.float32)
+    ax, aw = oracle.channel_amax(x), oracle.channel_amax(w)
+    s, r = oracle.smooth_factors(ax, aw, [0, K], [1.0])
+    xs = oracle.smooth_act(x, r)
+    assert np.all(np.abs(np.abs(xs).max(axis=0) - 1.0) <= 2.0 ** -22)
+    s, r = oracle.smooth_factors(ax, aw, [0, K], [0.0])
+    assert np.all(np.abs(np.abs(w * s).max(axis=0) - 1.0) <= 2.0 ** -22)
+    s, r = oracle.smooth_factors(ax, aw, [0, K], [0.5])
+    xs = oracle.smooth_act(x, r)
+    assert np.array_equal(xs, (x * r).astype(np.float32))                   # one fp32 multiplication per element
+    ref = x.astype(np.float64) @ w.astype(np.float64).T
+    got = xs.astype(np.float64) @ (w * s).astype(np.float64).T
+    assert np.abs(got - ref).max() <= 1e-5 * np.abs(ref).max()
+
+
+def test_power_of_two_smoothing_changes_nothing(oracle):
+    """A smoothing factor that is the same power of two for every channel of a K-segment only moves exponents: the
+    weight codes are those of the plain quantizer, the weight steps are multiplied by it, the activation codes are
+    unchanged when the activation steps are divided by it, and the layer's output is bit-identical."""
+    rng = np.random.default_rng(3)
+    M, K, N = 11, 64, 13
+    kseg, dual = [0, 24, 64], [1, 0]
+    w_ = wl.random_layer(M, K, N, kseg, [0, N], dual, seed=7, x_dtype="f32", act="gelu")
+    smooth = np.concatenate([np.full(24, 4.0, np.float32), np.full(40, 0.125, np.float32)])
+    inv = (np.float32(1.0) / smooth).astype(np.float32)
+    wq0, ws0 = oracle.quantize_weight(w_.w, kseg)
+    wq1, ws1 = oracle.quantize_weight_smoothed(w_.w, kseg, smooth)
+    assert np.array_equal(wq0, wq1)
+    assert np.array_equal(ws1[0], ws0[0] * np.float32(4.0)) and np.array_equal(ws1[1], ws0[1] * np.float32(0.125))
+    xs = oracle.smooth_act(w_.x, inv)
+    seg_s = np.array([4.0, 0.125], np.float32)
+    sp, sn = (w_.s_pos / seg_s).astype(np.float32), (w_.s_neg / seg_s).astype(np.float32)
+    xp0, xn0 = oracle.quantize_act(w_.x, kseg, dual, w_.s_pos, w_.s_neg)
+    xp1, xn1 = oracle.quantize_act(xs, kseg, dual, sp, sn)
+    assert np.array_equal(xp0, xp1) and np.array_equal(xn0, xn1)
+    ap, an = oracle.int_gemm(xp1, xn1, wq1, kseg, dual)
+    y0, _ = oracle.dequant(ap, an, [0, N], dual, w_.s_pos, w_.s_neg, ws0)
+    y1, _ = oracle.dequant(ap, an, [0, N], dual, sp, sn, ws1)
+    assert np.array_equal(y0.view(np.uint32), y1.view(np.uint32))
+
+
+def test_smoothed_weight_quantizer_is_the_quantizer_of_the_smoothed_weight(oracle):
+    rng = np.random.default_rng(4)
+    N, K = 17, 96
+    kseg = [0, 32, 96]
+    w = (rng.standard_normal((N, K)) * 0.03).astype(np.float32)
+    s = rng.uniform(0.2, 7.0, K).astype(np.float32)
+    a, b = oracle.quantize_weight_smoothed(w, kseg, s)
+    c, d = oracle.quantize_weight((w * s).astype(np.float32), kseg)
+    assert np.array_equal(a, c) and np.array_equal(b.view(np.uint32), d.view(np.uint32))
+    # exact-rational nearest code for a few entries
+    for (n, k) in [(0, 0), (3, 40), (16, 95)]:
+        ks = 0 if k < 32 else 1
+        v = Fraction(float(np.float32(w[n, k] * s[k]))) / Fraction(float(b[ks, n]))
+        assert abs(Fraction(int(a[n, k])) - v) <= Fraction(1, 2) + Fraction(1, 10 ** 6)
+
+
+def test_smoothing_lowers_the_error_on_outlier_channels(oracle):
+    """The purpose of the optimizer (App. B, Frobenius-norm table of single layers): with a few activation channels
+    20 times larger than the rest, migrating range to the weights (alpha = 0.5) lowers the layer's quantization error."""
+    rng = np.random.default_rng(5)
+    M, K, N = 64, 256, 48
+    x = rng.standard_normal((M, K)).astype(np.float32)
+    x[:, rng.permutation(K)[:3]] *= 20.0
+    w = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    kseg, nseg, dual = [0, K], [0, N], [0]
+    ref = x.astype(np.float64) @ w.astype(np.float64).T
+
+    def err(xx, ww_codes, ww_scales):
+        sp = np.array([np.abs(xx).max() / 127], np.float32)
+        xp, xn = oracle.quantize_act(xx, kseg, dual, sp, sp)
+        ap, an = oracle.int_gemm(xp, xn, ww_codes, kseg, dual)
+        y, _ = oracle.dequant(ap, an, nseg, dual, sp, sp, ww_scales)
+        return float(np.linalg.norm(y - ref))
+
+    plain = err(x, *oracle.quantize_weight(w, kseg))
+    s, r = oracle.smooth_factors(oracle.channel_amax(x), oracle.channel_amax(w), kseg, [0.5])
+    smoothed = err(oracle.smooth_act(x, r), *oracle.quantize_weight_smoothed(w, kseg, s))
+    assert smoothed < 0.6 * plain, (smoothed, plain)
