@@ -144,6 +144,37 @@ sq_status sq_calibrate_act_percentile_static(const sq_layer* layer, const void* 
                                              float* steps, int accumulate, void* stream);
 
 /*
+ * Smoothing in front of the quantizers with one migration strength per K-segment (Sec. 4.2.2, last paragraph: SegLinear
+ * shares SmoothQuant's alpha across a semantically coherent channel group; App. B: SmoothQuant is the optimizer of the
+ * 8-bit settings, alpha chosen per layer from 0.0 .. 1.0).  The published rule per input channel k of K-segment ks:
+ *   a_x[k] = max_m |X[m][k]| over the calibration batches,   a_w[k] = max_n |W[n][k]|,
+ *   s[k] = a_x[k]^alpha[ks] / a_w[k]^(1 - alpha[ks]),   X' = X diag(s)^-1,   W' = W diag(s)   (X' W'^T = X W^T),
+ * and X', W' go through the ordinary quantizers (activation steps are calibrated on X').
+ *   sq_calibrate_channel_amax   x dev [M][K] -> amax_k dev fp32 [K]; accumulate != 0 folds into the running maxima
+ *   sq_weight_channel_amax      w dev [N][K] -> amax_k dev fp32 [K]
+ *   sq_smooth_factors           HOST computation on HOST arrays (K numbers; the caller sweeps alpha): amax_x, amax_w
+ *                               fp32 [K] in, alpha fp32 [S] in (0 <= alpha <= 1), smooth, smooth_inv fp32 [K] out.
+ *                               Powers in double, rounded once to fp32; a channel with a_x = 0 or a_w = 0, or whose
+ *                               factor or reciprocal is not a finite positive fp32 number, keeps s = 1;
+ *                               smooth_inv[k] = 1 / smooth[k] (one fp32 division).  Launches nothing.
+ *   sq_quantize_weight_smoothed sq_quantize_weight of W diag(s): every weight is multiplied by smooth[k] (dev fp32 [K],
+ *                               one fp32 multiplication) before the maxima and the codes
+ *   sq_quantize_act_smoothed    sq_quantize_act of X diag(smooth_inv): every activation is multiplied by smooth_inv[k]
+ *                               (dev fp32 [K], one fp32 multiplication: the form in which the factor is folded into the
+ *                               operator in front of the layer) before Q_dual; layer->s_pos / s_neg are steps of X'
+ * sq_seglinear is unchanged: it sees the codes and steps of the smoothed operands.
+ */
+sq_status sq_calibrate_channel_amax(const sq_layer* layer, const void* x, sq_dtype x_dt, float* amax_k, int accumulate,
+                                    void* stream);
+sq_status sq_weight_channel_amax(const sq_layer* layer, const void* w, sq_dtype w_dt, float* amax_k, void* stream);
+sq_status sq_smooth_factors(const sq_layer* layer, const float* amax_x, const float* amax_w, const float* alpha,
+                            float* smooth, float* smooth_inv);
+sq_status sq_quantize_weight_smoothed(const sq_layer* layer, const void* w, sq_dtype w_dt, const float* smooth, int8_t* wq,
+                                      float* wscale, void* stream);
+sq_status sq_quantize_act_smoothed(const sq_layer* layer, const void* x, sq_dtype x_dt, const float* smooth_inv, int8_t* xq,
+                                   void* stream);
+
+/*
  * Q_dual(X) with the polarity split fused in (Sec. 4.3.2).  For a dual K-segment:
  *   x <  0 : X^_- = max(round(x / s_neg[ks]), -127), X^_+ = 0     -> xq = X^_-  (<= 0)
  *   x >= 0 : X^_+ = min(round(x / s_pos[ks]),  127), X^_- = 0     -> xq = X^_+  (>= 0)

@@ -28,7 +28,9 @@ EXPORTS = ("sq_quantize_weight", "sq_quantize_act", "sq_seglinear", "sq_seglinea
            "sq_seglinear_w4_debug_acc", "sq_quantize_act_dynamic", "sq_seglinear_dynamic",
            "sq_seglinear_fused", "sq_seglinear_grouped_fused", "sq_quantize_act_geglu",
            "sq_seglinear_fused_dynamic", "sq_unpack_w4", "sq_quantize_act_dynamic_bits", "sq_seglinear_grouped_w4",
-           "sq_calibrate_act_percentile_static", "sq_calibrate_static_scratch_bytes")
+           "sq_calibrate_act_percentile_static", "sq_calibrate_static_scratch_bytes",
+           "sq_calibrate_channel_amax", "sq_weight_channel_amax", "sq_smooth_factors", "sq_quantize_weight_smoothed",
+           "sq_quantize_act_smoothed")
 
 
 class SqError(RuntimeError):
@@ -97,6 +99,14 @@ def load_library() -> C.CDLL:
     lib.sq_calibrate_act_percentile_static.restype = i32
     lib.sq_calibrate_static_scratch_bytes.argtypes = []
     lib.sq_calibrate_static_scratch_bytes.restype = C.c_size_t
+    lib.sq_calibrate_channel_amax.argtypes = [lp, vp, i32, vp, i32, vp]
+    lib.sq_weight_channel_amax.argtypes = [lp, vp, i32, vp, vp]
+    lib.sq_smooth_factors.argtypes = [lp, vp, vp, vp, vp, vp]
+    lib.sq_quantize_weight_smoothed.argtypes = [lp, vp, i32, vp, vp, vp, vp]
+    lib.sq_quantize_act_smoothed.argtypes = [lp, vp, i32, vp, vp, vp]
+    for f in (lib.sq_calibrate_channel_amax, lib.sq_weight_channel_amax, lib.sq_smooth_factors,
+              lib.sq_quantize_weight_smoothed, lib.sq_quantize_act_smoothed):
+        f.restype = i32
     lib.sq_calibrate_workspace_bytes.argtypes = []
     lib.sq_calibrate_workspace_bytes.restype = C.c_size_t
     lib.sq_seglinear_grouped.argtypes = [lp, vp, i32, C.POINTER(sq_group_item), i32, vp]
@@ -235,6 +245,42 @@ def sq_calibrate_act_percentile_static(layer: Layer, x, p: float, amax, steps, a
     _check(load_library().sq_calibrate_act_percentile_static(C.byref(layer.c), _dptr(x), _dt(x), float(p), _dptr(amax),
                                                              _dptr(steps), 1 if accumulate else 0, _stream(stream)),
            "sq_calibrate_act_percentile_static")
+
+
+def sq_calibrate_channel_amax(layer: Layer, x, amax_k, accumulate: bool = False, stream=None) -> None:
+    """Per-input-channel maxima of |x| over one batch into amax_k (device fp32 [K]), running over batches if asked."""
+    _check(load_library().sq_calibrate_channel_amax(C.byref(layer.c), _dptr(x), _dt(x), _dptr(amax_k),
+                                                    1 if accumulate else 0, _stream(stream)), "sq_calibrate_channel_amax")
+
+
+def sq_weight_channel_amax(layer: Layer, w, amax_k, stream=None) -> None:
+    """Per-input-channel maxima of |w| over the output channels into amax_k (device fp32 [K])."""
+    _check(load_library().sq_weight_channel_amax(C.byref(layer.c), _dptr(w), _dt(w), _dptr(amax_k), _stream(stream)),
+           "sq_weight_channel_amax")
+
+
+def sq_smooth_factors(layer: Layer, amax_x: np.ndarray, amax_w: np.ndarray, alpha) -> tuple:
+    """Host computation: (smooth, smooth_inv) fp32 [K] from host arrays of channel maxima and one alpha per K-segment."""
+    ax = np.ascontiguousarray(amax_x, dtype=np.float32)
+    aw = np.ascontiguousarray(amax_w, dtype=np.float32)
+    al = np.ascontiguousarray(alpha, dtype=np.float32)
+    assert ax.shape == (layer.K,) and aw.shape == (layer.K,) and al.shape == (layer.S,)
+    s, r = np.empty(layer.K, np.float32), np.empty(layer.K, np.float32)
+    _check(load_library().sq_smooth_factors(C.byref(layer.c), ax.ctypes.data, aw.ctypes.data, al.ctypes.data, s.ctypes.data,
+                                            r.ctypes.data), "sq_smooth_factors")
+    return s, r
+
+
+def sq_quantize_weight_smoothed(layer: Layer, w, smooth, wq, wscale, stream=None) -> None:
+    """sq_quantize_weight of W diag(smooth); smooth: device fp32 [K]."""
+    _check(load_library().sq_quantize_weight_smoothed(C.byref(layer.c), _dptr(w), _dt(w), _dptr(smooth), _dptr(wq),
+                                                      _dptr(wscale), _stream(stream)), "sq_quantize_weight_smoothed")
+
+
+def sq_quantize_act_smoothed(layer: Layer, x, smooth_inv, xq, stream=None) -> None:
+    """sq_quantize_act of X diag(smooth_inv); smooth_inv: device fp32 [K]; the layer's steps are those of the smoothed X."""
+    _check(load_library().sq_quantize_act_smoothed(C.byref(layer.c), _dptr(x), _dt(x), _dptr(smooth_inv), _dptr(xq),
+                                                   _stream(stream)), "sq_quantize_act_smoothed")
 
 
 def sq_quantize_act(layer: Layer, x, xq, stream=None) -> None:

@@ -328,6 +328,82 @@ sq_status sq_quantize_act(const sq_layer* layer, const void* x, sq_dtype x_dt, i
   return quantize_act_common(layer, x, x_dt, nullptr, xq, nullptr, 0, stream);
 }
 
+sq_status sq_calibrate_channel_amax(const sq_layer* layer, const void* x, sq_dtype x_dt, float* amax_k, int accumulate,
+                                    void* stream) {
+  sq_status st = check_layer(layer, true, false);
+  if (st != SQ_OK) return st;
+  if (x == nullptr || amax_k == nullptr) return SQ_ERR_INVALID_ARG;
+  if (x_dt != SQ_F32 && x_dt != SQ_BF16) return SQ_ERR_INVALID_ARG;
+  hipError_t e = sq::launch_channel_amax(x, x_dt == SQ_BF16, layer->M, layer->K, amax_k, accumulate != 0,
+                                         reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
+sq_status sq_weight_channel_amax(const sq_layer* layer, const void* w, sq_dtype w_dt, float* amax_k, void* stream) {
+  sq_status st = check_layer(layer, false, false);
+  if (st != SQ_OK) return st;
+  if (w == nullptr || amax_k == nullptr) return SQ_ERR_INVALID_ARG;
+  if (w_dt != SQ_F32 && w_dt != SQ_BF16) return SQ_ERR_INVALID_ARG;
+  hipError_t e = sq::launch_channel_amax(w, w_dt == SQ_BF16, layer->N, layer->K, amax_k, false,
+                                         reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
+sq_status sq_smooth_factors(const sq_layer* layer, const float* amax_x, const float* amax_w, const float* alpha,
+                            float* smooth, float* smooth_inv) {
+  sq_status st = check_layer(layer, false, false);
+  if (st != SQ_OK) return st;
+  if (amax_x == nullptr || amax_w == nullptr || alpha == nullptr || smooth == nullptr || smooth_inv == nullptr)
+    return SQ_ERR_INVALID_ARG;
+  for (int s = 0; s < layer->S; ++s)
+    if (!(alpha[s] >= 0.0f && alpha[s] <= 1.0f)) return SQ_ERR_INVALID_ARG;
+  for (int k = 0; k < layer->K; ++k)
+    if (!(amax_x[k] >= 0.0f) || !(amax_w[k] >= 0.0f) || !std::isfinite(amax_x[k]) || !std::isfinite(amax_w[k]))
+      return SQ_ERR_INVALID_ARG;
+  sq::KsegTable tb;
+  tb.S = layer->S;
+  for (int s = 0; s <= layer->S; ++s) tb.off[s] = layer->kseg_off[s];
+  sq::smooth_factors_host(amax_x, amax_w, layer->K, tb, alpha, smooth, smooth_inv);
+  return SQ_OK;
+}
+
+sq_status sq_quantize_weight_smoothed(const sq_layer* layer, const void* w, sq_dtype w_dt, const float* smooth, int8_t* wq,
+                                      float* wscale, void* stream) {
+  sq_status st = check_layer(layer, false, false);
+  if (st != SQ_OK) return st;
+  if (w == nullptr || smooth == nullptr || wq == nullptr || wscale == nullptr) return SQ_ERR_INVALID_ARG;
+  if (w_dt != SQ_F32 && w_dt != SQ_BF16) return SQ_ERR_INVALID_ARG;
+  sq::KsegTable tb;
+  tb.S = layer->S;
+  for (int s = 0; s <= layer->S; ++s) tb.off[s] = layer->kseg_off[s];
+  hipError_t e = sq::launch_quantize_weight_smoothed(w, w_dt == SQ_BF16, smooth, wq, wscale, layer->N, layer->K, tb,
+                                                     reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
+sq_status sq_quantize_act_smoothed(const sq_layer* layer, const void* x, sq_dtype x_dt, const float* smooth_inv, int8_t* xq,
+                                   void* stream) {
+  sq_status st = check_layer(layer, true, true);
+  if (st != SQ_OK) return st;
+  if (x == nullptr || smooth_inv == nullptr || xq == nullptr) return SQ_ERR_INVALID_ARG;
+  if (x_dt != SQ_F32 && x_dt != SQ_BF16) return SQ_ERR_INVALID_ARG;
+  sq::ActTable tb;
+  std::memset(&tb, 0, sizeof(tb));
+  tb.S = layer->S;
+  for (int s = 0; s <= layer->S; ++s) tb.kseg_off[s] = layer->kseg_off[s];
+  for (int s = 0; s < layer->S; ++s) {
+    tb.dual[s] = layer->dual[s] ? 1 : 0;
+    tb.s_pos[s] = layer->s_pos[s];
+    tb.inv_pos[s] = safe_inv(layer->s_pos[s]);
+    tb.s_neg[s] = layer->dual[s] ? layer->s_neg[s] : 1.0f;
+    tb.inv_neg[s] = layer->dual[s] ? safe_inv(layer->s_neg[s]) : 1.0f;
+    tb.act[s] = SQ_ACT_NONE;
+  }
+  hipError_t e = sq::launch_quantize_act_smoothed(x, x_dt == SQ_BF16, smooth_inv, xq, layer->M, layer->K, tb,
+                                                  reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
 size_t sq_quantize_act_fused_workspace_bytes(const sq_layer* layer) {
   if (layer == nullptr || layer->S < 1 || layer->S > SQ_MAX_SEGMENTS) return 0;
   return sq::quantize_act_fused_workspace_bytes(layer->S);

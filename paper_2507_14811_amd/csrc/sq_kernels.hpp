@@ -53,6 +53,16 @@ size_t calibrate_static_scratch_bytes();
 hipError_t launch_calibrate_act_percentile_static(const void* x, bool x_is_bf16, int M, int K, const ActTable& tb, double p,
                                                   float* amax, float* steps, bool accumulate, hipStream_t st);
 
+// smooth.hip : SmoothQuant factors with one migration strength per K-segment (per-channel maxima, factors on the host,
+// quantizers on the smoothed operands)
+hipError_t launch_channel_amax(const void* a, bool is_bf16, int R, int K, float* amax, bool accumulate, hipStream_t st);
+void smooth_factors_host(const float* amax_x, const float* amax_w, int K, const KsegTable& tb, const float* alpha,
+                         float* smooth, float* smooth_inv);
+hipError_t launch_quantize_weight_smoothed(const void* w, bool w_is_bf16, const float* smooth, int8_t* wq, float* wscale, int N,
+                                           int K, const KsegTable& tb, hipStream_t st);
+hipError_t launch_quantize_act_smoothed(const void* x, bool x_is_bf16, const float* rinv, int8_t* xq, int M, int K,
+                                        const ActTable& tb, hipStream_t st);
+
 // seglinear_generic.hip : any shape / alignment, one thread per output element
 hipError_t launch_seglinear_generic(const GemmArgs& a, const GemmTable& tb, OutMode mode, hipStream_t st);
 

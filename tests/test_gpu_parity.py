@@ -535,6 +535,90 @@ def test_quantize_weight_block(oracle, case):
     assert np.array_equal(gl.wq.cpu().numpy(), rq)
 
 
+SMOOTH = [
+    dict(M=300, K=1536, N=200, kseg=[0, 1536], dual=[0], alpha=[0.5], x_dtype="bf16", w_dtype="f32", outliers=15),      # fused QKV with outlier channels
+    dict(M=130, K=640, N=70, kseg=[0, 128, 640], dual=[0, 1], alpha=[0.3, 0.8], x_dtype="bf16", w_dtype="bf16", outliers=4),
+    dict(M=64, K=256, N=33, kseg=[0, 64, 128, 256], dual=[1, 1, 0], alpha=[0.0, 1.0, 0.5], x_dtype="f32", w_dtype="f32", outliers=2),
+    dict(M=13, K=100, N=9, kseg=[0, 37, 100], dual=[1, 0], alpha=[0.6, 0.4], x_dtype="f32", w_dtype="bf16", outliers=1),  # unaligned: one element per thread
+    dict(M=1, K=16, N=1, kseg=[0, 16], dual=[1], alpha=[0.5], x_dtype="bf16", w_dtype="f32", outliers=0),
+]
+
+
+@pytest.mark.parametrize("case", SMOOTH)
+def test_smoothed_layer(oracle, case):
+    """SmoothQuant factors with one alpha per K-segment in front of the quantizers: per-channel maxima over two
+    calibration batches, factors, smoothed weight codes and steps, smoothed activation codes: all bit-exact against the
+    oracle; the layer's accumulators bit-exact and its output within the fp32 tolerance, every element."""
+    import torch
+
+    g = _gpu()
+    M, K, N, kseg, dual = case["M"], case["K"], case["N"], case["kseg"], case["dual"]
+    w = wl.random_layer(M, K, N, kseg, [0, N], dual, seed=M + K, x_dtype=case["x_dtype"], act="gelu", with_bias=True)
+    rng = np.random.default_rng(K)
+    if case["outliers"]:
+        w.x[:, rng.permutation(K)[:case["outliers"]]] *= 20.0
+        if case["x_dtype"] == "bf16":
+            w.x = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(w.x))
+    if case["w_dtype"] == "bf16":
+        w.w = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(w.w))
+    w.w[:, 0] = 0.0                                            # a dead weight channel keeps the neutral factor
+    gl = g.GpuLayer(w, w_dtype=case["w_dtype"])
+    # calibration: two batches of activations (the second is the first, scaled), the weight
+    x2 = (w.x * np.float32(0.5)).astype(np.float32)
+    x2[:, 1] *= 7.0
+    if case["x_dtype"] == "bf16":
+        x2 = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(x2))
+        x2d = torch.from_numpy(wl.f32_to_bf16_bits(x2).view(np.int16)).view(torch.bfloat16).to(g.DEV)
+    else:
+        x2d = torch.from_numpy(x2).to(g.DEV)
+    ax = torch.full((K,), float("nan"), dtype=torch.float32, device=g.DEV)
+    aw = torch.full((K,), float("nan"), dtype=torch.float32, device=g.DEV)
+    sq.sq_calibrate_channel_amax(gl.layer, gl.x, ax)
+    sq.sq_calibrate_channel_amax(gl.layer, x2d, ax, accumulate=True)
+    sq.sq_weight_channel_amax(gl.layer, gl.wt, aw)
+    torch.cuda.synchronize()
+    r_ax = oracle.channel_amax(x2, running=oracle.channel_amax(w.x))
+    r_aw = oracle.channel_amax(w.w)
+    assert np.array_equal(ax.cpu().numpy().view(np.uint32), r_ax.view(np.uint32))
+    assert np.array_equal(aw.cpu().numpy().view(np.uint32), r_aw.view(np.uint32))
+    smooth, inv = sq.sq_smooth_factors(gl.layer, ax.cpu().numpy(), aw.cpu().numpy(), case["alpha"])
+    r_s, r_inv = oracle.smooth_factors(r_ax, r_aw, kseg, case["alpha"])
+    assert np.array_equal(smooth.view(np.uint32), r_s.view(np.uint32)) and np.array_equal(inv.view(np.uint32), r_inv.view(np.uint32))
+    assert smooth[0] == 1.0
+    # weights
+    sq.sq_quantize_weight_smoothed(gl.layer, gl.wt, torch.from_numpy(smooth).to(g.DEV), gl.wq, gl.wscale)
+    torch.cuda.synchronize()
+    r_wq, r_ws = oracle.quantize_weight_smoothed(w.w, kseg, r_s)
+    assert np.array_equal(gl.wq.cpu().numpy(), r_wq)
+    assert np.array_equal(gl.wscale.cpu().numpy().view(np.uint32), r_ws.view(np.uint32))
+    # activations: steps calibrated on the smoothed tensor (oracle side: no device value enters the oracle)
+    xs = oracle.smooth_act(w.x, r_inv)
+    sp, sn, _, _ = oracle.calibrate_act(xs, kseg, dual)
+    lay = sq.Layer(M, K, N, kseg, [0, N], dual, sp, sn)
+    sq.sq_quantize_act_smoothed(lay, gl.x, torch.from_numpy(inv).to(g.DEV), gl.xq)
+    torch.cuda.synchronize()
+    r_xp, r_xn = oracle.quantize_act(xs, kseg, dual, sp, sn)
+    xp, xn = g.split_codes(w, gl.xq.cpu().numpy())
+    assert np.array_equal(xp, r_xp) and np.array_equal(xn, r_xn)
+    # the layer on the smoothed operands
+    r_ap, r_an = oracle.int_gemm(r_xp, r_xn, r_wq, kseg, dual)
+    r_y, _ = oracle.dequant(r_ap, r_an, [0, N], dual, sp, sn, r_ws, None, w.bias)
+    ap = torch.empty((w.S, M, N), dtype=torch.int32, device=g.DEV)
+    an = torch.empty((w.S, M, N), dtype=torch.int32, device=g.DEV)
+    sq.sq_seglinear_debug_acc(lay, gl.xq, gl.wq, ap, an)
+    y = torch.full((M, N), float("nan"), dtype=torch.float32, device=g.DEV)
+    sq.sq_seglinear(lay, gl.xq, gl.wq, gl.wscale, gl.bias, y)
+    torch.cuda.synchronize()
+    assert np.array_equal(ap.cpu().numpy(), r_ap) and np.array_equal(an.cpu().numpy(), r_an)
+    ymax = float(np.abs(r_y).max())
+    assert float(np.abs(y.cpu().numpy().astype(np.float64) - r_y).max()) <= RTOL * ymax
+    # and it serves its purpose: closer to the unquantized layer than the plain quantizers on the outlier case
+    if case["outliers"] >= 15:
+        ref = w.x.astype(np.float64) @ w.w.astype(np.float64).T + w.bias
+        plain = oracle.seglinear(w.x, w.w, kseg, [0, N], dual, w.s_pos, w.s_neg, None, w.bias)
+        assert np.linalg.norm(r_y - ref) < np.linalg.norm(plain.y32 - ref)
+
+
 GENERIC = [
     dict(M=7, K=100, N=13, kseg=[0, 37, 100], nseg=[0, 5, 13], dual=[1, 0]),
     dict(M=70, K=96, N=65, kseg=[0, 96], nseg=[0, 65], dual=[1]),

@@ -57,6 +57,28 @@ def test_probe_library_exports_its_header(sq):
     assert lib.sqp_copy(None, None, ctypes.c_size_t(16), None) == 1
 
 
+def test_smooth_factors_on_the_host_match_the_oracle(sq, oracle):
+    """sq_smooth_factors is a host computation (it launches nothing): bit-equal to the oracle's, dead channels and the
+    ends of alpha included; alpha outside [0, 1] and negative maxima are rejected."""
+    rng = np.random.default_rng(12)
+    K, kseg = 300, [0, 100, 180, 300]
+    layer = sq.Layer(4, K, 8, kseg, [0, 8], [1, 0, 1])
+    ax = rng.uniform(0.0, 40.0, K).astype(np.float32)
+    aw = rng.uniform(0.0, 1.5, K).astype(np.float32)
+    ax[[3, 150]] = 0.0
+    aw[[7, 299]] = 0.0
+    ax[10], aw[10] = 1e30, 1e-30                     # the factor overflows fp32: the channel keeps 1
+    for alpha in ([0.5, 0.5, 0.5], [0.0, 1.0, 0.3], [0.1, 0.9, 0.7]):
+        s, r = sq.sq_smooth_factors(layer, ax, aw, alpha)
+        os_, or_ = oracle.smooth_factors(ax, aw, kseg, alpha)
+        assert np.array_equal(s.view(np.uint32), os_.view(np.uint32)) and np.array_equal(r.view(np.uint32), or_.view(np.uint32))
+        assert s[3] == 1.0 and s[7] == 1.0
+    with pytest.raises(sq.SqError):
+        sq.sq_smooth_factors(layer, ax, aw, [0.5, 1.2, 0.5])
+    with pytest.raises(sq.SqError):
+        sq.sq_smooth_factors(layer, -ax - 1, aw, [0.5, 0.5, 0.5])
+
+
 def test_status_strings_and_version(sq):
     assert sq.sq_version() >= 100
     assert [sq.status_string(i) for i in range(4)] == ["SQ_OK", "SQ_ERR_INVALID_ARG", "SQ_ERR_UNSUPPORTED", "SQ_ERR_LAUNCH"]
