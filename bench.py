@@ -27,6 +27,7 @@ sys.path.insert(0, ROOT)
 INT8_MFMA_PEAK_TOPS = 5033.2   # 256 CU x 2.4 GHz x 8192 int8 ops/clk/CU (dense)
 HBM_PEAK_GBS = 8000.0
 PREROLL_MS = 80.0              # untimed load before the warm-up steps, so that the device clocks have settled
+USE_GRAPHS = True              # --no-graph: time small kernels with plain launches (for runs under rocprofv3)
 
 # Fabric-side traffic per GEMM launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by the
 # readings of a plain 256 MiB copy kernel (profiles/bench_all_kernels_rocprofv3.txt), bytes.  None for a
@@ -79,12 +80,23 @@ def _gpu_side_ms(fns, launches=200, replays=5):
     From Python a launch through ctypes costs 6-7 us of host time, more than the small kernels take."""
     import torch
 
+    n = max(len(fns), (launches // len(fns)) * len(fns))
+    if not USE_GRAPHS:      # under a profiler: plain launches, one event pair around all of them (host cost included)
+        for f in fns:
+            f()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(n):
+            fns[i % len(fns)]()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
     st = torch.cuda.Stream()
     with torch.cuda.stream(st):
         for f in fns:
             f()
     torch.cuda.synchronize()
-    n = max(len(fns), (launches // len(fns)) * len(fns))
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g, stream=st):
         for i in range(n):
@@ -103,7 +115,7 @@ def _gpu_side_ms(fns, launches=200, replays=5):
     return float(np.median(ts))
 
 
-def measure(name, steps, warmup, rotate_quant=True):
+def measure(name, steps, warmup, rotate_quant=True, hot_only=False):
     """Times one workload.  Returns a dict of per-kernel and per-step figures."""
     import torch
 
@@ -188,47 +200,49 @@ def measure(name, steps, warmup, rotate_quant=True):
     quant()
     torch.cuda.synchronize()
 
-    # calibration-side kernels on the same tensors: min/max steps (one read of the activations) and the
-    # block-granular weight quantizer
-    amax = torch.empty((2, w.S), dtype=torch.float32, device="cuda:0")
-    stp = torch.empty((2, w.S), dtype=torch.float32, device="cuda:0")
-    sq.sq_calibrate_act(layer, s["x"], amax, stp)
-    torch.cuda.synchronize()
-    ms_calib = float(np.median(_time_events(lambda: sq.sq_calibrate_act(layer, s["x"], amax, stp), 10)))
-    # the activation fused in front of the quantizer: GELU on the dual K-segments (the headline layer's MLP half)
-    codes = [sq.SQ_ACT_GELU if d else sq.SQ_ACT_NONE for d in w.dual]
-    xq_f = torch.empty_like(s["xq"])
-    sq.sq_quantize_act_fused(layer, s["x"], codes, xq_f)
-    torch.cuda.synchronize()
-    ms_quant_fused = float(np.median(_time_events(lambda: sq.sq_quantize_act_fused(layer, s["x"], codes, xq_f), 20)))
-    fws = torch.empty((sq.sq_quantize_act_fused_workspace_bytes(layer),), dtype=torch.uint8, device="cuda:0")
-    sq.sq_quantize_act_fused(layer, s["x"], codes, xq_f, workspace=fws)
-    torch.cuda.synchronize()
-    ms_quant_fused_lut = float(np.median(_time_events(lambda: sq.sq_quantize_act_fused(layer, s["x"], codes, xq_f, workspace=fws), 20)))
-    del xq_f
-    # dynamic per-token activation steps (the 4-bit settings' activation rule) on the same layer: quantizer that also
-    # writes every row's steps, and the GEMM that reads them in its flushes (8-bit weights)
-    ms_quant_dyn = ms_gemm_dyn = None
-    if w.M > 64:
-        tok = torch.empty((2, w.M, w.S), dtype=torch.float32, device="cuda:0")
-        xq_d = torch.empty_like(s["xq"])
-        y_d = torch.empty_like(s["y"])
-        sq.sq_quantize_act_dynamic(layer, s["x"], xq_d, tok)
-        sq.sq_seglinear_dynamic(layer, xq_d, tok, s["wq"], 8, s["wscale"], None, y_d)
+    ms_calib = ms_quant_fused = ms_quant_fused_lut = ms_quant_dyn = ms_gemm_dyn = ms_calib_pct = ms_wblock = None
+    if not hot_only:
+        # calibration-side kernels on the same tensors: min/max steps (one read of the activations) and the
+        # block-granular weight quantizer
+        amax = torch.empty((2, w.S), dtype=torch.float32, device="cuda:0")
+        stp = torch.empty((2, w.S), dtype=torch.float32, device="cuda:0")
+        sq.sq_calibrate_act(layer, s["x"], amax, stp)
         torch.cuda.synchronize()
-        ms_quant_dyn = float(np.median(_time_events(lambda: sq.sq_quantize_act_dynamic(layer, s["x"], xq_d, tok), 10)))
-        ms_gemm_dyn = float(np.median(_time_events(
-            lambda: sq.sq_seglinear_dynamic(layer, xq_d, tok, s["wq"], 8, s["wscale"], None, y_d), 10)))
-        del xq_d, y_d, tok
-    pws = torch.empty((sq.sq_calibrate_workspace_bytes(),), dtype=torch.uint8, device="cuda:0")
-    sq.sq_calibrate_act_percentile(layer, s["x"], 0.9999, amax, stp, pws)
-    torch.cuda.synchronize()
-    ms_calib_pct = float(np.median(_time_events(lambda: sq.sq_calibrate_act_percentile(layer, s["x"], 0.9999, amax, stp, pws), 10)))
-    wq2, ws2 = torch.empty_like(s["wq"]), torch.empty_like(s["wscale"])
-    sq.sq_quantize_weight_block(layer, s["wt"], wq2, ws2)
-    torch.cuda.synchronize()
-    ms_wblock = float(np.median(_time_events(lambda: sq.sq_quantize_weight_block(layer, s["wt"], wq2, ws2), 5)))
-    del wq2, ws2
+        ms_calib = float(np.median(_time_events(lambda: sq.sq_calibrate_act(layer, s["x"], amax, stp), 10)))
+        # the activation fused in front of the quantizer: GELU on the dual K-segments (the headline layer's MLP half)
+        codes = [sq.SQ_ACT_GELU if d else sq.SQ_ACT_NONE for d in w.dual]
+        xq_f = torch.empty_like(s["xq"])
+        sq.sq_quantize_act_fused(layer, s["x"], codes, xq_f)
+        torch.cuda.synchronize()
+        ms_quant_fused = float(np.median(_time_events(lambda: sq.sq_quantize_act_fused(layer, s["x"], codes, xq_f), 20)))
+        fws = torch.empty((sq.sq_quantize_act_fused_workspace_bytes(layer),), dtype=torch.uint8, device="cuda:0")
+        sq.sq_quantize_act_fused(layer, s["x"], codes, xq_f, workspace=fws)
+        torch.cuda.synchronize()
+        ms_quant_fused_lut = float(np.median(_time_events(lambda: sq.sq_quantize_act_fused(layer, s["x"], codes, xq_f, workspace=fws), 20)))
+        del xq_f
+        # dynamic per-token activation steps (the 4-bit settings' activation rule) on the same layer: quantizer that also
+        # writes every row's steps, and the GEMM that reads them in its flushes (8-bit weights)
+        ms_quant_dyn = ms_gemm_dyn = None
+        if w.M > 64:
+            tok = torch.empty((2, w.M, w.S), dtype=torch.float32, device="cuda:0")
+            xq_d = torch.empty_like(s["xq"])
+            y_d = torch.empty_like(s["y"])
+            sq.sq_quantize_act_dynamic(layer, s["x"], xq_d, tok)
+            sq.sq_seglinear_dynamic(layer, xq_d, tok, s["wq"], 8, s["wscale"], None, y_d)
+            torch.cuda.synchronize()
+            ms_quant_dyn = float(np.median(_time_events(lambda: sq.sq_quantize_act_dynamic(layer, s["x"], xq_d, tok), 10)))
+            ms_gemm_dyn = float(np.median(_time_events(
+                lambda: sq.sq_seglinear_dynamic(layer, xq_d, tok, s["wq"], 8, s["wscale"], None, y_d), 10)))
+            del xq_d, y_d, tok
+        pws = torch.empty((sq.sq_calibrate_workspace_bytes(),), dtype=torch.uint8, device="cuda:0")
+        sq.sq_calibrate_act_percentile(layer, s["x"], 0.9999, amax, stp, pws)
+        torch.cuda.synchronize()
+        ms_calib_pct = float(np.median(_time_events(lambda: sq.sq_calibrate_act_percentile(layer, s["x"], 0.9999, amax, stp, pws), 10)))
+        wq2, ws2 = torch.empty_like(s["wq"]), torch.empty_like(s["wscale"])
+        sq.sq_quantize_weight_block(layer, s["wt"], wq2, ws2)
+        torch.cuda.synchronize()
+        ms_wblock = float(np.median(_time_events(lambda: sq.sq_quantize_weight_block(layer, s["wt"], wq2, ws2), 5)))
+        del wq2, ws2
 
     gbytes = w.seglinear_bytes("bf16")
 
@@ -268,7 +282,7 @@ def measure(name, steps, warmup, rotate_quant=True):
         ms_gemm_b2b=ms_gemm_b2b, gemm_tops_b2b=w.int8_ops / (ms_gemm_b2b * 1e-3) / 1e12,
         gemm_bytes=gbytes, gemm_gbs=gbytes / (ms_gemm * 1e-3) / 1e9, gemm_gbs_b2b=gbytes / (ms_gemm_b2b * 1e-3) / 1e9,
         ms_gemm_hbm=ms_gemm_hbm, ms_gemm_hbm_stream=ms_gemm_hbm_stream, ms_quant_stream=ms_quant_stream, weight_sets=nsets, ms_quant_fused=ms_quant_fused, ms_quant_fused_lut=ms_quant_fused_lut, ms_quant_dyn=ms_quant_dyn, ms_gemm_dyn=ms_gemm_dyn, ms_calibrate=ms_calib, ms_calibrate_percentile=ms_calib_pct, ms_quantize_weight_block=ms_wblock,
-        calib_gbs=(w.M * w.K * (2 if w.x_dtype == "bf16" else 4)) / (ms_calib * 1e-3) / 1e9,
+        calib_gbs=None if ms_calib is None else (w.M * w.K * (2 if w.x_dtype == "bf16" else 4)) / (ms_calib * 1e-3) / 1e9,
         gemm_gbs_hbm=(gbytes / (ms_gemm_hbm * 1e-3) / 1e9) if ms_gemm_hbm else None,
         quant_bytes=qbytes, quant_gbs=qbytes / (ms_quant * 1e-3) / 1e9, quant_rotation=nrot,
     )
@@ -602,7 +616,13 @@ def main():
     ap.add_argument("--others", default="cfg2,cfg3,cfg3x28,cfg4,cfg4d", help="extra workloads summarised in the same line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--variant", type=int, default=-1, help="force an MFMA tile variant (diagnostics)")
+    ap.add_argument("--no-graph", action="store_true", help="no HIP graphs: small kernels are timed with plain launches "
+                    "(host launch cost included); for runs under rocprofv3")
+    ap.add_argument("--only", default="", help="time this one workload (hot path only) and print a short JSON line: "
+                    "one workload per profiler pass")
     args = ap.parse_args()
+    global USE_GRAPHS
+    USE_GRAPHS = not args.no_graph
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
               "(token rows are independent: a second GPU would take its own share of M, with no exchange)", file=sys.stderr)
@@ -623,6 +643,12 @@ def main():
     # the reading of FETCH_SIZE / WRITE_SIZE for a known traffic, which scales the kernels' readings.
     from paper_2507_14811_amd import probes
 
+    if args.only:
+        r = measure(args.only, args.steps, args.warmup, hot_only=True)
+        print(json.dumps({"workload": r["name"], "ms_quantize_act": round(r["ms_quant"], 5), "ms_seglinear": round(r["ms_gemm_b2b"], 5),
+                          "ms_seglinear_from_hbm": None if r["ms_gemm_hbm"] is None else round(r["ms_gemm_hbm"], 5)}))
+        return
+
     cal_src = torch.zeros(256 << 20, dtype=torch.int8, device="cuda:0")
     cal_dst = torch.empty_like(cal_src)
     probes.sqp_copy(cal_src, cal_dst)      # probe_copy_kernel: 256 MiB fetched, 256 MiB written
@@ -639,7 +665,7 @@ def main():
     others = {}
     for name in [n for n in args.others.split(",") if n and n != args.config]:
         sq.sq_tuning_set("gemm_variant", -1)
-        r = measure(name, max(10, args.steps // 2), max(3, args.warmup // 2))
+        r = measure(name, max(10, args.steps // 2), max(3, args.warmup // 2), hot_only=True)
         skinny = r["M"] <= 64
         others[name] = {
             "M": r["M"], "K": r["K"], "N": r["N"], "ms_gemm_in_step": round(r["ms_gemm"], 5),
