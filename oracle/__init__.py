@@ -34,4 +34,5 @@ from .segquant_oracle import (  # noqa: F401
     smooth_factors,
     quantize_weight_smoothed,
     smooth_act,
+    lowrank,
 )

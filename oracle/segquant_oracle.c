@@ -631,3 +631,30 @@ int sqo_smooth_act(const float* x, int M, int K, const float* smooth_inv, float*
     for (int k = 0; k < K; ++k) xs[(int64_t)m * K + k] = x[(int64_t)m * K + k] * smooth_inv[k];
   return 0;
 }
+
+/*
+ * Low-rank side branch of the 4-bit settings (main results, W4A8 rows; App. B: SVDQuant is the optimizer of the 4-bit
+ * settings, "the low-rank setting is fixed at 64").  The published decomposition W = Lu Ld + R keeps a rank-r part in
+ * 16 bit next to the quantized residual R; on the forward path
+ *   y[m][n] = y_q[m][n] + sum_j ( sum_k X[m][k] Ld[j][k] ) Lu[n][j],      Ld [r][K], Lu [N][r],
+ * where y_q is the quantized layer on R (sq-oracle functions above) and X are the unquantized 16-bit activations.
+ * Evaluated here in double, in that order (down projection, then up projection); y_q may be NULL (= 0).
+ */
+int sqo_lowrank(const float* x, const float* ld, const float* lu, const float* y_q, int M, int K, int N, int r,
+                double* t_out, double* y_out) {
+  if (M < 1 || K < 1 || N < 1 || r < 1) return 1;
+#pragma omp parallel for schedule(static)
+  for (int m = 0; m < M; ++m) {
+    for (int j = 0; j < r; ++j) {
+      double acc = 0.0;
+      for (int k = 0; k < K; ++k) acc += (double)x[(int64_t)m * K + k] * (double)ld[(int64_t)j * K + k];
+      t_out[(int64_t)m * r + j] = acc;
+    }
+    for (int n = 0; n < N; ++n) {
+      double acc = 0.0;
+      for (int j = 0; j < r; ++j) acc += t_out[(int64_t)m * r + j] * (double)lu[(int64_t)n * r + j];
+      y_out[(int64_t)m * N + n] = acc + (y_q ? (double)y_q[(int64_t)m * N + n] : 0.0);
+    }
+  }
+  return 0;
+}

@@ -384,3 +384,17 @@ def smooth_act(x: np.ndarray, smooth_inv) -> np.ndarray:
     out = np.empty((M, K), np.float32)
     _check(_load().sqo_smooth_act(_p(x), C.c_int(M), C.c_int(K), _p(r), _p(out)), "smooth_act")
     return out
+
+
+def lowrank(x, ld, lu, y_q=None):
+    """Low-rank side branch of the 4-bit settings: y = y_q + (X Ld^T) Lu^T, Ld [r][K], Lu [N][r], in double.
+    -> (t fp64 [M][r], y fp64 [M][N])"""
+    x, ld, lu = _f32(x), _f32(ld), _f32(lu)
+    M, K = x.shape
+    r, N = ld.shape[0], lu.shape[0]
+    assert ld.shape == (r, K) and lu.shape == (N, r)
+    yq = None if y_q is None else _f32(y_q)
+    t, y = np.empty((M, r), np.float64), np.empty((M, N), np.float64)
+    _check(_load().sqo_lowrank(_p(x), _p(ld), _p(lu), _p(yq), C.c_int(M), C.c_int(K), C.c_int(N), C.c_int(r), _p(t), _p(y)),
+           "lowrank")
+    return t, y

@@ -873,3 +873,56 @@ def test_smoothing_lowers_the_error_on_outlier_channels(oracle):
     s, r = oracle.smooth_factors(oracle.channel_amax(x), oracle.channel_amax(w), kseg, [0.5])
     smoothed = err(oracle.smooth_act(x, r), *oracle.quantize_weight_smoothed(w, kseg, s))
     assert smoothed < 0.6 * plain, (smoothed, plain)
+
+
+# ----------------------------------------------------------------------------------------------------
+# low-rank side branch of the 4-bit settings (App. B: SVDQuant, rank 64)
+# ----------------------------------------------------------------------------------------------------
+def test_lowrank_branch_handworked_and_orientation(oracle):
+    """y = y_q + (X Ld^T) Lu^T: integers by hand, a rank-1 outer product in closed form, and the orientation of the
+    two factors (Ld [r][K] multiplies the input features, Lu [N][r] makes the output features)."""
+    x = np.array([[1, 2, 3], [0, -1, 4]], np.float32)                       # M = 2, K = 3
+    ld = np.array([[1, 0, 2], [0, 1, -1]], np.float32)                      # r = 2
+    lu = np.array([[1, 1], [2, 0], [0, -3], [1, -1]], np.float32)           # N = 4
+    t, y = oracle.lowrank(x, ld, lu)
+    assert t.tolist() == [[7.0, -1.0], [8.0, -5.0]]
+    assert y.tolist() == [[6.0, 14.0, 3.0, 8.0], [3.0, 16.0, 15.0, 13.0]]
+    yq = np.arange(8, dtype=np.float32).reshape(2, 4)
+    _, y2 = oracle.lowrank(x, ld, lu, yq)
+    assert np.array_equal(y2, y + yq)
+    rng = np.random.default_rng(0)
+    u, v, xx = rng.standard_normal(7), rng.standard_normal(5), rng.standard_normal((3, 5))
+    u, v, xx = u.astype(np.float32), v.astype(np.float32), xx.astype(np.float32)
+    _, y = oracle.lowrank(xx, v[None, :], u[:, None])                       # W = u v^T
+    want = (xx.astype(np.float64) @ v.astype(np.float64))[:, None] * u.astype(np.float64)[None, :]
+    assert np.abs(y - want).max() <= 1e-14 * np.abs(want).max()
+
+
+def test_lowrank_branch_reproduces_a_low_rank_weight(oracle):
+    """A weight of rank <= r is reproduced by its factors: X W^T == (X Ld^T) Lu^T to double precision (numpy's SVD as
+    the independent factorisation), and the branch plus the quantized residual is closer to the unquantized layer than
+    the 4-bit quantizer alone when the weight has a strong low-rank part (the purpose of the optimizer)."""
+    rng = np.random.default_rng(1)
+    M, K, N, r = 24, 256, 40, 8
+    a, b = rng.standard_normal((N, r)), rng.standard_normal((r, K))
+    x = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(rng.standard_normal((M, K)).astype(np.float32)))
+    w_low = (a @ b).astype(np.float32)
+    uu, ss, vt = np.linalg.svd(w_low.astype(np.float64), full_matrices=False)
+    lu = (uu[:, :r] * ss[:r]).astype(np.float32)
+    ld = vt[:r].astype(np.float32)
+    _, y = oracle.lowrank(x, ld, lu)
+    ref = x.astype(np.float64) @ w_low.astype(np.float64).T
+    assert np.abs(y - ref).max() <= 1e-5 * np.abs(ref).max()             # fp32 factors of an fp32 matrix
+    # weight = strong low-rank part + small dense part, 4-bit residual
+    w = (w_low * 0.05 + 0.02 * rng.standard_normal((N, K))).astype(np.float32)
+    uu, ss, vt = np.linalg.svd(w.astype(np.float64), full_matrices=False)
+    lu = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits((uu[:, :r] * ss[:r]).astype(np.float32)))
+    ld = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(vt[:r].astype(np.float32)))
+    resid = (w.astype(np.float64) - lu.astype(np.float64) @ ld.astype(np.float64)).astype(np.float32)
+    kseg, nseg, dual = [0, K], [0, N], [0]
+    sp = np.array([np.abs(x).max() / 127], np.float32)
+    ref = x.astype(np.float64) @ w.astype(np.float64).T
+    plain = oracle.seglinear(x, w, kseg, nseg, dual, sp, sp, wbits=4)
+    res = oracle.seglinear(x, resid, kseg, nseg, dual, sp, sp, wbits=4)
+    _, y = oracle.lowrank(x, ld, lu, res.y32)
+    assert np.linalg.norm(y - ref) < 0.5 * np.linalg.norm(plain.y32 - ref)
