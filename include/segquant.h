@@ -386,6 +386,24 @@ sq_status sq_seglinear_dynamic(const sq_layer* layer, const int8_t* xq, const fl
                                int32_t w_bits, const float* wscale, const float* bias, void* y, sq_dtype y_dt,
                                void* stream);
 
+/*
+ * Low-rank side branch of the 4-bit settings (main results, W4A8 rows; App. B: SVDQuant is the optimizer of the 4-bit
+ * settings, the rank is fixed at 64).  The published decomposition keeps W = Lu Ld + R: the residual R is quantized
+ * (sq_quantize_weight_w4) and runs through sq_seglinear_w4 / sq_seglinear_dynamic, the rank-r part runs in 16 bit on the
+ * unquantized activations and is added to the quantized product before the output is rounded:
+ *   y[m][n] = y_q[m][n] + sum_j T[m][j] Lu[n][j],     T[m][j] = sum_k X[m][k] Ld[j][k].
+ * Arithmetic: X, Ld, Lu are bf16 (fp32 X is rounded to bf16 on entry: the branch is a 16-bit one); T is accumulated
+ * and kept in fp32 (bf16 matrix cores, K cut into slices whose partial sums are added in ascending order); the second
+ * product and the addition are fp32 FMAs over j ascending; one rounding to y_dt.  Deterministic.
+ *   x     dev [M][K] of x_dt                      ld  dev bf16 [rank][K]            lu  dev bf16 [N][rank]
+ *   y_q   dev fp32 [M][N] (the quantized layer's fp32 output) or NULL (= 0)          y   dev [M][N] of y_dt (may be y_q)
+ *   rank  32 or 64;  K a multiple of 16 (SQ_ERR_UNSUPPORTED otherwise);  x, ld, lu, workspace 16-byte aligned
+ *   workspace  dev, sq_lowrank_workspace_bytes(layer, rank) bytes, contents irrelevant, used only during the call
+ */
+size_t sq_lowrank_workspace_bytes(const sq_layer* layer, int32_t rank);
+sq_status sq_lowrank_add(const sq_layer* layer, const void* x, sq_dtype x_dt, const void* ld, const void* lu, int32_t rank,
+                         const float* y_q, void* y, sq_dtype y_dt, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Human-readable name of a status code (static storage). */
 const char* sq_status_string(sq_status s);
 

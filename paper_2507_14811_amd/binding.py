@@ -30,7 +30,7 @@ EXPORTS = ("sq_quantize_weight", "sq_quantize_act", "sq_seglinear", "sq_seglinea
            "sq_seglinear_fused_dynamic", "sq_unpack_w4", "sq_quantize_act_dynamic_bits", "sq_seglinear_grouped_w4",
            "sq_calibrate_act_percentile_static", "sq_calibrate_static_scratch_bytes",
            "sq_calibrate_channel_amax", "sq_weight_channel_amax", "sq_smooth_factors", "sq_quantize_weight_smoothed",
-           "sq_quantize_act_smoothed")
+           "sq_quantize_act_smoothed", "sq_lowrank_add", "sq_lowrank_workspace_bytes")
 
 
 class SqError(RuntimeError):
@@ -107,6 +107,10 @@ def load_library() -> C.CDLL:
     for f in (lib.sq_calibrate_channel_amax, lib.sq_weight_channel_amax, lib.sq_smooth_factors,
               lib.sq_quantize_weight_smoothed, lib.sq_quantize_act_smoothed):
         f.restype = i32
+    lib.sq_lowrank_add.argtypes = [lp, vp, i32, vp, vp, i32, vp, vp, i32, vp, C.c_size_t, vp]
+    lib.sq_lowrank_add.restype = i32
+    lib.sq_lowrank_workspace_bytes.argtypes = [lp, i32]
+    lib.sq_lowrank_workspace_bytes.restype = C.c_size_t
     lib.sq_calibrate_workspace_bytes.argtypes = []
     lib.sq_calibrate_workspace_bytes.restype = C.c_size_t
     lib.sq_seglinear_grouped.argtypes = [lp, vp, i32, C.POINTER(sq_group_item), i32, vp]
@@ -281,6 +285,19 @@ def sq_quantize_act_smoothed(layer: Layer, x, smooth_inv, xq, stream=None) -> No
     """sq_quantize_act of X diag(smooth_inv); smooth_inv: device fp32 [K]; the layer's steps are those of the smoothed X."""
     _check(load_library().sq_quantize_act_smoothed(C.byref(layer.c), _dptr(x), _dt(x), _dptr(smooth_inv), _dptr(xq),
                                                    _stream(stream)), "sq_quantize_act_smoothed")
+
+
+def sq_lowrank_workspace_bytes(layer: Layer, rank: int) -> int:
+    """Device bytes sq_lowrank_add needs as workspace for this layer and rank."""
+    return int(load_library().sq_lowrank_workspace_bytes(C.byref(layer.c), int(rank)))
+
+
+def sq_lowrank_add(layer: Layer, x, ld, lu, y_q, y, workspace, stream=None) -> None:
+    """y = y_q + (x ld^T) lu^T: the 16-bit low-rank side branch (ld bf16 [rank][K], lu bf16 [N][rank], y_q fp32 or None)."""
+    rank = int(ld.shape[0])
+    _check(load_library().sq_lowrank_add(C.byref(layer.c), _dptr(x), _dt(x), _dptr(ld), _dptr(lu), rank, _dptr(y_q), _dptr(y),
+                                         _dt(y), _dptr(workspace), workspace.numel() * workspace.element_size(),
+                                         _stream(stream)), "sq_lowrank_add")
 
 
 def sq_quantize_act(layer: Layer, x, xq, stream=None) -> None:

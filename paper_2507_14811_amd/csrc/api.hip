@@ -404,6 +404,30 @@ sq_status sq_quantize_act_smoothed(const sq_layer* layer, const void* x, sq_dtyp
   return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 
+size_t sq_lowrank_workspace_bytes(const sq_layer* layer, int32_t rank) {
+  if (check_layer(layer, true, false) != SQ_OK || (rank != 32 && rank != 64)) return 0;
+  return sq::lowrank_workspace_bytes(layer->M, layer->K, rank, sq::device_cus());
+}
+
+sq_status sq_lowrank_add(const sq_layer* layer, const void* x, sq_dtype x_dt, const void* ld, const void* lu, int32_t rank,
+                         const float* y_q, void* y, sq_dtype y_dt, void* workspace, size_t workspace_bytes, void* stream) {
+  sq_status st = check_layer(layer, true, false);
+  if (st != SQ_OK) return st;
+  if (x == nullptr || ld == nullptr || lu == nullptr || y == nullptr || workspace == nullptr) return SQ_ERR_INVALID_ARG;
+  if ((x_dt != SQ_F32 && x_dt != SQ_BF16) || (y_dt != SQ_F32 && y_dt != SQ_BF16)) return SQ_ERR_INVALID_ARG;
+  if (rank != 32 && rank != 64) return SQ_ERR_UNSUPPORTED;
+  if (layer->K % 16 != 0) return SQ_ERR_UNSUPPORTED;
+  if ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(ld) | reinterpret_cast<uintptr_t>(lu) |
+       reinterpret_cast<uintptr_t>(workspace)) % 16 != 0)
+    return SQ_ERR_INVALID_ARG;
+  if (workspace_bytes < sq::lowrank_workspace_bytes(layer->M, layer->K, rank, sq::device_cus())) return SQ_ERR_INVALID_ARG;
+  hipError_t e = sq::launch_lowrank_add(x, x_dt == SQ_BF16, reinterpret_cast<const uint16_t*>(ld),
+                                        reinterpret_cast<const uint16_t*>(lu), rank, y_q, y, y_dt == SQ_BF16, layer->M,
+                                        layer->K, layer->N, reinterpret_cast<float*>(workspace), sq::device_cus(),
+                                        reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
 size_t sq_quantize_act_fused_workspace_bytes(const sq_layer* layer) {
   if (layer == nullptr || layer->S < 1 || layer->S > SQ_MAX_SEGMENTS) return 0;
   return sq::quantize_act_fused_workspace_bytes(layer->S);

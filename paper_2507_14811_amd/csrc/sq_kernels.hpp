@@ -63,6 +63,11 @@ hipError_t launch_quantize_weight_smoothed(const void* w, bool w_is_bf16, const 
 hipError_t launch_quantize_act_smoothed(const void* x, bool x_is_bf16, const float* rinv, int8_t* xq, int M, int K,
                                         const ActTable& tb, hipStream_t st);
 
+// lowrank.hip : 16-bit low-rank side branch of the 4-bit settings, y = y_q + (X Ld^T) Lu^T (rank 32 or 64, K % 16 == 0)
+size_t lowrank_workspace_bytes(int M, int K, int rank, int cus);
+hipError_t launch_lowrank_add(const void* x, bool x_is_bf16, const uint16_t* ld, const uint16_t* lu, int rank, const float* y_in,
+                              void* y_out, bool y_is_bf16, int M, int K, int N, float* workspace, int cus, hipStream_t st);
+
 // seglinear_generic.hip : any shape / alignment, one thread per output element
 hipError_t launch_seglinear_generic(const GemmArgs& a, const GemmTable& tb, OutMode mode, hipStream_t st);
 

@@ -619,6 +619,122 @@ def test_smoothed_layer(oracle, case):
         assert np.linalg.norm(r_y - ref) < np.linalg.norm(plain.y32 - ref)
 
 
+LOWRANK = [
+    dict(M=300, K=512, N=200, rank=64, x_dtype="bf16", yq=True),
+    dict(M=33, K=48, N=7, rank=32, x_dtype="f32", yq=False),             # shorter than one group of four steps, ragged everywhere
+    dict(M=129, K=1040, N=257, rank=64, x_dtype="f32", yq=True),         # K = 16 * 65: groups of four steps and a tail
+    dict(M=2048, K=4608, N=1152, rank=64, x_dtype="bf16", yq=True),      # several K slices, many row blocks
+    dict(M=16, K=1152, N=6912, rank=64, x_dtype="bf16", yq=False),
+]
+
+
+def _bf16_round(a):
+    return wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(np.ascontiguousarray(a, dtype=np.float32)))
+
+
+def _bf16_dev(g, a):
+    import torch
+
+    return torch.from_numpy(wl.f32_to_bf16_bits(a).view(np.int16)).view(torch.bfloat16).to(g.DEV)
+
+
+def _lowrank_bound(x, ld, lu, K):
+    """fp32 evaluation of the two products against the double-precision oracle: both sums run in fp32 (matrix cores over
+    K, FMAs over the rank), so the error of an output is bounded by the rounding unit times the sum of the magnitudes of
+    its terms, times a factor that grows like the square root of the number of terms (with a wide safety margin)."""
+    b = np.abs(x).astype(np.float64) @ np.abs(ld).astype(np.float64).T @ np.abs(lu).astype(np.float64).T
+    return (8.0 * np.sqrt(K) + 64.0) * 2.0 ** -24 * b
+
+
+@pytest.mark.parametrize("case", LOWRANK)
+def test_lowrank_add(oracle, case):
+    """y = y_q + (X Ld^T) Lu^T: the 16-bit side branch of the 4-bit settings against the double-precision oracle on every
+    element, fp32 and bf16 outputs, with and without a quantized-layer output to add to."""
+    import torch
+
+    g = _gpu()
+    M, K, N, r = case["M"], case["K"], case["N"], case["rank"]
+    rng = np.random.default_rng(M + K + r)
+    x = rng.standard_normal((M, K)).astype(np.float32)
+    x[:, :3] *= 15.0
+    ld = _bf16_round(rng.standard_normal((r, K)) / np.sqrt(K))
+    lu = _bf16_round(rng.standard_normal((N, r)) * 0.1)
+    yq = (rng.standard_normal((M, N)) * 0.3).astype(np.float32) if case["yq"] else None
+    xb = _bf16_round(x)                                   # what the 16-bit branch multiplies
+    if case["x_dtype"] == "bf16":
+        x = xb
+        xd = _bf16_dev(g, x)
+    else:
+        xd = torch.from_numpy(x).to(g.DEV)
+    layer = sq.Layer(M, K, N, [0, K], [0, N], [0])
+    ws = torch.full((sq.sq_lowrank_workspace_bytes(layer, r),), 0xFF, dtype=torch.uint8, device=g.DEV)
+    yqd = None if yq is None else torch.from_numpy(yq).to(g.DEV)
+    _, ref = oracle.lowrank(xb, ld, lu, yq)
+    bound = _lowrank_bound(xb, ld, lu, K) + (0 if yq is None else np.abs(yq) * 2.0 ** -23)
+    for ydt in ("f32", "bf16"):
+        y = torch.full((M, N), float("nan"), dtype=torch.bfloat16 if ydt == "bf16" else torch.float32, device=g.DEV)
+        sq.sq_lowrank_add(layer, xd, _bf16_dev(g, ld), _bf16_dev(g, lu), yqd, y, ws)
+        torch.cuda.synchronize()
+        got = y.float().cpu().numpy().astype(np.float64)
+        assert not np.isnan(got).any()
+        tol = bound + (np.abs(ref) * 2.0 ** -8 if ydt == "bf16" else np.abs(ref) * 2.0 ** -23)
+        assert (np.abs(got - ref) <= tol + 1e-30).all(), float((np.abs(got - ref) / (tol + 1e-30)).max())
+        if ydt == "f32":      # the typical error is far inside the bound
+            assert np.abs(got - ref).max() <= 2e-5 * np.abs(ref).max()
+    # run-to-run determinism and in-place use (y is y_q)
+    if yq is not None:
+        y1 = yqd.clone()
+        sq.sq_lowrank_add(layer, xd, _bf16_dev(g, ld), _bf16_dev(g, lu), y1, y1, ws)
+        y2 = torch.empty_like(yqd)
+        sq.sq_lowrank_add(layer, xd, _bf16_dev(g, ld), _bf16_dev(g, lu), yqd, y2, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(y1, y2)
+
+
+@pytest.mark.parametrize("M", [16, 300])
+def test_w4_layer_with_lowrank_branch(oracle, M):
+    """The 4-bit setting end to end: W = Lu Ld + R (numpy's SVD, rank 64), R through the 4-bit weight quantizer and the
+    SegLinear kernels (weight stream for a few token rows; unpacked into the tile kernel for many), the rank-64 part
+    through sq_lowrank_add: against the oracle's composition of the same steps on every element, and closer to the
+    unquantized layer than the 4-bit quantizer alone."""
+    import torch
+
+    g = _gpu()
+    K, N, r = 1152, 640, 64
+    w = wl.random_layer(M, K, N, [0, K], [0, N], [1], seed=31 + M, x_dtype="bf16", act="silu")
+    rng = np.random.default_rng(M)
+    low = (rng.standard_normal((N, 12)) @ rng.standard_normal((12, K))).astype(np.float32) * 0.02
+    wt = (w.w + low).astype(np.float32)
+    uu, ss, vt = np.linalg.svd(wt.astype(np.float64), full_matrices=False)
+    lu, ld = _bf16_round(uu[:, :r] * ss[:r]), _bf16_round(vt[:r])
+    resid = (wt.astype(np.float64) - lu.astype(np.float64) @ ld.astype(np.float64)).astype(np.float32)
+    w.w = resid
+    gl = g.GpuLayer(w)
+    wq4 = torch.empty((((N + 15) // 16) * 16 * (K // 2),), dtype=torch.uint8, device=g.DEV)
+    sq.sq_quantize_weight_w4(gl.layer, gl.wt, wq4, gl.wscale)
+    gl.quantize_act()
+    yq = torch.full((M, N), float("nan"), dtype=torch.float32, device=g.DEV)
+    if M <= 64:
+        sq.sq_seglinear_w4(gl.layer, gl.xq, wq4, gl.wscale, None, yq)
+    else:
+        sq.sq_unpack_w4(gl.layer, wq4, gl.wq)
+        sq.sq_seglinear(gl.layer, gl.xq, gl.wq, gl.wscale, None, yq)
+    ws = torch.empty((sq.sq_lowrank_workspace_bytes(gl.layer, r),), dtype=torch.uint8, device=g.DEV)
+    y = torch.full((M, N), float("nan"), dtype=torch.float32, device=g.DEV)
+    sq.sq_lowrank_add(gl.layer, gl.x, _bf16_dev(g, ld), _bf16_dev(g, lu), yq, y, ws)
+    torch.cuda.synchronize()
+    r_q = oracle.seglinear(w.x, resid, w.kseg_off, w.nseg_off, w.dual, w.s_pos, w.s_neg, wbits=4)
+    ymax = float(np.abs(r_q.y32).max())
+    assert float(np.abs(yq.cpu().numpy().astype(np.float64) - r_q.y32).max()) <= RTOL * ymax
+    _, ref = oracle.lowrank(w.x, ld, lu, r_q.y32)
+    tol = _lowrank_bound(w.x, ld, lu, K) + RTOL * ymax + np.abs(ref) * 2.0 ** -23
+    got = y.cpu().numpy().astype(np.float64)
+    assert (np.abs(got - ref) <= tol).all()
+    full = w.x.astype(np.float64) @ wt.astype(np.float64).T
+    plain = oracle.seglinear(w.x, wt, w.kseg_off, w.nseg_off, w.dual, w.s_pos, w.s_neg, wbits=4)
+    assert np.linalg.norm(got - full) < np.linalg.norm(plain.y32 - full)
+
+
 GENERIC = [
     dict(M=7, K=100, N=13, kseg=[0, 37, 100], nseg=[0, 5, 13], dual=[1, 0]),
     dict(M=70, K=96, N=65, kseg=[0, 96], nseg=[0, 65], dual=[1]),
