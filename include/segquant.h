@@ -394,7 +394,8 @@ sq_status sq_seglinear_dynamic(const sq_layer* layer, const int8_t* xq, const fl
  *   y[m][n] = y_q[m][n] + sum_j T[m][j] Lu[n][j],     T[m][j] = sum_k X[m][k] Ld[j][k].
  * Arithmetic: X, Ld, Lu are bf16 (fp32 X is rounded to bf16 on entry: the branch is a 16-bit one); T is accumulated
  * and kept in fp32 (bf16 matrix cores, K cut into slices whose partial sums are added in ascending order); the second
- * product and the addition are fp32 FMAs over j ascending; one rounding to y_dt.  Deterministic.
+ * product runs on the fp32 matrix cores (fp32 operands and accumulation), then the addition and one rounding to y_dt.
+ * Deterministic.
  *   x     dev [M][K] of x_dt                      ld  dev bf16 [rank][K]            lu  dev bf16 [N][rank]
  *   y_q   dev fp32 [M][N] (the quantized layer's fp32 output) or NULL (= 0)          y   dev [M][N] of y_dt (may be y_q)
  *   rank  32 or 64;  K a multiple of 16 (SQ_ERR_UNSUPPORTED otherwise);  x, ld, lu, workspace 16-byte aligned
