@@ -515,6 +515,47 @@ def _timed_launches(fn, reps=200):
     return b2b, single
 
 
+def measure_optimizer_side(name="cfg5"):
+    """The entry points that serve the paper's optimizers on the headline layer's shape: SmoothQuant factors with one
+    alpha per K-segment (per-channel maxima, smoothed quantizers; the factors themselves are a host computation) and the
+    rank-64 low-rank side branch of the 4-bit settings."""
+    import torch
+
+    import paper_2507_14811_amd as sq
+
+    s = _setup(name)
+    w, layer = s["w"], s["layer"]
+    dev = "cuda:0"
+    ax = torch.empty((w.K,), dtype=torch.float32, device=dev)
+    aw = torch.empty((w.K,), dtype=torch.float32, device=dev)
+    t_ax = float(np.median(_time_events(lambda: sq.sq_calibrate_channel_amax(layer, s["x"], ax), 10)))
+    t_aw = float(np.median(_time_events(lambda: sq.sq_weight_channel_amax(layer, s["wt"], aw), 10)))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    smooth, inv = sq.sq_smooth_factors(layer, ax.cpu().numpy(), aw.cpu().numpy(), [0.5] * w.S)
+    t_host = (time.perf_counter() - t0) * 1e3
+    sm, iv = torch.from_numpy(smooth).to(dev), torch.from_numpy(inv).to(dev)
+    t_qw = float(np.median(_time_events(lambda: sq.sq_quantize_weight_smoothed(layer, s["wt"], sm, s["wq"], s["wscale"]), 5)))
+    t_qa = float(np.median(_time_events(lambda: sq.sq_quantize_act_smoothed(layer, s["x"], iv, s["xq"]), 20)))
+    ld = torch.randn((64, w.K), device=dev).to(torch.bfloat16)
+    lu = torch.randn((w.N, 64), device=dev).to(torch.bfloat16)
+    yq = torch.zeros((w.M, w.N), dtype=torch.float32, device=dev)
+    ws = torch.empty((sq.sq_lowrank_workspace_bytes(layer, 64),), dtype=torch.uint8, device=dev)
+    t_lr = float(np.median(_time_events(lambda: sq.sq_lowrank_add(layer, s["x"], ld, lu, yq, s["y"], ws), 20)))
+    qbytes = w.quantize_act_bytes()
+    return {"workload": w.name,
+            "smoothing": {"ms_calibrate_channel_amax": round(t_ax, 5), "ms_weight_channel_amax": round(t_aw, 5),
+                          "ms_smooth_factors_on_the_host": round(t_host, 3), "ms_quantize_weight_smoothed": round(t_qw, 5),
+                          "ms_quantize_act_smoothed": round(t_qa, 5),
+                          "quantize_act_smoothed_gbs": round(qbytes / (t_qa * 1e-3) / 1e9, 1),
+                          "quantize_act_smoothed_frac_hbm_peak": round(qbytes / (t_qa * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+            "lowrank_rank64": {"ms_per_call": round(t_lr, 5), "launches": 3,
+                               "bytes": int(w.M * w.K * 2 + w.M * w.N * 6),
+                               "gbs": round((w.M * w.K * 2 + w.M * w.N * 6) / (t_lr * 1e-3) / 1e9, 1),
+                               "note": "down projection (bf16 matrix cores, K slices), slice sum, up projection + add (fp32 "
+                                       "matrix cores): bytes = X once, y_q read as fp32, y written as bf16"}}
+
+
 def measured_ceilings(head_setup_codes, dual_cols=None):
     """Ceilings and floors measured on this device with the probe library, reported next to the datasheet peaks:
     the sustained int8 MFMA rate of a register-only loop (all-zero operands; operands distributed like the headline
@@ -662,6 +703,7 @@ def main():
     grouped = measure_grouped() if "cfg3" in args.others.split(",") else None
     w4 = measure_w4() if "cfg3x28" in args.others.split(",") else None
     geglu = measure_geglu()
+    optimizer_side = measure_optimizer_side(args.config)
     others = {}
     for name in [n for n in args.others.split(",") if n and n != args.config]:
         sq.sq_tuning_set("gemm_variant", -1)
@@ -750,6 +792,7 @@ def main():
         "other_workloads": others,
         "grouped_skinny": grouped,
         "w4_skinny": w4,
+        "optimizer_side": optimizer_side,
         "measured_ceilings": ceilings,
     }
     if not args.no_cpu_baseline:
