@@ -33,11 +33,15 @@ USE_GRAPHS = True              # --no-graph: time small kernels with plain launc
 # readings of a plain 256 MiB copy kernel (profiles/bench_all_kernels_rocprofv3.txt), bytes.  None for a
 # workload without a committed counter run.
 MEASURED_TRAFFIC = {
-    "cfg5_outproj": int(287525.1 * 1024 * 2.0 + 51711.2 * 1024 * 1.0),       # 641.8 MB (algorithmic 146.3 MB)
-    "cfg4d_qkv_dual": int(69502.6 * 1024 * 2.0 + 76534.9 * 1024 * 1.0),
-    "cfg4_qkv": int(69365.0 * 1024 * 2.0 + 76558.4 * 1024 * 1.0),
-    "cfg2_dit_fc2": int(19735.5 * 1024 * 2.0 + 4608.0 * 1024 * 1.0),
+    "cfg5_outproj": int(294447.2 * 1024 * 2.0 + 54732.0 * 1024 * 1.0),       # 659.1 MB (algorithmic 146.3 MB)
+    "cfg4d_qkv_dual": int(69542.1 * 1024 * 2.0 + 76545.7 * 1024 * 1.0),
+    "cfg4_qkv": int(69402.0 * 1024 * 2.0 + 76588.6 * 1024 * 1.0),
+    "cfg2_dit_fc2": int(19727.0 * 1024 * 2.0 + 4608.0 * 1024 * 1.0),
 }
+# the same for the skinny weight stream and the activation quantizer (passes of their own in profiles/)
+MEASURED_TRAFFIC_SKINNY = {"cfg3": int(4071.5 * 1024 * 2.0 + 216.0 * 1024), "cfg3x28": int(109776.6 * 1024 * 2.0 + 6049.9 * 1024)}
+MEASURED_TRAFFIC_QUANT = {"cfg5": int(69204.7 * 1024 * 2.0 + 69120.0 * 1024), "cfg2": int(9252.1 * 1024 * 2.0 + 9216.0 * 1024),
+                          "cfg4": int(12786.2 * 1024 * 2.0 + 12750.0 * 1024), "cfg4d": int(12786.2 * 1024 * 2.0 + 12750.0 * 1024)}
 
 
 def _setup(name):
@@ -727,6 +731,10 @@ def main():
                 "gemm_frac_hbm_peak_from_hbm": round(r["gemm_gbs_hbm"] / HBM_PEAK_GBS, 4),
                 "gemm_gbs_cache_resident": round(r["gemm_gbs_b2b"], 1)})
 
+    for name, o in others.items():
+        o["quant_traffic"] = MEASURED_TRAFFIC_QUANT.get(name)
+        if o["gemm_bound"] == "hbm":
+            o["gemm_traffic"] = MEASURED_TRAFFIC_SKINNY.get(name)
     floors = ceilings["launch_floor_us"]
     for name, o in others.items():
         if o["gemm_bound"] == "hbm":
@@ -769,7 +777,7 @@ def main():
         },
         "quantize_act": {"bound": "hbm", "achieved": round(head["quant_gbs"], 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                          "frac": round(head["quant_gbs"] / HBM_PEAK_GBS, 4), "ms_per_launch": round(head["ms_quant"], 5),
-                         "bytes": head["quant_bytes"]},
+                         "bytes": head["quant_bytes"], "traffic": MEASURED_TRAFFIC_QUANT.get(args.config)},
         "quantize_act_fused": {"bound": "hbm", "activation": "GELU (tanh form) on the dual K-segments",
                                "path": "code tables in LDS (bf16 input, two launches: table fill + stream)",
                                "ms_per_call": round(head["ms_quant_fused_lut"], 5),
