@@ -658,3 +658,126 @@ int sqo_lowrank(const float* x, const float* ld, const float* lu, const float* y
   }
   return 0;
 }
+
+/*
+ * The 8-bit floating-point variant (main results, the 8/8 fp rows of the SDXL table): the same layer with fp8 codes in
+ * place of int8 ones.  Format: the published OCP 8-bit float E4M3 (1 sign, 4 exponent bits with bias 7, 3 mantissa
+ * bits, subnormals, no infinity, S.1111.111 = NaN, largest finite value 448).  The Sec. 3 quantizer becomes
+ *   code = e4m3( clip(v / s, -448, 448) ),  round to nearest, ties to even,   s = max|v| / 448  (1.0 if 0),
+ * Q_dual (Sec. 4.3.2) keeps its two steps s_+ = max x / 448, s_- = |min x| / 448, the products X^_+ W^ and X^_- W^ are
+ * sums of exact products of code values, and DeQuant is the same scaled sum.
+ */
+#define SQO_FP8_MAX 448.0f
+
+float sqo_fp8_decode(uint8_t c) {
+  int sign = c >> 7, e = (c >> 3) & 15, m = c & 7;
+  float v;
+  if (e == 15 && m == 7) return NAN;
+  if (e == 0) v = ldexpf((float)m, -9);            /* subnormal: m/8 * 2^-6 */
+  else v = ldexpf((float)(8 + m), e - 10);         /* (1 + m/8) * 2^(e-7) */
+  return sign ? -v : v;
+}
+
+/* Nearest E4M3 value to v (finite), ties to the even mantissa, saturating at +-448. */
+uint8_t sqo_fp8_encode(float v) {
+  uint8_t sign = signbit(v) ? 0x80 : 0x00;
+  float a = fabsf(v);
+  if (!(a < SQO_FP8_MAX)) return sign | 0x7E;      /* 448 and beyond */
+  /* walk the 127 non-negative finite codes: the representable values are ascending in the code */
+  int lo = 0;
+  for (int c = 1; c <= 0x7E; ++c)
+    if (sqo_fp8_decode((uint8_t)c) <= a) lo = c;
+  if (lo == 0x7E) return sign | 0x7E;
+  float vlo = sqo_fp8_decode((uint8_t)lo), vhi = sqo_fp8_decode((uint8_t)(lo + 1));
+  double dlo = (double)a - (double)vlo, dhi = (double)vhi - (double)a;
+  int pick = dlo < dhi ? lo : (dhi < dlo ? lo + 1 : ((lo & 1) ? lo + 1 : lo));
+  return sign | (uint8_t)pick;
+}
+
+void sqo_fp8_encode_array(const float* v, int64_t n, uint8_t* out) {
+  for (int64_t i = 0; i < n; ++i) out[i] = sqo_fp8_encode(v[i]);
+}
+void sqo_fp8_decode_array(const uint8_t* c, int64_t n, float* out) {
+  for (int64_t i = 0; i < n; ++i) out[i] = sqo_fp8_decode(c[i]);
+}
+
+int sqo_quantize_weight_fp8(const float* w, int N, int K, int S, const int32_t* kseg_off, uint8_t* wq, float* wscale) {
+  if (check_offsets(K, S, kseg_off)) return 1;
+#pragma omp parallel for schedule(static)
+  for (int n = 0; n < N; ++n)
+    for (int ks = 0; ks < S; ++ks) {
+      float a = 0.0f;
+      for (int k = kseg_off[ks]; k < kseg_off[ks + 1]; ++k) {
+        float v = fabsf(w[(int64_t)n * K + k]);
+        if (v > a) a = v;
+      }
+      float sw = (a == 0.0f) ? 1.0f : a / SQO_FP8_MAX;
+      wscale[(int64_t)ks * N + n] = sw;
+      for (int k = kseg_off[ks]; k < kseg_off[ks + 1]; ++k) wq[(int64_t)n * K + k] = sqo_fp8_encode(w[(int64_t)n * K + k] / sw);
+    }
+  return 0;
+}
+
+/* Q_dual with fp8 codes: x < 0 takes s_-, x >= 0 takes s_+; the other polarity's code is +0. */
+int sqo_quantize_act_fp8(const float* x, int M, int K, int S, const int32_t* kseg_off, const uint8_t* dual,
+                         const float* s_pos, const float* s_neg, uint8_t* xq_pos, uint8_t* xq_neg) {
+  if (check_offsets(K, S, kseg_off)) return 1;
+#pragma omp parallel for schedule(static)
+  for (int m = 0; m < M; ++m)
+    for (int ks = 0; ks < S; ++ks)
+      for (int k = kseg_off[ks]; k < kseg_off[ks + 1]; ++k) {
+        int64_t i = (int64_t)m * K + k;
+        float v = x[i];
+        if (dual[ks] && v < 0.0f) {
+          xq_neg[i] = sqo_fp8_encode(v / s_neg[ks]);
+          xq_pos[i] = 0;
+        } else {
+          xq_pos[i] = sqo_fp8_encode(v / s_pos[ks]);
+          xq_neg[i] = 0;
+        }
+      }
+  return 0;
+}
+
+/*
+ * The layer on fp8 codes, in double: per K-segment the two products of code VALUES (exact in double: every product is
+ * a multiple of 2^-18 below 2^18, a segment has at most 2^17 terms), then
+ *   y = sum_ks seg_scale[ks][ns(n)] wscale[ks][n] ( s_+[ks] acc_+ + s_-[ks] acc_- ) + bias[n].
+ * Also returns mag[m][n], the same sum over the magnitudes of the terms (the scale of the rounding error of an fp32
+ * evaluation).
+ */
+int sqo_seglinear_fp8(const uint8_t* xq_pos, const uint8_t* xq_neg, const uint8_t* wq, int M, int K, int N, int S,
+                      const int32_t* kseg_off, int T, const int32_t* nseg_off, const uint8_t* dual, const float* s_pos,
+                      const float* s_neg, const float* wscale, const float* seg_scale, const float* bias, double* y,
+                      double* mag) {
+  if (check_offsets(K, S, kseg_off) || check_offsets(N, T, nseg_off)) return 1;
+  float tab[256];
+  for (int c = 0; c < 256; ++c) tab[c] = ((c & 0x7F) == 0x7F) ? 0.0f : sqo_fp8_decode((uint8_t)c);
+#pragma omp parallel for schedule(static)
+  for (int m = 0; m < M; ++m)
+    for (int n = 0; n < N; ++n) {
+      int ns = 0;
+      while (ns + 1 < T && n >= nseg_off[ns + 1]) ++ns;
+      double yy = 0.0, mm = 0.0;
+      for (int ks = 0; ks < S; ++ks) {
+        double ap = 0.0, an = 0.0, mp = 0.0, mn = 0.0;
+        for (int k = kseg_off[ks]; k < kseg_off[ks + 1]; ++k) {
+          double wv = tab[wq[(int64_t)n * K + k]];
+          double p = (double)tab[xq_pos[(int64_t)m * K + k]] * wv;
+          ap += p;
+          mp += fabs(p);
+          if (dual[ks]) {
+            double q = (double)tab[xq_neg[(int64_t)m * K + k]] * wv;
+            an += q;
+            mn += fabs(q);
+          }
+        }
+        double c = (double)wscale[(int64_t)ks * N + n] * (seg_scale ? (double)seg_scale[ks * T + ns] : 1.0);
+        yy += c * ((double)s_pos[ks] * ap + (dual[ks] ? (double)s_neg[ks] * an : 0.0));
+        mm += fabs(c) * ((double)s_pos[ks] * mp + (dual[ks] ? (double)s_neg[ks] * mn : 0.0));
+      }
+      y[(int64_t)m * N + n] = yy + (bias ? (double)bias[n] : 0.0);
+      mag[(int64_t)m * N + n] = mm + (bias ? fabs((double)bias[n]) : 0.0);
+    }
+  return 0;
+}

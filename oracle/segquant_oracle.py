@@ -398,3 +398,54 @@ def lowrank(x, ld, lu, y_q=None):
     _check(_load().sqo_lowrank(_p(x), _p(ld), _p(lu), _p(yq), C.c_int(M), C.c_int(K), C.c_int(N), C.c_int(r), _p(t), _p(y)),
            "lowrank")
     return t, y
+
+
+def fp8_encode(v) -> np.ndarray:
+    """fp32 -> OCP E4M3 codes (uint8), nearest, ties to even, saturating at +-448."""
+    v = _f32(v)
+    out = np.empty(v.shape, np.uint8)
+    _load().sqo_fp8_encode_array(_p(v), C.c_int64(v.size), _p(out))
+    return out
+
+
+def fp8_decode(c) -> np.ndarray:
+    c = _u8(c)
+    out = np.empty(c.shape, np.float32)
+    _load().sqo_fp8_decode_array(_p(c), C.c_int64(c.size), _p(out))
+    return out
+
+
+def quantize_weight_fp8(w, kseg_off):
+    """-> (wq uint8 [N][K] E4M3 codes, wscale fp32 [S][N] = max|w| / 448)"""
+    w, off = _f32(w), _i32(kseg_off)
+    N, K = w.shape
+    S = len(off) - 1
+    wq, ws = np.empty((N, K), np.uint8), np.empty((S, N), np.float32)
+    _check(_load().sqo_quantize_weight_fp8(_p(w), C.c_int(N), C.c_int(K), C.c_int(S), _p(off), _p(wq), _p(ws)), "quantize_weight_fp8")
+    return wq, ws
+
+
+def quantize_act_fp8(x, kseg_off, dual, s_pos, s_neg):
+    """Q_dual with E4M3 codes -> (xq_pos, xq_neg) uint8 [M][K]"""
+    x, off, dual, sp, sn = _f32(x), _i32(kseg_off), _u8(dual), _f32(s_pos), _f32(s_neg)
+    M, K = x.shape
+    xp, xn = np.empty((M, K), np.uint8), np.empty((M, K), np.uint8)
+    _check(_load().sqo_quantize_act_fp8(_p(x), C.c_int(M), C.c_int(K), C.c_int(len(off) - 1), _p(off), _p(dual), _p(sp), _p(sn),
+                                        _p(xp), _p(xn)), "quantize_act_fp8")
+    return xp, xn
+
+
+def seglinear_fp8(xq_pos, xq_neg, wq, kseg_off, nseg_off, dual, s_pos, s_neg, wscale, seg_scale=None, bias=None):
+    """The layer on E4M3 codes in double -> (y fp64 [M][N], mag fp64 [M][N] = the same sum over |terms|)"""
+    xp, xn, wq = _u8(xq_pos), _u8(xq_neg), _u8(wq)
+    M, K = xp.shape
+    N = wq.shape[0]
+    koff, noff, dual = _i32(kseg_off), _i32(nseg_off), _u8(dual)
+    sp, sn, ws = _f32(s_pos), _f32(s_neg), _f32(wscale)
+    sg = None if seg_scale is None else _f32(seg_scale)
+    b = None if bias is None else _f32(bias)
+    y, mag = np.empty((M, N), np.float64), np.empty((M, N), np.float64)
+    _check(_load().sqo_seglinear_fp8(_p(xp), _p(xn), _p(wq), C.c_int(M), C.c_int(K), C.c_int(N), C.c_int(len(koff) - 1), _p(koff),
+                                     C.c_int(len(noff) - 1), _p(noff), _p(dual), _p(sp), _p(sn), _p(ws), _p(sg), _p(b), _p(y), _p(mag)),
+           "seglinear_fp8")
+    return y, mag

@@ -926,3 +926,85 @@ def test_lowrank_branch_reproduces_a_low_rank_weight(oracle):
     res = oracle.seglinear(x, resid, kseg, nseg, dual, sp, sp, wbits=4)
     _, y = oracle.lowrank(x, ld, lu, res.y32)
     assert np.linalg.norm(y - ref) < 0.5 * np.linalg.norm(plain.y32 - ref)
+
+
+# ----------------------------------------------------------------------------------------------------
+# fp8 variant (the 8/8 floating-point rows of the main results): OCP E4M3 codes in place of int8 ones
+# ----------------------------------------------------------------------------------------------------
+def test_fp8_format_against_the_published_table_and_torch(oracle):
+    """E4M3: landmark values of the published format, every code against torch's float8_e4m3fn (an independent
+    implementation), round trip of every finite code, ties to even, saturation at 448."""
+    torch = pytest.importorskip("torch")
+    codes = np.arange(256, dtype=np.uint8)
+    v = oracle.fp8_decode(codes)
+    assert v[0x00] == 0.0 and v[0x01] == 2.0 ** -9 and v[0x07] == 7 * 2.0 ** -9 and v[0x08] == 2.0 ** -6      # subnormals, first normal
+    assert v[0x38] == 1.0 and v[0x3C] == 1.5 and v[0x7E] == 448.0 and np.isnan(v[0x7F]) and np.isnan(v[0xFF])
+    assert v[0xB8] == -1.0 and v[0xFE] == -448.0
+    t = torch.from_numpy(codes).view(torch.float8_e4m3fn).float().numpy()
+    assert np.array_equal(np.nan_to_num(v, nan=-1e9), np.nan_to_num(t, nan=-1e9))
+    fin = (codes & 0x7F) != 0x7F
+    back = oracle.fp8_encode(v[fin])
+    want = codes[fin].copy()
+    assert np.array_equal(back & 0x7F, want & 0x7F) and np.array_equal(back[want != 0x80], want[want != 0x80])
+    # ties: halfway between neighbours goes to the even mantissa; just off the tie goes to the nearer one
+    assert oracle.fp8_encode(np.array([1.0625, 1.1875, 1.0626, 1.0624], np.float32)).tolist() == [0x38, 0x3A, 0x39, 0x38]
+    assert oracle.fp8_encode(np.array([2.0 ** -10, 3 * 2.0 ** -10, 2.0 ** -11], np.float32)).tolist() == [0x00, 0x02, 0x00]
+    assert oracle.fp8_encode(np.array([448.0, 449.0, 1e9, -1e9, 464.0], np.float32)).tolist() == [0x7E, 0x7E, 0x7E, 0xFE, 0x7E]
+    rng = np.random.default_rng(0)
+    x = (rng.standard_normal(100000) * rng.choice([1e-3, 0.05, 1, 30, 200], 100000)).astype(np.float32)
+    x = np.clip(x, -448, 448)
+    te = torch.from_numpy(x).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(oracle.fp8_encode(x), te)
+    # nearest: no other code is closer
+    grid = v[:0x7F].astype(np.float64)
+    xa = np.abs(x[:2000]).astype(np.float64)
+    got = oracle.fp8_decode(oracle.fp8_encode(np.abs(x[:2000]))).astype(np.float64)
+    assert np.all(np.abs(got - xa) <= np.abs(grid[None, :] - xa[:, None]).min(axis=1) + 1e-300)
+
+
+def test_fp8_quantizers_and_layer(oracle):
+    """Steps = range / 448; the extreme gets +-448; values on the code grid with power-of-two steps round-trip and the
+    layer is then exact; Q_dual keeps the two polarity matrices disjoint; the layer in double agrees with a float64
+    matmul of the decoded operands; the error against the unquantized layer stays inside the format's bound."""
+    rng = np.random.default_rng(1)
+    M, K, N = 9, 64, 7
+    kseg, nseg, dual = [0, 24, 64], [0, 3, 7], [1, 0]
+    w_ = wl.random_layer(M, K, N, kseg, nseg, dual, seed=3, x_dtype="f32", act="gelu", with_seg_scale=True, with_bias=True)
+    wq, ws = oracle.quantize_weight_fp8(w_.w, kseg)
+    for ks in range(2):
+        blk = np.abs(w_.w[:, kseg[ks]:kseg[ks + 1]]).max(axis=1)
+        assert np.array_equal(ws[ks], (blk / np.float32(448)).astype(np.float32))
+        assert np.all((wq[:, kseg[ks]:kseg[ks + 1]] & 0x7F).max(axis=1) == 0x7E)
+    sp, sn, ap, an = oracle.calibrate_act(w_.x, kseg, dual)
+    sp8 = np.where(ap == 0, np.float32(1), ap / np.float32(448)).astype(np.float32)
+    sn8 = np.where(an == 0, np.float32(1), an / np.float32(448)).astype(np.float32)
+    xp, xn = oracle.quantize_act_fp8(w_.x, kseg, dual, sp8, sn8)
+    assert not np.logical_and((xp & 0x7F) != 0, (xn & 0x7F) != 0).any()
+    assert np.all(xn[:, 24:] == 0) and np.all((xn & 0x80)[(xn & 0x7F) != 0] == 0x80) and np.all((xp[:, :24] & 0x80) == 0)
+    y, mag = oracle.seglinear_fp8(xp, xn, wq, kseg, nseg, dual, sp8, sn8, ws, w_.seg_scale, w_.bias)
+    # independent evaluation: decode, scale, float64 matmul per K-segment
+    ref = np.zeros((M, N))
+    nsof = np.searchsorted(np.asarray(nseg), np.arange(N), side="right") - 1
+    for ks in range(2):
+        sl = slice(kseg[ks], kseg[ks + 1])
+        xv = oracle.fp8_decode(xp[:, sl]).astype(np.float64) * sp8[ks] + oracle.fp8_decode(xn[:, sl]).astype(np.float64) * sn8[ks]
+        wv = oracle.fp8_decode(wq[:, sl]).astype(np.float64) * ws[ks][:, None].astype(np.float64)
+        ref += (xv @ wv.T) * w_.seg_scale.reshape(2, -1)[ks][nsof][None, :]
+    ref += w_.bias
+    assert np.abs(y - ref).max() <= 1e-12 * np.abs(mag).max()
+    assert np.all(mag + 1e-300 >= np.abs(y) - 1e-12 * np.abs(mag).max())
+    # grid values, power-of-two steps: exact
+    gx = oracle.fp8_decode(rng.integers(0, 0x7F, size=(4, 16)).astype(np.uint8)) * np.float32(0.25)
+    gx[0, 0] = 448 * 0.25
+    gw = oracle.fp8_decode(rng.integers(0x80, 0xFF, size=(3, 16)).astype(np.uint8)) * np.float32(2.0)
+    gw[:, 0] = -448 * 2.0                                  # every output channel holds the extreme: its step is exactly 2
+    q, s = oracle.quantize_weight_fp8(gw, [0, 16])
+    assert np.all(s == 2.0) and np.array_equal(oracle.fp8_decode(q) * 2.0, gw)
+    p, n_ = oracle.quantize_act_fp8(gx, [0, 16], [0], [0.25], [0.25])
+    yy, _ = oracle.seglinear_fp8(p, n_, q, [0, 16], [0, 3], [0], [0.25], [0.25], s)
+    assert np.array_equal(yy, gx.astype(np.float64) @ gw.astype(np.float64).T)
+    # error against the unquantized layer: relative 2^-4 per operand (3 mantissa bits), subnormal codes aside
+    full = w_.x.astype(np.float64) @ w_.w.astype(np.float64).T
+    plain, _ = oracle.seglinear_fp8(xp, xn, wq, kseg, nseg, dual, sp8, sn8, ws)
+    bound = (np.abs(w_.x).astype(np.float64) @ np.abs(w_.w).astype(np.float64).T) * (2 * 2.0 ** -4 + 2.0 ** -8) + 1e-3
+    assert np.all(np.abs(plain - full) <= bound)
