@@ -405,6 +405,30 @@ size_t sq_lowrank_workspace_bytes(const sq_layer* layer, int32_t rank);
 sq_status sq_lowrank_add(const sq_layer* layer, const void* x, sq_dtype x_dt, const void* ld, const void* lu, int32_t rank,
                          const float* y_q, void* y, sq_dtype y_dt, void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * The 8-bit floating-point variant of the layer (main results, the 8-bit fp rows: weights and activations as fp8 in place
+ * of int8).  Codes are bytes in the published OCP 8-bit format E4M3 (1 sign bit, 4 exponent bits with bias 7, 3 mantissa
+ * bits, subnormals, no infinities, 0x7F / 0xFF = NaN and never produced, largest finite value 448):
+ *   code(v, s) = e4m3(clip(v / s, -448, 448)), nearest value, ties to the even mantissa, the quotient an IEEE fp32 division;
+ *   a result of zero is stored as +0 (0x00).
+ * The quantizers of Sec. 3 and Sec. 4.3.2 are otherwise unchanged: weight steps are max|w| / 448 per output channel and
+ * K-segment (1 where that maximum is 0), written to wscale [S][N]; the activation steps are the layer's s_pos / s_neg
+ * (calibrated ranges / 448: the caller divides the amax that sq_calibrate_act* return).  Q_dual splits by the sign of x,
+ * so the two polarity matrices travel as one byte matrix: X^_+ = codes with a clear sign bit, X^_- = codes with the sign
+ * bit set (the other positions +0).
+ *   y[m][n] = sum_ks wscale[ks][n] g(ks, n) (s_pos[ks] X^_+ W^T + s_neg[ks] X^_- W^T)[m][n] + bias[n]
+ * with the products of the decoded codes summed in fp32 on the fp8 matrix cores within a K-segment (the order of that
+ * sum is the hardware's: results are reproducible on this device, and within (8 sqrt(K) + 64) 2^-24 of the sum of the
+ * terms' magnitudes of the exact value).  K, every K-segment boundary: multiples of 128, xq / wq 16-byte aligned
+ * (SQ_ERR_UNSUPPORTED otherwise; the quantizers take any shape).
+ *   w   dev [N][K] of w_dt      wq  dev, bytes [N][K]      wscale  dev fp32 [S][N]
+ *   x   dev [M][K] of x_dt      xq  dev, bytes [M][K]      bias    dev fp32 [N] or NULL      y  dev [M][N] of y_dt
+ */
+sq_status sq_quantize_weight_fp8(const sq_layer* layer, const void* w, sq_dtype w_dt, uint8_t* wq, float* wscale, void* stream);
+sq_status sq_quantize_act_fp8(const sq_layer* layer, const void* x, sq_dtype x_dt, uint8_t* xq, void* stream);
+sq_status sq_seglinear_fp8(const sq_layer* layer, const uint8_t* xq, const uint8_t* wq, const float* wscale, const float* bias,
+                           void* y, sq_dtype y_dt, void* stream);
+
 /* Human-readable name of a status code (static storage). */
 const char* sq_status_string(sq_status s);
 

@@ -30,7 +30,8 @@ EXPORTS = ("sq_quantize_weight", "sq_quantize_act", "sq_seglinear", "sq_seglinea
            "sq_seglinear_fused_dynamic", "sq_unpack_w4", "sq_quantize_act_dynamic_bits", "sq_seglinear_grouped_w4",
            "sq_calibrate_act_percentile_static", "sq_calibrate_static_scratch_bytes",
            "sq_calibrate_channel_amax", "sq_weight_channel_amax", "sq_smooth_factors", "sq_quantize_weight_smoothed",
-           "sq_quantize_act_smoothed", "sq_lowrank_add", "sq_lowrank_workspace_bytes")
+           "sq_quantize_act_smoothed", "sq_lowrank_add", "sq_lowrank_workspace_bytes",
+           "sq_quantize_weight_fp8", "sq_quantize_act_fp8", "sq_seglinear_fp8")
 
 
 class SqError(RuntimeError):
@@ -109,6 +110,12 @@ def load_library() -> C.CDLL:
         f.restype = i32
     lib.sq_lowrank_add.argtypes = [lp, vp, i32, vp, vp, i32, vp, vp, i32, vp, C.c_size_t, vp]
     lib.sq_lowrank_add.restype = i32
+    lib.sq_quantize_weight_fp8.argtypes = [lp, vp, i32, vp, vp, vp]
+    lib.sq_quantize_weight_fp8.restype = i32
+    lib.sq_quantize_act_fp8.argtypes = [lp, vp, i32, vp, vp]
+    lib.sq_quantize_act_fp8.restype = i32
+    lib.sq_seglinear_fp8.argtypes = [lp, vp, vp, vp, vp, vp, i32, vp]
+    lib.sq_seglinear_fp8.restype = i32
     lib.sq_lowrank_workspace_bytes.argtypes = [lp, i32]
     lib.sq_lowrank_workspace_bytes.restype = C.c_size_t
     lib.sq_calibrate_workspace_bytes.argtypes = []
@@ -298,6 +305,24 @@ def sq_lowrank_add(layer: Layer, x, ld, lu, y_q, y, workspace, stream=None) -> N
     _check(load_library().sq_lowrank_add(C.byref(layer.c), _dptr(x), _dt(x), _dptr(ld), _dptr(lu), rank, _dptr(y_q), _dptr(y),
                                          _dt(y), _dptr(workspace), workspace.numel() * workspace.element_size(),
                                          _stream(stream)), "sq_lowrank_add")
+
+
+def sq_quantize_weight_fp8(layer: Layer, w, wq, wscale, stream=None) -> None:
+    """w [N][K] fp32/bf16 -> wq uint8 [N][K] (E4M3 codes), wscale fp32 [S][N] = max|w| / 448 per channel and K-segment."""
+    _check(load_library().sq_quantize_weight_fp8(C.byref(layer.c), _dptr(w), _dt(w), _dptr(wq), _dptr(wscale),
+                                                 _stream(stream)), "sq_quantize_weight_fp8")
+
+
+def sq_quantize_act_fp8(layer: Layer, x, xq, stream=None) -> None:
+    """x [M][K] fp32/bf16 -> xq uint8 [M][K], E4M3 codes of Q_dual (X^_+: sign bit clear, X^_-: sign bit set)."""
+    _check(load_library().sq_quantize_act_fp8(C.byref(layer.c), _dptr(x), _dt(x), _dptr(xq), _stream(stream)),
+           "sq_quantize_act_fp8")
+
+
+def sq_seglinear_fp8(layer: Layer, xq, wq, wscale, bias, y, stream=None) -> None:
+    """The layer on fp8 codes: K-segment sums on the fp8 matrix cores (fp32 accumulation), dequantized into y."""
+    _check(load_library().sq_seglinear_fp8(C.byref(layer.c), _dptr(xq), _dptr(wq), _dptr(wscale), _dptr(bias), _dptr(y),
+                                           _dt(y), _stream(stream)), "sq_seglinear_fp8")
 
 
 def sq_quantize_act(layer: Layer, x, xq, stream=None) -> None:

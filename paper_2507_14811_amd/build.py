@@ -28,7 +28,7 @@ FLAGS = [
     f"-I{os.path.join(ROOT, 'include')}", f"-I{CSRC}",
 ]
 PLAIN_SOURCES = ["api.hip", "quantize.hip", "seglinear_generic.hip", "seglinear_skinny.hip", "seglinear_stream.hip", "calibrate.hip",
-                 "seglinear_mfma.hip", "smooth.hip", "lowrank.hip"]
+                 "seglinear_mfma.hip", "smooth.hip", "lowrank.hip", "fp8.hip"]
 # benchmark probes: a library of their own (include/segquant_probes.h), loaded by bench.py only
 PROBE_LIB = os.path.join(PKG, "libsegquant_probes.so")
 

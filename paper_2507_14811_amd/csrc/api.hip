@@ -428,6 +428,60 @@ sq_status sq_lowrank_add(const sq_layer* layer, const void* x, sq_dtype x_dt, co
   return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 
+sq_status sq_quantize_weight_fp8(const sq_layer* layer, const void* w, sq_dtype w_dt, uint8_t* wq, float* wscale, void* stream) {
+  sq_status st = check_layer(layer, false, false);
+  if (st != SQ_OK) return st;
+  if (w == nullptr || wq == nullptr || wscale == nullptr) return SQ_ERR_INVALID_ARG;
+  if (w_dt != SQ_F32 && w_dt != SQ_BF16) return SQ_ERR_INVALID_ARG;
+  sq::KsegTable tb;
+  tb.S = layer->S;
+  for (int s = 0; s <= layer->S; ++s) tb.off[s] = layer->kseg_off[s];
+  hipError_t e = sq::launch_quantize_weight_fp8(w, w_dt == SQ_BF16, wq, wscale, layer->N, layer->K, tb,
+                                                reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
+sq_status sq_quantize_act_fp8(const sq_layer* layer, const void* x, sq_dtype x_dt, uint8_t* xq, void* stream) {
+  sq_status st = check_layer(layer, true, true);
+  if (st != SQ_OK) return st;
+  if (x == nullptr || xq == nullptr) return SQ_ERR_INVALID_ARG;
+  if (x_dt != SQ_F32 && x_dt != SQ_BF16) return SQ_ERR_INVALID_ARG;
+  sq::ActTable tb;
+  std::memset(&tb, 0, sizeof(tb));
+  tb.S = layer->S;
+  for (int s = 0; s <= layer->S; ++s) tb.kseg_off[s] = layer->kseg_off[s];
+  for (int s = 0; s < layer->S; ++s) {
+    tb.dual[s] = layer->dual[s] ? 1 : 0;
+    tb.s_pos[s] = layer->s_pos[s];
+    tb.s_neg[s] = layer->dual[s] ? layer->s_neg[s] : 1.0f;
+    tb.act[s] = SQ_ACT_NONE;
+  }
+  hipError_t e = sq::launch_quantize_act_fp8(x, x_dt == SQ_BF16, xq, layer->M, layer->K, tb, reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
+sq_status sq_seglinear_fp8(const sq_layer* layer, const uint8_t* xq, const uint8_t* wq, const float* wscale, const float* bias,
+                           void* y, sq_dtype y_dt, void* stream) {
+  sq_status st = check_layer(layer, true, true);
+  if (st != SQ_OK) return st;
+  if (xq == nullptr || wq == nullptr || wscale == nullptr || y == nullptr) return SQ_ERR_INVALID_ARG;
+  if (y_dt != SQ_F32 && y_dt != SQ_BF16) return SQ_ERR_INVALID_ARG;
+  sq::GemmTable tb;
+  fill_gemm_table(layer, tb);
+  sq::GemmArgs a{};
+  a.xq = reinterpret_cast<const int8_t*>(xq);
+  a.wq = reinterpret_cast<const int8_t*>(wq);
+  a.wscale = wscale;
+  a.bias = bias;
+  a.y = y;
+  a.M = layer->M;
+  a.K = layer->K;
+  a.N = layer->N;
+  if (!sq::fp8_gemm_supported(a, tb)) return SQ_ERR_UNSUPPORTED;
+  hipError_t e = sq::launch_seglinear_fp8(a, tb, y_dt == SQ_BF16 ? sq::OUT_BF16 : sq::OUT_F32, reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
 size_t sq_quantize_act_fused_workspace_bytes(const sq_layer* layer) {
   if (layer == nullptr || layer->S < 1 || layer->S > SQ_MAX_SEGMENTS) return 0;
   return sq::quantize_act_fused_workspace_bytes(layer->S);

@@ -68,6 +68,14 @@ size_t lowrank_workspace_bytes(int M, int K, int rank, int cus);
 hipError_t launch_lowrank_add(const void* x, bool x_is_bf16, const uint16_t* ld, const uint16_t* lu, int rank, const float* y_in,
                               void* y_out, bool y_is_bf16, int M, int K, int N, float* workspace, int cus, hipStream_t st);
 
+// fp8.hip : the 8-bit floating-point variant (OCP E4M3 codes, steps range / 448, fp8 matrix cores with fp32 accumulation).
+// The GEMM needs K and every K-segment boundary % 128 == 0 and 16-byte aligned code matrices.
+hipError_t launch_quantize_weight_fp8(const void* w, bool w_is_bf16, uint8_t* wq, float* wscale, int N, int K,
+                                      const KsegTable& tb, hipStream_t st);
+hipError_t launch_quantize_act_fp8(const void* x, bool x_is_bf16, uint8_t* xq, int M, int K, const ActTable& tb, hipStream_t st);
+bool fp8_gemm_supported(const GemmArgs& a, const GemmTable& tb);
+hipError_t launch_seglinear_fp8(const GemmArgs& a, const GemmTable& tb, OutMode mode, hipStream_t st);
+
 // seglinear_generic.hip : any shape / alignment, one thread per output element
 hipError_t launch_seglinear_generic(const GemmArgs& a, const GemmTable& tb, OutMode mode, hipStream_t st);
 

@@ -735,6 +735,213 @@ def test_w4_layer_with_lowrank_branch(oracle, M):
     assert np.linalg.norm(got - full) < np.linalg.norm(plain.y32 - full)
 
 
+# ----------------------------------------------------------------------------------------------------
+# the 8-bit floating-point variant (OCP E4M3 codes)
+# ----------------------------------------------------------------------------------------------------
+def _plus_zero(c):
+    """The library stores every zero as +0; the format's -0 is the same value."""
+    c = c.copy()
+    c[c == 0x80] = 0
+    return c
+
+
+def _split_fp8(w, xq):
+    """Documented decoding of the merged fp8 activation codes: in a dual K-segment X^_- holds the codes with the sign bit
+    set and X^_+ the others, the rest +0; elsewhere X^_+ = xq (index work only)."""
+    mask = _gpu().dual_col_mask(w)
+    xp, xn = xq.copy(), np.zeros_like(xq)
+    neg = (xq & 0x80) != 0
+    neg[:, ~mask] = False
+    xn[neg] = xq[neg]
+    xp[neg] = 0
+    return xp, xn
+
+
+@pytest.mark.parametrize("w_dtype", ["f32", "bf16"])
+def test_fp8_encoding_through_the_weight_quantizer(oracle, w_dtype):
+    """Rows whose largest magnitude is 448 have step 1, so their codes are the bare fp32 -> E4M3 conversion: every finite
+    code's value, every midpoint between neighbours (ties), the fp32 neighbours of those midpoints, the subnormal range,
+    zeros of both signs and values that underflow.  Other rows: random steps."""
+    import torch
+
+    g = _gpu()
+    vals = oracle.fp8_decode(np.array([c for c in range(256) if (c & 0x7F) != 0x7F], np.uint8))
+    pos = np.sort(np.unique(np.abs(vals)))
+    mid = ((pos[:-1].astype(np.float64) + pos[1:].astype(np.float64)) / 2).astype(np.float32)
+    probe = np.concatenate([vals, mid, -mid, np.nextafter(mid, np.float32(0)), np.nextafter(mid, np.float32(1e9)),
+                            -np.nextafter(mid, np.float32(0)), np.float32([0.0, -0.0, 1e-6, -1e-6, 2.0 ** -10, -2.0 ** -10, 447.9, 448.0])])
+    if w_dtype == "bf16":
+        probe = _bf16_round(probe)
+    K = 1024
+    assert probe.size <= K - 1
+    rng = np.random.default_rng(5)
+    N = 37
+    wm = (rng.standard_normal((N, K)) * 0.05).astype(np.float32)
+    wm[0, :probe.size] = probe
+    wm[0, probe.size:] = 0.0
+    wm[0, K - 1] = -448.0
+    wm[1] = 0.0                                                   # dead channel: step 1, codes +0
+    wm[2] = np.float32(1e-30) * rng.standard_normal(K).astype(np.float32)
+    if w_dtype == "bf16":
+        wm = _bf16_round(wm)
+    for kseg in ([0, K], [0, 100, 612, K]):
+        S = len(kseg) - 1
+        layer = sq.Layer(4, K, N, kseg, [0, N], [0] * S)
+        wd = _bf16_dev(g, wm) if w_dtype == "bf16" else torch.from_numpy(wm).to(g.DEV)
+        wq = torch.full((N, K), 0x7F, dtype=torch.uint8, device=g.DEV)
+        ws = torch.full((S, N), float("nan"), dtype=torch.float32, device=g.DEV)
+        sq.sq_quantize_weight_fp8(layer, wd, wq, ws)
+        torch.cuda.synchronize()
+        r_wq, r_ws = oracle.quantize_weight_fp8(wm, kseg)
+        assert np.array_equal(ws.cpu().numpy().view(np.uint32), r_ws.view(np.uint32))
+        assert np.array_equal(wq.cpu().numpy(), _plus_zero(r_wq))
+    assert r_ws[0, 1] == 1.0
+
+
+@pytest.mark.parametrize("case", [
+    dict(M=9, K=64, kseg=[0, 64], dual=[1], x_dtype="bf16"),
+    dict(M=70, K=512, kseg=[0, 128, 512], dual=[0, 1], x_dtype="f32"),
+    dict(M=13, K=100, kseg=[0, 37, 100], dual=[1, 1], x_dtype="bf16"),        # unaligned: element-wise kernel
+    dict(M=13, K=100, kseg=[0, 37, 100], dual=[1, 0], x_dtype="f32"),
+    dict(M=300, K=2048, kseg=[0, 2048], dual=[0], x_dtype="bf16"),
+    dict(M=129, K=1024, kseg=[0, 16, 32, 48, 1024], dual=[1, 0, 1, 1], x_dtype="bf16"),
+])
+@pytest.mark.parametrize("scales", ["amax", "pow2", "clip"])
+def test_quantize_act_fp8(oracle, case, scales):
+    import torch
+
+    g = _gpu()
+    w = wl.random_layer(case["M"], case["K"], 4, case["kseg"], [0, 4], case["dual"], seed=case["K"] + case["M"],
+                        x_dtype=case["x_dtype"], act="gelu")
+    S = w.S
+    w.s_pos = (w.s_pos * np.float32(127.0 / 448.0)).astype(np.float32)      # the calibrated ranges over 448
+    w.s_neg = (w.s_neg * np.float32(127.0 / 448.0)).astype(np.float32)
+    if scales == "pow2":      # exact quotients, many of them ties of the 3-bit mantissa
+        w.x = np.round(w.x * 64).astype(np.float32) / 64
+        w.s_pos = np.full(S, 2.0 ** -5, np.float32)
+        w.s_neg = np.full(S, 2.0 ** -8, np.float32)
+    elif scales == "clip":    # steps far too small: saturation at +-448
+        w.s_pos = (w.s_pos / 50).astype(np.float32)
+        w.s_neg = (w.s_neg / 50).astype(np.float32)
+    w.x[0, 0] = -0.0
+    gl = g.GpuLayer(w)
+    xq = torch.full((w.M, w.K), 0x7F, dtype=torch.uint8, device=g.DEV)
+    sq.sq_quantize_act_fp8(gl.layer, gl.x, xq)
+    torch.cuda.synchronize()
+    r_xp, r_xn = oracle.quantize_act_fp8(w.x, w.kseg_off, w.dual, w.s_pos, w.s_neg)
+    xp, xn = _split_fp8(w, xq.cpu().numpy())
+    assert np.array_equal(xp, _plus_zero(r_xp)) and np.array_equal(xn, _plus_zero(r_xn))
+    if scales == "clip":
+        assert (xp == 0x7E).any()
+
+
+FP8GEMM = [
+    dict(M=300, K=512, N=200, kseg=[0, 128, 512], nseg=[0, 200], dual=[1, 0], bias=True),
+    dict(M=128, K=1152, N=256, kseg=[0, 1152], nseg=[0, 256], dual=[1], bias=False),
+    dict(M=5, K=128, N=3, kseg=[0, 128], nseg=[0, 3], dual=[0], bias=True),              # one stage, mostly masked tile
+    dict(M=257, K=1536, N=385, kseg=[0, 256, 384, 1536], nseg=[0, 129, 385], dual=[0, 1, 1], bias=True, seg_scale=True),
+    dict(M=1024, K=4608, N=1152, kseg=[0, 1536, 4608], nseg=[0, 1152], dual=[0, 1], bias=True),
+]
+
+
+def _fp8_tol(K, mag, ref, ydt):
+    """Error of the fp32 evaluation (products of codes are exact in fp32; their sum of up to K terms and the few
+    multiplications of the flush are rounded) plus the output rounding."""
+    return (8.0 * np.sqrt(K) + 64.0) * 2.0 ** -24 * mag + np.abs(ref) * (2.0 ** -8 if ydt == "bf16" else 2.0 ** -23) + 1e-30
+
+
+@pytest.mark.parametrize("case", FP8GEMM)
+def test_seglinear_fp8(oracle, case):
+    """The fp8 layer end to end on every element: codes and steps bit-exact, outputs within the bound of an fp32
+    evaluation around the double-precision oracle, fp32 and bf16 outputs."""
+    import torch
+
+    g = _gpu()
+    M, K, N = case["M"], case["K"], case["N"]
+    w = wl.random_layer(M, K, N, case["kseg"], case["nseg"], case["dual"], seed=M + K + N, x_dtype="bf16", act="silu",
+                        with_bias=case["bias"], with_seg_scale=case.get("seg_scale", False))
+    w.s_pos = (w.s_pos * np.float32(127.0 / 448.0)).astype(np.float32)
+    w.s_neg = (w.s_neg * np.float32(127.0 / 448.0)).astype(np.float32)
+    gl = g.GpuLayer(w)
+    wq = torch.full((N, K), 0x7F, dtype=torch.uint8, device=g.DEV)
+    xq = torch.full((M, K), 0x7F, dtype=torch.uint8, device=g.DEV)
+    sq.sq_quantize_weight_fp8(gl.layer, gl.wt, wq, gl.wscale)
+    sq.sq_quantize_act_fp8(gl.layer, gl.x, xq)
+    torch.cuda.synchronize()
+    r_wq, r_ws = oracle.quantize_weight_fp8(w.w, w.kseg_off)
+    r_xp, r_xn = oracle.quantize_act_fp8(w.x, w.kseg_off, w.dual, w.s_pos, w.s_neg)
+    assert np.array_equal(wq.cpu().numpy(), _plus_zero(r_wq))
+    assert np.array_equal(gl.wscale.cpu().numpy().view(np.uint32), r_ws.view(np.uint32))
+    xp, xn = _split_fp8(w, xq.cpu().numpy())
+    assert np.array_equal(xp, _plus_zero(r_xp)) and np.array_equal(xn, _plus_zero(r_xn))
+    ref, mag = oracle.seglinear_fp8(r_xp, r_xn, r_wq, w.kseg_off, w.nseg_off, w.dual, w.s_pos, w.s_neg, r_ws, w.seg_scale, w.bias)
+    for ydt in ("f32", "bf16"):
+        y = torch.full((M, N), float("nan"), dtype=torch.bfloat16 if ydt == "bf16" else torch.float32, device=g.DEV)
+        sq.sq_seglinear_fp8(gl.layer, xq, wq, gl.wscale, gl.bias, y)
+        torch.cuda.synchronize()
+        got = y.float().cpu().numpy().astype(np.float64)
+        assert not np.isnan(got).any()
+        tol = _fp8_tol(K, mag, ref, ydt)
+        assert (np.abs(got - ref) <= tol).all(), float((np.abs(got - ref) / tol).max())
+        if ydt == "f32":          # the typical error is far inside the bound
+            assert np.abs(got - ref).max() <= 2e-5 * np.abs(ref).max()
+    # the variant does its job: close to the unquantized layer (3 mantissa bits: a few percent)
+    if w.seg_scale is None:
+        full = w.x.astype(np.float64) @ w.w.astype(np.float64).T + (0.0 if w.bias is None else w.bias)
+        assert np.linalg.norm(ref - full) < 0.06 * np.linalg.norm(full)
+
+
+def test_seglinear_fp8_exact_sums_and_polarity(oracle):
+    """Codes of small integers and steps that are powers of two: every partial sum is an integer below 2^24, so the fp32
+    evaluation is exact in any order and the output must equal the oracle's to the bit; the dual K-segment has both
+    polarities in every row."""
+    import torch
+
+    g = _gpu()
+    M, K, N = 200, 640, 136
+    kseg, dual = [0, 256, 640], [1, 0]
+    rng = np.random.default_rng(9)
+    xi = rng.integers(-8, 9, size=(M, K)).astype(np.float32)
+    wi = rng.integers(-8, 9, size=(N, K)).astype(np.float32)
+    wi[:, 0] = 448.0                                        # weight steps of exactly 1 in the first K-segment
+    wi[:, 300] = -448.0
+    s_pos, s_neg = np.float32([0.5, 2.0]), np.float32([0.25, 1.0])
+    x = xi.copy()
+    x[:, :256] *= np.where(xi[:, :256] < 0, s_neg[0], s_pos[0])
+    x[:, 256:] *= s_pos[1]
+    layer = sq.Layer(M, K, N, kseg, [0, N], dual, s_pos, s_neg)
+    xq = torch.empty((M, K), dtype=torch.uint8, device=g.DEV)
+    wq = torch.empty((N, K), dtype=torch.uint8, device=g.DEV)
+    ws = torch.empty((2, N), dtype=torch.float32, device=g.DEV)
+    y = torch.full((M, N), float("nan"), dtype=torch.float32, device=g.DEV)
+    sq.sq_quantize_weight_fp8(layer, torch.from_numpy(wi).to(g.DEV), wq, ws)
+    sq.sq_quantize_act_fp8(layer, torch.from_numpy(x).to(g.DEV), xq)
+    sq.sq_seglinear_fp8(layer, xq, wq, ws, None, y)
+    torch.cuda.synchronize()
+    r_wq, r_ws = oracle.quantize_weight_fp8(wi, kseg)
+    r_xp, r_xn = oracle.quantize_act_fp8(x, kseg, dual, s_pos, s_neg)
+    assert (r_ws == 1.0).all()
+    ref, _ = oracle.seglinear_fp8(r_xp, r_xn, r_wq, kseg, [0, N], dual, s_pos, s_neg, r_ws)
+    assert np.array_equal(y.cpu().numpy().astype(np.float64), ref)
+    # and the plain definition on the integers themselves
+    plain = (x.astype(np.float64) @ wi.astype(np.float64).T)
+    assert np.array_equal(ref, plain)
+
+
+def test_seglinear_fp8_rejects_unaligned_layouts():
+    import torch
+
+    g = _gpu()
+    for K, kseg in ((192, [0, 192]), (256, [0, 64, 256])):
+        layer = sq.Layer(4, K, 8, kseg, [0, 8], [0] * (len(kseg) - 1), np.ones(len(kseg) - 1, np.float32), np.ones(len(kseg) - 1, np.float32))
+        xq = torch.zeros((4, K), dtype=torch.uint8, device=g.DEV)
+        wq = torch.zeros((8, K), dtype=torch.uint8, device=g.DEV)
+        ws = torch.ones((len(kseg) - 1, 8), dtype=torch.float32, device=g.DEV)
+        y = torch.zeros((4, 8), dtype=torch.float32, device=g.DEV)
+        with pytest.raises(sq.SqError):
+            sq.sq_seglinear_fp8(layer, xq, wq, ws, None, y)
+
+
 GENERIC = [
     dict(M=7, K=100, N=13, kseg=[0, 37, 100], nseg=[0, 5, 13], dual=[1, 0]),
     dict(M=70, K=96, N=65, kseg=[0, 96], nseg=[0, 65], dual=[1]),
