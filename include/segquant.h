@@ -420,7 +420,9 @@ sq_status sq_lowrank_add(const sq_layer* layer, const void* x, sq_dtype x_dt, co
  * with the products of the decoded codes summed in fp32 on the fp8 matrix cores within a K-segment (the order of that
  * sum is the hardware's: results are reproducible on this device, and within (8 sqrt(K) + 64) 2^-24 of the sum of the
  * terms' magnitudes of the exact value).  K, every K-segment boundary: multiples of 128, xq / wq 16-byte aligned
- * (SQ_ERR_UNSUPPORTED otherwise; the quantizers take any shape).
+ * (SQ_ERR_UNSUPPORTED otherwise; the quantizers take any shape).  The product runs on the pipelined tile kernel of
+ * sq_seglinear with fp8 operands (tile shape chosen per layer; sq_tuning_set "gemm_variant" selects one, "force_path" 0
+ * a plain tile kernel without the software pipeline).
  *   w   dev [N][K] of w_dt      wq  dev, bytes [N][K]      wscale  dev fp32 [S][N]
  *   x   dev [M][K] of x_dt      xq  dev, bytes [M][K]      bias    dev fp32 [N] or NULL      y  dev [M][N] of y_dt
  */

@@ -24,6 +24,13 @@ extern "C" {
 int sqp_mfma(const int8_t* codes, size_t bytes, int iters, double* ops, void* stream);
 
 /*
+ * The same loop on the fp8 matrix cores (v_mfma_f32_32x32x64_f8f6f4 with E4M3 operands, no block scales, fp32
+ * accumulators): `codes` as above, read as E4M3 bytes (every 256-byte group: 128 bytes of A operands, then 128 of B;
+ * NaN codes are turned into the neighbouring finite code).  *ops receives the floating-point operations of one launch.
+ */
+int sqp_mfma_fp8(const uint8_t* codes, size_t bytes, int iters, double* ops, void* stream);
+
+/*
  * Launch floor: a kernel of `grid` workgroups of `block` threads (a multiple of 64, at most 1024) that reserves
  * `lds_bytes` of LDS (0 .. 160 KiB) and does nothing.  What a call of this costs is what no kernel of that launch
  * shape can go below.

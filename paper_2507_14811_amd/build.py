@@ -38,11 +38,20 @@ def _num_variants() -> int:
         return int(re.search(r"kNumMfmaVariants\s*=\s*(\d+)", f.read()).group(1))
 
 
+def _fp8_variants() -> list:
+    with open(os.path.join(CSRC, "seglinear_mfma_variants.hpp")) as f:
+        flags = re.search(r"kMfmaVariantHasFp8\[[^\]]*\]\s*=\s*\{([^}]*)\}", f.read()).group(1)
+    return [i for i, t in enumerate(flags.split(",")) if t.strip() == "true"]
+
+
 def _jobs():
     jobs = [(os.path.join(CSRC, s), os.path.join(OBJ, s.replace(".hip", ".o")), []) for s in PLAIN_SOURCES]
     for v in range(_num_variants()):
         jobs.append((os.path.join(CSRC, "seglinear_mfma_inst.hip"), os.path.join(OBJ, f"seglinear_mfma_v{v}.o"),
                      [f"-DSQ_VARIANT={v}"]))
+    for v in _fp8_variants():          # the same tiles on fp8 codes
+        jobs.append((os.path.join(CSRC, "seglinear_mfma_inst.hip"), os.path.join(OBJ, f"seglinear_mfma_fp8_v{v}.o"),
+                     [f"-DSQ_VARIANT={v}", "-DSQ_FP8=1"]))
     return jobs
 
 

@@ -454,6 +454,8 @@ sq_status sq_quantize_act_fp8(const sq_layer* layer, const void* x, sq_dtype x_d
     tb.dual[s] = layer->dual[s] ? 1 : 0;
     tb.s_pos[s] = layer->s_pos[s];
     tb.s_neg[s] = layer->dual[s] ? layer->s_neg[s] : 1.0f;
+    tb.inv_pos[s] = safe_inv(tb.s_pos[s]);
+    tb.inv_neg[s] = safe_inv(tb.s_neg[s]);
     tb.act[s] = SQ_ACT_NONE;
   }
   hipError_t e = sq::launch_quantize_act_fp8(x, x_dt == SQ_BF16, xq, layer->M, layer->K, tb, reinterpret_cast<hipStream_t>(stream));
@@ -478,7 +480,17 @@ sq_status sq_seglinear_fp8(const sq_layer* layer, const uint8_t* xq, const uint8
   a.K = layer->K;
   a.N = layer->N;
   if (!sq::fp8_gemm_supported(a, tb)) return SQ_ERR_UNSUPPORTED;
-  hipError_t e = sq::launch_seglinear_fp8(a, tb, y_dt == SQ_BF16 ? sq::OUT_BF16 : sq::OUT_F32, reinterpret_cast<hipStream_t>(stream));
+  const sq::OutMode mode = y_dt == SQ_BF16 ? sq::OUT_BF16 : sq::OUT_F32;
+  hipStream_t hs = reinterpret_cast<hipStream_t>(stream);
+  // force_path 0: the plain tile kernel of fp8.hip; otherwise the pipelined tile kernel shared with the int8 path
+  hipError_t e;
+  if (g_force_path == 0) {
+    e = sq::launch_seglinear_fp8(a, tb, mode, hs);
+  } else {
+    const int v = g_gemm_variant >= 0 ? g_gemm_variant : sq::mfma_fp8_pick_variant(a, tb);
+    e = sq::launch_seglinear_mfma_fp8(a, tb, mode, v, hs);
+    if (e == hipErrorInvalidConfiguration) return SQ_ERR_UNSUPPORTED;
+  }
   return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 

@@ -3,32 +3,36 @@
 // place of the int8 ones.  Quantizers: code = e4m3(clip(v / s, +-448)), nearest, ties to even, s = range / 448;
 // Q_dual (Sec. 4.3.2) keeps its two steps, and the two polarity matrices again travel as one byte matrix: X^_+ holds
 // the codes with a clear sign bit, X^_- those with the sign bit set (a zero is stored as +0).  GEMM: the fp8 matrix
-// cores of gfx950 (v_mfma_scale_f32_32x32x64_f8f6f4 with unit scales: 64 bytes of K per instruction, fp32
+// cores of gfx950 (v_mfma_f32_32x32x64_f8f6f4, no block scales: 64 bytes of K per instruction, fp32
 // accumulation), both polarity products fed from the same LDS fragments, the fp32 sums scaled into a running sum at
 // every K-segment boundary (Sec. 4.2.2 item 2), per-column constants and bias in the epilogue.
 #include "sq_kernels.hpp"
 
 namespace sq {
 
-typedef int v8i __attribute__((ext_vector_type(8)));
 constexpr float kFp8Max = 448.0f;
 
-// Nearest E4M3 code of a finite v, ties to the even mantissa, saturating at +-448; a zero result is +0.
-__device__ __forceinline__ uint32_t fp8_encode(float v) {
-  const uint32_t sign = (__float_as_uint(v) >> 24) & 0x80u;
-  const float a = __builtin_fabsf(v);
-  uint32_t code;
-  if (!(a < kFp8Max)) {
-    code = 0x7Eu;
-  } else if (a >= 0.015625f) {                                // normal codes: round the mantissa to 3 bits
-    uint32_t b = __float_as_uint(a);
-    b += 0x7FFFFu + ((b >> 20) & 1u);                          // round half to even at bit 20 (a carry moves into the exponent)
-    b >>= 20;
-    code = (((b >> 3) - 120u) << 3) | (b & 7u);                // exponent re-biased from 127 to 7
-  } else {                                                     // subnormal codes: multiples of 2^-9 (8 is the first normal code)
-    code = (uint32_t)__builtin_rintf(a * 512.0f);
-  }
-  return code == 0u ? 0u : (sign | code);
+// Nearest E4M3 codes of four finite values, ties to the even mantissa, saturating at +-448, zeros stored as +0: the
+// hardware conversion of gfx950 (v_cvt_pk_fp8_f32: OCP E4M3, round to nearest even, subnormals) behind a clip, then the
+// sign bit of every byte whose other seven bits are zero is cleared.
+__device__ __forceinline__ uint32_t fp8_encode4(float q0, float q1, float q2, float q3) {
+  auto clip = [](float q) { return __builtin_fminf(__builtin_fmaxf(q, -kFp8Max), kFp8Max); };
+  int p = __builtin_amdgcn_cvt_pk_fp8_f32(clip(q0), clip(q1), 0, false);
+  p = __builtin_amdgcn_cvt_pk_fp8_f32(clip(q2), clip(q3), p, true);
+  const uint32_t u = (uint32_t)p;
+  const uint32_t nz = ((u & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) & 0x80808080u;     // bit 7 of the bytes with a non-zero magnitude
+  return u & (nz | 0x7F7F7F7Fu);
+}
+__device__ __forceinline__ uint32_t fp8_encode(float v) { return fp8_encode4(v, 0.0f, 0.0f, 0.0f) & 0xFFu; }
+
+// v / s for the encoder without the division: v * (1 / s) is within two units in the last place of the quotient, so it
+// decides the code unless it lies within 16 units of a tie of the 3-bit mantissa (the 2^-9 grid of the subnormal codes is
+// brought under the same test by adding 2^-6).  fp8_near_tie tells; the caller then evaluates the true division, behind
+// a branch that is taken for about one element in 30000.
+__device__ __forceinline__ bool fp8_near_tie(float q) {
+  const float a = __builtin_fabsf(q);
+  const float a2 = a + (a < 0.015625f ? 0.015625f : 0.0f);
+  return ((__float_as_uint(a2) & 0xFFFFFu) - 0x7FFF0u) < 0x20u;
 }
 
 // ---- weight quantizer: one wavefront per (output channel, K-segment) -------------------------------------------------
@@ -91,10 +95,10 @@ __global__ __launch_bounds__(256) void quantize_act_fp8_fast_kernel(const void* 
 #pragma unroll
   for (int l = 0; l < NL; ++l) raw[l] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(x) + ((size_t)NL * c + l));
   const int col = (int)((c % kchunks) * 16u);
-  float sp = tb.s_pos[0], sn = tb.s_neg[0];
+  float sp = tb.s_pos[0], sn = tb.s_neg[0], ip = tb.inv_pos[0], in = tb.inv_neg[0];
   bool dual = tb.dual[0] != 0;
   for (int s = 1; s < tb.S; ++s)
-    if (col >= tb.kseg_off[s]) { sp = tb.s_pos[s]; sn = tb.s_neg[s]; dual = tb.dual[s] != 0; }
+    if (col >= tb.kseg_off[s]) { sp = tb.s_pos[s]; sn = tb.s_neg[s]; ip = tb.inv_pos[s]; in = tb.inv_neg[s]; dual = tb.dual[s] != 0; }
   v4i out;
 #pragma unroll
   for (int g = 0; g < 4; ++g) {
@@ -110,12 +114,23 @@ __global__ __launch_bounds__(256) void quantize_act_fp8_fast_kernel(const void* 
 #pragma unroll
       for (int i = 0; i < 4; ++i) v[i] = __int_as_float(raw[BF16 ? 0 : g][i]);
     }
-    uint32_t pk = 0;
+    float q[4];
+    bool near = false;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const bool ng = dual && (v[i] < 0.0f);
-      pk |= fp8_encode(v[i] / (ng ? sn : sp)) << (8 * i);
+      q[i] = v[i] * (ng ? in : ip);
+      near = near || fp8_near_tie(q[i]);
     }
+    if (__builtin_expect(near, 0)) {
+      asm volatile("" ::: "memory");                       // keeps the divisions behind the branch
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const bool ng = dual && (v[i] < 0.0f);
+        q[i] = v[i] / (ng ? sn : sp);
+      }
+    }
+    const uint32_t pk = fp8_encode4(q[0], q[1], q[2], q[3]);
     out[g] = (int)pk;
   }
   reinterpret_cast<v4i*>(xq)[c] = out;
@@ -124,6 +139,8 @@ __global__ __launch_bounds__(256) void quantize_act_fp8_fast_kernel(const void* 
 hipError_t launch_quantize_act_fp8(const void* x, bool x_is_bf16, uint8_t* xq, int M, int K, const ActTable& tb, hipStream_t st) {
   bool aligned = (K % 16 == 0) && ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(xq)) % 16 == 0);
   for (int s = 0; s <= tb.S; ++s) aligned = aligned && (tb.kseg_off[s] % 16 == 0);
+  for (int s = 0; s < tb.S; ++s)      // the fast kernel multiplies by the reciprocals of the steps: they must be usable
+    aligned = aligned && (tb.inv_pos[s] == tb.inv_pos[s]) && (tb.inv_neg[s] == tb.inv_neg[s]);
   if (aligned) {
     const uint32_t kchunks = (uint32_t)(K / 16), nchunks = (uint32_t)(((size_t)M * K) / 16);
     const unsigned blocks = (nchunks + 255u) / 256u;
@@ -203,7 +220,7 @@ __global__ __launch_bounds__(256) void seglinear_fp8_kernel(const GemmArgs a, co
     f[4] = hi[0]; f[5] = hi[1]; f[6] = hi[2]; f[7] = hi[3];
     return f;
   };
-  constexpr int kUnit = 0x7F7F7F7F;                                       // block scales of 2^0
+  constexpr int kUnit = 0;                       // constant-zero scale operands select the unscaled instruction
   v16f accp[2][2], accn[2][2], fsum[2][2];
 #pragma unroll
   for (int i = 0; i < 2; ++i)

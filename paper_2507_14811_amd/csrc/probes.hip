@@ -8,7 +8,9 @@
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v16f __attribute__((ext_vector_type(16)));
 
 int device_cus() {
   int dev = 0, cus = 256;
@@ -44,6 +46,40 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(const v4i* __restrict__
   if (s == 0x7E57AB1E && sink) sink[0] = s;     // keeps the loop alive; practically never true
 }
 
+// The same loop on the fp8 matrix cores (E4M3 operands of 32 bytes per lane, no block scales, fp32 accumulators).
+__global__ __launch_bounds__(256) void probe_mfma_fp8_kernel(const v4i* __restrict__ codes, const uint32_t nvec,
+                                                             const int iters, int* __restrict__ sink) {
+  const uint32_t gid = blockIdx.x * 256u + threadIdx.x;
+  v8i a[4], b[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const v4i a0 = codes[(gid * 16u + 2 * i) % nvec], a1 = codes[(gid * 16u + 2 * i + 1) % nvec];
+    const v4i b0 = codes[(gid * 16u + 8u + 2 * i) % nvec], b1 = codes[(gid * 16u + 9u + 2 * i) % nvec];
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      // never a NaN code (0x7F / 0xFF): clear mantissa bit 0 of every byte whose low seven bits are all set
+      auto clean = [](int x) { const int m = x & (x >> 1) & (x >> 2) & (x >> 3) & (x >> 4) & (x >> 5) & (x >> 6) & 0x01010101; return x & ~m; };
+      a[i][d] = clean(a0[d]); a[i][4 + d] = clean(a1[d]);
+      b[i][d] = clean(b0[d]); b[i][4 + d] = clean(b1[d]);
+    }
+  }
+  v16f acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc[i] = (v16f)(0.0f);
+#pragma unroll 1
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      acc[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[i & 3], b[(i >> 1) & 3], acc[i], 0, 0, 0, 0, 0, 0);   // zero scale operands: the unscaled instruction
+  }
+  float s = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s += acc[i][v];
+  if (s == 1.2345678e-30f && sink) sink[0] = 1;   // keeps the loop alive; practically never true
+}
+
 __global__ void probe_launch_kernel(int* sink) {
   extern __shared__ char lds[];
   if (sink != nullptr && threadIdx.x == 4096) sink[0] = lds[0];   // never true: the kernel does nothing
@@ -71,6 +107,17 @@ int sqp_mfma(const int8_t* codes, size_t bytes, int iters, double* ops, void* st
   const int cus = device_cus();
   if (ops) *ops = (double)cus * 4.0 * (double)iters * 8.0 * 65536.0;   // 2*32*32*32 per MFMA
   hipLaunchKernelGGL(probe_mfma_kernel, dim3(cus), dim3(256), 0, reinterpret_cast<hipStream_t>(stream),
+                     reinterpret_cast<const v4i*>(codes), (uint32_t)(bytes / 16), iters, (int*)nullptr);
+  return status_of(hipGetLastError());
+}
+
+int sqp_mfma_fp8(const uint8_t* codes, size_t bytes, int iters, double* ops, void* stream) {
+  (void)hipGetLastError();
+  if (codes == nullptr || bytes < 4096 || bytes > 0xFFFFFFFFull || iters < 1 || iters > (1 << 24)) return 1;
+  if (reinterpret_cast<uintptr_t>(codes) % 16 != 0) return 1;
+  const int cus = device_cus();
+  if (ops) *ops = (double)cus * 4.0 * (double)iters * 8.0 * 131072.0;   // 2*32*32*64 per MFMA
+  hipLaunchKernelGGL(probe_mfma_fp8_kernel, dim3(cus), dim3(256), 0, reinterpret_cast<hipStream_t>(stream),
                      reinterpret_cast<const v4i*>(codes), (uint32_t)(bytes / 16), iters, (int*)nullptr);
   return status_of(hipGetLastError());
 }

@@ -12,8 +12,13 @@ template <int V> static constexpr MfmaVariantInfo info_of() {
   using P = MfmaVariant<V>;
   return {P::BM, P::BN, P::SK, P::MINB, P::DUAL_OK, P::MULTI_OK, P::MULTI_DUAL_OK, P::SHARE_OK, P::TOK_OK};
 }
+template <int V> static constexpr LaunchFn fp8_launcher() {
+  if constexpr (kMfmaVariantHasFp8[V]) return &launch_mfma_variant<V, true>;
+  else return nullptr;
+}
 template <int... V> struct VariantTables {
   static constexpr LaunchFn launch[sizeof...(V)] = {&launch_mfma_variant<V>...};
+  static constexpr LaunchFn launch_fp8[sizeof...(V)] = {fp8_launcher<V>()...};
   static constexpr MfmaVariantInfo info[sizeof...(V)] = {info_of<V>()...};
 };
 template <int... V> static constexpr VariantTables<V...> tables_of(std::integer_sequence<int, V...>) { return {}; }
@@ -100,10 +105,49 @@ int mfma_pick_variant(const GemmArgs& a, const GemmTable& tb, OutMode) {
   return best;
 }
 
+// fp8 codes: the tile configurations built for them (128-byte stages, static steps), same fill-times-efficiency choice
+// (relative efficiencies measured on MI355X: 8500 x 1536 x 4608 single-path and dual, 4608 x 15360 x 3072 dual with two
+// K-segments, 2048 x 4608 x 1152 dual)
+static const float kEffFp8Single[kNumMfmaVariants] = {0.76f, 0.68f, 0.0f, 0.52f, 1.00f, 0.83f, 0.0f, 0.0f, 0.87f};
+static const float kEffFp8Dual[kNumMfmaVariants] = {0.96f, 0.80f, 0.0f, 0.69f, 0.0f, 0.83f, 0.0f, 0.0f, 1.00f};
+static bool fp8_variant_ok(int v, bool dual, bool multi, bool share, int kalign) {
+  return kalign == 128 && variant_ok(v, dual, multi, share, kalign, false) && kMfmaVariantHasFp8[v];
+}
+int mfma_fp8_pick_variant(const GemmArgs& a, const GemmTable& tb) {
+  bool dual, multi, share;
+  layer_flags(tb, dual, multi, share);
+  const int cus = device_cus();
+  const float* eff = dual ? kEffFp8Dual : kEffFp8Single;
+  int best = -1;
+  float best_score = -1.0f;
+  for (int v = 0; v < kNumMfmaVariants; ++v) {
+    if (!fp8_variant_ok(v, dual, multi, share, k_alignment(a, tb))) continue;
+    const MfmaVariantInfo i = variant_info(v);
+    const long tiles = (long)((a.M + i.BM - 1) / i.BM) * ((a.N + i.BN - 1) / i.BN);
+    const long slots = (long)cus * i.MINB;
+    const long rounds = (tiles + slots - 1) / slots;
+    const float score = (float)((double)a.M * a.N / ((double)rounds * slots * i.BM * i.BN)) * eff[v];
+    if (score > best_score) { best_score = score; best = v; }
+  }
+  return best;
+}
+
+static hipError_t launch_tiles(GemmArgs a, const GemmTable& tb_in, OutMode mode, int variant, bool fp8, hipStream_t st);
+
 hipError_t launch_seglinear_mfma(GemmArgs a, const GemmTable& tb_in, OutMode mode, int variant, hipStream_t st) {
+  return launch_tiles(a, tb_in, mode, variant, false, st);
+}
+hipError_t launch_seglinear_mfma_fp8(GemmArgs a, const GemmTable& tb_in, OutMode mode, int variant, hipStream_t st) {
+  if (a.tok_steps != nullptr || mode == OUT_DEBUG_ACC) return hipErrorInvalidConfiguration;
+  return launch_tiles(a, tb_in, mode, variant, true, st);
+}
+
+static hipError_t launch_tiles(GemmArgs a, const GemmTable& tb_in, OutMode mode, int variant, bool fp8, hipStream_t st) {
   bool dual, multi, share;
   layer_flags(tb_in, dual, multi, share);
-  if (!variant_ok(variant, dual, multi, share, k_alignment(a, tb_in), a.tok_steps != nullptr)) return hipErrorInvalidConfiguration;
+  if (fp8 ? !fp8_variant_ok(variant, dual, multi, share, k_alignment(a, tb_in))
+          : !variant_ok(variant, dual, multi, share, k_alignment(a, tb_in), a.tok_steps != nullptr))
+    return hipErrorInvalidConfiguration;
   const MfmaVariantInfo i = variant_info(variant);
   GemmTable tb = tb_in;
   share = share && i.share_ok;        // prefer the register-sharing mode wherever the tile supports it
@@ -122,7 +166,7 @@ hipError_t launch_seglinear_mfma(GemmArgs a, const GemmTable& tb_in, OutMode mod
   const long slots = (long)device_cus() * i.MINB;
   const long tiles = (long)a.tiles_m * a.tiles_n;
   a.num_wg = (int)(tiles < slots ? tiles : slots);
-  return Tables::launch[variant](a, tb, mode, dual, multi, share, st);
+  return (fp8 ? Tables::launch_fp8[variant] : Tables::launch[variant])(a, tb, mode, dual, multi, share, st);
 }
 
 }  // namespace sq

@@ -73,7 +73,7 @@ __device__ __forceinline__ void wait_vmcnt(int n) {
 
 #define SQ_LDS(p) ((__attribute__((address_space(3))) char*)(p))
 
-template <int BM, int BN, int WM, int WN, int NSTAGE, int SK, bool DUAL, bool MULTI, bool SHARE>
+template <int BM, int BN, int WM, int WN, int NSTAGE, int SK, bool DUAL, bool MULTI, bool SHARE, bool FP8 = false>
 struct MfmaCfg {
   static constexpr int NW = WM * WN;
   static constexpr int THREADS = NW * 64;
@@ -84,7 +84,8 @@ struct MfmaCfg {
   static constexpr int RPL = 1024 / SK;            // rows covered by one direct-load instruction
   static constexpr int GA = BM / RPL / NW;         // load instructions per wave and stage
   static constexpr int GB = BN / RPL / NW;
-  static constexpr int SUB = SK / 32;              // 32-byte MFMA k-steps per stage
+  static constexpr int FW = FP8 ? 8 : 4;           // dwords of K per lane and MFMA: int8 32x32x32 / fp8 32x32x64
+  static constexpr int SUB = SK / (8 * FW);        // MFMA k-steps per stage (32 bytes of K each, 64 for fp8)
   static constexpr int CPR = SK / 16;              // 16-byte chunks per row
   static constexpr int LDS_BYTES = NSTAGE * STAGE;
   static constexpr int LT = GA + GB;               // direct-load slots of one stage: X^ groups, W^ groups
@@ -106,16 +107,28 @@ __device__ __forceinline__ void split_polarity(const int x, int& pos, int& neg) 
   pos = x ^ neg;
 }
 
+// Value of an accumulator register: an exact int32 sum, or (fp8 codes) the bits of an fp32 sum.
+template <bool FP8> __device__ __forceinline__ float acc_value(int bits) {
+  if constexpr (FP8) return __int_as_float(bits);
+  else return (float)bits;
+}
+
 template <int SK> __device__ __forceinline__ int row_swizzle(int row) {
   return SK == 128 ? ((row >> 1) & 7) : ((row >> 2) & 3);
 }
 
 // TOK: dynamic per-token activation steps (App. B, 4-bit settings): the flushes take s_+ / s_- of every lane's own token
 // rows from a.tok_steps [2][M][S] instead of the layer's static steps.
-template <int BM, int BN, int WM, int WN, int NSTAGE, int SK, int MINB, bool DUAL, bool MULTI, bool SHARE, bool TOK = false>
+// FP8: the codes are OCP E4M3 bytes and the products run on v_mfma_f32_32x32x64_f8f6f4 (no block scales)
+// (64 bytes of K per instruction: a lane's operand is two neighbouring 16-byte chunks); the sums are fp32, kept as bits
+// in the same accumulator registers; X^_- holds the codes with the sign bit set.
+template <int BM, int BN, int WM, int WN, int NSTAGE, int SK, int MINB, bool DUAL, bool MULTI, bool SHARE, bool TOK = false,
+          bool FP8 = false>
 __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(const GemmArgs a, const GemmTable tb,
                                                                          const int mode) {
-  using C = MfmaCfg<BM, BN, WM, WN, NSTAGE, SK, DUAL, MULTI, SHARE>;
+  using C = MfmaCfg<BM, BN, WM, WN, NSTAGE, SK, DUAL, MULTI, SHARE, FP8>;
+  constexpr int FW = C::FW, CH = FW / 4;      // dwords / 16-byte chunks of a lane's operand
+  using vfrag = std::conditional_t<FP8, v8i, v4i>;
   constexpr bool FSUM = MULTI && !SHARE;      // a separate fp32 running-sum register set
   constexpr int IM = C::IM, JN = C::JN, GA = C::GA, GB = C::GB, STAGE = C::STAGE, RPL = C::RPL, SUB = C::SUB;
   constexpr int KSH = SK == 128 ? 7 : 6;
@@ -181,7 +194,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
   const int frow = lane & 31, fsw = row_swizzle<SK>(frow), fhi = lane >> 5;
   int foff[SUB];
 #pragma unroll
-  for (int h = 0; h < SUB; ++h) foff[h] = frow * SK + (((2 * h + fhi) ^ fsw) << 4);
+  for (int h = 0; h < SUB; ++h) foff[h] = frow * SK + (((2 * CH * h + CH * fhi) ^ fsw) << 4);   // fp8: second chunk at this ^ 16
   const char* fragA = smem + (wm * C::TM) * SK;
   const char* fragB = smem + C::AROWS * SK + (wn * C::TN) * SK;
 
@@ -271,19 +284,39 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
   };
 
   // ---- fragments: two register sets, the one being multiplied and the one being fetched ----------------
-  v4i bfr[2][JN], afr[2][IM], nfr[2][DUAL ? IM : 1];
+  vfrag bfr[2][JN], afr[2][IM], nfr[2][DUAL ? IM : 1];
+  auto read_chunk = [&](vfrag& f, const int c, const char* p) __attribute__((always_inline)) {   // 16 bytes into dwords 4c .. 4c+3
+    const v4i t = *reinterpret_cast<const v4i*>(p);
+    if constexpr (FP8) {
+#pragma unroll
+      for (int d = 0; d < 4; ++d) f[4 * c + d] = t[d];
+    } else {
+      f = t;
+    }
+  };
   auto load_frags = [&](const int set, const int fo) __attribute__((always_inline)) {
+    if constexpr (FP8) {
 #pragma unroll
-    for (int i = 0; i < IM; ++i) afr[set][i] = *reinterpret_cast<const v4i*>(fragA + i * (32 * SK) + fo);
+      for (int i = 0; i < IM; ++i)
 #pragma unroll
-    for (int j = 0; j < JN; ++j) bfr[set][j] = *reinterpret_cast<const v4i*>(fragB + j * (32 * SK) + fo);
+        for (int c = 0; c < CH; ++c) read_chunk(afr[set][i], c, fragA + i * (32 * SK) + (fo ^ (16 * c)));
+#pragma unroll
+      for (int j = 0; j < JN; ++j)
+#pragma unroll
+        for (int c = 0; c < CH; ++c) read_chunk(bfr[set][j], c, fragB + j * (32 * SK) + (fo ^ (16 * c)));
+    } else {
+#pragma unroll
+      for (int i = 0; i < IM; ++i) afr[set][i] = *reinterpret_cast<const v4i*>(fragA + i * (32 * SK) + fo);
+#pragma unroll
+      for (int j = 0; j < JN; ++j) bfr[set][j] = *reinterpret_cast<const v4i*>(fragB + j * (32 * SK) + fo);
+    }
   };
   // polarity separation of a fetched X^ fragment set: afr <- X^_+ codes, nfr <- X^_- codes
   auto split_frags = [&](const int set) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < IM; ++i)
 #pragma unroll
-      for (int d = 0; d < 4; ++d) {
+      for (int d = 0; d < FW; ++d) {
         int pos, neg;
         split_polarity(afr[set][i][d], pos, neg);
         afr[set][i][d] = pos;
@@ -307,11 +340,11 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
     constexpr int GRP = decltype(grp_tag)::value;
     const int nxt = cur ^ 1;
     constexpr int NM = IM * JN * (DL ? 2 : 1);               // MFMAs of this k-step
-    constexpr int NR = PF ? IM + JN : 0;                     // LDS reads (16 bytes per lane each)
+    constexpr int NR = PF ? (IM + JN) * CH : 0;              // LDS reads (16 bytes per lane each)
     constexpr int RPS = NR > NM ? (NR + NM - 1) / NM : 1;    // LDS reads per slot (1 unless the tile is tiny)
     constexpr int RSTEP = NM * RPS >= 2 * NR ? 2 : 1;        // MFMA slots between reads
-    constexpr int ND = (PF && DL) ? IM * 4 : 0;              // dwords to separate
-    constexpr int QV_RAW = ((IM - 1) / RPS) * RSTEP + 6;     // first slot with separation work
+    constexpr int ND = (PF && DL) ? IM * FW : 0;             // dwords to separate
+    constexpr int QV_RAW = ((IM * CH - 1) / RPS) * RSTEP + (FP8 ? 3 : 6);   // first slot with separation work
     constexpr int QV0 = QV_RAW < NM / 2 ? QV_RAW : NM / 2;
     constexpr int DPS = ND ? (ND + (NM - QV0) - 1) / (NM - QV0) : 0;   // dwords per slot
     constexpr int NG = GRP >= 0 ? ((GRP + 1) * LT + SUB - 1) / SUB - (GRP * LT + SUB - 1) / SUB : 0;   // loads of the group
@@ -320,30 +353,47 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
       {
         const int idx = DL ? (q >> 1) : q;
         const int i = idx / JN, j = idx % JN;
+        if constexpr (FP8) {
+          constexpr int kUnit = 0;                           // constant-zero scale operands select the unscaled instruction
+          if (!DL || (q & 1) == 0)
+            accp[i][j] = __builtin_bit_cast(v16i, __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                bfr[cur][j], afr[cur][i], __builtin_bit_cast(v16f, accp[i][j]), 0, 0, 0, kUnit, 0, kUnit));
+          else
+            accn[DUAL ? i : 0][DUAL ? j : 0] = __builtin_bit_cast(v16i, __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                bfr[cur][j], nfr[cur][DUAL ? i : 0], __builtin_bit_cast(v16f, accn[DUAL ? i : 0][DUAL ? j : 0]), 0, 0, 0, kUnit,
+                0, kUnit));
+        } else {
         if (!DL || (q & 1) == 0)
           accp[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bfr[cur][j], afr[cur][i], accp[i][j], 0, 0, 0);
         else
           accn[DUAL ? i : 0][DUAL ? j : 0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
               bfr[cur][j], nfr[cur][DUAL ? i : 0], accn[DUAL ? i : 0][DUAL ? j : 0], 0, 0, 0);
+        }
       }
       __builtin_amdgcn_sched_barrier(0);
       if (PF) {
 #pragma unroll
         for (int r = 0; r < NR; ++r)                         // read r goes out in slot (r / RPS) * RSTEP
           if ((r / RPS) * RSTEP == q) {
+            if constexpr (FP8) {
+              const int f = r / CH, c = r % CH;              // fragment and 16-byte half
+              if (f < IM) read_chunk(afr[nxt][f < IM ? f : 0], c, fragA + (f < IM ? f : 0) * (32 * SK) + (fo_next ^ (16 * c)));
+              else read_chunk(bfr[nxt][f >= IM ? f - IM : 0], c, fragB + (f >= IM ? f - IM : 0) * (32 * SK) + (fo_next ^ (16 * c)));
+            } else {
             if (r < IM) afr[nxt][r < IM ? r : 0] = *reinterpret_cast<const v4i*>(fragA + (r < IM ? r : 0) * (32 * SK) + fo_next);
             else bfr[nxt][r >= IM ? r - IM : 0] = *reinterpret_cast<const v4i*>(fragB + (r >= IM ? r - IM : 0) * (32 * SK) + fo_next);
+            }
           }
       }
       if (ND && q >= QV0) {
 #pragma unroll
         for (int t = 0; t < DPS; ++t) {
-          const int w = (q - QV0) * DPS + t;                 // dword index: fragment w / 4, element w % 4
+          const int w = (q - QV0) * DPS + t;                 // dword index: fragment w / FW, element w % FW
           if (w < ND) {
             int pos, neg;
-            split_polarity(afr[nxt][w / 4][w % 4], pos, neg);
-            afr[nxt][w / 4][w % 4] = pos;
-            nfr[nxt][DUAL ? w / 4 : 0][w % 4] = neg;
+            split_polarity(afr[nxt][w / FW][w % FW], pos, neg);
+            afr[nxt][w / FW][w % FW] = pos;
+            nfr[nxt][DUAL ? w / FW : 0][w % FW] = neg;
           }
         }
       }
@@ -630,11 +680,11 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
             const float cpos = cw[v] * spr[i], cneg = cw[v] * snr[i];
             if (SHARE) {
               const int old = accn[DUAL ? i : 0][DUAL ? j : 0][v];
-              const float prev = first ? cneg * (float)old : __int_as_float(old);
-              accn[DUAL ? i : 0][DUAL ? j : 0][v] = __float_as_int(prev + cpos * (float)accp[i][j][v]);
+              const float prev = first ? cneg * acc_value<FP8>(old) : __int_as_float(old);
+              accn[DUAL ? i : 0][DUAL ? j : 0][v] = __float_as_int(prev + cpos * acc_value<FP8>(accp[i][j][v]));
             } else {
-              float t = cpos * (float)accp[i][j][v];
-              if (DUAL) t += cneg * (float)accn[DUAL ? i : 0][DUAL ? j : 0][v];
+              float t = cpos * acc_value<FP8>(accp[i][j][v]);
+              if (DUAL) t += cneg * acc_value<FP8>(accn[DUAL ? i : 0][DUAL ? j : 0][v]);
               fsum[FSUM ? i : 0][FSUM ? j : 0][v] += t;
             }
           }
@@ -688,9 +738,9 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
         float t[16];
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          float u = (cw[v] * spr[i]) * (float)accp[i][j][v];
+          float u = (cw[v] * spr[i]) * acc_value<FP8>(accp[i][j][v]);
           if (SHARE) u += __int_as_float(accn[DUAL ? i : 0][DUAL ? j : 0][v]);   // running sum (never the first segment)
-          else if (DUAL) u += (cw[v] * snr[i]) * (float)accn[DUAL ? i : 0][DUAL ? j : 0][v];
+          else if (DUAL) u += (cw[v] * snr[i]) * acc_value<FP8>(accn[DUAL ? i : 0][DUAL ? j : 0][v]);
           if (FSUM) u += fsum[FSUM ? i : 0][FSUM ? j : 0][v];
           t[v] = u + bs[v];
         }

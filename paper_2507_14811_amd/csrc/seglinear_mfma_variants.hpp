@@ -27,10 +27,12 @@ SQ_DEF_VARIANT(7, 64, 192, 2, 2, 4, 128, 1, true, true, true, true)     // wave 
 SQ_DEF_VARIANT(8, 128, 192, 2, 2, 3, 128, 1, true, true, true, true)    // wave tile 64 x 96
 #undef SQ_DEF_VARIANT
 constexpr int kNumMfmaVariants = 9;
+// tile configurations also built for fp8 codes (128-byte stages only); listed again in the build script
+constexpr bool kMfmaVariantHasFp8[kNumMfmaVariants] = {true, true, false, true, true, true, false, false, true};
 
 struct MfmaVariantInfo { int BM, BN, SK, MINB; bool dual_ok, multi_ok, multi_dual_ok, share_ok, tok_ok; };
 
-template <int V>
+template <int V, bool FP8 = false>
 hipError_t launch_mfma_variant(const GemmArgs& a, const GemmTable& tb, int mode, bool dual, bool multi, bool share,
                                hipStream_t st);
 

@@ -85,6 +85,9 @@ void mfma_set_group_m(int g);   // diagnostics: panel height of the tile order (
 bool mfma_supported(const GemmArgs& a, const GemmTable& tb);
 int mfma_pick_variant(const GemmArgs& a, const GemmTable& tb, OutMode mode);
 hipError_t launch_seglinear_mfma(GemmArgs a, const GemmTable& tb, OutMode mode, int variant, hipStream_t st);
+// the same tile kernel on fp8 (E4M3) codes: K and every K-segment boundary % 128 == 0, static steps
+int mfma_fp8_pick_variant(const GemmArgs& a, const GemmTable& tb);
+hipError_t launch_seglinear_mfma_fp8(GemmArgs a, const GemmTable& tb, OutMode mode, int variant, hipStream_t st);
 
 // seglinear_skinny.hip : M <= 64, weight-streaming kernel.  Same alignment needs as the MFMA kernel.
 bool skinny_supported(const GemmArgs& a, const GemmTable& tb);

@@ -8,7 +8,7 @@ import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsegquant_probes.so")
-EXPORTS = ("sqp_mfma", "sqp_launch", "sqp_roundtrip", "sqp_copy")
+EXPORTS = ("sqp_mfma", "sqp_mfma_fp8", "sqp_launch", "sqp_roundtrip", "sqp_copy")
 _lib = None
 
 
@@ -23,6 +23,7 @@ def load_library() -> C.CDLL:
     lib = C.CDLL(LIB_PATH)
     vp, i32 = C.c_void_p, C.c_int
     lib.sqp_mfma.argtypes = [vp, C.c_size_t, i32, C.POINTER(C.c_double), vp]
+    lib.sqp_mfma_fp8.argtypes = [vp, C.c_size_t, i32, C.POINTER(C.c_double), vp]
     lib.sqp_launch.argtypes = [i32, i32, i32, vp]
     lib.sqp_roundtrip.argtypes = [vp, vp, i32, i32, vp]
     lib.sqp_copy.argtypes = [vp, vp, C.c_size_t, vp]
@@ -47,6 +48,13 @@ def sqp_mfma(codes, iters: int, stream=None) -> float:
     """Launches the register-only int8 MFMA loop on int8 device tensor `codes`; returns the ops of one launch."""
     ops = C.c_double(0.0)
     _check(load_library().sqp_mfma(codes.data_ptr(), codes.numel(), int(iters), C.byref(ops), _stream(stream)), "sqp_mfma")
+    return float(ops.value)
+
+
+def sqp_mfma_fp8(codes, iters: int, stream=None) -> float:
+    """The same loop on the fp8 matrix cores, `codes` read as E4M3 bytes; returns the flops of one launch."""
+    ops = C.c_double(0.0)
+    _check(load_library().sqp_mfma_fp8(codes.data_ptr(), codes.numel(), int(iters), C.byref(ops), _stream(stream)), "sqp_mfma_fp8")
     return float(ops.value)
 
 

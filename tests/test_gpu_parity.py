@@ -875,16 +875,27 @@ def test_seglinear_fp8(oracle, case):
     xp, xn = _split_fp8(w, xq.cpu().numpy())
     assert np.array_equal(xp, _plus_zero(r_xp)) and np.array_equal(xn, _plus_zero(r_xn))
     ref, mag = oracle.seglinear_fp8(r_xp, r_xn, r_wq, w.kseg_off, w.nseg_off, w.dual, w.s_pos, w.s_neg, r_ws, w.seg_scale, w.bias)
-    for ydt in ("f32", "bf16"):
-        y = torch.full((M, N), float("nan"), dtype=torch.bfloat16 if ydt == "bf16" else torch.float32, device=g.DEV)
-        sq.sq_seglinear_fp8(gl.layer, xq, wq, gl.wscale, gl.bias, y)
-        torch.cuda.synchronize()
-        got = y.float().cpu().numpy().astype(np.float64)
-        assert not np.isnan(got).any()
-        tol = _fp8_tol(K, mag, ref, ydt)
-        assert (np.abs(got - ref) <= tol).all(), float((np.abs(got - ref) / tol).max())
-        if ydt == "f32":          # the typical error is far inside the bound
-            assert np.abs(got - ref).max() <= 2e-5 * np.abs(ref).max()
+    # automatic choice, the plain tile kernel, and every tile configuration of the pipelined kernel built for fp8 codes
+    ran = 0
+    for path, variant in [(-1, -1), (0, -1)] + [(1, v) for v in range(9)]:
+        sq.sq_tuning_set("force_path", path)
+        sq.sq_tuning_set("gemm_variant", variant)
+        for ydt in ("f32", "bf16"):
+            y = torch.full((M, N), float("nan"), dtype=torch.bfloat16 if ydt == "bf16" else torch.float32, device=g.DEV)
+            try:
+                sq.sq_seglinear_fp8(gl.layer, xq, wq, gl.wscale, gl.bias, y)
+            except sq.SqError:
+                assert variant >= 0           # a tile configuration that does not serve this layer class
+                continue
+            torch.cuda.synchronize()
+            ran += 1
+            got = y.float().cpu().numpy().astype(np.float64)
+            assert not np.isnan(got).any(), (path, variant)
+            tol = _fp8_tol(K, mag, ref, ydt)
+            assert (np.abs(got - ref) <= tol).all(), (path, variant, float((np.abs(got - ref) / tol).max()))
+            if ydt == "f32":          # the typical error is far inside the bound
+                assert np.abs(got - ref).max() <= 2e-5 * np.abs(ref).max()
+    assert ran >= 8
     # the variant does its job: close to the unquantized layer (3 mantissa bits: a few percent)
     if w.seg_scale is None:
         full = w.x.astype(np.float64) @ w.w.astype(np.float64).T + (0.0 if w.bias is None else w.bias)
