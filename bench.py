@@ -25,6 +25,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 INT8_MFMA_PEAK_TOPS = 5033.2   # 256 CU x 2.4 GHz x 8192 int8 ops/clk/CU (dense)
+FP8_MFMA_PEAK_TFLOPS = 5033.2  # the same rate for dense fp8 operands (v_mfma_f32_32x32x64_f8f6f4)
 HBM_PEAK_GBS = 8000.0
 PREROLL_MS = 80.0              # untimed load before the warm-up steps, so that the device clocks have settled
 USE_GRAPHS = True              # --no-graph: time small kernels with plain launches (for runs under rocprofv3)
@@ -560,6 +561,62 @@ def measure_optimizer_side(name="cfg5"):
                                        "matrix cores): bytes = X once, y_q read as fp32, y written as bf16"}}
 
 
+def measure_fp8(names=("cfg5", "cfg4", "cfg2")):
+    """The 8-bit floating-point variant (E4M3 codes, fp8 matrix cores) on the named layers: activation quantizer and
+    product, timed GPU-side like the int8 path, against the fp8 matrix-core peak and the register-only fp8 MFMA probe
+    fed with the layer's own codes."""
+    import torch
+
+    import paper_2507_14811_amd as sq
+    from paper_2507_14811_amd import probes
+
+    out = {}
+    for name in names:
+        s = _setup(name)
+        w = s["w"]
+        dev = "cuda:0"
+        sp = (w.s_pos * np.float32(127.0 / 448.0)).astype(np.float32)      # the same calibrated ranges over 448
+        sn = (w.s_neg * np.float32(127.0 / 448.0)).astype(np.float32)
+        layer = sq.Layer(w.M, w.K, w.N, w.kseg_off, w.nseg_off, w.dual, sp, sn, w.seg_scale)
+        xq = torch.empty((w.M, w.K), dtype=torch.uint8, device=dev)
+        wq = torch.empty((w.N, w.K), dtype=torch.uint8, device=dev)
+        sq.sq_quantize_weight_fp8(layer, s["wt"], wq, s["wscale"])
+        quant = lambda: sq.sq_quantize_act_fp8(layer, s["x"], xq)
+        gemm = lambda: sq.sq_seglinear_fp8(layer, xq, wq, s["wscale"], None, s["y"])
+        quant()
+        for _ in range(10):
+            gemm()
+        torch.cuda.synchronize()
+        t_q = _gpu_side_ms([quant], launches=50)
+        t_g = _gpu_side_ms([gemm], launches=50)
+        t_step = _gpu_side_ms([quant, gemm], launches=50) * 2        # per pair
+        flops = float(w.int8_ops)                                     # the same multiply-adds, both polarity products
+        r = {"M": int(w.M), "K": int(w.K), "N": int(w.N), "ms_quantize_act_fp8": round(t_q, 5), "ms_seglinear_fp8": round(t_g, 5),
+             "ms_step": round(t_step, 5), "tflops": round(flops / (t_g * 1e-3) / 1e12, 1),
+             "frac_fp8_mfma_peak": round(flops / (t_g * 1e-3) / 1e12 / FP8_MFMA_PEAK_TFLOPS, 4),
+             "step_tflops": round(flops / (t_step * 1e-3) / 1e12, 1),
+             "quant_gbs": round(w.quantize_act_bytes() / (t_q * 1e-3) / 1e9, 1),
+             "quant_frac_hbm_peak": round(w.quantize_act_bytes() / (t_q * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        if name == names[0]:
+            codes = xq.view(-1)[: 16 << 20]
+            for _ in range(3):
+                probes.sqp_mfma_fp8(codes, 10000)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            ops = probes.sqp_mfma_fp8(codes, 10000)
+            e1.record()
+            torch.cuda.synchronize()
+            ceil = ops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+            r["mfma_fp8_tflops_layer_like_operands"] = round(ceil, 1)
+            r["frac_of_measured_fp8_mfma_ceiling"] = round(flops / (t_g * 1e-3) / 1e12 / ceil, 4)
+        out[name] = r
+        del s, xq, wq
+    return {"peak_tflops": FP8_MFMA_PEAK_TFLOPS, "workloads": out,
+            "note": "OCP E4M3 codes, steps range / 448, products on v_mfma_f32_32x32x64_f8f6f4 with fp32 sums; flops count both "
+                    "polarity products of the dual K-segments like the int8 figure"}
+
+
 def measured_ceilings(head_setup_codes, dual_cols=None):
     """Ceilings and floors measured on this device with the probe library, reported next to the datasheet peaks:
     the sustained int8 MFMA rate of a register-only loop (all-zero operands; operands distributed like the headline
@@ -708,6 +765,7 @@ def main():
     w4 = measure_w4() if "cfg3x28" in args.others.split(",") else None
     geglu = measure_geglu()
     optimizer_side = measure_optimizer_side(args.config)
+    fp8 = measure_fp8((args.config,) + tuple(n for n in ("cfg4", "cfg2") if n in args.others.split(",") and n != args.config))
     others = {}
     for name in [n for n in args.others.split(",") if n and n != args.config]:
         sq.sq_tuning_set("gemm_variant", -1)
@@ -801,6 +859,7 @@ def main():
         "grouped_skinny": grouped,
         "w4_skinny": w4,
         "optimizer_side": optimizer_side,
+        "fp8_variant": fp8,
         "measured_ceilings": ceilings,
     }
     if not args.no_cpu_baseline:

@@ -87,18 +87,25 @@ __global__ __launch_bounds__(256) void quantize_act_fp8_kernel(const void* __res
 // aligned shapes: 16 consecutive elements of one row and K-segment per thread (16-byte loads and stores)
 template <bool BF16>
 __global__ __launch_bounds__(256) void quantize_act_fp8_fast_kernel(const void* __restrict__ x, uint8_t* __restrict__ xq,
-                                                                    uint32_t nchunks, uint32_t kchunks, const ActTable tb) {
+                                                                    uint32_t nchunks, uint32_t kchunks, uint32_t kmagic,
+                                                                    const ActTable tb) {
   const uint32_t c = blockIdx.x * 256u + threadIdx.x;
   if (c >= nchunks) return;
   constexpr int NL = BF16 ? 2 : 4;
   v4i raw[NL];
 #pragma unroll
   for (int l = 0; l < NL; ++l) raw[l] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(x) + ((size_t)NL * c + l));
-  const int col = (int)((c % kchunks) * 16u);
   float sp = tb.s_pos[0], sn = tb.s_neg[0], ip = tb.inv_pos[0], in = tb.inv_neg[0];
   bool dual = tb.dual[0] != 0;
-  for (int s = 1; s < tb.S; ++s)
-    if (col >= tb.kseg_off[s]) { sp = tb.s_pos[s]; sn = tb.s_neg[s]; ip = tb.inv_pos[s]; in = tb.inv_neg[s]; dual = tb.dual[s] != 0; }
+  if (tb.S > 1) {
+    // column of this chunk: c mod kchunks via a reciprocal multiply (the quotient is exact or one too small)
+    const uint32_t qc = __umulhi(c, kmagic);
+    uint32_t r = c - qc * kchunks;
+    if (r >= kchunks) r -= kchunks;
+    const int col = (int)(r * 16u);
+    for (int s = 1; s < tb.S; ++s)
+      if (col >= tb.kseg_off[s]) { sp = tb.s_pos[s]; sn = tb.s_neg[s]; ip = tb.inv_pos[s]; in = tb.inv_neg[s]; dual = tb.dual[s] != 0; }
+  }
   v4i out;
 #pragma unroll
   for (int g = 0; g < 4; ++g) {
@@ -144,8 +151,9 @@ hipError_t launch_quantize_act_fp8(const void* x, bool x_is_bf16, uint8_t* xq, i
   if (aligned) {
     const uint32_t kchunks = (uint32_t)(K / 16), nchunks = (uint32_t)(((size_t)M * K) / 16);
     const unsigned blocks = (nchunks + 255u) / 256u;
-    if (x_is_bf16) hipLaunchKernelGGL(quantize_act_fp8_fast_kernel<true>, dim3(blocks), dim3(256), 0, st, x, xq, nchunks, kchunks, tb);
-    else hipLaunchKernelGGL(quantize_act_fp8_fast_kernel<false>, dim3(blocks), dim3(256), 0, st, x, xq, nchunks, kchunks, tb);
+    const uint32_t kmagic = (uint32_t)(0x100000000ull / kchunks > 0xFFFFFFFFull ? 0xFFFFFFFFull : 0x100000000ull / kchunks);
+    if (x_is_bf16) hipLaunchKernelGGL(quantize_act_fp8_fast_kernel<true>, dim3(blocks), dim3(256), 0, st, x, xq, nchunks, kchunks, kmagic, tb);
+    else hipLaunchKernelGGL(quantize_act_fp8_fast_kernel<false>, dim3(blocks), dim3(256), 0, st, x, xq, nchunks, kchunks, kmagic, tb);
   } else {
     const size_t total = (size_t)M * K;
     const unsigned blocks = (unsigned)((total + 255) / 256 > 65536 ? 65536 : (total + 255) / 256);
