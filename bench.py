@@ -720,6 +720,8 @@ def main():
     ap.add_argument("--variant", type=int, default=-1, help="force an MFMA tile variant (diagnostics)")
     ap.add_argument("--no-graph", action="store_true", help="no HIP graphs: small kernels are timed with plain launches "
                     "(host launch cost included); for runs under rocprofv3")
+    ap.add_argument("--fp8-only", action="store_true", help="time only the 8-bit floating-point variant and print its JSON object "
+                    "(the command of the fp8 profile passes)")
     ap.add_argument("--only", default="", help="time this one workload (hot path only) and print a short JSON line: "
                     "one workload per profiler pass")
     args = ap.parse_args()
@@ -745,6 +747,10 @@ def main():
     # the reading of FETCH_SIZE / WRITE_SIZE for a known traffic, which scales the kernels' readings.
     from paper_2507_14811_amd import probes
 
+    if args.fp8_only:
+        probes.sqp_copy(torch.zeros(256 << 20, dtype=torch.int8, device="cuda:0"), torch.empty(256 << 20, dtype=torch.int8, device="cuda:0"))
+        print(json.dumps(measure_fp8((args.config,) + tuple(n for n in ("cfg4", "cfg2") if n in args.others.split(",") and n != args.config))))
+        return
     if args.only:
         r = measure(args.only, args.steps, args.warmup, hot_only=True)
         print(json.dumps({"workload": r["name"], "ms_quantize_act": round(r["ms_quant"], 5), "ms_seglinear": round(r["ms_gemm_b2b"], 5),
