@@ -393,9 +393,10 @@ sq_status sq_seglinear_dynamic(const sq_layer* layer, const int8_t* xq, const fl
  * unquantized activations and is added to the quantized product before the output is rounded:
  *   y[m][n] = y_q[m][n] + sum_j T[m][j] Lu[n][j],     T[m][j] = sum_k X[m][k] Ld[j][k].
  * Arithmetic: X, Ld, Lu are bf16 (fp32 X is rounded to bf16 on entry: the branch is a 16-bit one); T is accumulated
- * and kept in fp32 (bf16 matrix cores, K cut into slices whose partial sums are added in ascending order); the second
- * product runs on the fp32 matrix cores (fp32 operands and accumulation), then the addition and one rounding to y_dt.
- * Deterministic.
+ * and kept in fp32 (bf16 matrix cores, K cut into slices whose partial sums are added in ascending order); for the second
+ * product every fp32 T value is split exactly into three bf16 terms (their sum carries its 24-bit mantissa), which run
+ * through the bf16 matrix cores with fp32 accumulation, so T is not rounded to 16 bit; then the addition and one rounding
+ * to y_dt.  Deterministic.
  *   x     dev [M][K] of x_dt                      ld  dev bf16 [rank][K]            lu  dev bf16 [N][rank]
  *   y_q   dev fp32 [M][N] (the quantized layer's fp32 output) or NULL (= 0)          y   dev [M][N] of y_dt (may be y_q)
  *   rank  32 or 64;  K a multiple of 16 (SQ_ERR_UNSUPPORTED otherwise);  x, ld, lu, workspace 16-byte aligned

@@ -625,6 +625,9 @@ LOWRANK = [
     dict(M=129, K=1040, N=257, rank=64, x_dtype="f32", yq=True),         # K = 16 * 65: groups of four steps and a tail
     dict(M=2048, K=4608, N=1152, rank=64, x_dtype="bf16", yq=True),      # several K slices, many row blocks
     dict(M=16, K=1152, N=6912, rank=64, x_dtype="bf16", yq=False),
+    dict(M=257, K=64, N=40, rank=32, x_dtype="bf16", yq=True),           # LDS-staged down projection: a single stage
+    dict(M=1000, K=1088, N=96, rank=32, x_dtype="bf16", yq=False),       # 17 stages dealt unevenly over the K slices
+    dict(M=515, K=8192, N=64, rank=64, x_dtype="bf16", yq=True),         # long slices: the ring wraps many times
 ]
 
 
