@@ -613,7 +613,7 @@ def measure_fp8(names=("cfg5", "cfg4", "cfg2")):
         out[name] = r
         del s, xq, wq
     return {"peak_tflops": FP8_MFMA_PEAK_TFLOPS, "workloads": out,
-            "note": "OCP E4M3 codes, steps range / 448, products on v_mfma_f32_32x32x64_f8f6f4 with fp32 sums; flops count both "
+            "note": "OCP E4M3 codes, steps range / 448, products on v_mfma_f32_32x32x64_f8f6f4 with fp32 accumulators; flops count both "
                     "polarity products of the dual K-segments like the int8 figure"}
 
 

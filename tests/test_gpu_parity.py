@@ -848,9 +848,13 @@ FP8GEMM = [
 
 
 def _fp8_tol(K, mag, ref, ydt):
-    """Error of the fp32 evaluation (products of codes are exact in fp32; their sum of up to K terms and the few
-    multiplications of the flush are rounded) plus the output rounding."""
-    return (8.0 * np.sqrt(K) + 64.0) * 2.0 ** -24 * mag + np.abs(ref) * (2.0 ** -8 if ydt == "bf16" else 2.0 ** -23) + 1e-30
+    """Error of the device's evaluation around the double-precision oracle.  The fp8 matrix instruction adds the eight
+    products of every aligned group of eight k after aligning them to the group's largest exponent sum E and dropping
+    the bits below 2^(E - 13) (measured: a product 2^14 below the largest one of its group vanishes, one in another group
+    of the same instruction does not), so a group loses less than 8 * 2^(E - 13) <= 2^-10 of its largest product and an
+    output less than 2^-10 of the sum of its terms' magnitudes, `mag`; the sums across groups, K-segments and the
+    dequantization are fp32 (second term); then the output rounding."""
+    return (2.0 ** -10 + (8.0 * np.sqrt(K) + 64.0) * 2.0 ** -24) * mag + np.abs(ref) * (2.0 ** -8 if ydt == "bf16" else 2.0 ** -23) + 1e-30
 
 
 @pytest.mark.parametrize("case", FP8GEMM)
@@ -906,9 +910,10 @@ def test_seglinear_fp8(oracle, case):
 
 
 def test_seglinear_fp8_exact_sums_and_polarity(oracle):
-    """Codes of small integers and steps that are powers of two: every partial sum is an integer below 2^24, so the fp32
-    evaluation is exact in any order and the output must equal the oracle's to the bit; the dual K-segment has both
-    polarities in every row."""
+    """Codes of small integers and steps that are powers of two: every product is an integer within 2^13 of the largest
+    one (the window the matrix instruction keeps inside a group of eight) and every partial sum an integer below 2^24, so
+    the device's evaluation is exact in any order and the output must equal the oracle's to the bit; the dual K-segment has
+    both polarities in every row."""
     import torch
 
     g = _gpu()
@@ -940,6 +945,40 @@ def test_seglinear_fp8_exact_sums_and_polarity(oracle):
     # and the plain definition on the integers themselves
     plain = (x.astype(np.float64) @ wi.astype(np.float64).T)
     assert np.array_equal(ref, plain)
+
+
+def test_fp8_products_far_below_the_largest_of_their_group(oracle):
+    """The case the tolerance is derived from: one product of 2^17.6 next to 127 products of 2^-j.  Inside its group of
+    eight the matrix instruction drops what lies 2^14 below the largest product, elsewhere the sum is fp32: the output
+    stays within the derived bound of the double-precision value, and the plain and the pipelined kernel (same
+    instruction, same groups) agree to the bit."""
+    import torch
+
+    g = _gpu()
+    M, K, N = 32, 128, 32
+    one = np.ones(1, np.float32)
+    layer = sq.Layer(M, K, N, [0, K], [0, N], [0], one, one)
+    for j in range(10):
+        t = np.float32(2.0 ** -j)
+        xv = np.full((M, K), t, np.float32)
+        wv = np.ones((N, K), np.float32)
+        xv[:, 0] = 448.0
+        wv[:, 0] = 448.0
+        xq, wq = oracle.fp8_encode(xv), oracle.fp8_encode(wv)
+        ref, mag = oracle.seglinear_fp8(xq, np.zeros_like(xq), wq, [0, K], [0, N], [0], one, one, np.ones((1, N), np.float32))
+        assert ref[0, 0] == 448.0 * 448.0 + 127 * float(t)
+        outs = []
+        for path in (0, -1):
+            sq.sq_tuning_set("force_path", path)
+            y = torch.full((M, N), float("nan"), dtype=torch.float32, device=g.DEV)
+            sq.sq_seglinear_fp8(layer, torch.from_numpy(xq).to(g.DEV), torch.from_numpy(wq).to(g.DEV),
+                                torch.ones((1, N), dtype=torch.float32, device=g.DEV), None, y)
+            torch.cuda.synchronize()
+            outs.append(y.cpu().numpy())
+        assert np.array_equal(outs[0], outs[1])
+        err = np.abs(outs[0].astype(np.float64) - ref)
+        assert (err <= _fp8_tol(K, mag, ref, "f32")).all()
+        assert (err <= 8 * float(t)).all()          # at most the seven neighbours of the large product (and fp32 rounding)
 
 
 def test_seglinear_fp8_rejects_unaligned_layouts():
@@ -1742,6 +1781,99 @@ def _random_segments(rng, total, align, maxs):
     n = int(rng.integers(1, min(maxs, units) + 1))
     cuts = sorted(rng.choice(np.arange(1, units), size=n - 1, replace=False).tolist()) if n > 1 else []
     return [0] + [c * align for c in cuts] + [total]
+
+
+def test_fp8_random_shapes_against_oracle(oracle):
+    """A seeded walk over shapes, K / N segmentations, input types, tile configurations and the plain kernel for the fp8
+    variant: codes and weight steps bit-exact, outputs within the bound of an fp32 evaluation."""
+    import torch
+
+    g = _gpu()
+    rng = np.random.default_rng(20250715)
+    ran = 0
+    for n in range(60):
+        M = int(rng.choice([1, 17, 64, 100, 129, 257, 300, 385, 700]))
+        K = 128 * int(rng.integers(1, 13))
+        N = int(rng.choice([7, 33, 64, 100, 128, 130, 192, 256, 300, 520]))
+        kseg = _random_segments(rng, K, 128, 4)
+        nseg = _random_segments(rng, N, 1, 3)
+        dual = [int(rng.integers(0, 2)) for _ in kseg[:-1]]
+        xdt = str(rng.choice(["bf16", "f32"]))
+        act = str(rng.choice(["silu", "gelu", "normal", "relu", "neg"]))
+        path, variant = (0, -1) if rng.integers(0, 4) == 0 else (-1, int(rng.choice([-1, -1, 0, 1, 3, 4, 5, 8])))
+        what = dict(case=n, M=M, K=K, N=N, kseg=kseg, nseg=nseg, dual=dual, xdt=xdt, act=act, path=path, variant=variant)
+        w = wl.random_layer(M, K, N, kseg, nseg, dual, seed=9000 + n, x_dtype=xdt, act=act,
+                            with_seg_scale=bool(rng.integers(0, 2)), with_bias=bool(rng.integers(0, 2)))
+        w.s_pos = (w.s_pos * np.float32(127.0 / 448.0)).astype(np.float32)
+        w.s_neg = (w.s_neg * np.float32(127.0 / 448.0)).astype(np.float32)
+        gl = g.GpuLayer(w)
+        wq = torch.full((N, K), 0x7F, dtype=torch.uint8, device=g.DEV)
+        xq = torch.full((M, K), 0x7F, dtype=torch.uint8, device=g.DEV)
+        sq.sq_quantize_weight_fp8(gl.layer, gl.wt, wq, gl.wscale)
+        sq.sq_quantize_act_fp8(gl.layer, gl.x, xq)
+        ydt = str(rng.choice(["f32", "bf16"]))
+        y = torch.full((M, N), float("nan"), dtype=torch.bfloat16 if ydt == "bf16" else torch.float32, device=g.DEV)
+        sq.sq_tuning_set("force_path", path)
+        sq.sq_tuning_set("gemm_variant", variant)
+        try:
+            sq.sq_seglinear_fp8(gl.layer, xq, wq, gl.wscale, gl.bias, y)
+        except sq.SqError as e:
+            assert e.status == 2 and variant >= 0, what           # a tile configuration that does not serve this layer class
+            continue
+        torch.cuda.synchronize()
+        r_wq, r_ws = oracle.quantize_weight_fp8(w.w, w.kseg_off)
+        r_xp, r_xn = oracle.quantize_act_fp8(w.x, w.kseg_off, w.dual, w.s_pos, w.s_neg)
+        assert np.array_equal(wq.cpu().numpy(), _plus_zero(r_wq)), what
+        assert np.array_equal(gl.wscale.cpu().numpy().view(np.uint32), r_ws.view(np.uint32)), what
+        xp, xn = _split_fp8(w, xq.cpu().numpy())
+        assert np.array_equal(xp, _plus_zero(r_xp)) and np.array_equal(xn, _plus_zero(r_xn)), what
+        ref, mag = oracle.seglinear_fp8(r_xp, r_xn, r_wq, w.kseg_off, w.nseg_off, w.dual, w.s_pos, w.s_neg, r_ws, w.seg_scale, w.bias)
+        got = y.float().cpu().numpy().astype(np.float64)
+        tol = _fp8_tol(K, mag, ref, ydt)
+        assert not np.isnan(got).any() and (np.abs(got - ref) <= tol).all(), (what, float((np.abs(got - ref) / tol).max()))
+        ran += 1
+    assert ran >= 45
+
+
+def test_fp8_many_tiles_and_graph_replay(oracle):
+    """More tiles than compute units (the persistent workgroups walk several tiles and prefetch across their boundaries), dual
+    with several K-segments, ragged edges; then the quantizer and the product captured into a HIP graph and replayed with
+    eager work in between: every replay must reproduce the eager result to the bit."""
+    import torch
+
+    g = _gpu()
+    M, K, N = 3000, 768, 2500
+    w = wl.random_layer(M, K, N, [0, 256, 768], [0, 1000, N], [1, 0], seed=77, x_dtype="bf16", act="gelu",
+                        with_seg_scale=True, with_bias=True)
+    w.s_pos = (w.s_pos * np.float32(127.0 / 448.0)).astype(np.float32)
+    w.s_neg = (w.s_neg * np.float32(127.0 / 448.0)).astype(np.float32)
+    gl = g.GpuLayer(w)
+    wq = torch.empty((N, K), dtype=torch.uint8, device=g.DEV)
+    xq = torch.empty((M, K), dtype=torch.uint8, device=g.DEV)
+    y = torch.full((M, N), float("nan"), dtype=torch.float32, device=g.DEV)
+    sq.sq_quantize_weight_fp8(gl.layer, gl.wt, wq, gl.wscale)
+    sq.sq_tuning_set("gemm_variant", 3)                          # 64 x 128 tiles: 47 x 20 = 940 of them
+    sq.sq_quantize_act_fp8(gl.layer, gl.x, xq)
+    sq.sq_seglinear_fp8(gl.layer, xq, wq, gl.wscale, gl.bias, y)
+    torch.cuda.synchronize()
+    r_wq, r_ws = oracle.quantize_weight_fp8(w.w, w.kseg_off)
+    r_xp, r_xn = oracle.quantize_act_fp8(w.x, w.kseg_off, w.dual, w.s_pos, w.s_neg)
+    ref, mag = oracle.seglinear_fp8(r_xp, r_xn, r_wq, w.kseg_off, w.nseg_off, w.dual, w.s_pos, w.s_neg, r_ws, w.seg_scale, w.bias)
+    got = y.cpu().numpy().astype(np.float64)
+    assert (np.abs(got - ref) <= _fp8_tol(K, mag, ref, "f32")).all()
+    eager = y.clone()
+    st = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=st):
+        sq.sq_quantize_act_fp8(gl.layer, gl.x, xq)
+        sq.sq_seglinear_fp8(gl.layer, xq, wq, gl.wscale, gl.bias, y)
+    for _ in range(3):
+        y.fill_(float("nan"))
+        xq.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, eager)
 
 
 def test_random_shapes_against_oracle(oracle):
