@@ -541,7 +541,7 @@ def measure_optimizer_side(name="cfg5"):
     t_host = (time.perf_counter() - t0) * 1e3
     sm, iv = torch.from_numpy(smooth).to(dev), torch.from_numpy(inv).to(dev)
     t_qw = float(np.median(_time_events(lambda: sq.sq_quantize_weight_smoothed(layer, s["wt"], sm, s["wq"], s["wscale"]), 5)))
-    t_qa = float(np.median(_time_events(lambda: sq.sq_quantize_act_smoothed(layer, s["x"], iv, s["xq"]), 20)))
+    t_qa = _gpu_side_ms([lambda: sq.sq_quantize_act_smoothed(layer, s["x"], iv, s["xq"])], launches=40)
     ld = torch.randn((64, w.K), device=dev).to(torch.bfloat16)
     lu = torch.randn((w.N, 64), device=dev).to(torch.bfloat16)
     yq = torch.zeros((w.M, w.N), dtype=torch.float32, device=dev)
