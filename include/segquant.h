@@ -423,10 +423,11 @@ sq_status sq_lowrank_add(const sq_layer* layer, const void* x, sq_dtype x_dt, co
  * exponent sum E, bits below 2^(E-13) dropped (a product 2^14 below the largest of its group vanishes), the groups and
  * instructions are then added in fp32.  Results are reproducible on this device and lie within
  * (2^-10 + (8 sqrt(K) + 64) 2^-24) of the sum of the terms' magnitudes of the exact value; on layer-like data the error
- * is below 2e-5 of the largest output.  K, every K-segment boundary: multiples of 128, xq / wq 16-byte aligned
- * (SQ_ERR_UNSUPPORTED otherwise; the quantizers take any shape).  The product runs on the pipelined tile kernel of
- * sq_seglinear with fp8 operands (tile shape chosen per layer; sq_tuning_set "gemm_variant" selects one, "force_path" 0
- * a plain tile kernel without the software pipeline).
+ * is a few 1e-5 of the largest output.  K, every K-segment boundary: multiples of 128, xq / wq 16-byte aligned
+ * (SQ_ERR_UNSUPPORTED otherwise; the quantizers take any shape).  The product runs on the kernels of sq_seglinear with
+ * fp8 operands: the weight-stream kernel for M <= 32 (where its X^ slab fits), else the pipelined tile kernel (tile shape
+ * chosen per layer; sq_tuning_set "gemm_variant" selects one; "force_path" 3 / 1 force either kernel, 0 a plain tile
+ * kernel without the software pipeline).
  *   w   dev [N][K] of w_dt      wq  dev, bytes [N][K]      wscale  dev fp32 [S][N]
  *   x   dev [M][K] of x_dt      xq  dev, bytes [M][K]      bias    dev fp32 [N] or NULL      y  dev [M][N] of y_dt
  */

@@ -49,6 +49,8 @@ def _jobs():
     for v in range(_num_variants()):
         jobs.append((os.path.join(CSRC, "seglinear_mfma_inst.hip"), os.path.join(OBJ, f"seglinear_mfma_v{v}.o"),
                      [f"-DSQ_VARIANT={v}"]))
+    # the weight-stream kernel on fp8 codes: the same source, a translation unit of its own
+    jobs.append((os.path.join(CSRC, "seglinear_stream.hip"), os.path.join(OBJ, "seglinear_stream_fp8.o"), ["-DSQ_STREAM_FP8=1"]))
     for v in _fp8_variants():          # the same tiles on fp8 codes
         jobs.append((os.path.join(CSRC, "seglinear_mfma_inst.hip"), os.path.join(OBJ, f"seglinear_mfma_fp8_v{v}.o"),
                      [f"-DSQ_VARIANT={v}", "-DSQ_FP8=1"]))

@@ -482,10 +482,15 @@ sq_status sq_seglinear_fp8(const sq_layer* layer, const uint8_t* xq, const uint8
   if (!sq::fp8_gemm_supported(a, tb)) return SQ_ERR_UNSUPPORTED;
   const sq::OutMode mode = y_dt == SQ_BF16 ? sq::OUT_BF16 : sq::OUT_F32;
   hipStream_t hs = reinterpret_cast<hipStream_t>(stream);
-  // force_path 0: the plain tile kernel of fp8.hip; otherwise the pipelined tile kernel shared with the int8 path
+  // up to two 16-row tiles of tokens: the weight-stream kernel; otherwise the pipelined tile kernel shared with the int8
+  // path.  force_path 0: the plain tile kernel of fp8.hip, 1: the pipelined tile kernel, 3: the weight-stream kernel
+  const bool stream_ok = sq::stream_supported(a, tb);
+  if (g_force_path == 3 && !stream_ok) return SQ_ERR_UNSUPPORTED;
   hipError_t e;
   if (g_force_path == 0) {
     e = sq::launch_seglinear_fp8(a, tb, mode, hs);
+  } else if (g_force_path == 3 || (g_force_path < 0 && a.M <= 32 && stream_ok)) {
+    e = sq::launch_seglinear_stream_fp8(a, tb, mode, sq::device_cus(), hs);
   } else {
     const int v = g_gemm_variant >= 0 ? g_gemm_variant : sq::mfma_fp8_pick_variant(a, tb);
     e = sq::launch_seglinear_mfma_fp8(a, tb, mode, v, hs);

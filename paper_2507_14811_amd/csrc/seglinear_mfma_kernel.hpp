@@ -107,12 +107,6 @@ __device__ __forceinline__ void split_polarity(const int x, int& pos, int& neg) 
   pos = x ^ neg;
 }
 
-// Value of an accumulator register: an exact int32 sum, or (fp8 codes) the bits of an fp32 sum.
-template <bool FP8> __device__ __forceinline__ float acc_value(int bits) {
-  if constexpr (FP8) return __int_as_float(bits);
-  else return (float)bits;
-}
-
 template <int SK> __device__ __forceinline__ int row_swizzle(int row) {
   return SK == 128 ? ((row >> 1) & 7) : ((row >> 2) & 3);
 }

@@ -86,9 +86,13 @@ struct StreamCfg {
 
 // TB: GemmTable (one layer; GT = NoGroups) or GroupSegTable (GT = GroupTable: L layers of the same shape that share
 // X^ and its steps; the 16-column groups of all layers form one list, layer = group / groups per layer).
-template <int MT, bool DUAL, int SLAB_KB, class TB, class GT, bool W4 = false, bool PS = false>
+// FP8: the codes are OCP E4M3 bytes; a 128-byte step is one v_mfma_f32_16x16x128_f8f6f4 (no block scales: a lane's operand
+// is its two 16-byte chunks of the step, the same k set for W^ and X^), the sums are fp32 kept as bits in the accumulator
+// registers, X^_- holds the codes with the sign bit set.  Static steps, code input only.
+template <int MT, bool DUAL, int SLAB_KB, class TB, class GT, bool W4 = false, bool PS = false, bool FP8 = false>
 __global__ __launch_bounds__(stream_waves(MT) * 64) void seglinear_stream_kernel(const GemmArgs a, const TB tb, const GT gt, const int mode) {
   static_assert(!PS || DUAL, "two slab planes only where both polarity paths run");
+  static_assert(!FP8 || !W4, "fp8 codes are bytes");
   using C = StreamCfg<MT, SLAB_KB, W4, PS>;
   constexpr bool GROUPED = std::is_same<GT, GroupTable>::value;
   constexpr int RING = C::RING, STEP = C::STEP, LPS = C::LPS, NW = C::NW;
@@ -490,6 +494,33 @@ __global__ __launch_bounds__(stream_waves(MT) * 64) void seglinear_stream_kernel
               wf[1][d] = pk & (int)0xF0F0F0F0u;
             }
           }
+          if constexpr (FP8) {
+            v8i w8;
+#pragma unroll
+            for (int d = 0; d < 4; ++d) { w8[d] = wf[0][d]; w8[4 + d] = wf[1][d]; }
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+              v8i p8, n8;
+#pragma unroll
+              for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                  int pos = xf[h][mt][d], neg = 0;
+                  if (DL) {
+                    if (PS) neg = nfp[h][mt][d];
+                    else split_polarity(xf[h][mt][d], pos, neg);
+                  }
+                  p8[4 * h + d] = pos;
+                  n8[4 * h + d] = neg;
+                }
+              // constant-zero scale operands select the unscaled instruction
+              accp[mt] = __builtin_bit_cast(v4i, __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
+                  w8, p8, __builtin_bit_cast(v4f, accp[mt]), 0, 0, 0, 0, 0, 0));
+              if (DL)
+                accn[mt] = __builtin_bit_cast(v4i, __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
+                    w8, n8, __builtin_bit_cast(v4f, accn[mt]), 0, 0, 0, 0, 0, 0));
+            }
+          } else {
 #pragma unroll
           for (int h = 0; h < 2; ++h)
 #pragma unroll
@@ -514,6 +545,7 @@ __global__ __launch_bounds__(stream_waves(MT) * 64) void seglinear_stream_kernel
               if (h == 0) accp[mt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf[h], pf, accp[mt], 0, 0, 0);
               else accp1[mt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf[h], pf, accp1[mt], 0, 0, 0);
             }
+          }
           // step consumed (its fragments are in registers): free the slot, keep the stream going
           cslot = (cslot + 1 == RING) ? 0 : cslot + 1;
           if (issued_steps < total) issue_step();
@@ -528,7 +560,9 @@ __global__ __launch_bounds__(stream_waves(MT) * 64) void seglinear_stream_kernel
       if (dl) step_loop(std::true_type{});
       else step_loop(std::false_type{});
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) { accp[mt] += accp1[mt]; accn[mt] += accn1[mt]; }
+      for (int mt = 0; mt < MT; ++mt) {
+        if (!FP8) { accp[mt] += accp1[mt]; accn[mt] += accn1[mt]; }     // (fp8: one instruction per step, one set)
+      }
       // ---- K-segment boundary (kseg boundaries are multiples of 128 here, so a step never straddles one) ------
       if (mode == OUT_DEBUG_ACC) {
 #pragma unroll
@@ -573,8 +607,8 @@ __global__ __launch_bounds__(stream_waves(MT) * 64) void seglinear_stream_kernel
           }
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
-            float t = (cw[r] * sp) * (float)accp[mt][r];
-            if (DUAL) t += (cw[r] * sn) * (float)accn[mt][r];
+            float t = (cw[r] * sp) * acc_value<FP8>(accp[mt][r]);
+            if (DUAL) t += (cw[r] * sn) * acc_value<FP8>(accn[mt][r]);
             fsum[mt][r] += t;
           }
         }
@@ -640,6 +674,9 @@ static int stream_slab_kb(const GemmArgs& a, bool dual, bool* two_planes) {
   return 0;
 }
 
+// This file is compiled twice: as it is (int8 and packed 4-bit codes), and with -DSQ_STREAM_FP8=1 for the instantiations
+// on fp8 codes only (the kernel is the largest of the library; two translation units build side by side).
+#ifndef SQ_STREAM_FP8
 bool stream_supported(const GemmArgs& a, const GemmTable& tb) {
   if (a.M > 64 || a.K % 128 != 0 || a.K < 128) return false;
   for (int s = 0; s <= tb.S; ++s)
@@ -649,10 +686,11 @@ bool stream_supported(const GemmArgs& a, const GemmTable& tb) {
   if (stream_slab_kb(a, any_dual(tb.dual, tb.S), &ps) == 0) return false;
   return true;
 }
+#endif
 
-template <int MT, int SLAB_KB, bool W4>
+template <int MT, int SLAB_KB, bool W4, bool FP8>
 static hipError_t launch_stream_ms(const GemmArgs& a, const GemmTable& tb, int mode, bool dual, bool ps, int grid, hipStream_t st) {
-#define SQ_K(D, P) hipLaunchKernelGGL((seglinear_stream_kernel<MT, D, SLAB_KB, GemmTable, NoGroups, W4, P>), dim3(grid), dim3(stream_waves(MT) * 64), 0, st, a, tb, NoGroups{}, mode)
+#define SQ_K(D, P) hipLaunchKernelGGL((seglinear_stream_kernel<MT, D, SLAB_KB, GemmTable, NoGroups, W4, P, FP8>), dim3(grid), dim3(stream_waves(MT) * 64), 0, st, a, tb, NoGroups{}, mode)
   if constexpr (MT <= 2) {
     if (dual && ps) { SQ_K(true, true); return hipGetLastError(); }
   }
@@ -662,7 +700,7 @@ static hipError_t launch_stream_ms(const GemmArgs& a, const GemmTable& tb, int m
   return hipGetLastError();
 }
 
-template <bool W4>
+template <bool W4, bool FP8>
 static hipError_t launch_stream_impl(const GemmArgs& a, const GemmTable& tb, OutMode mode, int cus, hipStream_t st) {
   const bool dual = any_dual(tb.dual, tb.S);
   const int mt = (a.M + 15) / 16;
@@ -671,7 +709,7 @@ static hipError_t launch_stream_impl(const GemmArgs& a, const GemmTable& tb, Out
   bool ps;
   const int slab = stream_slab_kb(a, dual, &ps);
 #define SQ_STREAM(MT_) \
-  (slab == 24 ? launch_stream_ms<MT_, 24, W4>(a, tb, mode, dual, ps, grid, st) : launch_stream_ms<MT_, 80, W4>(a, tb, mode, dual, ps, grid, st))
+  (slab == 24 ? launch_stream_ms<MT_, 24, W4, FP8>(a, tb, mode, dual, ps, grid, st) : launch_stream_ms<MT_, 80, W4, FP8>(a, tb, mode, dual, ps, grid, st))
   switch (mt) {
     case 1: return SQ_STREAM(1);
     case 2: return SQ_STREAM(2);
@@ -681,13 +719,20 @@ static hipError_t launch_stream_impl(const GemmArgs& a, const GemmTable& tb, Out
 #undef SQ_STREAM
 }
 
+#ifdef SQ_STREAM_FP8
+// fp8 (E4M3) codes: same shapes as stream_supported(); static steps
+hipError_t launch_seglinear_stream_fp8(const GemmArgs& a, const GemmTable& tb, OutMode mode, int cus, hipStream_t st) {
+  if (a.x_raw != nullptr || a.tok_steps != nullptr || mode == OUT_DEBUG_ACC) return hipErrorInvalidConfiguration;
+  return launch_stream_impl<false, true>(a, tb, mode, cus, st);
+}
+#else
 hipError_t launch_seglinear_stream(const GemmArgs& a, const GemmTable& tb, OutMode mode, int cus, hipStream_t st) {
-  return launch_stream_impl<false>(a, tb, mode, cus, st);
+  return launch_stream_impl<false, false>(a, tb, mode, cus, st);
 }
 
 // a.wq points at packed 4-bit codes [N][K/2]
 hipError_t launch_seglinear_stream_w4(const GemmArgs& a, const GemmTable& tb, OutMode mode, int cus, hipStream_t st) {
-  return launch_stream_impl<true>(a, tb, mode, cus, st);
+  return launch_stream_impl<true, false>(a, tb, mode, cus, st);
 }
 
 // Grouped call: L layers of one shape that share X^ (M <= 32).  a.wq / a.wscale / a.bias / a.y are unused.
@@ -729,5 +774,6 @@ hipError_t launch_seglinear_grouped(const GemmArgs& a, const GroupSegTable& tb, 
                                     hipStream_t st, bool w4) {
   return w4 ? launch_grouped_impl<true>(a, tb, gt, mode, cus, st) : launch_grouped_impl<false>(a, tb, gt, mode, cus, st);
 }
+#endif
 
 }  // namespace sq

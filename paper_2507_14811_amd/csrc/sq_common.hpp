@@ -154,6 +154,12 @@ __device__ __forceinline__ int clip_code(float r) {
   return (int)__builtin_fminf(__builtin_fmaxf(r, -kQmax), kQmax);
 }
 
+// Value of an accumulator register: an exact int32 sum, or (fp8 codes) the bits of an fp32 sum.
+template <bool FP8> __device__ __forceinline__ float acc_value(int bits) {
+  if constexpr (FP8) return __int_as_float(bits);
+  else return (float)bits;
+}
+
 // Column-dependent multiplier seg_scale[ks][ns(n)] without per-lane indexing of the by-value table.
 __device__ __forceinline__ float seg_scale_of(const GemmTable& tb, int ks, int n) {
   if (!tb.has_seg_scale) return 1.0f;

@@ -844,6 +844,11 @@ FP8GEMM = [
     dict(M=5, K=128, N=3, kseg=[0, 128], nseg=[0, 3], dual=[0], bias=True),              # one stage, mostly masked tile
     dict(M=257, K=1536, N=385, kseg=[0, 256, 384, 1536], nseg=[0, 129, 385], dual=[0, 1, 1], bias=True, seg_scale=True),
     dict(M=1024, K=4608, N=1152, kseg=[0, 1536, 4608], nseg=[0, 1152], dual=[0, 1], bias=True),
+    # skinny layers: the weight-stream kernel on fp8 codes (two slab planes / one plane, one to four 16-row tiles)
+    dict(M=16, K=1152, N=640, kseg=[0, 1152], nseg=[0, 640], dual=[1], bias=True),
+    dict(M=40, K=512, N=200, kseg=[0, 128, 512], nseg=[0, 200], dual=[1, 0], bias=False),
+    dict(M=64, K=2304, N=1157, kseg=[0, 1024, 1152, 2304], nseg=[0, 500, 1157], dual=[0, 1, 1], bias=True, seg_scale=True),
+    dict(M=31, K=256, N=7000, kseg=[0, 256], nseg=[0, 7000], dual=[0], bias=True),      # more column groups than waves
 ]
 
 
@@ -884,7 +889,7 @@ def test_seglinear_fp8(oracle, case):
     ref, mag = oracle.seglinear_fp8(r_xp, r_xn, r_wq, w.kseg_off, w.nseg_off, w.dual, w.s_pos, w.s_neg, r_ws, w.seg_scale, w.bias)
     # automatic choice, the plain tile kernel, and every tile configuration of the pipelined kernel built for fp8 codes
     ran = 0
-    for path, variant in [(-1, -1), (0, -1)] + [(1, v) for v in range(9)]:
+    for path, variant in [(-1, -1), (0, -1), (3, -1)] + [(1, v) for v in range(9)]:
         sq.sq_tuning_set("force_path", path)
         sq.sq_tuning_set("gemm_variant", variant)
         for ydt in ("f32", "bf16"):
@@ -892,7 +897,7 @@ def test_seglinear_fp8(oracle, case):
             try:
                 sq.sq_seglinear_fp8(gl.layer, xq, wq, gl.wscale, gl.bias, y)
             except sq.SqError:
-                assert variant >= 0           # a tile configuration that does not serve this layer class
+                assert variant >= 0 or path == 3   # a tile configuration that does not serve this layer class; no room for the X^ slab
                 continue
             torch.cuda.synchronize()
             ran += 1
@@ -901,7 +906,7 @@ def test_seglinear_fp8(oracle, case):
             tol = _fp8_tol(K, mag, ref, ydt)
             assert (np.abs(got - ref) <= tol).all(), (path, variant, float((np.abs(got - ref) / tol).max()))
             if ydt == "f32":          # the typical error is far inside the bound
-                assert np.abs(got - ref).max() <= 2e-5 * np.abs(ref).max()
+                assert np.abs(got - ref).max() <= 5e-5 * np.abs(ref).max(), (path, variant)
     assert ran >= 8
     # the variant does its job: close to the unquantized layer (3 mantissa bits: a few percent)
     if w.seg_scale is None:
@@ -1800,7 +1805,8 @@ def test_fp8_random_shapes_against_oracle(oracle):
         dual = [int(rng.integers(0, 2)) for _ in kseg[:-1]]
         xdt = str(rng.choice(["bf16", "f32"]))
         act = str(rng.choice(["silu", "gelu", "normal", "relu", "neg"]))
-        path, variant = (0, -1) if rng.integers(0, 4) == 0 else (-1, int(rng.choice([-1, -1, 0, 1, 3, 4, 5, 8])))
+        pick = int(rng.integers(0, 8))
+        path, variant = (0, -1) if pick < 2 else (3, -1) if pick == 2 else (-1, int(rng.choice([-1, -1, 0, 1, 3, 4, 5, 8])))
         what = dict(case=n, M=M, K=K, N=N, kseg=kseg, nseg=nseg, dual=dual, xdt=xdt, act=act, path=path, variant=variant)
         w = wl.random_layer(M, K, N, kseg, nseg, dual, seed=9000 + n, x_dtype=xdt, act=act,
                             with_seg_scale=bool(rng.integers(0, 2)), with_bias=bool(rng.integers(0, 2)))
@@ -1818,7 +1824,7 @@ def test_fp8_random_shapes_against_oracle(oracle):
         try:
             sq.sq_seglinear_fp8(gl.layer, xq, wq, gl.wscale, gl.bias, y)
         except sq.SqError as e:
-            assert e.status == 2 and variant >= 0, what           # a tile configuration that does not serve this layer class
+            assert e.status == 2 and (variant >= 0 or path == 3), what     # a tile configuration / kernel that does not serve this layer
             continue
         torch.cuda.synchronize()
         r_wq, r_ws = oracle.quantize_weight_fp8(w.w, w.kseg_off)
