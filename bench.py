@@ -588,7 +588,14 @@ def measure_fp8(names=("cfg5", "cfg4", "cfg2")):
             gemm()
         torch.cuda.synchronize()
         t_q = _gpu_side_ms([quant], launches=50)
-        t_g = _gpu_side_ms([gemm], launches=50)
+        if w.M <= 64:
+            # a skinny layer is a weight stream: rotate over distinct weight sets so that the bytes come from HBM
+            nsets = max(2, min(64, int(2.5e9 // max(1, w.N * w.K))))
+            sets = [wq] + [wq.clone() for _ in range(nsets - 1)]
+            t_g = _gpu_side_ms([(lambda q=q: sq.sq_seglinear_fp8(layer, xq, q, s["wscale"], None, s["y"])) for q in sets], launches=64)
+            del sets
+        else:
+            t_g = _gpu_side_ms([gemm], launches=50)
         t_step = _gpu_side_ms([quant, gemm], launches=50) * 2        # per pair
         flops = float(w.int8_ops)                                     # the same multiply-adds, both polarity products
         r = {"M": int(w.M), "K": int(w.K), "N": int(w.N), "ms_quantize_act_fp8": round(t_q, 5), "ms_seglinear_fp8": round(t_g, 5),
@@ -597,6 +604,10 @@ def measure_fp8(names=("cfg5", "cfg4", "cfg2")):
              "step_tflops": round(flops / (t_step * 1e-3) / 1e12, 1),
              "quant_gbs": round(w.quantize_act_bytes() / (t_q * 1e-3) / 1e9, 1),
              "quant_frac_hbm_peak": round(w.quantize_act_bytes() / (t_q * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        if w.M <= 64:
+            gb = w.seglinear_bytes()
+            r.update({"bound": "hbm", "bytes": int(gb), "gbs_from_hbm": round(gb / (t_g * 1e-3) / 1e9, 1),
+                      "frac_hbm_peak_from_hbm": round(gb / (t_g * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)})
         if name == names[0]:
             codes = xq.view(-1)[: 16 << 20]
             for _ in range(3):
@@ -749,7 +760,7 @@ def main():
 
     if args.fp8_only:
         probes.sqp_copy(torch.zeros(256 << 20, dtype=torch.int8, device="cuda:0"), torch.empty(256 << 20, dtype=torch.int8, device="cuda:0"))
-        print(json.dumps(measure_fp8((args.config,) + tuple(n for n in ("cfg4", "cfg2") if n in args.others.split(",") and n != args.config))))
+        print(json.dumps(measure_fp8((args.config,) + tuple(n for n in ("cfg4", "cfg2", "cfg3x28") if n in args.others.split(",") and n != args.config))))
         return
     if args.only:
         r = measure(args.only, args.steps, args.warmup, hot_only=True)
@@ -771,7 +782,7 @@ def main():
     w4 = measure_w4() if "cfg3x28" in args.others.split(",") else None
     geglu = measure_geglu()
     optimizer_side = measure_optimizer_side(args.config)
-    fp8 = measure_fp8((args.config,) + tuple(n for n in ("cfg4", "cfg2") if n in args.others.split(",") and n != args.config))
+    fp8 = measure_fp8((args.config,) + tuple(n for n in ("cfg4", "cfg2", "cfg3x28") if n in args.others.split(",") and n != args.config))
     others = {}
     for name in [n for n in args.others.split(",") if n and n != args.config]:
         sq.sq_tuning_set("gemm_variant", -1)
