@@ -595,6 +595,11 @@ def measure_fp8(names=("cfg5", "cfg4", "cfg2")):
         quant = lambda: sq.sq_quantize_act_fp8(layer, s["x"], xq)
         gemm = lambda: sq.sq_seglinear_fp8(layer, xq, wq, s["wscale"], None, s["y"])
         quant()
+        if w.M > 64:          # clock-ramp pre-roll on the fp8 MFMA probe, like measure()
+            t0 = time.perf_counter()
+            while (time.perf_counter() - t0) * 1e3 < PREROLL_MS:
+                probes.sqp_mfma_fp8(xq.view(-1)[: 16 << 20], 10000)
+                torch.cuda.synchronize()
         for _ in range(10):
             gemm()
         torch.cuda.synchronize()
