@@ -222,6 +222,56 @@ def test_invalid_arguments_are_rejected_on_the_host(sq):
     assert lib.sq_seglinear_grouped_fused(C.byref(_layer(sq, M=40).c), FAKE, 1, None, 1, one, 0, None) == UNSUPPORTED
 
 
+def test_invalid_arguments_of_the_optimizer_side_and_fp8_entry_points(sq):
+    """Smoothing, low-rank branch, fp8 variant, allocation-free calibration: rejected on the host before anything is
+    launched (no GPU needed)."""
+    INVALID, UNSUPPORTED = 1, 2
+    lib = sq.load_library()
+    ok = _layer(sq)                                               # K = 128
+    c = lambda l: C.byref(l.c)
+    # per-channel maxima and smoothed quantizers
+    assert lib.sq_calibrate_channel_amax(c(ok), None, 1, FAKE, 0, None) == INVALID
+    assert lib.sq_calibrate_channel_amax(c(ok), FAKE, 1, None, 0, None) == INVALID
+    assert lib.sq_calibrate_channel_amax(c(ok), FAKE, 6, FAKE, 0, None) == INVALID
+    assert lib.sq_weight_channel_amax(c(ok), None, 0, FAKE, None) == INVALID
+    assert lib.sq_weight_channel_amax(c(ok), FAKE, 0, None, None) == INVALID
+    assert lib.sq_smooth_factors(c(ok), None, FAKE, FAKE, FAKE, FAKE) == INVALID
+    assert lib.sq_smooth_factors(c(ok), FAKE, FAKE, None, FAKE, FAKE) == INVALID
+    assert lib.sq_quantize_weight_smoothed(c(ok), FAKE, 0, None, FAKE, FAKE, None) == INVALID
+    assert lib.sq_quantize_weight_smoothed(c(ok), FAKE, 4, FAKE, FAKE, FAKE, None) == INVALID
+    assert lib.sq_quantize_act_smoothed(c(ok), FAKE, 1, None, FAKE, None) == INVALID
+    assert lib.sq_quantize_act_smoothed(c(ok), None, 1, FAKE, FAKE, None) == INVALID
+    assert lib.sq_quantize_act_smoothed(c(_layer(sq, s_pos=[0.0])), FAKE, 1, FAKE, FAKE, None) == INVALID
+    # low-rank side branch
+    lr = lambda layer=ok, x=FAKE, dt=1, ld=FAKE, lu=FAKE, rank=64, y=FAKE, ydt=1, ws=FAKE, nbytes=1 << 30: lib.sq_lowrank_add(
+        c(layer), x, dt, ld, lu, rank, None, y, ydt, ws, nbytes, None)
+    assert lr(x=None) == INVALID and lr(ld=None) == INVALID and lr(lu=None) == INVALID and lr(y=None) == INVALID
+    assert lr(ws=None) == INVALID and lr(dt=3) == INVALID and lr(ydt=7) == INVALID
+    assert lr(rank=48) == UNSUPPORTED and lr(rank=0) == UNSUPPORTED
+    assert lr(layer=_layer(sq, K=72, kseg_off=[0, 72])) == UNSUPPORTED                 # K not a multiple of 16
+    assert lr(x=C.c_void_p(0x1004)) == INVALID                                       # 16-byte alignment
+    need = lib.sq_lowrank_workspace_bytes(c(ok), 64)
+    assert need > 0 and lr(nbytes=need - 1) == INVALID
+    assert lib.sq_lowrank_workspace_bytes(c(ok), 48) == 0 and lib.sq_lowrank_workspace_bytes(None, 64) == 0
+    # fp8 variant
+    assert lib.sq_quantize_weight_fp8(c(ok), None, 0, FAKE, FAKE, None) == INVALID
+    assert lib.sq_quantize_weight_fp8(c(ok), FAKE, 0, FAKE, None, None) == INVALID
+    assert lib.sq_quantize_weight_fp8(c(ok), FAKE, 2, FAKE, FAKE, None) == INVALID
+    assert lib.sq_quantize_act_fp8(c(ok), None, 1, FAKE, None) == INVALID
+    assert lib.sq_quantize_act_fp8(c(ok), FAKE, 1, None, None) == INVALID
+    assert lib.sq_quantize_act_fp8(c(_layer(sq, s_neg=[float("nan")])), FAKE, 1, FAKE, None) == INVALID
+    f8 = lambda layer=ok, xq=FAKE, wq=FAKE, ws=FAKE, y=FAKE, ydt=1: lib.sq_seglinear_fp8(c(layer), xq, wq, ws, None, y, ydt, None)
+    assert f8(xq=None) == INVALID and f8(wq=None) == INVALID and f8(ws=None) == INVALID and f8(y=None) == INVALID
+    assert f8(ydt=5) == INVALID
+    assert f8(layer=_layer(sq, K=192, kseg_off=[0, 192])) == UNSUPPORTED             # K not a multiple of 128
+    assert f8(layer=_layer(sq, K=256, kseg_off=[0, 64, 256], dual=[1, 0], s_pos=[1, 1], s_neg=[1, 1])) == UNSUPPORTED
+    assert f8(xq=C.c_void_p(0x1008)) == UNSUPPORTED                                  # 16-byte alignment of the code matrices
+    # percentile calibration on the library's own scratch array
+    assert 0 < lib.sq_calibrate_static_scratch_bytes() < (1 << 20)
+    st = lambda p, x=FAKE, amax=FAKE, steps=FAKE: lib.sq_calibrate_act_percentile_static(c(ok), x, 1, p, amax, steps, 0, None)
+    assert st(0.0) == INVALID and st(1.5) == INVALID and st(0.99, x=None) == INVALID and st(0.99, amax=None) == INVALID
+
+
 def test_missing_library_fails_loudly(monkeypatch, sq):
     from paper_2507_14811_amd import binding
 
