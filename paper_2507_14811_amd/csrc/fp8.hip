@@ -13,28 +13,30 @@ namespace sq {
 
 constexpr float kFp8Max = 448.0f;
 
-// Nearest E4M3 codes of four finite values, ties to the even mantissa, saturating at +-448, zeros stored as +0: the
-// hardware conversion of gfx950 (v_cvt_pk_fp8_f32: OCP E4M3, round to nearest even, subnormals) behind a clip, then the
-// sign bit of every byte whose other seven bits are zero is cleared.
-__device__ __forceinline__ uint32_t fp8_encode4(float q0, float q1, float q2, float q3) {
+// Nearest E4M3 codes of four finite values, ties to the even mantissa, saturating at +-448: the hardware conversion of
+// gfx950 (v_cvt_pk_fp8_f32: OCP E4M3, round to nearest even, subnormals) behind a clip.  fp8_plus_zero then clears the sign
+// bit of every byte whose other seven bits are zero (zeros are stored as +0).
+__device__ __forceinline__ uint32_t fp8_convert4(float q0, float q1, float q2, float q3) {
   auto clip = [](float q) { return __builtin_fminf(__builtin_fmaxf(q, -kFp8Max), kFp8Max); };
   int p = __builtin_amdgcn_cvt_pk_fp8_f32(clip(q0), clip(q1), 0, false);
   p = __builtin_amdgcn_cvt_pk_fp8_f32(clip(q2), clip(q3), p, true);
-  const uint32_t u = (uint32_t)p;
+  return (uint32_t)p;
+}
+__device__ __forceinline__ uint32_t fp8_plus_zero(uint32_t u) {
   const uint32_t nz = ((u & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) & 0x80808080u;     // bit 7 of the bytes with a non-zero magnitude
   return u & (nz | 0x7F7F7F7Fu);
 }
+__device__ __forceinline__ uint32_t fp8_encode4(float q0, float q1, float q2, float q3) {
+  return fp8_plus_zero(fp8_convert4(q0, q1, q2, q3));
+}
 __device__ __forceinline__ uint32_t fp8_encode(float v) { return fp8_encode4(v, 0.0f, 0.0f, 0.0f) & 0xFFu; }
 
-// v / s for the encoder without the division: v * (1 / s) is within two units in the last place of the quotient, so it
-// decides the code unless it lies within 16 units of a tie of the 3-bit mantissa (the 2^-9 grid of the subnormal codes is
-// brought under the same test by adding 2^-6).  fp8_near_tie tells; the caller then evaluates the true division, behind
-// a branch that is taken for about one element in 30000.
-__device__ __forceinline__ bool fp8_near_tie(float q) {
-  const float a = __builtin_fabsf(q);
-  const float a2 = a + (a < 0.015625f ? 0.015625f : 0.0f);
-  return ((__float_as_uint(a2) & 0xFFFFFu) - 0x7FFF0u) < 0x20u;
-}
+// v / s for the encoder without the division: q0 = v * (1 / s) is within two units in the last place of the quotient, so
+// the quotient lies between q0 (1 - 2^-21) and q0 (1 + 2^-21); the encoder is monotonic, so where both ends of that
+// interval get the same code the quotient gets it too.  Only where they differ (a tie of the 3-bit mantissa, or of the
+// 2^-9 grid of the subnormal codes, falls inside the interval: about one element in 100 000) the true division is
+// evaluated, for the group of four, behind a branch.
+constexpr float kFp8Lo = 1.0f - 0x1p-21f, kFp8Hi = 1.0f + 0x1p-21f;
 
 // ---- weight quantizer: one wavefront per (output channel, K-segment) -------------------------------------------------
 template <bool BF16>
@@ -122,23 +124,25 @@ __global__ __launch_bounds__(256) void quantize_act_fp8_fast_kernel(const void* 
 #pragma unroll
       for (int i = 0; i < 4; ++i) v[i] = __int_as_float(raw[BF16 ? 0 : g][i]);
     }
-    float q[4];
-    bool near = false;
+    float q0[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const bool ng = dual && (v[i] < 0.0f);
-      q[i] = v[i] * (ng ? in : ip);
-      near = near || fp8_near_tie(q[i]);
+      q0[i] = v[i] * (ng ? in : ip);
     }
-    if (__builtin_expect(near, 0)) {
+    uint32_t pk = fp8_convert4(q0[0] * kFp8Lo, q0[1] * kFp8Lo, q0[2] * kFp8Lo, q0[3] * kFp8Lo);
+    const uint32_t ph = fp8_convert4(q0[0] * kFp8Hi, q0[1] * kFp8Hi, q0[2] * kFp8Hi, q0[3] * kFp8Hi);
+    if (__builtin_expect(pk != ph, 0)) {
       asm volatile("" ::: "memory");                       // keeps the divisions behind the branch
+      float q[4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const bool ng = dual && (v[i] < 0.0f);
         q[i] = v[i] / (ng ? sn : sp);
       }
+      pk = fp8_convert4(q[0], q[1], q[2], q[3]);
     }
-    const uint32_t pk = fp8_encode4(q[0], q[1], q[2], q[3]);
+    pk = fp8_plus_zero(pk);
     out[g] = (int)pk;
   }
   reinterpret_cast<v4i*>(xq)[c] = out;
