@@ -436,6 +436,12 @@ sq_status sq_quantize_act_fp8(const sq_layer* layer, const void* x, sq_dtype x_d
 sq_status sq_seglinear_fp8(const sq_layer* layer, const uint8_t* xq, const uint8_t* wq, const float* wscale, const float* bias,
                            void* y, sq_dtype y_dt, void* stream);
 
+/* sq_seglinear_grouped on fp8 codes: xq from sq_quantize_act_fp8, every item's wq / wscale from sq_quantize_weight_fp8
+ * (the item's wq member points at E4M3 bytes); per layer the arithmetic is that of sq_seglinear_fp8; limits as for
+ * sq_seglinear_grouped. */
+sq_status sq_seglinear_grouped_fp8(const sq_layer* layer, const uint8_t* xq, int32_t L, const sq_group_item* items,
+                                   sq_dtype y_dt, void* stream);
+
 /* Human-readable name of a status code (static storage). */
 const char* sq_status_string(sq_status s);
 

@@ -31,7 +31,7 @@ EXPORTS = ("sq_quantize_weight", "sq_quantize_act", "sq_seglinear", "sq_seglinea
            "sq_calibrate_act_percentile_static", "sq_calibrate_static_scratch_bytes",
            "sq_calibrate_channel_amax", "sq_weight_channel_amax", "sq_smooth_factors", "sq_quantize_weight_smoothed",
            "sq_quantize_act_smoothed", "sq_lowrank_add", "sq_lowrank_workspace_bytes",
-           "sq_quantize_weight_fp8", "sq_quantize_act_fp8", "sq_seglinear_fp8")
+           "sq_quantize_weight_fp8", "sq_quantize_act_fp8", "sq_seglinear_fp8", "sq_seglinear_grouped_fp8")
 
 
 class SqError(RuntimeError):
@@ -122,6 +122,8 @@ def load_library() -> C.CDLL:
     lib.sq_calibrate_workspace_bytes.restype = C.c_size_t
     lib.sq_seglinear_grouped.argtypes = [lp, vp, i32, C.POINTER(sq_group_item), i32, vp]
     lib.sq_seglinear_grouped.restype = i32
+    lib.sq_seglinear_grouped_fp8.argtypes = [lp, vp, i32, C.POINTER(sq_group_item), i32, vp]
+    lib.sq_seglinear_grouped_fp8.restype = i32
     lib.sq_quantize_act_geglu.argtypes = [lp, vp, i32, vp, vp]
     lib.sq_quantize_act_geglu.restype = i32
     lib.sq_seglinear_fused.argtypes = [lp, vp, i32, C.POINTER(C.c_int32), vp, vp, vp, vp, i32, vp]
@@ -425,6 +427,13 @@ def sq_seglinear_grouped(layer: Layer, xq, items, stream=None) -> None:
     g = items if isinstance(items, GroupItems) else GroupItems(items)
     _check(load_library().sq_seglinear_grouped(C.byref(layer.c), _dptr(xq), g.n, g.arr, g.y_dt, _stream(stream)),
            "sq_seglinear_grouped")
+
+
+def sq_seglinear_grouped_fp8(layer: Layer, xq, items, stream=None) -> None:
+    """sq_seglinear_grouped on fp8 (E4M3) codes: xq and the items' wq are uint8 code tensors."""
+    g = items if isinstance(items, GroupItems) else GroupItems(items)
+    _check(load_library().sq_seglinear_grouped_fp8(C.byref(layer.c), _dptr(xq), g.n, g.arr, g.y_dt, _stream(stream)),
+           "sq_seglinear_grouped_fp8")
 
 
 def _act_codes(layer: Layer, act):

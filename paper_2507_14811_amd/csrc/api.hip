@@ -557,7 +557,7 @@ sq_status sq_seglinear_fused(const sq_layer* layer, const void* x, sq_dtype x_dt
 
 static sq_status grouped_common(const sq_layer* layer, const int8_t* xq, const void* x_raw, sq_dtype x_dt, const int32_t* act,
                                 int32_t L, const sq_group_item* items, sq_dtype y_dt, void* stream, int w_bits = 8,
-                                const float* tok_steps = nullptr) {
+                                const float* tok_steps = nullptr, bool fp8 = false) {
   sq_status st = check_layer(layer, true, tok_steps == nullptr);
   if (st != SQ_OK) return st;
   if (w_bits != 8 && w_bits != 4) return SQ_ERR_INVALID_ARG;
@@ -601,8 +601,10 @@ static sq_status grouped_common(const sq_layer* layer, const int8_t* xq, const v
   a.N = layer->N;
   a.tok_steps = tok_steps;
   if (!sq::stream_grouped_supported(a, tb)) return SQ_ERR_UNSUPPORTED;
-  hipError_t e = sq::launch_seglinear_grouped(a, tb, gt, y_dt == SQ_BF16 ? sq::OUT_BF16 : sq::OUT_F32, sq::device_cus(),
-                                              reinterpret_cast<hipStream_t>(stream), w_bits == 4);
+  const sq::OutMode mode = y_dt == SQ_BF16 ? sq::OUT_BF16 : sq::OUT_F32;
+  hipError_t e = fp8 ? sq::launch_seglinear_grouped_fp8(a, tb, gt, mode, sq::device_cus(), reinterpret_cast<hipStream_t>(stream))
+                     : sq::launch_seglinear_grouped(a, tb, gt, mode, sq::device_cus(), reinterpret_cast<hipStream_t>(stream),
+                                                    w_bits == 4);
   return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 
@@ -610,6 +612,13 @@ sq_status sq_seglinear_grouped(const sq_layer* layer, const int8_t* xq, int32_t 
                                sq_dtype y_dt, void* stream) {
   if (xq == nullptr) return SQ_ERR_INVALID_ARG;
   return grouped_common(layer, xq, nullptr, SQ_F32, nullptr, L, items, y_dt, stream);
+}
+
+sq_status sq_seglinear_grouped_fp8(const sq_layer* layer, const uint8_t* xq, int32_t L, const sq_group_item* items,
+                                   sq_dtype y_dt, void* stream) {
+  if (xq == nullptr) return SQ_ERR_INVALID_ARG;
+  return grouped_common(layer, reinterpret_cast<const int8_t*>(xq), nullptr, SQ_F32, nullptr, L, items, y_dt, stream, 8, nullptr,
+                        true);
 }
 
 sq_status sq_seglinear_grouped_w4(const sq_layer* layer, const int8_t* xq, const float* tok_steps, int32_t L,

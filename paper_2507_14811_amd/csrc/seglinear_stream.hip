@@ -745,10 +745,12 @@ bool stream_grouped_supported(const GemmArgs& a, const GroupSegTable& tb) {
   return stream_slab_kb(a, any_dual(tb.dual, tb.S), &ps) != 0;
 }
 
-template <int MT, int SLAB_KB, bool W4>
+#endif
+
+template <int MT, int SLAB_KB, bool W4, bool FP8>
 static hipError_t launch_grouped_ms(const GemmArgs& a, const GroupSegTable& tb, const GroupTable& gt, int mode, bool dual,
                                     bool ps, int grid, hipStream_t st) {
-#define SQ_K(D, P) hipLaunchKernelGGL((seglinear_stream_kernel<MT, D, SLAB_KB, GroupSegTable, GroupTable, W4, P>), dim3(grid), dim3(stream_waves(MT) * 64), 0, st, a, tb, gt, mode)
+#define SQ_K(D, P) hipLaunchKernelGGL((seglinear_stream_kernel<MT, D, SLAB_KB, GroupSegTable, GroupTable, W4, P, FP8>), dim3(grid), dim3(stream_waves(MT) * 64), 0, st, a, tb, gt, mode)
   if (dual && ps) SQ_K(true, true);
   else if (dual) SQ_K(true, false);
   else SQ_K(false, false);
@@ -756,7 +758,7 @@ static hipError_t launch_grouped_ms(const GemmArgs& a, const GroupSegTable& tb, 
   return hipGetLastError();
 }
 
-template <bool W4>
+template <bool W4, bool FP8>
 static hipError_t launch_grouped_impl(const GemmArgs& a, const GroupSegTable& tb, const GroupTable& gt, OutMode mode, int cus,
                                       hipStream_t st) {
   const bool dual = any_dual(tb.dual, tb.S);
@@ -765,14 +767,22 @@ static hipError_t launch_grouped_impl(const GemmArgs& a, const GroupSegTable& tb
   const int grid = (int)(ngroups < cus ? ngroups : cus);
   bool ps;
   const int slab = stream_slab_kb(a, dual, &ps);
-  if (mt == 1) return slab == 24 ? launch_grouped_ms<1, 24, W4>(a, tb, gt, mode, dual, ps, grid, st) : launch_grouped_ms<1, 80, W4>(a, tb, gt, mode, dual, ps, grid, st);
-  return slab == 24 ? launch_grouped_ms<2, 24, W4>(a, tb, gt, mode, dual, ps, grid, st) : launch_grouped_ms<2, 80, W4>(a, tb, gt, mode, dual, ps, grid, st);
+  if (mt == 1) return slab == 24 ? launch_grouped_ms<1, 24, W4, FP8>(a, tb, gt, mode, dual, ps, grid, st) : launch_grouped_ms<1, 80, W4, FP8>(a, tb, gt, mode, dual, ps, grid, st);
+  return slab == 24 ? launch_grouped_ms<2, 24, W4, FP8>(a, tb, gt, mode, dual, ps, grid, st) : launch_grouped_ms<2, 80, W4, FP8>(a, tb, gt, mode, dual, ps, grid, st);
 }
 
+#ifndef SQ_STREAM_FP8
 // w4: the items' wq point to packed 4-bit codes (quantize_weight_w4_kernel's layout)
 hipError_t launch_seglinear_grouped(const GemmArgs& a, const GroupSegTable& tb, const GroupTable& gt, OutMode mode, int cus,
                                     hipStream_t st, bool w4) {
-  return w4 ? launch_grouped_impl<true>(a, tb, gt, mode, cus, st) : launch_grouped_impl<false>(a, tb, gt, mode, cus, st);
+  return w4 ? launch_grouped_impl<true, false>(a, tb, gt, mode, cus, st) : launch_grouped_impl<false, false>(a, tb, gt, mode, cus, st);
+}
+#else
+// the items' wq point to fp8 (E4M3) codes; static steps, code input
+hipError_t launch_seglinear_grouped_fp8(const GemmArgs& a, const GroupSegTable& tb, const GroupTable& gt, OutMode mode, int cus,
+                                        hipStream_t st) {
+  if (a.x_raw != nullptr || a.tok_steps != nullptr || mode == OUT_DEBUG_ACC) return hipErrorInvalidConfiguration;
+  return launch_grouped_impl<false, true>(a, tb, gt, mode, cus, st);
 }
 #endif
 

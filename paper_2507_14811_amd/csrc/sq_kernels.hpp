@@ -76,6 +76,8 @@ hipError_t launch_quantize_act_fp8(const void* x, bool x_is_bf16, uint8_t* xq, i
 bool fp8_gemm_supported(const GemmArgs& a, const GemmTable& tb);
 // seglinear_stream.hip built with -DSQ_STREAM_FP8=1: the weight-stream kernel on fp8 codes (shapes of stream_supported())
 hipError_t launch_seglinear_stream_fp8(const GemmArgs& a, const GemmTable& tb, OutMode mode, int cus, hipStream_t st);
+hipError_t launch_seglinear_grouped_fp8(const GemmArgs& a, const GroupSegTable& tb, const GroupTable& gt, OutMode mode, int cus,
+                                        hipStream_t st);
 hipError_t launch_seglinear_fp8(const GemmArgs& a, const GemmTable& tb, OutMode mode, hipStream_t st);
 
 // seglinear_generic.hip : any shape / alignment, one thread per output element

@@ -371,6 +371,55 @@ def test_seglinear_grouped(oracle, case):
             g.check_bf16_against(g.bf16_tensor_bits(items[l][3]), r.y32, r.y_bf16_bits, RTOL * ymax)
 
 
+@pytest.mark.parametrize("case", [
+    dict(M=16, K=1152, N=576, L=5, kseg=[0, 1152], dual=[1], ydt="f32"),              # two slab planes
+    dict(M=32, K=512, N=200, L=3, kseg=[0, 128, 512], dual=[0, 1], ydt="bf16"),
+    dict(M=7, K=256, N=1000, L=28, kseg=[0, 256], dual=[0], ydt="f32"),                # more groups than waves
+])
+def test_seglinear_grouped_fp8(oracle, case):
+    """L layers on fp8 codes that share the quantized input, one launch: every layer against the oracle, layer by layer, and
+    bit-identical to the single-layer call."""
+    import torch
+
+    g = _gpu()
+    M, K, N, L = case["M"], case["K"], case["N"], case["L"]
+    base = wl.random_layer(M, K, N, case["kseg"], [0, N], case["dual"], seed=K + L, x_dtype="bf16", act="silu", with_bias=True)
+    base.s_pos = (base.s_pos * np.float32(127.0 / 448.0)).astype(np.float32)
+    base.s_neg = (base.s_neg * np.float32(127.0 / 448.0)).astype(np.float32)
+    gl = g.GpuLayer(base)
+    xq = torch.empty((M, K), dtype=torch.uint8, device=g.DEV)
+    sq.sq_quantize_act_fp8(gl.layer, gl.x, xq)
+    r_xp, r_xn = oracle.quantize_act_fp8(base.x, base.kseg_off, base.dual, base.s_pos, base.s_neg)
+    rng = np.random.default_rng(L * 1000 + N)
+    tdt = torch.bfloat16 if case["ydt"] == "bf16" else torch.float32
+    items, hosts = [], []
+    for l in range(L):
+        wl_l = (rng.standard_normal((N, K)) * (0.01 * (1 + l % 5))).astype(np.float32)
+        bias_l = None if l % 3 == 2 else rng.standard_normal(N).astype(np.float32)
+        wq = torch.empty((N, K), dtype=torch.uint8, device=g.DEV)
+        ws = torch.empty((base.S, N), dtype=torch.float32, device=g.DEV)
+        sq.sq_quantize_weight_fp8(gl.layer, torch.from_numpy(wl_l).to(g.DEV), wq, ws)
+        y = torch.full((M, N), float("nan"), dtype=tdt, device=g.DEV)
+        items.append((wq, ws, None if bias_l is None else torch.from_numpy(bias_l).to(g.DEV), y))
+        hosts.append((wl_l, bias_l))
+    sq.sq_seglinear_grouped_fp8(gl.layer, xq, items)
+    torch.cuda.synchronize()
+    for l in range(L):
+        wl_l, bias_l = hosts[l]
+        r_wq, r_ws = oracle.quantize_weight_fp8(wl_l, base.kseg_off)
+        assert np.array_equal(items[l][0].cpu().numpy(), _plus_zero(r_wq))
+        ref, mag = oracle.seglinear_fp8(r_xp, r_xn, r_wq, base.kseg_off, base.nseg_off, base.dual, base.s_pos, base.s_neg, r_ws,
+                                        None, bias_l)
+        got = items[l][3].float().cpu().numpy().astype(np.float64)
+        assert not np.isnan(got).any()
+        assert (np.abs(got - ref) <= _fp8_tol(K, mag, ref, case["ydt"])).all(), l
+        single = torch.empty_like(items[l][3])
+        sq.sq_tuning_set("force_path", 3)
+        sq.sq_seglinear_fp8(gl.layer, xq, items[l][0], items[l][1], items[l][2], single)
+        torch.cuda.synchronize()
+        assert torch.equal(single, items[l][3])
+
+
 def test_grouped_rejects_what_it_cannot_run(oracle):
     import torch
 

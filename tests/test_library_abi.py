@@ -266,6 +266,12 @@ def test_invalid_arguments_of_the_optimizer_side_and_fp8_entry_points(sq):
     assert f8(layer=_layer(sq, K=192, kseg_off=[0, 192])) == UNSUPPORTED             # K not a multiple of 128
     assert f8(layer=_layer(sq, K=256, kseg_off=[0, 64, 256], dual=[1, 0], s_pos=[1, 1], s_neg=[1, 1])) == UNSUPPORTED
     assert f8(xq=C.c_void_p(0x1008)) == UNSUPPORTED                                  # 16-byte alignment of the code matrices
+    from paper_2507_14811_amd.binding import sq_group_item
+    one = (sq_group_item * 1)(sq_group_item(0x1000, 0x1000, None, 0x1000))
+    assert lib.sq_seglinear_grouped_fp8(c(ok), None, 1, one, 0, None) == INVALID
+    assert lib.sq_seglinear_grouped_fp8(c(ok), FAKE, 1, None, 0, None) == INVALID
+    assert lib.sq_seglinear_grouped_fp8(c(ok), FAKE, 65, one, 0, None) == UNSUPPORTED
+    assert lib.sq_seglinear_grouped_fp8(c(_layer(sq, M=40)), FAKE, 1, one, 0, None) == UNSUPPORTED
     # percentile calibration on the library's own scratch array
     assert 0 < lib.sq_calibrate_static_scratch_bytes() < (1 << 20)
     st = lambda p, x=FAKE, amax=FAKE, steps=FAKE: lib.sq_calibrate_act_percentile_static(c(ok), x, 1, p, amax, steps, 0, None)
