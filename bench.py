@@ -625,6 +625,10 @@ def measure_fp8(names=("cfg5", "cfg4", "cfg2")):
             r.update({"bound": "hbm", "bytes": int(gb), "gbs_from_hbm": round(gb / (t_g * 1e-3) / 1e9, 1),
                       "frac_hbm_peak_from_hbm": round(gb / (t_g * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)})
         if name == names[0]:
+            acts = [sq.SQ_ACT_GELU if d else sq.SQ_ACT_NONE for d in w.dual]
+            t_qf = _gpu_side_ms([lambda: sq.sq_quantize_act_fp8_fused(layer, s["x"], acts, xq)], launches=30)
+            quant()                                               # restore the codes of the plain quantizer
+            r["ms_quantize_act_fp8_fused_gelu"] = round(t_qf, 5)
             codes = xq.view(-1)[: 16 << 20]
             for _ in range(3):
                 probes.sqp_mfma_fp8(codes, 10000)

@@ -433,6 +433,11 @@ sq_status sq_lowrank_add(const sq_layer* layer, const void* x, sq_dtype x_dt, co
  */
 sq_status sq_quantize_weight_fp8(const sq_layer* layer, const void* w, sq_dtype w_dt, uint8_t* wq, float* wscale, void* stream);
 sq_status sq_quantize_act_fp8(const sq_layer* layer, const void* x, sq_dtype x_dt, uint8_t* xq, void* stream);
+/* The same with the activation in front of the layer applied first (Sec. 4.3.1-4.3.2; App. B): xq = Q_dual(act(h)) on the
+ * fp8 grid, act as for sq_quantize_act_fused (host, int32 [S], SQ_ACT_* per K-segment, must not be NULL; the fp32
+ * operation sequence documented there), one pass, per element. */
+sq_status sq_quantize_act_fp8_fused(const sq_layer* layer, const void* h, sq_dtype h_dt, const int32_t* act, uint8_t* xq,
+                                    void* stream);
 sq_status sq_seglinear_fp8(const sq_layer* layer, const uint8_t* xq, const uint8_t* wq, const float* wscale, const float* bias,
                            void* y, sq_dtype y_dt, void* stream);
 

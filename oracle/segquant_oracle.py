@@ -435,6 +435,11 @@ def quantize_act_fp8(x, kseg_off, dual, s_pos, s_neg):
     return xp, xn
 
 
+def quantize_act_fp8_fused(h, kseg_off, dual, act, s_pos, s_neg):
+    """Q_dual(act(h)) with E4M3 codes: the activation (bit-specified fp32, `activation`), then `quantize_act_fp8`."""
+    return quantize_act_fp8(activation(h, kseg_off, act), kseg_off, dual, s_pos, s_neg)
+
+
 def seglinear_fp8(xq_pos, xq_neg, wq, kseg_off, nseg_off, dual, s_pos, s_neg, wscale, seg_scale=None, bias=None):
     """The layer on E4M3 codes in double -> (y fp64 [M][N], mag fp64 [M][N] = the same sum over |terms|)"""
     xp, xn, wq = _u8(xq_pos), _u8(xq_neg), _u8(wq)

@@ -31,7 +31,7 @@ EXPORTS = ("sq_quantize_weight", "sq_quantize_act", "sq_seglinear", "sq_seglinea
            "sq_calibrate_act_percentile_static", "sq_calibrate_static_scratch_bytes",
            "sq_calibrate_channel_amax", "sq_weight_channel_amax", "sq_smooth_factors", "sq_quantize_weight_smoothed",
            "sq_quantize_act_smoothed", "sq_lowrank_add", "sq_lowrank_workspace_bytes",
-           "sq_quantize_weight_fp8", "sq_quantize_act_fp8", "sq_seglinear_fp8", "sq_seglinear_grouped_fp8")
+           "sq_quantize_weight_fp8", "sq_quantize_act_fp8", "sq_seglinear_fp8", "sq_seglinear_grouped_fp8", "sq_quantize_act_fp8_fused")
 
 
 class SqError(RuntimeError):
@@ -114,6 +114,8 @@ def load_library() -> C.CDLL:
     lib.sq_quantize_weight_fp8.restype = i32
     lib.sq_quantize_act_fp8.argtypes = [lp, vp, i32, vp, vp]
     lib.sq_quantize_act_fp8.restype = i32
+    lib.sq_quantize_act_fp8_fused.argtypes = [lp, vp, i32, C.POINTER(C.c_int32), vp, vp]
+    lib.sq_quantize_act_fp8_fused.restype = i32
     lib.sq_seglinear_fp8.argtypes = [lp, vp, vp, vp, vp, vp, i32, vp]
     lib.sq_seglinear_fp8.restype = i32
     lib.sq_lowrank_workspace_bytes.argtypes = [lp, i32]
@@ -319,6 +321,15 @@ def sq_quantize_act_fp8(layer: Layer, x, xq, stream=None) -> None:
     """x [M][K] fp32/bf16 -> xq uint8 [M][K], E4M3 codes of Q_dual (X^_+: sign bit clear, X^_-: sign bit set)."""
     _check(load_library().sq_quantize_act_fp8(C.byref(layer.c), _dptr(x), _dt(x), _dptr(xq), _stream(stream)),
            "sq_quantize_act_fp8")
+
+
+def sq_quantize_act_fp8_fused(layer: Layer, h, act, xq, stream=None) -> None:
+    """xq = Q_dual(act(h)) with E4M3 codes: h [M][K] fp32/bf16 pre-activation, act: SQ_ACT_* per K-segment (host sequence)."""
+    if len(act) != layer.c.S:
+        raise ValueError("one activation code per K-segment")
+    codes = (C.c_int32 * max(len(act), 1))(*[int(a) for a in act])
+    _check(load_library().sq_quantize_act_fp8_fused(C.byref(layer.c), _dptr(h), _dt(h), codes, _dptr(xq), _stream(stream)),
+           "sq_quantize_act_fp8_fused")
 
 
 def sq_seglinear_fp8(layer: Layer, xq, wq, wscale, bias, y, stream=None) -> None:

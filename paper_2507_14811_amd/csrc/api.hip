@@ -441,7 +441,21 @@ sq_status sq_quantize_weight_fp8(const sq_layer* layer, const void* w, sq_dtype 
   return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 
+static sq_status quantize_act_fp8_common(const sq_layer* layer, const void* x, sq_dtype x_dt, const int32_t* act, uint8_t* xq,
+                                         void* stream);
+
 sq_status sq_quantize_act_fp8(const sq_layer* layer, const void* x, sq_dtype x_dt, uint8_t* xq, void* stream) {
+  return quantize_act_fp8_common(layer, x, x_dt, nullptr, xq, stream);
+}
+
+sq_status sq_quantize_act_fp8_fused(const sq_layer* layer, const void* h, sq_dtype h_dt, const int32_t* act, uint8_t* xq,
+                                    void* stream) {
+  if (act == nullptr) return SQ_ERR_INVALID_ARG;
+  return quantize_act_fp8_common(layer, h, h_dt, act, xq, stream);
+}
+
+static sq_status quantize_act_fp8_common(const sq_layer* layer, const void* x, sq_dtype x_dt, const int32_t* act, uint8_t* xq,
+                                         void* stream) {
   sq_status st = check_layer(layer, true, true);
   if (st != SQ_OK) return st;
   if (x == nullptr || xq == nullptr) return SQ_ERR_INVALID_ARG;
@@ -457,6 +471,10 @@ sq_status sq_quantize_act_fp8(const sq_layer* layer, const void* x, sq_dtype x_d
     tb.inv_pos[s] = safe_inv(tb.s_pos[s]);
     tb.inv_neg[s] = safe_inv(tb.s_neg[s]);
     tb.act[s] = SQ_ACT_NONE;
+    if (act != nullptr) {
+      if (act[s] != SQ_ACT_NONE && act[s] != SQ_ACT_SILU && act[s] != SQ_ACT_GELU) return SQ_ERR_INVALID_ARG;
+      tb.act[s] = act[s];
+    }
   }
   hipError_t e = sq::launch_quantize_act_fp8(x, x_dt == SQ_BF16, xq, layer->M, layer->K, tb, reinterpret_cast<hipStream_t>(stream));
   return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;

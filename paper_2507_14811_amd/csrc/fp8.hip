@@ -71,7 +71,9 @@ hipError_t launch_quantize_weight_fp8(const void* w, bool w_is_bf16, uint8_t* wq
 }
 
 // ---- activation quantizer: Q_dual with fp8 codes, one element per thread and loop trip ------------------------------
-template <bool BF16>
+// ACT: the activation in front of the layer (SiLU / GELU per K-segment, the bit-specified fp32 sequence of sq_common.hpp)
+// is applied to the input first: Q_dual(act(h)) in one pass.
+template <bool BF16, bool ACT>
 __global__ __launch_bounds__(256) void quantize_act_fp8_kernel(const void* __restrict__ x, uint8_t* __restrict__ xq, int M, int K,
                                                                const ActTable tb) {
   const size_t total = (size_t)M * K;
@@ -79,16 +81,18 @@ __global__ __launch_bounds__(256) void quantize_act_fp8_kernel(const void* __res
     const int col = (int)(i % (size_t)K);
     float sp = tb.s_pos[0], sn = tb.s_neg[0];
     bool dual = tb.dual[0] != 0;
+    int acode = tb.act[0];
     for (int s = 1; s < tb.S; ++s)
-      if (col >= tb.kseg_off[s]) { sp = tb.s_pos[s]; sn = tb.s_neg[s]; dual = tb.dual[s] != 0; }
-    const float v = BF16 ? bf16_to_f32(reinterpret_cast<const uint16_t*>(x)[i]) : reinterpret_cast<const float*>(x)[i];
+      if (col >= tb.kseg_off[s]) { sp = tb.s_pos[s]; sn = tb.s_neg[s]; dual = tb.dual[s] != 0; acode = tb.act[s]; }
+    float v = BF16 ? bf16_to_f32(reinterpret_cast<const uint16_t*>(x)[i]) : reinterpret_cast<const float*>(x)[i];
+    if (ACT) v = activate(acode, v);
     const bool ng = dual && (v < 0.0f);
     xq[i] = (uint8_t)fp8_encode(v / (ng ? sn : sp));
   }
 }
 
 // aligned shapes: 16 consecutive elements of one row and K-segment per thread (16-byte loads and stores)
-template <bool BF16>
+template <bool BF16, bool ACT>
 __global__ __launch_bounds__(256) void quantize_act_fp8_fast_kernel(const void* __restrict__ x, uint8_t* __restrict__ xq,
                                                                     uint32_t nchunks, uint32_t kchunks, uint32_t kmagic,
                                                                     const ActTable tb) {
@@ -100,6 +104,7 @@ __global__ __launch_bounds__(256) void quantize_act_fp8_fast_kernel(const void* 
   for (int l = 0; l < NL; ++l) raw[l] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(x) + ((size_t)NL * c + l));
   float sp = tb.s_pos[0], sn = tb.s_neg[0], ip = tb.inv_pos[0], in = tb.inv_neg[0];
   bool dual = tb.dual[0] != 0;
+  int acode = ACT ? tb.act[0] : SQ_ACT_NONE;
   if (tb.S > 1) {
     // column of this chunk: c mod kchunks via a reciprocal multiply (the quotient is exact or one too small)
     const uint32_t qc = __umulhi(c, kmagic);
@@ -107,7 +112,10 @@ __global__ __launch_bounds__(256) void quantize_act_fp8_fast_kernel(const void* 
     if (r >= kchunks) r -= kchunks;
     const int col = (int)(r * 16u);
     for (int s = 1; s < tb.S; ++s)
-      if (col >= tb.kseg_off[s]) { sp = tb.s_pos[s]; sn = tb.s_neg[s]; ip = tb.inv_pos[s]; in = tb.inv_neg[s]; dual = tb.dual[s] != 0; }
+      if (col >= tb.kseg_off[s]) {
+        sp = tb.s_pos[s]; sn = tb.s_neg[s]; ip = tb.inv_pos[s]; in = tb.inv_neg[s]; dual = tb.dual[s] != 0;
+        if (ACT) acode = tb.act[s];
+      }
   }
   v4i out;
 #pragma unroll
@@ -123,6 +131,10 @@ __global__ __launch_bounds__(256) void quantize_act_fp8_fast_kernel(const void* 
     } else {
 #pragma unroll
       for (int i = 0; i < 4; ++i) v[i] = __int_as_float(raw[BF16 ? 0 : g][i]);
+    }
+    if (ACT) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) v[i] = activate(acode, v[i]);
     }
     float q0[4];
 #pragma unroll
@@ -148,7 +160,9 @@ __global__ __launch_bounds__(256) void quantize_act_fp8_fast_kernel(const void* 
   reinterpret_cast<v4i*>(xq)[c] = out;
 }
 
-hipError_t launch_quantize_act_fp8(const void* x, bool x_is_bf16, uint8_t* xq, int M, int K, const ActTable& tb, hipStream_t st) {
+template <bool ACT>
+static hipError_t launch_quantize_act_fp8_impl(const void* x, bool x_is_bf16, uint8_t* xq, int M, int K, const ActTable& tb,
+                                               hipStream_t st) {
   bool aligned = (K % 16 == 0) && ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(xq)) % 16 == 0);
   for (int s = 0; s <= tb.S; ++s) aligned = aligned && (tb.kseg_off[s] % 16 == 0);
   for (int s = 0; s < tb.S; ++s)      // the fast kernel multiplies by the reciprocals of the steps: they must be usable
@@ -157,15 +171,23 @@ hipError_t launch_quantize_act_fp8(const void* x, bool x_is_bf16, uint8_t* xq, i
     const uint32_t kchunks = (uint32_t)(K / 16), nchunks = (uint32_t)(((size_t)M * K) / 16);
     const unsigned blocks = (nchunks + 255u) / 256u;
     const uint32_t kmagic = (uint32_t)(0x100000000ull / kchunks > 0xFFFFFFFFull ? 0xFFFFFFFFull : 0x100000000ull / kchunks);
-    if (x_is_bf16) hipLaunchKernelGGL(quantize_act_fp8_fast_kernel<true>, dim3(blocks), dim3(256), 0, st, x, xq, nchunks, kchunks, kmagic, tb);
-    else hipLaunchKernelGGL(quantize_act_fp8_fast_kernel<false>, dim3(blocks), dim3(256), 0, st, x, xq, nchunks, kchunks, kmagic, tb);
+    if (x_is_bf16) hipLaunchKernelGGL((quantize_act_fp8_fast_kernel<true, ACT>), dim3(blocks), dim3(256), 0, st, x, xq, nchunks, kchunks, kmagic, tb);
+    else hipLaunchKernelGGL((quantize_act_fp8_fast_kernel<false, ACT>), dim3(blocks), dim3(256), 0, st, x, xq, nchunks, kchunks, kmagic, tb);
   } else {
     const size_t total = (size_t)M * K;
     const unsigned blocks = (unsigned)((total + 255) / 256 > 65536 ? 65536 : (total + 255) / 256);
-    if (x_is_bf16) hipLaunchKernelGGL(quantize_act_fp8_kernel<true>, dim3(blocks), dim3(256), 0, st, x, xq, M, K, tb);
-    else hipLaunchKernelGGL(quantize_act_fp8_kernel<false>, dim3(blocks), dim3(256), 0, st, x, xq, M, K, tb);
+    if (x_is_bf16) hipLaunchKernelGGL((quantize_act_fp8_kernel<true, ACT>), dim3(blocks), dim3(256), 0, st, x, xq, M, K, tb);
+    else hipLaunchKernelGGL((quantize_act_fp8_kernel<false, ACT>), dim3(blocks), dim3(256), 0, st, x, xq, M, K, tb);
   }
   return hipGetLastError();
+}
+
+// tb.act[] other than SQ_ACT_NONE in any K-segment selects the instantiation with the activation in front
+hipError_t launch_quantize_act_fp8(const void* x, bool x_is_bf16, uint8_t* xq, int M, int K, const ActTable& tb, hipStream_t st) {
+  bool any = false;
+  for (int s = 0; s < tb.S; ++s) any = any || tb.act[s] != SQ_ACT_NONE;
+  return any ? launch_quantize_act_fp8_impl<true>(x, x_is_bf16, xq, M, K, tb, st)
+             : launch_quantize_act_fp8_impl<false>(x, x_is_bf16, xq, M, K, tb, st);
 }
 
 // ---- GEMM ------------------------------------------------------------------------------------------------------------

@@ -887,6 +887,42 @@ def test_quantize_act_fp8(oracle, case, scales):
         assert (xp == 0x7E).any()
 
 
+@pytest.mark.parametrize("case", [
+    dict(M=70, K=512, kseg=[0, 128, 512], dual=[0, 1], act=[0, 2], x_dtype="bf16"),
+    dict(M=33, K=1024, kseg=[0, 1024], dual=[1], act=[1], x_dtype="f32"),
+    dict(M=13, K=100, kseg=[0, 37, 100], dual=[1, 1], act=[2, 1], x_dtype="bf16"),      # unaligned: element-wise kernel
+    dict(M=300, K=2048, kseg=[0, 512, 2048], dual=[1, 0], act=[1, 0], x_dtype="bf16"),
+])
+def test_quantize_act_fp8_fused(oracle, case):
+    """Q_dual(act(h)) with fp8 codes in one pass: bit-exact against the oracle's activation followed by its fp8 quantizer."""
+    import torch
+
+    g = _gpu()
+    w = wl.random_layer(case["M"], case["K"], 4, case["kseg"], [0, 4], case["dual"], seed=case["K"] + case["M"],
+                        x_dtype=case["x_dtype"], act="normal")
+    w.x = (w.x * np.float32(2.0)).astype(np.float32)
+    if case["x_dtype"] == "bf16":
+        w.x = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(w.x))
+    a = oracle.activation(w.x, case["kseg"], case["act"])
+    sp, sn, _, _ = oracle.calibrate_act(a, case["kseg"], case["dual"])
+    w.s_pos = (sp * np.float32(127.0 / 448.0)).astype(np.float32)
+    w.s_neg = (sn * np.float32(127.0 / 448.0)).astype(np.float32)
+    gl = g.GpuLayer(w)
+    xq = torch.full((w.M, w.K), 0x7F, dtype=torch.uint8, device=g.DEV)
+    sq.sq_quantize_act_fp8_fused(gl.layer, gl.x, case["act"], xq)
+    torch.cuda.synchronize()
+    r_xp, r_xn = oracle.quantize_act_fp8_fused(w.x, w.kseg_off, w.dual, case["act"], w.s_pos, w.s_neg)
+    xp, xn = _split_fp8(w, xq.cpu().numpy())
+    assert np.array_equal(xp, _plus_zero(r_xp)) and np.array_equal(xn, _plus_zero(r_xn))
+    # all-none codes: the plain quantizer
+    xq2 = torch.empty_like(xq)
+    xq3 = torch.empty_like(xq)
+    sq.sq_quantize_act_fp8_fused(gl.layer, gl.x, [0] * w.S, xq2)
+    sq.sq_quantize_act_fp8(gl.layer, gl.x, xq3)
+    torch.cuda.synchronize()
+    assert torch.equal(xq2, xq3)
+
+
 FP8GEMM = [
     dict(M=300, K=512, N=200, kseg=[0, 128, 512], nseg=[0, 200], dual=[1, 0], bias=True),
     dict(M=128, K=1152, N=256, kseg=[0, 1152], nseg=[0, 256], dual=[1], bias=False),

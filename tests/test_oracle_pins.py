@@ -1008,3 +1008,35 @@ def test_fp8_quantizers_and_layer(oracle):
     plain, _ = oracle.seglinear_fp8(xp, xn, wq, kseg, nseg, dual, sp8, sn8, ws)
     bound = (np.abs(w_.x).astype(np.float64) @ np.abs(w_.w).astype(np.float64).T) * (2 * 2.0 ** -4 + 2.0 ** -8) + 1e-3
     assert np.all(np.abs(plain - full) <= bound)
+
+
+def test_fp8_quantizer_behind_the_activation(oracle):
+    """Q_dual(act(h)) on the fp8 grid: hand-worked landmarks (SiLU(0) = 0, GELU of a large argument is the argument, both
+    activations' minima are negative and small, so with a dual K-segment they take the s_- step), the single-scale
+    K-segment passes h through unchanged, and the code of every element is the nearest E4M3 value of act(h) / s computed in
+    double from the closed forms."""
+    kseg, dual, act = [0, 4, 8, 12], [1, 1, 0], [1, 2, 0]           # SiLU | GELU | none
+    s_pos, s_neg = np.float32([0.25, 0.125, 0.5]), np.float32([2.0 ** -9, 2.0 ** -9, 1.0])
+    h = np.float32([[0.0, 8.0, -1.0, 30.0, 0.0, 8.0, -0.75, 30.0, 3.0, -3.0, 0.0, 224.0]])
+    xp, xn = oracle.quantize_act_fp8_fused(h, kseg, dual, act, s_pos, s_neg)
+    vp, vn = oracle.fp8_decode(xp)[0], oracle.fp8_decode(xn)[0]
+    assert vp[0] == 0 and vn[0] == 0 and vp[4] == 0 and vn[4] == 0
+    assert vp[3] == 120.0 and vp[7] == 240.0                        # 30 / 0.25, 30 / 0.125: exact grid values
+    assert vp[1] == 32.0 and vn[1] == 0                             # SiLU(8) = 7.997 -> 31.99 -> 32
+    assert vp[2] == 0 and vn[2] == -144.0                           # SiLU(-1) = -0.26894 / 2^-9 = -137.7 -> -144 (step 16 there)
+    assert vp[6] == 0 and vn[6] == -88.0                            # GELU(-0.75) = -0.17004 / 2^-9 = -87.06 -> -88 (step 8 there)
+    assert list(vp[8:]) == [6.0, -6.0, 0.0, 448.0] and not vn[8:].any()
+    rng = np.random.default_rng(11)
+    h = (rng.standard_normal((64, 12)) * 2.5).astype(np.float32)
+    xp, xn = oracle.quantize_act_fp8_fused(h, kseg, dual, act, s_pos, s_neg)
+    z = h.astype(np.float64)
+    a = np.where(np.arange(12) < 4, z / (1 + np.exp(-z)),
+                 np.where(np.arange(12) < 8, 0.5 * z * (1 + np.tanh(np.sqrt(2 / np.pi) * (z + 0.044715 * z ** 3))), z))
+    step = np.where(a < 0, np.repeat(s_neg, 4).astype(np.float64), np.repeat(s_pos, 4).astype(np.float64))
+    step[:, 8:] = s_pos[2]
+    q = np.clip(a / step, -448, 448)
+    grid = np.unique(oracle.fp8_decode(np.array([c for c in range(256) if (c & 0x7F) != 0x7F], np.uint8)).astype(np.float64))
+    got = (oracle.fp8_decode(xp).astype(np.float64) + oracle.fp8_decode(xn).astype(np.float64))
+    nearest = np.abs(q[..., None] - grid).min(axis=-1)
+    assert (np.abs(got - q) <= nearest * (1 + 1e-5) + 1e-6 * np.abs(q) + 1e-12).all()
+    assert (oracle.fp8_decode(xp)[:, :8] >= 0).all() and (oracle.fp8_decode(xn)[:, :8] <= 0).all()
