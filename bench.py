@@ -627,6 +627,9 @@ def measure_fp8(names=("cfg5", "cfg4", "cfg2")):
         if name == names[0]:
             acts = [sq.SQ_ACT_GELU if d else sq.SQ_ACT_NONE for d in w.dual]
             t_qf = _gpu_side_ms([lambda: sq.sq_quantize_act_fp8_fused(layer, s["x"], acts, xq)], launches=30)
+            lut_ws = torch.empty((sq.sq_quantize_act_fused_workspace_bytes(layer),), dtype=torch.uint8, device=dev)
+            t_qt = _gpu_side_ms([lambda: sq.sq_quantize_act_fp8_fused(layer, s["x"], acts, xq, lut_ws)], launches=30)   # per call (two launches)
+            r["ms_quantize_act_fp8_fused_gelu_by_code_table"] = round(t_qt, 5)
             quant()                                               # restore the codes of the plain quantizer
             r["ms_quantize_act_fp8_fused_gelu"] = round(t_qf, 5)
             codes = xq.view(-1)[: 16 << 20]

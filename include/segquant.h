@@ -435,9 +435,11 @@ sq_status sq_quantize_weight_fp8(const sq_layer* layer, const void* w, sq_dtype 
 sq_status sq_quantize_act_fp8(const sq_layer* layer, const void* x, sq_dtype x_dt, uint8_t* xq, void* stream);
 /* The same with the activation in front of the layer applied first (Sec. 4.3.1-4.3.2; App. B): xq = Q_dual(act(h)) on the
  * fp8 grid, act as for sq_quantize_act_fused (host, int32 [S], SQ_ACT_* per K-segment, must not be NULL; the fp32
- * operation sequence documented there), one pass, per element. */
+ * operation sequence documented there).  workspace as for sq_quantize_act_fused (NULL, or
+ * sq_quantize_act_fused_workspace_bytes(layer) device bytes, 16-byte aligned: bf16 inputs are then served by code tables,
+ * same codes, two launches); SQ_ERR_INVALID_ARG for a workspace that is too small or misaligned. */
 sq_status sq_quantize_act_fp8_fused(const sq_layer* layer, const void* h, sq_dtype h_dt, const int32_t* act, uint8_t* xq,
-                                    void* stream);
+                                    void* workspace, size_t workspace_bytes, void* stream);
 sq_status sq_seglinear_fp8(const sq_layer* layer, const uint8_t* xq, const uint8_t* wq, const float* wscale, const float* bias,
                            void* y, sq_dtype y_dt, void* stream);
 

@@ -114,7 +114,7 @@ def load_library() -> C.CDLL:
     lib.sq_quantize_weight_fp8.restype = i32
     lib.sq_quantize_act_fp8.argtypes = [lp, vp, i32, vp, vp]
     lib.sq_quantize_act_fp8.restype = i32
-    lib.sq_quantize_act_fp8_fused.argtypes = [lp, vp, i32, C.POINTER(C.c_int32), vp, vp]
+    lib.sq_quantize_act_fp8_fused.argtypes = [lp, vp, i32, C.POINTER(C.c_int32), vp, vp, C.c_size_t, vp]
     lib.sq_quantize_act_fp8_fused.restype = i32
     lib.sq_seglinear_fp8.argtypes = [lp, vp, vp, vp, vp, vp, i32, vp]
     lib.sq_seglinear_fp8.restype = i32
@@ -323,13 +323,15 @@ def sq_quantize_act_fp8(layer: Layer, x, xq, stream=None) -> None:
            "sq_quantize_act_fp8")
 
 
-def sq_quantize_act_fp8_fused(layer: Layer, h, act, xq, stream=None) -> None:
-    """xq = Q_dual(act(h)) with E4M3 codes: h [M][K] fp32/bf16 pre-activation, act: SQ_ACT_* per K-segment (host sequence)."""
+def sq_quantize_act_fp8_fused(layer: Layer, h, act, xq, workspace=None, stream=None) -> None:
+    """xq = Q_dual(act(h)) with E4M3 codes: h [M][K] fp32/bf16 pre-activation, act: SQ_ACT_* per K-segment (host sequence);
+    workspace: optional device byte tensor (bf16 inputs are then served by code tables)."""
     if len(act) != layer.c.S:
         raise ValueError("one activation code per K-segment")
     codes = (C.c_int32 * max(len(act), 1))(*[int(a) for a in act])
-    _check(load_library().sq_quantize_act_fp8_fused(C.byref(layer.c), _dptr(h), _dt(h), codes, _dptr(xq), _stream(stream)),
-           "sq_quantize_act_fp8_fused")
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load_library().sq_quantize_act_fp8_fused(C.byref(layer.c), _dptr(h), _dt(h), codes, _dptr(xq), _dptr(workspace),
+                                                    nbytes, _stream(stream)), "sq_quantize_act_fp8_fused")
 
 
 def sq_seglinear_fp8(layer: Layer, xq, wq, wscale, bias, y, stream=None) -> None:

@@ -442,20 +442,20 @@ sq_status sq_quantize_weight_fp8(const sq_layer* layer, const void* w, sq_dtype 
 }
 
 static sq_status quantize_act_fp8_common(const sq_layer* layer, const void* x, sq_dtype x_dt, const int32_t* act, uint8_t* xq,
-                                         void* stream);
+                                         void* workspace, size_t workspace_bytes, void* stream);
 
 sq_status sq_quantize_act_fp8(const sq_layer* layer, const void* x, sq_dtype x_dt, uint8_t* xq, void* stream) {
-  return quantize_act_fp8_common(layer, x, x_dt, nullptr, xq, stream);
+  return quantize_act_fp8_common(layer, x, x_dt, nullptr, xq, nullptr, 0, stream);
 }
 
 sq_status sq_quantize_act_fp8_fused(const sq_layer* layer, const void* h, sq_dtype h_dt, const int32_t* act, uint8_t* xq,
-                                    void* stream) {
+                                    void* workspace, size_t workspace_bytes, void* stream) {
   if (act == nullptr) return SQ_ERR_INVALID_ARG;
-  return quantize_act_fp8_common(layer, h, h_dt, act, xq, stream);
+  return quantize_act_fp8_common(layer, h, h_dt, act, xq, workspace, workspace_bytes, stream);
 }
 
 static sq_status quantize_act_fp8_common(const sq_layer* layer, const void* x, sq_dtype x_dt, const int32_t* act, uint8_t* xq,
-                                         void* stream) {
+                                         void* workspace, size_t workspace_bytes, void* stream) {
   sq_status st = check_layer(layer, true, true);
   if (st != SQ_OK) return st;
   if (x == nullptr || xq == nullptr) return SQ_ERR_INVALID_ARG;
@@ -476,7 +476,17 @@ static sq_status quantize_act_fp8_common(const sq_layer* layer, const void* x, s
       tb.act[s] = act[s];
     }
   }
-  hipError_t e = sq::launch_quantize_act_fp8(x, x_dt == SQ_BF16, xq, layer->M, layer->K, tb, reinterpret_cast<hipStream_t>(stream));
+  hipStream_t hs = reinterpret_cast<hipStream_t>(stream);
+  if (workspace != nullptr) {            // bf16 inputs by code table, as sq_quantize_act_fused
+    if (workspace_bytes < sq::quantize_act_fused_workspace_bytes(layer->S) || reinterpret_cast<uintptr_t>(workspace) % 16 != 0)
+      return SQ_ERR_INVALID_ARG;
+    if (sq::quantize_act_lut_usable(x, x_dt == SQ_BF16, reinterpret_cast<const int8_t*>(xq), layer->K, tb)) {
+      hipError_t el = sq::launch_quantize_act_lut(x, reinterpret_cast<int8_t*>(xq), layer->M, layer->K, tb, workspace,
+                                                  sq::device_cus(), hs, true);
+      return el == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+    }
+  }
+  hipError_t e = sq::launch_quantize_act_fp8(x, x_dt == SQ_BF16, xq, layer->M, layer->K, tb, hs);
   return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 

@@ -11,25 +11,6 @@
 
 namespace sq {
 
-constexpr float kFp8Max = 448.0f;
-
-// Nearest E4M3 codes of four finite values, ties to the even mantissa, saturating at +-448: the hardware conversion of
-// gfx950 (v_cvt_pk_fp8_f32: OCP E4M3, round to nearest even, subnormals) behind a clip.  fp8_plus_zero then clears the sign
-// bit of every byte whose other seven bits are zero (zeros are stored as +0).
-__device__ __forceinline__ uint32_t fp8_convert4(float q0, float q1, float q2, float q3) {
-  auto clip = [](float q) { return __builtin_fminf(__builtin_fmaxf(q, -kFp8Max), kFp8Max); };
-  int p = __builtin_amdgcn_cvt_pk_fp8_f32(clip(q0), clip(q1), 0, false);
-  p = __builtin_amdgcn_cvt_pk_fp8_f32(clip(q2), clip(q3), p, true);
-  return (uint32_t)p;
-}
-__device__ __forceinline__ uint32_t fp8_plus_zero(uint32_t u) {
-  const uint32_t nz = ((u & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) & 0x80808080u;     // bit 7 of the bytes with a non-zero magnitude
-  return u & (nz | 0x7F7F7F7Fu);
-}
-__device__ __forceinline__ uint32_t fp8_encode4(float q0, float q1, float q2, float q3) {
-  return fp8_plus_zero(fp8_convert4(q0, q1, q2, q3));
-}
-__device__ __forceinline__ uint32_t fp8_encode(float v) { return fp8_encode4(v, 0.0f, 0.0f, 0.0f) & 0xFFu; }
 
 // v / s for the encoder without the division: q0 = v * (1 / s) is within two units in the last place of the quotient, so
 // the quotient lies between q0 (1 - 2^-21) and q0 (1 + 2^-21); the encoder is monotonic, so where both ends of that

@@ -148,6 +148,8 @@ static hipError_t launch_quantize_act_impl(const void* x, bool x_is_bf16, int8_t
 constexpr int kLutBytes = 65536;
 constexpr int kLutThreads = 512;    // 256 and 1024 measured slower
 
+// FP8: the table holds OCP E4M3 codes (nearest value of the IEEE quotient, clipped to +-448, zeros as +0) instead of int8 ones.
+template <bool FP8>
 __global__ __launch_bounds__(256) void act_lut_build_kernel(const ActTable tb, int8_t* __restrict__ lut) {
   const int ks = blockIdx.y;
   const uint32_t bits = blockIdx.x * 256u + threadIdx.x;                    // grid.x = 256
@@ -158,7 +160,8 @@ __global__ __launch_bounds__(256) void act_lut_build_kernel(const ActTable tb, i
     if (s == ks) { sp = tb.s_pos[s]; sn = tb.s_neg[s]; ip = tb.inv_pos[s]; in = tb.inv_neg[s]; dual = tb.dual[s] != 0; acode = tb.act[s]; }
   const float v = activate(acode, __uint_as_float(bits << 16));
   const bool ng = dual && (v < 0.0f);
-  lut[(size_t)ks * kLutBytes + bits] = (int8_t)clip_code(round_quotient(v, ng ? sn : sp, ng ? in : ip));
+  if (FP8) lut[(size_t)ks * kLutBytes + bits] = (int8_t)fp8_encode(v / (ng ? sn : sp));
+  else lut[(size_t)ks * kLutBytes + bits] = (int8_t)clip_code(round_quotient(v, ng ? sn : sp, ng ? in : ip));
 }
 
 struct LutPlan {                         // workgroups [wg_begin[s], wg_begin[s+1]) stream K-segment s
@@ -224,9 +227,10 @@ bool quantize_act_lut_usable(const void* h, bool h_is_bf16, const int8_t* xq, in
 }
 
 hipError_t launch_quantize_act_lut(const void* h, int8_t* xq, int M, int K, const ActTable& tb, void* workspace, int cus,
-                                   hipStream_t st) {
+                                   hipStream_t st, bool fp8) {
   int8_t* lut = reinterpret_cast<int8_t*>(workspace);
-  hipLaunchKernelGGL(act_lut_build_kernel, dim3(256, tb.S), dim3(256), 0, st, tb, lut);
+  if (fp8) hipLaunchKernelGGL(act_lut_build_kernel<true>, dim3(256, tb.S), dim3(256), 0, st, tb, lut);
+  else hipLaunchKernelGGL(act_lut_build_kernel<false>, dim3(256, tb.S), dim3(256), 0, st, tb, lut);
   // two workgroups per CU, dealt to the K-segments in proportion to their share of the matrix (at least one each)
   const int total = 2 * cus > tb.S ? 2 * cus : tb.S;
   LutPlan plan;

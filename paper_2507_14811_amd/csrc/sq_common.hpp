@@ -154,6 +154,26 @@ __device__ __forceinline__ int clip_code(float r) {
   return (int)__builtin_fminf(__builtin_fmaxf(r, -kQmax), kQmax);
 }
 
+constexpr float kFp8Max = 448.0f;     // largest finite OCP E4M3 value
+
+// Nearest E4M3 codes of four finite values, ties to the even mantissa, saturating at +-448: the hardware conversion of
+// gfx950 (v_cvt_pk_fp8_f32: OCP E4M3, round to nearest even, subnormals) behind a clip.  fp8_plus_zero then clears the sign
+// bit of every byte whose other seven bits are zero (zeros are stored as +0).
+__device__ __forceinline__ uint32_t fp8_convert4(float q0, float q1, float q2, float q3) {
+  auto clip = [](float q) { return __builtin_fminf(__builtin_fmaxf(q, -kFp8Max), kFp8Max); };
+  int p = __builtin_amdgcn_cvt_pk_fp8_f32(clip(q0), clip(q1), 0, false);
+  p = __builtin_amdgcn_cvt_pk_fp8_f32(clip(q2), clip(q3), p, true);
+  return (uint32_t)p;
+}
+__device__ __forceinline__ uint32_t fp8_plus_zero(uint32_t u) {
+  const uint32_t nz = ((u & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) & 0x80808080u;     // bit 7 of the bytes with a non-zero magnitude
+  return u & (nz | 0x7F7F7F7Fu);
+}
+__device__ __forceinline__ uint32_t fp8_encode4(float q0, float q1, float q2, float q3) {
+  return fp8_plus_zero(fp8_convert4(q0, q1, q2, q3));
+}
+__device__ __forceinline__ uint32_t fp8_encode(float v) { return fp8_encode4(v, 0.0f, 0.0f, 0.0f) & 0xFFu; }
+
 // Value of an accumulator register: an exact int32 sum, or (fp8 codes) the bits of an fp32 sum.
 template <bool FP8> __device__ __forceinline__ float acc_value(int bits) {
   if constexpr (FP8) return __int_as_float(bits);

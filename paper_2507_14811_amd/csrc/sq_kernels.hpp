@@ -18,7 +18,7 @@ hipError_t launch_quantize_act(const void* x, bool x_is_bf16, int8_t* xq, int M,
 size_t quantize_act_fused_workspace_bytes(int S);
 bool quantize_act_lut_usable(const void* h, bool h_is_bf16, const int8_t* xq, int K, const ActTable& tb);
 hipError_t launch_quantize_act_lut(const void* h, int8_t* xq, int M, int K, const ActTable& tb, void* workspace, int cus,
-                                   hipStream_t st);
+                                   hipStream_t st, bool fp8 = false);     // fp8: the tables (and xq) hold OCP E4M3 codes
 hipError_t launch_quantize_weight(const void* w, bool w_is_bf16, int8_t* wq, float* wscale, int N, int K,
                                   const KsegTable& tb, hipStream_t st);
 

@@ -914,6 +914,12 @@ def test_quantize_act_fp8_fused(oracle, case):
     r_xp, r_xn = oracle.quantize_act_fp8_fused(w.x, w.kseg_off, w.dual, case["act"], w.s_pos, w.s_neg)
     xp, xn = _split_fp8(w, xq.cpu().numpy())
     assert np.array_equal(xp, _plus_zero(r_xp)) and np.array_equal(xn, _plus_zero(r_xn))
+    # with a workspace (bf16 inputs: code tables in LDS): the same codes
+    ws = torch.full((sq.sq_quantize_act_fused_workspace_bytes(gl.layer),), 0xA5, dtype=torch.uint8, device=g.DEV)
+    xq_t = torch.full_like(xq, 0x7F)
+    sq.sq_quantize_act_fp8_fused(gl.layer, gl.x, case["act"], xq_t, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(xq_t, xq)
     # all-none codes: the plain quantizer
     xq2 = torch.empty_like(xq)
     xq3 = torch.empty_like(xq)

@@ -261,9 +261,11 @@ def test_invalid_arguments_of_the_optimizer_side_and_fp8_entry_points(sq):
     assert lib.sq_quantize_act_fp8(c(ok), FAKE, 1, None, None) == INVALID
     assert lib.sq_quantize_act_fp8(c(_layer(sq, s_neg=[float("nan")])), FAKE, 1, FAKE, None) == INVALID
     one_code = (C.c_int32 * 1)(1)
-    assert lib.sq_quantize_act_fp8_fused(c(ok), FAKE, 1, None, FAKE, None) == INVALID
-    assert lib.sq_quantize_act_fp8_fused(c(ok), None, 1, one_code, FAKE, None) == INVALID
-    assert lib.sq_quantize_act_fp8_fused(c(ok), FAKE, 1, (C.c_int32 * 1)(3), FAKE, None) == INVALID
+    assert lib.sq_quantize_act_fp8_fused(c(ok), FAKE, 1, None, FAKE, None, 0, None) == INVALID
+    assert lib.sq_quantize_act_fp8_fused(c(ok), None, 1, one_code, FAKE, None, 0, None) == INVALID
+    assert lib.sq_quantize_act_fp8_fused(c(ok), FAKE, 1, (C.c_int32 * 1)(3), FAKE, None, 0, None) == INVALID
+    assert lib.sq_quantize_act_fp8_fused(c(ok), FAKE, 1, one_code, FAKE, FAKE, 65535, None) == INVALID
+    assert lib.sq_quantize_act_fp8_fused(c(ok), FAKE, 1, one_code, FAKE, C.c_void_p(0x1008), 65536, None) == INVALID
     f8 = lambda layer=ok, xq=FAKE, wq=FAKE, ws=FAKE, y=FAKE, ydt=1: lib.sq_seglinear_fp8(c(layer), xq, wq, ws, None, y, ydt, None)
     assert f8(xq=None) == INVALID and f8(wq=None) == INVALID and f8(ws=None) == INVALID and f8(y=None) == INVALID
     assert f8(ydt=5) == INVALID
