@@ -101,5 +101,6 @@ def check_bf16_against(y_bits: np.ndarray, ref32: np.ndarray, ref_bits: np.ndarr
         half_ulp = np.abs(yv) * 2.0 ** -8
         assert (np.abs(yv - r32) <= tol_abs + half_ulp * (1 + 1e-6) + 1e-38).all(), \
             "bf16 output is not the rounding of a value within the fp32 tolerance"
-    assert rate < 1e-3, f"bf16 mismatch rate {rate}"
+    # rare: at most one output in a thousand (two in a small matrix, where a single straddle is already above that rate)
+    assert int(neq.sum()) <= max(2, int(1e-3 * neq.size)), f"bf16 mismatch rate {rate}"
     return rate
