@@ -23,18 +23,18 @@ static hipError_t launch_one(const GemmArgs& a, const GemmTable& tb, int mode, h
     hipLaunchKernelGGL(kern, dim3(a.num_wg), dim3(P::WM * P::WN * 64), 0, st, a, tb, mode);
     return hipGetLastError();
   } else {
-  if (a.tok_steps != nullptr) {                      // dynamic per-token steps: built for the tiles listed in TOK_OK
-    if constexpr (P::TOK_OK) {
-      auto kern = seglinear_mfma_kernel<P::BM, P::BN, P::WM, P::WN, P::NS, P::SK, P::MINB, DUAL, MULTI, SHARE, true>;
-      hipLaunchKernelGGL(kern, dim3(a.num_wg), dim3(P::WM * P::WN * 64), 0, st, a, tb, mode);
-      return hipGetLastError();
-    } else {
-      return hipErrorInvalidConfiguration;
+    if (a.tok_steps != nullptr) {                      // dynamic per-token steps: built for the tiles listed in TOK_OK
+      if constexpr (P::TOK_OK) {
+        auto kern = seglinear_mfma_kernel<P::BM, P::BN, P::WM, P::WN, P::NS, P::SK, P::MINB, DUAL, MULTI, SHARE, true>;
+        hipLaunchKernelGGL(kern, dim3(a.num_wg), dim3(P::WM * P::WN * 64), 0, st, a, tb, mode);
+        return hipGetLastError();
+      } else {
+        return hipErrorInvalidConfiguration;
+      }
     }
-  }
-  auto kern = seglinear_mfma_kernel<P::BM, P::BN, P::WM, P::WN, P::NS, P::SK, P::MINB, DUAL, MULTI, SHARE>;
-  hipLaunchKernelGGL(kern, dim3(a.num_wg), dim3(P::WM * P::WN * 64), 0, st, a, tb, mode);
-  return hipGetLastError();
+    auto kern = seglinear_mfma_kernel<P::BM, P::BN, P::WM, P::WN, P::NS, P::SK, P::MINB, DUAL, MULTI, SHARE>;
+    hipLaunchKernelGGL(kern, dim3(a.num_wg), dim3(P::WM * P::WN * 64), 0, st, a, tb, mode);
+    return hipGetLastError();
   }
 }
 

@@ -357,11 +357,11 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
                 bfr[cur][j], nfr[cur][DUAL ? i : 0], __builtin_bit_cast(v16f, accn[DUAL ? i : 0][DUAL ? j : 0]), 0, 0, 0, kUnit,
                 0, kUnit));
         } else {
-        if (!DL || (q & 1) == 0)
-          accp[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bfr[cur][j], afr[cur][i], accp[i][j], 0, 0, 0);
-        else
-          accn[DUAL ? i : 0][DUAL ? j : 0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
-              bfr[cur][j], nfr[cur][DUAL ? i : 0], accn[DUAL ? i : 0][DUAL ? j : 0], 0, 0, 0);
+          if (!DL || (q & 1) == 0)
+            accp[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bfr[cur][j], afr[cur][i], accp[i][j], 0, 0, 0);
+          else
+            accn[DUAL ? i : 0][DUAL ? j : 0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
+                bfr[cur][j], nfr[cur][DUAL ? i : 0], accn[DUAL ? i : 0][DUAL ? j : 0], 0, 0, 0);
         }
       }
       __builtin_amdgcn_sched_barrier(0);
@@ -374,8 +374,8 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void seglinear_mfma_kernel(cons
               if (f < IM) read_chunk(afr[nxt][f < IM ? f : 0], c, fragA + (f < IM ? f : 0) * (32 * SK) + (fo_next ^ (16 * c)));
               else read_chunk(bfr[nxt][f >= IM ? f - IM : 0], c, fragB + (f >= IM ? f - IM : 0) * (32 * SK) + (fo_next ^ (16 * c)));
             } else {
-            if (r < IM) afr[nxt][r < IM ? r : 0] = *reinterpret_cast<const v4i*>(fragA + (r < IM ? r : 0) * (32 * SK) + fo_next);
-            else bfr[nxt][r >= IM ? r - IM : 0] = *reinterpret_cast<const v4i*>(fragB + (r >= IM ? r - IM : 0) * (32 * SK) + fo_next);
+              if (r < IM) afr[nxt][r < IM ? r : 0] = *reinterpret_cast<const v4i*>(fragA + (r < IM ? r : 0) * (32 * SK) + fo_next);
+              else bfr[nxt][r >= IM ? r - IM : 0] = *reinterpret_cast<const v4i*>(fragB + (r >= IM ? r - IM : 0) * (32 * SK) + fo_next);
             }
           }
       }

@@ -522,29 +522,29 @@ __global__ __launch_bounds__(stream_waves(MT) * 64) void seglinear_stream_kernel
             }
           } else {
 #pragma unroll
-          for (int h = 0; h < 2; ++h)
+            for (int h = 0; h < 2; ++h)
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-              v4i pf = xf[h][mt];
-              if (DL) {                                            // X^_+ = max(X^, 0), X^_- = min(X^, 0), byte-wise
-                v4i nf;
-                if (PS) {
-                  nf = nfp[h][mt];
-                } else {
+              for (int mt = 0; mt < MT; ++mt) {
+                v4i pf = xf[h][mt];
+                if (DL) {                                            // X^_+ = max(X^, 0), X^_- = min(X^, 0), byte-wise
+                  v4i nf;
+                  if (PS) {
+                    nf = nfp[h][mt];
+                  } else {
 #pragma unroll
-                  for (int d = 0; d < 4; ++d) {
-                    int pos, neg;
-                    split_polarity(pf[d], pos, neg);
-                    pf[d] = pos;
-                    nf[d] = neg;
+                    for (int d = 0; d < 4; ++d) {
+                      int pos, neg;
+                      split_polarity(pf[d], pos, neg);
+                      pf[d] = pos;
+                      nf[d] = neg;
+                    }
                   }
+                  if (h == 0) accn[mt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf[h], nf, accn[mt], 0, 0, 0);
+                  else accn1[mt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf[h], nf, accn1[mt], 0, 0, 0);
                 }
-                if (h == 0) accn[mt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf[h], nf, accn[mt], 0, 0, 0);
-                else accn1[mt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf[h], nf, accn1[mt], 0, 0, 0);
+                if (h == 0) accp[mt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf[h], pf, accp[mt], 0, 0, 0);
+                else accp1[mt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf[h], pf, accp1[mt], 0, 0, 0);
               }
-              if (h == 0) accp[mt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf[h], pf, accp[mt], 0, 0, 0);
-              else accp1[mt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf[h], pf, accp1[mt], 0, 0, 0);
-            }
           }
           // step consumed (its fragments are in registers): free the slot, keep the stream going
           cslot = (cslot + 1 == RING) ? 0 : cslot + 1;
