@@ -801,7 +801,7 @@ const char* sq_status_string(sq_status s) {
   }
 }
 
-int sq_version(void) { return 300; }
+int sq_version(void) { return 400; }   // 0.4.0: smoothing, low-rank branch, fp8 variant, allocation-free calibration entry
 
 sq_status sq_tuning_set(const char* key, int value) {
   if (key == nullptr) return SQ_ERR_INVALID_ARG;
